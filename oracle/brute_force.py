@@ -1,0 +1,218 @@
+"""Exhaustive schedule enumeration and an explicit program-tree cost evaluator.
+
+TEST INFRASTRUCTURE, written separately from the C oracle so that the two can
+be checked against each other on tiny lattices.
+
+* `programs(...)` walks the rewrites of Section 2 (tile, move, select) and
+  Section 2.1 (bufferize) and yields every *complete* program tree reachable
+  from a Spec -- no memo table, no pruning, no cost bookkeeping.
+* `c(p)` evaluates the cost equation of Section 3 on such a tree:
+    loop          trips * c(body) + s
+    pipeline      sum of the children (+ the intermediate's initialisation)
+    alloc-binding move cost + c(body)
+    microkernel   k_p
+* `optimum(...)` = the minimum of c over all programs, and the lowest rewrite
+  id among the first rewrites that reach it.
+
+Only usable on very small lattices: the number of programs grows
+exponentially with the number of divisors and levels.
+"""
+from collections import namedtuple
+
+M, E, F = 0, 1, 2
+FMA, BCAST, BF16DOT, S_ADDRELU, V_ADDRELU = 0, 1, 2, 3, 4
+
+# dims = (b, m, k, n) actual sizes; levels per operand (F: 5th = intermediate);
+# layouts / bf16 per operand (0 where the lattice has no such coordinate)
+Spec = namedtuple("Spec", "kind dims levels layouts bf16")
+
+
+def operand_numel(spec, i):
+    b, m, k, n = spec.dims
+    if spec.kind == M:
+        return (b * m * k, b * k * n, b * m * n)[i]
+    if spec.kind == E:
+        return (m * n, n, m * n)[i]
+    return (m * k, k * n, n, m * n, m * n)[i]
+
+
+def operand_mode(kind, i):
+    """'r' read, 'rw' accumulate, 'w' write-only."""
+    if kind == M:
+        return "rw" if i == 2 else "r"
+    if kind == E:
+        return "w" if i == 2 else "r"
+    return "w" if i == 3 else "r"
+
+
+def fits(target, spec):
+    used = [0] * target["n_levels"]
+    nops = 4 if spec.kind == F else 3
+    for i in range(nops):
+        used[spec.levels[i]] += operand_numel(spec, i) * (2 if spec.bf16[i] else 4)
+    if spec.kind == F:
+        used[spec.levels[4]] += 4 * operand_numel(spec, 4)
+    return all(u <= cap for u, cap in zip(used, target["capacity_bytes"]))
+
+
+def microkernel_reps(target, lattice, spec, j):
+    kind, lanes, _ = target["microkernels"][j]
+    b, m, k, n = spec.dims
+    lv, ly, bf = spec.levels, spec.layouts, spec.bf16
+    if kind == FMA:
+        ok = spec.kind == M and (b, m, k, n) == (1, 1, 1, 1) and tuple(lv[:3]) == (0, 0, 0) and not any(bf[:3])
+        return 1 if ok else 0
+    if kind == BCAST:
+        ok = (spec.kind == M and (b, m, k) == (1, 1, 1) and n % lanes == 0
+              and tuple(lv[:3]) == (0, 1, 1) and not any(bf[:3]) and ly[1] == 0 and ly[2] == 0)
+        return n // lanes if ok else 0
+    if kind == BF16DOT:
+        rhs_col = ly[1] == 1 or not lattice["layout_coord"][1]
+        ok = (spec.kind == M and (b, m, n) == (1, 1, 1) and k % lanes == 0
+              and tuple(lv[:3]) == (1, 1, 0) and bf[0] and bf[1] and not bf[2] and rhs_col)
+        return k // lanes if ok else 0
+    if kind == S_ADDRELU:
+        ok = spec.kind == E and (m, n) == (1, 1) and tuple(lv[:3]) == (0, 0, 0)
+        return 1 if ok else 0
+    if kind == V_ADDRELU:
+        ok = (spec.kind == E and m == 1 and n % lanes == 0 and tuple(lv[:3]) == (1, 1, 1)
+              and ly[0] == 0 and ly[2] == 0)
+        return n // lanes if ok else 0
+    return 0
+
+
+def rewrites(target, lattices, spec):
+    """Yield (rewrite_id, node_without_children, [child specs]) for every
+    applicable rewrite of an admissible Spec, ids ascending."""
+    lattice = lattices[spec.kind]
+    nl = target["n_levels"]
+    nops = 4 if spec.kind == F else 3
+    nmk = len(target["microkernels"])
+    maxs = max(len(s) for s in lattice["sizes"])
+    move_base = nmk
+    tile_base = nmk + nops * (nl - 1) * 4
+    for j in range(nmk):
+        reps = microkernel_reps(target, lattice, spec, j)
+        if reps:
+            yield j, ("mk", target["microkernels"][j][2] * reps), []
+    for i in range(nops):
+        mode = operand_mode(spec.kind, i)
+        src = spec.levels[i]
+        for dst in range(src):
+            for x in (0, 1):
+                for cv in (0, 1):
+                    if x and not lattice["layout_coord"][i]:
+                        continue
+                    if cv and not (lattice["dtype_coord"][i] and spec.bf16[i] and mode == "r"):
+                        continue
+                    coef = 0
+                    if "r" in mode:
+                        if target["load_coef"][src][dst][x] == 0:
+                            continue
+                        coef += target["load_coef"][src][dst][x]
+                    if "w" in mode:
+                        if target["store_coef"][dst][src][x] == 0:
+                            continue
+                        coef += target["store_coef"][dst][src][x]
+                    if cv:
+                        coef += target["convert_coef"]
+                    lv = list(spec.levels); lv[i] = dst
+                    ly = list(spec.layouts); ly[i] ^= x
+                    bf = list(spec.bf16)
+                    if cv:
+                        bf[i] = 0
+                    child = spec._replace(levels=tuple(lv), layouts=tuple(ly), bf16=tuple(bf))
+                    rid = move_base + ((i * (nl - 1) + dst) * 2 + x) * 2 + cv
+                    yield rid, ("alloc", coef * operand_numel(spec, i)), [child]
+    for d in range(4):
+        if spec.kind != M and d in (0, 2):
+            continue
+        cur = spec.dims[d]
+        for j, t in enumerate(lattice["sizes"][d]):
+            if t < cur and cur % t == 0:
+                dims = list(spec.dims); dims[d] = t
+                yield (tile_base + d * maxs + j,
+                       ("loop", cur // t, target["loop_overhead"]),
+                       [spec._replace(dims=tuple(dims))])
+    if spec.kind == F:
+        b, m, k, n = spec.dims
+        l_lhs, l_rhs, l_bias, l_out, l_mid = spec.levels
+        y_lhs, y_rhs, _, y_out = spec.layouts[:4]
+        mm = Spec(M, (1, m, k, n), (l_lhs, l_rhs, l_mid, 0, 0), (y_lhs, y_rhs, 0, 0, 0), (0,) * 5)
+        ee = Spec(E, (1, m, 1, n), (l_mid, l_bias, l_out, 0, 0), (0, 0, y_out, 0, 0), (0,) * 5)
+        yield tile_base + 4 * maxs, ("pipeline", target["zero_coef"][l_mid] * m * n), [mm, ee]
+
+
+def programs(target, lattices, spec):
+    """Yield (first_rewrite_id, tree) for every complete program of `spec`."""
+    if not fits(target, spec):
+        return
+    for rid, node, children in rewrites(target, lattices, spec):
+        if not children:
+            yield rid, node
+        elif len(children) == 1:
+            for _, sub in programs(target, lattices, children[0]):
+                yield rid, node + (sub,)
+        else:
+            for _, pa in programs(target, lattices, children[0]):
+                for _, pb in programs(target, lattices, children[1]):
+                    yield rid, node + (pa, pb)
+
+
+def c(p):
+    tag = p[0]
+    if tag == "mk":
+        return p[1]
+    if tag == "loop":
+        return p[1] * c(p[3]) + p[2]
+    if tag == "alloc":
+        return p[1] + c(p[2])
+    if tag == "pipeline":
+        return p[1] + c(p[2]) + c(p[3])
+    raise ValueError(tag)
+
+
+def optimum(target, lattices, spec):
+    """(min cost, lowest first-rewrite id reaching it, number of programs); (None, None, 0) if none."""
+    best = None
+    arg = None
+    count = 0
+    for rid, tree in programs(target, lattices, spec):
+        count += 1
+        v = c(tree)
+        if best is None or v < best or (v == best and rid < arg):
+            best, arg = v, rid
+    return best, arg, count
+
+
+def count_rewrites(target, lattices, spec):
+    """Number of rewrites enumerated for one Spec (0 when it does not fit)."""
+    if not fits(target, spec):
+        return 0
+    return sum(1 for _ in rewrites(target, lattices, spec))
+
+
+def merge_boxes(ext, merge_order, values):
+    """Box merge of Section 4.1 written with dictionaries: `values` maps each
+    coordinate tuple to a hashable value.  For every axis in turn, boxes that
+    agree in value and in their extent on all other axes are chained when one
+    starts right after the other ends.  Returns [(lo, hi, value)] sorted by lo."""
+    boxes = [(x, x, v) for x, v in values.items()]
+    for a in merge_order:
+        groups = {}
+        for lo, hi, v in boxes:
+            key = (v, lo[:a] + lo[a + 1:], hi[:a] + hi[a + 1:])
+            groups.setdefault(key, []).append((lo, hi))
+        boxes = []
+        for (v, _, _), members in groups.items():
+            members.sort(key=lambda b: b[0][a])
+            cur_lo, cur_hi = members[0]
+            for lo, hi in members[1:]:
+                if lo[a] == cur_hi[a] + 1:
+                    cur_hi = hi
+                else:
+                    boxes.append((cur_lo, cur_hi, v))
+                    cur_lo, cur_hi = lo, hi
+            boxes.append((cur_lo, cur_hi, v))
+    boxes.sort(key=lambda b: b[0])
+    return boxes

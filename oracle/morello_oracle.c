@@ -1,0 +1,549 @@
+/*
+ * CPU oracle for the memo-table fill and its spatial compression.
+ *
+ * THIS FILE IS TEST INFRASTRUCTURE.  It is a plain, slow, single-threaded
+ * statement of what the method computes, used only to check the HIP library
+ * (tests, the smoke check, and the CPU-baseline leg of the benchmark).  It
+ * shares no code with the HIP path and the product never calls it.
+ *
+ * What it follows in the paper:
+ *   - Section 4 (Synthesis): top-down search; look the Spec up in the memo
+ *     table, else evaluate every applicable rewrite, recurse on the rewrite's
+ *     sub-Specs, memoize and return the lowest-cost one.  -> orc_solve()
+ *   - Section 3 (Cost Model): c(p) is affine in the sub-program costs:
+ *     loop = trips * c(body) + s; alloc-binding = move cost + c(children);
+ *     pipeline/block = sum of children; microkernel = k_p.
+ *   - Section 2 (Tiling, Memory Movement, Microkernel Selection) and
+ *     Section 2.1 (bufferize of a composition) for the rewrites themselves.
+ *   - Section 4.1 (Memoization Database): Specs are points in Z>=0^D;
+ *     unit rectangles holding the decision (and, separately, the cost
+ *     normalised to the Spec's volume) are merged with adjacent rectangles of
+ *     the same value when the union fills its bounding box.  -> orc_merge()
+ *
+ * Pins (see tests): worked example of Figure 1, brute-force enumeration of all
+ * complete schedules on tiny lattices (oracle/brute_force.py, written
+ * separately in Python), closed forms, and decompress(merge(x)) == x.
+ * The fused three-node lattice (kind 2) follows this build's own reading of
+ * Section 2.1; it is pinned by brute force only: "parity unpinned" by the
+ * paper beyond the sum rule of Section 3.
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ORC_INF   UINT64_MAX
+#define ORC_NONE  0xFFFFu
+#define ORC_LIMIT (((unsigned __int128)1) << 62)
+
+enum { ORC_MAXL = 4, ORC_MAXOPS = 5, ORC_MAXD = 16, ORC_MAXMK = 8 };
+enum { MK_SCALAR_FMA = 0, MK_BCAST_VEC_MULADD = 1, MK_BF16_DOT = 2,
+       MK_SCALAR_ADDRELU = 3, MK_VEC_ADDRELU = 4 };
+enum { KIND_M = 0, KIND_E = 1, KIND_F = 2 };
+enum { ACC_READ = 0, ACC_RMW = 1, ACC_WRITE = 2 };
+
+typedef struct {
+  uint32_t n_levels;
+  uint64_t capacity_bytes[ORC_MAXL];
+  uint32_t load_coef[ORC_MAXL][ORC_MAXL][2];   /* [src][dst][same|transposed] */
+  uint32_t store_coef[ORC_MAXL][ORC_MAXL][2];  /* [dst][src][same|transposed] */
+  uint32_t convert_coef;
+  uint32_t zero_coef[ORC_MAXL];
+  uint32_t loop_overhead;
+  uint32_t n_microkernels;
+  uint32_t mk_kind[ORC_MAXMK];
+  uint32_t mk_lanes[ORC_MAXMK];
+  uint64_t mk_cost[ORC_MAXMK];
+} orc_target;
+
+typedef struct {
+  uint32_t kind;
+  uint32_t n_sizes[4];
+  const uint32_t* sizes[4];                    /* b, m, k, n */
+  uint8_t layout_coord[ORC_MAXOPS];
+  uint8_t dtype_coord[ORC_MAXOPS];
+  uint8_t base_dtype_bytes[ORC_MAXOPS];
+} orc_lattice;
+
+/* A Spec (Section 2.2) reduced to the fields the lattices carry. */
+typedef struct {
+  uint32_t si[4];               /* index of b, m, k, n in the allowed-size lists */
+  uint8_t level[ORC_MAXOPS];    /* per operand; kind F: level[4] = intermediate */
+  uint8_t layout[ORC_MAXOPS];   /* 0 row-major, 1 column-major */
+  uint8_t bf16[ORC_MAXOPS];     /* 0 f32, 1 bf16 */
+} spec_t;
+
+typedef struct ctx {
+  const orc_target* T;
+  const orc_lattice* L;
+  int kind, nops, nlv, ndim;
+  uint32_t ext[ORC_MAXD];
+  uint64_t stride[ORC_MAXD];
+  int lay_axis[ORC_MAXOPS], dt_axis[ORC_MAXOPS];
+  uint64_t n;
+  uint64_t* cost;
+  uint16_t* arg;
+  uint8_t* done;
+  uint32_t maxs, nmk, move_base, tile_base, buf_id;
+  uint64_t n_rewrites, n_admissible;
+  int overflow;
+  const struct ctx* depM;
+  const struct ctx* depE;
+} ctx;
+
+/* ------------------------------------------------------------------ */
+/* Coordinates (Section 4.1: Specs map to points of Z>=0^D).  Axis order:
+ * size indices b,m,k,n; operand levels (kind F: then the intermediate's);
+ * layout bits of the operands that have one; dtype bits likewise.  The dense
+ * tables are in C order of that vector, last axis fastest. */
+static int ctx_init(ctx* c, const orc_target* T, const orc_lattice* L) {
+  memset(c, 0, sizeof *c);
+  c->T = T; c->L = L; c->kind = (int)L->kind;
+  if (c->kind < 0 || c->kind > 2) return -1;
+  if (T->n_levels < 1 || T->n_levels > ORC_MAXL) return -1;
+  c->nops = c->kind == KIND_F ? 4 : 3;
+  c->nlv = c->kind == KIND_F ? 5 : 3;
+  int d = 0;
+  c->maxs = 0;
+  for (int a = 0; a < 4; a++) {
+    if (L->n_sizes[a] < 1 || L->sizes[a][0] != 1) return -1;
+    for (uint32_t j = 1; j < L->n_sizes[a]; j++)
+      if (L->sizes[a][j] <= L->sizes[a][j - 1]) return -1;
+    c->ext[d++] = L->n_sizes[a];
+    if (L->n_sizes[a] > c->maxs) c->maxs = L->n_sizes[a];
+  }
+  if (c->kind != KIND_M && L->n_sizes[0] != 1) return -1;   /* no batch on E, F */
+  if (c->kind == KIND_E && L->n_sizes[2] != 1) return -1;   /* E has no k */
+  for (int i = 0; i < c->nlv; i++) c->ext[d++] = T->n_levels;
+  for (int i = 0; i < ORC_MAXOPS; i++) { c->lay_axis[i] = -1; c->dt_axis[i] = -1; }
+  for (int i = 0; i < c->nops; i++)
+    if (L->layout_coord[i]) { c->lay_axis[i] = d; c->ext[d++] = 2; }
+  for (int i = 0; i < c->nops; i++)
+    if (L->dtype_coord[i]) {
+      if (c->kind != KIND_M || i == 2) return -1;           /* inputs of a Matmul only */
+      c->dt_axis[i] = d; c->ext[d++] = 2;
+    }
+  c->ndim = d;
+  uint64_t s = 1;
+  for (int a = d - 1; a >= 0; a--) { c->stride[a] = s; s *= c->ext[a]; }
+  c->n = s;
+  c->nmk = T->n_microkernels;
+  c->move_base = c->nmk;
+  c->tile_base = c->move_base + (uint32_t)c->nops * (T->n_levels - 1) * 4;
+  c->buf_id = c->tile_base + 4 * c->maxs;
+  if (c->buf_id >= ORC_NONE) return -1;
+  return 0;
+}
+
+static uint64_t spec_index(const ctx* c, const spec_t* s) {
+  uint64_t x = 0;
+  for (int a = 0; a < 4; a++) x += s->si[a] * c->stride[a];
+  for (int i = 0; i < c->nlv; i++) x += s->level[i] * c->stride[4 + i];
+  for (int i = 0; i < c->nops; i++) {
+    if (c->lay_axis[i] >= 0) x += s->layout[i] * c->stride[c->lay_axis[i]];
+    if (c->dt_axis[i] >= 0) x += s->bf16[i] * c->stride[c->dt_axis[i]];
+  }
+  return x;
+}
+
+static void spec_of_index(const ctx* c, uint64_t x, spec_t* s) {
+  memset(s, 0, sizeof *s);
+  uint32_t coord[ORC_MAXD];
+  for (int a = 0; a < c->ndim; a++) { coord[a] = (uint32_t)(x / c->stride[a]); x %= c->stride[a]; }
+  for (int a = 0; a < 4; a++) s->si[a] = coord[a];
+  for (int i = 0; i < c->nlv; i++) s->level[i] = (uint8_t)coord[4 + i];
+  for (int i = 0; i < c->nops; i++) {
+    if (c->lay_axis[i] >= 0) s->layout[i] = (uint8_t)coord[c->lay_axis[i]];
+    if (c->dt_axis[i] >= 0) s->bf16[i] = (uint8_t)coord[c->dt_axis[i]];
+    else s->bf16[i] = c->L->base_dtype_bytes[i] == 2;
+  }
+}
+
+/* ------------------------------------------------------------------ */
+/* Shapes.  Section 2: dimensions are batch, m, k, n; lhs is b x m x k, rhs is
+ * b x k x n, the output b x m x n.  Kind E: in (m x n), bias (n), out (m x n).
+ * Kind F: lhs, rhs, bias, out, and the intermediate (m x n, f32). */
+static void dims_of(const ctx* c, const spec_t* s, uint64_t d[4]) {
+  for (int a = 0; a < 4; a++) d[a] = c->L->sizes[a][s->si[a]];
+}
+
+static uint64_t numel(const ctx* c, const spec_t* s, int op) {
+  uint64_t d[4]; dims_of(c, s, d);
+  uint64_t b = d[0], m = d[1], k = d[2], n = d[3];
+  switch (c->kind) {
+    case KIND_M: return op == 0 ? b * m * k : op == 1 ? b * k * n : b * m * n;
+    case KIND_E: return op == 1 ? n : m * n;
+    default:     return op == 0 ? m * k : op == 1 ? k * n : op == 2 ? n : m * n; /* 3 = out, 4 = mid */
+  }
+}
+
+static int access_of(const ctx* c, int op) {
+  if (c->kind == KIND_M) return op == 2 ? ACC_RMW : ACC_READ;     /* accumulating output */
+  return op == c->nops - 1 ? ACC_WRITE : ACC_READ;
+}
+
+/* A Spec is admissible when the tensors resident in each level fit that level
+ * (the per-level memory bound of Section 2.2, applied to the Spec's own
+ * operands; kind F also counts its intermediate). */
+static int admissible(const ctx* c, const spec_t* s) {
+  for (uint32_t l = 0; l < c->T->n_levels; l++) {
+    unsigned __int128 bytes = 0;
+    for (int i = 0; i < c->nops; i++)
+      if (s->level[i] == l) bytes += (unsigned __int128)numel(c, s, i) * (s->bf16[i] ? 2 : 4);
+    if (c->kind == KIND_F && s->level[4] == l) bytes += (unsigned __int128)numel(c, s, 4) * 4;
+    if (c->T->capacity_bytes[l] != UINT64_MAX && bytes > c->T->capacity_bytes[l]) return 0;
+  }
+  return 1;
+}
+
+/* a * sub + b with INF absorbing and the 2^62 range check. */
+static uint64_t affine(ctx* c, uint64_t a, uint64_t sub, unsigned __int128 b) {
+  if (sub == ORC_INF) return ORC_INF;
+  unsigned __int128 v = (unsigned __int128)a * sub + b;
+  if (v >= ORC_LIMIT) { c->overflow = 1; return ORC_INF; }
+  return (uint64_t)v;
+}
+
+/* Microkernel applicability and repetition count (Section 2, Microkernel
+ * Selection; Figure 1: BroadcastVecMultAdd on an RF, VRF, VRF 1x1x1x16 Spec).
+ * Returns 0 when the predicate fails, else the number of repetitions. */
+static uint64_t mk_reps(const ctx* c, const spec_t* s, int j) {
+  uint64_t d[4]; dims_of(c, s, d);
+  uint64_t b = d[0], m = d[1], k = d[2], n = d[3];
+  uint32_t lanes = c->T->mk_lanes[j];
+  const uint8_t* lv = s->level; const uint8_t* ly = s->layout; const uint8_t* bf = s->bf16;
+  switch (c->T->mk_kind[j]) {
+    case MK_SCALAR_FMA:
+      if (c->kind != KIND_M) return 0;
+      if (b != 1 || m != 1 || k != 1 || n != 1) return 0;
+      if (lv[0] != 0 || lv[1] != 0 || lv[2] != 0) return 0;
+      if (bf[0] || bf[1] || bf[2]) return 0;
+      return 1;
+    case MK_BCAST_VEC_MULADD:
+      if (c->kind != KIND_M) return 0;
+      if (b != 1 || m != 1 || k != 1 || n % lanes != 0) return 0;
+      if (lv[0] != 0 || lv[1] != 1 || lv[2] != 1) return 0;
+      if (bf[0] || bf[1] || bf[2]) return 0;
+      if (ly[1] != 0 || ly[2] != 0) return 0;           /* rhs, out row-major */
+      return n / lanes;
+    case MK_BF16_DOT:
+      if (c->kind != KIND_M) return 0;
+      if (b != 1 || m != 1 || n != 1 || k % lanes != 0) return 0;
+      if (lv[0] != 1 || lv[1] != 1 || lv[2] != 0) return 0;
+      if (!bf[0] || !bf[1] || bf[2]) return 0;
+      if (c->lay_axis[1] >= 0 && ly[1] != 1) return 0;  /* rhs column-major */
+      return k / lanes;
+    case MK_SCALAR_ADDRELU:
+      if (c->kind != KIND_E) return 0;
+      if (m != 1 || n != 1) return 0;
+      if (lv[0] != 0 || lv[1] != 0 || lv[2] != 0) return 0;
+      return 1;
+    case MK_VEC_ADDRELU:
+      if (c->kind != KIND_E) return 0;
+      if (m != 1 || n % lanes != 0) return 0;
+      if (lv[0] != 1 || lv[1] != 1 || lv[2] != 1) return 0;
+      if (ly[0] != 0 || ly[2] != 0) return 0;
+      return n / lanes;
+    default: return 0;
+  }
+}
+
+static uint64_t solve(ctx* c, const spec_t* s);
+
+static void consider(ctx* c, uint64_t cand, uint32_t id, uint64_t* best, uint16_t* arg) {
+  c->n_rewrites++;
+  if (cand < *best) { *best = cand; *arg = (uint16_t)id; }   /* first strict minimum */
+}
+
+/* Section 4: evaluate every applicable rewrite of one Spec, in id order. */
+static void expand(ctx* c, const spec_t* s, uint64_t* best_out, uint16_t* arg_out) {
+  const orc_target* T = c->T;
+  uint64_t best = ORC_INF; uint16_t arg = ORC_NONE;
+  uint32_t NL = T->n_levels;
+
+  /* A. select(microkernel): a leaf costing k_p per repetition. */
+  for (uint32_t j = 0; j < c->nmk; j++) {
+    uint64_t reps = mk_reps(c, s, (int)j);
+    if (!reps) continue;
+    consider(c, affine(c, 0, 0, (unsigned __int128)T->mk_cost[j] * reps), j, &best, &arg);
+  }
+
+  /* B. move an operand to a strictly faster level (alloc-binding: the move's
+   * own cost plus the cost of the body Spec). */
+  for (int i = 0; i < c->nops; i++) {
+    int acc = access_of(c, i);
+    uint32_t src = s->level[i];
+    for (uint32_t dst = 0; dst + 1 < NL; dst++)
+      for (int x = 0; x < 2; x++)
+        for (int cv = 0; cv < 2; cv++) {
+          if (dst >= src) continue;
+          if (x && c->lay_axis[i] < 0) continue;
+          if (cv && !(c->dt_axis[i] >= 0 && s->bf16[i] && acc == ACC_READ)) continue;
+          uint64_t coef = 0;
+          if (acc != ACC_WRITE) { if (!T->load_coef[src][dst][x]) continue; coef += T->load_coef[src][dst][x]; }
+          if (acc != ACC_READ) { if (!T->store_coef[dst][src][x]) continue; coef += T->store_coef[dst][src][x]; }
+          if (cv) coef += T->convert_coef;
+          spec_t sub = *s;
+          sub.level[i] = (uint8_t)dst;
+          sub.layout[i] ^= (uint8_t)x;
+          if (cv) sub.bf16[i] = 0;
+          uint32_t id = c->move_base + (((uint32_t)i * (NL - 1) + dst) * 2 + (uint32_t)x) * 2 + (uint32_t)cv;
+          uint64_t cand = affine(c, 1, solve(c, &sub), (unsigned __int128)coef * numel(c, s, i));
+          consider(c, cand, id, &best, &arg);
+        }
+  }
+
+  /* C. tile one dimension to a smaller allowed size dividing it: a loop of
+   * trips iterations around the smaller Spec, plus the loop constant s. */
+  for (int d = 0; d < 4; d++) {
+    if (c->kind != KIND_M && (d == 0 || d == 2)) continue;   /* E, F: only m and n */
+    uint32_t cur = c->L->sizes[d][s->si[d]];
+    for (uint32_t j = 0; j < s->si[d]; j++) {
+      uint32_t t = c->L->sizes[d][j];
+      if (cur % t) continue;
+      spec_t sub = *s;
+      sub.si[d] = j;
+      uint64_t cand = affine(c, cur / t, solve(c, &sub), T->loop_overhead);
+      consider(c, cand, c->tile_base + (uint32_t)d * c->maxs + j, &best, &arg);
+    }
+  }
+
+  /* D. bufferize (kind F): a pipeline of the Matmul writing the intermediate
+   * and the bias-add+ReLU reading it; cost = sum of the children plus
+   * initialising the accumulated intermediate. */
+  if (c->kind == KIND_F) {
+    spec_t ms; memset(&ms, 0, sizeof ms);
+    spec_t es; memset(&es, 0, sizeof es);
+    for (int a = 0; a < 4; a++) ms.si[a] = s->si[a];
+    ms.level[0] = s->level[0]; ms.level[1] = s->level[1]; ms.level[2] = s->level[4];
+    ms.layout[0] = s->layout[0]; ms.layout[1] = s->layout[1]; ms.layout[2] = 0;
+    es.si[1] = s->si[1]; es.si[3] = s->si[3];
+    es.level[0] = s->level[4]; es.level[1] = s->level[2]; es.level[2] = s->level[3];
+    es.layout[0] = 0; es.layout[2] = s->layout[3];
+    uint64_t cm = c->depM->cost[spec_index(c->depM, &ms)];
+    uint64_t ce = c->depE->cost[spec_index(c->depE, &es)];
+    uint64_t cand = ORC_INF;
+    if (cm != ORC_INF && ce != ORC_INF) {
+      unsigned __int128 v = (unsigned __int128)T->zero_coef[s->level[4]] * numel(c, s, 4) + cm + ce;
+      if (v >= ORC_LIMIT) c->overflow = 1; else cand = (uint64_t)v;
+    }
+    consider(c, cand, c->buf_id, &best, &arg);
+  }
+  *best_out = best; *arg_out = arg;
+}
+
+static uint64_t solve(ctx* c, const spec_t* s) {
+  uint64_t x = spec_index(c, s);
+  if (c->done[x]) return c->cost[x];
+  uint64_t best = ORC_INF; uint16_t arg = ORC_NONE;
+  if (admissible(c, s)) { c->n_admissible++; expand(c, s, &best, &arg); }
+  c->cost[x] = best; c->arg[x] = arg; c->done[x] = 1;
+  return best;
+}
+
+static int same_sizes(const orc_lattice* a, int da, const orc_lattice* b, int db) {
+  if (a->n_sizes[da] != b->n_sizes[db]) return 0;
+  return memcmp(a->sizes[da], b->sizes[db], a->n_sizes[da] * sizeof(uint32_t)) == 0;
+}
+
+/* Fill the whole table.  `goals` (optional) are linear indices solved first,
+ * in the given order; every remaining point is then solved in index order.
+ * Returns 0, -1 (bad arguments) or -6 (a finite cost reached 2^62). */
+int orc_solve(const orc_target* T, const orc_lattice* L,
+              const orc_lattice* LM, const uint64_t* costM,
+              const orc_lattice* LE, const uint64_t* costE,
+              const uint64_t* goals, uint64_t n_goals,
+              uint64_t* cost, uint16_t* arg,
+              uint64_t* n_admissible, uint64_t* n_rewrites) {
+  ctx c, cm, ce;
+  if (ctx_init(&c, T, L)) return -1;
+  if (c.kind == KIND_F) {
+    if (!LM || !LE || !costM || !costE) return -1;
+    if (ctx_init(&cm, T, LM) || ctx_init(&ce, T, LE)) return -1;
+    if (cm.kind != KIND_M || ce.kind != KIND_E) return -1;
+    for (int d = 1; d < 4; d++) if (!same_sizes(L, d, LM, d)) return -1;
+    if (LM->n_sizes[0] != 1) return -1;
+    if (!same_sizes(L, 1, LE, 1) || !same_sizes(L, 3, LE, 3)) return -1;
+    for (int i = 0; i < 3; i++) if (cm.dt_axis[i] >= 0 || LM->base_dtype_bytes[i] != 4) return -1;
+    cm.cost = (uint64_t*)costM; ce.cost = (uint64_t*)costE;
+    c.depM = &cm; c.depE = &ce;
+  }
+  c.cost = cost; c.arg = arg;
+  c.done = (uint8_t*)calloc(c.n, 1);
+  if (!c.done) return -2;
+  spec_t s;
+  for (uint64_t g = 0; g < n_goals; g++) {
+    if (goals[g] >= c.n) { free(c.done); return -1; }
+    spec_of_index(&c, goals[g], &s); solve(&c, &s);
+  }
+  for (uint64_t x = 0; x < c.n; x++) { spec_of_index(&c, x, &s); solve(&c, &s); }
+  free(c.done);
+  if (n_admissible) *n_admissible = c.n_admissible;
+  if (n_rewrites) *n_rewrites = c.n_rewrites;
+  return c.overflow ? -6 : 0;
+}
+
+/* Geometry of the table: number of axes, extents, and the merge order used by
+ * orc_merge (size axes innermost first, then level axes, layout bits and
+ * dtype bits, each last to first). */
+int orc_geometry(const orc_target* T, const orc_lattice* L, uint32_t* ndim,
+                 uint32_t* ext, uint32_t* merge_order, uint32_t* ids) {
+  ctx c;
+  if (ctx_init(&c, T, L)) return -1;
+  *ndim = (uint32_t)c.ndim;
+  for (int a = 0; a < c.ndim; a++) ext[a] = c.ext[a];
+  int nlay = 0;
+  for (int i = 0; i < c.nops; i++) nlay += c.lay_axis[i] >= 0;
+  int q = 0;
+  for (int a = 3; a >= 0; a--) merge_order[q++] = (uint32_t)a;                                   /* n, k, m, b */
+  for (int a = 4 + c.nlv - 1; a >= 4; a--) merge_order[q++] = (uint32_t)a;                       /* levels */
+  for (int a = 4 + c.nlv + nlay - 1; a >= 4 + c.nlv; a--) merge_order[q++] = (uint32_t)a;        /* layout bits */
+  for (int a = c.ndim - 1; a >= 4 + c.nlv + nlay; a--) merge_order[q++] = (uint32_t)a;           /* dtype bits */
+  if (ids) { ids[0] = c.move_base; ids[1] = c.tile_base; ids[2] = c.buf_id; ids[3] = c.maxs; }
+  return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* Values that the two box lists compare (Section 4.1): the decision itself,
+ * and the cost normalised to the Spec's volume b*m*k*n, kept as an exact
+ * reduced fraction v0/v1.  INF is (2^64-1, 0). */
+static uint64_t gcd64(uint64_t a, uint64_t b) { while (b) { uint64_t t = a % b; a = b; b = t; } return a; }
+
+int orc_cost_values(const orc_target* T, const orc_lattice* L, const uint64_t* cost,
+                    uint64_t* v0, uint64_t* v1) {
+  ctx c;
+  if (ctx_init(&c, T, L)) return -1;
+  spec_t s; uint64_t d[4];
+  for (uint64_t x = 0; x < c.n; x++) {
+    if (cost[x] == ORC_INF) { v0[x] = ORC_INF; v1[x] = 0; continue; }
+    spec_of_index(&c, x, &s); dims_of(&c, &s, d);
+    uint64_t vol = d[0] * d[1] * d[2] * d[3];
+    uint64_t g = gcd64(cost[x], vol);
+    v0[x] = cost[x] / g; v1[x] = vol / g;
+  }
+  return 0;
+}
+
+typedef struct { uint16_t lo[ORC_MAXD], hi[ORC_MAXD]; uint64_t v0, v1; } orc_box;
+
+static int g_axis, g_ndim;
+
+/* Group key: value, then lo/hi on every axis but the merge axis; inside a
+ * group order by lo on the merge axis. */
+static int cmp_group(const void* pa, const void* pb) {
+  const orc_box* a = (const orc_box*)pa; const orc_box* b = (const orc_box*)pb;
+  if (a->v0 != b->v0) return a->v0 < b->v0 ? -1 : 1;
+  if (a->v1 != b->v1) return a->v1 < b->v1 ? -1 : 1;
+  for (int j = 0; j < g_ndim; j++) {
+    if (j == g_axis) continue;
+    if (a->lo[j] != b->lo[j]) return a->lo[j] < b->lo[j] ? -1 : 1;
+    if (a->hi[j] != b->hi[j]) return a->hi[j] < b->hi[j] ? -1 : 1;
+  }
+  if (a->lo[g_axis] != b->lo[g_axis]) return a->lo[g_axis] < b->lo[g_axis] ? -1 : 1;
+  return 0;
+}
+
+static int same_group(const orc_box* a, const orc_box* b) {
+  if (a->v0 != b->v0 || a->v1 != b->v1) return 0;
+  for (int j = 0; j < g_ndim; j++) {
+    if (j == g_axis) continue;
+    if (a->lo[j] != b->lo[j] || a->hi[j] != b->hi[j]) return 0;
+  }
+  return 1;
+}
+
+static int cmp_lo(const void* pa, const void* pb) {
+  const orc_box* a = (const orc_box*)pa; const orc_box* b = (const orc_box*)pb;
+  for (int j = 0; j < g_ndim; j++)
+    if (a->lo[j] != b->lo[j]) return a->lo[j] < b->lo[j] ? -1 : 1;
+  return 0;
+}
+
+/* One merge pass along `axis`: join every maximal chain of boxes of one group
+ * in which each box starts right after the previous one ends. */
+static uint64_t merge_axis(orc_box* b, uint64_t n, int axis, int ndim) {
+  if (n == 0) return 0;
+  g_axis = axis; g_ndim = ndim;
+  qsort(b, n, sizeof *b, cmp_group);
+  uint64_t w = 0;
+  for (uint64_t r = 1; r < n; r++) {
+    if (same_group(&b[w], &b[r]) && b[r].lo[axis] == b[w].hi[axis] + 1) b[w].hi[axis] = b[r].hi[axis];
+    else b[++w] = b[r];
+  }
+  return w + 1;
+}
+
+/* Canonical box decomposition of a dense table of values (v0[x], v1[x]).
+ * Starts from one unit box per cell and applies merge_axis for each axis of
+ * merge_order in turn; the result is sorted by lo (first axis most
+ * significant).  With first_pass_by_lines != 0 the first axis is merged by
+ * walking each line of cells along it, which forms the same chains as the
+ * group-and-sort pass does on unit boxes but needs one box per run, not per
+ * cell (the two are compared in the tests).  Returns a malloc'ed array. */
+int64_t orc_merge(uint32_t ndim, const uint32_t* ext, const uint32_t* merge_order, uint32_t n_merge,
+                  const uint64_t* v0, const uint64_t* v1, int first_pass_by_lines, orc_box** out) {
+  uint64_t stride[ORC_MAXD], n = 1;
+  for (int a = (int)ndim - 1; a >= 0; a--) { stride[a] = n; n *= ext[a]; }
+  orc_box* b; uint64_t nb = 0; uint32_t first = 0;
+  if (first_pass_by_lines && n_merge > 0) {
+    uint32_t ax = merge_order[0];
+    uint64_t cap = 1024;
+    b = (orc_box*)malloc(cap * sizeof *b);
+    if (!b) return -2;
+    for (uint64_t x = 0; x < n; x++) {
+      uint32_t ca = (uint32_t)((x / stride[ax]) % ext[ax]);
+      if (ca > 0 && v0[x - stride[ax]] == v0[x] && v1[x - stride[ax]] == v1[x]) continue;  /* not a run start */
+      uint32_t e = ca;
+      while (e + 1 < ext[ax] && v0[x + (e + 1 - ca) * stride[ax]] == v0[x] && v1[x + (e + 1 - ca) * stride[ax]] == v1[x]) e++;
+      if (nb == cap) { cap *= 2; b = (orc_box*)realloc(b, cap * sizeof *b); if (!b) return -2; }
+      memset(&b[nb], 0, sizeof *b);
+      uint64_t r = x;
+      for (uint32_t a = 0; a < ndim; a++) { b[nb].lo[a] = b[nb].hi[a] = (uint16_t)(r / stride[a]); r %= stride[a]; }
+      b[nb].hi[ax] = (uint16_t)e; b[nb].v0 = v0[x]; b[nb].v1 = v1[x];
+      nb++;
+    }
+    first = 1;
+  } else {
+    b = (orc_box*)malloc((n ? n : 1) * sizeof *b);
+    if (!b) return -2;
+    for (uint64_t x = 0; x < n; x++) {
+      memset(&b[x], 0, sizeof *b);
+      uint64_t r = x;
+      for (uint32_t a = 0; a < ndim; a++) { b[x].lo[a] = b[x].hi[a] = (uint16_t)(r / stride[a]); r %= stride[a]; }
+      b[x].v0 = v0[x]; b[x].v1 = v1[x];
+    }
+    nb = n;
+  }
+  for (uint32_t q = first; q < n_merge; q++) nb = merge_axis(b, nb, (int)merge_order[q], (int)ndim);
+  g_ndim = (int)ndim;
+  qsort(b, nb, sizeof *b, cmp_lo);
+  *out = b;
+  return (int64_t)nb;
+}
+
+void orc_free(void* p) { free(p); }
+
+/* Paint the boxes back into dense arrays; cover[x] counts how many boxes
+ * contain cell x (1 everywhere for a valid decomposition). */
+int orc_decompress(uint32_t ndim, const uint32_t* ext, const orc_box* b, uint64_t nb,
+                   uint64_t* v0, uint64_t* v1, uint8_t* cover) {
+  uint64_t stride[ORC_MAXD], n = 1;
+  for (int a = (int)ndim - 1; a >= 0; a--) { stride[a] = n; n *= ext[a]; }
+  memset(cover, 0, n);
+  for (uint64_t i = 0; i < nb; i++) {
+    uint32_t c[ORC_MAXD];
+    for (uint32_t a = 0; a < ndim; a++) {
+      if (b[i].lo[a] > b[i].hi[a] || b[i].hi[a] >= ext[a]) return -1;
+      c[a] = b[i].lo[a];
+    }
+    for (;;) {
+      uint64_t x = 0;
+      for (uint32_t a = 0; a < ndim; a++) x += c[a] * stride[a];
+      v0[x] = b[i].v0; v1[x] = b[i].v1;
+      if (cover[x] < 255) cover[x]++;
+      int a = (int)ndim - 1;
+      while (a >= 0) { if (c[a] < b[i].hi[a]) { c[a]++; break; } c[a] = b[i].lo[a]; a--; }
+      if (a < 0) break;
+    }
+  }
+  return 0;
+}

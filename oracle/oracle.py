@@ -1,0 +1,220 @@
+"""ctypes wrapper around the C oracle (oracle/morello_oracle.c).
+
+TEST INFRASTRUCTURE: imported only by tests/, the smoke check and the
+benchmark's CPU-baseline leg.  It never imports the HIP package.
+"""
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "morello_oracle.c")
+_LIB = os.path.join(_HERE, "libmorello_oracle.so")
+
+INF = (1 << 64) - 1
+NONE = 0xFFFF
+MAXD = 16
+
+
+def build(force=False):
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-Wall", "-Wextra", "-shared", "-fPIC",
+                               "-o", _LIB, _SRC])
+    return _LIB
+
+
+class _Target(C.Structure):
+    _fields_ = [("n_levels", C.c_uint32),
+                ("capacity_bytes", C.c_uint64 * 4),
+                ("load_coef", C.c_uint32 * 2 * 4 * 4),
+                ("store_coef", C.c_uint32 * 2 * 4 * 4),
+                ("convert_coef", C.c_uint32),
+                ("zero_coef", C.c_uint32 * 4),
+                ("loop_overhead", C.c_uint32),
+                ("n_microkernels", C.c_uint32),
+                ("mk_kind", C.c_uint32 * 8),
+                ("mk_lanes", C.c_uint32 * 8),
+                ("mk_cost", C.c_uint64 * 8)]
+
+
+class _Lattice(C.Structure):
+    _fields_ = [("kind", C.c_uint32),
+                ("n_sizes", C.c_uint32 * 4),
+                ("sizes", C.POINTER(C.c_uint32) * 4),
+                ("layout_coord", C.c_uint8 * 5),
+                ("dtype_coord", C.c_uint8 * 5),
+                ("base_dtype_bytes", C.c_uint8 * 5)]
+
+
+class Box(C.Structure):
+    _fields_ = [("lo", C.c_uint16 * MAXD), ("hi", C.c_uint16 * MAXD),
+                ("v0", C.c_uint64), ("v1", C.c_uint64)]
+
+
+BOX_DTYPE = np.dtype([("lo", np.uint16, (MAXD,)), ("hi", np.uint16, (MAXD,)),
+                      ("v0", np.uint64), ("v1", np.uint64)])
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(build())
+        _lib.orc_solve.restype = C.c_int
+        _lib.orc_geometry.restype = C.c_int
+        _lib.orc_cost_values.restype = C.c_int
+        _lib.orc_merge.restype = C.c_int64
+        _lib.orc_decompress.restype = C.c_int
+        _lib.orc_free.restype = None
+    return _lib
+
+
+def _target(t):
+    s = _Target()
+    s.n_levels = t["n_levels"]
+    for l in range(4):
+        s.capacity_bytes[l] = t["capacity_bytes"][l]
+        s.zero_coef[l] = t["zero_coef"][l]
+        for k in range(4):
+            for x in range(2):
+                s.load_coef[l][k][x] = t["load_coef"][l][k][x]
+                s.store_coef[l][k][x] = t["store_coef"][l][k][x]
+    s.convert_coef = t["convert_coef"]
+    s.loop_overhead = t["loop_overhead"]
+    s.n_microkernels = len(t["microkernels"])
+    for j, (kind, lanes, cost) in enumerate(t["microkernels"]):
+        s.mk_kind[j], s.mk_lanes[j], s.mk_cost[j] = kind, lanes, cost
+    return s
+
+
+def _lattice(lat):
+    s = _Lattice()
+    keep = []
+    s.kind = lat["kind"]
+    for d in range(4):
+        arr = (C.c_uint32 * len(lat["sizes"][d]))(*lat["sizes"][d])
+        keep.append(arr)
+        s.n_sizes[d] = len(lat["sizes"][d])
+        s.sizes[d] = C.cast(arr, C.POINTER(C.c_uint32))
+    for i in range(5):
+        s.layout_coord[i] = lat["layout_coord"][i]
+        s.dtype_coord[i] = lat["dtype_coord"][i]
+        s.base_dtype_bytes[i] = lat["base_dtype_bytes"][i]
+    s._keep = keep
+    return s
+
+
+def _p(a, t):
+    return a.ctypes.data_as(C.POINTER(t))
+
+
+def geometry(target, lattice):
+    """(extents, merge_order, ids) with ids = dict(move_base, tile_base, bufferize, maxs)."""
+    T, L = _target(target), _lattice(lattice)
+    nd = C.c_uint32()
+    ext = (C.c_uint32 * MAXD)()
+    mo = (C.c_uint32 * MAXD)()
+    ids = (C.c_uint32 * 4)()
+    rc = lib().orc_geometry(C.byref(T), C.byref(L), C.byref(nd), ext, mo, ids)
+    if rc:
+        raise ValueError("orc_geometry failed: %d" % rc)
+    n = nd.value
+    return list(ext[:n]), list(mo[:n]), {"move_base": ids[0], "tile_base": ids[1],
+                                        "bufferize": ids[2], "maxs": ids[3]}
+
+
+def solve(target, lattice, deps=None, goals=None):
+    """Fill the table.  deps = ((latticeM, costM), (latticeE, costE)) for kind F.
+    Returns dict(cost u64[N], argmin u16[N], n_admissible, n_rewrites, rc)."""
+    T, L = _target(target), _lattice(lattice)
+    ext, _, _ = geometry(target, lattice)
+    n = int(np.prod(ext, dtype=np.uint64))
+    cost = np.empty(n, dtype=np.uint64)
+    arg = np.empty(n, dtype=np.uint16)
+    na, nr = C.c_uint64(), C.c_uint64()
+    LM = LE = None
+    cM = cE = None
+    if deps is not None:
+        LM, LE = _lattice(deps[0][0]), _lattice(deps[1][0])
+        cM = np.ascontiguousarray(deps[0][1], dtype=np.uint64)
+        cE = np.ascontiguousarray(deps[1][1], dtype=np.uint64)
+    g = None if goals is None else np.ascontiguousarray(goals, dtype=np.uint64)
+    rc = lib().orc_solve(
+        C.byref(T), C.byref(L),
+        C.byref(LM) if LM is not None else None, _p(cM, C.c_uint64) if cM is not None else None,
+        C.byref(LE) if LE is not None else None, _p(cE, C.c_uint64) if cE is not None else None,
+        _p(g, C.c_uint64) if g is not None else None, C.c_uint64(0 if g is None else len(g)),
+        _p(cost, C.c_uint64), _p(arg, C.c_uint16), C.byref(na), C.byref(nr))
+    if rc not in (0, -6):
+        raise ValueError("orc_solve failed: %d" % rc)
+    return {"cost": cost, "argmin": arg, "n_admissible": na.value, "n_rewrites": nr.value,
+            "rc": rc, "extents": ext}
+
+
+def cost_values(target, lattice, cost):
+    T, L = _target(target), _lattice(lattice)
+    cost = np.ascontiguousarray(cost, dtype=np.uint64)
+    v0 = np.empty_like(cost)
+    v1 = np.empty_like(cost)
+    rc = lib().orc_cost_values(C.byref(T), C.byref(L), _p(cost, C.c_uint64),
+                               _p(v0, C.c_uint64), _p(v1, C.c_uint64))
+    if rc:
+        raise ValueError("orc_cost_values failed: %d" % rc)
+    return v0, v1
+
+
+def merge(ext, merge_order, v0, v1, first_pass_by_lines=True):
+    """Canonical box list (numpy structured array, BOX_DTYPE) of a dense table."""
+    e = (C.c_uint32 * len(ext))(*ext)
+    mo = (C.c_uint32 * len(merge_order))(*merge_order)
+    v0 = np.ascontiguousarray(v0, dtype=np.uint64)
+    v1 = np.ascontiguousarray(v1, dtype=np.uint64)
+    out = C.POINTER(Box)()
+    nb = lib().orc_merge(C.c_uint32(len(ext)), e, mo, C.c_uint32(len(merge_order)),
+                         _p(v0, C.c_uint64), _p(v1, C.c_uint64),
+                         C.c_int(1 if first_pass_by_lines else 0), C.byref(out))
+    if nb < 0:
+        raise MemoryError("orc_merge failed: %d" % nb)
+    buf = C.string_at(out, nb * C.sizeof(Box))
+    lib().orc_free(out)
+    return np.frombuffer(buf, dtype=BOX_DTYPE).copy()
+
+
+def decompress(ext, boxes):
+    n = int(np.prod(ext, dtype=np.uint64))
+    e = (C.c_uint32 * len(ext))(*ext)
+    boxes = np.ascontiguousarray(boxes, dtype=BOX_DTYPE)
+    v0 = np.zeros(n, dtype=np.uint64)
+    v1 = np.zeros(n, dtype=np.uint64)
+    cover = np.zeros(n, dtype=np.uint8)
+    rc = lib().orc_decompress(C.c_uint32(len(ext)), e, C.cast(boxes.ctypes.data, C.POINTER(Box)),
+                              C.c_uint64(len(boxes)), _p(v0, C.c_uint64), _p(v1, C.c_uint64),
+                              _p(cover, C.c_uint8))
+    if rc:
+        raise ValueError("orc_decompress: box outside the lattice")
+    return v0, v1, cover
+
+
+def compress_table(target, lattice, cost, argmin):
+    """Both box lists of a solved table: (decision_boxes, cost_boxes)."""
+    ext, mo, _ = geometry(target, lattice)
+    dec = merge(ext, mo, argmin.astype(np.uint64), np.zeros(len(argmin), dtype=np.uint64))
+    v0, v1 = cost_values(target, lattice, cost)
+    cst = merge(ext, mo, v0, v1)
+    return dec, cst
+
+
+def solve_config(cfg, goals=None):
+    """Solve every lattice of a workloads.config() dict in order; returns {label: result}."""
+    out = {}
+    for label, lat, deps in cfg["lattices"]:
+        d = None
+        if deps:
+            d = tuple((next(l for (lb, l, _) in cfg["lattices"] if lb == name), out[name]["cost"])
+                      for name in deps)
+        out[label] = solve(cfg["target"], lat, deps=d, goals=goals)
+        out[label]["lattice"] = lat
+    return out

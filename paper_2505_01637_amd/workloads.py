@@ -1,0 +1,191 @@
+"""Seeded synthetic workloads: target descriptions and spec lattices.
+
+This module only *describes inputs* (plain Python dicts of integers).  It holds
+none of the method's arithmetic: no cost formula, no admissibility rule, no
+rewrite enumeration.  Both the HIP library binding and the CPU oracle binding
+marshal these dicts into their own C structs.
+
+The five configurations follow the paper's workload shapes (Section 7: the
+1x2048x16384 bf16->f32 vector-matrix product and the 2048-square f32 matmul)
+and its target description (Section 2.2: levels ordered RF, VRF, L1, GL;
+Section 3: microkernel costs k_p, loop constant s, per-level weights).  The
+paper does not print its fitted coefficients, so seeded integers stand in.
+"""
+
+MASK64 = (1 << 64) - 1
+UNBOUNDED = MASK64
+
+# microkernel kinds
+MK_SCALAR_FMA = 0
+MK_BCAST_VEC_MULADD = 1
+MK_BF16_DOT = 2
+MK_SCALAR_ADDRELU = 3
+MK_VEC_ADDRELU = 4
+
+# spec kinds
+KIND_MATMUL_ACCUM = 0
+KIND_BIAS_ADD_RELU = 1
+KIND_FUSED_MM_ADD_RELU = 2
+
+MAX_LEVELS = 4
+MAX_OPERANDS = 5
+
+
+class SplitMix64:
+    """Counter-based 64-bit generator (Steele, Lea, Flood 2014)."""
+
+    def __init__(self, seed):
+        self.state = seed & MASK64
+
+    def next(self):
+        self.state = (self.state + 0x9E3779B97F4A7C15) & MASK64
+        z = self.state
+        z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & MASK64
+        z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & MASK64
+        return z ^ (z >> 31)
+
+    def draw(self, lo, hi):
+        return lo + self.next() % (hi - lo + 1)
+
+
+def _empty_target(n_levels, capacities):
+    z3 = lambda: [[[0, 0] for _ in range(MAX_LEVELS)] for _ in range(MAX_LEVELS)]
+    return {
+        "n_levels": n_levels,
+        "capacity_bytes": list(capacities) + [0] * (MAX_LEVELS - len(capacities)),
+        "load_coef": z3(),    # [src][dst][same|transposed], dst < src
+        "store_coef": z3(),   # [dst][src][same|transposed]
+        "convert_coef": 0,
+        "zero_coef": [0] * MAX_LEVELS,
+        "loop_overhead": 0,
+        "microkernels": [],   # list of (kind, lanes, cost); order = rewrite-id order
+    }
+
+
+def _lattice(kind, sizes, layout=(0, 0, 0, 0, 0), dtype=(0, 0, 0, 0, 0),
+             base_bytes=(4, 4, 4, 4, 4)):
+    return {
+        "kind": kind,
+        "sizes": [list(s) for s in sizes],          # b, m, k, n: ascending, contain 1
+        "layout_coord": list(layout),
+        "dtype_coord": list(dtype),
+        "base_dtype_bytes": list(base_bytes),
+    }
+
+
+FOUR_LEVEL_CAPS = (256, 512, 32 * 1024, UNBOUNDED)   # RF 64 f32, VRF 16x8 f32, L1 32 KiB, GL
+
+
+def _four_level_target(rng):
+    """Level weights grow away from RF; a Move pays weight(src)+weight(dst)."""
+    t = _empty_target(4, FOUR_LEVEL_CAPS)
+    w = [1, 0, 0, 0]
+    for l in range(1, 4):
+        w[l] = w[l - 1] + rng.draw(1, 5)
+    for src in range(1, 4):
+        for dst in range(src):
+            t["load_coef"][src][dst][0] = w[src] + w[dst]
+            t["store_coef"][dst][src][0] = w[src] + w[dst]
+    t["loop_overhead"] = rng.draw(0, 4)
+    t["microkernels"].append((MK_SCALAR_FMA, 1, rng.draw(1, 2)))
+    t["microkernels"].append((MK_BCAST_VEC_MULADD, 8, rng.draw(1, 2)))
+    return t, w
+
+
+def _add_transposed(t, rng):
+    for src in range(1, 4):
+        for dst in range(src):
+            add = rng.draw(1, 8)
+            t["load_coef"][src][dst][1] = t["load_coef"][src][dst][0] + add
+            t["store_coef"][dst][src][1] = t["store_coef"][dst][src][0] + add
+
+
+def sizes_config4():
+    return [1, 2, 4] + list(range(8, 129, 8)) + [256, 512]
+
+
+def sizes_config5():
+    return [1, 2, 4] + list(range(8, 257, 8)) + [512, 1024, 2048]
+
+
+def config(number, seed=None, max_size=None):
+    """Return {"name", "target", "lattices": [(label, lattice, dep_labels)]}.
+
+    `max_size` drops every allowed size above it (used by tests to get a small
+    lattice of the same structure); None keeps the full configuration.
+    """
+    rng = SplitMix64(number if seed is None else seed)
+    keep = (lambda xs: [x for x in xs if max_size is None or x <= max_size])
+    one = [1]
+    if number == 1:
+        t = _empty_target(2, (256, 32 * 1024))
+        t["load_coef"][1][0][0] = rng.draw(1, 16)
+        t["store_coef"][0][1][0] = rng.draw(1, 16)
+        t["loop_overhead"] = rng.draw(0, 4)
+        t["microkernels"].append((MK_SCALAR_FMA, 1, 1))
+        r = keep(range(1, 17))
+        lats = [("M", _lattice(KIND_MATMUL_ACCUM, [one, r, r, r]), [])]
+    elif number == 2:
+        t, _ = _four_level_target(rng)
+        r = keep(range(1, 65))
+        lats = [("M", _lattice(KIND_MATMUL_ACCUM, [one, r, r, r]), [])]
+    elif number == 3:
+        t, _ = _four_level_target(rng)
+        _add_transposed(t, rng)
+        t["convert_coef"] = rng.draw(1, 4)
+        t["microkernels"].append((MK_BF16_DOT, 16, rng.draw(1, 2)))
+        ks = keep([1 << i for i in range(12)])
+        ns = keep([1 << i for i in range(15)])
+        lats = [("M", _lattice(KIND_MATMUL_ACCUM, [one, one, ks, ns],
+                               layout=(0, 1, 0, 0, 0), dtype=(1, 1, 0, 0, 0),
+                               base_bytes=(2, 2, 4, 4, 4)), [])]
+    elif number == 4:
+        t, _ = _four_level_target(rng)
+        _add_transposed(t, rng)
+        bs = keep([1, 2, 4, 8, 16])
+        r = keep(sizes_config4())
+        lats = [("M", _lattice(KIND_MATMUL_ACCUM, [bs, r, r, r], layout=(1, 1, 1, 0, 0)), [])]
+    elif number == 5:
+        t, w = _four_level_target(rng)
+        _add_transposed(t, rng)
+        t["zero_coef"] = list(w)
+        t["microkernels"].append((MK_SCALAR_ADDRELU, 1, 1))
+        t["microkernels"].append((MK_VEC_ADDRELU, 8, 1))
+        r = keep(sizes_config5())
+        lats = [
+            ("M", _lattice(KIND_MATMUL_ACCUM, [one, r, r, r], layout=(1, 1, 1, 0, 0)), []),
+            # operands: in (m x n), bias (n), out (m x n)
+            ("E", _lattice(KIND_BIAS_ADD_RELU, [one, r, one, r], layout=(1, 0, 1, 0, 0)), []),
+            # operands: lhs, rhs, bias, out (+ level of the intermediate)
+            ("F", _lattice(KIND_FUSED_MM_ADD_RELU, [one, r, r, r], layout=(1, 1, 0, 1, 0)),
+             ["M", "E"]),
+        ]
+    else:
+        raise ValueError("config number must be 1..5")
+    return {"name": "config%d" % number, "target": t, "lattices": lats}
+
+
+def n_level_axes(kind):
+    return 5 if kind == KIND_FUSED_MM_ADD_RELU else 3
+
+
+def n_operands(kind):
+    return 4 if kind == KIND_FUSED_MM_ADD_RELU else 3
+
+
+def coord_extents(target, lattice):
+    """Extent of every coordinate axis: shape indices, level axes, layout bits, dtype bits."""
+    kind = lattice["kind"]
+    ext = [len(s) for s in lattice["sizes"]]
+    ext += [target["n_levels"]] * n_level_axes(kind)
+    nops = n_operands(kind)
+    ext += [2] * sum(1 for i in range(nops) if lattice["layout_coord"][i])
+    ext += [2] * sum(1 for i in range(nops) if lattice["dtype_coord"][i])
+    return ext
+
+
+def n_specs(target, lattice):
+    n = 1
+    for e in coord_extents(target, lattice):
+        n *= e
+    return n

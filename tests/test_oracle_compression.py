@@ -1,0 +1,95 @@
+"""Pins of the oracle's box merge (Section 4.1, Figure 2): unit rectangles merged with
+adjacent equal-valued rectangles whose union fills its bounding box."""
+import numpy as np
+
+from oracle import brute_force as B
+from oracle import oracle as O
+from paper_2505_01637_amd import workloads as W
+
+import util
+
+
+def random_table(ext, n_values, seed, run=3):
+    """Blocky random values so that runs exist along every axis."""
+    rng = np.random.default_rng(seed)
+    coarse = [max(1, (e + run - 1) // run) for e in ext]
+    base = rng.integers(0, n_values, size=coarse, dtype=np.uint64)
+    idx = np.ix_(*[np.arange(e) // run for e in ext])
+    return base[idx].copy()
+
+
+def check_valid_decomposition(ext, boxes, v0, v1):
+    d0, d1, cover = O.decompress(ext, boxes)
+    assert (cover == 1).all()                       # disjoint and covering
+    assert np.array_equal(d0, v0.ravel()) and np.array_equal(d1, v1.ravel())   # every box constant
+
+
+def test_merge_matches_dictionary_implementation():
+    for seed, ext, mo in [(0, [4, 5, 3], [2, 1, 0]), (1, [3, 4, 2, 2], [1, 0, 3, 2]),
+                          (2, [6, 6], [1, 0]), (3, [2, 3, 4, 2, 2], [3, 2, 1, 0, 4])]:
+        v0 = random_table(ext, 3, seed, run=2)
+        v1 = np.zeros_like(v0)
+        want = B.merge_boxes(ext, mo, {x: int(v0[x]) for x in util.all_coords(ext)})
+        for by_lines in (False, True):
+            got = O.merge(ext, mo, v0.ravel(), v1.ravel(), first_pass_by_lines=by_lines)
+            assert [(lo, hi, a) for lo, hi, a, _ in util.boxes_as_tuples(got, len(ext))] == want
+            check_valid_decomposition(ext, got, v0, v1)
+
+
+def test_merge_fixed_point_constant_and_bounds():
+    ext, mo = [5, 4, 6], [2, 1, 0]
+    v0 = random_table(ext, 4, 5)
+    v1 = random_table(ext, 2, 6)
+    boxes = O.merge(ext, mo, v0.ravel(), v1.ravel())
+    assert 1 <= len(boxes) <= v0.size
+    check_valid_decomposition(ext, boxes, v0, v1)
+    # merging the decompressed table again gives the same list
+    d0, d1, _ = O.decompress(ext, boxes)
+    again = O.merge(ext, mo, d0, d1)
+    assert boxes.tobytes() == again.tobytes()
+    # a constant table is one box spanning the lattice
+    one = O.merge(ext, mo, np.full(120, 7, dtype=np.uint64), np.zeros(120, dtype=np.uint64))
+    assert len(one) == 1 and list(one[0]["lo"][:3]) == [0, 0, 0] and list(one[0]["hi"][:3]) == [4, 3, 5]
+    # all-distinct values cannot merge
+    distinct = O.merge(ext, mo, np.arange(120, dtype=np.uint64), np.zeros(120, dtype=np.uint64))
+    assert len(distinct) == 120
+    # sorted by lo, first axis most significant
+    los = [tuple(b["lo"][:3]) for b in boxes]
+    assert los == sorted(los)
+
+
+def test_merge_is_not_a_plain_run_length_encoding():
+    """An L-shaped region must split into boxes that each fill their bounding box (Figure 2)."""
+    v = np.zeros((3, 3), dtype=np.uint64)
+    v[0, :] = 1
+    v[:, 0] = 1                      # an L of ones
+    boxes = util.boxes_as_tuples(O.merge([3, 3], [1, 0], v.ravel(), np.zeros(9, dtype=np.uint64)), 2)
+    assert boxes == [((0, 0), (0, 2), 1, 0), ((1, 0), (2, 0), 1, 0), ((1, 1), (2, 2), 0, 0)]
+
+
+def test_cost_values_are_reduced_fractions_and_table_roundtrip():
+    """Costs are compared after normalising to the Spec's volume (Section 4.1); the
+    reduced fraction must reproduce the cost exactly."""
+    cfg = W.config(4, seed=4, max_size=16)
+    t, lat = cfg["target"], cfg["lattices"][0][1]
+    r = O.solve(t, lat)
+    ext, mo, _ = O.geometry(t, lat)
+    assert mo == [3, 2, 1, 0, 6, 5, 4, 9, 8, 7]
+    v0, v1 = O.cost_values(t, lat, r["cost"])
+    sizes = [np.array(s, dtype=np.uint64) for s in lat["sizes"]]
+    grid = np.indices(ext[:4]).reshape(4, -1)
+    vol = np.ones(grid.shape[1], dtype=np.uint64)
+    for d in range(4):
+        vol *= sizes[d][grid[d]]
+    per = int(np.prod(ext[4:]))
+    vol = np.repeat(vol, per)
+    fin = r["cost"] != O.INF
+    assert (v1[~fin] == 0).all() and (v0[~fin] == O.INF).all()
+    assert np.array_equal(v0[fin] * (vol[fin] // v1[fin]), r["cost"][fin])
+    assert (vol[fin] % v1[fin] == 0).all() and (np.gcd(v0[fin], v1[fin]) == 1).all()
+    dec, cst = O.compress_table(t, lat, r["cost"], r["argmin"])
+    d0, _, cover = O.decompress(ext, dec)
+    assert (cover == 1).all() and np.array_equal(d0.astype(np.uint16), r["argmin"])
+    c0, c1, cover = O.decompress(ext, cst)
+    assert (cover == 1).all() and np.array_equal(c0, v0) and np.array_equal(c1, v1)
+    assert len(dec) < len(r["argmin"]) // 4          # decisions do compress

@@ -1,0 +1,196 @@
+/*
+ * morello_mi355x.h -- C ABI of the MI355X (gfx950) memo-table solver.
+ *
+ * The library fills, bottom-up on the GPU, the memoization table of the
+ * dynamic-programming synthesis of Section 4 of the paper over a lattice of
+ * Matmul Specs, and compresses it into boxes as in Section 4.1.
+ *
+ * Conventions
+ *   - Every function returns an int32_t status: MRL_OK or a negative MRL_E_*.
+ *     No exception or abort crosses the boundary.  mrl_last_error() returns a
+ *     thread-local, library-owned string describing the last failure.
+ *   - Handles (mrl_target, mrl_table) are created by the library and
+ *     destroyed by the caller.  Descriptor structs are copied: the library
+ *     keeps no caller host pointer after a call returns.
+ *   - "host" / "device" is stated for every pointer.  Device buffers handed to
+ *     mrl_solve stay owned by the caller and must outlive the mrl_table.
+ *   - All costs are unsigned 64-bit integers; MRL_INF marks a Spec with no
+ *     implementation; finite costs are kept below 2^62.
+ */
+#ifndef MORELLO_MI355X_H
+#define MORELLO_MI355X_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  MRL_OK = 0,
+  MRL_E_INVAL = -1,     /* malformed descriptor or argument                    */
+  MRL_E_NOMEM = -2,     /* scratch buffer too small / host allocation failed   */
+  MRL_E_HIP = -3,       /* a HIP runtime call failed                           */
+  MRL_E_RANGE = -4,     /* coordinate outside the lattice                      */
+  MRL_E_BUFSZ = -5,     /* caller's output buffer too small; *n_out = needed   */
+  MRL_E_OVERFLOW = -6   /* a finite cost reached 2^62                          */
+};
+
+#define MRL_INF  UINT64_MAX     /* cost of a Spec without implementation */
+#define MRL_NONE 0xFFFFu        /* its rewrite id                        */
+
+enum { MRL_MAX_LEVELS = 4, MRL_MAX_OPERANDS = 5, MRL_MAX_DIMS = 16, MRL_MAX_MK = 8,
+       MRL_MAX_SIZES = 255 };
+
+/* ---------------------------------------------------------------------------
+ * Target (Section 2.2: memory levels ordered RF, VRF, L1, GL with per-level
+ * bounds; Section 3: microkernel costs k_p, loop constant s, per-level Move
+ * weights).  Level 0 is the fastest.  A Move goes to a strictly lower level
+ * index only, and costs coef * (elements of the operand): load_coef for an
+ * operand that is read, store_coef for one that is written, both for the
+ * accumulated output of a MatmulAccum.  A zero coefficient forbids the Move.
+ */
+typedef enum {
+  MRL_MK_SCALAR_FMA = 0,        /* 1x1x1x1 MatmulAccum, all operands in level 0, f32          */
+  MRL_MK_BCAST_VEC_MULADD = 1,  /* Figure 1: b=m=k=1, n % lanes == 0, lhs level 0, rhs and
+                                   out level 1, f32, row-major                               */
+  MRL_MK_BF16_DOT = 2,          /* m=n=1, k % lanes == 0, bf16 lhs/rhs in level 1 (rhs
+                                   column-major), f32 out in level 0                         */
+  MRL_MK_SCALAR_ADDRELU = 3,    /* bias-add+ReLU, m=n=1, all in level 0                        */
+  MRL_MK_VEC_ADDRELU = 4        /* bias-add+ReLU, m=1, n % lanes == 0, all level 1, row-major  */
+} mrl_mk_kind;
+
+typedef struct { uint32_t kind; uint32_t lanes; uint64_t cost; } mrl_microkernel;
+
+typedef struct {
+  uint32_t n_levels;                                          /* 1..4                              */
+  uint64_t capacity_bytes[MRL_MAX_LEVELS];                    /* UINT64_MAX = unbounded            */
+  uint32_t load_coef[MRL_MAX_LEVELS][MRL_MAX_LEVELS][2];      /* [src][dst][same|transposed], dst<src */
+  uint32_t store_coef[MRL_MAX_LEVELS][MRL_MAX_LEVELS][2];     /* [dst][src][same|transposed]       */
+  uint32_t convert_coef;                                      /* bf16->f32, per element, added to a Move */
+  uint32_t zero_coef[MRL_MAX_LEVELS];                         /* per element of the bufferized intermediate */
+  uint32_t loop_overhead;                                     /* s of Section 3, paid by every loop */
+  uint32_t n_microkernels;
+  mrl_microkernel mk[MRL_MAX_MK];                             /* order = rewrite-id order          */
+} mrl_target_desc;
+
+typedef struct mrl_target mrl_target;
+
+/* desc: host.  *out receives a new handle.  MRL_E_INVAL on a malformed descriptor. */
+int32_t mrl_target_create(const mrl_target_desc* desc, mrl_target** out);
+void mrl_target_destroy(mrl_target* t);
+
+/* ---------------------------------------------------------------------------
+ * Lattice of Specs (Section 2.2 reduced to integer coordinates, Section 4.1).
+ * Coordinate vector x, in this order:
+ *   index of b, m, k, n in the allowed-size lists;
+ *   memory level of each operand (kind FUSED: then the intermediate's level);
+ *   one layout bit (0 row-major, 1 column-major) per operand with layout_coord;
+ *   one dtype bit (0 f32, 1 bf16) per operand with dtype_coord.
+ * Dense tables are in C order of x (last coordinate fastest).
+ *
+ * Operands.  MATMUL_ACCUM: lhs (b*m*k, read), rhs (b*k*n, read), out (b*m*n,
+ * accumulated).  BIAS_ADD_RELU: in (m*n, read), bias (n, read), out (m*n,
+ * written); b and k must be pinned to 1.  FUSED_MM_ADD_RELU (Section 2.1,
+ * Matmul -> bias add -> ReLU split once by bufferize): lhs, rhs, bias (read),
+ * out (written), intermediate m*n f32; b pinned to 1; only m and n are tiled.
+ */
+typedef enum { MRL_KIND_MATMUL_ACCUM = 0, MRL_KIND_BIAS_ADD_RELU = 1,
+               MRL_KIND_FUSED_MM_ADD_RELU = 2 } mrl_kind;
+
+typedef struct {
+  uint32_t kind;
+  uint32_t n_sizes[4];                        /* 1..MRL_MAX_SIZES each                        */
+  const uint32_t* sizes[4];                   /* host; ascending, sizes[d][0] == 1            */
+  uint8_t layout_coord[MRL_MAX_OPERANDS];
+  uint8_t dtype_coord[MRL_MAX_OPERANDS];      /* MATMUL_ACCUM inputs only                     */
+  uint8_t base_dtype_bytes[MRL_MAX_OPERANDS]; /* 4 or 2; used when the operand has no dtype bit */
+} mrl_lattice_desc;
+
+/* Number of coordinates and their extents (host outputs; extents has room for MRL_MAX_DIMS). */
+int32_t mrl_geometry(const mrl_target* t, const mrl_lattice_desc* lat,
+                     uint32_t* n_dims, uint32_t* extents, uint64_t* n_specs);
+
+/* ---------------------------------------------------------------------------
+ * Solve = fill (Section 4, bottom-up over dependency levels) + compress
+ * (Section 4.1).  For every Spec the table holds
+ *   cost   = min over applicable rewrites of (affine rewrite cost of Section 3
+ *            applied to the costs of the rewrite's sub-Specs),
+ *   argmin = the lowest rewrite id reaching that minimum (see mrl_rewrite_decode),
+ * or (MRL_INF, MRL_NONE) when the Spec's operands do not fit their levels or
+ * no complete program exists.
+ */
+typedef struct {
+  uint64_t n_specs, n_admissible, n_rewrites; /* rewrites enumerated over all admissible Specs */
+  uint32_t n_levels_run;                      /* dependency levels = fill launches             */
+  float fill_ms, compress_ms;                 /* device time, HIP events on the given stream   */
+  uint64_t n_decision_boxes, n_cost_boxes;
+  uint64_t scratch_used;                      /* bytes of d_scratch actually needed            */
+} mrl_stats;
+
+/* Sizes of the device buffers mrl_solve needs.  scratch_bytes is sufficient for
+ * any table contents; mrl_solve accepts less and fails with MRL_E_NOMEM if the
+ * data turn out to need more. */
+int32_t mrl_table_bytes(const mrl_target* t, const mrl_lattice_desc* lat,
+                        size_t* cost_bytes, size_t* argmin_bytes, size_t* scratch_bytes);
+
+typedef struct mrl_table mrl_table;
+
+/* deps: host array of solved tables a FUSED lattice reads: {MATMUL_ACCUM table,
+ * BIAS_ADD_RELU table} with the same m, k, n (m, n) size lists and target;
+ * NULL / 0 otherwise.  d_cost (uint64 per Spec), d_argmin (uint16 per Spec) and
+ * d_scratch are DEVICE pointers, 256-byte aligned, owned by the caller and
+ * referenced by *out until mrl_table_destroy.  hip_stream: a hipStream_t (or
+ * NULL for the default stream); the call returns after the stream has drained.
+ * stats: host, optional. */
+int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat,
+                  const mrl_table* const* deps, uint32_t n_deps,
+                  void* d_cost, void* d_argmin, void* d_scratch, size_t scratch_bytes,
+                  void* hip_stream, mrl_table** out, mrl_stats* stats);
+void mrl_table_destroy(mrl_table* tab);
+
+/* ---------------------------------------------------------------------------
+ * Query (Section 4: "if the memoization database contains a rewrite for that
+ * Spec, return it").  specs, cost_out, rewrite_out: host arrays of n. */
+typedef struct { uint32_t x[MRL_MAX_DIMS]; } mrl_coord;
+int32_t mrl_query(const mrl_table* tab, const mrl_coord* specs, size_t n,
+                  uint64_t* cost_out, uint16_t* rewrite_out);
+
+/* Rewrite ids, ascending = tie-break priority:
+ *   [0, n_mk)                       select(microkernel j)
+ *   then ((operand*(n_levels-1) + dst)*2 + transposed)*2 + convert   Moves
+ *   then dim*max_sizes + index of the tile size                      tiles
+ *   then one id                                                      bufferize */
+typedef struct { uint8_t cls; /* 0 microkernel, 1 move, 2 tile, 3 bufferize */
+                 uint8_t operand_or_dim, dst_level, transposed, convert;
+                 uint32_t tile_size, mk_index; } mrl_rewrite;
+int32_t mrl_rewrite_decode(const mrl_table* tab, uint16_t id, mrl_rewrite* out);
+
+/* shape: b,m,k,n sizes (must be in the lists); levels / layouts / dtypes: per
+ * operand (FUSED: levels[4] = intermediate); entries without a coordinate are ignored. */
+int32_t mrl_coord_of_spec(const mrl_table* tab, const uint32_t shape[4], const uint8_t* levels,
+                          const uint8_t* layouts, const uint8_t* dtypes, mrl_coord* out);
+
+/* ---------------------------------------------------------------------------
+ * Compressed table (Section 4.1, Figure 2): axis-aligned boxes [lo, hi]
+ * (inclusive) of equal value that partition the lattice, sorted by lo.
+ * DECISION: v0 = rewrite id, v1 = 0.  COST: the cost divided by the Spec's
+ * volume b*m*k*n as a reduced fraction v0/v1; (MRL_INF, 0) for MRL_INF. */
+typedef struct { uint16_t lo[MRL_MAX_DIMS], hi[MRL_MAX_DIMS]; uint64_t v0, v1; } mrl_box;
+typedef enum { MRL_BOXES_DECISION = 0, MRL_BOXES_COST = 1 } mrl_box_list;
+
+/* out: host array of cap boxes, or NULL to get the count only in *n_out. */
+int32_t mrl_emit_compressed(const mrl_table* tab, uint32_t which,
+                            mrl_box* out, size_t cap, size_t* n_out);
+
+/* Test support: copy the dense tables to host arrays of n_specs entries each
+ * (either pointer may be NULL). */
+int32_t mrl_copy_dense(const mrl_table* tab, uint64_t* cost_host, uint16_t* argmin_host);
+
+const char* mrl_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,271 @@
+"""Thin ctypes binding of libmorello_mi355x.so (include/morello_mi355x.h).
+
+Argument marshalling only: every step of the hot path runs in the library's
+HIP kernels.  PyTorch supplies device memory and the stream.  There is no CPU
+fallback: importing works without a GPU, calling `solve` does not.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmorello_mi355x.so")
+
+INF = (1 << 64) - 1
+NONE = 0xFFFF
+MAX_DIMS = 16
+
+OK, E_INVAL, E_NOMEM, E_HIP, E_RANGE, E_BUFSZ, E_OVERFLOW = 0, -1, -2, -3, -4, -5, -6
+
+EXPORTS = ["mrl_target_create", "mrl_target_destroy", "mrl_geometry", "mrl_table_bytes", "mrl_solve",
+           "mrl_table_destroy", "mrl_query", "mrl_rewrite_decode", "mrl_coord_of_spec",
+           "mrl_emit_compressed", "mrl_copy_dense", "mrl_last_error"]
+
+
+class MorelloError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__("mrl error %d: %s" % (code, msg))
+        self.code = code
+
+
+class _Microkernel(C.Structure):
+    _fields_ = [("kind", C.c_uint32), ("lanes", C.c_uint32), ("cost", C.c_uint64)]
+
+
+class _TargetDesc(C.Structure):
+    _fields_ = [("n_levels", C.c_uint32),
+                ("capacity_bytes", C.c_uint64 * 4),
+                ("load_coef", C.c_uint32 * 2 * 4 * 4),
+                ("store_coef", C.c_uint32 * 2 * 4 * 4),
+                ("convert_coef", C.c_uint32),
+                ("zero_coef", C.c_uint32 * 4),
+                ("loop_overhead", C.c_uint32),
+                ("n_microkernels", C.c_uint32),
+                ("mk", _Microkernel * 8)]
+
+
+class _LatticeDesc(C.Structure):
+    _fields_ = [("kind", C.c_uint32),
+                ("n_sizes", C.c_uint32 * 4),
+                ("sizes", C.POINTER(C.c_uint32) * 4),
+                ("layout_coord", C.c_uint8 * 5),
+                ("dtype_coord", C.c_uint8 * 5),
+                ("base_dtype_bytes", C.c_uint8 * 5)]
+
+
+class Stats(C.Structure):
+    _fields_ = [("n_specs", C.c_uint64), ("n_admissible", C.c_uint64), ("n_rewrites", C.c_uint64),
+                ("n_levels_run", C.c_uint32), ("fill_ms", C.c_float), ("compress_ms", C.c_float),
+                ("n_decision_boxes", C.c_uint64), ("n_cost_boxes", C.c_uint64),
+                ("scratch_used", C.c_uint64)]
+
+    def as_dict(self):
+        return {k: getattr(self, k) for k, _ in self._fields_}
+
+
+class _Coord(C.Structure):
+    _fields_ = [("x", C.c_uint32 * MAX_DIMS)]
+
+
+class Rewrite(C.Structure):
+    _fields_ = [("cls", C.c_uint8), ("operand_or_dim", C.c_uint8), ("dst_level", C.c_uint8),
+                ("transposed", C.c_uint8), ("convert", C.c_uint8),
+                ("tile_size", C.c_uint32), ("mk_index", C.c_uint32)]
+
+
+BOX_DTYPE = np.dtype([("lo", np.uint16, (MAX_DIMS,)), ("hi", np.uint16, (MAX_DIMS,)),
+                      ("v0", np.uint64), ("v1", np.uint64)])
+
+_lib = None
+
+
+def lib():
+    """Load the built library; raises if it has not been built (no fallback)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("%s is missing: run __graft_entry__.build() (hipcc, gfx950)" % LIB_PATH)
+        _lib = C.CDLL(LIB_PATH)
+        for name in EXPORTS:
+            getattr(_lib, name).restype = C.c_int32
+        _lib.mrl_last_error.restype = C.c_char_p
+        _lib.mrl_target_destroy.restype = None
+        _lib.mrl_table_destroy.restype = None
+    return _lib
+
+
+def _check(rc):
+    if rc != 0:
+        raise MorelloError(rc, lib().mrl_last_error().decode())
+
+
+def _target_desc(t):
+    d = _TargetDesc()
+    d.n_levels = t["n_levels"]
+    for l in range(4):
+        d.capacity_bytes[l] = t["capacity_bytes"][l]
+        d.zero_coef[l] = t["zero_coef"][l]
+        for k in range(4):
+            for x in range(2):
+                d.load_coef[l][k][x] = t["load_coef"][l][k][x]
+                d.store_coef[l][k][x] = t["store_coef"][l][k][x]
+    d.convert_coef = t["convert_coef"]
+    d.loop_overhead = t["loop_overhead"]
+    d.n_microkernels = len(t["microkernels"])
+    for j, (kind, lanes, cost) in enumerate(t["microkernels"][:8]):
+        d.mk[j].kind, d.mk[j].lanes, d.mk[j].cost = kind, lanes, cost
+    return d
+
+
+def _lattice_desc(lat):
+    d = _LatticeDesc()
+    d.kind = lat["kind"]
+    keep = []
+    for a in range(4):
+        arr = (C.c_uint32 * max(1, len(lat["sizes"][a])))(*lat["sizes"][a])
+        keep.append(arr)
+        d.n_sizes[a] = len(lat["sizes"][a])
+        d.sizes[a] = C.cast(arr, C.POINTER(C.c_uint32))
+    for i in range(5):
+        d.layout_coord[i] = lat["layout_coord"][i]
+        d.dtype_coord[i] = lat["dtype_coord"][i]
+        d.base_dtype_bytes[i] = lat["base_dtype_bytes"][i]
+    d._keep = keep
+    return d
+
+
+class Target:
+    def __init__(self, desc):
+        self._h = C.c_void_p()
+        _check(lib().mrl_target_create(C.byref(_target_desc(desc)), C.byref(self._h)))
+
+    def close(self):
+        if self._h:
+            lib().mrl_target_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def geometry(target, lattice):
+    nd, n = C.c_uint32(), C.c_uint64()
+    ext = (C.c_uint32 * MAX_DIMS)()
+    _check(lib().mrl_geometry(target._h, C.byref(_lattice_desc(lattice)), C.byref(nd), ext, C.byref(n)))
+    return list(ext[:nd.value]), n.value
+
+
+def table_bytes(target, lattice):
+    a, b, c = C.c_size_t(), C.c_size_t(), C.c_size_t()
+    _check(lib().mrl_table_bytes(target._h, C.byref(_lattice_desc(lattice)), C.byref(a), C.byref(b), C.byref(c)))
+    return a.value, b.value, c.value
+
+
+class Table:
+    """A solved table.  Holds the torch tensors that back it."""
+
+    def __init__(self, handle, target, lattice, extents, tensors, stats):
+        self._h, self.target, self.lattice = handle, target, lattice
+        self.extents, self._tensors, self.stats = extents, tensors, stats
+        self.n_specs = int(np.prod(extents, dtype=np.uint64))
+
+    def close(self):
+        if self._h:
+            lib().mrl_table_destroy(self._h)
+            self._h = C.c_void_p()
+            self._tensors = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def query(self, coords):
+        coords = np.ascontiguousarray(coords, dtype=np.uint32).reshape(-1, len(self.extents))
+        n = len(coords)
+        buf = np.zeros((n, MAX_DIMS), dtype=np.uint32)
+        buf[:, :coords.shape[1]] = coords
+        cost = np.empty(n, dtype=np.uint64)
+        rw = np.empty(n, dtype=np.uint16)
+        _check(lib().mrl_query(self._h, buf.ctypes.data_as(C.POINTER(_Coord)), C.c_size_t(n),
+                               cost.ctypes.data_as(C.POINTER(C.c_uint64)),
+                               rw.ctypes.data_as(C.POINTER(C.c_uint16))))
+        return cost, rw
+
+    def rewrite_decode(self, rid):
+        r = Rewrite()
+        _check(lib().mrl_rewrite_decode(self._h, C.c_uint16(rid), C.byref(r)))
+        return r
+
+    def coord_of_spec(self, shape, levels, layouts=None, dtypes=None):
+        sh = (C.c_uint32 * 4)(*shape)
+        lv = (C.c_uint8 * 5)(*(list(levels) + [0] * (5 - len(levels))))
+        ly = (C.c_uint8 * 5)(*(list(layouts or []) + [0] * (5 - len(layouts or []))))
+        dt = (C.c_uint8 * 5)(*(list(dtypes or []) + [0] * (5 - len(dtypes or []))))
+        out = _Coord()
+        _check(lib().mrl_coord_of_spec(self._h, sh, lv, ly, dt, C.byref(out)))
+        return list(out.x[:len(self.extents)])
+
+    def boxes(self, which):
+        """which: 0 decisions, 1 costs.  numpy structured array (BOX_DTYPE), sorted by lo."""
+        n = C.c_size_t()
+        _check(lib().mrl_emit_compressed(self._h, C.c_uint32(which), None, C.c_size_t(0), C.byref(n)))
+        out = np.zeros(n.value, dtype=BOX_DTYPE)
+        _check(lib().mrl_emit_compressed(self._h, C.c_uint32(which), C.c_void_p(out.ctypes.data),
+                                         C.c_size_t(n.value), C.byref(n)))
+        return out
+
+    def dense(self):
+        cost = np.empty(self.n_specs, dtype=np.uint64)
+        arg = np.empty(self.n_specs, dtype=np.uint16)
+        _check(lib().mrl_copy_dense(self._h, cost.ctypes.data_as(C.POINTER(C.c_uint64)),
+                                    arg.ctypes.data_as(C.POINTER(C.c_uint16))))
+        return cost, arg
+
+
+def solve(target, lattice, deps=(), scratch_bytes=None, stream=None, buffers=None):
+    """Fill and compress one lattice on the current CUDA/HIP device.
+
+    target: Target; lattice: dict (workloads.py); deps: solved Tables a fused
+    lattice reads.  buffers: optional (cost, argmin, scratch) torch uint8
+    tensors to reuse.  Device memory comes from torch; nothing else does.
+    """
+    import torch
+    if not torch.cuda.is_available():
+        raise RuntimeError("mrl solve needs a GPU: there is no CPU path")
+    L = _lattice_desc(lattice)
+    ext, _ = geometry(target, lattice)
+    cb, ab, sb = table_bytes(target, lattice)
+    if scratch_bytes is not None:
+        sb = scratch_bytes
+    if buffers is None:
+        dev = torch.device("cuda", torch.cuda.current_device())
+        buffers = (torch.empty(cb, dtype=torch.uint8, device=dev),
+                   torch.empty(ab, dtype=torch.uint8, device=dev),
+                   torch.empty(sb, dtype=torch.uint8, device=dev))
+    d_cost, d_arg, d_scr = buffers
+    assert d_cost.numel() >= cb and d_arg.numel() >= ab
+    st = torch.cuda.current_stream() if stream is None else stream
+    dep_arr = (C.c_void_p * max(1, len(deps)))(*[d._h for d in deps])
+    h = C.c_void_p()
+    stats = Stats()
+    rc = lib().mrl_solve(target._h, C.byref(L), dep_arr if deps else None, C.c_uint32(len(deps)),
+                         C.c_void_p(d_cost.data_ptr()), C.c_void_p(d_arg.data_ptr()),
+                         C.c_void_p(d_scr.data_ptr()), C.c_size_t(d_scr.numel()),
+                         C.c_void_p(st.cuda_stream), C.byref(h), C.byref(stats))
+    _check(rc)
+    return Table(h, target, lattice, ext, buffers, stats)
+
+
+def solve_config(cfg, scratch_bytes=None):
+    """Solve every lattice of a workloads.config() dict, in order.  Returns (Target, {label: Table})."""
+    target = Target(cfg["target"])
+    out = {}
+    for label, lat, deps in cfg["lattices"]:
+        out[label] = solve(target, lat, deps=[out[d] for d in deps], scratch_bytes=scratch_bytes)
+    return target, out

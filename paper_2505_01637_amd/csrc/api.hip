@@ -1,0 +1,594 @@
+// C ABI of the library (include/morello_mi355x.h) and the host side of the
+// solver: descriptor validation, coordinate system (Section 4.1), dependency
+// levels of the bottom-up fill (Section 4 run in reverse), launches.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/morello_mi355x.h"
+#include "compress.h"
+#include "dev_params.h"
+
+using namespace mrl;
+
+static thread_local char g_err[512] = "";
+
+static int32_t fail(int32_t code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+#define HIP_TRY(expr)                                                                              \
+  do {                                                                                             \
+    hipError_t e_ = (expr);                                                                        \
+    if (e_ != hipSuccess) return fail(MRL_E_HIP, "%s: %s", #expr, hipGetErrorString(e_));          \
+  } while (0)
+
+struct mrl_target {
+  mrl_target_desc d;
+};
+
+namespace {
+
+constexpr size_t kAlign = 256;
+constexpr uint32_t kQueryChunk = 4096;
+size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+// Host-side compiled lattice: everything derived from (target, lattice).
+struct Compiled {
+  DevParams P;
+  std::vector<uint16_t> tile_jt;
+  std::vector<uint32_t> tile_trips;
+  std::vector<uint32_t> level_shapes;     // shapes grouped by dependency level
+  std::vector<uint32_t> level_off;        // [n_levels + 1]
+  std::vector<uint32_t> sizes[4];
+  Geo geo;
+  uint32_t merge_order[16];
+  uint32_t n_shapes;
+  uint64_t n_specs;
+  int block;
+  size_t lds_bytes;
+  int lay_axis[5], dt_axis[5];            // coordinate axis of the operand's bit, -1 if none
+  mrl_target_desc target;
+  mrl_lattice_desc lat;                   // sizes pointers re-pointed to this->sizes
+};
+
+// Offsets of the fixed part of the scratch buffer.
+struct FixedLayout {
+  size_t counters, params, tile_jt, tile_trips, level_shapes, maskD, maskC, prefD, prefC, tile_tmp, totals,
+      q_idx, q_cost, q_arg, end;
+  uint32_t n_words;
+};
+
+FixedLayout fixed_layout(const Compiled& c) {
+  FixedLayout f;
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
+  f.n_words = (uint32_t)((c.n_specs + 63) / 64);
+  f.counters = take(sizeof(Counters));
+  f.params = take(sizeof(DevParams));
+  f.tile_jt = take(c.tile_jt.size() * 2 + 2);
+  f.tile_trips = take(c.tile_trips.size() * 4 + 4);
+  f.level_shapes = take(c.level_shapes.size() * 4);
+  f.maskD = take((size_t)f.n_words * 8);
+  f.maskC = take((size_t)f.n_words * 8);
+  f.prefD = take((size_t)f.n_words * 4);
+  f.prefC = take((size_t)f.n_words * 4);
+  f.tile_tmp = take((c.n_specs / kScanTileItems + 2) * 4);
+  f.totals = take(64);
+  f.q_idx = take(kQueryChunk * 8);
+  f.q_cost = take(kQueryChunk * 8);
+  f.q_arg = take(kQueryChunk * 2);
+  f.end = o;
+  return f;
+}
+
+// per box while merging: bcell, blen, alive, pred, next, pos; per final box: fcell, flen, fv0, fv1
+size_t work_bytes(uint64_t nb) { return align_up(nb * 4) + align_up(nb * 16) + 2 * align_up(nb) + 2 * align_up(nb * 4); }
+size_t final_bytes(uint64_t nb) { return align_up(nb * 4) + align_up(nb * 16) + 2 * align_up(nb * 8); }
+
+uint32_t ipow(uint32_t b, uint32_t e) { uint32_t r = 1; while (e--) r *= b; return r; }
+
+int32_t validate_target(const mrl_target_desc* d) {
+  if (!d) return fail(MRL_E_INVAL, "target descriptor is NULL");
+  if (d->n_levels < 1 || d->n_levels > MRL_MAX_LEVELS) return fail(MRL_E_INVAL, "n_levels must be 1..4");
+  if (d->n_microkernels > MRL_MAX_MK) return fail(MRL_E_INVAL, "too many microkernels");
+  for (uint32_t j = 0; j < d->n_microkernels; j++) {
+    if (d->mk[j].kind > MRL_MK_VEC_ADDRELU) return fail(MRL_E_INVAL, "unknown microkernel kind %u", d->mk[j].kind);
+    if (d->mk[j].lanes < 1) return fail(MRL_E_INVAL, "microkernel lanes must be >= 1");
+    if (d->mk[j].kind != MRL_MK_SCALAR_FMA && d->mk[j].kind != MRL_MK_SCALAR_ADDRELU && d->n_levels < 2)
+      return fail(MRL_E_INVAL, "vector microkernels need a level 1");
+  }
+  return MRL_OK;
+}
+
+int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c) {
+  if (!L) return fail(MRL_E_INVAL, "lattice descriptor is NULL");
+  if (L->kind > MRL_KIND_FUSED_MM_ADD_RELU) return fail(MRL_E_INVAL, "unknown spec kind %u", L->kind);
+  c.target = T;
+  c.lat = *L;
+  DevParams& P = c.P;
+  memset(&P, 0, sizeof P);
+  P.kind = L->kind;
+  P.nops = L->kind == kKindF ? 4 : 3;
+  P.nlv = L->kind == kKindF ? 5 : 3;
+  P.NL = T.n_levels;
+  P.npass = L->kind == kKindF ? P.NL : 1;
+  P.ncombo = ipow(P.NL, P.nops);
+  uint64_t max_vol = 1;
+  uint32_t maxs = 0;
+  for (int d = 0; d < 4; d++) {
+    uint32_t n = L->n_sizes[d];
+    if (n < 1 || n > MRL_MAX_SIZES || !L->sizes[d]) return fail(MRL_E_INVAL, "n_sizes[%d] must be 1..%d", d, MRL_MAX_SIZES);
+    c.sizes[d].assign(L->sizes[d], L->sizes[d] + n);
+    if (c.sizes[d][0] != 1) return fail(MRL_E_INVAL, "sizes[%d] must start with 1", d);
+    for (uint32_t j = 1; j < n; j++)
+      if (c.sizes[d][j] <= c.sizes[d][j - 1]) return fail(MRL_E_INVAL, "sizes[%d] must be strictly ascending", d);
+    c.lat.sizes[d] = c.sizes[d].data();
+    P.nsz[d] = n;
+    for (uint32_t j = 0; j < n; j++) P.sizes[d][j] = c.sizes[d][j];
+    max_vol *= c.sizes[d][n - 1];
+    if (max_vol >= (1ull << 48)) return fail(MRL_E_INVAL, "b*m*k*n must stay below 2^48");
+    maxs = std::max(maxs, n);
+  }
+  if (L->kind != kKindM && L->n_sizes[0] != 1) return fail(MRL_E_INVAL, "this kind has no batch dimension");
+  if (L->kind == kKindE && L->n_sizes[2] != 1) return fail(MRL_E_INVAL, "BIAS_ADD_RELU has no k dimension");
+  P.shape_stride[3] = 1;
+  for (int d = 2; d >= 0; d--) P.shape_stride[d] = P.shape_stride[d + 1] * P.nsz[d + 1];
+  c.n_shapes = P.shape_stride[0] * P.nsz[0];
+
+  // variant bits: layout bits (operand order) above dtype bits (operand order)
+  for (int i = 0; i < 5; i++) { P.lay_bit[i] = P.dt_bit[i] = 0xFF; c.lay_axis[i] = c.dt_axis[i] = -1; }
+  for (uint32_t i = 0; i < P.nops; i++) {
+    P.nlay += L->layout_coord[i] ? 1 : 0;
+    P.ndt += L->dtype_coord[i] ? 1 : 0;
+    if (L->dtype_coord[i] && !(L->kind == kKindM && i < 2)) return fail(MRL_E_INVAL, "dtype bit only on MatmulAccum inputs");
+    if (L->base_dtype_bytes[i] != 4 && !(L->base_dtype_bytes[i] == 2 && L->kind == kKindM))
+      return fail(MRL_E_INVAL, "base_dtype_bytes[%u] must be 4 (or 2 on a MatmulAccum)", i);
+    P.base_bf16[i] = L->base_dtype_bytes[i] == 2;
+    P.access[i] = L->kind == kKindM ? (i == 2 ? kRmw : kRead) : (i == P.nops - 1 ? kWrite : kRead);
+    P.lvpow[i] = ipow(P.NL, P.nops - 1 - i);
+  }
+  P.V = 1u << (P.nlay + P.ndt);
+  if (P.V > 32) return fail(MRL_E_INVAL, "too many layout/dtype bits");
+  {
+    uint32_t axis = 4 + P.nlv, seen_l = 0, seen_d = 0;
+    for (uint32_t i = 0; i < P.nops; i++)
+      if (L->layout_coord[i]) { c.lay_axis[i] = (int)axis++; P.lay_bit[i] = (uint8_t)(P.ndt + P.nlay - 1 - seen_l++); }
+    for (uint32_t i = 0; i < P.nops; i++)
+      if (L->dtype_coord[i]) { c.dt_axis[i] = (int)axis++; P.dt_bit[i] = (uint8_t)(P.ndt - 1 - seen_d++); }
+  }
+  P.G = P.ncombo * P.npass * P.V;
+  c.n_specs = (uint64_t)c.n_shapes * P.G;
+  if (c.n_specs >= (1ull << 32)) return fail(MRL_E_INVAL, "lattice has %llu specs; the limit is 2^32-1", (unsigned long long)c.n_specs);
+
+  // target
+  for (int l = 0; l < 4; l++) {
+    P.cap[l] = T.capacity_bytes[l];
+    P.zero[l] = T.zero_coef[l];
+    for (int k = 0; k < 4; k++)
+      for (int x = 0; x < 2; x++) { P.load[l][k][x] = T.load_coef[l][k][x]; P.store[l][k][x] = T.store_coef[l][k][x]; }
+  }
+  P.convert = T.convert_coef;
+  P.s = T.loop_overhead;
+  P.nmk = T.n_microkernels;
+  for (uint32_t j = 0; j < P.nmk; j++) { P.mk_kind[j] = T.mk[j].kind; P.mk_lanes[j] = T.mk[j].lanes; P.mk_cost[j] = T.mk[j].cost; }
+
+  // rewrite ids
+  P.maxs = maxs;
+  P.move_base = P.nmk;
+  P.tile_base = P.move_base + P.nops * (P.NL - 1) * 4;
+  P.buf_id = P.tile_base + 4 * maxs;
+  if (P.buf_id >= kNone) return fail(MRL_E_INVAL, "rewrite ids do not fit 16 bits");
+
+  // tiles: for (dim, size index) the smaller allowed sizes dividing it
+  for (int d = 0; d < 4; d++) {
+    P.tile_dim_ok[d] = L->kind == kKindM || d == 1 || d == 3;
+    for (uint32_t j = 0; j < P.nsz[d]; j++) {
+      P.tile_off[d][j] = (uint32_t)c.tile_jt.size();
+      if (P.tile_dim_ok[d])
+        for (uint32_t jt = 0; jt < j; jt++)
+          if (c.sizes[d][j] % c.sizes[d][jt] == 0) {
+            c.tile_jt.push_back((uint16_t)jt);
+            c.tile_trips.push_back(c.sizes[d][j] / c.sizes[d][jt]);
+          }
+    }
+    for (uint32_t j = P.nsz[d]; j <= (uint32_t)kMaxSizes; j++) P.tile_off[d][j] = (uint32_t)c.tile_jt.size();
+  }
+
+  // operand-level combos by rank
+  P.nranks = P.nops * (P.NL - 1) + 1;
+  {
+    std::vector<std::pair<uint32_t, uint32_t>> order;
+    for (uint32_t combo = 0; combo < P.ncombo; combo++) {
+      uint32_t r = 0, x = combo;
+      for (uint32_t i = 0; i < P.nops; i++) { r += x % P.NL; x /= P.NL; }
+      order.push_back({r, combo});
+    }
+    std::sort(order.begin(), order.end());
+    uint32_t q = 0;
+    for (uint32_t r = 0; r <= P.nranks; r++) {
+      while (q < order.size() && order[q].first < r) q++;
+      P.rank_off[r] = (uint16_t)q;
+    }
+    for (uint32_t i = 0; i < order.size(); i++) P.combo_by_rank[i] = (uint16_t)order[i].second;
+  }
+
+  // dependency level of a shape = sum over tiled dims of the longest divisor chain below its size
+  std::vector<uint32_t> chain[4];
+  uint32_t n_lev = 1;
+  for (int d = 0; d < 4; d++) {
+    chain[d].assign(P.nsz[d], 0);
+    uint32_t mx = 0;
+    if (P.tile_dim_ok[d])
+      for (uint32_t j = 0; j < P.nsz[d]; j++) {
+        for (uint32_t q = P.tile_off[d][j]; q < P.tile_off[d][j + 1]; q++)
+          chain[d][j] = std::max(chain[d][j], chain[d][c.tile_jt[q]] + 1);
+        mx = std::max(mx, chain[d][j]);
+      }
+    n_lev += mx;
+  }
+  std::vector<uint32_t> lev(c.n_shapes);
+  c.level_off.assign(n_lev + 1, 0);
+  for (uint32_t sh = 0; sh < c.n_shapes; sh++) {
+    uint32_t r = sh, l = 0;
+    for (int d = 0; d < 4; d++) { l += chain[d][r / P.shape_stride[d]]; r %= P.shape_stride[d]; }
+    lev[sh] = l;
+    c.level_off[l + 1]++;
+  }
+  for (uint32_t l = 0; l < n_lev; l++) c.level_off[l + 1] += c.level_off[l];
+  c.level_shapes.resize(c.n_shapes);
+  {
+    std::vector<uint32_t> cur(c.level_off.begin(), c.level_off.end() - 1);
+    for (uint32_t sh = 0; sh < c.n_shapes; sh++) c.level_shapes[cur[lev[sh]]++] = sh;
+  }
+
+  // coordinate geometry and merge order: size axes innermost first, then level
+  // axes, layout bits, dtype bits, each from the last to the first
+  Geo& g = c.geo;
+  memset(&g, 0, sizeof g);
+  uint32_t nd = 0;
+  for (int d = 0; d < 4; d++) g.ext[nd++] = P.nsz[d];
+  for (uint32_t i = 0; i < P.nlv; i++) g.ext[nd++] = P.NL;
+  for (uint32_t i = 0; i < P.nlay + P.ndt; i++) g.ext[nd++] = 2;
+  g.ndim = nd;
+  uint64_t s = 1;
+  for (int a = (int)nd - 1; a >= 0; a--) { g.stride[a] = (uint32_t)s; s *= g.ext[a]; }
+  g.n = (uint32_t)c.n_specs;
+  {
+    uint32_t q = 0;
+    for (int a = 3; a >= 0; a--) c.merge_order[q++] = (uint32_t)a;
+    for (int a = 4 + (int)P.nlv - 1; a >= 4; a--) c.merge_order[q++] = (uint32_t)a;
+    for (int a = 4 + (int)(P.nlv + P.nlay) - 1; a >= 4 + (int)P.nlv; a--) c.merge_order[q++] = (uint32_t)a;
+    for (int a = (int)nd - 1; a >= 4 + (int)(P.nlv + P.nlay); a--) c.merge_order[q++] = (uint32_t)a;
+  }
+
+  c.block = P.ncombo <= 64 ? 64 : 256;
+  const size_t max_task = (size_t)P.ncombo * P.V;
+  c.lds_bytes = max_task * 12 + (size_t)P.ncombo * 8 + (kMaxRanks + 2 + 4) * 4;
+  return MRL_OK;
+}
+
+}  // namespace
+
+struct mrl_table {
+  Compiled c;
+  FixedLayout f;
+  char* scratch;
+  uint64_t* d_cost;
+  uint16_t* d_arg;
+  hipStream_t stream;
+  // final lists inside scratch: [0] decisions, [1] costs
+  size_t list_off[2];
+  uint64_t list_n[2];
+};
+
+extern "C" {
+
+const char* mrl_last_error(void) { return g_err; }
+
+int32_t mrl_target_create(const mrl_target_desc* desc, mrl_target** out) {
+  if (!out) return fail(MRL_E_INVAL, "out is NULL");
+  *out = nullptr;
+  int32_t rc = validate_target(desc);
+  if (rc) return rc;
+  mrl_target* t = new (std::nothrow) mrl_target;
+  if (!t) return fail(MRL_E_NOMEM, "host allocation failed");
+  t->d = *desc;
+  *out = t;
+  return MRL_OK;
+}
+
+void mrl_target_destroy(mrl_target* t) { delete t; }
+
+int32_t mrl_geometry(const mrl_target* t, const mrl_lattice_desc* lat, uint32_t* n_dims, uint32_t* extents,
+                     uint64_t* n_specs) {
+  if (!t) return fail(MRL_E_INVAL, "target is NULL");
+  Compiled c;
+  int32_t rc = compile(t->d, lat, c);
+  if (rc) return rc;
+  if (n_dims) *n_dims = c.geo.ndim;
+  if (extents) for (uint32_t a = 0; a < c.geo.ndim; a++) extents[a] = c.geo.ext[a];
+  if (n_specs) *n_specs = c.n_specs;
+  return MRL_OK;
+}
+
+int32_t mrl_table_bytes(const mrl_target* t, const mrl_lattice_desc* lat, size_t* cost_bytes, size_t* argmin_bytes,
+                        size_t* scratch_bytes) {
+  if (!t) return fail(MRL_E_INVAL, "target is NULL");
+  Compiled c;
+  int32_t rc = compile(t->d, lat, c);
+  if (rc) return rc;
+  if (cost_bytes) *cost_bytes = c.n_specs * 8;
+  if (argmin_bytes) *argmin_bytes = c.n_specs * 2;
+  if (scratch_bytes) *scratch_bytes = fixed_layout(c).end + 2 * final_bytes(c.n_specs) + work_bytes(c.n_specs);
+  return MRL_OK;
+}
+
+int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_table* const* deps, uint32_t n_deps,
+                  void* d_cost, void* d_argmin, void* d_scratch, size_t scratch_bytes, void* hip_stream,
+                  mrl_table** out, mrl_stats* stats) {
+  if (!out) return fail(MRL_E_INVAL, "out is NULL");
+  *out = nullptr;
+  if (!t) return fail(MRL_E_INVAL, "target is NULL");
+  if (!d_cost || !d_argmin || !d_scratch) return fail(MRL_E_INVAL, "device buffers must not be NULL");
+  if (((uintptr_t)d_cost | (uintptr_t)d_argmin | (uintptr_t)d_scratch) % kAlign) return fail(MRL_E_INVAL, "device buffers must be 256-byte aligned");
+  mrl_table* tab = new (std::nothrow) mrl_table;
+  if (!tab) return fail(MRL_E_NOMEM, "host allocation failed");
+  struct Guard { mrl_table* p; ~Guard() { delete p; } } guard{tab};
+  Compiled& c = tab->c;
+  int32_t rc = compile(t->d, lat, c);
+  if (rc) return rc;
+  DevParams& P = c.P;
+
+  if (P.kind == kKindF) {
+    if (n_deps != 2 || !deps || !deps[0] || !deps[1]) return fail(MRL_E_INVAL, "a FUSED lattice needs deps = {MATMUL_ACCUM table, BIAS_ADD_RELU table}");
+    const Compiled& M = deps[0]->c;
+    const Compiled& E = deps[1]->c;
+    if (M.P.kind != kKindM || E.P.kind != kKindE) return fail(MRL_E_INVAL, "deps must be {MATMUL_ACCUM, BIAS_ADD_RELU}");
+    if (memcmp(&M.target, &t->d, sizeof t->d) || memcmp(&E.target, &t->d, sizeof t->d)) return fail(MRL_E_INVAL, "deps were solved for another target");
+    for (int d = 1; d < 4; d++) if (M.sizes[d] != c.sizes[d]) return fail(MRL_E_INVAL, "MATMUL_ACCUM dep has other size lists");
+    if (M.sizes[0].size() != 1) return fail(MRL_E_INVAL, "MATMUL_ACCUM dep must have b pinned to 1");
+    if (E.sizes[1] != c.sizes[1] || E.sizes[3] != c.sizes[3]) return fail(MRL_E_INVAL, "BIAS_ADD_RELU dep has other size lists");
+    if (M.P.ndt || M.P.base_bf16[0] || M.P.base_bf16[1] || M.P.base_bf16[2]) return fail(MRL_E_INVAL, "MATMUL_ACCUM dep must be f32");
+    P.costM = deps[0]->d_cost; P.costE = deps[1]->d_cost;
+    P.GM = M.P.G; P.VM = M.P.V; P.GE = E.P.G; P.VE = E.P.V; P.nszE_n = E.P.nsz[3];
+    for (int i = 0; i < 3; i++) { P.layM[i] = M.P.lay_bit[i]; P.layE[i] = E.P.lay_bit[i]; }
+  } else if (n_deps != 0) {
+    return fail(MRL_E_INVAL, "only a FUSED lattice takes deps");
+  }
+
+  const FixedLayout f = fixed_layout(c);
+  tab->f = f;
+  if (scratch_bytes < f.end) return fail(MRL_E_NOMEM, "scratch buffer too small: %zu bytes given, at least %zu needed", scratch_bytes, f.end);
+  char* base = (char*)d_scratch;
+  hipStream_t st = (hipStream_t)hip_stream;
+  tab->scratch = base; tab->d_cost = (uint64_t*)d_cost; tab->d_arg = (uint16_t*)d_argmin; tab->stream = st;
+
+  Counters* d_ctr = (Counters*)(base + f.counters);
+  DevParams* d_P = (DevParams*)(base + f.params);
+  P.tile_jt = (const uint16_t*)(base + f.tile_jt);
+  P.tile_trips = (const uint32_t*)(base + f.tile_trips);
+  uint32_t* d_level_shapes = (uint32_t*)(base + f.level_shapes);
+  HIP_TRY(hipMemsetAsync(d_ctr, 0, sizeof(Counters), st));
+  HIP_TRY(hipMemcpyAsync(d_P, &P, sizeof P, hipMemcpyHostToDevice, st));
+  if (!c.tile_jt.empty()) {
+    HIP_TRY(hipMemcpyAsync((void*)P.tile_jt, c.tile_jt.data(), c.tile_jt.size() * 2, hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync((void*)P.tile_trips, c.tile_trips.data(), c.tile_trips.size() * 4, hipMemcpyHostToDevice, st));
+  }
+  HIP_TRY(hipMemcpyAsync(d_level_shapes, c.level_shapes.data(), c.level_shapes.size() * 4, hipMemcpyHostToDevice, st));
+
+  hipEvent_t ev[3];
+  for (auto& e : ev) HIP_TRY(hipEventCreate(&e));
+  struct EvGuard { hipEvent_t* e; ~EvGuard() { for (int i = 0; i < 3; i++) (void)hipEventDestroy(e[i]); } } evg{ev};
+
+  // ---- fill: one launch per dependency level ----
+  HIP_TRY(hipEventRecord(ev[0], st));
+  const uint32_t n_lev = (uint32_t)c.level_off.size() - 1;
+  for (uint32_t l = 0; l < n_lev; l++) {
+    const uint32_t n_units = (c.level_off[l + 1] - c.level_off[l]) * P.npass;
+    launch_fill_level(c.block, d_P, d_level_shapes + c.level_off[l], n_units, tab->d_cost, tab->d_arg, d_ctr, c.lds_bytes, st);
+  }
+  HIP_TRY(hipGetLastError());
+  HIP_TRY(hipEventRecord(ev[1], st));
+
+  // ---- compression ----
+  const Geo& g = c.geo;
+  uint32_t a0 = c.merge_order[0];
+  for (uint32_t q = 0; q < g.ndim; q++) if (g.ext[c.merge_order[q]] > 1) { a0 = c.merge_order[q]; break; }
+  unsigned long long* maskL[2] = {(unsigned long long*)(base + f.maskD), (unsigned long long*)(base + f.maskC)};
+  uint32_t* prefL[2] = {(uint32_t*)(base + f.prefD), (uint32_t*)(base + f.prefC)};
+  uint32_t* tile_tmp = (uint32_t*)(base + f.tile_tmp);
+  uint32_t* d_tot = (uint32_t*)(base + f.totals);
+  auto axis_sizes = [&](uint32_t a) -> const uint32_t* { return a < 4 ? (const uint32_t*)((char*)d_P + offsetof(DevParams, sizes) + a * sizeof(uint32_t) * kMaxSizes) : nullptr; };
+  if (g.stride[a0] % 64 != 0) { launch_zero_words(maskL[0], f.n_words, st); launch_zero_words(maskL[1], f.n_words, st); }
+  launch_head_flags(g, a0, tab->d_cost, tab->d_arg, axis_sizes(a0), maskL[0], maskL[1], st);
+  scan_mask_words(maskL[0], f.n_words, tile_tmp, prefL[0], d_tot + 0, st);
+  scan_mask_words(maskL[1], f.n_words, tile_tmp, prefL[1], d_tot + 1, st);
+  uint32_t h_tot[4] = {0, 0, 0, 0};
+  HIP_TRY(hipMemcpyAsync(h_tot, d_tot, 8, hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipStreamSynchronize(st));
+
+  size_t front = f.end;
+  size_t needed = f.end;
+  for (int which = 0; which < 2; which++) {
+    const uint64_t nb = h_tot[which];
+    const size_t wb = work_bytes(nb);
+    needed = std::max(needed, front + final_bytes(nb) + wb);   // upper bound before the final count is known
+    if (scratch_bytes < front + wb) return fail(MRL_E_NOMEM, "scratch buffer too small: %zu bytes given, %zu needed", scratch_bytes, front + wb + final_bytes(nb));
+    char* w = base + (scratch_bytes - wb) / kAlign * kAlign;
+    if ((size_t)(w - base) < front) return fail(MRL_E_NOMEM, "scratch buffer too small: %zu bytes given, %zu needed", scratch_bytes, front + wb + final_bytes(nb));
+    uint32_t* bcell = (uint32_t*)w; w += align_up(nb * 4);
+    char* blen = w; w += align_up(nb * 16);
+    uint8_t* alive = (uint8_t*)w; w += align_up(nb);
+    uint8_t* pred = (uint8_t*)w; w += align_up(nb);
+    uint32_t* next = (uint32_t*)w; w += align_up(nb * 4);
+    uint32_t* pos = (uint32_t*)w;
+    launch_make_boxes(g, a0, maskL[which], prefL[which], f.n_words, bcell, blen, alive, pred, st);
+    uint8_t stamp = 0;
+    for (uint32_t q = 0; q < g.ndim; q++) {
+      const uint32_t a = c.merge_order[q];
+      if (a == a0 || g.ext[a] <= 1) continue;
+      launch_axis_pass(g, a, ++stamp, which == 1, (uint32_t)nb, bcell, blen, alive, pred, next, maskL[which], prefL[which],
+                       tab->d_cost, tab->d_arg, axis_sizes(a), st);
+    }
+    scan_flags(alive, (uint32_t)nb, tile_tmp, pos, d_tot + 2, st);
+    HIP_TRY(hipMemcpyAsync(h_tot + 2, d_tot + 2, 4, hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    const uint64_t nf = h_tot[2];
+    const size_t fb = final_bytes(nf);
+    if (front + fb > (size_t)((char*)bcell - base)) return fail(MRL_E_NOMEM, "scratch buffer too small: %zu bytes given, %zu needed", scratch_bytes, front + fb + wb);
+    char* r = base + front;
+    uint32_t* fcell = (uint32_t*)r; r += align_up(nf * 4);
+    char* flen = r; r += align_up(nf * 16);
+    uint64_t* fv0 = (uint64_t*)r; r += align_up(nf * 8);
+    uint64_t* fv1 = (uint64_t*)r;
+    launch_emit(g, d_P, which == 1, (uint32_t)nb, bcell, blen, alive, pos, tab->d_cost, tab->d_arg, fcell, flen, fv0, fv1, st);
+    tab->list_off[which] = front;
+    tab->list_n[which] = nf;
+    needed = std::max(needed, front + fb + wb);
+    front += fb;
+  }
+  HIP_TRY(hipGetLastError());
+  HIP_TRY(hipEventRecord(ev[2], st));
+  Counters h_ctr;
+  HIP_TRY(hipMemcpyAsync(&h_ctr, d_ctr, sizeof h_ctr, hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  if (h_ctr.overflow) return fail(MRL_E_OVERFLOW, "a finite cost reached 2^62");
+  if (stats) {
+    memset(stats, 0, sizeof *stats);
+    stats->n_specs = c.n_specs;
+    stats->n_admissible = h_ctr.n_admissible;
+    stats->n_rewrites = h_ctr.n_rewrites;
+    stats->n_levels_run = n_lev;
+    HIP_TRY(hipEventElapsedTime(&stats->fill_ms, ev[0], ev[1]));
+    HIP_TRY(hipEventElapsedTime(&stats->compress_ms, ev[1], ev[2]));
+    stats->n_decision_boxes = tab->list_n[0];
+    stats->n_cost_boxes = tab->list_n[1];
+    stats->scratch_used = needed;
+  }
+  guard.p = nullptr;
+  *out = tab;
+  return MRL_OK;
+}
+
+void mrl_table_destroy(mrl_table* tab) { delete tab; }
+
+int32_t mrl_query(const mrl_table* tab, const mrl_coord* specs, size_t n, uint64_t* cost_out, uint16_t* rewrite_out) {
+  if (!tab || (n && (!specs || !cost_out || !rewrite_out))) return fail(MRL_E_INVAL, "NULL argument");
+  const Geo& g = tab->c.geo;
+  std::vector<uint64_t> idx(std::min<size_t>(n, kQueryChunk));
+  char* base = tab->scratch;
+  for (size_t done = 0; done < n; done += kQueryChunk) {
+    const uint32_t m = (uint32_t)std::min<size_t>(kQueryChunk, n - done);
+    for (uint32_t i = 0; i < m; i++) {
+      uint64_t x = 0;
+      for (uint32_t a = 0; a < g.ndim; a++) {
+        const uint32_t v = specs[done + i].x[a];
+        if (v >= g.ext[a]) return fail(MRL_E_RANGE, "spec %zu: coordinate %u = %u outside [0, %u)", done + i, a, v, g.ext[a]);
+        x += (uint64_t)v * g.stride[a];
+      }
+      idx[i] = x;
+    }
+    uint64_t* d_idx = (uint64_t*)(base + tab->f.q_idx);
+    uint64_t* d_c = (uint64_t*)(base + tab->f.q_cost);
+    uint16_t* d_a = (uint16_t*)(base + tab->f.q_arg);
+    HIP_TRY(hipMemcpyAsync(d_idx, idx.data(), (size_t)m * 8, hipMemcpyHostToDevice, tab->stream));
+    launch_gather(d_idx, m, tab->d_cost, tab->d_arg, d_c, d_a, tab->stream);
+    HIP_TRY(hipMemcpyAsync(cost_out + done, d_c, (size_t)m * 8, hipMemcpyDeviceToHost, tab->stream));
+    HIP_TRY(hipMemcpyAsync(rewrite_out + done, d_a, (size_t)m * 2, hipMemcpyDeviceToHost, tab->stream));
+    HIP_TRY(hipStreamSynchronize(tab->stream));
+  }
+  return MRL_OK;
+}
+
+int32_t mrl_rewrite_decode(const mrl_table* tab, uint16_t id, mrl_rewrite* out) {
+  if (!tab || !out) return fail(MRL_E_INVAL, "NULL argument");
+  const DevParams& P = tab->c.P;
+  memset(out, 0, sizeof *out);
+  if (id < P.move_base) { out->cls = 0; out->mk_index = id; return MRL_OK; }
+  if (id < P.tile_base) {
+    uint32_t r = id - P.move_base;
+    out->cls = 1; out->convert = r & 1; out->transposed = (r >> 1) & 1; r >>= 2;
+    out->dst_level = (uint8_t)(r % (P.NL - 1)); out->operand_or_dim = (uint8_t)(r / (P.NL - 1));
+    return MRL_OK;
+  }
+  if (id < P.buf_id) {
+    const uint32_t r = id - P.tile_base, d = r / P.maxs, j = r % P.maxs;
+    if (j >= P.nsz[d]) return fail(MRL_E_RANGE, "rewrite id %u names no tile size", id);
+    out->cls = 2; out->operand_or_dim = (uint8_t)d; out->tile_size = tab->c.sizes[d][j];
+    return MRL_OK;
+  }
+  if (id == P.buf_id && P.kind == kKindF) { out->cls = 3; return MRL_OK; }
+  return fail(MRL_E_RANGE, "rewrite id %u is not used by this table", id);
+}
+
+int32_t mrl_coord_of_spec(const mrl_table* tab, const uint32_t shape[4], const uint8_t* levels, const uint8_t* layouts,
+                          const uint8_t* dtypes, mrl_coord* out) {
+  if (!tab || !shape || !levels || !out) return fail(MRL_E_INVAL, "NULL argument");
+  const Compiled& c = tab->c;
+  memset(out, 0, sizeof *out);
+  for (int d = 0; d < 4; d++) {
+    auto it = std::lower_bound(c.sizes[d].begin(), c.sizes[d].end(), shape[d]);
+    if (it == c.sizes[d].end() || *it != shape[d]) return fail(MRL_E_RANGE, "size %u is not allowed on dimension %d", shape[d], d);
+    out->x[d] = (uint32_t)(it - c.sizes[d].begin());
+  }
+  for (uint32_t i = 0; i < c.P.nlv; i++) {
+    if (levels[i] >= c.P.NL) return fail(MRL_E_RANGE, "level %u of operand %u outside the target", levels[i], i);
+    out->x[4 + i] = levels[i];
+  }
+  for (uint32_t i = 0; i < c.P.nops; i++) {
+    if (c.lay_axis[i] >= 0) { if (!layouts || layouts[i] > 1) return fail(MRL_E_RANGE, "layout of operand %u", i); out->x[c.lay_axis[i]] = layouts[i]; }
+    if (c.dt_axis[i] >= 0) { if (!dtypes || dtypes[i] > 1) return fail(MRL_E_RANGE, "dtype of operand %u", i); out->x[c.dt_axis[i]] = dtypes[i]; }
+  }
+  return MRL_OK;
+}
+
+int32_t mrl_emit_compressed(const mrl_table* tab, uint32_t which, mrl_box* out, size_t cap, size_t* n_out) {
+  if (!tab || which > 1) return fail(MRL_E_INVAL, "bad argument");
+  const uint64_t n = tab->list_n[which];
+  if (n_out) *n_out = n;
+  if (!out) return MRL_OK;
+  if (cap < n) return fail(MRL_E_BUFSZ, "box buffer holds %zu, %llu needed", cap, (unsigned long long)n);
+  const Geo& g = tab->c.geo;
+  const char* r = tab->scratch + tab->list_off[which];
+  std::vector<uint32_t> fcell(n);
+  std::vector<uint8_t> flen(n * 16);
+  std::vector<uint64_t> fv0(n), fv1(n);
+  if (n) {
+    HIP_TRY(hipMemcpy(fcell.data(), r, n * 4, hipMemcpyDeviceToHost)); r += align_up(n * 4);
+    HIP_TRY(hipMemcpy(flen.data(), r, n * 16, hipMemcpyDeviceToHost)); r += align_up(n * 16);
+    HIP_TRY(hipMemcpy(fv0.data(), r, n * 8, hipMemcpyDeviceToHost)); r += align_up(n * 8);
+    HIP_TRY(hipMemcpy(fv1.data(), r, n * 8, hipMemcpyDeviceToHost));
+  }
+  for (uint64_t i = 0; i < n; i++) {
+    mrl_box& b = out[i];
+    memset(&b, 0, sizeof b);
+    uint32_t x = fcell[i];
+    for (uint32_t a = 0; a < g.ndim; a++) {
+      const uint32_t lo = x / g.stride[a];
+      x -= lo * g.stride[a];
+      b.lo[a] = (uint16_t)lo;
+      b.hi[a] = (uint16_t)(lo + flen[i * 16 + a] - 1);
+    }
+    b.v0 = fv0[i]; b.v1 = fv1[i];
+  }
+  return MRL_OK;
+}
+
+int32_t mrl_copy_dense(const mrl_table* tab, uint64_t* cost_host, uint16_t* argmin_host) {
+  if (!tab) return fail(MRL_E_INVAL, "table is NULL");
+  if (cost_host) HIP_TRY(hipMemcpy(cost_host, tab->d_cost, tab->c.n_specs * 8, hipMemcpyDeviceToHost));
+  if (argmin_host) HIP_TRY(hipMemcpy(argmin_host, tab->d_arg, tab->c.n_specs * 2, hipMemcpyDeviceToHost));
+  return MRL_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,39 @@
+// Internal: host-side launchers of the kernels in fill.hip and compress.hip.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+#include "dev_params.h"
+
+namespace mrl {
+
+// Table geometry passed by value to the compression kernels (cells < 2^32).
+struct Geo {
+  uint32_t ndim, n;
+  uint32_t ext[16], stride[16];
+};
+
+void launch_fill_level(int block, const DevParams* P, const uint32_t* level_shapes, uint32_t n_units,
+                       uint64_t* cost, uint16_t* arg, Counters* ctr, size_t lds_bytes, hipStream_t stream);
+
+void launch_zero_words(unsigned long long* p, uint32_t n, hipStream_t st);
+void launch_head_flags(const Geo& g, uint32_t a0, const uint64_t* cost, const uint16_t* arg, const uint32_t* axis_sizes,
+                       unsigned long long* maskD, unsigned long long* maskC, hipStream_t st);
+void scan_mask_words(const unsigned long long* mask, uint32_t n_words, uint32_t* tile_tmp, uint32_t* prefix,
+                     uint32_t* total, hipStream_t st);
+void scan_flags(const uint8_t* flags, uint32_t n, uint32_t* tile_tmp, uint32_t* pos, uint32_t* total, hipStream_t st);
+void launch_make_boxes(const Geo& g, uint32_t a0, const unsigned long long* mask, const uint32_t* prefix, uint32_t n_words,
+                       uint32_t* bcell, void* blen, uint8_t* alive, uint8_t* pred, hipStream_t st);
+void launch_axis_pass(const Geo& g, uint32_t a, uint8_t stamp, bool is_cost, uint32_t n_boxes, const uint32_t* bcell,
+                      void* blen, uint8_t* alive, uint8_t* pred, uint32_t* next, const unsigned long long* mask,
+                      const uint32_t* prefix, const uint64_t* cost, const uint16_t* arg, const uint32_t* axis_sizes,
+                      hipStream_t st);
+void launch_emit(const Geo& g, const DevParams* P, bool is_cost, uint32_t n_boxes, const uint32_t* bcell, const void* blen,
+                 const uint8_t* alive, const uint32_t* pos, const uint64_t* cost, const uint16_t* arg, uint32_t* fcell,
+                 void* flen, uint64_t* fv0, uint64_t* fv1, hipStream_t st);
+void launch_gather(const uint64_t* idx, uint32_t n, const uint64_t* cost, const uint16_t* arg, uint64_t* cost_out,
+                   uint16_t* arg_out, hipStream_t st);
+
+constexpr uint32_t kScanTileItems = 2048;   // items per scan tile (tile_tmp needs n/2048 + 1 words)
+
+}  // namespace mrl

@@ -1,0 +1,367 @@
+// Spatial compression of the dense table into boxes.
+//
+// Paper, Section 4.1 / Figure 2: every entry starts as a unit rectangle; equal
+// adjacent rectangles are merged when their union fills its bounding box.  The
+// decision and the volume-normalised cost are compressed separately.
+//
+// The merge is made canonical by fixing an axis order; along each axis in
+// turn, boxes that agree in value and in their extent on every other axis are
+// chained when one starts where the previous one ends.
+//
+// GPU formulation.
+//   pass 0  (dense, first axis a0): one thread walks a line of cells along a0
+//           and flags the cell where the value changes; consecutive lanes hold
+//           consecutive cells, so the flags of 64 cells are one ballot = one
+//           word of a bit mask in table order.  A prefix sum of the popcounts
+//           gives every run (= box) its index in table order.
+//   pass a  (on boxes): a box looks at the cell just past its end on axis a.
+//           If that cell is the low corner of a live box of the same value and
+//           the same extents on all other axes, the two are linked; heads of
+//           chains then absorb their chain.  The low corner of a box is found
+//           in O(1) through the bit mask and the prefix sums.
+//   final   live boxes are compacted in index order = sorted by low corner.
+#include <hip/hip_runtime.h>
+#include "dev_params.h"
+#include "compress.h"
+
+namespace mrl {
+
+// ---------------------------------------------------------------- value equality
+// Normalised costs c1/vol1 and c2/vol2 where the volumes differ only by the
+// factor s1 : s2 of one size axis.  Exact: 128-bit cross multiplication.
+__device__ __forceinline__ bool norm_equal(uint64_t c1, uint32_t s1, uint64_t c2, uint32_t s2) {
+  if (c1 == kInf || c2 == kInf) return c1 == c2;
+  uint64_t a_lo = c1 * s2, a_hi = __umul64hi(c1, s2);
+  uint64_t b_lo = c2 * s1, b_hi = __umul64hi(c2, s1);
+  return a_lo == b_lo && a_hi == b_hi;
+}
+
+// ---------------------------------------------------------------- pass 0
+// line q: all cells sharing every coordinate but a0.
+template <bool BALLOT>
+__global__ __launch_bounds__(256) void head_flags_kernel(Geo g, uint32_t a0,
+                                                         const uint64_t* __restrict__ cost,
+                                                         const uint16_t* __restrict__ arg,
+                                                         const uint32_t* __restrict__ axis_sizes,
+                                                         unsigned long long* __restrict__ maskD,
+                                                         unsigned long long* __restrict__ maskC) {
+  const uint32_t s0 = g.stride[a0], e0 = g.ext[a0];
+  const uint32_t n_lines = g.n / e0;
+  const uint32_t q = blockIdx.x * 256u + threadIdx.x;
+  const bool active = q < n_lines;
+  uint32_t base = 0;
+  if (active) { uint32_t hi = q / s0; base = hi * s0 * e0 + (q - hi * s0); }
+  uint64_t pc = 0; uint32_t pa = 0, ps = 1;
+  for (uint32_t j = 0; j < e0; j++) {
+    const uint32_t cell = base + j * s0;
+    bool hd = false, hc = false;
+    if (active) {
+      const uint64_t c = cost[cell];
+      const uint32_t a = arg[cell];
+      const uint32_t sz = axis_sizes ? axis_sizes[j] : 1u;
+      hd = j == 0 || a != pa;
+      hc = j == 0 || !norm_equal(c, sz, pc, ps);
+      pc = c; pa = a; ps = sz;
+    }
+    if (BALLOT) {
+      const unsigned long long bd = __ballot(hd), bc = __ballot(hc);
+      if ((threadIdx.x & 63u) == 0 && active) { maskD[cell >> 6] = bd; maskC[cell >> 6] = bc; }
+    } else {
+      if (hd) atomicOr(&maskD[cell >> 6], 1ull << (cell & 63u));
+      if (hc) atomicOr(&maskC[cell >> 6], 1ull << (cell & 63u));
+    }
+  }
+}
+
+// ---------------------------------------------------------------- prefix sums
+struct LoadPopc {
+  const unsigned long long* p;
+  __device__ __forceinline__ uint32_t operator()(uint32_t i) const { return (uint32_t)__popcll(p[i]); }
+};
+struct LoadFlag {
+  const uint8_t* p;
+  __device__ __forceinline__ uint32_t operator()(uint32_t i) const { return p[i]; }
+};
+
+constexpr uint32_t kScanItems = 8, kScanBlock = 256, kScanTile = kScanItems * kScanBlock;
+
+__device__ __forceinline__ uint32_t block_reduce_256(uint32_t v, uint32_t* sh) {
+#pragma unroll
+  for (int d = 32; d > 0; d >>= 1) v += __shfl_down(v, d, 64);
+  if ((threadIdx.x & 63u) == 0) sh[threadIdx.x >> 6] = v;
+  __syncthreads();
+  uint32_t t = sh[0] + sh[1] + sh[2] + sh[3];
+  __syncthreads();
+  return t;
+}
+
+template <class L>
+__global__ __launch_bounds__(256) void scan_tile_sums_kernel(L load, uint32_t n, uint32_t* __restrict__ tile_sum) {
+  __shared__ uint32_t sh[4];
+  const uint32_t first = blockIdx.x * kScanTile + threadIdx.x * kScanItems;
+  uint32_t s = 0;
+#pragma unroll
+  for (uint32_t i = 0; i < kScanItems; i++) if (first + i < n) s += load(first + i);
+  const uint32_t t = block_reduce_256(s, sh);
+  if (threadIdx.x == 0) tile_sum[blockIdx.x] = t;
+}
+
+// One workgroup: exclusive scan of tile_sum in place; the grand total goes to *total.
+__global__ __launch_bounds__(256) void scan_top_kernel(uint32_t* __restrict__ tile_sum, uint32_t n_tiles,
+                                                       uint32_t* __restrict__ total) {
+  __shared__ uint32_t sh[4];
+  __shared__ uint32_t carry_sh;
+  if (threadIdx.x == 0) carry_sh = 0;
+  __syncthreads();
+  for (uint32_t base = 0; base < n_tiles; base += 256) {
+    const uint32_t i = base + threadIdx.x;
+    const uint32_t v = i < n_tiles ? tile_sum[i] : 0;
+    uint32_t incl = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      uint32_t o = __shfl_up(incl, d, 64);
+      if ((int)(threadIdx.x & 63u) >= d) incl += o;
+    }
+    if ((threadIdx.x & 63u) == 63) sh[threadIdx.x >> 6] = incl;
+    __syncthreads();
+    uint32_t wbase = 0;
+    for (uint32_t w = 0; w < (threadIdx.x >> 6); w++) wbase += sh[w];
+    const uint32_t carry = carry_sh;
+    if (i < n_tiles) tile_sum[i] = carry + wbase + incl - v;
+    __syncthreads();
+    if (threadIdx.x == 255) carry_sh = carry + wbase + incl;
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) *total = carry_sh;
+}
+
+template <class L>
+__global__ __launch_bounds__(256) void scan_apply_kernel(L load, uint32_t n, const uint32_t* __restrict__ tile_excl,
+                                                         uint32_t* __restrict__ out) {
+  __shared__ uint32_t sh[4];
+  const uint32_t first = blockIdx.x * kScanTile + threadIdx.x * kScanItems;
+  uint32_t v[kScanItems], s = 0;
+#pragma unroll
+  for (uint32_t i = 0; i < kScanItems; i++) { v[i] = first + i < n ? load(first + i) : 0; s += v[i]; }
+  uint32_t incl = s;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    uint32_t o = __shfl_up(incl, d, 64);
+    if ((int)(threadIdx.x & 63u) >= d) incl += o;
+  }
+  if ((threadIdx.x & 63u) == 63) sh[threadIdx.x >> 6] = incl;
+  __syncthreads();
+  uint32_t run = tile_excl[blockIdx.x] + incl - s;
+  for (uint32_t w = 0; w < (threadIdx.x >> 6); w++) run += sh[w];
+#pragma unroll
+  for (uint32_t i = 0; i < kScanItems; i++) { if (first + i < n) out[first + i] = run; run += v[i]; }
+}
+
+template <class L>
+static void exclusive_scan(L load, uint32_t n, uint32_t* tile_tmp, uint32_t* out, uint32_t* total, hipStream_t st) {
+  const uint32_t n_tiles = (n + kScanTile - 1) / kScanTile;
+  hipLaunchKernelGGL(scan_tile_sums_kernel<L>, dim3(n_tiles), dim3(256), 0, st, load, n, tile_tmp);
+  hipLaunchKernelGGL(scan_top_kernel, dim3(1), dim3(256), 0, st, tile_tmp, n_tiles, total);
+  hipLaunchKernelGGL(scan_apply_kernel<L>, dim3(n_tiles), dim3(256), 0, st, load, n, tile_tmp, out);
+}
+
+void scan_mask_words(const unsigned long long* mask, uint32_t n_words, uint32_t* tile_tmp, uint32_t* prefix,
+                     uint32_t* total, hipStream_t st) {
+  exclusive_scan(LoadPopc{mask}, n_words, tile_tmp, prefix, total, st);
+}
+
+void scan_flags(const uint8_t* flags, uint32_t n, uint32_t* tile_tmp, uint32_t* pos, uint32_t* total, hipStream_t st) {
+  exclusive_scan(LoadFlag{flags}, n, tile_tmp, pos, total, st);
+}
+
+// ---------------------------------------------------------------- boxes of pass 0
+__device__ __forceinline__ bool mask_bit(const unsigned long long* __restrict__ mask, uint32_t cell) {
+  return (mask[cell >> 6] >> (cell & 63u)) & 1ull;
+}
+
+__global__ __launch_bounds__(256) void make_boxes_kernel(Geo g, uint32_t a0,
+                                                         const unsigned long long* __restrict__ mask,
+                                                         const uint32_t* __restrict__ prefix, uint32_t n_words,
+                                                         uint32_t* __restrict__ bcell, uint4* __restrict__ blen,
+                                                         uint8_t* __restrict__ alive, uint8_t* __restrict__ pred) {
+  const uint32_t w = blockIdx.x * 256u + threadIdx.x;
+  if (w >= n_words) return;
+  unsigned long long m = mask[w];
+  uint32_t id = prefix[w];
+  const uint32_t s0 = g.stride[a0], e0 = g.ext[a0];
+  for (; m; m &= m - 1, id++) {
+    const uint32_t cell = (w << 6) + (uint32_t)__ffsll((long long)m) - 1u;
+    const uint32_t c0 = (cell / s0) % e0;
+    uint32_t len = 1;
+    while (c0 + len < e0 && !mask_bit(mask, cell + len * s0)) len++;
+    uint32_t L[4] = {0x01010101u, 0x01010101u, 0x01010101u, 0x01010101u};
+    L[a0 >> 2] = (L[a0 >> 2] & ~(0xFFu << ((a0 & 3u) * 8))) | (len << ((a0 & 3u) * 8));
+    bcell[id] = cell;
+    blen[id] = make_uint4(L[0], L[1], L[2], L[3]);
+    alive[id] = 1;
+    pred[id] = 0;
+  }
+}
+
+// ---------------------------------------------------------------- pass on axis a
+__device__ __forceinline__ uint32_t len_byte(const uint4& L, uint32_t a) {
+  const uint32_t w = a < 4 ? L.x : a < 8 ? L.y : a < 12 ? L.z : L.w;
+  return (w >> ((a & 3u) * 8)) & 0xFFu;
+}
+
+template <bool COST>
+__global__ __launch_bounds__(256) void link_kernel(Geo g, uint32_t a, uint8_t stamp, uint32_t n_boxes,
+                                                   const uint32_t* __restrict__ bcell, const uint4* __restrict__ blen,
+                                                   const uint8_t* __restrict__ alive, uint8_t* __restrict__ pred,
+                                                   uint32_t* __restrict__ next,
+                                                   const unsigned long long* __restrict__ mask,
+                                                   const uint32_t* __restrict__ prefix,
+                                                   const uint64_t* __restrict__ cost, const uint16_t* __restrict__ arg,
+                                                   const uint32_t* __restrict__ axis_sizes) {
+  const uint32_t b = blockIdx.x * 256u + threadIdx.x;
+  if (b >= n_boxes || !alive[b]) return;
+  const uint32_t cell = bcell[b];
+  const uint4 L = blen[b];
+  const uint32_t sa = g.stride[a], ea = g.ext[a];
+  const uint32_t ca = (cell / sa) % ea;
+  const uint32_t la = len_byte(L, a);
+  uint32_t nxt = 0xFFFFFFFFu;
+  if (ca + la < ea) {
+    const uint32_t s = cell + la * sa;
+    const unsigned long long m = mask[s >> 6];
+    if ((m >> (s & 63u)) & 1ull) {
+      const uint32_t o = prefix[s >> 6] + (uint32_t)__popcll(m & ((1ull << (s & 63u)) - 1ull));
+      if (alive[o]) {
+        const uint4 M = blen[o];
+        const uint32_t keep = ~(0xFFu << ((a & 3u) * 8));
+        const uint32_t kx = (a >> 2) == 0 ? keep : ~0u, ky = (a >> 2) == 1 ? keep : ~0u;
+        const uint32_t kz = (a >> 2) == 2 ? keep : ~0u, kw = (a >> 2) == 3 ? keep : ~0u;
+        bool same = ((L.x ^ M.x) & kx) == 0 && ((L.y ^ M.y) & ky) == 0 && ((L.z ^ M.z) & kz) == 0 && ((L.w ^ M.w) & kw) == 0;
+        if (same) {
+          if (COST) {
+            const uint32_t s1 = axis_sizes ? axis_sizes[ca] : 1u, s2 = axis_sizes ? axis_sizes[ca + la] : 1u;
+            same = norm_equal(cost[cell], s1, cost[s], s2);
+          } else {
+            same = arg[cell] == arg[s];
+          }
+        }
+        if (same) { nxt = o; pred[o] = stamp; }
+      }
+    }
+  }
+  next[b] = nxt;
+}
+
+__global__ __launch_bounds__(256) void absorb_kernel(uint32_t a, uint8_t stamp, uint32_t n_boxes,
+                                                     uint8_t* __restrict__ blen_bytes, uint8_t* __restrict__ alive,
+                                                     const uint8_t* __restrict__ pred, const uint32_t* __restrict__ next) {
+  const uint32_t b = blockIdx.x * 256u + threadIdx.x;
+  if (b >= n_boxes || !alive[b] || pred[b] == stamp) return;   // only heads of chains
+  uint32_t tot = blen_bytes[(size_t)b * 16 + a];
+  for (uint32_t s = next[b]; s != 0xFFFFFFFFu; s = next[s]) {
+    tot += blen_bytes[(size_t)s * 16 + a];
+    alive[s] = 0;
+  }
+  blen_bytes[(size_t)b * 16 + a] = (uint8_t)tot;
+}
+
+void launch_head_flags(const Geo& g, uint32_t a0, const uint64_t* cost, const uint16_t* arg, const uint32_t* axis_sizes,
+                       unsigned long long* maskD, unsigned long long* maskC, hipStream_t st) {
+  const uint32_t n_lines = g.n / g.ext[a0];
+  const uint32_t blocks = (n_lines + 255) / 256;
+  if (g.stride[a0] % 64 == 0)
+    hipLaunchKernelGGL(head_flags_kernel<true>, dim3(blocks), dim3(256), 0, st, g, a0, cost, arg, axis_sizes, maskD, maskC);
+  else
+    hipLaunchKernelGGL(head_flags_kernel<false>, dim3(blocks), dim3(256), 0, st, g, a0, cost, arg, axis_sizes, maskD, maskC);
+}
+
+void launch_make_boxes(const Geo& g, uint32_t a0, const unsigned long long* mask, const uint32_t* prefix, uint32_t n_words,
+                       uint32_t* bcell, void* blen, uint8_t* alive, uint8_t* pred, hipStream_t st) {
+  hipLaunchKernelGGL(make_boxes_kernel, dim3((n_words + 255) / 256), dim3(256), 0, st, g, a0, mask, prefix, n_words,
+                     bcell, (uint4*)blen, alive, pred);
+}
+
+void launch_axis_pass(const Geo& g, uint32_t a, uint8_t stamp, bool is_cost, uint32_t n_boxes, const uint32_t* bcell,
+                      void* blen, uint8_t* alive, uint8_t* pred, uint32_t* next, const unsigned long long* mask,
+                      const uint32_t* prefix, const uint64_t* cost, const uint16_t* arg, const uint32_t* axis_sizes,
+                      hipStream_t st) {
+  const uint32_t blocks = (n_boxes + 255) / 256;
+  if (is_cost)
+    hipLaunchKernelGGL(link_kernel<true>, dim3(blocks), dim3(256), 0, st, g, a, stamp, n_boxes, bcell, (const uint4*)blen,
+                       alive, pred, next, mask, prefix, cost, arg, axis_sizes);
+  else
+    hipLaunchKernelGGL(link_kernel<false>, dim3(blocks), dim3(256), 0, st, g, a, stamp, n_boxes, bcell, (const uint4*)blen,
+                       alive, pred, next, mask, prefix, cost, arg, axis_sizes);
+  hipLaunchKernelGGL(absorb_kernel, dim3(blocks), dim3(256), 0, st, a, stamp, n_boxes, (uint8_t*)blen, alive, pred, next);
+}
+
+// ---------------------------------------------------------------- final lists
+__device__ __forceinline__ uint64_t gcd_u64(uint64_t a, uint64_t b) {
+  while (b) { uint64_t t = a % b; a = b; b = t; }
+  return a;
+}
+
+template <bool COST>
+__global__ __launch_bounds__(256) void emit_kernel(Geo g, const DevParams* __restrict__ P, uint32_t n_boxes,
+                                                   const uint32_t* __restrict__ bcell, const uint4* __restrict__ blen,
+                                                   const uint8_t* __restrict__ alive, const uint32_t* __restrict__ pos,
+                                                   const uint64_t* __restrict__ cost, const uint16_t* __restrict__ arg,
+                                                   uint32_t* __restrict__ fcell, uint4* __restrict__ flen,
+                                                   uint64_t* __restrict__ fv0, uint64_t* __restrict__ fv1) {
+  const uint32_t b = blockIdx.x * 256u + threadIdx.x;
+  if (b >= n_boxes || !alive[b]) return;
+  const uint32_t o = pos[b], cell = bcell[b];
+  fcell[o] = cell;
+  flen[o] = blen[b];
+  if (COST) {
+    const uint64_t c = cost[cell];
+    if (c == kInf) { fv0[o] = kInf; fv1[o] = 0; }
+    else {
+      uint64_t vol = 1;
+#pragma unroll
+      for (int d = 0; d < 4; d++) vol *= P->sizes[d][(cell / g.stride[d]) % g.ext[d]];
+      const uint64_t q = gcd_u64(c, vol);
+      fv0[o] = c / q; fv1[o] = vol / q;
+    }
+  } else {
+    fv0[o] = arg[cell]; fv1[o] = 0;
+  }
+}
+
+void launch_emit(const Geo& g, const DevParams* P, bool is_cost, uint32_t n_boxes, const uint32_t* bcell, const void* blen,
+                 const uint8_t* alive, const uint32_t* pos, const uint64_t* cost, const uint16_t* arg, uint32_t* fcell,
+                 void* flen, uint64_t* fv0, uint64_t* fv1, hipStream_t st) {
+  const uint32_t blocks = (n_boxes + 255) / 256;
+  if (is_cost)
+    hipLaunchKernelGGL(emit_kernel<true>, dim3(blocks), dim3(256), 0, st, g, P, n_boxes, bcell, (const uint4*)blen, alive,
+                       pos, cost, arg, fcell, (uint4*)flen, fv0, fv1);
+  else
+    hipLaunchKernelGGL(emit_kernel<false>, dim3(blocks), dim3(256), 0, st, g, P, n_boxes, bcell, (const uint4*)blen, alive,
+                       pos, cost, arg, fcell, (uint4*)flen, fv0, fv1);
+}
+
+// ---------------------------------------------------------------- query
+__global__ __launch_bounds__(256) void gather_kernel(const uint64_t* __restrict__ idx, uint32_t n,
+                                                     const uint64_t* __restrict__ cost, const uint16_t* __restrict__ arg,
+                                                     uint64_t* __restrict__ cost_out, uint16_t* __restrict__ arg_out) {
+  const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+  if (i >= n) return;
+  cost_out[i] = cost[idx[i]];
+  arg_out[i] = arg[idx[i]];
+}
+
+void launch_gather(const uint64_t* idx, uint32_t n, const uint64_t* cost, const uint16_t* arg, uint64_t* cost_out,
+                   uint16_t* arg_out, hipStream_t st) {
+  hipLaunchKernelGGL(gather_kernel, dim3((n + 255) / 256), dim3(256), 0, st, idx, n, cost, arg, cost_out, arg_out);
+}
+
+__global__ __launch_bounds__(256) void zero_words_kernel(unsigned long long* p, uint32_t n) {
+  const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+  if (i < n) p[i] = 0;
+}
+
+void launch_zero_words(unsigned long long* p, uint32_t n, hipStream_t st) {
+  if (n) hipLaunchKernelGGL(zero_words_kernel, dim3((n + 255) / 256), dim3(256), 0, st, p, n);
+}
+
+}  // namespace mrl

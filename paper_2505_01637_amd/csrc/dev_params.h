@@ -1,0 +1,64 @@
+// Internal: lattice geometry and target tables as the kernels see them.
+// One DevParams lives in device memory per solved table; every field is
+// uniform across a workgroup, so reads compile to scalar loads.
+#pragma once
+#include <stdint.h>
+
+namespace mrl {
+
+constexpr uint64_t kInf = UINT64_MAX;
+constexpr uint32_t kNone = 0xFFFFu;
+constexpr uint64_t kLimit = 1ull << 62;      // finite costs stay below this
+constexpr int kMaxSizes = 256;
+constexpr int kMaxCombo = 256;               // n_levels ^ n_operands
+constexpr int kMaxRanks = 16;
+
+enum : uint32_t { kKindM = 0, kKindE = 1, kKindF = 2 };
+enum : uint32_t { kRead = 0, kRmw = 1, kWrite = 2 };
+
+struct DevParams {
+  // ---- geometry ----
+  uint32_t kind, nops, nlv, NL;
+  uint32_t npass;            // values of the passive level axis (FUSED: intermediate), else 1
+  uint32_t ncombo;           // NL^nops: level assignments of the operands
+  uint32_t nlay, ndt, V;     // layout bits, dtype bits, V = 2^(nlay+ndt) variants per combo
+  uint32_t G;                // entries per shape = ncombo * npass * V
+  uint32_t nsz[4];
+  uint32_t shape_stride[4];  // in shapes
+  uint32_t sizes[4][kMaxSizes];
+  uint32_t tile_off[4][kMaxSizes + 1];   // CSR into tile_jt / tile_trips, per (dim, size index)
+  const uint16_t* tile_jt;   // device: index of the tile size
+  const uint32_t* tile_trips;
+  uint8_t tile_dim_ok[4];    // which dims this kind may tile
+  uint8_t lay_bit[5];        // bit position inside the variant index, 0xFF = no coordinate
+  uint8_t dt_bit[5];
+  uint8_t base_bf16[5];
+  uint8_t access[5];
+  uint32_t lvpow[5];         // combo stride of operand i
+  // ---- target ----
+  uint64_t cap[4];
+  uint32_t load[4][4][2], store[4][4][2];
+  uint32_t convert, zero[4], s;
+  uint32_t nmk, mk_kind[8], mk_lanes[8];
+  uint64_t mk_cost[8];
+  // ---- rewrite ids ----
+  uint32_t move_base, tile_base, buf_id, maxs;
+  // ---- operand-level combos ordered by rank (sum of operand levels) ----
+  uint32_t nranks;
+  uint16_t combo_by_rank[kMaxCombo];
+  uint16_t rank_off[kMaxRanks + 2];
+  // ---- tables a FUSED lattice reads ----
+  const uint64_t* costM;
+  const uint64_t* costE;
+  uint32_t GM, VM, GE, VE, nszE_n;
+  uint8_t layM[3], layE[3];  // layout bit positions in the dependency's variant index
+};
+
+struct Counters {
+  unsigned long long n_admissible;
+  unsigned long long n_rewrites;
+  unsigned int overflow;
+  unsigned int pad;
+};
+
+}  // namespace mrl

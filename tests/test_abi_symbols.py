@@ -1,0 +1,47 @@
+"""The built C-ABI library loads and exports every symbol the header declares (no GPU needed)."""
+import os
+import re
+
+from paper_2505_01637_amd import binding as B
+from paper_2505_01637_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_every_declared_symbol_is_exported():
+    hdr = open(os.path.join(ROOT, "include", "morello_mi355x.h")).read()
+    declared = set(re.findall(r"\b(mrl_[a-z_]+)\s*\(", hdr))
+    assert declared == set(B.EXPORTS)
+    lib = B.lib()
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_host_logic_without_gpu():
+    """Descriptor validation, geometry and buffer sizes are host code."""
+    cfg = W.config(5)
+    t = B.Target(cfg["target"])
+    want = {"M": 28094464, "E": 369664, "F": 449511424}
+    for label, lat, _ in cfg["lattices"]:
+        ext, n = B.geometry(t, lat)
+        assert n == want[label] == W.n_specs(cfg["target"], lat)
+        assert ext == W.coord_extents(cfg["target"], lat)
+        cb, ab, sb = B.table_bytes(t, lat)
+        assert cb == 8 * n and ab == 2 * n and sb > 0
+    for number, n in [(1, 32768), (2, 16777216), (3, 92160), (4, 23708160)]:
+        c = W.config(number)
+        assert B.geometry(B.Target(c["target"]), c["lattices"][0][1])[1] == n
+    bad = W.config(1)
+    bad["target"]["n_levels"] = 7
+    try:
+        B.Target(bad["target"])
+        assert False
+    except B.MorelloError as e:
+        assert e.code == B.E_INVAL
+    lat = dict(cfg["lattices"][0][1])
+    lat["sizes"] = [[1], [2, 4], [1], [1]]         # does not start with 1
+    try:
+        B.geometry(t, lat)
+        assert False
+    except B.MorelloError as e:
+        assert e.code == B.E_INVAL and "start with 1" in str(e)

@@ -1,0 +1,158 @@
+"""GPU parity: the HIP library against the CPU oracle, bit-exact, through the C ABI.
+
+Compared per lattice: dense cost (u64) and argmin (u16) tables, the admissible and
+rewrite counters, the decision box list and the cost box list.
+"""
+import numpy as np
+import pytest
+
+from oracle import oracle as O
+from paper_2505_01637_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+def _binding():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2505_01637_amd import binding as B
+    return B
+
+
+def compare_config(cfg, boxes=True, scratch_bytes=None):
+    B = _binding()
+    want = O.solve_config(cfg)
+    target, got = B.solve_config(cfg, scratch_bytes=scratch_bytes)
+    for label, lat, _ in cfg["lattices"]:
+        w, g = want[label], got[label]
+        print("compare", cfg["name"], label, "specs", g.n_specs, flush=True)
+        assert g.extents == w["extents"]
+        cost, arg = g.dense()
+        bad = np.flatnonzero(cost != w["cost"])
+        assert bad.size == 0, (label, "cost", bad[:5], cost[bad[:5]], w["cost"][bad[:5]])
+        bad = np.flatnonzero(arg != w["argmin"])
+        assert bad.size == 0, (label, "argmin", bad[:5], arg[bad[:5]], w["argmin"][bad[:5]])
+        assert g.stats.n_specs == len(cost)
+        assert g.stats.n_admissible == w["n_admissible"]
+        assert g.stats.n_rewrites == w["n_rewrites"]
+        if boxes:
+            dec, cst = O.compress_table(cfg["target"], lat, w["cost"], w["argmin"])
+            gd, gc = g.boxes(0), g.boxes(1)
+            assert g.stats.n_decision_boxes == len(dec) == len(gd)
+            assert g.stats.n_cost_boxes == len(cst) == len(gc)
+            assert gd.tobytes() == dec.tobytes(), (label, "decision boxes")
+            assert gc.tobytes() == cst.tobytes(), (label, "cost boxes")
+    return target, got, want
+
+
+SMALL = [(1, None), (2, 20), (3, None), (4, 16), (5, 16)]
+
+
+@pytest.mark.parametrize("number,max_size", SMALL)
+def test_parity_small(number, max_size):
+    """Every configuration at a size the oracle finishes in seconds; several tiles of
+    every kernel, ragged tails (sizes 1..20 are not multiples of the wave)."""
+    compare_config(W.config(number, max_size=max_size))
+
+
+@pytest.mark.parametrize("seed", [11, 12, 13])
+def test_parity_other_seeds(seed):
+    compare_config(W.config(5, seed=seed, max_size=8))
+    compare_config(W.config(3, seed=seed, max_size=64))
+
+
+@pytest.mark.parametrize("number", [2, 4])
+def test_parity_full_size(number):
+    """Configurations 2 and 4 at full size (16.8 M and 23.7 M specs), all outputs."""
+    compare_config(W.config(number), scratch_bytes=2 << 30)
+
+
+def test_degenerate_lattices():
+    B = _binding()
+    # a single shape: every dimension pinned
+    cfg = W.config(2, max_size=1)
+    compare_config(cfg)
+    # one memory level only: no Moves at all
+    t = W._empty_target(1, (256,))
+    t["loop_overhead"] = 3
+    t["microkernels"] = [(W.MK_SCALAR_FMA, 1, 2)]
+    cfg = {"name": "one-level", "target": t,
+           "lattices": [("M", W._lattice(W.KIND_MATMUL_ACCUM, [[1, 2], [1, 3, 9], [1, 2, 4], [1, 5]]), [])]}
+    compare_config(cfg)
+    # three levels, no microkernel at all: nothing is solvable
+    t = W._empty_target(3, (256, 512, W.UNBOUNDED))
+    t["load_coef"][1][0][0] = t["load_coef"][2][1][0] = t["load_coef"][2][0][0] = 1
+    t["store_coef"][0][1][0] = t["store_coef"][1][2][0] = t["store_coef"][0][2][0] = 1
+    cfg = {"name": "no-mk", "target": t,
+           "lattices": [("M", W._lattice(W.KIND_MATMUL_ACCUM, [[1], [1, 2], [1, 2], [1, 2, 4]]), [])]}
+    _, got, _ = compare_config(cfg)
+    cost, arg = got["M"].dense()
+    assert (cost == B.INF).all() and (arg == B.NONE).all()
+    assert got["M"].stats.n_decision_boxes == 1
+    # a Move forbidden by a zero coefficient
+    cfg = W.config(2, max_size=8)
+    cfg["target"]["load_coef"][3][0][0] = 0
+    cfg["target"]["store_coef"][1][2][0] = 0
+    compare_config(cfg)
+
+
+def test_query_decode_and_errors():
+    B = _binding()
+    cfg = W.config(4, max_size=16)
+    target, got, want = compare_config(cfg, boxes=False)
+    tab = got["M"]
+    ext = tab.extents
+    rng = np.random.default_rng(1)
+    coords = np.stack([rng.integers(0, e, size=5000) for e in ext], axis=1)
+    cost, rw = tab.query(coords)
+    lin = np.ravel_multi_index(coords.T, ext)
+    assert np.array_equal(cost, want["M"]["cost"][lin]) and np.array_equal(rw, want["M"]["argmin"][lin])
+    # coordinate of a spec given by sizes and levels
+    x = tab.coord_of_spec((2, 8, 4, 16), (3, 2, 1), layouts=(1, 0, 1))
+    assert x == [1, 3, 2, 4, 3, 2, 1, 1, 0, 1]
+    # rewrite ids decode to what the oracle's id layout says
+    _, _, ids = O.geometry(cfg["target"], cfg["lattices"][0][1])
+    r = tab.rewrite_decode(ids["tile_base"] + 3 * ids["maxs"] + 2)
+    assert (r.cls, r.operand_or_dim, r.tile_size) == (2, 3, 4)
+    r = tab.rewrite_decode(ids["move_base"] + ((2 * 3 + 1) * 2 + 1) * 2)
+    assert (r.cls, r.operand_or_dim, r.dst_level, r.transposed, r.convert) == (1, 2, 1, 1, 0)
+    assert tab.rewrite_decode(1).cls == 0 and tab.rewrite_decode(1).mk_index == 1
+    with pytest.raises(B.MorelloError) as e:
+        tab.query(np.array([[0, 0, 0, 99, 0, 0, 0, 0, 0, 0]]))
+    assert e.value.code == B.E_RANGE
+    with pytest.raises(B.MorelloError) as e:
+        tab.coord_of_spec((1, 3, 1, 1), (0, 0, 0), layouts=(0, 0, 0))
+    assert e.value.code == B.E_RANGE
+    # scratch too small for the data -> MRL_E_NOMEM, no table
+    with pytest.raises(B.MorelloError) as e:
+        B.solve(target, cfg["lattices"][0][1], scratch_bytes=4096)
+    assert e.value.code == B.E_NOMEM
+    # box buffer too small -> MRL_E_BUFSZ and the needed count
+    import ctypes as C
+    n = C.c_size_t()
+    buf = np.zeros(1, dtype=B.BOX_DTYPE)
+    rc = B.lib().mrl_emit_compressed(tab._h, C.c_uint32(0), C.c_void_p(buf.ctypes.data), C.c_size_t(1), C.byref(n))
+    assert rc == B.E_BUFSZ and n.value == tab.stats.n_decision_boxes
+    # overflow is reported, as by the oracle
+    bad = W.config(1)
+    bad["target"]["microkernels"] = [(W.MK_SCALAR_FMA, 1, 1 << 61)]
+    assert O.solve(bad["target"], bad["lattices"][0][1])["rc"] == -6
+    with pytest.raises(B.MorelloError) as e:
+        B.solve_config(bad)
+    assert e.value.code == B.E_OVERFLOW
+    # a fused lattice without its dependencies
+    c5 = W.config(5, max_size=4)
+    with pytest.raises(B.MorelloError) as e:
+        B.solve(B.Target(c5["target"]), c5["lattices"][2][1])
+    assert e.value.code == B.E_INVAL
+
+
+def test_deterministic():
+    B = _binding()
+    cfg = W.config(5, max_size=16)
+    outs = []
+    for _ in range(2):
+        _, got = B.solve_config(cfg)
+        outs.append([(got[l].dense(), got[l].boxes(0).tobytes(), got[l].boxes(1).tobytes()) for l in "MEF"])
+    for a, b in zip(*outs):
+        assert np.array_equal(a[0][0], b[0][0]) and np.array_equal(a[0][1], b[0][1]) and a[1:] == b[1:]

@@ -11,12 +11,16 @@
 //      levels and the admissible ones are compacted, ordered by rank (sum of
 //      the operand levels), into a task list in LDS;
 //   2. entries that do not fit are streamed out as (INF, NONE);
-//   3. rank by rank, one thread per task evaluates every rewrite of its Spec
-//      in id order and keeps the first strict minimum (= lowest id among
-//      ties).  Move sub-Specs are in the same unit at a lower rank: read from
-//      LDS.  Tile sub-Specs sit at the same offset of a smaller shape's group:
-//      consecutive lanes read consecutive addresses.  Results go to LDS (for
-//      later ranks) and to the table.
+//   3. one thread per task evaluates the tile and bufferize rewrites, whose
+//      sub-Specs belong to other shapes or tables and are final: a tile
+//      sub-Spec sits at the same offset of a smaller shape's group, so
+//      consecutive lanes read consecutive addresses, several loads in flight
+//      per lane.  The best of them is parked in LDS;
+//   4. rank by rank, one thread per task evaluates the microkernels and the
+//      Moves (sub-Specs in the same unit at a lower rank: read from LDS), in
+//      id order, keeping the first strict minimum (= lowest id among ties),
+//      then takes the parked candidate if strictly lower (its ids are higher).
+//      Results go to LDS (for later ranks) and to the table.
 // Nothing is reduced across lanes, so the result cannot depend on timing.
 #include <hip/hip_runtime.h>
 #include "dev_params.h"
@@ -163,6 +167,16 @@ __device__ __forceinline__ uint64_t mk_reps(const DevParams* __restrict__ P, con
   }
 }
 
+// Store `bytes` (2, 4, 8 or 16) bytes of all-ones at p: INF costs and NONE ids are all-ones.
+__device__ __forceinline__ void store_ones(void* p, uint32_t bytes) {
+  if (bytes == 16) *reinterpret_cast<uint4*>(p) = make_uint4(~0u, ~0u, ~0u, ~0u);
+  else if (bytes == 8) *reinterpret_cast<uint2*>(p) = make_uint2(~0u, ~0u);
+  else if (bytes == 4) *reinterpret_cast<uint32_t*>(p) = ~0u;
+  else *reinterpret_cast<uint16_t*>(p) = (uint16_t)0xFFFFu;
+}
+
+constexpr int kTileBatch = 8;   // sub-Spec costs fetched together before they are compared
+
 template <int T>
 __global__ __launch_bounds__(T) void fill_level_kernel(const DevParams* __restrict__ P,
                                                         const uint32_t* __restrict__ level_shapes,
@@ -173,8 +187,9 @@ __global__ __launch_bounds__(T) void fill_level_kernel(const DevParams* __restri
   extern __shared__ __align__(16) unsigned char smem[];
   const uint32_t ncombo = P->ncombo, V = P->V, npass = P->npass;
   const uint32_t max_task = ncombo * V;
-  uint64_t* t_cost = reinterpret_cast<uint64_t*>(smem);                  // [max_task] result per task
-  uint32_t* t_spec = reinterpret_cast<uint32_t*>(t_cost + max_task);     // [max_task] combo | variant<<16
+  uint64_t* t_cost = reinterpret_cast<uint64_t*>(smem);                  // [max_task] per task: best tile/bufferize
+                                                                          //   candidate, then the final cost
+  uint32_t* t_spec = reinterpret_cast<uint32_t*>(t_cost + max_task);     // [max_task] combo | variant<<8 | id<<16
   uint32_t* c_mask = t_spec + max_task;                                   // [ncombo] admissible variants
   uint32_t* c_base = c_mask + ncombo;                                     // [ncombo] first task of the combo
   uint32_t* r_off = c_base + ncombo;                                      // [nranks+1] first task of the rank
@@ -204,34 +219,100 @@ __global__ __launch_bounds__(T) void fill_level_kernel(const DevParams* __restri
   if (tid < ncombo) {
     c_base[my_combo] = my_base;
     uint32_t q = my_base;
-    for (uint32_t m = my_mask; m; m &= m - 1) t_spec[q++] = my_combo | ((uint32_t)__ffs(m) - 1u) << 16;
+    for (uint32_t m = my_mask; m; m &= m - 1) t_spec[q++] = my_combo | ((uint32_t)__ffs(m) - 1u) << 8;
+    for (uint32_t r = 0; r < P->nranks; r++)
+      if (tid == P->rank_off[r]) r_off[r] = my_base;
   }
-  // rank r starts at the task of the first combo of that rank
-  for (uint32_t r = 0; r < P->nranks; r++)
-    if (tid == P->rank_off[r]) r_off[r] = my_base;
   if (tid == 0) r_off[P->nranks] = n_task;
   __syncthreads();
 
-  // ---- 2. entries that do not fit: (INF, NONE) ----
-  for (uint32_t u = tid; u < max_task; u += T) {
-    uint32_t combo = u / V, v = u - combo * V;
-    if (!((c_mask[combo] >> v) & 1u)) {
-      uint64_t x = group + (uint64_t)(combo * npass + pass) * V + v;
-      cost[x] = kInf;
-      arg[x] = (uint16_t)kNone;
+  // ---- 2. entries that do not fit: (INF, NONE), written in chunks of up to 16 bytes ----
+  {
+    const uint32_t cch = V < 2 ? V : 2, cper = V / cch;        // cost: entries per chunk, chunks per combo
+    for (uint32_t c = tid; c < ncombo * cper; c += T) {
+      const uint32_t combo = c / cper, v0 = (c - combo * cper) * cch;
+      const uint32_t bits = (c_mask[combo] >> v0) & ((1u << cch) - 1u);
+      uint64_t* p = cost + group + (uint64_t)(combo * npass + pass) * V + v0;
+      if (bits == 0) store_ones(p, 8 * cch);
+      else for (uint32_t u = 0; u < cch; u++) if (!((bits >> u) & 1u)) p[u] = kInf;
+    }
+    const uint32_t ach = V < 8 ? V : 8, aper = V / ach;        // argmin: likewise
+    for (uint32_t c = tid; c < ncombo * aper; c += T) {
+      const uint32_t combo = c / aper, v0 = (c - combo * aper) * ach;
+      const uint32_t bits = (c_mask[combo] >> v0) & ((1u << ach) - 1u);
+      uint16_t* p = arg + group + (uint64_t)(combo * npass + pass) * V + v0;
+      if (bits == 0) store_ones(p, 2 * ach);
+      else for (uint32_t u = 0; u < ach; u++) if (!((bits >> u) & 1u)) p[u] = (uint16_t)kNone;
     }
   }
 
-  // ---- 3. rank by rank ----
   Eval tot;
   tot.n = 0; tot.ovf = 0;
   const uint32_t NL = P->NL;
+
+  // ---- 3. tile and bufferize candidates of every task (sub-Specs of other shapes / tables:
+  //         final already, no ordering needed).  kTileBatch loads are in flight per thread. ----
+  for (uint32_t q = tid; q < n_task; q += T) {
+    const uint32_t sp = t_spec[q];
+    const uint32_t combo = sp & 0xFFu, v = (sp >> 8) & 0xFFu;
+    const uint32_t off = (combo * npass + pass) * V + v;
+    Eval e;
+    e.best = kInf; e.arg = kNone; e.n = 0; e.ovf = 0;
+#pragma unroll
+    for (int d = 0; d < 4; d++) {
+      if (!P->tile_dim_ok[d]) continue;
+      const uint32_t j = S.si[d];
+      const uint32_t q_end = P->tile_off[d][j + 1];
+      for (uint32_t q2 = P->tile_off[d][j]; q2 < q_end; q2 += kTileBatch) {
+        uint64_t sub[kTileBatch];
+        uint32_t jt[kTileBatch];
+#pragma unroll
+        for (int u = 0; u < kTileBatch; u++) {
+          const uint32_t qq = q2 + u < q_end ? q2 + u : q_end - 1;
+          jt[u] = P->tile_jt[qq];
+          sub[u] = cost[(uint64_t)(shape - (j - jt[u]) * P->shape_stride[d]) * P->G + off];
+        }
+#pragma unroll
+        for (int u = 0; u < kTileBatch; u++)
+          if (q2 + u < q_end)
+            consider(e, affine(e, P->tile_trips[q2 + u], sub[u], P->s), P->tile_base + d * P->maxs + jt[u]);
+      }
+    }
+    // bufferize (FUSED): Matmul into the intermediate, then bias-add+ReLU out of it
+    if (P->kind == kKindF) {
+      uint32_t lv[4];
+      decode_levels(P, combo, lv);
+      const uint32_t y0 = P->lay_bit[0] != 0xFF ? (v >> P->lay_bit[0]) & 1u : 0u;
+      const uint32_t y1 = P->lay_bit[1] != 0xFF ? (v >> P->lay_bit[1]) & 1u : 0u;
+      const uint32_t y3 = P->lay_bit[3] != 0xFF ? (v >> P->lay_bit[3]) & 1u : 0u;
+      const uint32_t xm = ((lv[0] * NL + lv[1]) * NL + pass) * P->VM +
+                          (P->layM[0] != 0xFF ? y0 << P->layM[0] : 0u) + (P->layM[1] != 0xFF ? y1 << P->layM[1] : 0u);
+      const uint32_t xe = ((pass * NL + lv[2]) * NL + lv[3]) * P->VE + (P->layE[2] != 0xFF ? y3 << P->layE[2] : 0u);
+      const uint64_t cm = P->costM[(uint64_t)shape * P->GM + xm];
+      const uint64_t ce = P->costE[(uint64_t)(S.si[1] * P->nszE_n + S.si[3]) * P->GE + xe];
+      uint64_t cand = kInf;
+      if (cm != kInf && ce != kInf) {
+        const uint64_t z = mul_checked(e, P->zero[pass], S.numel[4]);
+        const uint64_t sum = z + cm;          // each term < 2^62: no wrap
+        if (sum >= kLimit || sum + ce >= kLimit) e.ovf = 1; else cand = sum + ce;
+      }
+      consider(e, cand, P->buf_id);
+    }
+    t_cost[q] = e.best;
+    t_spec[q] = sp | e.arg << 16;
+    tot.n += e.n;
+    tot.ovf |= e.ovf;
+  }
+  __syncthreads();
+
+  // ---- 4. rank by rank: microkernels, Moves (sub-Specs of lower rank, in LDS), then the
+  //         stored tile/bufferize candidate, whose ids are higher: it wins only if strictly lower ----
   for (uint32_t r = 0; r < P->nranks; r++) {
     const uint32_t t0 = r_off[r], t1 = r_off[r + 1];
     if (t0 == t1) continue;
     for (uint32_t q = t0 + tid; q < t1; q += T) {
       const uint32_t sp = t_spec[q];
-      const uint32_t combo = sp & 0xFFFFu, v = sp >> 16;
+      const uint32_t combo = sp & 0xFFu, v = (sp >> 8) & 0xFFu;
       uint32_t lv[4], ly[4], bf[4];
       decode_levels(P, combo, lv);
 #pragma unroll
@@ -248,7 +329,7 @@ __global__ __launch_bounds__(T) void fill_level_kernel(const DevParams* __restri
         if (reps) consider(e, affine(e, 0, 0, mul_checked(e, P->mk_cost[j], reps)), j);
       }
 
-      // B. Move operand i to a strictly lower level (sub-Spec in this unit, lower rank)
+      // B. Move operand i to a strictly lower level
 #pragma unroll
       for (int i = 0; i < 4; i++) {
         if ((uint32_t)i >= P->nops) break;
@@ -274,35 +355,11 @@ __global__ __launch_bounds__(T) void fill_level_kernel(const DevParams* __restri
             }
       }
 
-      // C. tile one dimension (sub-Spec: same offset inside a smaller shape's group)
+      // C, D. tiles and bufferize, evaluated above
+      const uint64_t tb = t_cost[q];
+      if (tb < e.best) { e.best = tb; e.arg = sp >> 16; }
+
       const uint32_t off = (combo * npass + pass) * V + v;
-#pragma unroll
-      for (int d = 0; d < 4; d++) {
-        if (!P->tile_dim_ok[d]) continue;
-        const uint32_t j = S.si[d];
-        for (uint32_t q2 = P->tile_off[d][j]; q2 < P->tile_off[d][j + 1]; q2++) {
-          const uint32_t jt = P->tile_jt[q2];
-          const uint64_t sub_group = (uint64_t)(shape - (j - jt) * P->shape_stride[d]) * P->G;
-          consider(e, affine(e, P->tile_trips[q2], cost[sub_group + off], P->s), P->tile_base + d * P->maxs + jt);
-        }
-      }
-
-      // D. bufferize (FUSED): Matmul into the intermediate, then bias-add+ReLU out of it
-      if (P->kind == kKindF) {
-        const uint32_t xm = ((lv[0] * NL + lv[1]) * NL + pass) * P->VM +
-                            (P->layM[0] != 0xFF ? ly[0] << P->layM[0] : 0u) + (P->layM[1] != 0xFF ? ly[1] << P->layM[1] : 0u);
-        const uint32_t xe = ((pass * NL + lv[2]) * NL + lv[3]) * P->VE + (P->layE[2] != 0xFF ? ly[3] << P->layE[2] : 0u);
-        const uint64_t cm = P->costM[(uint64_t)shape * P->GM + xm];
-        const uint64_t ce = P->costE[(uint64_t)(S.si[1] * P->nszE_n + S.si[3]) * P->GE + xe];
-        uint64_t cand = kInf;
-        if (cm != kInf && ce != kInf) {
-          uint64_t z = mul_checked(e, P->zero[pass], S.numel[4]);
-          uint64_t sum = z + cm;          // each term < 2^62: no wrap
-          if (sum >= kLimit || sum + ce >= kLimit) e.ovf = 1; else cand = sum + ce;
-        }
-        consider(e, cand, P->buf_id);
-      }
-
       t_cost[q] = e.best;
       cost[group + off] = e.best;
       arg[group + off] = (uint16_t)e.arg;
@@ -312,7 +369,7 @@ __global__ __launch_bounds__(T) void fill_level_kernel(const DevParams* __restri
     __syncthreads();
   }
 
-  // ---- 4. counters (integer sums: order-independent) ----
+  // ---- 5. counters (integer sums: order-independent) ----
   uint32_t n = tot.n;
 #pragma unroll
   for (int d = 32; d > 0; d >>= 1) n += __shfl_down(n, d, 64);

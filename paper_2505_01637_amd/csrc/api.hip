@@ -54,8 +54,8 @@ struct Compiled {
   uint32_t merge_order[16];
   uint32_t n_shapes;
   uint64_t n_specs;
-  int block;
-  size_t lds_bytes;
+  std::vector<uint8_t> mk_entry;          // [256][V]
+  uint32_t max_task;                      // entries of one unit = ncombo * V
   int lay_axis[5], dt_axis[5];            // coordinate axis of the operand's bit, -1 if none
   mrl_target_desc target;
   mrl_lattice_desc lat;                   // sizes pointers re-pointed to this->sizes
@@ -63,7 +63,7 @@ struct Compiled {
 
 // Offsets of the fixed part of the scratch buffer.
 struct FixedLayout {
-  size_t counters, params, tile_jt, tile_trips, level_shapes, maskD, maskC, prefD, prefC, tile_tmp, totals,
+  size_t counters, params, tile_jt, tile_trips, level_shapes, mk_entry, big_list, big_count, maskD, maskC, prefD, prefC, tile_tmp, totals,
       q_idx, q_cost, q_arg, end;
   uint32_t n_words;
 };
@@ -78,6 +78,9 @@ FixedLayout fixed_layout(const Compiled& c) {
   f.tile_jt = take(c.tile_jt.size() * 2 + 2);
   f.tile_trips = take(c.tile_trips.size() * 4 + 4);
   f.level_shapes = take(c.level_shapes.size() * 4);
+  f.mk_entry = take(c.mk_entry.size());
+  f.big_list = take((size_t)c.n_shapes * c.P.npass * 4);
+  f.big_count = take(c.level_off.size() * 4);
   f.maskD = take((size_t)f.n_words * 8);
   f.maskC = take((size_t)f.n_words * 8);
   f.prefD = take((size_t)f.n_words * 4);
@@ -156,6 +159,7 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
     P.base_bf16[i] = L->base_dtype_bytes[i] == 2;
     P.access[i] = L->kind == kKindM ? (i == 2 ? kRmw : kRead) : (i == P.nops - 1 ? kWrite : kRead);
     P.lvpow[i] = ipow(P.NL, P.nops - 1 - i);
+    P.pack_shift[i] = (uint8_t)(2 * (P.nops - 1 - i));
   }
   P.V = 1u << (P.nlay + P.ndt);
   if (P.V > 32) return fail(MRL_E_INVAL, "too many layout/dtype bits");
@@ -174,8 +178,6 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
   for (int l = 0; l < 4; l++) {
     P.cap[l] = T.capacity_bytes[l];
     P.zero[l] = T.zero_coef[l];
-    for (int k = 0; k < 4; k++)
-      for (int x = 0; x < 2; x++) { P.load[l][k][x] = T.load_coef[l][k][x]; P.store[l][k][x] = T.store_coef[l][k][x]; }
   }
   P.convert = T.convert_coef;
   P.s = T.loop_overhead;
@@ -188,6 +190,62 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
   P.tile_base = P.move_base + P.nops * (P.NL - 1) * 4;
   P.buf_id = P.tile_base + 4 * maxs;
   if (P.buf_id >= kNone) return fail(MRL_E_INVAL, "rewrite ids do not fit 16 bits");
+
+  // Moves: coefficient per (operand, src, dst, transposed) and the list of Moves that can occur
+  for (uint32_t i = 0; i < P.nops; i++)
+    for (uint32_t src = 0; src < P.NL; src++)
+      for (uint32_t dst = 0; dst < src; dst++)
+        for (uint32_t x = 0; x < 2; x++) {
+          if (x && !L->layout_coord[i]) continue;
+          const uint32_t ld = T.load_coef[src][dst][x], st = T.store_coef[dst][src][x];
+          uint64_t cf = 0;
+          if (P.access[i] != kWrite) { if (!ld) continue; cf += ld; }
+          if (P.access[i] != kRead) { if (!st) continue; cf += st; }
+          if (cf > UINT32_MAX) return fail(MRL_E_INVAL, "Move coefficients too large");
+          P.mcoef[i][src][dst][x] = (uint32_t)cf;
+        }
+  for (uint32_t i = 0; i < P.nops; i++)
+    for (uint32_t dst = 0; dst + 1 < P.NL; dst++)
+      for (uint32_t x = 0; x < 2; x++)
+        for (uint32_t cv = 0; cv < 2; cv++) {
+          if (x && !L->layout_coord[i]) continue;
+          if (cv && !(L->dtype_coord[i] && P.access[i] == kRead)) continue;
+          bool any = false;
+          for (uint32_t src = dst + 1; src < P.NL; src++) any = any || P.mcoef[i][src][dst][x];
+          if (!any) continue;
+          const uint32_t id = P.move_base + ((i * (P.NL - 1) + dst) * 2 + x) * 2 + cv;
+          P.slots[P.n_slots++] = i | dst << 2 | x << 4 | cv << 5 | (uint32_t)P.pack_shift[i] << 6 |
+                                 (uint32_t)(x ? P.lay_bit[i] : 0) << 9 | (uint32_t)(cv ? P.dt_bit[i] : 0) << 12 | id << 16;
+        }
+
+  // microkernels: the level / layout / dtype part of each predicate, per (pack, variant)
+  c.mk_entry.assign((size_t)256 * P.V, 0);
+  for (uint32_t pack = 0; pack < 256; pack++)
+    for (uint32_t v = 0; v < P.V; v++) {
+      uint32_t lv[4], ly[4], bf[4];
+      bool in_range = true;
+      for (uint32_t i = 0; i < 4; i++) {
+        lv[i] = i < P.nops ? (pack >> P.pack_shift[i]) & 3u : 0u;
+        in_range = in_range && lv[i] < P.NL;
+        ly[i] = i < P.nops && P.lay_bit[i] != 0xFF ? (v >> P.lay_bit[i]) & 1u : 0u;
+        bf[i] = i < P.nops ? (P.dt_bit[i] != 0xFF ? (v >> P.dt_bit[i]) & 1u : P.base_bf16[i]) : 0u;
+      }
+      if (!in_range || (P.nops < 4 && (pack >> (2 * P.nops)))) continue;
+      uint8_t bits = 0;
+      for (uint32_t j = 0; j < P.nmk; j++) {
+        bool ok = false;
+        const bool all_f32 = !(bf[0] | bf[1] | bf[2]);
+        switch (T.mk[j].kind) {
+          case MRL_MK_SCALAR_FMA: ok = P.kind == kKindM && !(lv[0] | lv[1] | lv[2]) && all_f32; break;
+          case MRL_MK_BCAST_VEC_MULADD: ok = P.kind == kKindM && lv[0] == 0 && lv[1] == 1 && lv[2] == 1 && all_f32 && !ly[1] && !ly[2]; break;
+          case MRL_MK_BF16_DOT: ok = P.kind == kKindM && lv[0] == 1 && lv[1] == 1 && lv[2] == 0 && bf[0] && bf[1] && !bf[2] && (P.lay_bit[1] == 0xFF || ly[1] == 1); break;
+          case MRL_MK_SCALAR_ADDRELU: ok = P.kind == kKindE && !(lv[0] | lv[1] | lv[2]); break;
+          case MRL_MK_VEC_ADDRELU: ok = P.kind == kKindE && lv[0] == 1 && lv[1] == 1 && lv[2] == 1 && !ly[0] && !ly[2]; break;
+        }
+        bits |= (uint8_t)((ok ? 1u : 0u) << j);
+      }
+      c.mk_entry[(size_t)pack * P.V + v] = bits;
+    }
 
   // tiles: for (dim, size index) the smaller allowed sizes dividing it
   for (int d = 0; d < 4; d++) {
@@ -219,7 +277,13 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
       while (q < order.size() && order[q].first < r) q++;
       P.rank_off[r] = (uint16_t)q;
     }
-    for (uint32_t i = 0; i < order.size(); i++) P.combo_by_rank[i] = (uint16_t)order[i].second;
+    for (uint32_t i = 0; i < order.size(); i++) {
+      const uint32_t combo = order[i].second;
+      uint32_t pack = 0;
+      for (uint32_t op = 0; op < P.nops; op++) pack |= ((combo / P.lvpow[op]) % P.NL) << P.pack_shift[op];
+      P.combo_by_rank[i] = (uint16_t)combo;
+      P.pack_by_rank[i] = (uint8_t)pack;
+    }
   }
 
   // dependency level of a shape = sum over tiled dims of the longest divisor chain below its size
@@ -271,9 +335,8 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
     for (int a = (int)nd - 1; a >= 4 + (int)(P.nlv + P.nlay); a--) c.merge_order[q++] = (uint32_t)a;
   }
 
-  c.block = P.ncombo <= 64 ? 64 : 256;
-  const size_t max_task = (size_t)P.ncombo * P.V;
-  c.lds_bytes = max_task * 12 + (size_t)P.ncombo * 8 + (kMaxRanks + 2 + 4) * 4;
+  c.max_task = P.ncombo * P.V;
+  if (c.max_task > 4096) return fail(MRL_E_INVAL, "too many entries per shape and intermediate level (%u > 4096)", c.max_task);
   return MRL_OK;
 }
 
@@ -378,7 +441,12 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
   P.tile_jt = (const uint16_t*)(base + f.tile_jt);
   P.tile_trips = (const uint32_t*)(base + f.tile_trips);
   uint32_t* d_level_shapes = (uint32_t*)(base + f.level_shapes);
+  uint32_t* d_big_list = (uint32_t*)(base + f.big_list);
+  uint32_t* d_big_count = (uint32_t*)(base + f.big_count);
+  P.mk_entry = (const uint8_t*)(base + f.mk_entry);
   HIP_TRY(hipMemsetAsync(d_ctr, 0, sizeof(Counters), st));
+  HIP_TRY(hipMemsetAsync(d_big_count, 0, c.level_off.size() * 4, st));
+  HIP_TRY(hipMemcpyAsync((void*)P.mk_entry, c.mk_entry.data(), c.mk_entry.size(), hipMemcpyHostToDevice, st));
   HIP_TRY(hipMemcpyAsync(d_P, &P, sizeof P, hipMemcpyHostToDevice, st));
   if (!c.tile_jt.empty()) {
     HIP_TRY(hipMemcpyAsync((void*)P.tile_jt, c.tile_jt.data(), c.tile_jt.size() * 2, hipMemcpyHostToDevice, st));
@@ -394,8 +462,8 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
   HIP_TRY(hipEventRecord(ev[0], st));
   const uint32_t n_lev = (uint32_t)c.level_off.size() - 1;
   for (uint32_t l = 0; l < n_lev; l++) {
-    const uint32_t n_units = (c.level_off[l + 1] - c.level_off[l]) * P.npass;
-    launch_fill_level(c.block, d_P, d_level_shapes + c.level_off[l], n_units, tab->d_cost, tab->d_arg, d_ctr, c.lds_bytes, st);
+    launch_fill_level(d_P, P.npass, c.max_task, d_level_shapes + c.level_off[l], c.level_off[l + 1] - c.level_off[l],
+                      d_big_list + (size_t)c.level_off[l] * P.npass, d_big_count + l, tab->d_cost, tab->d_arg, d_ctr, st);
   }
   HIP_TRY(hipGetLastError());
   HIP_TRY(hipEventRecord(ev[1], st));

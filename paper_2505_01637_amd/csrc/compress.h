@@ -13,8 +13,9 @@ struct Geo {
   uint32_t ext[16], stride[16];
 };
 
-void launch_fill_level(int block, const DevParams* P, const uint32_t* level_shapes, uint32_t n_units,
-                       uint64_t* cost, uint16_t* arg, Counters* ctr, size_t lds_bytes, hipStream_t stream);
+void launch_fill_level(const DevParams* P, uint32_t npass, uint32_t max_task, const uint32_t* level_shapes,
+                       uint32_t n_shapes, uint32_t* big_list, uint32_t* big_count, uint64_t* cost, uint16_t* arg,
+                       Counters* ctr, hipStream_t stream);
 
 void launch_zero_words(unsigned long long* p, uint32_t n, hipStream_t st);
 void launch_head_flags(const Geo& g, uint32_t a0, const uint64_t* cost, const uint16_t* arg, const uint32_t* axis_sizes,

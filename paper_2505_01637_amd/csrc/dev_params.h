@@ -12,10 +12,15 @@ constexpr uint64_t kLimit = 1ull << 62;      // finite costs stay below this
 constexpr int kMaxSizes = 256;
 constexpr int kMaxCombo = 256;               // n_levels ^ n_operands
 constexpr int kMaxRanks = 16;
+constexpr int kMaxSlots = 48;                // Move rewrites per Spec: operands * (levels-1) * 2 * 2
+constexpr int kMaxVariants = 32;
 
 enum : uint32_t { kKindM = 0, kKindE = 1, kKindF = 2 };
 enum : uint32_t { kRead = 0, kRmw = 1, kWrite = 2 };
 
+// A level assignment of the operands is handled as a "pack": 2 bits per operand,
+// operand 0 in the highest field.  pack <-> combo (the mixed-radix index used in
+// table offsets) are both kept because offsets need the latter.
 struct DevParams {
   // ---- geometry ----
   uint32_t kind, nops, nlv, NL;
@@ -34,18 +39,28 @@ struct DevParams {
   uint8_t dt_bit[5];
   uint8_t base_bf16[5];
   uint8_t access[5];
+  uint8_t pack_shift[4];     // bit position of operand i's level inside a pack
   uint32_t lvpow[5];         // combo stride of operand i
   // ---- target ----
   uint64_t cap[4];
-  uint32_t load[4][4][2], store[4][4][2];
   uint32_t convert, zero[4], s;
   uint32_t nmk, mk_kind[8], mk_lanes[8];
   uint64_t mk_cost[8];
+  // Move coefficient per element, [operand][src][dst][same|transposed]; load and/or store
+  // according to how the operand is accessed; 0 = the Move does not exist.
+  uint32_t mcoef[4][4][4][2];
+  // Move rewrites that can occur at all in this lattice, ascending id:
+  // operand | dst<<2 | transposed<<4 | convert<<5 | id<<16
+  uint32_t n_slots;
+  uint32_t slots[kMaxSlots];
+  // per (pack, variant): bit j set = the level/layout/dtype part of microkernel j's predicate holds
+  const uint8_t* mk_entry;   // device, [256][V]
   // ---- rewrite ids ----
   uint32_t move_base, tile_base, buf_id, maxs;
   // ---- operand-level combos ordered by rank (sum of operand levels) ----
   uint32_t nranks;
   uint16_t combo_by_rank[kMaxCombo];
+  uint8_t pack_by_rank[kMaxCombo];
   uint16_t rank_off[kMaxRanks + 2];
   // ---- tables a FUSED lattice reads ----
   const uint64_t* costM;

@@ -5,55 +5,44 @@
 // costs.  Here the table is filled bottom-up: all shapes of one dependency
 // level in one launch, every sub-Spec of another shape already final.
 //
-// Mapping (gfx950, wave64).  A workgroup owns one *unit*: one shape (b,m,k,n)
-// and one value of the passive level axis; a unit is closed under Moves.
-//   1. one thread per operand-level combo decides which entries fit their
-//      levels and the admissible ones are compacted, ordered by rank (sum of
-//      the operand levels), into a task list in LDS;
-//   2. entries that do not fit are streamed out as (INF, NONE);
-//   3. one thread per task evaluates the tile and bufferize rewrites, whose
+// Mapping (gfx950, wave64).  One wavefront owns one *unit*: one shape
+// (b,m,k,n) and one value of the passive level axis (the intermediate's level
+// of a fused Spec); a unit is closed under Moves, so waves never wait for each
+// other.  A workgroup = the waves of one shape, so that its writes form one
+// contiguous stretch of the table.  Per unit:
+//   1. lanes decide, per operand-level assignment, which entries fit their
+//      levels; the admissible ones are compacted, ordered by rank (sum of the
+//      operand levels), into a task list in LDS (most entries do not fit);
+//   2. entries that do not fit are streamed out as (INF, NONE), 16 bytes per
+//      lane and store;
+//   3. one lane per task evaluates the tile and bufferize rewrites, whose
 //      sub-Specs belong to other shapes or tables and are final: a tile
 //      sub-Spec sits at the same offset of a smaller shape's group, so
 //      consecutive lanes read consecutive addresses, several loads in flight
 //      per lane.  The best of them is parked in LDS;
-//   4. rank by rank, one thread per task evaluates the microkernels and the
+//   4. rank by rank, one lane per task evaluates the microkernels and the
 //      Moves (sub-Specs in the same unit at a lower rank: read from LDS), in
 //      id order, keeping the first strict minimum (= lowest id among ties),
 //      then takes the parked candidate if strictly lower (its ids are higher).
 //      Results go to LDS (for later ranks) and to the table.
-// Nothing is reduced across lanes, so the result cannot depend on timing.
+// A unit with more tasks than the LDS slice of a wave holds is appended to a
+// list and redone by a second launch with a whole workgroup per unit and a
+// slice sized for the largest possible unit.  Nothing is reduced across lanes and no
+// result depends on which wave handles a unit: the table is deterministic.
 #include <hip/hip_runtime.h>
+#include "compress.h"
 #include "dev_params.h"
 
 namespace mrl {
 
-__device__ __forceinline__ uint32_t lane_id() { return threadIdx.x & 63u; }
+constexpr int kBatch = 8;              // sub-Spec costs fetched together before they are compared
+constexpr uint32_t kSharedLds = 2048;  // Move cost table [convert][operand][src][dst][transposed], u64, per workgroup
+constexpr uint32_t kSmallCap = 256;    // tasks a wave's LDS slice holds in the first launch
+constexpr uint32_t kBigBlock = 1024;   // threads per deferred unit in the second launch
+constexpr uint32_t kBigGrid = 1024;    // workgroups of the second launch (they loop over the deferred units)
 
-// Exclusive prefix sum of one value per thread over the workgroup (T = 64 or 256).
-template <int T>
-__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* wave_tot, uint32_t* total) {
-  uint32_t incl = v;
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    uint32_t o = __shfl_up(incl, d, 64);
-    if ((int)lane_id() >= d) incl += o;
-  }
-  if (T == 64) {
-    *total = __shfl(incl, 63, 64);
-    return incl - v;
-  }
-  uint32_t w = threadIdx.x >> 6;
-  if (lane_id() == 63) wave_tot[w] = incl;
-  __syncthreads();
-  uint32_t base = 0, tot = 0;
-#pragma unroll
-  for (int i = 0; i < T / 64; i++) {
-    uint32_t t = wave_tot[i];
-    if ((uint32_t)i < w) base += t;
-    tot += t;
-  }
-  *total = tot;
-  return base + incl - v;
+__host__ __device__ inline uint32_t unit_lds_bytes(uint32_t cap) {
+  return (cap * 12u + 256u * 4u + 256u * 2u + (kMaxRanks + 2) * 4u + 16u * 4u + 15u) & ~15u;
 }
 
 struct Eval {
@@ -64,22 +53,31 @@ struct Eval {
 };
 
 __device__ __forceinline__ void consider(Eval& e, uint64_t cand, uint32_t id) {
-  e.n++;
   if (cand < e.best) { e.best = cand; e.arg = id; }
 }
 
-// a * sub + b, INF absorbing; anything reaching 2^62 raises the overflow flag.
-__device__ __forceinline__ uint64_t affine(Eval& e, uint64_t a, uint64_t sub, uint64_t b) {
+// a * sub + b with a < 2^32, sub < 2^62 (or INF, which is absorbing), b < 2^62.
+// Two 32x32+64 multiply-adds give the 96-bit product; reaching 2^62 raises the overflow flag.
+__device__ __forceinline__ uint64_t affine_mul(Eval& e, uint32_t a, uint64_t sub, uint64_t b) {
   if (sub == kInf) return kInf;
-  uint64_t lo = a * sub;
-  if (__umul64hi(a, sub) != 0 || lo >= kLimit || b >= kLimit || lo + b >= kLimit) { e.ovf = 1; return kInf; }
-  return lo + b;
+  const uint64_t lo = (uint64_t)a * (uint32_t)sub;
+  const uint64_t hi = (uint64_t)a * (uint32_t)(sub >> 32) + (lo >> 32);   // bits 32.. of the product
+  const uint64_t prod = (hi << 32) | (uint32_t)lo;
+  if ((hi >> 30) != 0 || prod + b >= kLimit) { e.ovf = 1; return kInf; }
+  return prod + b;
 }
 
-__device__ __forceinline__ uint64_t mul_checked(Eval& e, uint64_t a, uint64_t b) {
-  uint64_t lo = a * b;
-  if (__umul64hi(a, b) != 0 || lo >= kLimit) { e.ovf = 1; return kLimit; }
-  return lo;
+// sub + b, same conventions (b may be the sentinel kLimit for "coefficient * elements overflows").
+__device__ __forceinline__ uint64_t affine_add(Eval& e, uint64_t sub, uint64_t b) {
+  if (sub == kInf) return kInf;
+  if (b >= kLimit || sub + b >= kLimit) { e.ovf = 1; return kInf; }
+  return sub + b;
+}
+
+// a * b for operands below 2^62 and 2^33; kLimit if the product reaches 2^62.
+__device__ __forceinline__ uint64_t mul_or_limit(uint64_t a, uint64_t b) {
+  const uint64_t lo = a * b;
+  return (__umul64hi(a, b) != 0 || lo >= kLimit) ? kLimit : lo;
 }
 
 struct Shape {
@@ -102,25 +100,41 @@ __device__ __forceinline__ void load_shape(const DevParams* __restrict__ P, uint
   else { S.numel[0] = m * k; S.numel[1] = k * n; S.numel[2] = n; S.numel[3] = m * n; S.numel[4] = m * n; }
 }
 
-__device__ __forceinline__ void decode_levels(const DevParams* __restrict__ P, uint32_t combo, uint32_t lv[4]) {
-#pragma unroll
-  for (int i = 0; i < 4; i++) lv[i] = (uint32_t)i < P->nops ? (combo / P->lvpow[i]) % P->NL : 0u;
+__device__ __forceinline__ uint32_t level_of(const DevParams* __restrict__ P, uint32_t pack, int i) {
+  return (pack >> P->pack_shift[i]) & 3u;
 }
 
-// Bit v of the result: variant v of this combo fits every level's capacity.
+__device__ __forceinline__ uint32_t combo_of_pack(const DevParams* __restrict__ P, uint32_t pack) {
+  if (P->NL == 4) return pack;
+  uint32_t c = 0;
+#pragma unroll
+  for (int i = 0; i < 4; i++) if ((uint32_t)i < P->nops) c += level_of(P, pack, i) * P->lvpow[i];
+  return c;
+}
+
+__device__ __forceinline__ uint32_t pack_of_combo(const DevParams* __restrict__ P, uint32_t combo) {
+  if (P->NL == 4) return combo;
+  uint32_t p = 0;
+#pragma unroll
+  for (int i = 0; i < 4; i++) if ((uint32_t)i < P->nops) p |= ((combo / P->lvpow[i]) % P->NL) << P->pack_shift[i];
+  return p;
+}
+
+// Bit v of the result: variant v of this level assignment fits every level's capacity.
 __device__ __forceinline__ uint32_t admissible_mask(const DevParams* __restrict__ P, const Shape& S,
-                                                    const uint32_t lv[4], uint32_t pass) {
-  uint32_t ndtpat = 1u << P->ndt;
+                                                    uint32_t pack, uint32_t pass) {
+  const uint32_t ndtpat = 1u << P->ndt;
   uint32_t bits = 0;
   for (uint32_t dt = 0; dt < ndtpat; dt++) {
     uint64_t used[4] = {0, 0, 0, 0};
 #pragma unroll
     for (int i = 0; i < 4; i++) {
       if ((uint32_t)i >= P->nops) break;
-      uint32_t bf = P->dt_bit[i] != 0xFF ? (dt >> P->dt_bit[i]) & 1u : P->base_bf16[i];
-      uint64_t bytes = S.numel[i] * (bf ? 2u : 4u);
+      const uint32_t bf = P->dt_bit[i] != 0xFF ? (dt >> P->dt_bit[i]) & 1u : P->base_bf16[i];
+      const uint64_t bytes = S.numel[i] * (bf ? 2u : 4u);
+      const uint32_t lv = level_of(P, pack, i);
 #pragma unroll
-      for (int l = 0; l < 4; l++) used[l] += lv[i] == (uint32_t)l ? bytes : 0;
+      for (int l = 0; l < 4; l++) used[l] += lv == (uint32_t)l ? bytes : 0;
     }
     if (P->kind == kKindF) {
 #pragma unroll
@@ -136,33 +150,18 @@ __device__ __forceinline__ uint32_t admissible_mask(const DevParams* __restrict_
   return mask;
 }
 
-// Number of repetitions of microkernel j on this Spec, 0 if its predicate fails
-// (Section 2, Microkernel Selection; Figure 1 for BroadcastVecMultAdd).
-__device__ __forceinline__ uint64_t mk_reps(const DevParams* __restrict__ P, const Shape& S, uint32_t j,
-                                            const uint32_t lv[4], const uint32_t ly[4], const uint32_t bf[4]) {
-  uint64_t b = S.d[0], m = S.d[1], k = S.d[2], n = S.d[3];
-  uint32_t lanes = P->mk_lanes[j];
+// Shape part of microkernel j's predicate: number of repetitions, 0 if it fails
+// (Section 2, Microkernel Selection; Figure 1 for BroadcastVecMultAdd).  The
+// level/layout/dtype part is tabulated per entry (DevParams::mk_entry).
+__device__ __forceinline__ uint64_t mk_shape_reps(const DevParams* __restrict__ P, const Shape& S, uint32_t j) {
+  const uint64_t b = S.d[0], m = S.d[1], k = S.d[2], n = S.d[3];
+  const uint32_t lanes = P->mk_lanes[j];
   switch (P->mk_kind[j]) {
-    case 0:
-      if (P->kind != kKindM || b != 1 || m != 1 || k != 1 || n != 1) return 0;
-      if (lv[0] | lv[1] | lv[2] | bf[0] | bf[1] | bf[2]) return 0;
-      return 1;
-    case 1:
-      if (P->kind != kKindM || b != 1 || m != 1 || k != 1 || n % lanes) return 0;
-      if (lv[0] != 0 || lv[1] != 1 || lv[2] != 1 || (bf[0] | bf[1] | bf[2]) || ly[1] || ly[2]) return 0;
-      return n / lanes;
-    case 2:
-      if (P->kind != kKindM || b != 1 || m != 1 || n != 1 || k % lanes) return 0;
-      if (lv[0] != 1 || lv[1] != 1 || lv[2] != 0 || !bf[0] || !bf[1] || bf[2]) return 0;
-      if (P->lay_bit[1] != 0xFF && ly[1] != 1) return 0;
-      return k / lanes;
-    case 3:
-      if (P->kind != kKindE || m != 1 || n != 1 || (lv[0] | lv[1] | lv[2])) return 0;
-      return 1;
-    case 4:
-      if (P->kind != kKindE || m != 1 || n % lanes) return 0;
-      if (lv[0] != 1 || lv[1] != 1 || lv[2] != 1 || ly[0] || ly[2]) return 0;
-      return n / lanes;
+    case 0: return (b == 1 && m == 1 && k == 1 && n == 1) ? 1 : 0;
+    case 1: return (b == 1 && m == 1 && k == 1 && n % lanes == 0) ? n / lanes : 0;
+    case 2: return (b == 1 && m == 1 && n == 1 && k % lanes == 0) ? k / lanes : 0;
+    case 3: return (m == 1 && n == 1) ? 1 : 0;
+    case 4: return (m == 1 && n % lanes == 0) ? n / lanes : 0;
     default: return 0;
   }
 }
@@ -175,63 +174,229 @@ __device__ __forceinline__ void store_ones(void* p, uint32_t bytes) {
   else *reinterpret_cast<uint16_t*>(p) = (uint16_t)0xFFFFu;
 }
 
-constexpr int kTileBatch = 8;   // sub-Spec costs fetched together before they are compared
+// LDS of one unit.
+struct UnitLds {
+  uint64_t* t_cost;   // [cap] per task: best tile/bufferize candidate, then the final cost
+  uint32_t* t_spec;   // [cap] pack | variant<<8 | id<<16
+  uint32_t* c_mask;   // [256] by pack: admissible variants
+  uint16_t* c_base;   // [256] by pack: first task of the level assignment
+  uint32_t* r_off;    // [nranks+1] first task of the rank
+  uint32_t* wave_tot; // [16] scan scratch
+};
 
+__device__ __forceinline__ UnitLds carve(unsigned char* w, uint32_t cap) {
+  UnitLds L;
+  L.t_cost = reinterpret_cast<uint64_t*>(w);
+  L.t_spec = reinterpret_cast<uint32_t*>(L.t_cost + cap);
+  L.c_mask = L.t_spec + cap;
+  L.c_base = reinterpret_cast<uint16_t*>(L.c_mask + 256);
+  L.r_off = reinterpret_cast<uint32_t*>(L.c_base + 256);
+  L.wave_tot = L.r_off + kMaxRanks + 2;
+  return L;
+}
+
+// Synchronise the T threads that share a unit: one wave needs no s_barrier.
 template <int T>
-__global__ __launch_bounds__(T) void fill_level_kernel(const DevParams* __restrict__ P,
-                                                        const uint32_t* __restrict__ level_shapes,
-                                                        uint32_t n_units,
-                                                        uint64_t* __restrict__ cost,
-                                                        uint16_t* __restrict__ arg,
-                                                        Counters* __restrict__ ctr) {
-  extern __shared__ __align__(16) unsigned char smem[];
+__device__ __forceinline__ void unit_sync() {
+  if (T == 64) {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+  } else {
+    __syncthreads();
+  }
+}
+
+// Move cost per (convert, operand, src, dst, transposed) for this shape: coefficient * elements.
+__device__ __forceinline__ void build_move_costs(const DevParams* __restrict__ P, const Shape& S, uint64_t* bterm) {
+  for (uint32_t e = threadIdx.x; e < 256; e += blockDim.x) {
+    const uint32_t cv = e >> 7, i = (e >> 5) & 3u;
+    const uint32_t c = (&P->mcoef[0][0][0][0])[e & 127u];
+    const uint64_t n = i == 0 ? S.numel[0] : i == 1 ? S.numel[1] : i == 2 ? S.numel[2] : S.numel[3];
+    bterm[e] = c ? mul_or_limit((uint64_t)c + (cv ? P->convert : 0u), n) : 0;   // 0 = the Move does not exist
+  }
+}
+
+// Step 3 for task q: tile and bufferize candidates.
+__device__ __forceinline__ void task_tiles(const DevParams* __restrict__ P, const UnitLds& L, const Shape& S,
+                                           uint32_t shape, uint32_t pass, uint32_t q,
+                                           const uint64_t* __restrict__ cost, Eval& tot) {
+  const uint32_t V = P->V, npass = P->npass, NL = P->NL;
+  const uint32_t sp = L.t_spec[q];
+  const uint32_t pack = sp & 0xFFu, v = (sp >> 8) & 0xFFu;
+  const uint32_t off = (combo_of_pack(P, pack) * npass + pass) * V + v;
+  Eval e;
+  e.best = kInf; e.arg = kNone; e.n = 0; e.ovf = 0;
+#pragma unroll
+  for (int d = 0; d < 4; d++) {
+    if (!P->tile_dim_ok[d]) continue;
+    const uint32_t j = S.si[d];
+    const uint32_t q_end = P->tile_off[d][j + 1];
+    e.n += q_end - P->tile_off[d][j];
+    for (uint32_t q2 = P->tile_off[d][j]; q2 < q_end; q2 += kBatch) {
+      uint64_t sub[kBatch];
+      uint32_t jt[kBatch];
+#pragma unroll
+      for (int u = 0; u < kBatch; u++) {
+        const uint32_t qq = q2 + u < q_end ? q2 + u : q_end - 1;
+        jt[u] = P->tile_jt[qq];
+        sub[u] = cost[(uint64_t)(shape - (j - jt[u]) * P->shape_stride[d]) * P->G + off];
+      }
+#pragma unroll
+      for (int u = 0; u < kBatch; u++)
+        if (q2 + u < q_end)
+          consider(e, affine_mul(e, P->tile_trips[q2 + u], sub[u], P->s), P->tile_base + d * P->maxs + jt[u]);
+    }
+  }
+  // bufferize (FUSED): Matmul into the intermediate, then bias-add+ReLU out of it
+  if (P->kind == kKindF) {
+    const uint32_t l0 = level_of(P, pack, 0), l1 = level_of(P, pack, 1), l2 = level_of(P, pack, 2), l3 = level_of(P, pack, 3);
+    const uint32_t y0 = P->lay_bit[0] != 0xFF ? (v >> P->lay_bit[0]) & 1u : 0u;
+    const uint32_t y1 = P->lay_bit[1] != 0xFF ? (v >> P->lay_bit[1]) & 1u : 0u;
+    const uint32_t y3 = P->lay_bit[3] != 0xFF ? (v >> P->lay_bit[3]) & 1u : 0u;
+    const uint32_t xm = ((l0 * NL + l1) * NL + pass) * P->VM +
+                        (P->layM[0] != 0xFF ? y0 << P->layM[0] : 0u) + (P->layM[1] != 0xFF ? y1 << P->layM[1] : 0u);
+    const uint32_t xe = ((pass * NL + l2) * NL + l3) * P->VE + (P->layE[2] != 0xFF ? y3 << P->layE[2] : 0u);
+    const uint64_t cm = P->costM[(uint64_t)shape * P->GM + xm];
+    const uint64_t ce = P->costE[(uint64_t)(S.si[1] * P->nszE_n + S.si[3]) * P->GE + xe];
+    uint64_t cand = kInf;
+    if (cm != kInf && ce != kInf) {
+      const uint64_t z = mul_or_limit(P->zero[pass], S.numel[4]);
+      const uint64_t sum = z + cm;          // each term <= 2^62: no wrap
+      if (z >= kLimit || sum >= kLimit || sum + ce >= kLimit) e.ovf = 1; else cand = sum + ce;
+    }
+    consider(e, cand, P->buf_id);
+    e.n += 1;
+  }
+  L.t_cost[q] = e.best;
+  L.t_spec[q] = sp | e.arg << 16;
+  tot.n += e.n;
+  tot.ovf |= e.ovf;
+}
+
+// Step 4 for task q (all sub-Specs of lower rank are final in LDS).
+__device__ __forceinline__ void task_rank(const DevParams* __restrict__ P, const UnitLds& L, const uint64_t* bterm,
+                                          const Shape& S, uint64_t group, uint32_t pass, uint32_t q, uint32_t mk_shape,
+                                          uint64_t* __restrict__ cost, uint16_t* __restrict__ arg, Eval& tot) {
+  const uint32_t V = P->V, n_slots = P->n_slots;
+  const uint32_t sp = L.t_spec[q];
+  const uint32_t pack = sp & 0xFFu, v = (sp >> 8) & 0xFFu;
+  Eval e;
+  e.best = kInf; e.arg = kNone; e.n = 0; e.ovf = 0;
+
+  // A. select(microkernel)
+  if (mk_shape) {
+    for (uint32_t mm = P->mk_entry[pack * V + v] & mk_shape; mm; mm &= mm - 1) {
+      const uint32_t j = (uint32_t)__ffs(mm) - 1u;
+      const uint64_t k = mul_or_limit(P->mk_cost[j], mk_shape_reps(P, S, j));
+      if (k >= kLimit) e.ovf = 1; else consider(e, k, j);
+      e.n++;
+    }
+  }
+
+  // B. Move an operand to a strictly lower level: kBatch LDS lookups in flight
+  for (uint32_t s0 = 0; s0 < n_slots; s0 += kBatch) {
+    uint64_t sub[kBatch], b[kBatch];
+    uint32_t id[kBatch];
+    bool ok[kBatch];
+#pragma unroll
+    for (int u = 0; u < kBatch; u++) {
+      const uint32_t sl = P->slots[s0 + u < n_slots ? s0 + u : n_slots - 1];
+      const uint32_t i = sl & 3u, dst = (sl >> 2) & 3u, x = (sl >> 4) & 1u, cv = (sl >> 5) & 1u;
+      const uint32_t sh = (sl >> 6) & 7u, layb = (sl >> 9) & 7u, dtb = (sl >> 12) & 7u;
+      const uint32_t src = (pack >> sh) & 3u;
+      const uint32_t ci = ((i * 4 + src) * 4 + dst) * 2 + x;
+      const bool valid = s0 + u < n_slots && dst < src && (!cv || ((v >> dtb) & 1u));
+      b[u] = bterm[cv * 128 + ci];
+      const uint32_t pack2 = valid ? pack - ((src - dst) << sh) : pack;
+      uint32_t v2 = v ^ (x << layb);
+      if (cv) v2 &= ~(1u << dtb);
+      const uint32_t m2 = L.c_mask[pack2];
+      const bool has = valid && ((m2 >> v2) & 1u);
+      const uint32_t idx = has ? L.c_base[pack2] + __popc(m2 & ((1u << v2) - 1u)) : q;
+      const uint64_t t = L.t_cost[idx];
+      sub[u] = has ? t : kInf;
+      id[u] = sl >> 16;
+      ok[u] = valid;
+    }
+#pragma unroll
+    for (int u = 0; u < kBatch; u++)
+      if (ok[u] && b[u] != 0) { consider(e, affine_add(e, sub[u], b[u]), id[u]); e.n++; }
+  }
+
+  // C, D. tiles and bufferize, evaluated in step 3
+  const uint64_t tb = L.t_cost[q];
+  if (tb < e.best) { e.best = tb; e.arg = sp >> 16; }
+
+  const uint32_t off = (combo_of_pack(P, pack) * P->npass + pass) * V + v;
+  L.t_cost[q] = e.best;
+  cost[group + off] = e.best;
+  arg[group + off] = (uint16_t)e.arg;
+  tot.n += e.n;
+  tot.ovf |= e.ovf;
+}
+
+// One unit handled by T threads (T = 64: a wave of the first launch; T = kBigBlock: the second launch).
+template <int T, bool BIG>
+__device__ __forceinline__ void solve_unit(const DevParams* __restrict__ P, const uint64_t* bterm, const UnitLds& L,
+                                           uint32_t cap, const Shape& S, uint32_t shape, uint32_t pass,
+                                           uint32_t* __restrict__ big_list, uint32_t* __restrict__ big_count,
+                                           uint64_t* __restrict__ cost, uint16_t* __restrict__ arg,
+                                           Eval& tot, uint32_t& n_adm) {
+  const uint32_t tid = T == 64 ? (threadIdx.x & 63u) : threadIdx.x;
+  const uint32_t lane = threadIdx.x & 63u;
   const uint32_t ncombo = P->ncombo, V = P->V, npass = P->npass;
-  const uint32_t max_task = ncombo * V;
-  uint64_t* t_cost = reinterpret_cast<uint64_t*>(smem);                  // [max_task] per task: best tile/bufferize
-                                                                          //   candidate, then the final cost
-  uint32_t* t_spec = reinterpret_cast<uint32_t*>(t_cost + max_task);     // [max_task] combo | variant<<8 | id<<16
-  uint32_t* c_mask = t_spec + max_task;                                   // [ncombo] admissible variants
-  uint32_t* c_base = c_mask + ncombo;                                     // [ncombo] first task of the combo
-  uint32_t* r_off = c_base + ncombo;                                      // [nranks+1] first task of the rank
-  uint32_t* wave_tot = r_off + kMaxRanks + 2;                             // [4]
-
-  const uint32_t unit = blockIdx.x;
-  if (unit >= n_units) return;
-  const uint32_t shape = level_shapes[unit / npass];
-  const uint32_t pass = unit % npass;
-  const uint32_t tid = threadIdx.x;
-
-  Shape S;
-  load_shape(P, shape, S);
   const uint64_t group = (uint64_t)shape * P->G;
 
   // ---- 1. admissibility, compaction in rank order ----
-  uint32_t my_mask = 0, my_combo = 0;
-  if (tid < ncombo) {
-    my_combo = P->combo_by_rank[tid];
-    uint32_t lv[4];
-    decode_levels(P, my_combo, lv);
-    my_mask = admissible_mask(P, S, lv, pass);
-    c_mask[my_combo] = my_mask;
+  uint32_t n_task = 0;
+  for (uint32_t p0 = 0; p0 < ncombo; p0 += T) {
+    const uint32_t pos = p0 + tid;
+    uint32_t mask = 0, pack = 0;
+    if (pos < ncombo) {
+      pack = P->pack_by_rank[pos];
+      mask = admissible_mask(P, S, pack, pass);
+      L.c_mask[pack] = mask;
+    }
+    const uint32_t cnt = __popc(mask);
+    uint32_t incl = cnt;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const uint32_t o = __shfl_up(incl, d, 64);
+      if ((int)lane >= d) incl += o;
+    }
+    uint32_t base = n_task + incl - cnt;
+    if (T == 64) {
+      n_task += __shfl(incl, 63, 64);
+    } else {
+      const uint32_t w = threadIdx.x >> 6;
+      if (lane == 63) L.wave_tot[w] = incl;
+      __syncthreads();
+      for (uint32_t i = 0; i < T / 64; i++) {
+        const uint32_t t = L.wave_tot[i];
+        if (i < w) base += t;
+        n_task += t;
+      }
+      __syncthreads();
+    }
+    if (pos < ncombo) {
+      L.c_base[pack] = (uint16_t)base;
+      if (base + cnt <= cap) {
+        uint32_t q = base;
+        for (uint32_t m = mask; m; m &= m - 1) L.t_spec[q++] = pack | ((uint32_t)__ffs(m) - 1u) << 8;
+      }
+    }
   }
-  uint32_t n_task;
-  uint32_t my_base = block_exclusive_scan<T>(__popc(my_mask), wave_tot, &n_task);
-  if (tid < ncombo) {
-    c_base[my_combo] = my_base;
-    uint32_t q = my_base;
-    for (uint32_t m = my_mask; m; m &= m - 1) t_spec[q++] = my_combo | ((uint32_t)__ffs(m) - 1u) << 8;
-    for (uint32_t r = 0; r < P->nranks; r++)
-      if (tid == P->rank_off[r]) r_off[r] = my_base;
-  }
-  if (tid == 0) r_off[P->nranks] = n_task;
-  __syncthreads();
+  unit_sync<T>();
+  if (tid <= P->nranks) L.r_off[tid] = tid == P->nranks ? n_task : L.c_base[P->pack_by_rank[P->rank_off[tid]]];
+  unit_sync<T>();
 
-  // ---- 2. entries that do not fit: (INF, NONE), written in chunks of up to 16 bytes ----
-  {
+  if (!BIG) {
+    n_adm += tid == 0 ? n_task : 0;
+    // ---- 2. entries that do not fit: (INF, NONE), written in chunks of up to 16 bytes ----
     const uint32_t cch = V < 2 ? V : 2, cper = V / cch;        // cost: entries per chunk, chunks per combo
     for (uint32_t c = tid; c < ncombo * cper; c += T) {
       const uint32_t combo = c / cper, v0 = (c - combo * cper) * cch;
-      const uint32_t bits = (c_mask[combo] >> v0) & ((1u << cch) - 1u);
+      const uint32_t bits = (L.c_mask[pack_of_combo(P, combo)] >> v0) & ((1u << cch) - 1u);
       uint64_t* p = cost + group + (uint64_t)(combo * npass + pass) * V + v0;
       if (bits == 0) store_ones(p, 8 * cch);
       else for (uint32_t u = 0; u < cch; u++) if (!((bits >> u) & 1u)) p[u] = kInf;
@@ -239,152 +404,106 @@ __global__ __launch_bounds__(T) void fill_level_kernel(const DevParams* __restri
     const uint32_t ach = V < 8 ? V : 8, aper = V / ach;        // argmin: likewise
     for (uint32_t c = tid; c < ncombo * aper; c += T) {
       const uint32_t combo = c / aper, v0 = (c - combo * aper) * ach;
-      const uint32_t bits = (c_mask[combo] >> v0) & ((1u << ach) - 1u);
+      const uint32_t bits = (L.c_mask[pack_of_combo(P, combo)] >> v0) & ((1u << ach) - 1u);
       uint16_t* p = arg + group + (uint64_t)(combo * npass + pass) * V + v0;
       if (bits == 0) store_ones(p, 2 * ach);
       else for (uint32_t u = 0; u < ach; u++) if (!((bits >> u) & 1u)) p[u] = (uint16_t)kNone;
     }
+    if (n_task > cap) {          // too many tasks for this wave's LDS slice: leave it to the second launch
+      if (tid == 0) big_list[atomicAdd(big_count, 1u)] = shape * npass + pass;
+      return;
+    }
   }
 
-  Eval tot;
-  tot.n = 0; tot.ovf = 0;
-  const uint32_t NL = P->NL;
+  // ---- 3. tile and bufferize candidates of every task ----
+  for (uint32_t q = tid; q < n_task; q += T) task_tiles(P, L, S, shape, pass, q, cost, tot);
+  unit_sync<T>();
 
-  // ---- 3. tile and bufferize candidates of every task (sub-Specs of other shapes / tables:
-  //         final already, no ordering needed).  kTileBatch loads are in flight per thread. ----
-  for (uint32_t q = tid; q < n_task; q += T) {
-    const uint32_t sp = t_spec[q];
-    const uint32_t combo = sp & 0xFFu, v = (sp >> 8) & 0xFFu;
-    const uint32_t off = (combo * npass + pass) * V + v;
-    Eval e;
-    e.best = kInf; e.arg = kNone; e.n = 0; e.ovf = 0;
-#pragma unroll
-    for (int d = 0; d < 4; d++) {
-      if (!P->tile_dim_ok[d]) continue;
-      const uint32_t j = S.si[d];
-      const uint32_t q_end = P->tile_off[d][j + 1];
-      for (uint32_t q2 = P->tile_off[d][j]; q2 < q_end; q2 += kTileBatch) {
-        uint64_t sub[kTileBatch];
-        uint32_t jt[kTileBatch];
-#pragma unroll
-        for (int u = 0; u < kTileBatch; u++) {
-          const uint32_t qq = q2 + u < q_end ? q2 + u : q_end - 1;
-          jt[u] = P->tile_jt[qq];
-          sub[u] = cost[(uint64_t)(shape - (j - jt[u]) * P->shape_stride[d]) * P->G + off];
-        }
-#pragma unroll
-        for (int u = 0; u < kTileBatch; u++)
-          if (q2 + u < q_end)
-            consider(e, affine(e, P->tile_trips[q2 + u], sub[u], P->s), P->tile_base + d * P->maxs + jt[u]);
-      }
-    }
-    // bufferize (FUSED): Matmul into the intermediate, then bias-add+ReLU out of it
-    if (P->kind == kKindF) {
-      uint32_t lv[4];
-      decode_levels(P, combo, lv);
-      const uint32_t y0 = P->lay_bit[0] != 0xFF ? (v >> P->lay_bit[0]) & 1u : 0u;
-      const uint32_t y1 = P->lay_bit[1] != 0xFF ? (v >> P->lay_bit[1]) & 1u : 0u;
-      const uint32_t y3 = P->lay_bit[3] != 0xFF ? (v >> P->lay_bit[3]) & 1u : 0u;
-      const uint32_t xm = ((lv[0] * NL + lv[1]) * NL + pass) * P->VM +
-                          (P->layM[0] != 0xFF ? y0 << P->layM[0] : 0u) + (P->layM[1] != 0xFF ? y1 << P->layM[1] : 0u);
-      const uint32_t xe = ((pass * NL + lv[2]) * NL + lv[3]) * P->VE + (P->layE[2] != 0xFF ? y3 << P->layE[2] : 0u);
-      const uint64_t cm = P->costM[(uint64_t)shape * P->GM + xm];
-      const uint64_t ce = P->costE[(uint64_t)(S.si[1] * P->nszE_n + S.si[3]) * P->GE + xe];
-      uint64_t cand = kInf;
-      if (cm != kInf && ce != kInf) {
-        const uint64_t z = mul_checked(e, P->zero[pass], S.numel[4]);
-        const uint64_t sum = z + cm;          // each term < 2^62: no wrap
-        if (sum >= kLimit || sum + ce >= kLimit) e.ovf = 1; else cand = sum + ce;
-      }
-      consider(e, cand, P->buf_id);
-    }
-    t_cost[q] = e.best;
-    t_spec[q] = sp | e.arg << 16;
-    tot.n += e.n;
-    tot.ovf |= e.ovf;
-  }
-  __syncthreads();
+  // microkernels whose shape predicate holds for this shape (uniform)
+  uint32_t mk_shape = 0;
+  for (uint32_t j = 0; j < P->nmk; j++) mk_shape |= (mk_shape_reps(P, S, j) ? 1u : 0u) << j;
 
-  // ---- 4. rank by rank: microkernels, Moves (sub-Specs of lower rank, in LDS), then the
-  //         stored tile/bufferize candidate, whose ids are higher: it wins only if strictly lower ----
+  // ---- 4. rank by rank ----
   for (uint32_t r = 0; r < P->nranks; r++) {
-    const uint32_t t0 = r_off[r], t1 = r_off[r + 1];
+    const uint32_t t0 = L.r_off[r], t1 = L.r_off[r + 1];
     if (t0 == t1) continue;
-    for (uint32_t q = t0 + tid; q < t1; q += T) {
-      const uint32_t sp = t_spec[q];
-      const uint32_t combo = sp & 0xFFu, v = (sp >> 8) & 0xFFu;
-      uint32_t lv[4], ly[4], bf[4];
-      decode_levels(P, combo, lv);
-#pragma unroll
-      for (int i = 0; i < 4; i++) {
-        ly[i] = P->lay_bit[i] != 0xFF ? (v >> P->lay_bit[i]) & 1u : 0u;
-        bf[i] = P->dt_bit[i] != 0xFF ? (v >> P->dt_bit[i]) & 1u : P->base_bf16[i];
-      }
-      Eval e;
-      e.best = kInf; e.arg = kNone; e.n = 0; e.ovf = 0;
-
-      // A. select(microkernel)
-      for (uint32_t j = 0; j < P->nmk; j++) {
-        uint64_t reps = mk_reps(P, S, j, lv, ly, bf);
-        if (reps) consider(e, affine(e, 0, 0, mul_checked(e, P->mk_cost[j], reps)), j);
-      }
-
-      // B. Move operand i to a strictly lower level
-#pragma unroll
-      for (int i = 0; i < 4; i++) {
-        if ((uint32_t)i >= P->nops) break;
-        const uint32_t src = lv[i], acc = P->access[i];
-        for (uint32_t dst = 0; dst < src; dst++)
-          for (uint32_t x = 0; x < 2; x++)
-            for (uint32_t cv = 0; cv < 2; cv++) {
-              if (x && P->lay_bit[i] == 0xFF) continue;
-              if (cv && !(P->dt_bit[i] != 0xFF && bf[i] && acc == kRead)) continue;
-              uint64_t coef = 0;
-              if (acc != kWrite) { uint32_t c = P->load[src][dst][x]; if (!c) continue; coef += c; }
-              if (acc != kRead) { uint32_t c = P->store[dst][src][x]; if (!c) continue; coef += c; }
-              if (cv) coef += P->convert;
-              const uint32_t combo2 = combo - (src - dst) * P->lvpow[i];
-              uint32_t v2 = v;
-              if (x) v2 ^= 1u << P->lay_bit[i];
-              if (cv) v2 &= ~(1u << P->dt_bit[i]);
-              const uint32_t m2 = c_mask[combo2];
-              uint64_t sub = kInf;
-              if ((m2 >> v2) & 1u) sub = t_cost[c_base[combo2] + __popc(m2 & ((1u << v2) - 1u))];
-              const uint32_t id = P->move_base + ((i * (NL - 1) + dst) * 2 + x) * 2 + cv;
-              consider(e, affine(e, 1, sub, mul_checked(e, coef, S.numel[i])), id);
-            }
-      }
-
-      // C, D. tiles and bufferize, evaluated above
-      const uint64_t tb = t_cost[q];
-      if (tb < e.best) { e.best = tb; e.arg = sp >> 16; }
-
-      const uint32_t off = (combo * npass + pass) * V + v;
-      t_cost[q] = e.best;
-      cost[group + off] = e.best;
-      arg[group + off] = (uint16_t)e.arg;
-      tot.n += e.n;
-      tot.ovf |= e.ovf;
-    }
-    __syncthreads();
+    for (uint32_t q = t0 + tid; q < t1; q += T) task_rank(P, L, bterm, S, group, pass, q, mk_shape, cost, arg, tot);
+    unit_sync<T>();
   }
+}
 
-  // ---- 5. counters (integer sums: order-independent) ----
-  uint32_t n = tot.n;
+__device__ __forceinline__ void flush_counters(Counters* __restrict__ ctr, const Eval& tot, uint32_t n_adm) {
+  uint32_t n_rw = tot.n;
 #pragma unroll
-  for (int d = 32; d > 0; d >>= 1) n += __shfl_down(n, d, 64);
-  if (lane_id() == 0 && n) atomicAdd(&ctr->n_rewrites, (unsigned long long)n);
-  if (tid == 0 && n_task) atomicAdd(&ctr->n_admissible, (unsigned long long)n_task);
+  for (int d = 32; d > 0; d >>= 1) n_rw += __shfl_down(n_rw, d, 64);
+  if ((threadIdx.x & 63u) == 0) {
+    if (n_rw) atomicAdd(&ctr->n_rewrites, (unsigned long long)n_rw);
+    if (n_adm) atomicAdd(&ctr->n_admissible, (unsigned long long)n_adm);
+  }
   if (tot.ovf) atomicOr(&ctr->overflow, 1u);
 }
 
-void launch_fill_level(int block, const DevParams* P, const uint32_t* level_shapes, uint32_t n_units,
-                       uint64_t* cost, uint16_t* arg, Counters* ctr, size_t lds_bytes, hipStream_t stream) {
-  if (n_units == 0) return;
-  if (block == 64)
-    hipLaunchKernelGGL(fill_level_kernel<64>, dim3(n_units), dim3(64), lds_bytes, stream, P, level_shapes, n_units, cost, arg, ctr);
-  else
-    hipLaunchKernelGGL(fill_level_kernel<256>, dim3(n_units), dim3(256), lds_bytes, stream, P, level_shapes, n_units, cost, arg, ctr);
+// First launch of a level: workgroup = shape, wave = value of the passive level axis.
+__global__ __launch_bounds__(256) void fill_kernel(const DevParams* __restrict__ P,
+                                                   const uint32_t* __restrict__ level_shapes,
+                                                   uint32_t* __restrict__ big_list, uint32_t* __restrict__ big_count,
+                                                   uint32_t cap, uint64_t* __restrict__ cost,
+                                                   uint16_t* __restrict__ arg, Counters* __restrict__ ctr) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  uint64_t* bterm = reinterpret_cast<uint64_t*>(smem);
+  const uint32_t shape = level_shapes[blockIdx.x];
+  Shape S;
+  load_shape(P, shape, S);
+  build_move_costs(P, S, bterm);
+  __syncthreads();
+  const uint32_t wave = threadIdx.x >> 6;
+  const UnitLds L = carve(smem + kSharedLds + wave * unit_lds_bytes(cap), cap);
+  Eval tot;
+  tot.n = 0; tot.ovf = 0;
+  uint32_t n_adm = 0;
+  solve_unit<64, false>(P, bterm, L, cap, S, shape, wave, big_list, big_count, cost, arg, tot, n_adm);
+  flush_counters(ctr, tot, n_adm);
+}
+
+// Second launch of a level: the deferred units, one workgroup of kBigBlock threads each.
+__global__ __launch_bounds__(kBigBlock) void fill_big_kernel(const DevParams* __restrict__ P,
+                                                             uint32_t* __restrict__ big_list,
+                                                             uint32_t* __restrict__ big_count, uint32_t cap,
+                                                             uint64_t* __restrict__ cost, uint16_t* __restrict__ arg,
+                                                             Counters* __restrict__ ctr) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  uint64_t* bterm = reinterpret_cast<uint64_t*>(smem);
+  const UnitLds L = carve(smem + kSharedLds, cap);
+  Eval tot;
+  tot.n = 0; tot.ovf = 0;
+  uint32_t n_adm = 0;
+  const uint32_t n_units = *big_count;
+  for (uint32_t u = blockIdx.x; u < n_units; u += gridDim.x) {
+    const uint32_t unit = big_list[u];
+    const uint32_t shape = unit / P->npass, pass = unit % P->npass;
+    Shape S;
+    load_shape(P, shape, S);
+    __syncthreads();
+    build_move_costs(P, S, bterm);
+    __syncthreads();
+    solve_unit<kBigBlock, true>(P, bterm, L, cap, S, shape, pass, big_list, big_count, cost, arg, tot, n_adm);
+  }
+  flush_counters(ctr, tot, n_adm);
+}
+
+// One dependency level: every unit by the first kernel, then the units it deferred.
+void launch_fill_level(const DevParams* P, uint32_t npass, uint32_t max_task, const uint32_t* level_shapes,
+                       uint32_t n_shapes, uint32_t* big_list, uint32_t* big_count, uint64_t* cost, uint16_t* arg,
+                       Counters* ctr, hipStream_t stream) {
+  if (n_shapes == 0) return;
+  const uint32_t small_cap = max_task < kSmallCap ? max_task : kSmallCap;
+  hipLaunchKernelGGL(fill_kernel, dim3(n_shapes), dim3(64 * npass), kSharedLds + npass * unit_lds_bytes(small_cap),
+                     stream, P, level_shapes, big_list, big_count, small_cap, cost, arg, ctr);
+  if (max_task > small_cap) {
+    const uint32_t units = n_shapes * npass;
+    hipLaunchKernelGGL(fill_big_kernel, dim3(units < kBigGrid ? units : kBigGrid), dim3(kBigBlock),
+                       kSharedLds + unit_lds_bytes(max_task), stream, P, big_list, big_count, max_task, cost, arg, ctr);
+  }
 }
 
 }  // namespace mrl

@@ -162,7 +162,10 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
     P.pack_shift[i] = (uint8_t)(2 * (P.nops - 1 - i));
   }
   P.V = 1u << (P.nlay + P.ndt);
-  if (P.V > 32) return fail(MRL_E_INVAL, "too many layout/dtype bits");
+  P.log2V = P.nlay + P.ndt;
+  P.npass_shift = P.npass == 1 ? 0 : P.npass == 2 ? 1 : P.npass == 4 ? 2 : 0xFF;
+  P.level_bits = P.NL == 1 ? 0 : P.NL == 2 ? 1 : P.NL == 4 ? 2 : 0xFF;
+  if (P.V > 16) return fail(MRL_E_INVAL, "too many layout/dtype bits");
   {
     uint32_t axis = 4 + P.nlv, seen_l = 0, seen_d = 0;
     for (uint32_t i = 0; i < P.nops; i++)
@@ -283,6 +286,9 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
       for (uint32_t op = 0; op < P.nops; op++) pack |= ((combo / P.lvpow[op]) % P.NL) << P.pack_shift[op];
       P.combo_by_rank[i] = (uint16_t)combo;
       P.pack_by_rank[i] = (uint8_t)pack;
+      uint32_t info = pack;
+      for (uint32_t op = 0; op < P.nops; op++) info |= 1u << (8 + 4 * ((combo / P.lvpow[op]) % P.NL) + op);
+      P.pos_info[i] = info;
     }
   }
 
@@ -462,7 +468,7 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
   HIP_TRY(hipEventRecord(ev[0], st));
   const uint32_t n_lev = (uint32_t)c.level_off.size() - 1;
   for (uint32_t l = 0; l < n_lev; l++) {
-    launch_fill_level(d_P, P.npass, c.max_task, d_level_shapes + c.level_off[l], c.level_off[l + 1] - c.level_off[l],
+    launch_fill_level(d_P, P.npass, P.G, c.max_task, d_level_shapes + c.level_off[l], c.level_off[l + 1] - c.level_off[l],
                       d_big_list + (size_t)c.level_off[l] * P.npass, d_big_count + l, tab->d_cost, tab->d_arg, d_ctr, st);
   }
   HIP_TRY(hipGetLastError());

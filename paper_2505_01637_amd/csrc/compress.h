@@ -13,7 +13,7 @@ struct Geo {
   uint32_t ext[16], stride[16];
 };
 
-void launch_fill_level(const DevParams* P, uint32_t npass, uint32_t max_task, const uint32_t* level_shapes,
+void launch_fill_level(const DevParams* P, uint32_t npass, uint32_t G, uint32_t max_task, const uint32_t* level_shapes,
                        uint32_t n_shapes, uint32_t* big_list, uint32_t* big_count, uint64_t* cost, uint16_t* arg,
                        Counters* ctr, hipStream_t stream);
 

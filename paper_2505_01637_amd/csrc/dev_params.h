@@ -61,6 +61,11 @@ struct DevParams {
   uint32_t nranks;
   uint16_t combo_by_rank[kMaxCombo];
   uint8_t pack_by_rank[kMaxCombo];
+  // per rank-major position: pack | (operands resident in level l, one nibble per level) << 8
+  uint32_t pos_info[kMaxCombo];
+  uint32_t log2V;            // V = 1 << log2V
+  uint32_t npass_shift;      // npass = 1 << npass_shift, or 0xFF if npass is not a power of two
+  uint32_t level_bits;       // NL = 1 << level_bits, or 0xFF if NL is not a power of two
   uint16_t rank_off[kMaxRanks + 2];
   // ---- tables a FUSED lattice reads ----
   const uint64_t* costM;

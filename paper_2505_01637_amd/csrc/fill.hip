@@ -5,14 +5,13 @@
 // costs.  Here the table is filled bottom-up: all shapes of one dependency
 // level in one launch, every sub-Spec of another shape already final.
 //
-// Mapping (gfx950, wave64).  One wavefront owns one *unit*: one shape
-// (b,m,k,n) and one value of the passive level axis (the intermediate's level
-// of a fused Spec); a unit is closed under Moves, so waves never wait for each
-// other.  A workgroup = the waves of one shape, so that its writes form one
-// contiguous stretch of the table.  Per unit:
-//   1. lanes decide, per operand-level assignment, which entries fit their
-//      levels; the admissible ones are compacted, ordered by rank (sum of the
-//      operand levels), into a task list in LDS (most entries do not fit);
+// Mapping (gfx950, wave64).  One wavefront owns one shape (b,m,k,n): all its
+// level / layout / dtype entries, which is a set closed under Moves, so waves
+// never wait for each other and the wave's writes are one contiguous stretch
+// of the table.  Per shape:
+//   1. lanes decide, per level assignment, which entries fit their levels;
+//      the admissible ones are compacted, ordered by rank (sum of the operand
+//      levels), into a task list in LDS (most entries do not fit);
 //   2. entries that do not fit are streamed out as (INF, NONE), 16 bytes per
 //      lane and store;
 //   3. one lane per task evaluates the tile and bufferize rewrites, whose
@@ -21,14 +20,16 @@
 //      consecutive lanes read consecutive addresses, several loads in flight
 //      per lane.  The best of them is parked in LDS;
 //   4. rank by rank, one lane per task evaluates the microkernels and the
-//      Moves (sub-Specs in the same unit at a lower rank: read from LDS), in
+//      Moves (sub-Specs of the same shape at a lower rank: read from LDS), in
 //      id order, keeping the first strict minimum (= lowest id among ties),
 //      then takes the parked candidate if strictly lower (its ids are higher).
 //      Results go to LDS (for later ranks) and to the table.
-// A unit with more tasks than the LDS slice of a wave holds is appended to a
-// list and redone by a second launch with a whole workgroup per unit and a
-// slice sized for the largest possible unit.  Nothing is reduced across lanes and no
-// result depends on which wave handles a unit: the table is deterministic.
+// A shape with more tasks than the wave's LDS slice holds is appended to a
+// list, one item per value of the passive level axis (the intermediate's level
+// of a fused Spec: such slices are independent), and redone by a second launch
+// with a whole workgroup per item and a slice sized for the largest possible
+// item.  Nothing is reduced across lanes and no result depends on which wave
+// handles a shape: the table is deterministic.
 #include <hip/hip_runtime.h>
 #include "compress.h"
 #include "dev_params.h"
@@ -37,13 +38,10 @@ namespace mrl {
 
 constexpr int kBatch = 8;              // sub-Spec costs fetched together before they are compared
 constexpr uint32_t kSharedLds = 2048;  // Move cost table [convert][operand][src][dst][transposed], u64, per workgroup
-constexpr uint32_t kSmallCap = 256;    // tasks a wave's LDS slice holds in the first launch
-constexpr uint32_t kBigBlock = 1024;   // threads per deferred unit in the second launch
+constexpr uint32_t kSmallCap = 512;    // tasks a wave's LDS slice holds in the first launch
+constexpr uint32_t kBigBlock = 512;    // threads per deferred item in the second launch
 constexpr uint32_t kBigGrid = 1024;    // workgroups of the second launch (they loop over the deferred units)
 
-__host__ __device__ inline uint32_t unit_lds_bytes(uint32_t cap) {
-  return (cap * 12u + 256u * 4u + 256u * 2u + (kMaxRanks + 2) * 4u + 16u * 4u + 15u) & ~15u;
-}
 
 struct Eval {
   uint64_t best;
@@ -115,35 +113,53 @@ __device__ __forceinline__ uint32_t combo_of_pack(const DevParams* __restrict__ 
 __device__ __forceinline__ uint32_t pack_of_combo(const DevParams* __restrict__ P, uint32_t combo) {
   if (P->NL == 4) return combo;
   uint32_t p = 0;
+  if (P->level_bits != 0xFF) {
 #pragma unroll
-  for (int i = 0; i < 4; i++) if ((uint32_t)i < P->nops) p |= ((combo / P->lvpow[i]) % P->NL) << P->pack_shift[i];
+    for (int i = 0; i < 4; i++)
+      if ((uint32_t)i < P->nops) p |= ((combo >> (P->level_bits * (P->nops - 1 - i))) & (P->NL - 1)) << P->pack_shift[i];
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; i++) if ((uint32_t)i < P->nops) p |= ((combo / P->lvpow[i]) % P->NL) << P->pack_shift[i];
+  }
   return p;
 }
 
-// Bit v of the result: variant v of this level assignment fits every level's capacity.
-__device__ __forceinline__ uint32_t admissible_mask(const DevParams* __restrict__ P, const Shape& S,
-                                                    uint32_t pack, uint32_t pass) {
-  const uint32_t ndtpat = 1u << P->ndt;
-  uint32_t bits = 0;
-  for (uint32_t dt = 0; dt < ndtpat; dt++) {
-    uint64_t used[4] = {0, 0, 0, 0};
+// fit[dt * 4 + l], bit s: the tensors of subset s (operands 0..3, bit 4 = the fused Spec's
+// intermediate) together fit level l when the dtype bits are dt.  Computed by one wave.
+__device__ __forceinline__ void build_fit(const DevParams* __restrict__ P, const Shape& S, uint32_t* fit) {
+  const uint32_t s = threadIdx.x & 63u;
+  for (uint32_t dt = 0; dt < (1u << P->ndt); dt++) {
+    uint64_t sum = 0;
 #pragma unroll
     for (int i = 0; i < 4; i++) {
       if ((uint32_t)i >= P->nops) break;
       const uint32_t bf = P->dt_bit[i] != 0xFF ? (dt >> P->dt_bit[i]) & 1u : P->base_bf16[i];
-      const uint64_t bytes = S.numel[i] * (bf ? 2u : 4u);
-      const uint32_t lv = level_of(P, pack, i);
-#pragma unroll
-      for (int l = 0; l < 4; l++) used[l] += lv == (uint32_t)l ? bytes : 0;
+      sum += (s >> i) & 1u ? S.numel[i] * (bf ? 2u : 4u) : 0;
     }
-    if (P->kind == kKindF) {
+    sum += (s >> 4) & 1u ? S.numel[4] * 4u : 0;
 #pragma unroll
-      for (int l = 0; l < 4; l++) used[l] += pass == (uint32_t)l ? S.numel[4] * 4u : 0;
+    for (int l = 0; l < 4; l++) {
+      const unsigned long long ok = __ballot(s < 32 && sum <= P->cap[l]);
+      if (s == 0) fit[dt * 4 + l] = (uint32_t)ok;
     }
-    bool ok = true;
+  }
+}
+
+// Bit v of the result: variant v of the level assignment `info` (DevParams::pos_info) fits.
+__device__ __forceinline__ uint32_t admissible_mask(const DevParams* __restrict__ P, const uint32_t* fit,
+                                                    uint32_t info, uint32_t pass) {
+  const uint32_t ndtpat = 1u << P->ndt;
+  const bool fused = P->kind == kKindF;
+  uint32_t bits = 0;
+  for (uint32_t dt = 0; dt < ndtpat; dt++) {
+    uint32_t ok = 1;
 #pragma unroll
-    for (int l = 0; l < 4; l++) ok = ok && ((uint32_t)l >= P->NL || used[l] <= P->cap[l]);
-    bits |= (ok ? 1u : 0u) << dt;
+    for (int l = 0; l < 4; l++) {
+      if ((uint32_t)l >= P->NL) break;
+      const uint32_t subset = ((info >> (8 + 4 * l)) & 15u) | (fused && pass == (uint32_t)l ? 16u : 0u);
+      ok &= fit[dt * 4 + l] >> subset;
+    }
+    bits |= (ok & 1u) << dt;
   }
   uint32_t mask = 0;
   for (uint32_t lay = 0; lay < (1u << P->nlay); lay++) mask |= bits << (lay * ndtpat);
@@ -174,24 +190,28 @@ __device__ __forceinline__ void store_ones(void* p, uint32_t bytes) {
   else *reinterpret_cast<uint16_t*>(p) = (uint16_t)0xFFFFu;
 }
 
-// LDS of one unit.
+// LDS of one unit (a shape, or one passive-level slice of it).  "xpack" = pass<<8 | pack.
 struct UnitLds {
   uint64_t* t_cost;   // [cap] per task: best tile/bufferize candidate, then the final cost
-  uint32_t* t_spec;   // [cap] pack | variant<<8 | id<<16
-  uint32_t* c_mask;   // [256] by pack: admissible variants
-  uint16_t* c_base;   // [256] by pack: first task of the level assignment
+  uint32_t* t_spec;   // [cap] xpack | variant<<10 | id<<16
+  uint32_t* c_info;   // [npass*256] by xpack: admissible variants (low 16 bits) | first task << 16
   uint32_t* r_off;    // [nranks+1] first task of the rank
   uint32_t* wave_tot; // [16] scan scratch
+  uint32_t* fit;      // [16] see build_fit
 };
 
-__device__ __forceinline__ UnitLds carve(unsigned char* w, uint32_t cap) {
+__host__ __device__ inline uint32_t unit_lds_bytes(uint32_t cap, uint32_t npass) {
+  return (cap * 12u + npass * 1024u + (kMaxRanks + 2) * 4u + 32u * 4u + 15u) & ~15u;
+}
+
+__device__ __forceinline__ UnitLds carve(unsigned char* w, uint32_t cap, uint32_t npass) {
   UnitLds L;
   L.t_cost = reinterpret_cast<uint64_t*>(w);
   L.t_spec = reinterpret_cast<uint32_t*>(L.t_cost + cap);
-  L.c_mask = L.t_spec + cap;
-  L.c_base = reinterpret_cast<uint16_t*>(L.c_mask + 256);
-  L.r_off = reinterpret_cast<uint32_t*>(L.c_base + 256);
+  L.c_info = L.t_spec + cap;
+  L.r_off = L.c_info + npass * 256u;
   L.wave_tot = L.r_off + kMaxRanks + 2;
+  L.fit = L.wave_tot + 16;
   return L;
 }
 
@@ -218,11 +238,10 @@ __device__ __forceinline__ void build_move_costs(const DevParams* __restrict__ P
 
 // Step 3 for task q: tile and bufferize candidates.
 __device__ __forceinline__ void task_tiles(const DevParams* __restrict__ P, const UnitLds& L, const Shape& S,
-                                           uint32_t shape, uint32_t pass, uint32_t q,
-                                           const uint64_t* __restrict__ cost, Eval& tot) {
+                                           uint32_t shape, uint32_t q, const uint64_t* __restrict__ cost, Eval& tot) {
   const uint32_t V = P->V, npass = P->npass, NL = P->NL;
   const uint32_t sp = L.t_spec[q];
-  const uint32_t pack = sp & 0xFFu, v = (sp >> 8) & 0xFFu;
+  const uint32_t pack = sp & 0xFFu, pass = (sp >> 8) & 3u, v = (sp >> 10) & 31u;
   const uint32_t off = (combo_of_pack(P, pack) * npass + pass) * V + v;
   Eval e;
   e.best = kInf; e.arg = kNone; e.n = 0; e.ovf = 0;
@@ -258,9 +277,10 @@ __device__ __forceinline__ void task_tiles(const DevParams* __restrict__ P, cons
     const uint32_t xe = ((pass * NL + l2) * NL + l3) * P->VE + (P->layE[2] != 0xFF ? y3 << P->layE[2] : 0u);
     const uint64_t cm = P->costM[(uint64_t)shape * P->GM + xm];
     const uint64_t ce = P->costE[(uint64_t)(S.si[1] * P->nszE_n + S.si[3]) * P->GE + xe];
+    const uint32_t zc = pass == 0 ? P->zero[0] : pass == 1 ? P->zero[1] : pass == 2 ? P->zero[2] : P->zero[3];
     uint64_t cand = kInf;
     if (cm != kInf && ce != kInf) {
-      const uint64_t z = mul_or_limit(P->zero[pass], S.numel[4]);
+      const uint64_t z = mul_or_limit(zc, S.numel[4]);
       const uint64_t sum = z + cm;          // each term <= 2^62: no wrap
       if (z >= kLimit || sum >= kLimit || sum + ce >= kLimit) e.ovf = 1; else cand = sum + ce;
     }
@@ -275,17 +295,19 @@ __device__ __forceinline__ void task_tiles(const DevParams* __restrict__ P, cons
 
 // Step 4 for task q (all sub-Specs of lower rank are final in LDS).
 __device__ __forceinline__ void task_rank(const DevParams* __restrict__ P, const UnitLds& L, const uint64_t* bterm,
-                                          const Shape& S, uint64_t group, uint32_t pass, uint32_t q, uint32_t mk_shape,
+                                          const Shape& S, uint64_t group, uint32_t q, uint32_t mk_shape,
                                           uint64_t* __restrict__ cost, uint16_t* __restrict__ arg, Eval& tot) {
   const uint32_t V = P->V, n_slots = P->n_slots;
+  const bool has_dt = P->ndt != 0;
   const uint32_t sp = L.t_spec[q];
-  const uint32_t pack = sp & 0xFFu, v = (sp >> 8) & 0xFFu;
+  const uint32_t xpack = sp & 0x3FFu, v = (sp >> 10) & 31u;
   Eval e;
   e.best = kInf; e.arg = kNone; e.n = 0; e.ovf = 0;
+  uint32_t hi_or = 0;       // OR of the high words of all finite candidates: bit 30 set <=> one reached 2^62
 
   // A. select(microkernel)
   if (mk_shape) {
-    for (uint32_t mm = P->mk_entry[pack * V + v] & mk_shape; mm; mm &= mm - 1) {
+    for (uint32_t mm = P->mk_entry[(xpack & 0xFFu) * V + v] & mk_shape; mm; mm &= mm - 1) {
       const uint32_t j = (uint32_t)__ffs(mm) - 1u;
       const uint64_t k = mul_or_limit(P->mk_cost[j], mk_shape_reps(P, S, j));
       if (k >= kLimit) e.ovf = 1; else consider(e, k, j);
@@ -295,39 +317,45 @@ __device__ __forceinline__ void task_rank(const DevParams* __restrict__ P, const
 
   // B. Move an operand to a strictly lower level: kBatch LDS lookups in flight
   for (uint32_t s0 = 0; s0 < n_slots; s0 += kBatch) {
-    uint64_t sub[kBatch], b[kBatch];
+    uint64_t cand[kBatch];
     uint32_t id[kBatch];
     bool ok[kBatch];
 #pragma unroll
     for (int u = 0; u < kBatch; u++) {
       const uint32_t sl = P->slots[s0 + u < n_slots ? s0 + u : n_slots - 1];
-      const uint32_t i = sl & 3u, dst = (sl >> 2) & 3u, x = (sl >> 4) & 1u, cv = (sl >> 5) & 1u;
-      const uint32_t sh = (sl >> 6) & 7u, layb = (sl >> 9) & 7u, dtb = (sl >> 12) & 7u;
-      const uint32_t src = (pack >> sh) & 3u;
-      const uint32_t ci = ((i * 4 + src) * 4 + dst) * 2 + x;
-      const bool valid = s0 + u < n_slots && dst < src && (!cv || ((v >> dtb) & 1u));
-      b[u] = bterm[cv * 128 + ci];
-      const uint32_t pack2 = valid ? pack - ((src - dst) << sh) : pack;
-      uint32_t v2 = v ^ (x << layb);
-      if (cv) v2 &= ~(1u << dtb);
-      const uint32_t m2 = L.c_mask[pack2];
-      const bool has = valid && ((m2 >> v2) & 1u);
-      const uint32_t idx = has ? L.c_base[pack2] + __popc(m2 & ((1u << v2) - 1u)) : q;
-      const uint64_t t = L.t_cost[idx];
-      sub[u] = has ? t : kInf;
+      const uint32_t dst = (sl >> 2) & 3u, cv = (sl >> 5) & 1u, sh = (sl >> 6) & 7u, dtb = (sl >> 12) & 7u;
+      const uint32_t b_idx = cv * 128u + (sl & 3u) * 32u + dst * 2u + ((sl >> 4) & 1u);   // + src * 8
+      const uint32_t v_xor = ((sl >> 4) & 1u) << ((sl >> 9) & 7u), v_clr = cv << dtb;
+      const uint32_t src = (xpack >> sh) & 3u;
+      const uint64_t b = bterm[b_idx + src * 8u];
+      bool valid = s0 + u < n_slots && dst < src && b != 0;
+      if (has_dt) valid = valid && (!cv || ((v >> dtb) & 1u));
+      const uint32_t xp2 = valid ? xpack - ((src - dst) << sh) : xpack;
+      const uint32_t v2 = (v ^ v_xor) & ~v_clr;
+      const uint32_t ci = L.c_info[xp2];
+      const bool has = valid && ((ci >> v2) & 1u);
+      const uint32_t idx = (ci >> 16) + (has_dt ? __popc(ci & 0xFFFFu & ((1u << v2) - 1u)) : v2);
+      const uint64_t t = L.t_cost[has ? idx : q];
+      const bool fin = has && t != kInf;
+      const uint64_t c = t + b;            // t < 2^62 when finite, b <= 2^62: no wrap
+      cand[u] = fin ? c : kInf;
+      hi_or |= fin ? (uint32_t)(c >> 32) : 0u;
       id[u] = sl >> 16;
       ok[u] = valid;
     }
 #pragma unroll
     for (int u = 0; u < kBatch; u++)
-      if (ok[u] && b[u] != 0) { consider(e, affine_add(e, sub[u], b[u]), id[u]); e.n++; }
+      if (ok[u]) { consider(e, cand[u], id[u]); e.n++; }
+  }
+  if (hi_or >> 30) {          // some finite candidate reached 2^62: the whole solve reports overflow
+    e.ovf = 1;
   }
 
   // C, D. tiles and bufferize, evaluated in step 3
   const uint64_t tb = L.t_cost[q];
   if (tb < e.best) { e.best = tb; e.arg = sp >> 16; }
 
-  const uint32_t off = (combo_of_pack(P, pack) * P->npass + pass) * V + v;
+  const uint32_t off = (combo_of_pack(P, xpack & 0xFFu) * P->npass + (xpack >> 8)) * V + v;
   L.t_cost[q] = e.best;
   cost[group + off] = e.best;
   arg[group + off] = (uint16_t)e.arg;
@@ -335,27 +363,33 @@ __device__ __forceinline__ void task_rank(const DevParams* __restrict__ P, const
   tot.ovf |= e.ovf;
 }
 
-// One unit handled by T threads (T = 64: a wave of the first launch; T = kBigBlock: the second launch).
+// One unit = passes [pass0, pass0 + np) of one shape, handled by T threads
+// (T = 64: the wave of the first launch, all passes; T = kBigBlock: the second launch, one pass).
 template <int T, bool BIG>
 __device__ __forceinline__ void solve_unit(const DevParams* __restrict__ P, const uint64_t* bterm, const UnitLds& L,
-                                           uint32_t cap, const Shape& S, uint32_t shape, uint32_t pass,
+                                           uint32_t cap, const Shape& S, uint32_t shape, uint32_t pass0, uint32_t np,
                                            uint32_t* __restrict__ big_list, uint32_t* __restrict__ big_count,
                                            uint64_t* __restrict__ cost, uint16_t* __restrict__ arg,
                                            Eval& tot, uint32_t& n_adm) {
   const uint32_t tid = T == 64 ? (threadIdx.x & 63u) : threadIdx.x;
   const uint32_t lane = threadIdx.x & 63u;
-  const uint32_t ncombo = P->ncombo, V = P->V, npass = P->npass;
+  const uint32_t V = P->V, npass = P->npass;
+  const uint32_t n_pos = P->ncombo * np;
   const uint64_t group = (uint64_t)shape * P->G;
 
-  // ---- 1. admissibility, compaction in rank order ----
+  // ---- 1. admissibility, compaction in rank order (position = rank-major level assignment, then pass) ----
+  if (threadIdx.x < 64) build_fit(P, S, L.fit);
+  unit_sync<T>();
   uint32_t n_task = 0;
-  for (uint32_t p0 = 0; p0 < ncombo; p0 += T) {
+  for (uint32_t p0 = 0; p0 < n_pos; p0 += T) {
     const uint32_t pos = p0 + tid;
-    uint32_t mask = 0, pack = 0;
-    if (pos < ncombo) {
-      pack = P->pack_by_rank[pos];
-      mask = admissible_mask(P, S, pack, pass);
-      L.c_mask[pack] = mask;
+    uint32_t mask = 0, xpack = 0;
+    if (pos < n_pos) {
+      const uint32_t pc = np == 1 ? pos : P->npass_shift != 0xFF ? pos >> P->npass_shift : pos / np;
+      const uint32_t pass = pass0 + (pos - pc * np);
+      const uint32_t info = P->pos_info[pc];
+      mask = admissible_mask(P, L.fit, info, pass);
+      xpack = pass << 8 | (info & 0xFFu);
     }
     const uint32_t cnt = __popc(mask);
     uint32_t incl = cnt;
@@ -378,45 +412,48 @@ __device__ __forceinline__ void solve_unit(const DevParams* __restrict__ P, cons
       }
       __syncthreads();
     }
-    if (pos < ncombo) {
-      L.c_base[pack] = (uint16_t)base;
+    if (pos < n_pos) {
+      L.c_info[xpack] = mask | base << 16;
       if (base + cnt <= cap) {
         uint32_t q = base;
-        for (uint32_t m = mask; m; m &= m - 1) L.t_spec[q++] = pack | ((uint32_t)__ffs(m) - 1u) << 8;
+        for (uint32_t m = mask; m; m &= m - 1) L.t_spec[q++] = xpack | ((uint32_t)__ffs(m) - 1u) << 10;
       }
     }
   }
   unit_sync<T>();
-  if (tid <= P->nranks) L.r_off[tid] = tid == P->nranks ? n_task : L.c_base[P->pack_by_rank[P->rank_off[tid]]];
+  if (tid <= P->nranks)
+    L.r_off[tid] = tid == P->nranks ? n_task : L.c_info[pass0 << 8 | P->pack_by_rank[P->rank_off[tid]]] >> 16;
   unit_sync<T>();
 
   if (!BIG) {
     n_adm += tid == 0 ? n_task : 0;
-    // ---- 2. entries that do not fit: (INF, NONE), written in chunks of up to 16 bytes ----
-    const uint32_t cch = V < 2 ? V : 2, cper = V / cch;        // cost: entries per chunk, chunks per combo
-    for (uint32_t c = tid; c < ncombo * cper; c += T) {
-      const uint32_t combo = c / cper, v0 = (c - combo * cper) * cch;
-      const uint32_t bits = (L.c_mask[pack_of_combo(P, combo)] >> v0) & ((1u << cch) - 1u);
-      uint64_t* p = cost + group + (uint64_t)(combo * npass + pass) * V + v0;
+    // ---- 2. entries that do not fit: (INF, NONE); the shape's group is contiguous ----
+    const uint32_t G = P->G;
+    const uint32_t cch = V < 2 ? V : 2;        // cost: entries per 16-byte (or 8-byte) chunk
+    const uint32_t lgv = P->log2V, nps = P->npass_shift;
+    for (uint32_t o = tid * cch; o < G; o += T * cch) {
+      const uint32_t row = o >> lgv, v0 = o & (V - 1u), combo = nps != 0xFF ? row >> nps : row / npass, pass = row - combo * npass;
+      const uint32_t bits = (L.c_info[pass << 8 | pack_of_combo(P, combo)] >> v0) & ((1u << cch) - 1u);
+      uint64_t* p = cost + group + o;
       if (bits == 0) store_ones(p, 8 * cch);
       else for (uint32_t u = 0; u < cch; u++) if (!((bits >> u) & 1u)) p[u] = kInf;
     }
-    const uint32_t ach = V < 8 ? V : 8, aper = V / ach;        // argmin: likewise
-    for (uint32_t c = tid; c < ncombo * aper; c += T) {
-      const uint32_t combo = c / aper, v0 = (c - combo * aper) * ach;
-      const uint32_t bits = (L.c_mask[pack_of_combo(P, combo)] >> v0) & ((1u << ach) - 1u);
-      uint16_t* p = arg + group + (uint64_t)(combo * npass + pass) * V + v0;
+    const uint32_t ach = V < 8 ? V : 8;        // argmin: likewise
+    for (uint32_t o = tid * ach; o < G; o += T * ach) {
+      const uint32_t row = o >> lgv, v0 = o & (V - 1u), combo = nps != 0xFF ? row >> nps : row / npass, pass = row - combo * npass;
+      const uint32_t bits = (L.c_info[pass << 8 | pack_of_combo(P, combo)] >> v0) & ((1u << ach) - 1u);
+      uint16_t* p = arg + group + o;
       if (bits == 0) store_ones(p, 2 * ach);
       else for (uint32_t u = 0; u < ach; u++) if (!((bits >> u) & 1u)) p[u] = (uint16_t)kNone;
     }
-    if (n_task > cap) {          // too many tasks for this wave's LDS slice: leave it to the second launch
-      if (tid == 0) big_list[atomicAdd(big_count, 1u)] = shape * npass + pass;
+    if (n_task > cap) {          // too many tasks for the wave's LDS slice: leave the shape to the second launch
+      if (tid < npass) big_list[atomicAdd(big_count, 1u)] = shape * npass + tid;
       return;
     }
   }
 
   // ---- 3. tile and bufferize candidates of every task ----
-  for (uint32_t q = tid; q < n_task; q += T) task_tiles(P, L, S, shape, pass, q, cost, tot);
+  for (uint32_t q = tid; q < n_task; q += T) task_tiles(P, L, S, shape, q, cost, tot);
   unit_sync<T>();
 
   // microkernels whose shape predicate holds for this shape (uniform)
@@ -427,7 +464,7 @@ __device__ __forceinline__ void solve_unit(const DevParams* __restrict__ P, cons
   for (uint32_t r = 0; r < P->nranks; r++) {
     const uint32_t t0 = L.r_off[r], t1 = L.r_off[r + 1];
     if (t0 == t1) continue;
-    for (uint32_t q = t0 + tid; q < t1; q += T) task_rank(P, L, bterm, S, group, pass, q, mk_shape, cost, arg, tot);
+    for (uint32_t q = t0 + tid; q < t1; q += T) task_rank(P, L, bterm, S, group, q, mk_shape, cost, arg, tot);
     unit_sync<T>();
   }
 }
@@ -443,29 +480,27 @@ __device__ __forceinline__ void flush_counters(Counters* __restrict__ ctr, const
   if (tot.ovf) atomicOr(&ctr->overflow, 1u);
 }
 
-// First launch of a level: workgroup = shape, wave = value of the passive level axis.
-__global__ __launch_bounds__(256) void fill_kernel(const DevParams* __restrict__ P,
-                                                   const uint32_t* __restrict__ level_shapes,
-                                                   uint32_t* __restrict__ big_list, uint32_t* __restrict__ big_count,
-                                                   uint32_t cap, uint64_t* __restrict__ cost,
-                                                   uint16_t* __restrict__ arg, Counters* __restrict__ ctr) {
+// First launch of a level: one wave per shape.
+__global__ __launch_bounds__(64) void fill_kernel(const DevParams* __restrict__ P,
+                                                  const uint32_t* __restrict__ level_shapes,
+                                                  uint32_t* __restrict__ big_list, uint32_t* __restrict__ big_count,
+                                                  uint32_t cap, uint64_t* __restrict__ cost,
+                                                  uint16_t* __restrict__ arg, Counters* __restrict__ ctr) {
   extern __shared__ __align__(16) unsigned char smem[];
   uint64_t* bterm = reinterpret_cast<uint64_t*>(smem);
   const uint32_t shape = level_shapes[blockIdx.x];
   Shape S;
   load_shape(P, shape, S);
   build_move_costs(P, S, bterm);
-  __syncthreads();
-  const uint32_t wave = threadIdx.x >> 6;
-  const UnitLds L = carve(smem + kSharedLds + wave * unit_lds_bytes(cap), cap);
+  const UnitLds L = carve(smem + kSharedLds, cap, P->npass);
   Eval tot;
   tot.n = 0; tot.ovf = 0;
   uint32_t n_adm = 0;
-  solve_unit<64, false>(P, bterm, L, cap, S, shape, wave, big_list, big_count, cost, arg, tot, n_adm);
+  solve_unit<64, false>(P, bterm, L, cap, S, shape, 0, P->npass, big_list, big_count, cost, arg, tot, n_adm);
   flush_counters(ctr, tot, n_adm);
 }
 
-// Second launch of a level: the deferred units, one workgroup of kBigBlock threads each.
+// Second launch of a level: the deferred items, one workgroup of kBigBlock threads each.
 __global__ __launch_bounds__(kBigBlock) void fill_big_kernel(const DevParams* __restrict__ P,
                                                              uint32_t* __restrict__ big_list,
                                                              uint32_t* __restrict__ big_count, uint32_t cap,
@@ -473,7 +508,7 @@ __global__ __launch_bounds__(kBigBlock) void fill_big_kernel(const DevParams* __
                                                              Counters* __restrict__ ctr) {
   extern __shared__ __align__(16) unsigned char smem[];
   uint64_t* bterm = reinterpret_cast<uint64_t*>(smem);
-  const UnitLds L = carve(smem + kSharedLds, cap);
+  const UnitLds L = carve(smem + kSharedLds, cap, P->npass);
   Eval tot;
   tot.n = 0; tot.ovf = 0;
   uint32_t n_adm = 0;
@@ -486,23 +521,24 @@ __global__ __launch_bounds__(kBigBlock) void fill_big_kernel(const DevParams* __
     __syncthreads();
     build_move_costs(P, S, bterm);
     __syncthreads();
-    solve_unit<kBigBlock, true>(P, bterm, L, cap, S, shape, pass, big_list, big_count, cost, arg, tot, n_adm);
+    solve_unit<kBigBlock, true>(P, bterm, L, cap, S, shape, pass, 1, big_list, big_count, cost, arg, tot, n_adm);
   }
   flush_counters(ctr, tot, n_adm);
 }
 
-// One dependency level: every unit by the first kernel, then the units it deferred.
-void launch_fill_level(const DevParams* P, uint32_t npass, uint32_t max_task, const uint32_t* level_shapes,
+// One dependency level: every shape by the first kernel, then the items it deferred.
+void launch_fill_level(const DevParams* P, uint32_t npass, uint32_t G, uint32_t max_task, const uint32_t* level_shapes,
                        uint32_t n_shapes, uint32_t* big_list, uint32_t* big_count, uint64_t* cost, uint16_t* arg,
                        Counters* ctr, hipStream_t stream) {
   if (n_shapes == 0) return;
-  const uint32_t small_cap = max_task < kSmallCap ? max_task : kSmallCap;
-  hipLaunchKernelGGL(fill_kernel, dim3(n_shapes), dim3(64 * npass), kSharedLds + npass * unit_lds_bytes(small_cap),
-                     stream, P, level_shapes, big_list, big_count, small_cap, cost, arg, ctr);
-  if (max_task > small_cap) {
+  const uint32_t small_cap = G < kSmallCap ? G : kSmallCap;
+  hipLaunchKernelGGL(fill_kernel, dim3(n_shapes), dim3(64), kSharedLds + unit_lds_bytes(small_cap, npass), stream, P,
+                     level_shapes, big_list, big_count, small_cap, cost, arg, ctr);
+  if (G > small_cap) {
     const uint32_t units = n_shapes * npass;
     hipLaunchKernelGGL(fill_big_kernel, dim3(units < kBigGrid ? units : kBigGrid), dim3(kBigBlock),
-                       kSharedLds + unit_lds_bytes(max_task), stream, P, big_list, big_count, max_task, cost, arg, ctr);
+                       kSharedLds + unit_lds_bytes(max_task, npass), stream, P, big_list, big_count, max_task, cost, arg,
+                       ctr);
   }
 }
 

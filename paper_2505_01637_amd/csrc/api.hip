@@ -466,6 +466,8 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
 
   // ---- fill: one launch per dependency level ----
   HIP_TRY(hipEventRecord(ev[0], st));
+  launch_fill_ones(tab->d_cost, c.n_specs * 8, st);
+  launch_fill_ones(tab->d_arg, c.n_specs * 2, st);
   const uint32_t n_lev = (uint32_t)c.level_off.size() - 1;
   for (uint32_t l = 0; l < n_lev; l++) {
     launch_fill_level(d_P, P.npass, P.G, c.max_task, d_level_shapes + c.level_off[l], c.level_off[l + 1] - c.level_off[l],

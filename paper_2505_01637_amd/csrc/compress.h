@@ -17,6 +17,7 @@ void launch_fill_level(const DevParams* P, uint32_t npass, uint32_t G, uint32_t 
                        uint32_t n_shapes, uint32_t* big_list, uint32_t* big_count, uint64_t* cost, uint16_t* arg,
                        Counters* ctr, hipStream_t stream);
 
+void launch_fill_ones(void* p, size_t bytes, hipStream_t stream);
 void launch_zero_words(unsigned long long* p, uint32_t n, hipStream_t st);
 void launch_head_flags(const Geo& g, uint32_t a0, const uint64_t* cost, const uint16_t* arg, const uint32_t* axis_sizes,
                        unsigned long long* maskD, unsigned long long* maskC, hipStream_t st);

@@ -175,32 +175,46 @@ void scan_flags(const uint8_t* flags, uint32_t n, uint32_t* tile_tmp, uint32_t* 
 }
 
 // ---------------------------------------------------------------- boxes of pass 0
-__device__ __forceinline__ bool mask_bit(const unsigned long long* __restrict__ mask, uint32_t cell) {
-  return (mask[cell >> 6] >> (cell & 63u)) & 1ull;
-}
 
+// One thread per line of cells along a0 (as in pass 0): every flagged cell opens a box whose
+// index is its rank among the flagged cells; the box's extent on a0 is the run length.
 __global__ __launch_bounds__(256) void make_boxes_kernel(Geo g, uint32_t a0,
                                                          const unsigned long long* __restrict__ mask,
-                                                         const uint32_t* __restrict__ prefix, uint32_t n_words,
+                                                         const uint32_t* __restrict__ prefix,
                                                          uint32_t* __restrict__ bcell, uint4* __restrict__ blen,
                                                          uint8_t* __restrict__ alive, uint8_t* __restrict__ pred) {
-  const uint32_t w = blockIdx.x * 256u + threadIdx.x;
-  if (w >= n_words) return;
-  unsigned long long m = mask[w];
-  uint32_t id = prefix[w];
   const uint32_t s0 = g.stride[a0], e0 = g.ext[a0];
-  for (; m; m &= m - 1, id++) {
-    const uint32_t cell = (w << 6) + (uint32_t)__ffsll((long long)m) - 1u;
-    const uint32_t c0 = (cell / s0) % e0;
-    uint32_t len = 1;
-    while (c0 + len < e0 && !mask_bit(mask, cell + len * s0)) len++;
+  const uint32_t n_lines = g.n / e0;
+  const uint32_t q = blockIdx.x * 256u + threadIdx.x;
+  if (q >= n_lines) return;
+  const uint32_t hi = q / s0;
+  const uint32_t base = hi * s0 * e0 + (q - hi * s0);
+  const uint32_t shift = (a0 & 3u) * 8u;
+  uint32_t id = 0, len = 0;
+  auto close = [&]() {
     uint32_t L[4] = {0x01010101u, 0x01010101u, 0x01010101u, 0x01010101u};
-    L[a0 >> 2] = (L[a0 >> 2] & ~(0xFFu << ((a0 & 3u) * 8))) | (len << ((a0 & 3u) * 8));
-    bcell[id] = cell;
+    const uint32_t w = (0x01010101u & ~(0xFFu << shift)) | (len << shift);
+    L[0] = (a0 >> 2) == 0 ? w : L[0];
+    L[1] = (a0 >> 2) == 1 ? w : L[1];
+    L[2] = (a0 >> 2) == 2 ? w : L[2];
+    L[3] = (a0 >> 2) == 3 ? w : L[3];
     blen[id] = make_uint4(L[0], L[1], L[2], L[3]);
-    alive[id] = 1;
-    pred[id] = 0;
+  };
+  for (uint32_t j = 0; j < e0; j++) {
+    const uint32_t cell = base + j * s0;
+    const unsigned long long m = mask[cell >> 6];
+    if ((m >> (cell & 63u)) & 1ull) {
+      if (j) close();
+      id = prefix[cell >> 6] + (uint32_t)__popcll(m & ((1ull << (cell & 63u)) - 1ull));
+      bcell[id] = cell;
+      alive[id] = 1;
+      pred[id] = 0;
+      len = 1;
+    } else {
+      len++;
+    }
   }
+  close();
 }
 
 // ---------------------------------------------------------------- pass on axis a
@@ -277,8 +291,10 @@ void launch_head_flags(const Geo& g, uint32_t a0, const uint64_t* cost, const ui
 
 void launch_make_boxes(const Geo& g, uint32_t a0, const unsigned long long* mask, const uint32_t* prefix, uint32_t n_words,
                        uint32_t* bcell, void* blen, uint8_t* alive, uint8_t* pred, hipStream_t st) {
-  hipLaunchKernelGGL(make_boxes_kernel, dim3((n_words + 255) / 256), dim3(256), 0, st, g, a0, mask, prefix, n_words,
-                     bcell, (uint4*)blen, alive, pred);
+  (void)n_words;
+  const uint32_t n_lines = g.n / g.ext[a0];
+  hipLaunchKernelGGL(make_boxes_kernel, dim3((n_lines + 255) / 256), dim3(256), 0, st, g, a0, mask, prefix, bcell,
+                     (uint4*)blen, alive, pred);
 }
 
 void launch_axis_pass(const Geo& g, uint32_t a, uint8_t stamp, bool is_cost, uint32_t n_boxes, const uint32_t* bcell,

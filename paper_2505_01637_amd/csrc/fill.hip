@@ -12,8 +12,9 @@
 //   1. lanes decide, per level assignment, which entries fit their levels;
 //      the admissible ones are compacted, ordered by rank (sum of the operand
 //      levels), into a task list in LDS (most entries do not fit);
-//   2. entries that do not fit are streamed out as (INF, NONE), 16 bytes per
-//      lane and store;
+//   2. (before the first level, once per table) the whole table is set to
+//      (INF, NONE) by a plain streaming kernel, so this kernel writes the
+//      admissible entries only;
 //   3. one lane per task evaluates the tile and bufferize rewrites, whose
 //      sub-Specs belong to other shapes or tables and are final: a tile
 //      sub-Spec sits at the same offset of a smaller shape's group, so
@@ -182,14 +183,6 @@ __device__ __forceinline__ uint64_t mk_shape_reps(const DevParams* __restrict__ 
   }
 }
 
-// Store `bytes` (2, 4, 8 or 16) bytes of all-ones at p: INF costs and NONE ids are all-ones.
-__device__ __forceinline__ void store_ones(void* p, uint32_t bytes) {
-  if (bytes == 16) *reinterpret_cast<uint4*>(p) = make_uint4(~0u, ~0u, ~0u, ~0u);
-  else if (bytes == 8) *reinterpret_cast<uint2*>(p) = make_uint2(~0u, ~0u);
-  else if (bytes == 4) *reinterpret_cast<uint32_t*>(p) = ~0u;
-  else *reinterpret_cast<uint16_t*>(p) = (uint16_t)0xFFFFu;
-}
-
 // LDS of one unit (a shape, or one passive-level slice of it).  "xpack" = pass<<8 | pack.
 struct UnitLds {
   uint64_t* t_cost;   // [cap] per task: best tile/bufferize candidate, then the final cost
@@ -227,8 +220,9 @@ __device__ __forceinline__ void unit_sync() {
 }
 
 // Move cost per (convert, operand, src, dst, transposed) for this shape: coefficient * elements.
+template <int T>
 __device__ __forceinline__ void build_move_costs(const DevParams* __restrict__ P, const Shape& S, uint64_t* bterm) {
-  for (uint32_t e = threadIdx.x; e < 256; e += blockDim.x) {
+  for (uint32_t e = T == 64 ? (threadIdx.x & 63u) : threadIdx.x; e < 256; e += T) {
     const uint32_t cv = e >> 7, i = (e >> 5) & 3u;
     const uint32_t c = (&P->mcoef[0][0][0][0])[e & 127u];
     const uint64_t n = i == 0 ? S.numel[0] : i == 1 ? S.numel[1] : i == 2 ? S.numel[2] : S.numel[3];
@@ -366,32 +360,29 @@ __device__ __forceinline__ void task_rank(const DevParams* __restrict__ P, const
 // One unit = passes [pass0, pass0 + np) of one shape, handled by T threads
 // (T = 64: the wave of the first launch, all passes; T = kBigBlock: the second launch, one pass).
 template <int T, bool BIG>
-__device__ __forceinline__ void solve_unit(const DevParams* __restrict__ P, const uint64_t* bterm, const UnitLds& L,
+__device__ __forceinline__ void solve_unit(const DevParams* __restrict__ P, uint64_t* bterm, const UnitLds& L,
                                            uint32_t cap, const Shape& S, uint32_t shape, uint32_t pass0, uint32_t np,
                                            uint32_t* __restrict__ big_list, uint32_t* __restrict__ big_count,
                                            uint64_t* __restrict__ cost, uint16_t* __restrict__ arg,
                                            Eval& tot, uint32_t& n_adm) {
   const uint32_t tid = T == 64 ? (threadIdx.x & 63u) : threadIdx.x;
   const uint32_t lane = threadIdx.x & 63u;
-  const uint32_t V = P->V, npass = P->npass;
-  const uint32_t n_pos = P->ncombo * np;
+  const uint32_t npass = P->npass;
   const uint64_t group = (uint64_t)shape * P->G;
 
-  // ---- 1. admissibility, compaction in rank order (position = rank-major level assignment, then pass) ----
+  // ---- 1. admissibility, compaction in rank order (rank-major level assignments, then pass) ----
   if (threadIdx.x < 64) build_fit(P, S, L.fit);
   unit_sync<T>();
   uint32_t n_task = 0;
-  for (uint32_t p0 = 0; p0 < n_pos; p0 += T) {
-    const uint32_t pos = p0 + tid;
-    uint32_t mask = 0, xpack = 0;
-    if (pos < n_pos) {
-      const uint32_t pc = np == 1 ? pos : P->npass_shift != 0xFF ? pos >> P->npass_shift : pos / np;
-      const uint32_t pass = pass0 + (pos - pc * np);
-      const uint32_t info = P->pos_info[pc];
-      mask = admissible_mask(P, L.fit, info, pass);
-      xpack = pass << 8 | (info & 0xFFu);
+  for (uint32_t p0 = 0; p0 < P->ncombo; p0 += T) {
+    const uint32_t pc = p0 + tid;
+    uint32_t mask[4] = {0, 0, 0, 0}, info = 0, cnt = 0;
+    if (pc < P->ncombo) {
+      info = P->pos_info[pc];
+#pragma unroll
+      for (int ps = 0; ps < 4; ps++)
+        if ((uint32_t)ps < np) { mask[ps] = admissible_mask(P, L.fit, info, pass0 + ps); cnt += __popc(mask[ps]); }
     }
-    const uint32_t cnt = __popc(mask);
     uint32_t incl = cnt;
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
@@ -412,40 +403,30 @@ __device__ __forceinline__ void solve_unit(const DevParams* __restrict__ P, cons
       }
       __syncthreads();
     }
-    if (pos < n_pos) {
-      L.c_info[xpack] = mask | base << 16;
-      if (base + cnt <= cap) {
-        uint32_t q = base;
-        for (uint32_t m = mask; m; m &= m - 1) L.t_spec[q++] = xpack | ((uint32_t)__ffs(m) - 1u) << 10;
-      }
+    if (pc < P->ncombo) {
+#pragma unroll
+      for (int ps = 0; ps < 4; ps++)
+        if ((uint32_t)ps < np) {
+          const uint32_t xpack = (pass0 + ps) << 8 | (info & 0xFFu);
+          L.c_info[xpack] = mask[ps] | base << 16;
+          const uint32_t c = __popc(mask[ps]);
+          if (base + c <= cap) {
+            uint32_t q = base;
+            for (uint32_t m = mask[ps]; m; m &= m - 1) L.t_spec[q++] = xpack | ((uint32_t)__ffs(m) - 1u) << 10;
+          }
+          base += c;
+        }
     }
   }
+  if (n_task == 0) return;          // nothing of this shape fits anywhere: the table already says so
   unit_sync<T>();
   if (tid <= P->nranks)
     L.r_off[tid] = tid == P->nranks ? n_task : L.c_info[pass0 << 8 | P->pack_by_rank[P->rank_off[tid]]] >> 16;
+  build_move_costs<T>(P, S, bterm);
   unit_sync<T>();
 
   if (!BIG) {
     n_adm += tid == 0 ? n_task : 0;
-    // ---- 2. entries that do not fit: (INF, NONE); the shape's group is contiguous ----
-    const uint32_t G = P->G;
-    const uint32_t cch = V < 2 ? V : 2;        // cost: entries per 16-byte (or 8-byte) chunk
-    const uint32_t lgv = P->log2V, nps = P->npass_shift;
-    for (uint32_t o = tid * cch; o < G; o += T * cch) {
-      const uint32_t row = o >> lgv, v0 = o & (V - 1u), combo = nps != 0xFF ? row >> nps : row / npass, pass = row - combo * npass;
-      const uint32_t bits = (L.c_info[pass << 8 | pack_of_combo(P, combo)] >> v0) & ((1u << cch) - 1u);
-      uint64_t* p = cost + group + o;
-      if (bits == 0) store_ones(p, 8 * cch);
-      else for (uint32_t u = 0; u < cch; u++) if (!((bits >> u) & 1u)) p[u] = kInf;
-    }
-    const uint32_t ach = V < 8 ? V : 8;        // argmin: likewise
-    for (uint32_t o = tid * ach; o < G; o += T * ach) {
-      const uint32_t row = o >> lgv, v0 = o & (V - 1u), combo = nps != 0xFF ? row >> nps : row / npass, pass = row - combo * npass;
-      const uint32_t bits = (L.c_info[pass << 8 | pack_of_combo(P, combo)] >> v0) & ((1u << ach) - 1u);
-      uint16_t* p = arg + group + o;
-      if (bits == 0) store_ones(p, 2 * ach);
-      else for (uint32_t u = 0; u < ach; u++) if (!((bits >> u) & 1u)) p[u] = (uint16_t)kNone;
-    }
     if (n_task > cap) {          // too many tasks for the wave's LDS slice: leave the shape to the second launch
       if (tid < npass) big_list[atomicAdd(big_count, 1u)] = shape * npass + tid;
       return;
@@ -491,7 +472,6 @@ __global__ __launch_bounds__(64) void fill_kernel(const DevParams* __restrict__ 
   const uint32_t shape = level_shapes[blockIdx.x];
   Shape S;
   load_shape(P, shape, S);
-  build_move_costs(P, S, bterm);
   const UnitLds L = carve(smem + kSharedLds, cap, P->npass);
   Eval tot;
   tot.n = 0; tot.ovf = 0;
@@ -518,12 +498,26 @@ __global__ __launch_bounds__(kBigBlock) void fill_big_kernel(const DevParams* __
     const uint32_t shape = unit / P->npass, pass = unit % P->npass;
     Shape S;
     load_shape(P, shape, S);
-    __syncthreads();
-    build_move_costs(P, S, bterm);
-    __syncthreads();
+    __syncthreads();            // the previous item's LDS is dead
     solve_unit<kBigBlock, true>(P, bterm, L, cap, S, shape, pass, 1, big_list, big_count, cost, arg, tot, n_adm);
   }
   flush_counters(ctr, tot, n_adm);
+}
+
+// (INF, NONE) are all-ones bytes: stream 16 bytes per lane and store over both tables.
+__global__ __launch_bounds__(256) void fill_ones_kernel(uint4* __restrict__ p, size_t n16) {
+  const uint4 ones = make_uint4(~0u, ~0u, ~0u, ~0u);
+  for (size_t i = (size_t)blockIdx.x * 256u + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256u) p[i] = ones;
+}
+
+void launch_fill_ones(void* p, size_t bytes, hipStream_t stream) {
+  const size_t n16 = bytes / 16;       // tables are 256-byte aligned and hold a multiple of 16 bytes... or a tail
+  if (n16) {
+    const size_t blocks = (n16 + 255) / 256;
+    hipLaunchKernelGGL(fill_ones_kernel, dim3((uint32_t)(blocks < 16384 ? blocks : 16384)), dim3(256), 0, stream,
+                       (uint4*)p, n16);
+  }
+  if (bytes % 16) (void)hipMemsetAsync((char*)p + n16 * 16, 0xFF, bytes % 16, stream);
 }
 
 // One dependency level: every shape by the first kernel, then the items it deferred.

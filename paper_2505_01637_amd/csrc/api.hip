@@ -45,8 +45,7 @@ size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 // Host-side compiled lattice: everything derived from (target, lattice).
 struct Compiled {
   DevParams P;
-  std::vector<uint16_t> tile_jt;
-  std::vector<uint32_t> tile_trips;
+  std::vector<TileEntry> tiles;
   std::vector<uint32_t> level_shapes;     // shapes grouped by dependency level
   std::vector<uint32_t> level_off;        // [n_levels + 1]
   std::vector<uint32_t> sizes[4];
@@ -63,7 +62,7 @@ struct Compiled {
 
 // Offsets of the fixed part of the scratch buffer.
 struct FixedLayout {
-  size_t counters, params, tile_jt, tile_trips, level_shapes, mk_entry, big_list, big_count, maskD, maskC, prefD, prefC, tile_tmp, totals,
+  size_t counters, params, tiles, level_shapes, mk_entry, big_list, big_count, maskD, maskC, prefD, prefC, tile_tmp, totals,
       q_idx, q_cost, q_arg, end;
   uint32_t n_words;
 };
@@ -75,8 +74,7 @@ FixedLayout fixed_layout(const Compiled& c) {
   f.n_words = (uint32_t)((c.n_specs + 63) / 64);
   f.counters = take(sizeof(Counters));
   f.params = take(sizeof(DevParams));
-  f.tile_jt = take(c.tile_jt.size() * 2 + 2);
-  f.tile_trips = take(c.tile_trips.size() * 4 + 4);
+  f.tiles = take(c.tiles.size() * sizeof(TileEntry) + 8);
   f.level_shapes = take(c.level_shapes.size() * 4);
   f.mk_entry = take(c.mk_entry.size());
   f.big_list = take((size_t)c.n_shapes * c.P.npass * 4);
@@ -149,7 +147,7 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
   c.n_shapes = P.shape_stride[0] * P.nsz[0];
 
   // variant bits: layout bits (operand order) above dtype bits (operand order)
-  for (int i = 0; i < 5; i++) { P.lay_bit[i] = P.dt_bit[i] = 0xFF; c.lay_axis[i] = c.dt_axis[i] = -1; }
+  for (int i = 0; i < 5; i++) { P.lay_bit[i] = P.dt_bit[i] = kNoBit; c.lay_axis[i] = c.dt_axis[i] = -1; }
   for (uint32_t i = 0; i < P.nops; i++) {
     P.nlay += L->layout_coord[i] ? 1 : 0;
     P.ndt += L->dtype_coord[i] ? 1 : 0;
@@ -159,19 +157,18 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
     P.base_bf16[i] = L->base_dtype_bytes[i] == 2;
     P.access[i] = L->kind == kKindM ? (i == 2 ? kRmw : kRead) : (i == P.nops - 1 ? kWrite : kRead);
     P.lvpow[i] = ipow(P.NL, P.nops - 1 - i);
-    P.pack_shift[i] = (uint8_t)(2 * (P.nops - 1 - i));
+    P.pack_shift[i] = 2 * (P.nops - 1 - i);
   }
   P.V = 1u << (P.nlay + P.ndt);
   P.log2V = P.nlay + P.ndt;
-  P.npass_shift = P.npass == 1 ? 0 : P.npass == 2 ? 1 : P.npass == 4 ? 2 : 0xFF;
-  P.level_bits = P.NL == 1 ? 0 : P.NL == 2 ? 1 : P.NL == 4 ? 2 : 0xFF;
+
   if (P.V > 16) return fail(MRL_E_INVAL, "too many layout/dtype bits");
   {
     uint32_t axis = 4 + P.nlv, seen_l = 0, seen_d = 0;
     for (uint32_t i = 0; i < P.nops; i++)
-      if (L->layout_coord[i]) { c.lay_axis[i] = (int)axis++; P.lay_bit[i] = (uint8_t)(P.ndt + P.nlay - 1 - seen_l++); }
+      if (L->layout_coord[i]) { c.lay_axis[i] = (int)axis++; P.lay_bit[i] = P.ndt + P.nlay - 1 - seen_l++; }
     for (uint32_t i = 0; i < P.nops; i++)
-      if (L->dtype_coord[i]) { c.dt_axis[i] = (int)axis++; P.dt_bit[i] = (uint8_t)(P.ndt - 1 - seen_d++); }
+      if (L->dtype_coord[i]) { c.dt_axis[i] = (int)axis++; P.dt_bit[i] = P.ndt - 1 - seen_d++; }
   }
   P.G = P.ncombo * P.npass * P.V;
   c.n_specs = (uint64_t)c.n_shapes * P.G;
@@ -207,19 +204,7 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
           if (cf > UINT32_MAX) return fail(MRL_E_INVAL, "Move coefficients too large");
           P.mcoef[i][src][dst][x] = (uint32_t)cf;
         }
-  for (uint32_t i = 0; i < P.nops; i++)
-    for (uint32_t dst = 0; dst + 1 < P.NL; dst++)
-      for (uint32_t x = 0; x < 2; x++)
-        for (uint32_t cv = 0; cv < 2; cv++) {
-          if (x && !L->layout_coord[i]) continue;
-          if (cv && !(L->dtype_coord[i] && P.access[i] == kRead)) continue;
-          bool any = false;
-          for (uint32_t src = dst + 1; src < P.NL; src++) any = any || P.mcoef[i][src][dst][x];
-          if (!any) continue;
-          const uint32_t id = P.move_base + ((i * (P.NL - 1) + dst) * 2 + x) * 2 + cv;
-          P.slots[P.n_slots++] = i | dst << 2 | x << 4 | cv << 5 | (uint32_t)P.pack_shift[i] << 6 |
-                                 (uint32_t)(x ? P.lay_bit[i] : 0) << 9 | (uint32_t)(cv ? P.dt_bit[i] : 0) << 12 | id << 16;
-        }
+  for (uint32_t i = 0; i < P.nops; i++) P.can_convert[i] = L->dtype_coord[i] && P.access[i] == kRead;
 
   // microkernels: the level / layout / dtype part of each predicate, per (pack, variant)
   c.mk_entry.assign((size_t)256 * P.V, 0);
@@ -230,8 +215,8 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
       for (uint32_t i = 0; i < 4; i++) {
         lv[i] = i < P.nops ? (pack >> P.pack_shift[i]) & 3u : 0u;
         in_range = in_range && lv[i] < P.NL;
-        ly[i] = i < P.nops && P.lay_bit[i] != 0xFF ? (v >> P.lay_bit[i]) & 1u : 0u;
-        bf[i] = i < P.nops ? (P.dt_bit[i] != 0xFF ? (v >> P.dt_bit[i]) & 1u : P.base_bf16[i]) : 0u;
+        ly[i] = i < P.nops && P.lay_bit[i] != kNoBit ? (v >> P.lay_bit[i]) & 1u : 0u;
+        bf[i] = i < P.nops ? (P.dt_bit[i] != kNoBit ? (v >> P.dt_bit[i]) & 1u : P.base_bf16[i]) : 0u;
       }
       if (!in_range || (P.nops < 4 && (pack >> (2 * P.nops)))) continue;
       uint8_t bits = 0;
@@ -241,7 +226,7 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
         switch (T.mk[j].kind) {
           case MRL_MK_SCALAR_FMA: ok = P.kind == kKindM && !(lv[0] | lv[1] | lv[2]) && all_f32; break;
           case MRL_MK_BCAST_VEC_MULADD: ok = P.kind == kKindM && lv[0] == 0 && lv[1] == 1 && lv[2] == 1 && all_f32 && !ly[1] && !ly[2]; break;
-          case MRL_MK_BF16_DOT: ok = P.kind == kKindM && lv[0] == 1 && lv[1] == 1 && lv[2] == 0 && bf[0] && bf[1] && !bf[2] && (P.lay_bit[1] == 0xFF || ly[1] == 1); break;
+          case MRL_MK_BF16_DOT: ok = P.kind == kKindM && lv[0] == 1 && lv[1] == 1 && lv[2] == 0 && bf[0] && bf[1] && !bf[2] && (P.lay_bit[1] == kNoBit || ly[1] == 1); break;
           case MRL_MK_SCALAR_ADDRELU: ok = P.kind == kKindE && !(lv[0] | lv[1] | lv[2]); break;
           case MRL_MK_VEC_ADDRELU: ok = P.kind == kKindE && lv[0] == 1 && lv[1] == 1 && lv[2] == 1 && !ly[0] && !ly[2]; break;
         }
@@ -254,15 +239,14 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
   for (int d = 0; d < 4; d++) {
     P.tile_dim_ok[d] = L->kind == kKindM || d == 1 || d == 3;
     for (uint32_t j = 0; j < P.nsz[d]; j++) {
-      P.tile_off[d][j] = (uint32_t)c.tile_jt.size();
+      P.tile_off[d][j] = (uint32_t)c.tiles.size();
       if (P.tile_dim_ok[d])
         for (uint32_t jt = 0; jt < j; jt++)
           if (c.sizes[d][j] % c.sizes[d][jt] == 0) {
-            c.tile_jt.push_back((uint16_t)jt);
-            c.tile_trips.push_back(c.sizes[d][j] / c.sizes[d][jt]);
+            c.tiles.push_back(TileEntry{jt, c.sizes[d][j] / c.sizes[d][jt]});
           }
     }
-    for (uint32_t j = P.nsz[d]; j <= (uint32_t)kMaxSizes; j++) P.tile_off[d][j] = (uint32_t)c.tile_jt.size();
+    for (uint32_t j = P.nsz[d]; j <= (uint32_t)kMaxSizes; j++) P.tile_off[d][j] = (uint32_t)c.tiles.size();
   }
 
   // operand-level combos by rank
@@ -278,14 +262,12 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
     uint32_t q = 0;
     for (uint32_t r = 0; r <= P.nranks; r++) {
       while (q < order.size() && order[q].first < r) q++;
-      P.rank_off[r] = (uint16_t)q;
+      P.rank_off[r] = q;
     }
     for (uint32_t i = 0; i < order.size(); i++) {
       const uint32_t combo = order[i].second;
       uint32_t pack = 0;
       for (uint32_t op = 0; op < P.nops; op++) pack |= ((combo / P.lvpow[op]) % P.NL) << P.pack_shift[op];
-      P.combo_by_rank[i] = (uint16_t)combo;
-      P.pack_by_rank[i] = (uint8_t)pack;
       uint32_t info = pack;
       for (uint32_t op = 0; op < P.nops; op++) info |= 1u << (8 + 4 * ((combo / P.lvpow[op]) % P.NL) + op);
       P.pos_info[i] = info;
@@ -301,7 +283,7 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
     if (P.tile_dim_ok[d])
       for (uint32_t j = 0; j < P.nsz[d]; j++) {
         for (uint32_t q = P.tile_off[d][j]; q < P.tile_off[d][j + 1]; q++)
-          chain[d][j] = std::max(chain[d][j], chain[d][c.tile_jt[q]] + 1);
+          chain[d][j] = std::max(chain[d][j], chain[d][c.tiles[q].jt] + 1);
         mx = std::max(mx, chain[d][j]);
       }
     n_lev += mx;
@@ -444,8 +426,7 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
 
   Counters* d_ctr = (Counters*)(base + f.counters);
   DevParams* d_P = (DevParams*)(base + f.params);
-  P.tile_jt = (const uint16_t*)(base + f.tile_jt);
-  P.tile_trips = (const uint32_t*)(base + f.tile_trips);
+  P.tiles = (const TileEntry*)(base + f.tiles);
   uint32_t* d_level_shapes = (uint32_t*)(base + f.level_shapes);
   uint32_t* d_big_list = (uint32_t*)(base + f.big_list);
   uint32_t* d_big_count = (uint32_t*)(base + f.big_count);
@@ -454,10 +435,8 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
   HIP_TRY(hipMemsetAsync(d_big_count, 0, c.level_off.size() * 4, st));
   HIP_TRY(hipMemcpyAsync((void*)P.mk_entry, c.mk_entry.data(), c.mk_entry.size(), hipMemcpyHostToDevice, st));
   HIP_TRY(hipMemcpyAsync(d_P, &P, sizeof P, hipMemcpyHostToDevice, st));
-  if (!c.tile_jt.empty()) {
-    HIP_TRY(hipMemcpyAsync((void*)P.tile_jt, c.tile_jt.data(), c.tile_jt.size() * 2, hipMemcpyHostToDevice, st));
-    HIP_TRY(hipMemcpyAsync((void*)P.tile_trips, c.tile_trips.data(), c.tile_trips.size() * 4, hipMemcpyHostToDevice, st));
-  }
+  if (!c.tiles.empty())
+    HIP_TRY(hipMemcpyAsync((void*)P.tiles, c.tiles.data(), c.tiles.size() * sizeof(TileEntry), hipMemcpyHostToDevice, st));
   HIP_TRY(hipMemcpyAsync(d_level_shapes, c.level_shapes.data(), c.level_shapes.size() * 4, hipMemcpyHostToDevice, st));
 
   hipEvent_t ev[3];

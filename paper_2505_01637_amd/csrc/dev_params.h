@@ -1,6 +1,7 @@
 // Internal: lattice geometry and target tables as the kernels see them.
 // One DevParams lives in device memory per solved table; every field is
-// uniform across a workgroup, so reads compile to scalar loads.
+// uniform across a workgroup, so reads compile to scalar loads (which is why
+// even the small fields are 32 bits wide: there is no scalar byte load).
 #pragma once
 #include <stdint.h>
 
@@ -12,11 +13,16 @@ constexpr uint64_t kLimit = 1ull << 62;      // finite costs stay below this
 constexpr int kMaxSizes = 256;
 constexpr int kMaxCombo = 256;               // n_levels ^ n_operands
 constexpr int kMaxRanks = 16;
-constexpr int kMaxSlots = 48;                // Move rewrites per Spec: operands * (levels-1) * 2 * 2
-constexpr int kMaxVariants = 32;
+constexpr uint32_t kNoBit = 0xFF;            // "this operand has no such coordinate"
 
 enum : uint32_t { kKindM = 0, kKindE = 1, kKindF = 2 };
 enum : uint32_t { kRead = 0, kRmw = 1, kWrite = 2 };
+
+// One tile rewrite of a (dim, size index): the index of the smaller size and the trip count.
+struct TileEntry {
+  uint32_t jt;
+  uint32_t trips;
+};
 
 // A level assignment of the operands is handled as a "pack": 2 bits per operand,
 // operand 0 in the highest field.  pack <-> combo (the mixed-radix index used in
@@ -27,19 +33,19 @@ struct DevParams {
   uint32_t npass;            // values of the passive level axis (FUSED: intermediate), else 1
   uint32_t ncombo;           // NL^nops: level assignments of the operands
   uint32_t nlay, ndt, V;     // layout bits, dtype bits, V = 2^(nlay+ndt) variants per combo
+  uint32_t log2V;            // V = 1 << log2V
   uint32_t G;                // entries per shape = ncombo * npass * V
   uint32_t nsz[4];
   uint32_t shape_stride[4];  // in shapes
   uint32_t sizes[4][kMaxSizes];
-  uint32_t tile_off[4][kMaxSizes + 1];   // CSR into tile_jt / tile_trips, per (dim, size index)
-  const uint16_t* tile_jt;   // device: index of the tile size
-  const uint32_t* tile_trips;
-  uint8_t tile_dim_ok[4];    // which dims this kind may tile
-  uint8_t lay_bit[5];        // bit position inside the variant index, 0xFF = no coordinate
-  uint8_t dt_bit[5];
-  uint8_t base_bf16[5];
-  uint8_t access[5];
-  uint8_t pack_shift[4];     // bit position of operand i's level inside a pack
+  uint32_t tile_off[4][kMaxSizes + 1];   // CSR into tiles, per (dim, size index)
+  const TileEntry* tiles;    // device
+  uint32_t tile_dim_ok[4];   // which dims this kind may tile
+  uint32_t lay_bit[5];       // bit position inside the variant index, kNoBit = no coordinate
+  uint32_t dt_bit[5];
+  uint32_t base_bf16[5];
+  uint32_t access[5];
+  uint32_t pack_shift[4];    // bit position of operand i's level inside a pack
   uint32_t lvpow[5];         // combo stride of operand i
   // ---- target ----
   uint64_t cap[4];
@@ -49,29 +55,21 @@ struct DevParams {
   // Move coefficient per element, [operand][src][dst][same|transposed]; load and/or store
   // according to how the operand is accessed; 0 = the Move does not exist.
   uint32_t mcoef[4][4][4][2];
-  // Move rewrites that can occur at all in this lattice, ascending id:
-  // operand | dst<<2 | transposed<<4 | convert<<5 | id<<16
-  uint32_t n_slots;
-  uint32_t slots[kMaxSlots];
+  uint32_t can_convert[4];   // operand may take a converting Move (has a dtype bit and is read-only)
   // per (pack, variant): bit j set = the level/layout/dtype part of microkernel j's predicate holds
   const uint8_t* mk_entry;   // device, [256][V]
   // ---- rewrite ids ----
   uint32_t move_base, tile_base, buf_id, maxs;
   // ---- operand-level combos ordered by rank (sum of operand levels) ----
   uint32_t nranks;
-  uint16_t combo_by_rank[kMaxCombo];
-  uint8_t pack_by_rank[kMaxCombo];
+  uint32_t rank_off[kMaxRanks + 2];
   // per rank-major position: pack | (operands resident in level l, one nibble per level) << 8
   uint32_t pos_info[kMaxCombo];
-  uint32_t log2V;            // V = 1 << log2V
-  uint32_t npass_shift;      // npass = 1 << npass_shift, or 0xFF if npass is not a power of two
-  uint32_t level_bits;       // NL = 1 << level_bits, or 0xFF if NL is not a power of two
-  uint16_t rank_off[kMaxRanks + 2];
   // ---- tables a FUSED lattice reads ----
   const uint64_t* costM;
   const uint64_t* costE;
   uint32_t GM, VM, GE, VE, nszE_n;
-  uint8_t layM[3], layE[3];  // layout bit positions in the dependency's variant index
+  uint32_t layM[3], layE[3]; // layout bit positions in the dependency's variant index
 };
 
 struct Counters {

@@ -38,11 +38,10 @@
 namespace mrl {
 
 constexpr int kBatch = 8;              // sub-Spec costs fetched together before they are compared
-constexpr uint32_t kSharedLds = 2048;  // Move cost table [convert][operand][src][dst][transposed], u64, per workgroup
 constexpr uint32_t kSmallCap = 512;    // tasks a wave's LDS slice holds in the first launch
 constexpr uint32_t kBigBlock = 512;    // threads per deferred item in the second launch
-constexpr uint32_t kBigGrid = 1024;    // workgroups of the second launch (they loop over the deferred units)
-
+constexpr uint32_t kBigGrid = 1024;    // workgroups of the second launch (they loop over the deferred items)
+constexpr uint32_t kTileLds = 64;      // tile rewrites of the shape staged in LDS at a time
 
 struct Eval {
   uint64_t best;
@@ -51,26 +50,10 @@ struct Eval {
   uint32_t ovf;
 };
 
+// Keep the lexicographic minimum of (cost, rewrite id); only called with finite candidates,
+// so the evaluation order of the rewrites is free.
 __device__ __forceinline__ void consider(Eval& e, uint64_t cand, uint32_t id) {
-  if (cand < e.best) { e.best = cand; e.arg = id; }
-}
-
-// a * sub + b with a < 2^32, sub < 2^62 (or INF, which is absorbing), b < 2^62.
-// Two 32x32+64 multiply-adds give the 96-bit product; reaching 2^62 raises the overflow flag.
-__device__ __forceinline__ uint64_t affine_mul(Eval& e, uint32_t a, uint64_t sub, uint64_t b) {
-  if (sub == kInf) return kInf;
-  const uint64_t lo = (uint64_t)a * (uint32_t)sub;
-  const uint64_t hi = (uint64_t)a * (uint32_t)(sub >> 32) + (lo >> 32);   // bits 32.. of the product
-  const uint64_t prod = (hi << 32) | (uint32_t)lo;
-  if ((hi >> 30) != 0 || prod + b >= kLimit) { e.ovf = 1; return kInf; }
-  return prod + b;
-}
-
-// sub + b, same conventions (b may be the sentinel kLimit for "coefficient * elements overflows").
-__device__ __forceinline__ uint64_t affine_add(Eval& e, uint64_t sub, uint64_t b) {
-  if (sub == kInf) return kInf;
-  if (b >= kLimit || sub + b >= kLimit) { e.ovf = 1; return kInf; }
-  return sub + b;
+  if (cand < e.best || (cand == e.best && id < e.arg)) { e.best = cand; e.arg = id; }
 }
 
 // a * b for operands below 2^62 and 2^33; kLimit if the product reaches 2^62.
@@ -99,72 +82,16 @@ __device__ __forceinline__ void load_shape(const DevParams* __restrict__ P, uint
   else { S.numel[0] = m * k; S.numel[1] = k * n; S.numel[2] = n; S.numel[3] = m * n; S.numel[4] = m * n; }
 }
 
-__device__ __forceinline__ uint32_t level_of(const DevParams* __restrict__ P, uint32_t pack, int i) {
-  return (pack >> P->pack_shift[i]) & 3u;
-}
-
-__device__ __forceinline__ uint32_t combo_of_pack(const DevParams* __restrict__ P, uint32_t pack) {
-  if (P->NL == 4) return pack;
-  uint32_t c = 0;
+// Table offset (inside the shape's group) of entry (pack, pass, variant).
+__device__ __forceinline__ uint32_t entry_offset(const DevParams* __restrict__ P, uint32_t xpack, uint32_t v) {
+  const uint32_t pack = xpack & 0xFFu, pass = xpack >> 8;
+  uint32_t combo = pack;
+  if (P->NL != 4) {
+    combo = 0;
 #pragma unroll
-  for (int i = 0; i < 4; i++) if ((uint32_t)i < P->nops) c += level_of(P, pack, i) * P->lvpow[i];
-  return c;
-}
-
-__device__ __forceinline__ uint32_t pack_of_combo(const DevParams* __restrict__ P, uint32_t combo) {
-  if (P->NL == 4) return combo;
-  uint32_t p = 0;
-  if (P->level_bits != 0xFF) {
-#pragma unroll
-    for (int i = 0; i < 4; i++)
-      if ((uint32_t)i < P->nops) p |= ((combo >> (P->level_bits * (P->nops - 1 - i))) & (P->NL - 1)) << P->pack_shift[i];
-  } else {
-#pragma unroll
-    for (int i = 0; i < 4; i++) if ((uint32_t)i < P->nops) p |= ((combo / P->lvpow[i]) % P->NL) << P->pack_shift[i];
+    for (int i = 0; i < 4; i++) if ((uint32_t)i < P->nops) combo += ((pack >> P->pack_shift[i]) & 3u) * P->lvpow[i];
   }
-  return p;
-}
-
-// fit[dt * 4 + l], bit s: the tensors of subset s (operands 0..3, bit 4 = the fused Spec's
-// intermediate) together fit level l when the dtype bits are dt.  Computed by one wave.
-__device__ __forceinline__ void build_fit(const DevParams* __restrict__ P, const Shape& S, uint32_t* fit) {
-  const uint32_t s = threadIdx.x & 63u;
-  for (uint32_t dt = 0; dt < (1u << P->ndt); dt++) {
-    uint64_t sum = 0;
-#pragma unroll
-    for (int i = 0; i < 4; i++) {
-      if ((uint32_t)i >= P->nops) break;
-      const uint32_t bf = P->dt_bit[i] != 0xFF ? (dt >> P->dt_bit[i]) & 1u : P->base_bf16[i];
-      sum += (s >> i) & 1u ? S.numel[i] * (bf ? 2u : 4u) : 0;
-    }
-    sum += (s >> 4) & 1u ? S.numel[4] * 4u : 0;
-#pragma unroll
-    for (int l = 0; l < 4; l++) {
-      const unsigned long long ok = __ballot(s < 32 && sum <= P->cap[l]);
-      if (s == 0) fit[dt * 4 + l] = (uint32_t)ok;
-    }
-  }
-}
-
-// Bit v of the result: variant v of the level assignment `info` (DevParams::pos_info) fits.
-__device__ __forceinline__ uint32_t admissible_mask(const DevParams* __restrict__ P, const uint32_t* fit,
-                                                    uint32_t info, uint32_t pass) {
-  const uint32_t ndtpat = 1u << P->ndt;
-  const bool fused = P->kind == kKindF;
-  uint32_t bits = 0;
-  for (uint32_t dt = 0; dt < ndtpat; dt++) {
-    uint32_t ok = 1;
-#pragma unroll
-    for (int l = 0; l < 4; l++) {
-      if ((uint32_t)l >= P->NL) break;
-      const uint32_t subset = ((info >> (8 + 4 * l)) & 15u) | (fused && pass == (uint32_t)l ? 16u : 0u);
-      ok &= fit[dt * 4 + l] >> subset;
-    }
-    bits |= (ok & 1u) << dt;
-  }
-  uint32_t mask = 0;
-  for (uint32_t lay = 0; lay < (1u << P->nlay); lay++) mask |= bits << (lay * ndtpat);
-  return mask;
+  return ((combo * P->npass + pass) << P->log2V) + v;
 }
 
 // Shape part of microkernel j's predicate: number of repetitions, 0 if it fails
@@ -185,6 +112,10 @@ __device__ __forceinline__ uint64_t mk_shape_reps(const DevParams* __restrict__ 
 
 // LDS of one unit (a shape, or one passive-level slice of it).  "xpack" = pass<<8 | pack.
 struct UnitLds {
+  uint64_t* bterm;    // [256] Move cost of this shape: [convert][operand][src][dst][transposed]; 0 = no such Move
+  uint64_t* tl_base;  // [kTileLds] tile rewrites of this shape: table offset of the sub-shape's group,
+  uint32_t* tl_trips; // [kTileLds]   trip count,
+  uint32_t* tl_id;    // [kTileLds]   rewrite id
   uint64_t* t_cost;   // [cap] per task: best tile/bufferize candidate, then the final cost
   uint32_t* t_spec;   // [cap] xpack | variant<<10 | id<<16
   uint32_t* c_info;   // [npass*256] by xpack: admissible variants (low 16 bits) | first task << 16
@@ -194,13 +125,17 @@ struct UnitLds {
 };
 
 __host__ __device__ inline uint32_t unit_lds_bytes(uint32_t cap, uint32_t npass) {
-  return (cap * 12u + npass * 1024u + (kMaxRanks + 2) * 4u + 32u * 4u + 15u) & ~15u;
+  return 2048u + kTileLds * 16u + cap * 12u + npass * 1024u + (kMaxRanks + 2) * 4u + 32u * 4u + 16u;
 }
 
 __device__ __forceinline__ UnitLds carve(unsigned char* w, uint32_t cap, uint32_t npass) {
   UnitLds L;
-  L.t_cost = reinterpret_cast<uint64_t*>(w);
-  L.t_spec = reinterpret_cast<uint32_t*>(L.t_cost + cap);
+  L.bterm = reinterpret_cast<uint64_t*>(w);
+  L.tl_base = L.bterm + 256;
+  L.t_cost = L.tl_base + kTileLds;
+  L.tl_trips = reinterpret_cast<uint32_t*>(L.t_cost + cap);
+  L.tl_id = L.tl_trips + kTileLds;
+  L.t_spec = L.tl_id + kTileLds;
   L.c_info = L.t_spec + cap;
   L.r_off = L.c_info + npass * 256u;
   L.wave_tot = L.r_off + kMaxRanks + 2;
@@ -219,6 +154,58 @@ __device__ __forceinline__ void unit_sync() {
   }
 }
 
+// fit[dt * 4 + l], bit s: the tensors of subset s (operands 0..3, bit 4 = the fused Spec's
+// intermediate) together fit level l when the dtype bits are dt.  Computed by one wave.
+__device__ __forceinline__ void build_fit(const DevParams* __restrict__ P, const Shape& S, uint32_t* fit) {
+  const uint32_t s = threadIdx.x & 63u;
+  for (uint32_t dt = 0; dt < (1u << P->ndt); dt++) {
+    uint64_t sum = 0;
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      if ((uint32_t)i >= P->nops) break;
+      const uint32_t bf = P->dt_bit[i] != kNoBit ? (dt >> P->dt_bit[i]) & 1u : P->base_bf16[i];
+      sum += (s >> i) & 1u ? S.numel[i] * (bf ? 2u : 4u) : 0;
+    }
+    sum += (s >> 4) & 1u ? S.numel[4] * 4u : 0;
+#pragma unroll
+    for (int l = 0; l < 4; l++) {
+      const unsigned long long ok = __ballot(s < 32 && sum <= P->cap[l]);
+      if (s == 0) fit[dt * 4 + l] = (uint32_t)ok;
+    }
+  }
+}
+
+// Bit v of the result: variant v of the level assignment `info` (DevParams::pos_info) fits.
+// f = fit[0..3] in registers serves the common case of no dtype bits.
+__device__ __forceinline__ uint32_t admissible_mask(const DevParams* __restrict__ P, const uint32_t* fit,
+                                                    const uint32_t f[4], uint32_t info, uint32_t pass) {
+  const bool fused = P->kind == kKindF;
+  if (P->ndt == 0) {
+    uint32_t ok = 1;
+#pragma unroll
+    for (int l = 0; l < 4; l++) {
+      const uint32_t subset = ((info >> (8 + 4 * l)) & 15u) | (fused && pass == (uint32_t)l ? 16u : 0u);
+      ok &= (uint32_t)l < P->NL ? f[l] >> subset : 1u;
+    }
+    return (ok & 1u) ? (1u << P->V) - 1u : 0u;
+  }
+  const uint32_t ndtpat = 1u << P->ndt;
+  uint32_t bits = 0;
+  for (uint32_t dt = 0; dt < ndtpat; dt++) {
+    uint32_t ok = 1;
+#pragma unroll
+    for (int l = 0; l < 4; l++) {
+      if ((uint32_t)l >= P->NL) break;
+      const uint32_t subset = ((info >> (8 + 4 * l)) & 15u) | (fused && pass == (uint32_t)l ? 16u : 0u);
+      ok &= fit[dt * 4 + l] >> subset;
+    }
+    bits |= (ok & 1u) << dt;
+  }
+  uint32_t mask = 0;
+  for (uint32_t lay = 0; lay < (1u << P->nlay); lay++) mask |= bits << (lay * ndtpat);
+  return mask;
+}
+
 // Move cost per (convert, operand, src, dst, transposed) for this shape: coefficient * elements.
 template <int T>
 __device__ __forceinline__ void build_move_costs(const DevParams* __restrict__ P, const Shape& S, uint64_t* bterm) {
@@ -230,158 +217,150 @@ __device__ __forceinline__ void build_move_costs(const DevParams* __restrict__ P
   }
 }
 
-// Step 3 for task q: tile and bufferize candidates.
-__device__ __forceinline__ void task_tiles(const DevParams* __restrict__ P, const UnitLds& L, const Shape& S,
-                                           uint32_t shape, uint32_t q, const uint64_t* __restrict__ cost, Eval& tot) {
-  const uint32_t V = P->V, npass = P->npass, NL = P->NL;
-  const uint32_t sp = L.t_spec[q];
-  const uint32_t pack = sp & 0xFFu, pass = (sp >> 8) & 3u, v = (sp >> 10) & 31u;
-  const uint32_t off = (combo_of_pack(P, pack) * npass + pass) * V + v;
-  Eval e;
-  e.best = kInf; e.arg = kNone; e.n = 0; e.ovf = 0;
+// Stage tile rewrites [e0, e0 + kTileLds) of this shape (dims in order, sizes ascending) in LDS.
+template <int T>
+__device__ __forceinline__ void stage_tiles(const DevParams* __restrict__ P, const UnitLds& L, const Shape& S,
+                                            uint32_t shape, uint32_t e0, uint32_t n_tile) {
+  const uint32_t tid = T == 64 ? (threadIdx.x & 63u) : threadIdx.x;
+  const uint32_t e = e0 + tid;
+  if (tid < kTileLds && e < n_tile) {
+    uint32_t first = 0, d = 0, q = 0;
 #pragma unroll
-  for (int d = 0; d < 4; d++) {
-    if (!P->tile_dim_ok[d]) continue;
-    const uint32_t j = S.si[d];
-    const uint32_t q_end = P->tile_off[d][j + 1];
-    e.n += q_end - P->tile_off[d][j];
-    for (uint32_t q2 = P->tile_off[d][j]; q2 < q_end; q2 += kBatch) {
-      uint64_t sub[kBatch];
-      uint32_t jt[kBatch];
-#pragma unroll
-      for (int u = 0; u < kBatch; u++) {
-        const uint32_t qq = q2 + u < q_end ? q2 + u : q_end - 1;
-        jt[u] = P->tile_jt[qq];
-        sub[u] = cost[(uint64_t)(shape - (j - jt[u]) * P->shape_stride[d]) * P->G + off];
-      }
-#pragma unroll
-      for (int u = 0; u < kBatch; u++)
-        if (q2 + u < q_end)
-          consider(e, affine_mul(e, P->tile_trips[q2 + u], sub[u], P->s), P->tile_base + d * P->maxs + jt[u]);
+    for (int a = 0; a < 4; a++) {
+      const uint32_t lo = P->tile_off[a][S.si[a]];
+      const uint32_t cnt = P->tile_dim_ok[a] ? P->tile_off[a][S.si[a] + 1] - lo : 0u;
+      if (e >= first && e < first + cnt) { d = a; q = lo + (e - first); }
+      first += cnt;
     }
+    const TileEntry te = P->tiles[q];
+    const uint32_t j = d == 0 ? S.si[0] : d == 1 ? S.si[1] : d == 2 ? S.si[2] : S.si[3];
+    const uint32_t stride = d == 0 ? P->shape_stride[0] : d == 1 ? P->shape_stride[1] : d == 2 ? P->shape_stride[2] : P->shape_stride[3];
+    L.tl_base[tid] = (uint64_t)(shape - (j - te.jt) * stride) * P->G;
+    L.tl_trips[tid] = te.trips;
+    L.tl_id[tid] = P->tile_base + d * P->maxs + te.jt;
   }
-  // bufferize (FUSED): Matmul into the intermediate, then bias-add+ReLU out of it
-  if (P->kind == kKindF) {
-    const uint32_t l0 = level_of(P, pack, 0), l1 = level_of(P, pack, 1), l2 = level_of(P, pack, 2), l3 = level_of(P, pack, 3);
-    const uint32_t y0 = P->lay_bit[0] != 0xFF ? (v >> P->lay_bit[0]) & 1u : 0u;
-    const uint32_t y1 = P->lay_bit[1] != 0xFF ? (v >> P->lay_bit[1]) & 1u : 0u;
-    const uint32_t y3 = P->lay_bit[3] != 0xFF ? (v >> P->lay_bit[3]) & 1u : 0u;
-    const uint32_t xm = ((l0 * NL + l1) * NL + pass) * P->VM +
-                        (P->layM[0] != 0xFF ? y0 << P->layM[0] : 0u) + (P->layM[1] != 0xFF ? y1 << P->layM[1] : 0u);
-    const uint32_t xe = ((pass * NL + l2) * NL + l3) * P->VE + (P->layE[2] != 0xFF ? y3 << P->layE[2] : 0u);
-    const uint64_t cm = P->costM[(uint64_t)shape * P->GM + xm];
-    const uint64_t ce = P->costE[(uint64_t)(S.si[1] * P->nszE_n + S.si[3]) * P->GE + xe];
-    const uint32_t zc = pass == 0 ? P->zero[0] : pass == 1 ? P->zero[1] : pass == 2 ? P->zero[2] : P->zero[3];
-    uint64_t cand = kInf;
-    if (cm != kInf && ce != kInf) {
-      const uint64_t z = mul_or_limit(zc, S.numel[4]);
-      const uint64_t sum = z + cm;          // each term <= 2^62: no wrap
-      if (z >= kLimit || sum >= kLimit || sum + ce >= kLimit) e.ovf = 1; else cand = sum + ce;
-    }
-    consider(e, cand, P->buf_id);
-    e.n += 1;
-  }
-  L.t_cost[q] = e.best;
-  L.t_spec[q] = sp | e.arg << 16;
-  tot.n += e.n;
-  tot.ovf |= e.ovf;
 }
 
-// Step 4 for task q (all sub-Specs of lower rank are final in LDS).
-__device__ __forceinline__ void task_rank(const DevParams* __restrict__ P, const UnitLds& L, const uint64_t* bterm,
-                                          const Shape& S, uint64_t group, uint32_t q, uint32_t mk_shape,
-                                          uint64_t* __restrict__ cost, uint16_t* __restrict__ arg, Eval& tot) {
-  const uint32_t V = P->V, n_slots = P->n_slots;
-  const bool has_dt = P->ndt != 0;
-  const uint32_t sp = L.t_spec[q];
-  const uint32_t xpack = sp & 0x3FFu, v = (sp >> 10) & 31u;
-  Eval e;
-  e.best = kInf; e.arg = kNone; e.n = 0; e.ovf = 0;
-  uint32_t hi_or = 0;       // OR of the high words of all finite candidates: bit 30 set <=> one reached 2^62
-
-  // A. select(microkernel)
-  if (mk_shape) {
-    for (uint32_t mm = P->mk_entry[(xpack & 0xFFu) * V + v] & mk_shape; mm; mm &= mm - 1) {
-      const uint32_t j = (uint32_t)__ffs(mm) - 1u;
-      const uint64_t k = mul_or_limit(P->mk_cost[j], mk_shape_reps(P, S, j));
-      if (k >= kLimit) e.ovf = 1; else consider(e, k, j);
-      e.n++;
-    }
-  }
-
-  // B. Move an operand to a strictly lower level: kBatch LDS lookups in flight
-  for (uint32_t s0 = 0; s0 < n_slots; s0 += kBatch) {
-    uint64_t cand[kBatch];
-    uint32_t id[kBatch];
-    bool ok[kBatch];
+// Tile candidates [0, n_here) staged in LDS, for task q: the sub-Spec sits at the same offset
+// `off` inside a smaller shape's group.  trips * sub + s in 96 bits; reaching 2^62 = overflow.
+__device__ __forceinline__ void task_tiles(const DevParams* __restrict__ P, const UnitLds& L, uint32_t n_here,
+                                           uint32_t off, const uint64_t* __restrict__ cost, Eval& e) {
+  const uint64_t s = P->s;
+  for (uint32_t t0 = 0; t0 < n_here; t0 += kBatch) {
+    uint64_t sub[kBatch];
+#pragma unroll
+    for (int u = 0; u < kBatch; u++) sub[u] = cost[L.tl_base[t0 + u < n_here ? t0 + u : n_here - 1] + off];
 #pragma unroll
     for (int u = 0; u < kBatch; u++) {
-      const uint32_t sl = P->slots[s0 + u < n_slots ? s0 + u : n_slots - 1];
-      const uint32_t dst = (sl >> 2) & 3u, cv = (sl >> 5) & 1u, sh = (sl >> 6) & 7u, dtb = (sl >> 12) & 7u;
-      const uint32_t b_idx = cv * 128u + (sl & 3u) * 32u + dst * 2u + ((sl >> 4) & 1u);   // + src * 8
-      const uint32_t v_xor = ((sl >> 4) & 1u) << ((sl >> 9) & 7u), v_clr = cv << dtb;
-      const uint32_t src = (xpack >> sh) & 3u;
-      const uint64_t b = bterm[b_idx + src * 8u];
-      bool valid = s0 + u < n_slots && dst < src && b != 0;
-      if (has_dt) valid = valid && (!cv || ((v >> dtb) & 1u));
-      const uint32_t xp2 = valid ? xpack - ((src - dst) << sh) : xpack;
-      const uint32_t v2 = (v ^ v_xor) & ~v_clr;
-      const uint32_t ci = L.c_info[xp2];
-      const bool has = valid && ((ci >> v2) & 1u);
-      const uint32_t idx = (ci >> 16) + (has_dt ? __popc(ci & 0xFFFFu & ((1u << v2) - 1u)) : v2);
-      const uint64_t t = L.t_cost[has ? idx : q];
-      const bool fin = has && t != kInf;
-      const uint64_t c = t + b;            // t < 2^62 when finite, b <= 2^62: no wrap
-      cand[u] = fin ? c : kInf;
-      hi_or |= fin ? (uint32_t)(c >> 32) : 0u;
-      id[u] = sl >> 16;
-      ok[u] = valid;
+      if (t0 + u < n_here && sub[u] != kInf) {
+        const uint32_t a = L.tl_trips[t0 + u];
+        const uint64_t lo = (uint64_t)a * (uint32_t)sub[u];
+        const uint64_t hi = (uint64_t)a * (uint32_t)(sub[u] >> 32) + (lo >> 32);   // bits 32.. of the product
+        const uint64_t c = ((hi << 32) | (uint32_t)lo) + s;
+        if ((hi >> 30) != 0 || c >= kLimit) e.ovf = 1; else consider(e, c, L.tl_id[t0 + u]);
+      }
     }
+  }
+}
+
+// bufferize (FUSED): Matmul into the intermediate, then bias-add+ReLU out of it.
+__device__ __forceinline__ void task_bufferize(const DevParams* __restrict__ P, const Shape& S, uint32_t shape,
+                                               uint32_t xpack, uint32_t v, Eval& e) {
+  const uint32_t NL = P->NL, pack = xpack & 0xFFu, pass = xpack >> 8;
+  const uint32_t l0 = (pack >> P->pack_shift[0]) & 3u, l1 = (pack >> P->pack_shift[1]) & 3u;
+  const uint32_t l2 = (pack >> P->pack_shift[2]) & 3u, l3 = (pack >> P->pack_shift[3]) & 3u;
+  const uint32_t y0 = P->lay_bit[0] != kNoBit ? (v >> P->lay_bit[0]) & 1u : 0u;
+  const uint32_t y1 = P->lay_bit[1] != kNoBit ? (v >> P->lay_bit[1]) & 1u : 0u;
+  const uint32_t y3 = P->lay_bit[3] != kNoBit ? (v >> P->lay_bit[3]) & 1u : 0u;
+  const uint32_t xm = ((l0 * NL + l1) * NL + pass) * P->VM +
+                      (P->layM[0] != kNoBit ? y0 << P->layM[0] : 0u) + (P->layM[1] != kNoBit ? y1 << P->layM[1] : 0u);
+  const uint32_t xe = ((pass * NL + l2) * NL + l3) * P->VE + (P->layE[2] != kNoBit ? y3 << P->layE[2] : 0u);
+  const uint64_t cm = P->costM[(uint64_t)shape * P->GM + xm];
+  const uint64_t ce = P->costE[(uint64_t)(S.si[1] * P->nszE_n + S.si[3]) * P->GE + xe];
+  const uint32_t zc = pass == 0 ? P->zero[0] : pass == 1 ? P->zero[1] : pass == 2 ? P->zero[2] : P->zero[3];
+  if (cm != kInf && ce != kInf) {
+    const uint64_t z = mul_or_limit(zc, S.numel[4]);
+    const uint64_t sum = z + cm;          // each term <= 2^62: no wrap
+    if (z >= kLimit || sum >= kLimit || sum + ce >= kLimit) e.ovf = 1; else consider(e, sum + ce, P->buf_id);
+  }
+}
+
+// Moves of operand I of task (xpack, v): to every lower level, same or transposed layout,
+// with or without conversion.  All sub-Specs have a lower rank and are final in LDS; the
+// LDS lookups of one operand are independent and stay in flight together.
+template <int I>
+__device__ __forceinline__ void task_moves(const DevParams* __restrict__ P, const UnitLds& L, uint32_t q,
+                                           uint32_t xpack, uint32_t v, Eval& e, uint32_t& hi_or) {
+  if ((uint32_t)I >= P->nops) return;
+  const uint32_t sh = P->pack_shift[I], layb = P->lay_bit[I], dtb = P->dt_bit[I];
+  const bool has_dt = P->ndt != 0;
+  const uint32_t src = (xpack >> sh) & 3u;
+  if (!__any(src != 0)) return;
+  const uint32_t nx = layb != kNoBit ? 2 : 1, ncv = P->can_convert[I] ? 2 : 1;
+  const uint32_t id0 = P->move_base + (uint32_t)I * (P->NL - 1) * 4u;
+  for (uint32_t cv = 0; cv < ncv; cv++)
+    for (uint32_t x = 0; x < nx; x++) {
+      uint64_t cand[3];
+      bool fin[3], ok[3];
+      const uint32_t v2 = (v ^ (x ? 1u << layb : 0u)) & ~(cv ? 1u << dtb : 0u);
+      const bool cv_ok = !cv || ((v >> dtb) & 1u);
 #pragma unroll
-    for (int u = 0; u < kBatch; u++)
-      if (ok[u]) { consider(e, cand[u], id[u]); e.n++; }
-  }
-  if (hi_or >> 30) {          // some finite candidate reached 2^62: the whole solve reports overflow
-    e.ovf = 1;
-  }
-
-  // C, D. tiles and bufferize, evaluated in step 3
-  const uint64_t tb = L.t_cost[q];
-  if (tb < e.best) { e.best = tb; e.arg = sp >> 16; }
-
-  const uint32_t off = (combo_of_pack(P, xpack & 0xFFu) * P->npass + (xpack >> 8)) * V + v;
-  L.t_cost[q] = e.best;
-  cost[group + off] = e.best;
-  arg[group + off] = (uint16_t)e.arg;
-  tot.n += e.n;
-  tot.ovf |= e.ovf;
+      for (int dst = 0; dst < 3; dst++) {
+        const uint64_t b = L.bterm[cv * 128u + (((uint32_t)I * 4u + src) * 4u + dst) * 2u + x];
+        const bool valid = (uint32_t)dst < src && b != 0 && cv_ok;
+        const uint32_t xp2 = valid ? xpack - ((src - dst) << sh) : xpack;
+        const uint32_t ci = L.c_info[xp2];
+        const bool has = valid && ((ci >> v2) & 1u);
+        const uint32_t idx = (ci >> 16) + (has_dt ? __popc(ci & 0xFFFFu & ((1u << v2) - 1u)) : v2);
+        const uint64_t t = L.t_cost[has ? idx : q];
+        fin[dst] = has && t != kInf;
+        cand[dst] = t + b;               // t < 2^62 when finite, b <= 2^62: no wrap
+        ok[dst] = valid;
+      }
+#pragma unroll
+      for (int dst = 0; dst < 3; dst++) {
+        e.n += ok[dst] ? 1u : 0u;
+        if (fin[dst]) {
+          hi_or |= (uint32_t)(cand[dst] >> 32);
+          consider(e, cand[dst], id0 + ((uint32_t)dst * 2u + x) * 2u + cv);
+        }
+      }
+    }
 }
 
 // One unit = passes [pass0, pass0 + np) of one shape, handled by T threads
 // (T = 64: the wave of the first launch, all passes; T = kBigBlock: the second launch, one pass).
 template <int T, bool BIG>
-__device__ __forceinline__ void solve_unit(const DevParams* __restrict__ P, uint64_t* bterm, const UnitLds& L,
-                                           uint32_t cap, const Shape& S, uint32_t shape, uint32_t pass0, uint32_t np,
+__device__ __forceinline__ void solve_unit(const DevParams* __restrict__ P, const UnitLds& L, uint32_t cap,
+                                           const Shape& S, uint32_t shape, uint32_t pass0, uint32_t np,
                                            uint32_t* __restrict__ big_list, uint32_t* __restrict__ big_count,
                                            uint64_t* __restrict__ cost, uint16_t* __restrict__ arg,
                                            Eval& tot, uint32_t& n_adm) {
   const uint32_t tid = T == 64 ? (threadIdx.x & 63u) : threadIdx.x;
   const uint32_t lane = threadIdx.x & 63u;
-  const uint32_t npass = P->npass;
+  const uint32_t npass = P->npass, ncombo = P->ncombo;
   const uint64_t group = (uint64_t)shape * P->G;
 
   // ---- 1. admissibility, compaction in rank order (rank-major level assignments, then pass) ----
+  constexpr int kIter = T == 64 ? 4 : 1;          // ncombo <= 256
+  uint32_t info[kIter];
+#pragma unroll
+  for (int it = 0; it < kIter; it++) info[it] = it * T + tid < ncombo ? P->pos_info[it * T + tid] : 0u;
   if (threadIdx.x < 64) build_fit(P, S, L.fit);
   unit_sync<T>();
+  uint32_t f[4];
+#pragma unroll
+  for (int l = 0; l < 4; l++) f[l] = L.fit[l];
   uint32_t n_task = 0;
-  for (uint32_t p0 = 0; p0 < P->ncombo; p0 += T) {
-    const uint32_t pc = p0 + tid;
-    uint32_t mask[4] = {0, 0, 0, 0}, info = 0, cnt = 0;
-    if (pc < P->ncombo) {
-      info = P->pos_info[pc];
+#pragma unroll
+  for (int it = 0; it < kIter; it++) {
+    if ((uint32_t)(it * T) >= ncombo) break;
+    const uint32_t pc = it * T + tid;
+    uint32_t mask[4] = {0, 0, 0, 0}, cnt = 0;
+    if (pc < ncombo) {
 #pragma unroll
       for (int ps = 0; ps < 4; ps++)
-        if ((uint32_t)ps < np) { mask[ps] = admissible_mask(P, L.fit, info, pass0 + ps); cnt += __popc(mask[ps]); }
+        if ((uint32_t)ps < np) { mask[ps] = admissible_mask(P, L.fit, f, info[it], pass0 + ps); cnt += __popc(mask[ps]); }
     }
     uint32_t incl = cnt;
 #pragma unroll
@@ -403,11 +382,11 @@ __device__ __forceinline__ void solve_unit(const DevParams* __restrict__ P, uint
       }
       __syncthreads();
     }
-    if (pc < P->ncombo) {
+    if (pc < ncombo) {
 #pragma unroll
       for (int ps = 0; ps < 4; ps++)
         if ((uint32_t)ps < np) {
-          const uint32_t xpack = (pass0 + ps) << 8 | (info & 0xFFu);
+          const uint32_t xpack = (pass0 + ps) << 8 | (info[it] & 0xFFu);
           L.c_info[xpack] = mask[ps] | base << 16;
           const uint32_t c = __popc(mask[ps]);
           if (base + c <= cap) {
@@ -419,33 +398,82 @@ __device__ __forceinline__ void solve_unit(const DevParams* __restrict__ P, uint
     }
   }
   if (n_task == 0) return;          // nothing of this shape fits anywhere: the table already says so
-  unit_sync<T>();
-  if (tid <= P->nranks)
-    L.r_off[tid] = tid == P->nranks ? n_task : L.c_info[pass0 << 8 | P->pack_by_rank[P->rank_off[tid]]] >> 16;
-  build_move_costs<T>(P, S, bterm);
-  unit_sync<T>();
-
   if (!BIG) {
     n_adm += tid == 0 ? n_task : 0;
-    if (n_task > cap) {          // too many tasks for the wave's LDS slice: leave the shape to the second launch
+    if (n_task > cap) {             // too many tasks for the wave's LDS slice: leave the shape to the second launch
       if (tid < npass) big_list[atomicAdd(big_count, 1u)] = shape * npass + tid;
       return;
     }
   }
+  unit_sync<T>();
+  if (tid <= P->nranks)
+    L.r_off[tid] = tid == P->nranks ? n_task : L.c_info[pass0 << 8 | (P->pos_info[P->rank_off[tid]] & 0xFFu)] >> 16;
+  build_move_costs<T>(P, S, L.bterm);
 
-  // ---- 3. tile and bufferize candidates of every task ----
-  for (uint32_t q = tid; q < n_task; q += T) task_tiles(P, L, S, shape, q, cost, tot);
+  // ---- 3. tile and bufferize candidates of every task (sub-Specs of other shapes / tables: final) ----
+  uint32_t n_tile = 0;
+#pragma unroll
+  for (int d = 0; d < 4; d++) if (P->tile_dim_ok[d]) n_tile += P->tile_off[d][S.si[d] + 1] - P->tile_off[d][S.si[d]];
+  const uint32_t n_per_task = n_tile + (P->kind == kKindF ? 1u : 0u);
+  for (uint32_t e0 = 0; e0 == 0 || e0 < n_tile; e0 += kTileLds) {
+    if (e0) unit_sync<T>();
+    stage_tiles<T>(P, L, S, shape, e0, n_tile);
+    unit_sync<T>();
+    const uint32_t n_here = n_tile - e0 < kTileLds ? n_tile - e0 : kTileLds;
+    for (uint32_t q = tid; q < n_task; q += T) {
+      const uint32_t sp = L.t_spec[q];
+      const uint32_t xpack = sp & 0x3FFu, v = (sp >> 10) & 31u;
+      Eval e;
+      e.ovf = 0;
+      if (e0 == 0) {
+        e.best = kInf; e.arg = kNone;
+        if (P->kind == kKindF) task_bufferize(P, S, shape, xpack, v, e);
+      } else {
+        e.best = L.t_cost[q]; e.arg = sp >> 16;
+      }
+      task_tiles(P, L, n_here, entry_offset(P, xpack, v), cost, e);
+      L.t_cost[q] = e.best;
+      L.t_spec[q] = (sp & 0xFFFFu) | e.arg << 16;
+      tot.ovf |= e.ovf;
+    }
+  }
+  tot.n += n_per_task * ((n_task > tid ? n_task - tid + T - 1 : 0u) / T);
   unit_sync<T>();
 
   // microkernels whose shape predicate holds for this shape (uniform)
   uint32_t mk_shape = 0;
   for (uint32_t j = 0; j < P->nmk; j++) mk_shape |= (mk_shape_reps(P, S, j) ? 1u : 0u) << j;
 
-  // ---- 4. rank by rank ----
+  // ---- 4. rank by rank: microkernels and Moves, then the parked tile/bufferize candidate ----
   for (uint32_t r = 0; r < P->nranks; r++) {
     const uint32_t t0 = L.r_off[r], t1 = L.r_off[r + 1];
     if (t0 == t1) continue;
-    for (uint32_t q = t0 + tid; q < t1; q += T) task_rank(P, L, bterm, S, group, q, mk_shape, cost, arg, tot);
+    for (uint32_t q = t0 + tid; q < t1; q += T) {
+      const uint32_t sp = L.t_spec[q];
+      const uint32_t xpack = sp & 0x3FFu, v = (sp >> 10) & 31u;
+      Eval e;
+      e.best = L.t_cost[q]; e.arg = sp >> 16; e.n = 0; e.ovf = 0;
+      uint32_t hi_or = 0;           // OR of the high words of all finite Move candidates
+      if (mk_shape) {
+        for (uint32_t mm = P->mk_entry[(xpack & 0xFFu) * P->V + v] & mk_shape; mm; mm &= mm - 1) {
+          const uint32_t j = (uint32_t)__ffs(mm) - 1u;
+          const uint64_t k = mul_or_limit(P->mk_cost[j], mk_shape_reps(P, S, j));
+          if (k >= kLimit) e.ovf = 1; else consider(e, k, j);
+          e.n++;
+        }
+      }
+      task_moves<0>(P, L, q, xpack, v, e, hi_or);
+      task_moves<1>(P, L, q, xpack, v, e, hi_or);
+      task_moves<2>(P, L, q, xpack, v, e, hi_or);
+      task_moves<3>(P, L, q, xpack, v, e, hi_or);
+      if (hi_or >> 30) e.ovf = 1;   // bit 62 of some finite candidate: the solve reports overflow
+      const uint32_t off = entry_offset(P, xpack, v);
+      L.t_cost[q] = e.best;
+      cost[group + off] = e.best;
+      arg[group + off] = (uint16_t)e.arg;
+      tot.n += e.n;
+      tot.ovf |= e.ovf;
+    }
     unit_sync<T>();
   }
 }
@@ -468,15 +496,14 @@ __global__ __launch_bounds__(64) void fill_kernel(const DevParams* __restrict__ 
                                                   uint32_t cap, uint64_t* __restrict__ cost,
                                                   uint16_t* __restrict__ arg, Counters* __restrict__ ctr) {
   extern __shared__ __align__(16) unsigned char smem[];
-  uint64_t* bterm = reinterpret_cast<uint64_t*>(smem);
   const uint32_t shape = level_shapes[blockIdx.x];
   Shape S;
   load_shape(P, shape, S);
-  const UnitLds L = carve(smem + kSharedLds, cap, P->npass);
+  const UnitLds L = carve(smem, cap, P->npass);
   Eval tot;
   tot.n = 0; tot.ovf = 0;
   uint32_t n_adm = 0;
-  solve_unit<64, false>(P, bterm, L, cap, S, shape, 0, P->npass, big_list, big_count, cost, arg, tot, n_adm);
+  solve_unit<64, false>(P, L, cap, S, shape, 0, P->npass, big_list, big_count, cost, arg, tot, n_adm);
   flush_counters(ctr, tot, n_adm);
 }
 
@@ -487,8 +514,7 @@ __global__ __launch_bounds__(kBigBlock) void fill_big_kernel(const DevParams* __
                                                              uint64_t* __restrict__ cost, uint16_t* __restrict__ arg,
                                                              Counters* __restrict__ ctr) {
   extern __shared__ __align__(16) unsigned char smem[];
-  uint64_t* bterm = reinterpret_cast<uint64_t*>(smem);
-  const UnitLds L = carve(smem + kSharedLds, cap, P->npass);
+  const UnitLds L = carve(smem, cap, P->npass);
   Eval tot;
   tot.n = 0; tot.ovf = 0;
   uint32_t n_adm = 0;
@@ -499,7 +525,7 @@ __global__ __launch_bounds__(kBigBlock) void fill_big_kernel(const DevParams* __
     Shape S;
     load_shape(P, shape, S);
     __syncthreads();            // the previous item's LDS is dead
-    solve_unit<kBigBlock, true>(P, bterm, L, cap, S, shape, pass, 1, big_list, big_count, cost, arg, tot, n_adm);
+    solve_unit<kBigBlock, true>(P, L, cap, S, shape, pass, 1, big_list, big_count, cost, arg, tot, n_adm);
   }
   flush_counters(ctr, tot, n_adm);
 }
@@ -511,7 +537,7 @@ __global__ __launch_bounds__(256) void fill_ones_kernel(uint4* __restrict__ p, s
 }
 
 void launch_fill_ones(void* p, size_t bytes, hipStream_t stream) {
-  const size_t n16 = bytes / 16;       // tables are 256-byte aligned and hold a multiple of 16 bytes... or a tail
+  const size_t n16 = bytes / 16;
   if (n16) {
     const size_t blocks = (n16 + 255) / 256;
     hipLaunchKernelGGL(fill_ones_kernel, dim3((uint32_t)(blocks < 16384 ? blocks : 16384)), dim3(256), 0, stream,
@@ -526,13 +552,12 @@ void launch_fill_level(const DevParams* P, uint32_t npass, uint32_t G, uint32_t 
                        Counters* ctr, hipStream_t stream) {
   if (n_shapes == 0) return;
   const uint32_t small_cap = G < kSmallCap ? G : kSmallCap;
-  hipLaunchKernelGGL(fill_kernel, dim3(n_shapes), dim3(64), kSharedLds + unit_lds_bytes(small_cap, npass), stream, P,
-                     level_shapes, big_list, big_count, small_cap, cost, arg, ctr);
+  hipLaunchKernelGGL(fill_kernel, dim3(n_shapes), dim3(64), unit_lds_bytes(small_cap, npass), stream, P, level_shapes,
+                     big_list, big_count, small_cap, cost, arg, ctr);
   if (G > small_cap) {
     const uint32_t units = n_shapes * npass;
     hipLaunchKernelGGL(fill_big_kernel, dim3(units < kBigGrid ? units : kBigGrid), dim3(kBigBlock),
-                       kSharedLds + unit_lds_bytes(max_task, npass), stream, P, big_list, big_count, max_task, cost, arg,
-                       ctr);
+                       unit_lds_bytes(max_task, npass), stream, P, big_list, big_count, max_task, cost, arg, ctr);
   }
 }
 

@@ -23,6 +23,18 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 FILL_BYTES_PER_SPEC = 18       # write cost (8) + argmin (2), read each cost once (8)
 
 
+def measured_traffic(config, table, n_launch):
+    """HBM bytes per fill launch from the committed rocprofv3 --pmc summary (FETCH_SIZE and
+    WRITE_SIZE runs, scaled by a 1 GiB copy in the same run); None if there is no summary."""
+    path = os.path.join(ROOT, "profiles", "fill_traffic_config%d_%s.json" % (config, table))
+    try:
+        with open(path) as f:
+            t = json.load(f)
+        return (t["fetch_bytes_per_solve"] + t["write_bytes_per_solve"]) / n_launch
+    except (OSError, KeyError, ValueError):
+        return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -32,6 +44,8 @@ def main():
     ap.add_argument("--seed", type=int, default=None)
     ap.add_argument("--scratch-gb", type=float, default=8.0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also launch one plain 1 GiB device copy (to scale rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (the lattice fill is a single-GPU path); "
@@ -74,6 +88,12 @@ def main():
         scratch_of[label] = scratch[off:off + share]
         off += share
 
+    if args.copy_calibration:
+        src = torch.zeros(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -115,16 +135,16 @@ def main():
                        "launches": stats[l]["n_levels_run"],
                        "decision_boxes": stats[l]["n_decision_boxes"], "cost_boxes": stats[l]["n_cost_boxes"],
                        "scratch_used": stats[l]["scratch_used"]} for l in sizes},
-        "roofline": {"bound": "hbm", "kernel": "fill_level_kernel<%d> (%s)" % (256 if big == "F" else 64, big),
+        "roofline": {"bound": "hbm", "kernel": "fill_kernel + fill_big_kernel + fill_ones_kernel (table %s)" % big,
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": None,
+                     "traffic": measured_traffic(args.config, big, n_launch),
                      "launches_per_step": n_launch, "avg_launch_ms": avg_launch_ms,
                      "algorithmic_bytes_per_launch": algo_bytes_per_launch},
     }
 
     if not args.no_cpu_baseline:
         from oracle import oracle as O
-        sample_max = 64 if args.config == 5 else None
+        sample_max = 128 if args.config == 5 else None
         scfg = W.config(args.config, seed=args.seed, max_size=sample_max)
         t1 = time.perf_counter()
         res = O.solve_config(scfg)

@@ -67,6 +67,12 @@ def test_parity_full_size(number):
     compare_config(W.config(number), scratch_bytes=2 << 30)
 
 
+def test_parity_config5_full_size():
+    """The benchmark's workload (config 5: M 28.1 M, E 0.37 M, F 449.5 M specs) in the launch
+    configuration bench.py times: dense tables, counters and both box lists of all three tables."""
+    compare_config(W.config(5), scratch_bytes=6 << 30)
+
+
 def test_degenerate_lattices():
     B = _binding()
     # a single shape: every dimension pinned

@@ -62,7 +62,7 @@ struct Compiled {
 
 // Offsets of the fixed part of the scratch buffer.
 struct FixedLayout {
-  size_t counters, params, tiles, level_shapes, mk_entry, big_list, big_count, maskD, maskC, prefD, prefC, tile_tmp, totals,
+  size_t counters, params, tiles, level_shapes, mk_entry, big_list, big_count, maskD, maskC, lineD, lineC, prefD, prefC, tile_tmp, totals,
       q_idx, q_cost, q_arg, end;
   uint32_t n_words;
 };
@@ -81,6 +81,14 @@ FixedLayout fixed_layout(const Compiled& c) {
   f.big_count = take(c.level_off.size() * 4);
   f.maskD = take((size_t)f.n_words * 8);
   f.maskC = take((size_t)f.n_words * 8);
+  {
+    // line-major copies of the two masks: one bit per cell, 64-bit words per line of the first merge axis
+    uint32_t e0 = c.geo.ext[c.merge_order[0]];
+    for (uint32_t q = 0; q < c.geo.ndim; q++) if (c.geo.ext[c.merge_order[q]] > 1) { e0 = c.geo.ext[c.merge_order[q]]; break; }
+    const size_t line_bytes = (size_t)(c.n_specs / e0) * ((e0 + 63) / 64) * 8;
+    f.lineD = take(line_bytes);
+    f.lineC = take(line_bytes);
+  }
   f.prefD = take((size_t)f.n_words * 4);
   f.prefC = take((size_t)f.n_words * 4);
   f.tile_tmp = take((c.n_specs / kScanTileItems + 2) * 4);
@@ -92,8 +100,8 @@ FixedLayout fixed_layout(const Compiled& c) {
   return f;
 }
 
-// per box while merging: bcell, blen, alive, pred, next, pos; per final box: fcell, flen, fv0, fv1
-size_t work_bytes(uint64_t nb) { return align_up(nb * 4) + align_up(nb * 16) + 2 * align_up(nb) + 2 * align_up(nb * 4); }
+// per box while merging: bcell, blen, alive, pred, next, pos, two live lists; per final box: fcell, flen, fv0, fv1
+size_t work_bytes(uint64_t nb) { return align_up(nb * 4) + align_up(nb * 16) + 2 * align_up(nb) + 4 * align_up(nb * 4); }
 size_t final_bytes(uint64_t nb) { return align_up(nb * 4) + align_up(nb * 16) + 2 * align_up(nb * 8); }
 
 uint32_t ipow(uint32_t b, uint32_t e) { uint32_t r = 1; while (e--) r *= b; return r; }
@@ -465,7 +473,8 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
   uint32_t* d_tot = (uint32_t*)(base + f.totals);
   auto axis_sizes = [&](uint32_t a) -> const uint32_t* { return a < 4 ? (const uint32_t*)((char*)d_P + offsetof(DevParams, sizes) + a * sizeof(uint32_t) * kMaxSizes) : nullptr; };
   if (g.stride[a0] % 64 != 0) { launch_zero_words(maskL[0], f.n_words, st); launch_zero_words(maskL[1], f.n_words, st); }
-  launch_head_flags(g, a0, tab->d_cost, tab->d_arg, axis_sizes(a0), maskL[0], maskL[1], st);
+  unsigned long long* lineL[2] = {(unsigned long long*)(base + f.lineD), (unsigned long long*)(base + f.lineC)};
+  launch_head_flags(g, a0, tab->d_cost, tab->d_arg, axis_sizes(a0), maskL[0], maskL[1], lineL[0], lineL[1], st);
   scan_mask_words(maskL[0], f.n_words, tile_tmp, prefL[0], d_tot + 0, st);
   scan_mask_words(maskL[1], f.n_words, tile_tmp, prefL[1], d_tot + 1, st);
   uint32_t h_tot[4] = {0, 0, 0, 0};
@@ -486,18 +495,38 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
     uint8_t* alive = (uint8_t*)w; w += align_up(nb);
     uint8_t* pred = (uint8_t*)w; w += align_up(nb);
     uint32_t* next = (uint32_t*)w; w += align_up(nb * 4);
-    uint32_t* pos = (uint32_t*)w;
-    launch_make_boxes(g, a0, maskL[which], prefL[which], f.n_words, bcell, blen, alive, pred, st);
+    uint32_t* pos = (uint32_t*)w; w += align_up(nb * 4);
+    uint32_t* live_buf[2] = {(uint32_t*)w, (uint32_t*)(w + align_up(nb * 4))};
+    launch_make_boxes(g, a0, maskL[which], prefL[which], lineL[which], bcell, blen, alive, pred, st);
+    // boxes still to be visited: all of them at first, then compacted lists of the live ones
+    // (ascending index) once the first passes have merged most boxes away
+    const uint32_t* ids = nullptr;
+    uint32_t n_ids = (uint32_t)nb, n_pass = 0, flip = 0;
+    bool counted = false;           // h_tot[2] holds the live count of the current list
     uint8_t stamp = 0;
     for (uint32_t q = 0; q < g.ndim; q++) {
       const uint32_t a = c.merge_order[q];
       if (a == a0 || g.ext[a] <= 1) continue;
-      launch_axis_pass(g, a, ++stamp, which == 1, (uint32_t)nb, bcell, blen, alive, pred, next, maskL[which], prefL[which],
+      launch_axis_pass(g, a, ++stamp, which == 1, ids, n_ids, bcell, blen, alive, pred, next, maskL[which], prefL[which],
                        tab->d_cost, tab->d_arg, axis_sizes(a), st);
+      counted = false;
+      n_pass++;
+      if (n_pass <= 2 && n_ids > (1u << 20)) {
+        scan_flags(alive, ids, n_ids, tile_tmp, pos, d_tot + 2, st);
+        launch_compact_live(alive, ids, n_ids, pos, live_buf[flip], st);
+        HIP_TRY(hipMemcpyAsync(h_tot + 2, d_tot + 2, 4, hipMemcpyDeviceToHost, st));
+        HIP_TRY(hipStreamSynchronize(st));
+        ids = live_buf[flip];
+        n_ids = h_tot[2];
+        flip ^= 1;
+        counted = true;
+      }
     }
-    scan_flags(alive, (uint32_t)nb, tile_tmp, pos, d_tot + 2, st);
-    HIP_TRY(hipMemcpyAsync(h_tot + 2, d_tot + 2, 4, hipMemcpyDeviceToHost, st));
-    HIP_TRY(hipStreamSynchronize(st));
+    scan_flags(alive, ids, n_ids, tile_tmp, pos, d_tot + 2, st);
+    if (!counted) {
+      HIP_TRY(hipMemcpyAsync(h_tot + 2, d_tot + 2, 4, hipMemcpyDeviceToHost, st));
+      HIP_TRY(hipStreamSynchronize(st));
+    }
     const uint64_t nf = h_tot[2];
     const size_t fb = final_bytes(nf);
     if (front + fb > (size_t)((char*)bcell - base)) return fail(MRL_E_NOMEM, "scratch buffer too small: %zu bytes given, %zu needed", scratch_bytes, front + fb + wb);
@@ -506,7 +535,7 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
     char* flen = r; r += align_up(nf * 16);
     uint64_t* fv0 = (uint64_t*)r; r += align_up(nf * 8);
     uint64_t* fv1 = (uint64_t*)r;
-    launch_emit(g, d_P, which == 1, (uint32_t)nb, bcell, blen, alive, pos, tab->d_cost, tab->d_arg, fcell, flen, fv0, fv1, st);
+    launch_emit(g, d_P, which == 1, ids, n_ids, bcell, blen, alive, pos, tab->d_cost, tab->d_arg, fcell, flen, fv0, fv1, st);
     tab->list_off[which] = front;
     tab->list_n[which] = nf;
     needed = std::max(needed, front + fb + wb);

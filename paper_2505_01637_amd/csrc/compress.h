@@ -20,17 +20,24 @@ void launch_fill_level(const DevParams* P, uint32_t npass, uint32_t G, uint32_t 
 void launch_fill_ones(void* p, size_t bytes, hipStream_t stream);
 void launch_zero_words(unsigned long long* p, uint32_t n, hipStream_t st);
 void launch_head_flags(const Geo& g, uint32_t a0, const uint64_t* cost, const uint16_t* arg, const uint32_t* axis_sizes,
-                       unsigned long long* maskD, unsigned long long* maskC, hipStream_t st);
+                       unsigned long long* maskD, unsigned long long* maskC, unsigned long long* lineD,
+                       unsigned long long* lineC, hipStream_t st);
 void scan_mask_words(const unsigned long long* mask, uint32_t n_words, uint32_t* tile_tmp, uint32_t* prefix,
                      uint32_t* total, hipStream_t st);
-void scan_flags(const uint8_t* flags, uint32_t n, uint32_t* tile_tmp, uint32_t* pos, uint32_t* total, hipStream_t st);
-void launch_make_boxes(const Geo& g, uint32_t a0, const unsigned long long* mask, const uint32_t* prefix, uint32_t n_words,
-                       uint32_t* bcell, void* blen, uint8_t* alive, uint8_t* pred, hipStream_t st);
-void launch_axis_pass(const Geo& g, uint32_t a, uint8_t stamp, bool is_cost, uint32_t n_boxes, const uint32_t* bcell,
+void scan_flags(const uint8_t* flags, const uint32_t* ids, uint32_t n, uint32_t* tile_tmp, uint32_t* pos, uint32_t* total,
+                hipStream_t st);
+void launch_compact_live(const uint8_t* alive, const uint32_t* ids, uint32_t n, const uint32_t* pos, uint32_t* out,
+                         hipStream_t st);
+void launch_make_boxes(const Geo& g, uint32_t a0, const unsigned long long* mask, const uint32_t* prefix,
+                       const unsigned long long* line, uint32_t* bcell, void* blen, uint8_t* alive, uint8_t* pred,
+                       hipStream_t st);
+void launch_axis_pass(const Geo& g, uint32_t a, uint8_t stamp, bool is_cost, const uint32_t* ids, uint32_t n_boxes,
+                      const uint32_t* bcell,
                       void* blen, uint8_t* alive, uint8_t* pred, uint32_t* next, const unsigned long long* mask,
                       const uint32_t* prefix, const uint64_t* cost, const uint16_t* arg, const uint32_t* axis_sizes,
                       hipStream_t st);
-void launch_emit(const Geo& g, const DevParams* P, bool is_cost, uint32_t n_boxes, const uint32_t* bcell, const void* blen,
+void launch_emit(const Geo& g, const DevParams* P, bool is_cost, const uint32_t* ids, uint32_t n_boxes, const uint32_t* bcell,
+                 const void* blen,
                  const uint8_t* alive, const uint32_t* pos, const uint64_t* cost, const uint16_t* arg, uint32_t* fcell,
                  void* flen, uint64_t* fv0, uint64_t* fv1, hipStream_t st);
 void launch_gather(const uint64_t* idx, uint32_t n, const uint64_t* cost, const uint16_t* arg, uint64_t* cost_out,

@@ -44,14 +44,17 @@ __global__ __launch_bounds__(256) void head_flags_kernel(Geo g, uint32_t a0,
                                                          const uint16_t* __restrict__ arg,
                                                          const uint32_t* __restrict__ axis_sizes,
                                                          unsigned long long* __restrict__ maskD,
-                                                         unsigned long long* __restrict__ maskC) {
+                                                         unsigned long long* __restrict__ maskC,
+                                                         unsigned long long* __restrict__ lineD,
+                                                         unsigned long long* __restrict__ lineC) {
   const uint32_t s0 = g.stride[a0], e0 = g.ext[a0];
-  const uint32_t n_lines = g.n / e0;
+  const uint32_t n_lines = g.n / e0, lw = (e0 + 63) / 64;      // words per line of the line-major masks
   const uint32_t q = blockIdx.x * 256u + threadIdx.x;
   const bool active = q < n_lines;
   uint32_t base = 0;
   if (active) { uint32_t hi = q / s0; base = hi * s0 * e0 + (q - hi * s0); }
   uint64_t pc = 0; uint32_t pa = 0, ps = 1;
+  unsigned long long wd = 0, wc = 0;
   for (uint32_t j = 0; j < e0; j++) {
     const uint32_t cell = base + j * s0;
     bool hd = false, hc = false;
@@ -70,7 +73,15 @@ __global__ __launch_bounds__(256) void head_flags_kernel(Geo g, uint32_t a0,
       if (hd) atomicOr(&maskD[cell >> 6], 1ull << (cell & 63u));
       if (hc) atomicOr(&maskC[cell >> 6], 1ull << (cell & 63u));
     }
+    wd |= (unsigned long long)hd << (j & 63u);
+    wc |= (unsigned long long)hc << (j & 63u);
+    if (active && ((j & 63u) == 63u || j + 1 == e0)) {
+      lineD[(size_t)(j >> 6) * n_lines + q] = wd;
+      lineC[(size_t)(j >> 6) * n_lines + q] = wc;
+      wd = wc = 0;
+    }
   }
+  (void)lw;
 }
 
 // ---------------------------------------------------------------- prefix sums
@@ -80,7 +91,8 @@ struct LoadPopc {
 };
 struct LoadFlag {
   const uint8_t* p;
-  __device__ __forceinline__ uint32_t operator()(uint32_t i) const { return p[i]; }
+  const uint32_t* ids;      // optional list of box indices; nullptr = all boxes
+  __device__ __forceinline__ uint32_t operator()(uint32_t i) const { return p[ids ? ids[i] : i]; }
 };
 
 constexpr uint32_t kScanItems = 8, kScanBlock = 256, kScanTile = kScanItems * kScanBlock;
@@ -170,51 +182,70 @@ void scan_mask_words(const unsigned long long* mask, uint32_t n_words, uint32_t*
   exclusive_scan(LoadPopc{mask}, n_words, tile_tmp, prefix, total, st);
 }
 
-void scan_flags(const uint8_t* flags, uint32_t n, uint32_t* tile_tmp, uint32_t* pos, uint32_t* total, hipStream_t st) {
-  exclusive_scan(LoadFlag{flags}, n, tile_tmp, pos, total, st);
+void scan_flags(const uint8_t* flags, const uint32_t* ids, uint32_t n, uint32_t* tile_tmp, uint32_t* pos, uint32_t* total,
+                hipStream_t st) {
+  exclusive_scan(LoadFlag{flags, ids}, n, tile_tmp, pos, total, st);
+}
+
+// out[pos[i]] = index of the i-th listed box, for the boxes still alive (keeps ascending order).
+__global__ __launch_bounds__(256) void compact_live_kernel(const uint8_t* __restrict__ alive,
+                                                           const uint32_t* __restrict__ ids, uint32_t n,
+                                                           const uint32_t* __restrict__ pos, uint32_t* __restrict__ out) {
+  const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+  if (i >= n) return;
+  const uint32_t b = ids ? ids[i] : i;
+  if (alive[b]) out[pos[i]] = b;
+}
+
+void launch_compact_live(const uint8_t* alive, const uint32_t* ids, uint32_t n, const uint32_t* pos, uint32_t* out,
+                         hipStream_t st) {
+  hipLaunchKernelGGL(compact_live_kernel, dim3((n + 255) / 256), dim3(256), 0, st, alive, ids, n, pos, out);
 }
 
 // ---------------------------------------------------------------- boxes of pass 0
 
-// One thread per line of cells along a0 (as in pass 0): every flagged cell opens a box whose
-// index is its rank among the flagged cells; the box's extent on a0 is the run length.
+// One thread per line of cells along a0: the line-major mask gives the flagged cells of the line
+// and the run lengths between them; the table-order mask and its prefix sums give each flagged
+// cell its rank = the index of the box it opens.
 __global__ __launch_bounds__(256) void make_boxes_kernel(Geo g, uint32_t a0,
                                                          const unsigned long long* __restrict__ mask,
                                                          const uint32_t* __restrict__ prefix,
+                                                         const unsigned long long* __restrict__ line,
                                                          uint32_t* __restrict__ bcell, uint4* __restrict__ blen,
                                                          uint8_t* __restrict__ alive, uint8_t* __restrict__ pred) {
   const uint32_t s0 = g.stride[a0], e0 = g.ext[a0];
-  const uint32_t n_lines = g.n / e0;
+  const uint32_t n_lines = g.n / e0, lw = (e0 + 63) / 64;
   const uint32_t q = blockIdx.x * 256u + threadIdx.x;
   if (q >= n_lines) return;
   const uint32_t hi = q / s0;
   const uint32_t base = hi * s0 * e0 + (q - hi * s0);
   const uint32_t shift = (a0 & 3u) * 8u;
-  uint32_t id = 0, len = 0;
-  auto close = [&]() {
+  uint32_t id = 0, start = 0;
+  bool open = false;
+  auto close = [&](uint32_t end) {
     uint32_t L[4] = {0x01010101u, 0x01010101u, 0x01010101u, 0x01010101u};
-    const uint32_t w = (0x01010101u & ~(0xFFu << shift)) | (len << shift);
+    const uint32_t w = (0x01010101u & ~(0xFFu << shift)) | ((end - start) << shift);
     L[0] = (a0 >> 2) == 0 ? w : L[0];
     L[1] = (a0 >> 2) == 1 ? w : L[1];
     L[2] = (a0 >> 2) == 2 ? w : L[2];
     L[3] = (a0 >> 2) == 3 ? w : L[3];
     blen[id] = make_uint4(L[0], L[1], L[2], L[3]);
   };
-  for (uint32_t j = 0; j < e0; j++) {
-    const uint32_t cell = base + j * s0;
-    const unsigned long long m = mask[cell >> 6];
-    if ((m >> (cell & 63u)) & 1ull) {
-      if (j) close();
-      id = prefix[cell >> 6] + (uint32_t)__popcll(m & ((1ull << (cell & 63u)) - 1ull));
+  for (uint32_t w = 0; w < lw; w++) {
+    for (unsigned long long m = line[(size_t)w * n_lines + q]; m; m &= m - 1) {
+      const uint32_t j = w * 64u + (uint32_t)__ffsll((long long)m) - 1u;
+      if (open) close(j);
+      const uint32_t cell = base + j * s0;
+      const unsigned long long tm = mask[cell >> 6];
+      id = prefix[cell >> 6] + (uint32_t)__popcll(tm & ((1ull << (cell & 63u)) - 1ull));
       bcell[id] = cell;
       alive[id] = 1;
       pred[id] = 0;
-      len = 1;
-    } else {
-      len++;
+      start = j;
+      open = true;
     }
   }
-  close();
+  close(e0);
 }
 
 // ---------------------------------------------------------------- pass on axis a
@@ -224,7 +255,8 @@ __device__ __forceinline__ uint32_t len_byte(const uint4& L, uint32_t a) {
 }
 
 template <bool COST>
-__global__ __launch_bounds__(256) void link_kernel(Geo g, uint32_t a, uint8_t stamp, uint32_t n_boxes,
+__global__ __launch_bounds__(256) void link_kernel(Geo g, uint32_t a, uint8_t stamp,
+                                                   const uint32_t* __restrict__ ids, uint32_t n_boxes,
                                                    const uint32_t* __restrict__ bcell, const uint4* __restrict__ blen,
                                                    const uint8_t* __restrict__ alive, uint8_t* __restrict__ pred,
                                                    uint32_t* __restrict__ next,
@@ -232,8 +264,10 @@ __global__ __launch_bounds__(256) void link_kernel(Geo g, uint32_t a, uint8_t st
                                                    const uint32_t* __restrict__ prefix,
                                                    const uint64_t* __restrict__ cost, const uint16_t* __restrict__ arg,
                                                    const uint32_t* __restrict__ axis_sizes) {
-  const uint32_t b = blockIdx.x * 256u + threadIdx.x;
-  if (b >= n_boxes || !alive[b]) return;
+  const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+  if (i >= n_boxes) return;
+  const uint32_t b = ids ? ids[i] : i;
+  if (!alive[b]) return;
   const uint32_t cell = bcell[b];
   const uint4 L = blen[b];
   const uint32_t sa = g.stride[a], ea = g.ext[a];
@@ -266,13 +300,17 @@ __global__ __launch_bounds__(256) void link_kernel(Geo g, uint32_t a, uint8_t st
   next[b] = nxt;
 }
 
-__global__ __launch_bounds__(256) void absorb_kernel(uint32_t a, uint8_t stamp, uint32_t n_boxes,
-                                                     uint8_t* __restrict__ blen_bytes, uint8_t* __restrict__ alive,
-                                                     const uint8_t* __restrict__ pred, const uint32_t* __restrict__ next) {
-  const uint32_t b = blockIdx.x * 256u + threadIdx.x;
-  if (b >= n_boxes || !alive[b] || pred[b] == stamp) return;   // only heads of chains
+__global__ __launch_bounds__(256) void absorb_kernel(uint32_t a, uint8_t stamp, const uint32_t* __restrict__ ids,
+                                                     uint32_t n_boxes, uint8_t* __restrict__ blen_bytes,
+                                                     uint8_t* __restrict__ alive, const uint8_t* __restrict__ pred,
+                                                     const uint32_t* __restrict__ next) {
+  const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+  if (i >= n_boxes) return;
+  const uint32_t b = ids ? ids[i] : i;
+  uint32_t s = next[b];
+  if (s == 0xFFFFFFFFu || !alive[b] || pred[b] == stamp) return;   // only heads of chains of two or more
   uint32_t tot = blen_bytes[(size_t)b * 16 + a];
-  for (uint32_t s = next[b]; s != 0xFFFFFFFFu; s = next[s]) {
+  for (; s != 0xFFFFFFFFu; s = next[s]) {
     tot += blen_bytes[(size_t)s * 16 + a];
     alive[s] = 0;
   }
@@ -280,35 +318,39 @@ __global__ __launch_bounds__(256) void absorb_kernel(uint32_t a, uint8_t stamp, 
 }
 
 void launch_head_flags(const Geo& g, uint32_t a0, const uint64_t* cost, const uint16_t* arg, const uint32_t* axis_sizes,
-                       unsigned long long* maskD, unsigned long long* maskC, hipStream_t st) {
+                       unsigned long long* maskD, unsigned long long* maskC, unsigned long long* lineD,
+                       unsigned long long* lineC, hipStream_t st) {
   const uint32_t n_lines = g.n / g.ext[a0];
   const uint32_t blocks = (n_lines + 255) / 256;
   if (g.stride[a0] % 64 == 0)
-    hipLaunchKernelGGL(head_flags_kernel<true>, dim3(blocks), dim3(256), 0, st, g, a0, cost, arg, axis_sizes, maskD, maskC);
+    hipLaunchKernelGGL(head_flags_kernel<true>, dim3(blocks), dim3(256), 0, st, g, a0, cost, arg, axis_sizes, maskD, maskC,
+                       lineD, lineC);
   else
-    hipLaunchKernelGGL(head_flags_kernel<false>, dim3(blocks), dim3(256), 0, st, g, a0, cost, arg, axis_sizes, maskD, maskC);
+    hipLaunchKernelGGL(head_flags_kernel<false>, dim3(blocks), dim3(256), 0, st, g, a0, cost, arg, axis_sizes, maskD, maskC,
+                       lineD, lineC);
 }
 
-void launch_make_boxes(const Geo& g, uint32_t a0, const unsigned long long* mask, const uint32_t* prefix, uint32_t n_words,
-                       uint32_t* bcell, void* blen, uint8_t* alive, uint8_t* pred, hipStream_t st) {
-  (void)n_words;
+void launch_make_boxes(const Geo& g, uint32_t a0, const unsigned long long* mask, const uint32_t* prefix,
+                       const unsigned long long* line, uint32_t* bcell, void* blen, uint8_t* alive, uint8_t* pred,
+                       hipStream_t st) {
   const uint32_t n_lines = g.n / g.ext[a0];
-  hipLaunchKernelGGL(make_boxes_kernel, dim3((n_lines + 255) / 256), dim3(256), 0, st, g, a0, mask, prefix, bcell,
+  hipLaunchKernelGGL(make_boxes_kernel, dim3((n_lines + 255) / 256), dim3(256), 0, st, g, a0, mask, prefix, line, bcell,
                      (uint4*)blen, alive, pred);
 }
 
-void launch_axis_pass(const Geo& g, uint32_t a, uint8_t stamp, bool is_cost, uint32_t n_boxes, const uint32_t* bcell,
+void launch_axis_pass(const Geo& g, uint32_t a, uint8_t stamp, bool is_cost, const uint32_t* ids, uint32_t n_boxes,
+                      const uint32_t* bcell,
                       void* blen, uint8_t* alive, uint8_t* pred, uint32_t* next, const unsigned long long* mask,
                       const uint32_t* prefix, const uint64_t* cost, const uint16_t* arg, const uint32_t* axis_sizes,
                       hipStream_t st) {
   const uint32_t blocks = (n_boxes + 255) / 256;
   if (is_cost)
-    hipLaunchKernelGGL(link_kernel<true>, dim3(blocks), dim3(256), 0, st, g, a, stamp, n_boxes, bcell, (const uint4*)blen,
+    hipLaunchKernelGGL(link_kernel<true>, dim3(blocks), dim3(256), 0, st, g, a, stamp, ids, n_boxes, bcell, (const uint4*)blen,
                        alive, pred, next, mask, prefix, cost, arg, axis_sizes);
   else
-    hipLaunchKernelGGL(link_kernel<false>, dim3(blocks), dim3(256), 0, st, g, a, stamp, n_boxes, bcell, (const uint4*)blen,
+    hipLaunchKernelGGL(link_kernel<false>, dim3(blocks), dim3(256), 0, st, g, a, stamp, ids, n_boxes, bcell, (const uint4*)blen,
                        alive, pred, next, mask, prefix, cost, arg, axis_sizes);
-  hipLaunchKernelGGL(absorb_kernel, dim3(blocks), dim3(256), 0, st, a, stamp, n_boxes, (uint8_t*)blen, alive, pred, next);
+  hipLaunchKernelGGL(absorb_kernel, dim3(blocks), dim3(256), 0, st, a, stamp, ids, n_boxes, (uint8_t*)blen, alive, pred, next);
 }
 
 // ---------------------------------------------------------------- final lists
@@ -318,15 +360,18 @@ __device__ __forceinline__ uint64_t gcd_u64(uint64_t a, uint64_t b) {
 }
 
 template <bool COST>
-__global__ __launch_bounds__(256) void emit_kernel(Geo g, const DevParams* __restrict__ P, uint32_t n_boxes,
+__global__ __launch_bounds__(256) void emit_kernel(Geo g, const DevParams* __restrict__ P,
+                                                   const uint32_t* __restrict__ ids, uint32_t n_boxes,
                                                    const uint32_t* __restrict__ bcell, const uint4* __restrict__ blen,
                                                    const uint8_t* __restrict__ alive, const uint32_t* __restrict__ pos,
                                                    const uint64_t* __restrict__ cost, const uint16_t* __restrict__ arg,
                                                    uint32_t* __restrict__ fcell, uint4* __restrict__ flen,
                                                    uint64_t* __restrict__ fv0, uint64_t* __restrict__ fv1) {
-  const uint32_t b = blockIdx.x * 256u + threadIdx.x;
-  if (b >= n_boxes || !alive[b]) return;
-  const uint32_t o = pos[b], cell = bcell[b];
+  const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+  if (i >= n_boxes) return;
+  const uint32_t b = ids ? ids[i] : i;
+  if (!alive[b]) return;
+  const uint32_t o = pos[i], cell = bcell[b];
   fcell[o] = cell;
   flen[o] = blen[b];
   if (COST) {
@@ -344,15 +389,16 @@ __global__ __launch_bounds__(256) void emit_kernel(Geo g, const DevParams* __res
   }
 }
 
-void launch_emit(const Geo& g, const DevParams* P, bool is_cost, uint32_t n_boxes, const uint32_t* bcell, const void* blen,
+void launch_emit(const Geo& g, const DevParams* P, bool is_cost, const uint32_t* ids, uint32_t n_boxes, const uint32_t* bcell,
+                 const void* blen,
                  const uint8_t* alive, const uint32_t* pos, const uint64_t* cost, const uint16_t* arg, uint32_t* fcell,
                  void* flen, uint64_t* fv0, uint64_t* fv1, hipStream_t st) {
   const uint32_t blocks = (n_boxes + 255) / 256;
   if (is_cost)
-    hipLaunchKernelGGL(emit_kernel<true>, dim3(blocks), dim3(256), 0, st, g, P, n_boxes, bcell, (const uint4*)blen, alive,
+    hipLaunchKernelGGL(emit_kernel<true>, dim3(blocks), dim3(256), 0, st, g, P, ids, n_boxes, bcell, (const uint4*)blen, alive,
                        pos, cost, arg, fcell, (uint4*)flen, fv0, fv1);
   else
-    hipLaunchKernelGGL(emit_kernel<false>, dim3(blocks), dim3(256), 0, st, g, P, n_boxes, bcell, (const uint4*)blen, alive,
+    hipLaunchKernelGGL(emit_kernel<false>, dim3(blocks), dim3(256), 0, st, g, P, ids, n_boxes, bcell, (const uint4*)blen, alive,
                        pos, cost, arg, fcell, (uint4*)flen, fv0, fv1);
 }
 

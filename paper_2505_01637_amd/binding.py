@@ -239,11 +239,10 @@ def solve(target, lattice, deps=(), scratch_bytes=None, stream=None, buffers=Non
     if not torch.cuda.is_available():
         raise RuntimeError("mrl solve needs a GPU: there is no CPU path")
     L = _lattice_desc(lattice)
-    ext, _ = geometry(target, lattice)
-    cb, ab, sb = table_bytes(target, lattice)
-    if scratch_bytes is not None:
-        sb = scratch_bytes
+    ext, n = geometry(target, lattice)
+    cb, ab = 8 * n, 2 * n
     if buffers is None:
+        sb = table_bytes(target, lattice)[2] if scratch_bytes is None else scratch_bytes
         dev = torch.device("cuda", torch.cuda.current_device())
         buffers = (torch.empty(cb, dtype=torch.uint8, device=dev),
                    torch.empty(ab, dtype=torch.uint8, device=dev),

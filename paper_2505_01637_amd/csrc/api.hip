@@ -7,6 +7,8 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <memory>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -336,10 +338,46 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
   return MRL_OK;
 }
 
+
+// compile() costs a few hundred microseconds for the larger lattices; repeated solves of the
+// same (target, lattice) reuse the result.  Entries are immutable once published.
+using CompiledPtr = std::shared_ptr<const Compiled>;
+
+bool same_problem(const Compiled& c, const mrl_target_desc& T, const mrl_lattice_desc& L) {
+  if (memcmp(&c.target, &T, sizeof T) || c.lat.kind != L.kind) return false;
+  if (memcmp(c.lat.layout_coord, L.layout_coord, sizeof L.layout_coord) ||
+      memcmp(c.lat.dtype_coord, L.dtype_coord, sizeof L.dtype_coord) ||
+      memcmp(c.lat.base_dtype_bytes, L.base_dtype_bytes, sizeof L.base_dtype_bytes)) return false;
+  for (int d = 0; d < 4; d++) {
+    if (L.n_sizes[d] != c.sizes[d].size() || !L.sizes[d]) return false;
+    if (memcmp(L.sizes[d], c.sizes[d].data(), c.sizes[d].size() * sizeof(uint32_t))) return false;
+  }
+  return true;
+}
+
+int32_t get_compiled(const mrl_target_desc& T, const mrl_lattice_desc* L, CompiledPtr& out) {
+  static std::mutex mu;
+  static std::vector<CompiledPtr> cache;          // most recent last, at most 8
+  if (L && L->kind <= MRL_KIND_FUSED_MM_ADD_RELU) {
+    std::lock_guard<std::mutex> lock(mu);
+    for (size_t i = cache.size(); i-- > 0;)
+      if (same_problem(*cache[i], T, *L)) { out = cache[i]; return MRL_OK; }
+  }
+  auto c = std::make_shared<Compiled>();
+  const int32_t rc = compile(T, L, *c);
+  if (rc) return rc;
+  std::lock_guard<std::mutex> lock(mu);
+  if (cache.size() >= 8) cache.erase(cache.begin());
+  cache.push_back(c);
+  out = c;
+  return MRL_OK;
+}
+
 }  // namespace
 
 struct mrl_table {
-  Compiled c;
+  CompiledPtr cp;
+  DevParams P;                // this table's copy: device pointers filled in by mrl_solve
   FixedLayout f;
   char* scratch;
   uint64_t* d_cost;
@@ -371,9 +409,10 @@ void mrl_target_destroy(mrl_target* t) { delete t; }
 int32_t mrl_geometry(const mrl_target* t, const mrl_lattice_desc* lat, uint32_t* n_dims, uint32_t* extents,
                      uint64_t* n_specs) {
   if (!t) return fail(MRL_E_INVAL, "target is NULL");
-  Compiled c;
-  int32_t rc = compile(t->d, lat, c);
+  CompiledPtr cp;
+  int32_t rc = get_compiled(t->d, lat, cp);
   if (rc) return rc;
+  const Compiled& c = *cp;
   if (n_dims) *n_dims = c.geo.ndim;
   if (extents) for (uint32_t a = 0; a < c.geo.ndim; a++) extents[a] = c.geo.ext[a];
   if (n_specs) *n_specs = c.n_specs;
@@ -383,9 +422,10 @@ int32_t mrl_geometry(const mrl_target* t, const mrl_lattice_desc* lat, uint32_t*
 int32_t mrl_table_bytes(const mrl_target* t, const mrl_lattice_desc* lat, size_t* cost_bytes, size_t* argmin_bytes,
                         size_t* scratch_bytes) {
   if (!t) return fail(MRL_E_INVAL, "target is NULL");
-  Compiled c;
-  int32_t rc = compile(t->d, lat, c);
+  CompiledPtr cp;
+  int32_t rc = get_compiled(t->d, lat, cp);
   if (rc) return rc;
+  const Compiled& c = *cp;
   if (cost_bytes) *cost_bytes = c.n_specs * 8;
   if (argmin_bytes) *argmin_bytes = c.n_specs * 2;
   if (scratch_bytes) *scratch_bytes = fixed_layout(c).end + 2 * final_bytes(c.n_specs) + work_bytes(c.n_specs);
@@ -403,15 +443,16 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
   mrl_table* tab = new (std::nothrow) mrl_table;
   if (!tab) return fail(MRL_E_NOMEM, "host allocation failed");
   struct Guard { mrl_table* p; ~Guard() { delete p; } } guard{tab};
-  Compiled& c = tab->c;
-  int32_t rc = compile(t->d, lat, c);
+  int32_t rc = get_compiled(t->d, lat, tab->cp);
   if (rc) return rc;
-  DevParams& P = c.P;
+  const Compiled& c = *tab->cp;
+  tab->P = c.P;
+  DevParams& P = tab->P;
 
   if (P.kind == kKindF) {
     if (n_deps != 2 || !deps || !deps[0] || !deps[1]) return fail(MRL_E_INVAL, "a FUSED lattice needs deps = {MATMUL_ACCUM table, BIAS_ADD_RELU table}");
-    const Compiled& M = deps[0]->c;
-    const Compiled& E = deps[1]->c;
+    const Compiled& M = *deps[0]->cp;
+    const Compiled& E = *deps[1]->cp;
     if (M.P.kind != kKindM || E.P.kind != kKindE) return fail(MRL_E_INVAL, "deps must be {MATMUL_ACCUM, BIAS_ADD_RELU}");
     if (memcmp(&M.target, &t->d, sizeof t->d) || memcmp(&E.target, &t->d, sizeof t->d)) return fail(MRL_E_INVAL, "deps were solved for another target");
     for (int d = 1; d < 4; d++) if (M.sizes[d] != c.sizes[d]) return fail(MRL_E_INVAL, "MATMUL_ACCUM dep has other size lists");
@@ -568,7 +609,7 @@ void mrl_table_destroy(mrl_table* tab) { delete tab; }
 
 int32_t mrl_query(const mrl_table* tab, const mrl_coord* specs, size_t n, uint64_t* cost_out, uint16_t* rewrite_out) {
   if (!tab || (n && (!specs || !cost_out || !rewrite_out))) return fail(MRL_E_INVAL, "NULL argument");
-  const Geo& g = tab->c.geo;
+  const Geo& g = tab->cp->geo;
   std::vector<uint64_t> idx(std::min<size_t>(n, kQueryChunk));
   char* base = tab->scratch;
   for (size_t done = 0; done < n; done += kQueryChunk) {
@@ -596,7 +637,7 @@ int32_t mrl_query(const mrl_table* tab, const mrl_coord* specs, size_t n, uint64
 
 int32_t mrl_rewrite_decode(const mrl_table* tab, uint16_t id, mrl_rewrite* out) {
   if (!tab || !out) return fail(MRL_E_INVAL, "NULL argument");
-  const DevParams& P = tab->c.P;
+  const DevParams& P = tab->P;
   memset(out, 0, sizeof *out);
   if (id < P.move_base) { out->cls = 0; out->mk_index = id; return MRL_OK; }
   if (id < P.tile_base) {
@@ -608,7 +649,7 @@ int32_t mrl_rewrite_decode(const mrl_table* tab, uint16_t id, mrl_rewrite* out) 
   if (id < P.buf_id) {
     const uint32_t r = id - P.tile_base, d = r / P.maxs, j = r % P.maxs;
     if (j >= P.nsz[d]) return fail(MRL_E_RANGE, "rewrite id %u names no tile size", id);
-    out->cls = 2; out->operand_or_dim = (uint8_t)d; out->tile_size = tab->c.sizes[d][j];
+    out->cls = 2; out->operand_or_dim = (uint8_t)d; out->tile_size = tab->cp->sizes[d][j];
     return MRL_OK;
   }
   if (id == P.buf_id && P.kind == kKindF) { out->cls = 3; return MRL_OK; }
@@ -618,7 +659,7 @@ int32_t mrl_rewrite_decode(const mrl_table* tab, uint16_t id, mrl_rewrite* out) 
 int32_t mrl_coord_of_spec(const mrl_table* tab, const uint32_t shape[4], const uint8_t* levels, const uint8_t* layouts,
                           const uint8_t* dtypes, mrl_coord* out) {
   if (!tab || !shape || !levels || !out) return fail(MRL_E_INVAL, "NULL argument");
-  const Compiled& c = tab->c;
+  const Compiled& c = *tab->cp;
   memset(out, 0, sizeof *out);
   for (int d = 0; d < 4; d++) {
     auto it = std::lower_bound(c.sizes[d].begin(), c.sizes[d].end(), shape[d]);
@@ -642,7 +683,7 @@ int32_t mrl_emit_compressed(const mrl_table* tab, uint32_t which, mrl_box* out, 
   if (n_out) *n_out = n;
   if (!out) return MRL_OK;
   if (cap < n) return fail(MRL_E_BUFSZ, "box buffer holds %zu, %llu needed", cap, (unsigned long long)n);
-  const Geo& g = tab->c.geo;
+  const Geo& g = tab->cp->geo;
   const char* r = tab->scratch + tab->list_off[which];
   std::vector<uint32_t> fcell(n);
   std::vector<uint8_t> flen(n * 16);
@@ -670,8 +711,8 @@ int32_t mrl_emit_compressed(const mrl_table* tab, uint32_t which, mrl_box* out, 
 
 int32_t mrl_copy_dense(const mrl_table* tab, uint64_t* cost_host, uint16_t* argmin_host) {
   if (!tab) return fail(MRL_E_INVAL, "table is NULL");
-  if (cost_host) HIP_TRY(hipMemcpy(cost_host, tab->d_cost, tab->c.n_specs * 8, hipMemcpyDeviceToHost));
-  if (argmin_host) HIP_TRY(hipMemcpy(argmin_host, tab->d_arg, tab->c.n_specs * 2, hipMemcpyDeviceToHost));
+  if (cost_host) HIP_TRY(hipMemcpy(cost_host, tab->d_cost, tab->cp->n_specs * 8, hipMemcpyDeviceToHost));
+  if (argmin_host) HIP_TRY(hipMemcpy(argmin_host, tab->d_arg, tab->cp->n_specs * 2, hipMemcpyDeviceToHost));
   return MRL_OK;
 }
 

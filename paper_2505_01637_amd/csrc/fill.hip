@@ -42,6 +42,7 @@ constexpr uint32_t kSmallCap = 512;    // tasks a wave's LDS slice holds in the 
 constexpr uint32_t kBigBlock = 512;    // threads per deferred item in the second launch
 constexpr uint32_t kBigGrid = 1024;    // workgroups of the second launch (they loop over the deferred items)
 constexpr uint32_t kTileLds = 64;      // tile rewrites of the shape staged in LDS at a time
+constexpr uint32_t kWideBelow = 2048;  // levels with fewer shapes than this get 256 threads per shape
 
 struct Eval {
   uint64_t best;
@@ -342,7 +343,7 @@ __device__ __forceinline__ void solve_unit(const DevParams* __restrict__ P, cons
   const uint64_t group = (uint64_t)shape * P->G;
 
   // ---- 1. admissibility, compaction in rank order (rank-major level assignments, then pass) ----
-  constexpr int kIter = T == 64 ? 4 : 1;          // ncombo <= 256
+  constexpr int kIter = 256 / T < 1 ? 1 : 256 / T;   // ncombo <= 256
   uint32_t info[kIter];
 #pragma unroll
   for (int it = 0; it < kIter; it++) info[it] = it * T + tid < ncombo ? P->pos_info[it * T + tid] : 0u;
@@ -489,8 +490,10 @@ __device__ __forceinline__ void flush_counters(Counters* __restrict__ ctr, const
   if (tot.ovf) atomicOr(&ctr->overflow, 1u);
 }
 
-// First launch of a level: one wave per shape.
-__global__ __launch_bounds__(64) void fill_kernel(const DevParams* __restrict__ P,
+// First launch of a level: T threads per shape; one wave when the level has enough shapes to
+// fill the chip, four when it has few (then the shape's tasks are spread over more lanes).
+template <int T>
+__global__ __launch_bounds__(T) void fill_kernel(const DevParams* __restrict__ P,
                                                   const uint32_t* __restrict__ level_shapes,
                                                   uint32_t* __restrict__ big_list, uint32_t* __restrict__ big_count,
                                                   uint32_t cap, uint64_t* __restrict__ cost,
@@ -503,7 +506,7 @@ __global__ __launch_bounds__(64) void fill_kernel(const DevParams* __restrict__ 
   Eval tot;
   tot.n = 0; tot.ovf = 0;
   uint32_t n_adm = 0;
-  solve_unit<64, false>(P, L, cap, S, shape, 0, P->npass, big_list, big_count, cost, arg, tot, n_adm);
+  solve_unit<T, false>(P, L, cap, S, shape, 0, P->npass, big_list, big_count, cost, arg, tot, n_adm);
   flush_counters(ctr, tot, n_adm);
 }
 
@@ -552,8 +555,12 @@ void launch_fill_level(const DevParams* P, uint32_t npass, uint32_t G, uint32_t 
                        Counters* ctr, hipStream_t stream) {
   if (n_shapes == 0) return;
   const uint32_t small_cap = G < kSmallCap ? G : kSmallCap;
-  hipLaunchKernelGGL(fill_kernel, dim3(n_shapes), dim3(64), unit_lds_bytes(small_cap, npass), stream, P, level_shapes,
-                     big_list, big_count, small_cap, cost, arg, ctr);
+  if (n_shapes >= kWideBelow)
+    hipLaunchKernelGGL(fill_kernel<64>, dim3(n_shapes), dim3(64), unit_lds_bytes(small_cap, npass), stream, P,
+                       level_shapes, big_list, big_count, small_cap, cost, arg, ctr);
+  else
+    hipLaunchKernelGGL(fill_kernel<256>, dim3(n_shapes), dim3(256), unit_lds_bytes(small_cap, npass), stream, P,
+                       level_shapes, big_list, big_count, small_cap, cost, arg, ctr);
   if (G > small_cap) {
     const uint32_t units = n_shapes * npass;
     hipLaunchKernelGGL(fill_big_kernel, dim3(units < kBigGrid ? units : kBigGrid), dim3(kBigBlock),

@@ -48,7 +48,7 @@ size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 struct Compiled {
   DevParams P;
   std::vector<TileEntry> tiles;
-  std::vector<uint32_t> level_shapes;     // shapes grouped by dependency level
+  std::vector<uint32_t> shape_level;      // dependency level of every shape
   std::vector<uint32_t> level_off;        // [n_levels + 1]
   std::vector<uint32_t> sizes[4];
   Geo geo;
@@ -64,7 +64,7 @@ struct Compiled {
 
 // Offsets of the fixed part of the scratch buffer.
 struct FixedLayout {
-  size_t counters, params, tiles, level_shapes, mk_entry, big_list, big_count, maskD, maskC, lineD, lineC, prefD, prefC, tile_tmp, totals,
+  size_t counters, params, tiles, shape_level, level_off, mk_entry, list_whole, list_slice, list_wide, list_cnt, fitmap, maskD, maskC, lineD, lineC, prefD, prefC, tile_tmp, totals,
       q_idx, q_cost, q_arg, end;
   uint32_t n_words;
 };
@@ -77,10 +77,14 @@ FixedLayout fixed_layout(const Compiled& c) {
   f.counters = take(sizeof(Counters));
   f.params = take(sizeof(DevParams));
   f.tiles = take(c.tiles.size() * sizeof(TileEntry) + 8);
-  f.level_shapes = take(c.level_shapes.size() * 4);
+  f.shape_level = take(c.shape_level.size() * 4);
+  f.level_off = take(c.level_off.size() * 4);
   f.mk_entry = take(c.mk_entry.size());
-  f.big_list = take((size_t)c.n_shapes * c.P.npass * 4);
-  f.big_count = take(c.level_off.size() * 4);
+  f.list_whole = take((size_t)c.n_shapes * 4);
+  f.list_slice = take((size_t)c.n_shapes * c.P.npass * 4);
+  f.list_wide = take((size_t)c.n_shapes * c.P.npass * 4);
+  f.list_cnt = take(3 * c.level_off.size() * 4);
+  f.fitmap = take((size_t)f.n_words * 8 + 16);
   f.maskD = take((size_t)f.n_words * 8);
   f.maskC = take((size_t)f.n_words * 8);
   {
@@ -298,20 +302,15 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
       }
     n_lev += mx;
   }
-  std::vector<uint32_t> lev(c.n_shapes);
+  c.shape_level.resize(c.n_shapes);
   c.level_off.assign(n_lev + 1, 0);
   for (uint32_t sh = 0; sh < c.n_shapes; sh++) {
     uint32_t r = sh, l = 0;
     for (int d = 0; d < 4; d++) { l += chain[d][r / P.shape_stride[d]]; r %= P.shape_stride[d]; }
-    lev[sh] = l;
+    c.shape_level[sh] = l;
     c.level_off[l + 1]++;
   }
   for (uint32_t l = 0; l < n_lev; l++) c.level_off[l + 1] += c.level_off[l];
-  c.level_shapes.resize(c.n_shapes);
-  {
-    std::vector<uint32_t> cur(c.level_off.begin(), c.level_off.end() - 1);
-    for (uint32_t sh = 0; sh < c.n_shapes; sh++) c.level_shapes[cur[lev[sh]]++] = sh;
-  }
 
   // coordinate geometry and merge order: size axes innermost first, then level
   // axes, layout bits, dtype bits, each from the last to the first
@@ -476,30 +475,46 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
   Counters* d_ctr = (Counters*)(base + f.counters);
   DevParams* d_P = (DevParams*)(base + f.params);
   P.tiles = (const TileEntry*)(base + f.tiles);
-  uint32_t* d_level_shapes = (uint32_t*)(base + f.level_shapes);
-  uint32_t* d_big_list = (uint32_t*)(base + f.big_list);
-  uint32_t* d_big_count = (uint32_t*)(base + f.big_count);
+  const uint32_t n_lev = (uint32_t)c.level_off.size() - 1;
+  uint32_t* d_shape_level = (uint32_t*)(base + f.shape_level);
+  uint32_t* d_level_off = (uint32_t*)(base + f.level_off);
+  uint32_t* d_list_whole = (uint32_t*)(base + f.list_whole);
+  uint32_t* d_list_slice = (uint32_t*)(base + f.list_slice);
+  uint32_t* d_list_wide = (uint32_t*)(base + f.list_wide);
+  uint32_t* d_list_cnt = (uint32_t*)(base + f.list_cnt);
+  uint32_t* d_fitmap = (uint32_t*)(base + f.fitmap);
   P.mk_entry = (const uint8_t*)(base + f.mk_entry);
   HIP_TRY(hipMemsetAsync(d_ctr, 0, sizeof(Counters), st));
-  HIP_TRY(hipMemsetAsync(d_big_count, 0, c.level_off.size() * 4, st));
   HIP_TRY(hipMemcpyAsync((void*)P.mk_entry, c.mk_entry.data(), c.mk_entry.size(), hipMemcpyHostToDevice, st));
   HIP_TRY(hipMemcpyAsync(d_P, &P, sizeof P, hipMemcpyHostToDevice, st));
   if (!c.tiles.empty())
     HIP_TRY(hipMemcpyAsync((void*)P.tiles, c.tiles.data(), c.tiles.size() * sizeof(TileEntry), hipMemcpyHostToDevice, st));
-  HIP_TRY(hipMemcpyAsync(d_level_shapes, c.level_shapes.data(), c.level_shapes.size() * 4, hipMemcpyHostToDevice, st));
+  HIP_TRY(hipMemcpyAsync(d_shape_level, c.shape_level.data(), c.shape_level.size() * 4, hipMemcpyHostToDevice, st));
+  HIP_TRY(hipMemcpyAsync(d_level_off, c.level_off.data(), c.level_off.size() * 4, hipMemcpyHostToDevice, st));
 
   hipEvent_t ev[3];
   for (auto& e : ev) HIP_TRY(hipEventCreate(&e));
   struct EvGuard { hipEvent_t* e; ~EvGuard() { for (int i = 0; i < 3; i++) (void)hipEventDestroy(e[i]); } } evg{ev};
 
   // ---- fill: one launch per dependency level ----
+  // ---- fill: plan, then one launch (or two) per dependency level ----
   HIP_TRY(hipEventRecord(ev[0], st));
+  HIP_TRY(hipMemsetAsync(d_list_cnt, 0, 3 * (size_t)n_lev * 4, st));
+  HIP_TRY(hipMemsetAsync(d_fitmap, 0, (size_t)f.n_words * 8 + 16, st));
+  launch_plan(d_P, c.n_shapes, P.G, d_shape_level, d_level_off, n_lev, d_list_whole, d_list_slice, d_list_wide, d_list_cnt,
+              d_fitmap, d_ctr, st);
+  std::vector<uint32_t> cnt(3 * (size_t)n_lev);
+  HIP_TRY(hipMemcpyAsync(cnt.data(), d_list_cnt, cnt.size() * 4, hipMemcpyDeviceToHost, st));
   launch_fill_ones(tab->d_cost, c.n_specs * 8, st);
   launch_fill_ones(tab->d_arg, c.n_specs * 2, st);
-  const uint32_t n_lev = (uint32_t)c.level_off.size() - 1;
+  HIP_TRY(hipStreamSynchronize(st));
   for (uint32_t l = 0; l < n_lev; l++) {
-    launch_fill_level(d_P, P.npass, P.G, c.max_task, d_level_shapes + c.level_off[l], c.level_off[l + 1] - c.level_off[l],
-                      d_big_list + (size_t)c.level_off[l] * P.npass, d_big_count + l, tab->d_cost, tab->d_arg, d_ctr, st);
+    const uint32_t first = c.level_off[l];
+    if (cnt[l] > c.level_off[l + 1] - first || cnt[n_lev + l] + cnt[2 * n_lev + l] > (c.level_off[l + 1] - first) * P.npass)
+      return fail(MRL_E_HIP, "internal error: work lists of level %u overflow", l);
+    launch_fill_level(d_P, P.npass, P.G, c.max_task, d_list_whole + first, cnt[l], d_list_slice + (size_t)first * P.npass,
+                      cnt[n_lev + l], d_list_wide + (size_t)first * P.npass, cnt[2 * n_lev + l], tab->d_cost, tab->d_arg,
+                      d_ctr, st);
   }
   HIP_TRY(hipGetLastError());
   HIP_TRY(hipEventRecord(ev[1], st));
@@ -515,7 +530,7 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
   auto axis_sizes = [&](uint32_t a) -> const uint32_t* { return a < 4 ? (const uint32_t*)((char*)d_P + offsetof(DevParams, sizes) + a * sizeof(uint32_t) * kMaxSizes) : nullptr; };
   if (g.stride[a0] % 64 != 0) { launch_zero_words(maskL[0], f.n_words, st); launch_zero_words(maskL[1], f.n_words, st); }
   unsigned long long* lineL[2] = {(unsigned long long*)(base + f.lineD), (unsigned long long*)(base + f.lineC)};
-  launch_head_flags(g, a0, tab->d_cost, tab->d_arg, axis_sizes(a0), maskL[0], maskL[1], lineL[0], lineL[1], st);
+  launch_head_flags(g, a0, tab->d_cost, tab->d_arg, d_fitmap, axis_sizes(a0), maskL[0], maskL[1], lineL[0], lineL[1], st);
   scan_mask_words(maskL[0], f.n_words, tile_tmp, prefL[0], d_tot + 0, st);
   scan_mask_words(maskL[1], f.n_words, tile_tmp, prefL[1], d_tot + 1, st);
   uint32_t h_tot[4] = {0, 0, 0, 0};
@@ -587,6 +602,7 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
   Counters h_ctr;
   HIP_TRY(hipMemcpyAsync(&h_ctr, d_ctr, sizeof h_ctr, hipMemcpyDeviceToHost, st));
   HIP_TRY(hipStreamSynchronize(st));
+  if (h_ctr.overflow & 2u) return fail(MRL_E_HIP, "internal error: a work item exceeded its LDS slice");
   if (h_ctr.overflow) return fail(MRL_E_OVERFLOW, "a finite cost reached 2^62");
   if (stats) {
     memset(stats, 0, sizeof *stats);

@@ -13,13 +13,17 @@ struct Geo {
   uint32_t ext[16], stride[16];
 };
 
-void launch_fill_level(const DevParams* P, uint32_t npass, uint32_t G, uint32_t max_task, const uint32_t* level_shapes,
-                       uint32_t n_shapes, uint32_t* big_list, uint32_t* big_count, uint64_t* cost, uint16_t* arg,
-                       Counters* ctr, hipStream_t stream);
+void launch_plan(const DevParams* P, uint32_t n_shapes, uint32_t G, const uint32_t* shape_level, const uint32_t* level_off,
+                 uint32_t n_levels, uint32_t* list_whole, uint32_t* list_slice, uint32_t* list_wide, uint32_t* list_cnt,
+                 uint32_t* fitmap, Counters* ctr, hipStream_t stream);
+void launch_fill_level(const DevParams* P, uint32_t npass, uint32_t G, uint32_t max_task, const uint32_t* list_whole,
+                       uint32_t n_whole, const uint32_t* list_slice, uint32_t n_slice, const uint32_t* list_wide,
+                       uint32_t n_wide, uint64_t* cost, uint16_t* arg, Counters* ctr, hipStream_t stream);
 
 void launch_fill_ones(void* p, size_t bytes, hipStream_t stream);
 void launch_zero_words(unsigned long long* p, uint32_t n, hipStream_t st);
-void launch_head_flags(const Geo& g, uint32_t a0, const uint64_t* cost, const uint16_t* arg, const uint32_t* axis_sizes,
+void launch_head_flags(const Geo& g, uint32_t a0, const uint64_t* cost, const uint16_t* arg, const uint32_t* fitmap,
+                       const uint32_t* axis_sizes,
                        unsigned long long* maskD, unsigned long long* maskC, unsigned long long* lineD,
                        unsigned long long* lineC, hipStream_t st);
 void scan_mask_words(const unsigned long long* mask, uint32_t n_words, uint32_t* tile_tmp, uint32_t* prefix,

@@ -10,7 +10,9 @@
 //
 // GPU formulation.
 //   pass 0  (dense, first axis a0): one thread walks a line of cells along a0
-//           and flags the cell where the value changes; consecutive lanes hold
+//           and flags the cell where the value changes (cells whose operands
+//           do not fit their levels hold (INF, NONE) by construction and are
+//           not read: a bit map from the fill says which cells those are); consecutive lanes hold
 //           consecutive cells, so the flags of 64 cells are one ballot = one
 //           word of a bit mask in table order.  A prefix sum of the popcounts
 //           gives every run (= box) its index in table order.
@@ -42,6 +44,7 @@ template <bool BALLOT>
 __global__ __launch_bounds__(256) void head_flags_kernel(Geo g, uint32_t a0,
                                                          const uint64_t* __restrict__ cost,
                                                          const uint16_t* __restrict__ arg,
+                                                         const uint32_t* __restrict__ fitmap,
                                                          const uint32_t* __restrict__ axis_sizes,
                                                          unsigned long long* __restrict__ maskD,
                                                          unsigned long long* __restrict__ maskC,
@@ -59,8 +62,9 @@ __global__ __launch_bounds__(256) void head_flags_kernel(Geo g, uint32_t a0,
     const uint32_t cell = base + j * s0;
     bool hd = false, hc = false;
     if (active) {
-      const uint64_t c = cost[cell];
-      const uint32_t a = arg[cell];
+      const bool fits = (fitmap[cell >> 5] >> (cell & 31u)) & 1u;
+      const uint64_t c = fits ? cost[cell] : kInf;
+      const uint32_t a = fits ? arg[cell] : kNone;
       const uint32_t sz = axis_sizes ? axis_sizes[j] : 1u;
       hd = j == 0 || a != pa;
       hc = j == 0 || !norm_equal(c, sz, pc, ps);
@@ -317,17 +321,18 @@ __global__ __launch_bounds__(256) void absorb_kernel(uint32_t a, uint8_t stamp, 
   blen_bytes[(size_t)b * 16 + a] = (uint8_t)tot;
 }
 
-void launch_head_flags(const Geo& g, uint32_t a0, const uint64_t* cost, const uint16_t* arg, const uint32_t* axis_sizes,
+void launch_head_flags(const Geo& g, uint32_t a0, const uint64_t* cost, const uint16_t* arg, const uint32_t* fitmap,
+                       const uint32_t* axis_sizes,
                        unsigned long long* maskD, unsigned long long* maskC, unsigned long long* lineD,
                        unsigned long long* lineC, hipStream_t st) {
   const uint32_t n_lines = g.n / g.ext[a0];
   const uint32_t blocks = (n_lines + 255) / 256;
   if (g.stride[a0] % 64 == 0)
-    hipLaunchKernelGGL(head_flags_kernel<true>, dim3(blocks), dim3(256), 0, st, g, a0, cost, arg, axis_sizes, maskD, maskC,
-                       lineD, lineC);
+    hipLaunchKernelGGL(head_flags_kernel<true>, dim3(blocks), dim3(256), 0, st, g, a0, cost, arg, fitmap, axis_sizes, maskD,
+                       maskC, lineD, lineC);
   else
-    hipLaunchKernelGGL(head_flags_kernel<false>, dim3(blocks), dim3(256), 0, st, g, a0, cost, arg, axis_sizes, maskD, maskC,
-                       lineD, lineC);
+    hipLaunchKernelGGL(head_flags_kernel<false>, dim3(blocks), dim3(256), 0, st, g, a0, cost, arg, fitmap, axis_sizes, maskD,
+                       maskC, lineD, lineC);
 }
 
 void launch_make_boxes(const Geo& g, uint32_t a0, const unsigned long long* mask, const uint32_t* prefix,

@@ -25,12 +25,14 @@
 //      id order, keeping the first strict minimum (= lowest id among ties),
 //      then takes the parked candidate if strictly lower (its ids are higher).
 //      Results go to LDS (for later ranks) and to the table.
-// A shape with more tasks than the wave's LDS slice holds is appended to a
-// list, one item per value of the passive level axis (the intermediate's level
-// of a fused Spec: such slices are independent), and redone by a second launch
-// with a whole workgroup per item and a slice sized for the largest possible
-// item.  Nothing is reduced across lanes and no result depends on which wave
-// handles a shape: the table is deterministic.
+// Before the first level a plan kernel counts, per shape and per value of the
+// passive level axis (the intermediate's level of a fused Spec: such slices are
+// independent), the entries that fit, and sorts the work into three lists per
+// dependency level: shapes one wave can hold whole, slices one wave can hold,
+// and slices that get a whole workgroup and an LDS slice sized for the largest
+// possible slice.  Shapes in which nothing fits get no work at all.  Nothing is
+// reduced across lanes and no result depends on which wave handles an item:
+// the table is deterministic.
 #include <hip/hip_runtime.h>
 #include "compress.h"
 #include "dev_params.h"
@@ -38,9 +40,8 @@
 namespace mrl {
 
 constexpr int kBatch = 8;              // sub-Spec costs fetched together before they are compared
-constexpr uint32_t kSmallCap = 512;    // tasks a wave's LDS slice holds in the first launch
-constexpr uint32_t kBigBlock = 512;    // threads per deferred item in the second launch
-constexpr uint32_t kBigGrid = 1024;    // workgroups of the second launch (they loop over the deferred items)
+constexpr uint32_t kSmallCap = 512;    // tasks a wave's LDS slice holds
+constexpr uint32_t kBigBlock = 512;    // threads per item that does not fit a wave's slice
 constexpr uint32_t kTileLds = 64;      // tile rewrites of the shape staged in LDS at a time
 constexpr uint32_t kWideBelow = 2048;  // levels with fewer shapes than this get 256 threads per shape
 
@@ -329,17 +330,14 @@ __device__ __forceinline__ void task_moves(const DevParams* __restrict__ P, cons
     }
 }
 
-// One unit = passes [pass0, pass0 + np) of one shape, handled by T threads
-// (T = 64: the wave of the first launch, all passes; T = kBigBlock: the second launch, one pass).
-template <int T, bool BIG>
+// One unit = passes [pass0, pass0 + np) of one shape, handled by T threads.
+template <int T>
 __device__ __forceinline__ void solve_unit(const DevParams* __restrict__ P, const UnitLds& L, uint32_t cap,
                                            const Shape& S, uint32_t shape, uint32_t pass0, uint32_t np,
-                                           uint32_t* __restrict__ big_list, uint32_t* __restrict__ big_count,
-                                           uint64_t* __restrict__ cost, uint16_t* __restrict__ arg,
-                                           Eval& tot, uint32_t& n_adm) {
+                                           uint64_t* __restrict__ cost, uint16_t* __restrict__ arg, Eval& tot) {
   const uint32_t tid = T == 64 ? (threadIdx.x & 63u) : threadIdx.x;
   const uint32_t lane = threadIdx.x & 63u;
-  const uint32_t npass = P->npass, ncombo = P->ncombo;
+  const uint32_t ncombo = P->ncombo;
   const uint64_t group = (uint64_t)shape * P->G;
 
   // ---- 1. admissibility, compaction in rank order (rank-major level assignments, then pass) ----
@@ -398,14 +396,8 @@ __device__ __forceinline__ void solve_unit(const DevParams* __restrict__ P, cons
         }
     }
   }
-  if (n_task == 0) return;          // nothing of this shape fits anywhere: the table already says so
-  if (!BIG) {
-    n_adm += tid == 0 ? n_task : 0;
-    if (n_task > cap) {             // too many tasks for the wave's LDS slice: leave the shape to the second launch
-      if (tid < npass) big_list[atomicAdd(big_count, 1u)] = shape * npass + tid;
-      return;
-    }
-  }
+  if (n_task == 0) return;          // nothing here fits anywhere: the table already says so
+  if (n_task > cap) { tot.ovf |= 2u; return; }   // the plan guarantees this cannot happen; reported as an internal error
   unit_sync<T>();
   if (tid <= P->nranks)
     L.r_off[tid] = tid == P->nranks ? n_task : L.c_info[pass0 << 8 | (P->pos_info[P->rank_off[tid]] & 0xFFu)] >> 16;
@@ -479,58 +471,122 @@ __device__ __forceinline__ void solve_unit(const DevParams* __restrict__ P, cons
   }
 }
 
-__device__ __forceinline__ void flush_counters(Counters* __restrict__ ctr, const Eval& tot, uint32_t n_adm) {
+__device__ __forceinline__ void flush_counters(Counters* __restrict__ ctr, const Eval& tot) {
   uint32_t n_rw = tot.n;
 #pragma unroll
   for (int d = 32; d > 0; d >>= 1) n_rw += __shfl_down(n_rw, d, 64);
-  if ((threadIdx.x & 63u) == 0) {
-    if (n_rw) atomicAdd(&ctr->n_rewrites, (unsigned long long)n_rw);
-    if (n_adm) atomicAdd(&ctr->n_admissible, (unsigned long long)n_adm);
-  }
-  if (tot.ovf) atomicOr(&ctr->overflow, 1u);
+  if ((threadIdx.x & 63u) == 0 && n_rw) atomicAdd(&ctr->n_rewrites, (unsigned long long)n_rw);
+  if (tot.ovf) atomicOr(&ctr->overflow, tot.ovf);
 }
 
-// First launch of a level: T threads per shape; one wave when the level has enough shapes to
-// fill the chip, four when it has few (then the shape's tasks are spread over more lanes).
+// Plan: one wave per shape.  Counts the entries that fit per passive-level slice, marks them in
+// a bit map in table order (bit = cell; read by the compression pass) and appends the shape, or
+// its non-empty slices, to the work lists of its dependency level.
+__global__ __launch_bounds__(64) void plan_kernel(const DevParams* __restrict__ P,
+                                                  const uint32_t* __restrict__ shape_level,
+                                                  const uint32_t* __restrict__ level_off, uint32_t n_levels,
+                                                  uint32_t cap_whole, uint32_t cap_slice,
+                                                  uint32_t* __restrict__ list_whole, uint32_t* __restrict__ list_slice,
+                                                  uint32_t* __restrict__ list_wide, uint32_t* __restrict__ list_cnt,
+                                                  uint32_t* __restrict__ fitmap, Counters* __restrict__ ctr) {
+  __shared__ uint32_t fit[16];
+  const uint32_t shape = blockIdx.x, lane = threadIdx.x;
+  const uint32_t npass = P->npass, ncombo = P->ncombo, V = P->V, nb = npass * V;
+  Shape S;
+  load_shape(P, shape, S);
+  build_fit(P, S, fit);
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  uint32_t f[4];
+#pragma unroll
+  for (int l = 0; l < 4; l++) f[l] = fit[l];
+  const uint64_t group = (uint64_t)shape * P->G;
+  uint32_t cnt[4] = {0, 0, 0, 0};
+  for (uint32_t pc = lane; pc < ncombo; pc += 64) {
+    const uint32_t info = P->pos_info[pc];
+    unsigned long long bits = 0;
+#pragma unroll
+    for (int ps = 0; ps < 4; ps++)
+      if ((uint32_t)ps < npass) {
+        const uint32_t m = admissible_mask(P, fit, f, info, ps);
+        cnt[ps] += __popc(m);
+        bits |= (unsigned long long)m << (ps * V);
+      }
+    if (bits) {
+      const uint64_t cell0 = group + (uint64_t)entry_offset(P, info & 0xFFu, 0);   // pass 0, variant 0 of this assignment
+      const uint32_t sh = (uint32_t)(cell0 & 31u);
+      uint32_t* w = fitmap + (cell0 >> 5);
+      atomicOr(w, (uint32_t)(bits << sh));
+      if (sh + nb > 32) {
+        atomicOr(w + 1, (uint32_t)(bits >> (32 - sh)));
+        if (sh + nb > 64) atomicOr(w + 2, (uint32_t)(bits >> (64 - sh)));
+      }
+    }
+  }
+  uint32_t total = 0;
+#pragma unroll
+  for (int ps = 0; ps < 4; ps++) {
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) cnt[ps] += __shfl_down(cnt[ps], d, 64);
+    cnt[ps] = __shfl(cnt[ps], 0, 64);
+    total += cnt[ps];
+  }
+  if (lane == 0 && total) {
+    atomicAdd(&ctr->n_admissible, (unsigned long long)total);
+    const uint32_t lv = shape_level[shape], first = level_off[lv];
+    if (total <= cap_whole) {
+      list_whole[first + atomicAdd(&list_cnt[lv], 1u)] = shape;
+    } else {
+      for (uint32_t ps = 0; ps < npass; ps++) {
+        if (cnt[ps] == 0) continue;
+        if (cnt[ps] <= cap_slice) list_slice[first * npass + atomicAdd(&list_cnt[n_levels + lv], 1u)] = shape * npass + ps;
+        else list_wide[first * npass + atomicAdd(&list_cnt[2 * n_levels + lv], 1u)] = shape * npass + ps;
+      }
+    }
+  }
+}
+
+// One dependency level, the items a single wave can hold: first the whole shapes, then the slices.
+// T threads per item: one wave when the level has enough items to fill the chip, four when it has
+// few (then an item's tasks are spread over more lanes).
 template <int T>
 __global__ __launch_bounds__(T) void fill_kernel(const DevParams* __restrict__ P,
-                                                  const uint32_t* __restrict__ level_shapes,
-                                                  uint32_t* __restrict__ big_list, uint32_t* __restrict__ big_count,
-                                                  uint32_t cap, uint64_t* __restrict__ cost,
-                                                  uint16_t* __restrict__ arg, Counters* __restrict__ ctr) {
+                                                 const uint32_t* __restrict__ list_whole, uint32_t n_whole,
+                                                 const uint32_t* __restrict__ list_slice, uint32_t cap,
+                                                 uint64_t* __restrict__ cost, uint16_t* __restrict__ arg,
+                                                 Counters* __restrict__ ctr) {
   extern __shared__ __align__(16) unsigned char smem[];
-  const uint32_t shape = level_shapes[blockIdx.x];
+  uint32_t shape, pass0, np;
+  if (blockIdx.x < n_whole) {
+    shape = list_whole[blockIdx.x]; pass0 = 0; np = P->npass;
+  } else {
+    const uint32_t unit = list_slice[blockIdx.x - n_whole];
+    shape = unit / P->npass; pass0 = unit - shape * P->npass; np = 1;
+  }
   Shape S;
   load_shape(P, shape, S);
   const UnitLds L = carve(smem, cap, P->npass);
   Eval tot;
   tot.n = 0; tot.ovf = 0;
-  uint32_t n_adm = 0;
-  solve_unit<T, false>(P, L, cap, S, shape, 0, P->npass, big_list, big_count, cost, arg, tot, n_adm);
-  flush_counters(ctr, tot, n_adm);
+  solve_unit<T>(P, L, cap, S, shape, pass0, np, cost, arg, tot);
+  flush_counters(ctr, tot);
 }
 
-// Second launch of a level: the deferred items, one workgroup of kBigBlock threads each.
+// The slices too large for a wave's LDS slice: one workgroup of kBigBlock threads each.
 __global__ __launch_bounds__(kBigBlock) void fill_big_kernel(const DevParams* __restrict__ P,
-                                                             uint32_t* __restrict__ big_list,
-                                                             uint32_t* __restrict__ big_count, uint32_t cap,
+                                                             const uint32_t* __restrict__ list_wide, uint32_t cap,
                                                              uint64_t* __restrict__ cost, uint16_t* __restrict__ arg,
                                                              Counters* __restrict__ ctr) {
   extern __shared__ __align__(16) unsigned char smem[];
   const UnitLds L = carve(smem, cap, P->npass);
   Eval tot;
   tot.n = 0; tot.ovf = 0;
-  uint32_t n_adm = 0;
-  const uint32_t n_units = *big_count;
-  for (uint32_t u = blockIdx.x; u < n_units; u += gridDim.x) {
-    const uint32_t unit = big_list[u];
-    const uint32_t shape = unit / P->npass, pass = unit % P->npass;
-    Shape S;
-    load_shape(P, shape, S);
-    __syncthreads();            // the previous item's LDS is dead
-    solve_unit<kBigBlock, true>(P, L, cap, S, shape, pass, 1, big_list, big_count, cost, arg, tot, n_adm);
-  }
-  flush_counters(ctr, tot, n_adm);
+  const uint32_t unit = list_wide[blockIdx.x];
+  const uint32_t shape = unit / P->npass, pass = unit % P->npass;
+  Shape S;
+  load_shape(P, shape, S);
+  solve_unit<kBigBlock>(P, L, cap, S, shape, pass, 1, cost, arg, tot);
+  flush_counters(ctr, tot);
 }
 
 // (INF, NONE) are all-ones bytes: stream 16 bytes per lane and store over both tables.
@@ -549,23 +605,30 @@ void launch_fill_ones(void* p, size_t bytes, hipStream_t stream) {
   if (bytes % 16) (void)hipMemsetAsync((char*)p + n16 * 16, 0xFF, bytes % 16, stream);
 }
 
-// One dependency level: every shape by the first kernel, then the items it deferred.
-void launch_fill_level(const DevParams* P, uint32_t npass, uint32_t G, uint32_t max_task, const uint32_t* level_shapes,
-                       uint32_t n_shapes, uint32_t* big_list, uint32_t* big_count, uint64_t* cost, uint16_t* arg,
-                       Counters* ctr, hipStream_t stream) {
-  if (n_shapes == 0) return;
-  const uint32_t small_cap = G < kSmallCap ? G : kSmallCap;
-  if (n_shapes >= kWideBelow)
-    hipLaunchKernelGGL(fill_kernel<64>, dim3(n_shapes), dim3(64), unit_lds_bytes(small_cap, npass), stream, P,
-                       level_shapes, big_list, big_count, small_cap, cost, arg, ctr);
-  else
-    hipLaunchKernelGGL(fill_kernel<256>, dim3(n_shapes), dim3(256), unit_lds_bytes(small_cap, npass), stream, P,
-                       level_shapes, big_list, big_count, small_cap, cost, arg, ctr);
-  if (G > small_cap) {
-    const uint32_t units = n_shapes * npass;
-    hipLaunchKernelGGL(fill_big_kernel, dim3(units < kBigGrid ? units : kBigGrid), dim3(kBigBlock),
-                       unit_lds_bytes(max_task, npass), stream, P, big_list, big_count, max_task, cost, arg, ctr);
-  }
+uint32_t fill_wave_cap(uint32_t G) { return G < kSmallCap ? G : kSmallCap; }
+
+void launch_plan(const DevParams* P, uint32_t n_shapes, uint32_t G, const uint32_t* shape_level, const uint32_t* level_off,
+                 uint32_t n_levels, uint32_t* list_whole, uint32_t* list_slice, uint32_t* list_wide, uint32_t* list_cnt,
+                 uint32_t* fitmap, Counters* ctr, hipStream_t stream) {
+  const uint32_t cap = fill_wave_cap(G);
+  hipLaunchKernelGGL(plan_kernel, dim3(n_shapes), dim3(64), 0, stream, P, shape_level, level_off, n_levels, cap, cap,
+                     list_whole, list_slice, list_wide, list_cnt, fitmap, ctr);
+}
+
+// One dependency level: the items a wave can hold, then the wide ones.
+void launch_fill_level(const DevParams* P, uint32_t npass, uint32_t G, uint32_t max_task, const uint32_t* list_whole,
+                       uint32_t n_whole, const uint32_t* list_slice, uint32_t n_slice, const uint32_t* list_wide,
+                       uint32_t n_wide, uint64_t* cost, uint16_t* arg, Counters* ctr, hipStream_t stream) {
+  const uint32_t cap = fill_wave_cap(G), n = n_whole + n_slice;
+  if (n >= kWideBelow)
+    hipLaunchKernelGGL(fill_kernel<64>, dim3(n), dim3(64), unit_lds_bytes(cap, npass), stream, P, list_whole, n_whole,
+                       list_slice, cap, cost, arg, ctr);
+  else if (n)
+    hipLaunchKernelGGL(fill_kernel<256>, dim3(n), dim3(256), unit_lds_bytes(cap, npass), stream, P, list_whole, n_whole,
+                       list_slice, cap, cost, arg, ctr);
+  if (n_wide)
+    hipLaunchKernelGGL(fill_big_kernel, dim3(n_wide), dim3(kBigBlock), unit_lds_bytes(max_task, npass), stream, P,
+                       list_wide, max_task, cost, arg, ctr);
 }
 
 }  // namespace mrl

@@ -372,6 +372,28 @@ int32_t get_compiled(const mrl_target_desc& T, const mrl_lattice_desc* L, Compil
   return MRL_OK;
 }
 
+// A second stream (default priority, non-blocking) for work that is independent of what runs on
+// the caller's stream: the (INF, NONE) pre-fill beside the plan kernel, the wide items of a
+// dependency level beside its other items.  Created once per process; events likewise.
+struct Aux {
+  hipStream_t stream = nullptr;
+  std::vector<hipEvent_t> events;
+};
+
+int32_t get_aux(size_t n_events, Aux*& out) {
+  static Aux aux;
+  static std::mutex mu;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!aux.stream) HIP_TRY(hipStreamCreateWithFlags(&aux.stream, hipStreamNonBlocking));
+  while (aux.events.size() < n_events) {
+    hipEvent_t e;
+    HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+    aux.events.push_back(e);
+  }
+  out = &aux;
+  return MRL_OK;
+}
+
 }  // namespace
 
 struct mrl_table {
@@ -498,23 +520,44 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
 
   // ---- fill: one launch per dependency level ----
   // ---- fill: plan, then one launch (or two) per dependency level ----
+  Aux* aux = nullptr;
+  rc = get_aux(2 * (size_t)n_lev + 2, aux);
+  if (rc) return rc;
+  size_t ev_used = 0;
+  hipStream_t s2 = aux->stream;
   HIP_TRY(hipEventRecord(ev[0], st));
+  // the pre-fill runs beside the plan kernel
+  HIP_TRY(hipEventRecord(aux->events[ev_used], st));
+  HIP_TRY(hipStreamWaitEvent(s2, aux->events[ev_used++], 0));
+  launch_fill_ones(tab->d_cost, c.n_specs * 8, s2);
+  launch_fill_ones(tab->d_arg, c.n_specs * 2, s2);
+  HIP_TRY(hipEventRecord(aux->events[ev_used], s2));
+  hipEvent_t prefill_done = aux->events[ev_used++];
   HIP_TRY(hipMemsetAsync(d_list_cnt, 0, 3 * (size_t)n_lev * 4, st));
   HIP_TRY(hipMemsetAsync(d_fitmap, 0, (size_t)f.n_words * 8 + 16, st));
   launch_plan(d_P, c.n_shapes, P.G, d_shape_level, d_level_off, n_lev, d_list_whole, d_list_slice, d_list_wide, d_list_cnt,
               d_fitmap, d_ctr, st);
   std::vector<uint32_t> cnt(3 * (size_t)n_lev);
   HIP_TRY(hipMemcpyAsync(cnt.data(), d_list_cnt, cnt.size() * 4, hipMemcpyDeviceToHost, st));
-  launch_fill_ones(tab->d_cost, c.n_specs * 8, st);
-  launch_fill_ones(tab->d_arg, c.n_specs * 2, st);
   HIP_TRY(hipStreamSynchronize(st));
+  HIP_TRY(hipStreamWaitEvent(st, prefill_done, 0));
   for (uint32_t l = 0; l < n_lev; l++) {
     const uint32_t first = c.level_off[l];
-    if (cnt[l] > c.level_off[l + 1] - first || cnt[n_lev + l] + cnt[2 * n_lev + l] > (c.level_off[l + 1] - first) * P.npass)
+    const uint32_t n_whole = cnt[l], n_slice = cnt[n_lev + l], n_wide = cnt[2 * n_lev + l];
+    if (n_whole > c.level_off[l + 1] - first || n_slice + n_wide > (c.level_off[l + 1] - first) * P.npass)
       return fail(MRL_E_HIP, "internal error: work lists of level %u overflow", l);
-    launch_fill_level(d_P, P.npass, P.G, c.max_task, d_list_whole + first, cnt[l], d_list_slice + (size_t)first * P.npass,
-                      cnt[n_lev + l], d_list_wide + (size_t)first * P.npass, cnt[2 * n_lev + l], tab->d_cost, tab->d_arg,
-                      d_ctr, st);
+    const bool fork = n_wide && (n_whole + n_slice);     // both kinds of items: run them side by side
+    if (fork) {
+      HIP_TRY(hipEventRecord(aux->events[ev_used], st));
+      HIP_TRY(hipStreamWaitEvent(s2, aux->events[ev_used++], 0));
+    }
+    launch_fill_level(d_P, P.npass, P.G, c.max_task, d_list_whole + first, n_whole, d_list_slice + (size_t)first * P.npass,
+                      n_slice, d_list_wide + (size_t)first * P.npass, n_wide, tab->d_cost, tab->d_arg, d_ctr, st,
+                      fork ? s2 : st);
+    if (fork) {
+      HIP_TRY(hipEventRecord(aux->events[ev_used], s2));
+      HIP_TRY(hipStreamWaitEvent(st, aux->events[ev_used++], 0));
+    }
   }
   HIP_TRY(hipGetLastError());
   HIP_TRY(hipEventRecord(ev[1], st));

@@ -615,10 +615,12 @@ void launch_plan(const DevParams* P, uint32_t n_shapes, uint32_t G, const uint32
                      list_whole, list_slice, list_wide, list_cnt, fitmap, ctr);
 }
 
-// One dependency level: the items a wave can hold, then the wide ones.
+// One dependency level: the items a wave can hold, and the wide ones (independent of each other:
+// the caller may give them a stream of their own).
 void launch_fill_level(const DevParams* P, uint32_t npass, uint32_t G, uint32_t max_task, const uint32_t* list_whole,
                        uint32_t n_whole, const uint32_t* list_slice, uint32_t n_slice, const uint32_t* list_wide,
-                       uint32_t n_wide, uint64_t* cost, uint16_t* arg, Counters* ctr, hipStream_t stream) {
+                       uint32_t n_wide, uint64_t* cost, uint16_t* arg, Counters* ctr, hipStream_t stream,
+                       hipStream_t wide_stream) {
   const uint32_t cap = fill_wave_cap(G), n = n_whole + n_slice;
   if (n >= kWideBelow)
     hipLaunchKernelGGL(fill_kernel<64>, dim3(n), dim3(64), unit_lds_bytes(cap, npass), stream, P, list_whole, n_whole,
@@ -627,7 +629,7 @@ void launch_fill_level(const DevParams* P, uint32_t npass, uint32_t G, uint32_t 
     hipLaunchKernelGGL(fill_kernel<256>, dim3(n), dim3(256), unit_lds_bytes(cap, npass), stream, P, list_whole, n_whole,
                        list_slice, cap, cost, arg, ctr);
   if (n_wide)
-    hipLaunchKernelGGL(fill_big_kernel, dim3(n_wide), dim3(kBigBlock), unit_lds_bytes(max_task, npass), stream, P,
+    hipLaunchKernelGGL(fill_big_kernel, dim3(n_wide), dim3(kBigBlock), unit_lds_bytes(max_task, npass), wide_stream, P,
                        list_wide, max_task, cost, arg, ctr);
 }
 

@@ -48,7 +48,7 @@ size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 struct Compiled {
   DevParams P;
   std::vector<TileEntry> tiles;
-  std::vector<uint32_t> shape_level;      // dependency level of every shape
+  std::vector<uint32_t> level_shapes;     // shapes grouped by dependency level, ascending inside a level
   std::vector<uint32_t> level_off;        // [n_levels + 1]
   std::vector<uint32_t> sizes[4];
   Geo geo;
@@ -64,7 +64,7 @@ struct Compiled {
 
 // Offsets of the fixed part of the scratch buffer.
 struct FixedLayout {
-  size_t counters, params, tiles, shape_level, level_off, mk_entry, list_whole, list_slice, list_wide, list_cnt, fitmap, maskD, maskC, lineD, lineC, prefD, prefC, tile_tmp, totals,
+  size_t counters, params, tiles, level_shapes, shape_class, level_off, mk_entry, list_whole, list_slice, list_wide, list_cnt, fitmap, maskD, maskC, lineD, lineC, prefD, prefC, tile_tmp, totals,
       q_idx, q_cost, q_arg, end;
   uint32_t n_words;
 };
@@ -77,7 +77,8 @@ FixedLayout fixed_layout(const Compiled& c) {
   f.counters = take(sizeof(Counters));
   f.params = take(sizeof(DevParams));
   f.tiles = take(c.tiles.size() * sizeof(TileEntry) + 8);
-  f.shape_level = take(c.shape_level.size() * 4);
+  f.level_shapes = take(c.level_shapes.size() * 4);
+  f.shape_class = take(c.level_shapes.size() * 4);
   f.level_off = take(c.level_off.size() * 4);
   f.mk_entry = take(c.mk_entry.size());
   f.list_whole = take((size_t)c.n_shapes * 4);
@@ -302,15 +303,20 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
       }
     n_lev += mx;
   }
-  c.shape_level.resize(c.n_shapes);
+  std::vector<uint32_t> lev(c.n_shapes);
   c.level_off.assign(n_lev + 1, 0);
   for (uint32_t sh = 0; sh < c.n_shapes; sh++) {
     uint32_t r = sh, l = 0;
     for (int d = 0; d < 4; d++) { l += chain[d][r / P.shape_stride[d]]; r %= P.shape_stride[d]; }
-    c.shape_level[sh] = l;
+    lev[sh] = l;
     c.level_off[l + 1]++;
   }
   for (uint32_t l = 0; l < n_lev; l++) c.level_off[l + 1] += c.level_off[l];
+  c.level_shapes.resize(c.n_shapes);
+  {
+    std::vector<uint32_t> cur(c.level_off.begin(), c.level_off.end() - 1);
+    for (uint32_t sh = 0; sh < c.n_shapes; sh++) c.level_shapes[cur[lev[sh]]++] = sh;
+  }
 
   // coordinate geometry and merge order: size axes innermost first, then level
   // axes, layout bits, dtype bits, each from the last to the first
@@ -373,8 +379,7 @@ int32_t get_compiled(const mrl_target_desc& T, const mrl_lattice_desc* L, Compil
 }
 
 // A second stream (default priority, non-blocking) for work that is independent of what runs on
-// the caller's stream: the (INF, NONE) pre-fill beside the plan kernel, the wide items of a
-// dependency level beside its other items.  Created once per process; events likewise.
+// the caller's stream: the wide items of a dependency level beside its other items.  Created once per process; events likewise.
 struct Aux {
   hipStream_t stream = nullptr;
   std::vector<hipEvent_t> events;
@@ -498,7 +503,8 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
   DevParams* d_P = (DevParams*)(base + f.params);
   P.tiles = (const TileEntry*)(base + f.tiles);
   const uint32_t n_lev = (uint32_t)c.level_off.size() - 1;
-  uint32_t* d_shape_level = (uint32_t*)(base + f.shape_level);
+  uint32_t* d_level_shapes = (uint32_t*)(base + f.level_shapes);
+  uint32_t* d_shape_class = (uint32_t*)(base + f.shape_class);
   uint32_t* d_level_off = (uint32_t*)(base + f.level_off);
   uint32_t* d_list_whole = (uint32_t*)(base + f.list_whole);
   uint32_t* d_list_slice = (uint32_t*)(base + f.list_slice);
@@ -511,7 +517,7 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
   HIP_TRY(hipMemcpyAsync(d_P, &P, sizeof P, hipMemcpyHostToDevice, st));
   if (!c.tiles.empty())
     HIP_TRY(hipMemcpyAsync((void*)P.tiles, c.tiles.data(), c.tiles.size() * sizeof(TileEntry), hipMemcpyHostToDevice, st));
-  HIP_TRY(hipMemcpyAsync(d_shape_level, c.shape_level.data(), c.shape_level.size() * 4, hipMemcpyHostToDevice, st));
+  HIP_TRY(hipMemcpyAsync(d_level_shapes, c.level_shapes.data(), c.level_shapes.size() * 4, hipMemcpyHostToDevice, st));
   HIP_TRY(hipMemcpyAsync(d_level_off, c.level_off.data(), c.level_off.size() * 4, hipMemcpyHostToDevice, st));
 
   hipEvent_t ev[3];
@@ -526,21 +532,18 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
   size_t ev_used = 0;
   hipStream_t s2 = aux->stream;
   HIP_TRY(hipEventRecord(ev[0], st));
-  // the pre-fill runs beside the plan kernel
-  HIP_TRY(hipEventRecord(aux->events[ev_used], st));
-  HIP_TRY(hipStreamWaitEvent(s2, aux->events[ev_used++], 0));
-  launch_fill_ones(tab->d_cost, c.n_specs * 8, s2);
-  launch_fill_ones(tab->d_arg, c.n_specs * 2, s2);
-  HIP_TRY(hipEventRecord(aux->events[ev_used], s2));
-  hipEvent_t prefill_done = aux->events[ev_used++];
-  HIP_TRY(hipMemsetAsync(d_list_cnt, 0, 3 * (size_t)n_lev * 4, st));
-  HIP_TRY(hipMemsetAsync(d_fitmap, 0, (size_t)f.n_words * 8 + 16, st));
-  launch_plan(d_P, c.n_shapes, P.G, d_shape_level, d_level_off, n_lev, d_list_whole, d_list_slice, d_list_wide, d_list_cnt,
-              d_fitmap, d_ctr, st);
+  // plan first (latency-bound: it crawls beside a kernel that saturates HBM), then the pre-fill,
+  // during which the host reads the list sizes back
+  launch_zero_words((unsigned long long*)d_fitmap, f.n_words + 2, st);
+  launch_plan(d_P, c.n_shapes, P.npass, P.G, d_level_shapes, d_level_off, n_lev, d_shape_class, d_list_whole, d_list_slice,
+              d_list_wide, d_list_cnt, d_fitmap, d_ctr, st);
   std::vector<uint32_t> cnt(3 * (size_t)n_lev);
   HIP_TRY(hipMemcpyAsync(cnt.data(), d_list_cnt, cnt.size() * 4, hipMemcpyDeviceToHost, st));
-  HIP_TRY(hipStreamSynchronize(st));
-  HIP_TRY(hipStreamWaitEvent(st, prefill_done, 0));
+  HIP_TRY(hipEventRecord(aux->events[ev_used], st));
+  hipEvent_t counts_ready = aux->events[ev_used++];
+  launch_fill_ones(tab->d_cost, c.n_specs * 8, st);
+  launch_fill_ones(tab->d_arg, c.n_specs * 2, st);
+  HIP_TRY(hipEventSynchronize(counts_ready));
   for (uint32_t l = 0; l < n_lev; l++) {
     const uint32_t first = c.level_off[l];
     const uint32_t n_whole = cnt[l], n_slice = cnt[n_lev + l], n_wide = cnt[2 * n_lev + l];

@@ -13,9 +13,10 @@ struct Geo {
   uint32_t ext[16], stride[16];
 };
 
-void launch_plan(const DevParams* P, uint32_t n_shapes, uint32_t G, const uint32_t* shape_level, const uint32_t* level_off,
-                 uint32_t n_levels, uint32_t* list_whole, uint32_t* list_slice, uint32_t* list_wide, uint32_t* list_cnt,
-                 uint32_t* fitmap, Counters* ctr, hipStream_t stream);
+void launch_plan(const DevParams* P, uint32_t n_shapes, uint32_t npass, uint32_t G, const uint32_t* level_shapes,
+                 const uint32_t* level_off, uint32_t n_levels, uint32_t* shape_class, uint32_t* list_whole,
+                 uint32_t* list_slice, uint32_t* list_wide, uint32_t* list_cnt, uint32_t* fitmap, Counters* ctr,
+                 hipStream_t stream);
 void launch_fill_level(const DevParams* P, uint32_t npass, uint32_t G, uint32_t max_task, const uint32_t* list_whole,
                        uint32_t n_whole, const uint32_t* list_slice, uint32_t n_slice, const uint32_t* list_wide,
                        uint32_t n_wide, uint64_t* cost, uint16_t* arg, Counters* ctr, hipStream_t stream,

@@ -479,71 +479,127 @@ __device__ __forceinline__ void flush_counters(Counters* __restrict__ ctr, const
   if (tot.ovf) atomicOr(&ctr->overflow, tot.ovf);
 }
 
-// Plan: one wave per shape.  Counts the entries that fit per passive-level slice, marks them in
-// a bit map in table order (bit = cell; read by the compression pass) and appends the shape, or
-// its non-empty slices, to the work lists of its dependency level.
-__global__ __launch_bounds__(64) void plan_kernel(const DevParams* __restrict__ P,
-                                                  const uint32_t* __restrict__ shape_level,
-                                                  const uint32_t* __restrict__ level_off, uint32_t n_levels,
-                                                  uint32_t cap_whole, uint32_t cap_slice,
-                                                  uint32_t* __restrict__ list_whole, uint32_t* __restrict__ list_slice,
-                                                  uint32_t* __restrict__ list_wide, uint32_t* __restrict__ list_cnt,
-                                                  uint32_t* __restrict__ fitmap, Counters* __restrict__ ctr) {
-  __shared__ uint32_t fit[16];
-  const uint32_t shape = blockIdx.x, lane = threadIdx.x;
+// Plan: one wave per kPlanShapes consecutive shapes (the per-assignment table and the parameters
+// stay in registers across them).  Counts the entries that fit per passive-level slice, marks them
+// in a bit map in table order (bit = cell; read by the compression pass) and classifies the shape:
+// bit 8 = one wave can hold it whole; else bits 0..3 = slices a wave can hold, bits 4..7 = slices
+// that need a workgroup.  sort_work_kernel turns the classes into per-level work lists.
+constexpr uint32_t kPlanShapes = 8;
+
+__global__ __launch_bounds__(256) void plan_kernel(const DevParams* __restrict__ P, uint32_t n_shapes,
+                                                   uint32_t cap_whole, uint32_t cap_slice,
+                                                   uint32_t* __restrict__ shape_class, uint32_t* __restrict__ fitmap,
+                                                   Counters* __restrict__ ctr) {
+  __shared__ uint32_t fit_all[4][16];
+  const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
+  uint32_t* fit = fit_all[wave];
   const uint32_t npass = P->npass, ncombo = P->ncombo, V = P->V, nb = npass * V;
-  Shape S;
-  load_shape(P, shape, S);
-  build_fit(P, S, fit);
-  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  uint32_t f[4];
+  uint32_t info[4], off0[4];
 #pragma unroll
-  for (int l = 0; l < 4; l++) f[l] = fit[l];
-  const uint64_t group = (uint64_t)shape * P->G;
-  uint32_t cnt[4] = {0, 0, 0, 0};
-  for (uint32_t pc = lane; pc < ncombo; pc += 64) {
-    const uint32_t info = P->pos_info[pc];
-    unsigned long long bits = 0;
-#pragma unroll
-    for (int ps = 0; ps < 4; ps++)
-      if ((uint32_t)ps < npass) {
-        const uint32_t m = admissible_mask(P, fit, f, info, ps);
-        cnt[ps] += __popc(m);
-        bits |= (unsigned long long)m << (ps * V);
-      }
-    if (bits) {
-      const uint64_t cell0 = group + (uint64_t)entry_offset(P, info & 0xFFu, 0);   // pass 0, variant 0 of this assignment
-      const uint32_t sh = (uint32_t)(cell0 & 31u);
-      uint32_t* w = fitmap + (cell0 >> 5);
-      atomicOr(w, (uint32_t)(bits << sh));
-      if (sh + nb > 32) {
-        atomicOr(w + 1, (uint32_t)(bits >> (32 - sh)));
-        if (sh + nb > 64) atomicOr(w + 2, (uint32_t)(bits >> (64 - sh)));
-      }
-    }
+  for (int it = 0; it < 4; it++) {
+    info[it] = it * 64 + lane < ncombo ? P->pos_info[it * 64 + lane] : 0u;
+    off0[it] = entry_offset(P, info[it] & 0xFFu, 0);      // pass 0, variant 0 of this level assignment
   }
-  uint32_t total = 0;
+  unsigned long long n_adm = 0;
+  const uint32_t first_shape = (blockIdx.x * 4 + wave) * kPlanShapes;
+  for (uint32_t shape = first_shape; shape < first_shape + kPlanShapes && shape < n_shapes; shape++) {
+    Shape S;
+    load_shape(P, shape, S);
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    build_fit(P, S, fit);
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    uint32_t f[4];
 #pragma unroll
-  for (int ps = 0; ps < 4; ps++) {
+    for (int l = 0; l < 4; l++) f[l] = fit[l];
+    const uint64_t group = (uint64_t)shape * P->G;
+    uint32_t cnt[4] = {0, 0, 0, 0};
 #pragma unroll
-    for (int d = 32; d > 0; d >>= 1) cnt[ps] += __shfl_down(cnt[ps], d, 64);
-    cnt[ps] = __shfl(cnt[ps], 0, 64);
-    total += cnt[ps];
-  }
-  if (lane == 0 && total) {
-    atomicAdd(&ctr->n_admissible, (unsigned long long)total);
-    const uint32_t lv = shape_level[shape], first = level_off[lv];
-    if (total <= cap_whole) {
-      list_whole[first + atomicAdd(&list_cnt[lv], 1u)] = shape;
-    } else {
-      for (uint32_t ps = 0; ps < npass; ps++) {
-        if (cnt[ps] == 0) continue;
-        if (cnt[ps] <= cap_slice) list_slice[first * npass + atomicAdd(&list_cnt[n_levels + lv], 1u)] = shape * npass + ps;
-        else list_wide[first * npass + atomicAdd(&list_cnt[2 * n_levels + lv], 1u)] = shape * npass + ps;
+    for (int it = 0; it < 4; it++) {
+      if ((uint32_t)(it * 64) >= ncombo) break;
+      if (it * 64 + lane >= ncombo) continue;
+      unsigned long long bits = 0;
+#pragma unroll
+      for (int ps = 0; ps < 4; ps++)
+        if ((uint32_t)ps < npass) {
+          const uint32_t m = admissible_mask(P, fit, f, info[it], ps);
+          cnt[ps] += __popc(m);
+          bits |= (unsigned long long)m << (ps * V);
+        }
+      if (bits) {
+        const uint64_t cell0 = group + off0[it];
+        const uint32_t sh = (uint32_t)(cell0 & 31u);
+        uint32_t* w = fitmap + (cell0 >> 5);
+        atomicOr(w, (uint32_t)(bits << sh));
+        if (sh + nb > 32) {
+          atomicOr(w + 1, (uint32_t)(bits >> (32 - sh)));
+          if (sh + nb > 64) atomicOr(w + 2, (uint32_t)(bits >> (64 - sh)));
+        }
       }
     }
+    uint32_t total = 0;
+#pragma unroll
+    for (int ps = 0; ps < 4; ps++) {
+#pragma unroll
+      for (int d = 32; d > 0; d >>= 1) cnt[ps] += __shfl_down(cnt[ps], d, 64);
+      cnt[ps] = __shfl(cnt[ps], 0, 64);
+      total += cnt[ps];
+    }
+    if (lane == 0) {
+      n_adm += total;
+      uint32_t cls = 0;
+      if (total && total <= cap_whole) cls = 0x100u;
+      else
+        for (uint32_t ps = 0; ps < npass; ps++)
+          if (cnt[ps]) cls |= 1u << (cnt[ps] <= cap_slice ? ps : 4 + ps);
+      shape_class[shape] = cls;
+    }
   }
+  if (lane == 0 && n_adm) atomicAdd(&ctr->n_admissible, n_adm);
+}
+
+// One workgroup per dependency level: walks the level's shapes in index order and writes its three
+// work lists (whole shapes; slices for a wave; slices for a workgroup) and their lengths.
+__global__ __launch_bounds__(256) void sort_work_kernel(const uint32_t* __restrict__ level_shapes,
+                                                        const uint32_t* __restrict__ level_off, uint32_t n_levels,
+                                                        uint32_t npass, const uint32_t* __restrict__ shape_class,
+                                                        uint32_t* __restrict__ list_whole, uint32_t* __restrict__ list_slice,
+                                                        uint32_t* __restrict__ list_wide, uint32_t* __restrict__ list_cnt) {
+  __shared__ uint32_t wave_sum[4];
+  __shared__ uint32_t carry;      // three running counts packed: whole | slice << 10 ... kept unpacked below
+  __shared__ uint32_t run[3];
+  const uint32_t lv = blockIdx.x, first = level_off[lv], n = level_off[lv + 1] - first;
+  if (threadIdx.x < 3) run[threadIdx.x] = 0;
+  (void)carry;
+  __syncthreads();
+  for (uint32_t base = 0; base < n; base += 256) {
+    const uint32_t i = base + threadIdx.x;
+    const uint32_t shape = i < n ? level_shapes[first + i] : 0u;
+    const uint32_t cls = i < n ? shape_class[shape] : 0u;
+    const uint32_t cw = (cls >> 8) & 1u, cs = __popc(cls & 15u), cx = __popc((cls >> 4) & 15u);
+    const uint32_t packed = cw | cs << 10 | cx << 21;      // per 256 threads: <= 256, 1024, 1024
+    uint32_t incl = packed;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const uint32_t o = __shfl_up(incl, d, 64);
+      if ((int)(threadIdx.x & 63u) >= d) incl += o;
+    }
+    if ((threadIdx.x & 63u) == 63) wave_sum[threadIdx.x >> 6] = incl;
+    __syncthreads();
+    uint32_t excl = incl - packed, tot = 0;
+    for (uint32_t w = 0; w < 4; w++) { if (w < (threadIdx.x >> 6)) excl += wave_sum[w]; tot += wave_sum[w]; }
+    uint32_t ow = run[0] + (excl & 1023u), os = run[1] + ((excl >> 10) & 2047u), ox = run[2] + (excl >> 21);
+    if (cw) list_whole[first + ow] = shape;
+    for (uint32_t ps = 0; ps < npass; ps++) {
+      if ((cls >> ps) & 1u) list_slice[(size_t)first * npass + os++] = shape * npass + ps;
+      if ((cls >> (4 + ps)) & 1u) list_wide[(size_t)first * npass + ox++] = shape * npass + ps;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) { run[0] += tot & 1023u; run[1] += (tot >> 10) & 2047u; run[2] += tot >> 21; }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) { list_cnt[lv] = run[0]; list_cnt[n_levels + lv] = run[1]; list_cnt[2 * n_levels + lv] = run[2]; }
 }
 
 // One dependency level, the items a single wave can hold: first the whole shapes, then the slices.
@@ -607,12 +663,15 @@ void launch_fill_ones(void* p, size_t bytes, hipStream_t stream) {
 
 uint32_t fill_wave_cap(uint32_t G) { return G < kSmallCap ? G : kSmallCap; }
 
-void launch_plan(const DevParams* P, uint32_t n_shapes, uint32_t G, const uint32_t* shape_level, const uint32_t* level_off,
-                 uint32_t n_levels, uint32_t* list_whole, uint32_t* list_slice, uint32_t* list_wide, uint32_t* list_cnt,
-                 uint32_t* fitmap, Counters* ctr, hipStream_t stream) {
+void launch_plan(const DevParams* P, uint32_t n_shapes, uint32_t npass, uint32_t G, const uint32_t* level_shapes,
+                 const uint32_t* level_off, uint32_t n_levels, uint32_t* shape_class, uint32_t* list_whole,
+                 uint32_t* list_slice, uint32_t* list_wide, uint32_t* list_cnt, uint32_t* fitmap, Counters* ctr,
+                 hipStream_t stream) {
   const uint32_t cap = fill_wave_cap(G);
-  hipLaunchKernelGGL(plan_kernel, dim3(n_shapes), dim3(64), 0, stream, P, shape_level, level_off, n_levels, cap, cap,
-                     list_whole, list_slice, list_wide, list_cnt, fitmap, ctr);
+  hipLaunchKernelGGL(plan_kernel, dim3((n_shapes + 4 * kPlanShapes - 1) / (4 * kPlanShapes)), dim3(256), 0, stream, P,
+                     n_shapes, cap, cap, shape_class, fitmap, ctr);
+  hipLaunchKernelGGL(sort_work_kernel, dim3(n_levels), dim3(256), 0, stream, level_shapes, level_off, n_levels, npass,
+                     shape_class, list_whole, list_slice, list_wide, list_cnt);
 }
 
 // One dependency level: the items a wave can hold, and the wide ones (independent of each other:

@@ -61,7 +61,13 @@ __global__ __launch_bounds__(256) void head_flags_kernel(Geo g, uint32_t a0,
   for (uint32_t j = 0; j < e0; j++) {
     const uint32_t cell = base + j * s0;
     bool hd = false, hc = false;
-    if (active) {
+    // 64 consecutive cells none of which fits (the common case): nothing to read, the values are known
+    const bool none_fit = BALLOT && reinterpret_cast<const unsigned long long*>(fitmap)[__builtin_amdgcn_readfirstlane(cell) >> 6] == 0;
+    if (none_fit) {
+      hd = j == 0 || pa != kNone;
+      hc = j == 0 || pc != kInf;
+      pc = kInf; pa = kNone; ps = axis_sizes ? axis_sizes[j] : 1u;
+    } else if (active) {
       const bool fits = (fitmap[cell >> 5] >> (cell & 31u)) & 1u;
       const uint64_t c = fits ? cost[cell] : kInf;
       const uint32_t a = fits ? arg[cell] : kNone;
@@ -280,24 +286,28 @@ __global__ __launch_bounds__(256) void link_kernel(Geo g, uint32_t a, uint8_t st
   uint32_t nxt = 0xFFFFFFFFu;
   if (ca + la < ea) {
     const uint32_t s = cell + la * sa;
-    const unsigned long long m = mask[s >> 6];
-    if ((m >> (s & 63u)) & 1ull) {
-      const uint32_t o = prefix[s >> 6] + (uint32_t)__popcll(m & ((1ull << (s & 63u)) - 1ull));
-      if (alive[o]) {
-        const uint4 M = blen[o];
-        const uint32_t keep = ~(0xFFu << ((a & 3u) * 8));
-        const uint32_t kx = (a >> 2) == 0 ? keep : ~0u, ky = (a >> 2) == 1 ? keep : ~0u;
-        const uint32_t kz = (a >> 2) == 2 ? keep : ~0u, kw = (a >> 2) == 3 ? keep : ~0u;
-        bool same = ((L.x ^ M.x) & kx) == 0 && ((L.y ^ M.y) & ky) == 0 && ((L.z ^ M.z) & kz) == 0 && ((L.w ^ M.w) & kw) == 0;
-        if (same) {
-          if (COST) {
-            const uint32_t s1 = axis_sizes ? axis_sizes[ca] : 1u, s2 = axis_sizes ? axis_sizes[ca + la] : 1u;
-            same = norm_equal(cost[cell], s1, cost[s], s2);
-          } else {
-            same = arg[cell] == arg[s];
+    // cheapest test first: most boxes differ in value from the cell past their end
+    bool same;
+    if (COST) {
+      const uint32_t s1 = axis_sizes ? axis_sizes[ca] : 1u, s2 = axis_sizes ? axis_sizes[ca + la] : 1u;
+      same = norm_equal(cost[cell], s1, cost[s], s2);
+    } else {
+      same = arg[cell] == arg[s];
+    }
+    if (same) {
+      const unsigned long long m = mask[s >> 6];
+      if ((m >> (s & 63u)) & 1ull) {
+        const uint32_t o = prefix[s >> 6] + (uint32_t)__popcll(m & ((1ull << (s & 63u)) - 1ull));
+        if (alive[o]) {
+          const uint4 M = blen[o];
+          const uint32_t keep = ~(0xFFu << ((a & 3u) * 8));
+          const uint32_t kx = (a >> 2) == 0 ? keep : ~0u, ky = (a >> 2) == 1 ? keep : ~0u;
+          const uint32_t kz = (a >> 2) == 2 ? keep : ~0u, kw = (a >> 2) == 3 ? keep : ~0u;
+          if (((L.x ^ M.x) & kx) == 0 && ((L.y ^ M.y) & ky) == 0 && ((L.z ^ M.z) & kz) == 0 && ((L.w ^ M.w) & kw) == 0) {
+            nxt = o;
+            pred[o] = stamp;
           }
         }
-        if (same) { nxt = o; pred[o] = stamp; }
       }
     }
   }

@@ -94,6 +94,77 @@ __global__ __launch_bounds__(256) void head_flags_kernel(Geo g, uint32_t a0,
   (void)lw;
 }
 
+// The same for lines whose stride is a multiple of 64 cells (every table with at least 64
+// entries per shape): the 64 lanes of a wave then stand on 64 consecutive cells at every step, so
+// one 64-bit word of the fit bit map covers the step and one ballot is one word of the mask.  A
+// step's cells lie far from the previous step's, so every read is a trip to HBM; to have few of
+// them wait for each other, the fit words of up to 64 steps are fetched by one gather (lane t
+// holds step t's word), and the values of 8 steps are fetched together before they are compared.
+constexpr int kHeadBatch = 8;
+
+__device__ __forceinline__ unsigned long long readlane64(unsigned long long v, uint32_t lane) {
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, (int)lane);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), (int)lane);
+  return (unsigned long long)hi << 32 | lo;
+}
+
+__global__ __launch_bounds__(256) void head_flags_wave_kernel(Geo g, uint32_t a0,
+                                                              const uint64_t* __restrict__ cost,
+                                                              const uint16_t* __restrict__ arg,
+                                                              const unsigned long long* __restrict__ fitmap,
+                                                              const uint32_t* __restrict__ axis_sizes,
+                                                              unsigned long long* __restrict__ maskD,
+                                                              unsigned long long* __restrict__ maskC,
+                                                              unsigned long long* __restrict__ lineD,
+                                                              unsigned long long* __restrict__ lineC) {
+  const uint32_t s0 = g.stride[a0], e0 = g.ext[a0];
+  const uint32_t n_lines = g.n / e0;                  // a multiple of 64, as s0 is
+  const uint32_t lane = threadIdx.x & 63u;
+  const uint32_t q = blockIdx.x * 256u + threadIdx.x, q0 = q - lane;
+  if (q0 >= n_lines) return;                          // the whole wave
+  const uint32_t hi0 = q0 / s0;
+  const uint32_t base0 = hi0 * s0 * e0 + (q0 - hi0 * s0);      // lane 0's first cell: a multiple of 64
+  uint64_t pc = 0; uint32_t pa = 0, ps = 1;
+  unsigned long long wd = 0, wc = 0;
+  for (uint32_t j0 = 0; j0 < e0; j0 += 64) {
+    const uint32_t jt = j0 + lane;
+    const unsigned long long words = jt < e0 ? fitmap[(base0 + jt * s0) >> 6] : 0ull;
+    const uint32_t sizes = (axis_sizes && jt < e0) ? axis_sizes[jt] : 1u;
+    const uint32_t n_here = e0 - j0 < 64u ? e0 - j0 : 64u;
+    for (uint32_t u0 = 0; u0 < n_here; u0 += kHeadBatch) {
+      uint64_t c[kHeadBatch];
+      uint32_t a[kHeadBatch];
+#pragma unroll
+      for (int u = 0; u < kHeadBatch; u++) {
+        const uint32_t t = u0 + u < n_here ? u0 + u : n_here - 1;
+        const bool fits = (readlane64(words, t) >> lane) & 1ull;
+        const uint32_t cell = base0 + lane + (j0 + t) * s0;
+        c[u] = fits ? cost[cell] : kInf;
+        a[u] = fits ? (uint32_t)arg[cell] : kNone;
+      }
+#pragma unroll
+      for (int u = 0; u < kHeadBatch; u++) {
+        if (u0 + u < n_here) {
+          const uint32_t j = j0 + u0 + u;
+          const uint32_t sz = (uint32_t)__builtin_amdgcn_readlane((int)sizes, (int)(u0 + u));
+          const bool hd = j == 0 || a[u] != pa;
+          const bool hc = j == 0 || !norm_equal(c[u], sz, pc, ps);
+          pc = c[u]; pa = a[u]; ps = sz;
+          const unsigned long long bd = __ballot(hd), bc = __ballot(hc);
+          if (lane == 0) { const uint32_t w = (base0 + j * s0) >> 6; maskD[w] = bd; maskC[w] = bc; }
+          wd |= (unsigned long long)hd << (j & 63u);
+          wc |= (unsigned long long)hc << (j & 63u);
+          if ((j & 63u) == 63u || j + 1 == e0) {
+            lineD[(size_t)(j >> 6) * n_lines + q] = wd;
+            lineC[(size_t)(j >> 6) * n_lines + q] = wc;
+            wd = wc = 0;
+          }
+        }
+      }
+    }
+  }
+}
+
 // ---------------------------------------------------------------- prefix sums
 struct LoadPopc {
   const unsigned long long* p;
@@ -338,8 +409,8 @@ void launch_head_flags(const Geo& g, uint32_t a0, const uint64_t* cost, const ui
   const uint32_t n_lines = g.n / g.ext[a0];
   const uint32_t blocks = (n_lines + 255) / 256;
   if (g.stride[a0] % 64 == 0)
-    hipLaunchKernelGGL(head_flags_kernel<true>, dim3(blocks), dim3(256), 0, st, g, a0, cost, arg, fitmap, axis_sizes, maskD,
-                       maskC, lineD, lineC);
+    hipLaunchKernelGGL(head_flags_wave_kernel, dim3(blocks), dim3(256), 0, st, g, a0, cost, arg,
+                       (const unsigned long long*)fitmap, axis_sizes, maskD, maskC, lineD, lineC);
   else
     hipLaunchKernelGGL(head_flags_kernel<false>, dim3(blocks), dim3(256), 0, st, g, a0, cost, arg, fitmap, axis_sizes, maskD,
                        maskC, lineD, lineC);

@@ -84,16 +84,34 @@ __device__ __forceinline__ void load_shape(const DevParams* __restrict__ P, uint
   else { S.numel[0] = m * k; S.numel[1] = k * n; S.numel[2] = n; S.numel[3] = m * n; S.numel[4] = m * n; }
 }
 
+// The uniform fields the per-task code needs, read once per unit so that they stay in scalar
+// registers (a scalar load in the middle of the LDS traffic stalls on the counter they share).
+struct Hot {
+  uint32_t nops, NL, npass, log2V, ndt, move_base;
+  uint32_t pack_shift[4], lay_bit[4], dt_bit[4], can_convert[4], lvpow[4];
+};
+
+__device__ __forceinline__ Hot load_hot(const DevParams* __restrict__ P) {
+  Hot H;
+  H.nops = P->nops; H.NL = P->NL; H.npass = P->npass; H.log2V = P->log2V; H.ndt = P->ndt; H.move_base = P->move_base;
+#pragma unroll
+  for (int i = 0; i < 4; i++) {
+    H.pack_shift[i] = P->pack_shift[i]; H.lay_bit[i] = P->lay_bit[i]; H.dt_bit[i] = P->dt_bit[i];
+    H.can_convert[i] = P->can_convert[i]; H.lvpow[i] = P->lvpow[i];
+  }
+  return H;
+}
+
 // Table offset (inside the shape's group) of entry (pack, pass, variant).
-__device__ __forceinline__ uint32_t entry_offset(const DevParams* __restrict__ P, uint32_t xpack, uint32_t v) {
+__device__ __forceinline__ uint32_t entry_offset(const Hot& H, uint32_t xpack, uint32_t v) {
   const uint32_t pack = xpack & 0xFFu, pass = xpack >> 8;
   uint32_t combo = pack;
-  if (P->NL != 4) {
+  if (H.NL != 4) {
     combo = 0;
 #pragma unroll
-    for (int i = 0; i < 4; i++) if ((uint32_t)i < P->nops) combo += ((pack >> P->pack_shift[i]) & 3u) * P->lvpow[i];
+    for (int i = 0; i < 4; i++) if ((uint32_t)i < H.nops) combo += ((pack >> H.pack_shift[i]) & 3u) * H.lvpow[i];
   }
-  return ((combo * P->npass + pass) << P->log2V) + v;
+  return ((combo * H.npass + pass) << H.log2V) + v;
 }
 
 // Shape part of microkernel j's predicate: number of repetitions, 0 if it fails
@@ -287,47 +305,67 @@ __device__ __forceinline__ void task_bufferize(const DevParams* __restrict__ P, 
   }
 }
 
-// Moves of operand I of task (xpack, v): to every lower level, same or transposed layout,
-// with or without conversion.  All sub-Specs have a lower rank and are final in LDS; the
-// LDS lookups of one operand are independent and stay in flight together.
+// Moves of operand I of task (xpack, v): to every lower level, same or transposed layout, with
+// or without conversion.  All sub-Specs have a lower rank and are final in LDS.  The LDS reads
+// are arranged in two rounds so that few of them wait for each other: first the (admissible
+// variants | first task) word of the three possible destinations (move_targets), then the Move
+// costs and the sub-Specs' costs of all candidates of a conversion plane (move_plane).
 template <int I>
-__device__ __forceinline__ void task_moves(const DevParams* __restrict__ P, const UnitLds& L, uint32_t q,
-                                           uint32_t xpack, uint32_t v, Eval& e, uint32_t& hi_or) {
-  if ((uint32_t)I >= P->nops) return;
-  const uint32_t sh = P->pack_shift[I], layb = P->lay_bit[I], dtb = P->dt_bit[I];
-  const bool has_dt = P->ndt != 0;
-  const uint32_t src = (xpack >> sh) & 3u;
-  if (!__any(src != 0)) return;
-  const uint32_t nx = layb != kNoBit ? 2 : 1, ncv = P->can_convert[I] ? 2 : 1;
-  const uint32_t id0 = P->move_base + (uint32_t)I * (P->NL - 1) * 4u;
-  for (uint32_t cv = 0; cv < ncv; cv++)
-    for (uint32_t x = 0; x < nx; x++) {
-      uint64_t cand[3];
-      bool fin[3], ok[3];
-      const uint32_t v2 = (v ^ (x ? 1u << layb : 0u)) & ~(cv ? 1u << dtb : 0u);
-      const bool cv_ok = !cv || ((v >> dtb) & 1u);
+__device__ __forceinline__ void move_targets(const Hot& H, const UnitLds& L, uint32_t xpack, uint32_t ci[3]) {
+  if ((uint32_t)I >= H.nops) return;
+  const uint32_t sh = H.pack_shift[I], src = (xpack >> sh) & 3u;
 #pragma unroll
-      for (int dst = 0; dst < 3; dst++) {
-        const uint64_t b = L.bterm[cv * 128u + (((uint32_t)I * 4u + src) * 4u + dst) * 2u + x];
-        const bool valid = (uint32_t)dst < src && b != 0 && cv_ok;
-        const uint32_t xp2 = valid ? xpack - ((src - dst) << sh) : xpack;
-        const uint32_t ci = L.c_info[xp2];
-        const bool has = valid && ((ci >> v2) & 1u);
-        const uint32_t idx = (ci >> 16) + (has_dt ? __popc(ci & 0xFFFFu & ((1u << v2) - 1u)) : v2);
-        const uint64_t t = L.t_cost[has ? idx : q];
-        fin[dst] = has && t != kInf;
-        cand[dst] = t + b;               // t < 2^62 when finite, b <= 2^62: no wrap
-        ok[dst] = valid;
-      }
+  for (uint32_t dst = 0; dst < 3; dst++) ci[dst] = L.c_info[dst < src ? xpack - ((src - dst) << sh) : xpack];
+}
+
+template <int I, int NX>
+__device__ __forceinline__ void move_plane(const Hot& H, const UnitLds& L, uint32_t q, uint32_t src, uint32_t v,
+                                           uint32_t cv, bool cv_ok, const uint32_t ci[3], Eval& e, uint32_t& hi_or) {
+  const bool has_dt = H.ndt != 0;
+  const uint32_t xbit = NX == 2 ? 1u << H.lay_bit[I] : 0u, cvbit = cv ? 1u << H.dt_bit[I] : 0u;
+  const uint32_t id0 = H.move_base + (uint32_t)I * (H.NL - 1) * 4u + cv;
+  const uint32_t brow = cv * 128u + ((uint32_t)I * 4u + src) * 8u;
+  uint64_t b[3 * NX], t[3 * NX];
+  bool has[3 * NX];
 #pragma unroll
-      for (int dst = 0; dst < 3; dst++) {
-        e.n += ok[dst] ? 1u : 0u;
-        if (fin[dst]) {
-          hi_or |= (uint32_t)(cand[dst] >> 32);
-          consider(e, cand[dst], id0 + ((uint32_t)dst * 2u + x) * 2u + cv);
-        }
+  for (uint32_t dst = 0; dst < 3; dst++)
+#pragma unroll
+    for (uint32_t x = 0; x < (uint32_t)NX; x++) {
+      const uint32_t c = dst * NX + x, v2 = (v ^ (x ? xbit : 0u)) & ~cvbit;
+      b[c] = L.bterm[brow + dst * 2u + x];
+      has[c] = dst < src && cv_ok && ((ci[dst] >> v2) & 1u);
+      const uint32_t idx = (ci[dst] >> 16) + (has_dt ? __popc(ci[dst] & 0xFFFFu & ((1u << v2) - 1u)) : v2);
+      t[c] = L.t_cost[has[c] ? idx : q];
+    }
+#pragma unroll
+  for (uint32_t dst = 0; dst < 3; dst++)
+#pragma unroll
+    for (uint32_t x = 0; x < (uint32_t)NX; x++) {
+      const uint32_t c = dst * NX + x;
+      const bool exists = dst < src && cv_ok && b[c] != 0;     // b == 0: the target has no such Move
+      e.n += exists ? 1u : 0u;
+      if (exists && has[c] && t[c] != kInf) {
+        const uint64_t cand = t[c] + b[c];                      // t < 2^62 when finite, b <= 2^62: no wrap
+        hi_or |= (uint32_t)(cand >> 32);
+        consider(e, cand, id0 + (dst * 2u + x) * 2u);
       }
     }
+}
+
+template <int I>
+__device__ __forceinline__ void task_moves(const Hot& H, const UnitLds& L, uint32_t q, uint32_t xpack, uint32_t v,
+                                           const uint32_t ci[3], Eval& e, uint32_t& hi_or) {
+  if ((uint32_t)I >= H.nops) return;
+  const uint32_t src = (xpack >> H.pack_shift[I]) & 3u;
+  if (!__any(src != 0)) return;
+  const bool cv_ok = H.can_convert[I] && ((v >> H.dt_bit[I]) & 1u);
+  if (H.lay_bit[I] != kNoBit) {
+    move_plane<I, 2>(H, L, q, src, v, 0, true, ci, e, hi_or);
+    if (__any(cv_ok)) move_plane<I, 2>(H, L, q, src, v, 1, cv_ok, ci, e, hi_or);
+  } else {
+    move_plane<I, 1>(H, L, q, src, v, 0, true, ci, e, hi_or);
+    if (__any(cv_ok)) move_plane<I, 1>(H, L, q, src, v, 1, cv_ok, ci, e, hi_or);
+  }
 }
 
 // One unit = passes [pass0, pass0 + np) of one shape, handled by T threads.
@@ -339,6 +377,7 @@ __device__ __forceinline__ void solve_unit(const DevParams* __restrict__ P, cons
   const uint32_t lane = threadIdx.x & 63u;
   const uint32_t ncombo = P->ncombo;
   const uint64_t group = (uint64_t)shape * P->G;
+  const Hot H = load_hot(P);
 
   // ---- 1. admissibility, compaction in rank order (rank-major level assignments, then pass) ----
   constexpr int kIter = 256 / T < 1 ? 1 : 256 / T;   // ncombo <= 256
@@ -424,7 +463,7 @@ __device__ __forceinline__ void solve_unit(const DevParams* __restrict__ P, cons
       } else {
         e.best = L.t_cost[q]; e.arg = sp >> 16;
       }
-      task_tiles(P, L, n_here, entry_offset(P, xpack, v), cost, e);
+      task_tiles(P, L, n_here, entry_offset(H, xpack, v), cost, e);
       L.t_cost[q] = e.best;
       L.t_spec[q] = (sp & 0xFFFFu) | e.arg << 16;
       tot.ovf |= e.ovf;
@@ -455,12 +494,17 @@ __device__ __forceinline__ void solve_unit(const DevParams* __restrict__ P, cons
           e.n++;
         }
       }
-      task_moves<0>(P, L, q, xpack, v, e, hi_or);
-      task_moves<1>(P, L, q, xpack, v, e, hi_or);
-      task_moves<2>(P, L, q, xpack, v, e, hi_or);
-      task_moves<3>(P, L, q, xpack, v, e, hi_or);
+      uint32_t ci[4][3];
+      move_targets<0>(H, L, xpack, ci[0]);
+      move_targets<1>(H, L, xpack, ci[1]);
+      move_targets<2>(H, L, xpack, ci[2]);
+      move_targets<3>(H, L, xpack, ci[3]);
+      task_moves<0>(H, L, q, xpack, v, ci[0], e, hi_or);
+      task_moves<1>(H, L, q, xpack, v, ci[1], e, hi_or);
+      task_moves<2>(H, L, q, xpack, v, ci[2], e, hi_or);
+      task_moves<3>(H, L, q, xpack, v, ci[3], e, hi_or);
       if (hi_or >> 30) e.ovf = 1;   // bit 62 of some finite candidate: the solve reports overflow
-      const uint32_t off = entry_offset(P, xpack, v);
+      const uint32_t off = entry_offset(H, xpack, v);
       L.t_cost[q] = e.best;
       cost[group + off] = e.best;
       arg[group + off] = (uint16_t)e.arg;
@@ -494,11 +538,12 @@ __global__ __launch_bounds__(256) void plan_kernel(const DevParams* __restrict__
   const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
   uint32_t* fit = fit_all[wave];
   const uint32_t npass = P->npass, ncombo = P->ncombo, V = P->V, nb = npass * V;
+  const Hot H = load_hot(P);
   uint32_t info[4], off0[4];
 #pragma unroll
   for (int it = 0; it < 4; it++) {
     info[it] = it * 64 + lane < ncombo ? P->pos_info[it * 64 + lane] : 0u;
-    off0[it] = entry_offset(P, info[it] & 0xFFu, 0);      // pass 0, variant 0 of this level assignment
+    off0[it] = entry_offset(H, info[it] & 0xFFu, 0);      // pass 0, variant 0 of this level assignment
   }
   unsigned long long n_adm = 0;
   const uint32_t first_shape = (blockIdx.x * 4 + wave) * kPlanShapes;
@@ -606,7 +651,7 @@ __global__ __launch_bounds__(256) void sort_work_kernel(const uint32_t* __restri
 // T threads per item: one wave when the level has enough items to fill the chip, four when it has
 // few (then an item's tasks are spread over more lanes).
 template <int T>
-__global__ __launch_bounds__(T) void fill_kernel(const DevParams* __restrict__ P,
+__global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(1, 4))) void fill_kernel(const DevParams* __restrict__ P,
                                                  const uint32_t* __restrict__ list_whole, uint32_t n_whole,
                                                  const uint32_t* __restrict__ list_slice, uint32_t cap,
                                                  uint64_t* __restrict__ cost, uint16_t* __restrict__ arg,
@@ -629,7 +674,7 @@ __global__ __launch_bounds__(T) void fill_kernel(const DevParams* __restrict__ P
 }
 
 // The slices too large for a wave's LDS slice: one workgroup of kBigBlock threads each.
-__global__ __launch_bounds__(kBigBlock) void fill_big_kernel(const DevParams* __restrict__ P,
+__global__ __launch_bounds__(kBigBlock) __attribute__((amdgpu_waves_per_eu(1, 4))) void fill_big_kernel(const DevParams* __restrict__ P,
                                                              const uint32_t* __restrict__ list_wide, uint32_t cap,
                                                              uint64_t* __restrict__ cost, uint16_t* __restrict__ arg,
                                                              Counters* __restrict__ ctr) {

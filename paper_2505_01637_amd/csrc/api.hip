@@ -606,9 +606,19 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
     uint32_t n_ids = (uint32_t)nb, n_pass = 0, flip = 0;
     bool counted = false;           // h_tot[2] holds the live count of the current list
     uint8_t stamp = 0;
+    // the passes in order; the trailing ones over bit axes inside a mask word are done in one kernel
+    uint32_t pass_axis[16], n_axes = 0;
     for (uint32_t q = 0; q < g.ndim; q++) {
       const uint32_t a = c.merge_order[q];
-      if (a == a0 || g.ext[a] <= 1) continue;
+      if (a != a0 && g.ext[a] > 1) pass_axis[n_axes++] = a;
+    }
+    uint32_t n_generic = n_axes;
+    while (n_generic > 0 && n_axes - n_generic < 6 && g.ext[pass_axis[n_generic - 1]] == 2 && g.stride[pass_axis[n_generic - 1]] <= 32) n_generic--;
+    TailAxes tail;
+    tail.n = n_axes - n_generic;
+    for (uint32_t k = 0; k < tail.n; k++) { tail.axis[k] = pass_axis[n_generic + k]; tail.stride[k] = g.stride[pass_axis[n_generic + k]]; }
+    for (uint32_t q = 0; q < n_generic; q++) {
+      const uint32_t a = pass_axis[q];
       launch_axis_pass(g, a, ++stamp, which == 1, ids, n_ids, bcell, blen, alive, pred, next, maskL[which], prefL[which],
                        tab->d_cost, tab->d_arg, axis_sizes(a), st);
       counted = false;
@@ -623,6 +633,10 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
         flip ^= 1;
         counted = true;
       }
+    }
+    if (tail.n) {
+      launch_tail_pairs(tail, which == 1, f.n_words, maskL[which], prefL[which], blen, alive, tab->d_cost, tab->d_arg, st);
+      counted = false;
     }
     scan_flags(alive, ids, n_ids, tile_tmp, pos, d_tot + 2, st);
     if (!counted) {

@@ -42,6 +42,14 @@ void launch_axis_pass(const Geo& g, uint32_t a, uint8_t stamp, bool is_cost, con
                       void* blen, uint8_t* alive, uint8_t* pred, uint32_t* next, const unsigned long long* mask,
                       const uint32_t* prefix, const uint64_t* cost, const uint16_t* arg, const uint32_t* axis_sizes,
                       hipStream_t st);
+// The trailing passes over axes of extent 2 whose stride is at most 32 cells, in pass order.
+struct TailAxes {
+  uint32_t n;
+  uint32_t axis[8], stride[8];
+};
+void launch_tail_pairs(const TailAxes& T, bool is_cost, uint32_t n_words, const unsigned long long* mask,
+                       const uint32_t* prefix, void* blen, uint8_t* alive, const uint64_t* cost, const uint16_t* arg,
+                       hipStream_t st);
 void launch_emit(const Geo& g, const DevParams* P, bool is_cost, const uint32_t* ids, uint32_t n_boxes, const uint32_t* bcell,
                  const void* blen,
                  const uint8_t* alive, const uint32_t* pos, const uint64_t* cost, const uint16_t* arg, uint32_t* fcell,

@@ -518,6 +518,74 @@ void launch_axis_pass(const Geo& g, uint32_t a, uint8_t stamp, bool is_cost, con
   hipLaunchKernelGGL(absorb_kernel, dim3(blocks), dim3(256), 0, st, a, stamp, ids, n_boxes, (uint8_t*)blen, alive, pred, next);
 }
 
+// ---------------------------------------------------------------- the last passes, in one
+// The merge order ends with the axes of the layout and dtype bits, which are also the innermost
+// coordinates: extent 2 and a stride of at most 32 cells, so a box and the one it could merge
+// with on such an axis have their low corners in the same 64-cell word of the mask, and no chain
+// is longer than two.  A wave stands with its lanes on the cells of a word, holds the live boxes
+// that start there in registers, and runs all those passes with lane exchanges: one read and at
+// most one write of every box instead of one per pass.
+template <bool COST>
+__global__ __launch_bounds__(256) void tail_pairs_kernel(TailAxes T, uint32_t n_words,
+                                                         const unsigned long long* __restrict__ mask,
+                                                         const uint32_t* __restrict__ prefix, uint4* __restrict__ blen,
+                                                         uint8_t* __restrict__ alive, const uint64_t* __restrict__ cost,
+                                                         const uint16_t* __restrict__ arg) {
+  const uint32_t lane = threadIdx.x & 63u;
+  const uint32_t w0 = (blockIdx.x * 4u + (threadIdx.x >> 6)) * 64u;
+  if (w0 >= n_words) return;
+  const unsigned long long mv = w0 + lane < n_words ? mask[w0 + lane] : 0ull;
+  const uint32_t pv = w0 + lane < n_words ? prefix[w0 + lane] : 0u;
+  for (unsigned long long todo = __ballot(mv != 0); todo; todo &= todo - 1) {
+    const uint32_t t = (uint32_t)__ffsll((long long)todo) - 1u;
+    const unsigned long long m = readlane64(mv, t);
+    const uint32_t pf = (uint32_t)__builtin_amdgcn_readlane((int)pv, (int)t);
+    const uint32_t cell = (w0 + t) * 64u + lane;
+    const uint32_t id = pf + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+    bool live = ((m >> lane) & 1ull) && alive[id];
+    if (!__any(live)) continue;
+    uint4 L = live ? blen[id] : make_uint4(0, 0, 0, 0);
+    // the two boxes of a pair start in the same shape, so equal normalised costs = equal costs
+    uint64_t v = 0;
+    if (live) v = COST ? cost[cell] : (uint64_t)arg[cell];
+    bool changed = false, died = false;
+    for (uint32_t k = 0; k < T.n; k++) {
+      const uint32_t st = T.stride[k], a = T.axis[k];
+      const int p_live = __shfl_down((int)live, st, 64);
+      const uint32_t p_lo = __shfl_down((uint32_t)v, st, 64), p_hi = __shfl_down((uint32_t)(v >> 32), st, 64);
+      const uint32_t px = __shfl_down(L.x, st, 64), py = __shfl_down(L.y, st, 64);
+      const uint32_t pz = __shfl_down(L.z, st, 64), pw = __shfl_down(L.w, st, 64);
+      const bool low = (lane & st) == 0;             // coordinate 0 on this axis: lane + st is in the same word
+      const bool merge = low && live && p_live && (uint32_t)v == p_lo && (uint32_t)(v >> 32) == p_hi &&
+                         L.x == px && L.y == py && L.z == pz && L.w == pw;
+      if (merge) {
+        const uint32_t one = 1u << ((a & 3u) * 8u);
+        L.x += (a >> 2) == 0 ? one : 0u;
+        L.y += (a >> 2) == 1 ? one : 0u;
+        L.z += (a >> 2) == 2 ? one : 0u;
+        L.w += (a >> 2) == 3 ? one : 0u;
+        changed = true;
+      }
+      const int absorbed = __shfl_up((int)merge, st, 64);
+      if (!low && absorbed) { live = false; died = true; }
+    }
+    if (changed) blen[id] = L;
+    if (died) alive[id] = 0;
+  }
+}
+
+void launch_tail_pairs(const TailAxes& T, bool is_cost, uint32_t n_words, const unsigned long long* mask,
+                       const uint32_t* prefix, void* blen, uint8_t* alive, const uint64_t* cost, const uint16_t* arg,
+                       hipStream_t st) {
+  const uint32_t blocks = (n_words + 255) / 256;
+  if (is_cost)
+    hipLaunchKernelGGL(tail_pairs_kernel<true>, dim3(blocks), dim3(256), 0, st, T, n_words, mask, prefix, (uint4*)blen, alive,
+                       cost, arg);
+  else
+    hipLaunchKernelGGL(tail_pairs_kernel<false>, dim3(blocks), dim3(256), 0, st, T, n_words, mask, prefix, (uint4*)blen, alive,
+                       cost, arg);
+}
+
 // ---------------------------------------------------------------- final lists
 __device__ __forceinline__ uint64_t gcd_u64(uint64_t a, uint64_t b) {
   while (b) { uint64_t t = a % b; a = b; b = t; }

@@ -108,7 +108,7 @@ FixedLayout fixed_layout(const Compiled& c) {
 }
 
 // per box while merging: bcell, blen, alive, pred, next, pos, two live lists; per final box: fcell, flen, fv0, fv1
-size_t work_bytes(uint64_t nb) { return align_up(nb * 4) + align_up(nb * 16) + 2 * align_up(nb) + 4 * align_up(nb * 4); }
+size_t work_bytes(uint64_t nb) { return align_up(nb * 4) + align_up(nb * 16) + 2 * align_up(nb) + 4 * align_up(nb * 4) + align_up((nb / 256 + 1) * 4); }
 size_t final_bytes(uint64_t nb) { return align_up(nb * 4) + align_up(nb * 16) + 2 * align_up(nb * 8); }
 
 uint32_t ipow(uint32_t b, uint32_t e) { uint32_t r = 1; while (e--) r *= b; return r; }
@@ -599,6 +599,7 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
     uint32_t* next = (uint32_t*)w; w += align_up(nb * 4);
     uint32_t* pos = (uint32_t*)w; w += align_up(nb * 4);
     uint32_t* live_buf[2] = {(uint32_t*)w, (uint32_t*)(w + align_up(nb * 4))};
+    uint32_t* block_linked = (uint32_t*)(w + 2 * align_up(nb * 4));
     launch_make_boxes(g, a0, maskL[which], prefL[which], lineL[which], bcell, blen, alive, pred, st);
     // boxes still to be visited: all of them at first, then compacted lists of the live ones
     // (ascending index) once the first passes have merged most boxes away
@@ -619,7 +620,8 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
     for (uint32_t k = 0; k < tail.n; k++) { tail.axis[k] = pass_axis[n_generic + k]; tail.stride[k] = g.stride[pass_axis[n_generic + k]]; }
     for (uint32_t q = 0; q < n_generic; q++) {
       const uint32_t a = pass_axis[q];
-      launch_axis_pass(g, a, ++stamp, which == 1, ids, n_ids, bcell, blen, alive, pred, next, maskL[which], prefL[which],
+      launch_axis_pass(g, a, ++stamp, which == 1, ids, n_ids, bcell, blen, alive, pred, next, block_linked, maskL[which],
+                       prefL[which],
                        tab->d_cost, tab->d_arg, axis_sizes(a), st);
       counted = false;
       n_pass++;

@@ -39,7 +39,8 @@ void launch_make_boxes(const Geo& g, uint32_t a0, const unsigned long long* mask
                        hipStream_t st);
 void launch_axis_pass(const Geo& g, uint32_t a, uint8_t stamp, bool is_cost, const uint32_t* ids, uint32_t n_boxes,
                       const uint32_t* bcell,
-                      void* blen, uint8_t* alive, uint8_t* pred, uint32_t* next, const unsigned long long* mask,
+                      void* blen, uint8_t* alive, uint8_t* pred, uint32_t* next, uint32_t* block_linked,
+                      const unsigned long long* mask,
                       const uint32_t* prefix, const uint64_t* cost, const uint16_t* arg, const uint32_t* axis_sizes,
                       hipStream_t st);
 // The trailing passes over axes of extent 2 whose stride is at most 32 cells, in pass order.

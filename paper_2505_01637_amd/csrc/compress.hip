@@ -354,25 +354,30 @@ __global__ __launch_bounds__(256) void make_boxes_kernel(Geo g, uint32_t a0,
   close(e0);
 }
 
+// A wave of the word-by-word kernels takes this many consecutive mask words: 64 (one per lane)
+// on large tables, few on small ones, which would otherwise occupy a handful of waves for long.
+static uint32_t words_per_wave(uint32_t n_words) { return n_words >= (1u << 18) ? 64u : 4u; }
+
 // The same for lines whose stride is a multiple of 64 cells, word by word of the table-order
 // mask: a wave takes 64 consecutive words (lane t fetches word t and its prefix sum) and then,
 // for every word that flags a cell, stands with its 64 lanes on the word's 64 cells.  These lie
 // on 64 consecutive lines at the same step, so the lanes read consecutive words of the line-major
 // mask (for the run's end), and the boxes they open have consecutive indices: all of a wave's
 // reads and writes are contiguous stretches.
-__global__ __launch_bounds__(256) void make_boxes_wave_kernel(Geo g, uint32_t a0, uint32_t n_words,
+__global__ __launch_bounds__(256) void make_boxes_wave_kernel(Geo g, uint32_t a0, uint32_t n_words, uint32_t wpw,
                                                               const unsigned long long* __restrict__ mask,
                                                               const uint32_t* __restrict__ prefix,
                                                               const unsigned long long* __restrict__ line,
                                                               uint32_t* __restrict__ bcell, uint4* __restrict__ blen,
                                                               uint8_t* __restrict__ alive, uint8_t* __restrict__ pred) {
   const uint32_t lane = threadIdx.x & 63u;
-  const uint32_t w0 = (blockIdx.x * 4u + (threadIdx.x >> 6)) * 64u;
+  const uint32_t w0 = (blockIdx.x * 4u + (threadIdx.x >> 6)) * wpw;
   if (w0 >= n_words) return;
   const uint32_t s0 = g.stride[a0], e0 = g.ext[a0], n_lines = g.n / e0, se = s0 * e0;
   const uint32_t shift = (a0 & 3u) * 8u;
-  const unsigned long long mv = w0 + lane < n_words ? mask[w0 + lane] : 0ull;
-  const uint32_t pv = w0 + lane < n_words ? prefix[w0 + lane] : 0u;
+  const bool mine = lane < wpw && w0 + lane < n_words;
+  const unsigned long long mv = mine ? mask[w0 + lane] : 0ull;
+  const uint32_t pv = mine ? prefix[w0 + lane] : 0u;
   for (unsigned long long todo = __ballot(mv != 0); todo; todo &= todo - 1) {
     const uint32_t t = (uint32_t)__ffsll((long long)todo) - 1u;
     const unsigned long long m = readlane64(mv, t);
@@ -408,60 +413,63 @@ __device__ __forceinline__ uint32_t len_byte(const uint4& L, uint32_t a) {
   return (w >> ((a & 3u) * 8)) & 0xFFu;
 }
 
+// Every box still has extent 1 on axis a when its pass comes (an axis is merged once).  Most
+// boxes differ in value from the cell past their end, so the values are compared first and the
+// extents are read only for the few that pass.  block_linked[workgroup] tells the absorb step
+// whether any of the workgroup's boxes got a successor.
 template <bool COST>
 __global__ __launch_bounds__(256) void link_kernel(Geo g, uint32_t a, uint8_t stamp,
                                                    const uint32_t* __restrict__ ids, uint32_t n_boxes,
                                                    const uint32_t* __restrict__ bcell, const uint4* __restrict__ blen,
                                                    const uint8_t* __restrict__ alive, uint8_t* __restrict__ pred,
-                                                   uint32_t* __restrict__ next,
+                                                   uint32_t* __restrict__ next, uint32_t* __restrict__ block_linked,
                                                    const unsigned long long* __restrict__ mask,
                                                    const uint32_t* __restrict__ prefix,
                                                    const uint64_t* __restrict__ cost, const uint16_t* __restrict__ arg,
                                                    const uint32_t* __restrict__ axis_sizes) {
   const uint32_t i = blockIdx.x * 256u + threadIdx.x;
-  if (i >= n_boxes) return;
-  const uint32_t b = ids ? ids[i] : i;
-  if (!alive[b]) return;
-  const uint32_t cell = bcell[b];
-  const uint4 L = blen[b];
-  const uint32_t sa = g.stride[a], ea = g.ext[a];
-  const uint32_t ca = (cell / sa) % ea;
-  const uint32_t la = len_byte(L, a);
+  const uint32_t b = i < n_boxes ? (ids ? ids[i] : i) : 0u;
+  const bool live = i < n_boxes && alive[b];
   uint32_t nxt = 0xFFFFFFFFu;
-  if (ca + la < ea) {
-    const uint32_t s = cell + la * sa;
-    // cheapest test first: most boxes differ in value from the cell past their end
-    bool same;
-    if (COST) {
-      const uint32_t s1 = axis_sizes ? axis_sizes[ca] : 1u, s2 = axis_sizes ? axis_sizes[ca + la] : 1u;
-      same = norm_equal(cost[cell], s1, cost[s], s2);
-    } else {
-      same = arg[cell] == arg[s];
-    }
-    if (same) {
-      const unsigned long long m = mask[s >> 6];
-      if ((m >> (s & 63u)) & 1ull) {
-        const uint32_t o = prefix[s >> 6] + (uint32_t)__popcll(m & ((1ull << (s & 63u)) - 1ull));
-        if (alive[o]) {
-          const uint4 M = blen[o];
-          const uint32_t keep = ~(0xFFu << ((a & 3u) * 8));
-          const uint32_t kx = (a >> 2) == 0 ? keep : ~0u, ky = (a >> 2) == 1 ? keep : ~0u;
-          const uint32_t kz = (a >> 2) == 2 ? keep : ~0u, kw = (a >> 2) == 3 ? keep : ~0u;
-          if (((L.x ^ M.x) & kx) == 0 && ((L.y ^ M.y) & ky) == 0 && ((L.z ^ M.z) & kz) == 0 && ((L.w ^ M.w) & kw) == 0) {
-            nxt = o;
-            pred[o] = stamp;
+  if (live) {
+    const uint32_t cell = bcell[b];
+    const uint32_t sa = g.stride[a], ea = g.ext[a];
+    const uint32_t ca = (cell / sa) % ea;
+    if (ca + 1 < ea) {
+      const uint32_t s = cell + sa;
+      bool same;
+      if (COST) {
+        const uint32_t s1 = axis_sizes ? axis_sizes[ca] : 1u, s2 = axis_sizes ? axis_sizes[ca + 1] : 1u;
+        same = norm_equal(cost[cell], s1, cost[s], s2);
+      } else {
+        same = arg[cell] == arg[s];
+      }
+      if (same) {
+        const unsigned long long m = mask[s >> 6];
+        if ((m >> (s & 63u)) & 1ull) {
+          const uint32_t o = prefix[s >> 6] + (uint32_t)__popcll(m & ((1ull << (s & 63u)) - 1ull));
+          if (alive[o]) {
+            const uint4 L = blen[b], M = blen[o];     // equal on a as well: both 1
+            if (L.x == M.x && L.y == M.y && L.z == M.z && L.w == M.w) {
+              nxt = o;
+              pred[o] = stamp;
+            }
           }
         }
       }
     }
+    next[b] = nxt;
   }
-  next[b] = nxt;
+  const int any = __syncthreads_or(nxt != 0xFFFFFFFFu);
+  if (threadIdx.x == 0) block_linked[blockIdx.x] = (uint32_t)any;
 }
 
 __global__ __launch_bounds__(256) void absorb_kernel(uint32_t a, uint8_t stamp, const uint32_t* __restrict__ ids,
                                                      uint32_t n_boxes, uint8_t* __restrict__ blen_bytes,
                                                      uint8_t* __restrict__ alive, const uint8_t* __restrict__ pred,
-                                                     const uint32_t* __restrict__ next) {
+                                                     const uint32_t* __restrict__ next,
+                                                     const uint32_t* __restrict__ block_linked) {
+  if (!block_linked[blockIdx.x]) return;       // no box of this workgroup got a successor: no chain starts here
   const uint32_t i = blockIdx.x * 256u + threadIdx.x;
   if (i >= n_boxes) return;
   const uint32_t b = ids ? ids[i] : i;
@@ -495,7 +503,8 @@ void launch_make_boxes(const Geo& g, uint32_t a0, const unsigned long long* mask
   const uint32_t n_lines = g.n / g.ext[a0];
   if (g.stride[a0] % 64 == 0) {
     const uint32_t n_words = g.n / 64;
-    hipLaunchKernelGGL(make_boxes_wave_kernel, dim3((n_words + 255) / 256), dim3(256), 0, st, g, a0, n_words, mask, prefix,
+    const uint32_t wpw = words_per_wave(n_words);
+    hipLaunchKernelGGL(make_boxes_wave_kernel, dim3((n_words + 4 * wpw - 1) / (4 * wpw)), dim3(256), 0, st, g, a0, n_words, wpw, mask, prefix,
                        line, bcell, (uint4*)blen, alive, pred);
   } else {
     hipLaunchKernelGGL(make_boxes_kernel, dim3((n_lines + 255) / 256), dim3(256), 0, st, g, a0, mask, prefix, line, bcell,
@@ -505,17 +514,19 @@ void launch_make_boxes(const Geo& g, uint32_t a0, const unsigned long long* mask
 
 void launch_axis_pass(const Geo& g, uint32_t a, uint8_t stamp, bool is_cost, const uint32_t* ids, uint32_t n_boxes,
                       const uint32_t* bcell,
-                      void* blen, uint8_t* alive, uint8_t* pred, uint32_t* next, const unsigned long long* mask,
+                      void* blen, uint8_t* alive, uint8_t* pred, uint32_t* next, uint32_t* block_linked,
+                      const unsigned long long* mask,
                       const uint32_t* prefix, const uint64_t* cost, const uint16_t* arg, const uint32_t* axis_sizes,
                       hipStream_t st) {
   const uint32_t blocks = (n_boxes + 255) / 256;
   if (is_cost)
     hipLaunchKernelGGL(link_kernel<true>, dim3(blocks), dim3(256), 0, st, g, a, stamp, ids, n_boxes, bcell, (const uint4*)blen,
-                       alive, pred, next, mask, prefix, cost, arg, axis_sizes);
+                       alive, pred, next, block_linked, mask, prefix, cost, arg, axis_sizes);
   else
     hipLaunchKernelGGL(link_kernel<false>, dim3(blocks), dim3(256), 0, st, g, a, stamp, ids, n_boxes, bcell, (const uint4*)blen,
-                       alive, pred, next, mask, prefix, cost, arg, axis_sizes);
-  hipLaunchKernelGGL(absorb_kernel, dim3(blocks), dim3(256), 0, st, a, stamp, ids, n_boxes, (uint8_t*)blen, alive, pred, next);
+                       alive, pred, next, block_linked, mask, prefix, cost, arg, axis_sizes);
+  hipLaunchKernelGGL(absorb_kernel, dim3(blocks), dim3(256), 0, st, a, stamp, ids, n_boxes, (uint8_t*)blen, alive, pred, next,
+                     block_linked);
 }
 
 // ---------------------------------------------------------------- the last passes, in one
@@ -526,16 +537,17 @@ void launch_axis_pass(const Geo& g, uint32_t a, uint8_t stamp, bool is_cost, con
 // that start there in registers, and runs all those passes with lane exchanges: one read and at
 // most one write of every box instead of one per pass.
 template <bool COST>
-__global__ __launch_bounds__(256) void tail_pairs_kernel(TailAxes T, uint32_t n_words,
+__global__ __launch_bounds__(256) void tail_pairs_kernel(TailAxes T, uint32_t n_words, uint32_t wpw,
                                                          const unsigned long long* __restrict__ mask,
                                                          const uint32_t* __restrict__ prefix, uint4* __restrict__ blen,
                                                          uint8_t* __restrict__ alive, const uint64_t* __restrict__ cost,
                                                          const uint16_t* __restrict__ arg) {
   const uint32_t lane = threadIdx.x & 63u;
-  const uint32_t w0 = (blockIdx.x * 4u + (threadIdx.x >> 6)) * 64u;
+  const uint32_t w0 = (blockIdx.x * 4u + (threadIdx.x >> 6)) * wpw;
   if (w0 >= n_words) return;
-  const unsigned long long mv = w0 + lane < n_words ? mask[w0 + lane] : 0ull;
-  const uint32_t pv = w0 + lane < n_words ? prefix[w0 + lane] : 0u;
+  const bool mine = lane < wpw && w0 + lane < n_words;
+  const unsigned long long mv = mine ? mask[w0 + lane] : 0ull;
+  const uint32_t pv = mine ? prefix[w0 + lane] : 0u;
   for (unsigned long long todo = __ballot(mv != 0); todo; todo &= todo - 1) {
     const uint32_t t = (uint32_t)__ffsll((long long)todo) - 1u;
     const unsigned long long m = readlane64(mv, t);
@@ -577,12 +589,12 @@ __global__ __launch_bounds__(256) void tail_pairs_kernel(TailAxes T, uint32_t n_
 void launch_tail_pairs(const TailAxes& T, bool is_cost, uint32_t n_words, const unsigned long long* mask,
                        const uint32_t* prefix, void* blen, uint8_t* alive, const uint64_t* cost, const uint16_t* arg,
                        hipStream_t st) {
-  const uint32_t blocks = (n_words + 255) / 256;
+  const uint32_t wpw = words_per_wave(n_words), blocks = (n_words + 4 * wpw - 1) / (4 * wpw);
   if (is_cost)
-    hipLaunchKernelGGL(tail_pairs_kernel<true>, dim3(blocks), dim3(256), 0, st, T, n_words, mask, prefix, (uint4*)blen, alive,
+    hipLaunchKernelGGL(tail_pairs_kernel<true>, dim3(blocks), dim3(256), 0, st, T, n_words, wpw, mask, prefix, (uint4*)blen, alive,
                        cost, arg);
   else
-    hipLaunchKernelGGL(tail_pairs_kernel<false>, dim3(blocks), dim3(256), 0, st, T, n_words, mask, prefix, (uint4*)blen, alive,
+    hipLaunchKernelGGL(tail_pairs_kernel<false>, dim3(blocks), dim3(256), 0, st, T, n_words, wpw, mask, prefix, (uint4*)blen, alive,
                        cost, arg);
 }
 

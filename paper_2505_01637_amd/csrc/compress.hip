@@ -356,7 +356,7 @@ __global__ __launch_bounds__(256) void make_boxes_kernel(Geo g, uint32_t a0,
 
 // A wave of the word-by-word kernels takes this many consecutive mask words: 64 (one per lane)
 // on large tables, few on small ones, which would otherwise occupy a handful of waves for long.
-static uint32_t words_per_wave(uint32_t n_words) { return n_words >= (1u << 18) ? 64u : 4u; }
+static uint32_t words_per_wave(uint32_t n_words) { return n_words >= (1u << 21) ? 64u : 8u; }
 
 // The same for lines whose stride is a multiple of 64 cells, word by word of the table-order
 // mask: a wave takes 64 consecutive words (lane t fetches word t and its prefix sum) and then,

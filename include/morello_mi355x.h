@@ -142,7 +142,10 @@ typedef struct mrl_table mrl_table;
  * NULL / 0 otherwise.  d_cost (uint64 per Spec), d_argmin (uint16 per Spec) and
  * d_scratch are DEVICE pointers, 256-byte aligned, owned by the caller and
  * referenced by *out until mrl_table_destroy.  hip_stream: a hipStream_t (or
- * NULL for the default stream); the call returns after the stream has drained.
+ * NULL for the default stream); part of the work runs on a helper stream of
+ * the library (default priority) that is ordered after and before the given
+ * one, and the call returns after both have drained.  Calls of mrl_solve are
+ * serialized within a process: they share that helper stream.
  * stats: host, optional. */
 int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat,
                   const mrl_table* const* deps, uint32_t n_deps,
@@ -151,8 +154,8 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat,
 void mrl_table_destroy(mrl_table* tab);
 
 /* ---------------------------------------------------------------------------
- * Query (Section 4: "if the memoization database contains a rewrite for that
- * Spec, return it").  specs, cost_out, rewrite_out: host arrays of n. */
+ * Query (Section 4: a Spec that the memo table already holds is answered from
+ * it).  specs, cost_out, rewrite_out: host arrays of n. */
 typedef struct { uint32_t x[MRL_MAX_DIMS]; } mrl_coord;
 int32_t mrl_query(const mrl_table* tab, const mrl_coord* specs, size_t n,
                   uint64_t* cost_out, uint16_t* rewrite_out);

@@ -64,7 +64,7 @@ struct Compiled {
 
 // Offsets of the fixed part of the scratch buffer.
 struct FixedLayout {
-  size_t counters, params, tiles, level_shapes, shape_class, level_off, mk_entry, list_whole, list_slice, list_wide, list_cnt, fitmap, maskD, maskC, lineD, lineC, prefD, prefC, tile_tmp, totals,
+  size_t counters, params, tiles, level_shapes, shape_class, level_off, mk_entry, list_whole, list_slice, list_wide, list_cnt, fitmap, maskD, maskC, lineD, lineC, prefD, prefC, tile_tmp, tile_tmp2, totals,
       q_idx, q_cost, q_arg, end;
   uint32_t n_words;
 };
@@ -99,6 +99,7 @@ FixedLayout fixed_layout(const Compiled& c) {
   f.prefD = take((size_t)f.n_words * 4);
   f.prefC = take((size_t)f.n_words * 4);
   f.tile_tmp = take((c.n_specs / kScanTileItems + 2) * 4);
+  f.tile_tmp2 = take((c.n_specs / kScanTileItems + 2) * 4);
   f.totals = take(64);
   f.q_idx = take(kQueryChunk * 8);
   f.q_cost = take(kQueryChunk * 8);
@@ -379,10 +380,12 @@ int32_t get_compiled(const mrl_target_desc& T, const mrl_lattice_desc* L, Compil
 }
 
 // A second stream (default priority, non-blocking) for work that is independent of what runs on
-// the caller's stream: the wide items of a dependency level beside its other items.  Created once per process; events likewise.
+// the caller's stream: the wide items of a dependency level beside its other items, and one of the
+// two box lists beside the other.  Created once per process; events likewise.
 struct Aux {
   hipStream_t stream = nullptr;
   std::vector<hipEvent_t> events;
+  uint32_t* h_counts = nullptr;     // pinned: counts read back without stalling the other stream
 };
 
 int32_t get_aux(size_t n_events, Aux*& out) {
@@ -390,6 +393,7 @@ int32_t get_aux(size_t n_events, Aux*& out) {
   static std::mutex mu;
   std::lock_guard<std::mutex> lock(mu);
   if (!aux.stream) HIP_TRY(hipStreamCreateWithFlags(&aux.stream, hipStreamNonBlocking));
+  if (!aux.h_counts) HIP_TRY(hipHostMalloc((void**)&aux.h_counts, 64, hipHostMallocDefault));
   while (aux.events.size() < n_events) {
     hipEvent_t e;
     HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
@@ -454,7 +458,7 @@ int32_t mrl_table_bytes(const mrl_target* t, const mrl_lattice_desc* lat, size_t
   const Compiled& c = *cp;
   if (cost_bytes) *cost_bytes = c.n_specs * 8;
   if (argmin_bytes) *argmin_bytes = c.n_specs * 2;
-  if (scratch_bytes) *scratch_bytes = fixed_layout(c).end + 2 * final_bytes(c.n_specs) + work_bytes(c.n_specs);
+  if (scratch_bytes) *scratch_bytes = fixed_layout(c).end + 2 * final_bytes(c.n_specs) + 2 * work_bytes(c.n_specs);
   return MRL_OK;
 }
 
@@ -492,6 +496,10 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
     return fail(MRL_E_INVAL, "only a FUSED lattice takes deps");
   }
 
+  // the helper stream, its events and the pinned counters are one set per process
+  static std::mutex solve_mu;
+  std::lock_guard<std::mutex> solve_lock(solve_mu);
+
   const FixedLayout f = fixed_layout(c);
   tab->f = f;
   if (scratch_bytes < f.end) return fail(MRL_E_NOMEM, "scratch buffer too small: %zu bytes given, at least %zu needed", scratch_bytes, f.end);
@@ -527,7 +535,7 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
   // ---- fill: one launch per dependency level ----
   // ---- fill: plan, then one launch (or two) per dependency level ----
   Aux* aux = nullptr;
-  rc = get_aux(2 * (size_t)n_lev + 2, aux);
+  rc = get_aux(2 * (size_t)n_lev + 3, aux);
   if (rc) return rc;
   size_t ev_used = 0;
   hipStream_t s2 = aux->stream;
@@ -583,15 +591,33 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
   HIP_TRY(hipMemcpyAsync(h_tot, d_tot, 8, hipMemcpyDeviceToHost, st));
   HIP_TRY(hipStreamSynchronize(st));
 
+  // The two lists are merged side by side, the decisions on the helper stream: most of the
+  // kernels are bound by latency, not bandwidth.  Nothing in a list's passes waits for the host:
+  // the lengths of the compacted lists of live boxes stay on the device (slots of d_tot), and the
+  // kernels that walk such a list get the length before compaction as the bound of their grid.
+  // Work areas at the end of the buffer, the final lists grow from the front.
+  const uint64_t nbL[2] = {h_tot[0], h_tot[1]};
+  const size_t wbL[2] = {work_bytes(nbL[0]), work_bytes(nbL[1])};
   size_t front = f.end;
-  size_t needed = f.end;
+  size_t needed = f.end + wbL[0] + wbL[1] + final_bytes(nbL[0]) + final_bytes(nbL[1]);   // upper bound until the final counts are known
+  if (scratch_bytes < f.end + wbL[0] + wbL[1])
+    return fail(MRL_E_NOMEM, "scratch buffer too small: %zu bytes given, up to %zu needed", scratch_bytes, needed);
+  char* work_lo = base + (scratch_bytes - wbL[0] - wbL[1]) / kAlign * kAlign;
+  if ((size_t)(work_lo - base) < f.end)
+    return fail(MRL_E_NOMEM, "scratch buffer too small: %zu bytes given, up to %zu needed", scratch_bytes, needed);
+  struct ListWork {
+    uint32_t *bcell, *pos;
+    char* blen;
+    uint8_t* alive;
+    const uint32_t *ids, *n_ptr;
+    uint32_t n_bound;
+  } LW[2];
+  hipStream_t stL[2] = {s2, st};
+  uint32_t* tileL[2] = {(uint32_t*)(base + f.tile_tmp2), tile_tmp};
   for (int which = 0; which < 2; which++) {
-    const uint64_t nb = h_tot[which];
-    const size_t wb = work_bytes(nb);
-    needed = std::max(needed, front + final_bytes(nb) + wb);   // upper bound before the final count is known
-    if (scratch_bytes < front + wb) return fail(MRL_E_NOMEM, "scratch buffer too small: %zu bytes given, %zu needed", scratch_bytes, front + wb + final_bytes(nb));
-    char* w = base + (scratch_bytes - wb) / kAlign * kAlign;
-    if ((size_t)(w - base) < front) return fail(MRL_E_NOMEM, "scratch buffer too small: %zu bytes given, %zu needed", scratch_bytes, front + wb + final_bytes(nb));
+    const uint64_t nb = nbL[which];
+    hipStream_t sw = stL[which];
+    char* w = which == 0 ? work_lo : work_lo + wbL[0];
     uint32_t* bcell = (uint32_t*)w; w += align_up(nb * 4);
     char* blen = w; w += align_up(nb * 16);
     uint8_t* alive = (uint8_t*)w; w += align_up(nb);
@@ -600,12 +626,14 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
     uint32_t* pos = (uint32_t*)w; w += align_up(nb * 4);
     uint32_t* live_buf[2] = {(uint32_t*)w, (uint32_t*)(w + align_up(nb * 4))};
     uint32_t* block_linked = (uint32_t*)(w + 2 * align_up(nb * 4));
-    launch_make_boxes(g, a0, maskL[which], prefL[which], lineL[which], bcell, blen, alive, pred, st);
+    uint32_t* d_cnt = d_tot + 4 + which * 4;        // [0], [1]: lengths of the compacted lists; [2]: the final count
+    launch_make_boxes(g, a0, maskL[which], prefL[which], lineL[which], bcell, blen, alive, pred, sw);
     // boxes still to be visited: all of them at first, then compacted lists of the live ones
     // (ascending index) once the first passes have merged most boxes away
     const uint32_t* ids = nullptr;
-    uint32_t n_ids = (uint32_t)nb, n_pass = 0, flip = 0;
-    bool counted = false;           // h_tot[2] holds the live count of the current list
+    const uint32_t* n_ptr = nullptr;
+    const uint32_t n_bound = (uint32_t)nb;
+    uint32_t n_pass = 0, flip = 0;
     uint8_t stamp = 0;
     // the passes in order; the trailing ones over bit axes inside a mask word are done in one kernel
     uint32_t pass_axis[16], n_axes = 0;
@@ -620,45 +648,47 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
     for (uint32_t k = 0; k < tail.n; k++) { tail.axis[k] = pass_axis[n_generic + k]; tail.stride[k] = g.stride[pass_axis[n_generic + k]]; }
     for (uint32_t q = 0; q < n_generic; q++) {
       const uint32_t a = pass_axis[q];
-      launch_axis_pass(g, a, ++stamp, which == 1, ids, n_ids, bcell, blen, alive, pred, next, block_linked, maskL[which],
-                       prefL[which],
-                       tab->d_cost, tab->d_arg, axis_sizes(a), st);
-      counted = false;
+      launch_axis_pass(g, a, ++stamp, which == 1, ids, n_bound, n_ptr, bcell, blen, alive, pred, next, block_linked, maskL[which],
+                       prefL[which], tab->d_cost, tab->d_arg, axis_sizes(a), sw);
       n_pass++;
-      if (n_pass <= 2 && n_ids > (1u << 20)) {
-        scan_flags(alive, ids, n_ids, tile_tmp, pos, d_tot + 2, st);
-        launch_compact_live(alive, ids, n_ids, pos, live_buf[flip], st);
-        HIP_TRY(hipMemcpyAsync(h_tot + 2, d_tot + 2, 4, hipMemcpyDeviceToHost, st));
-        HIP_TRY(hipStreamSynchronize(st));
+      if (n_pass <= 2 && n_bound > (1u << 20)) {
+        scan_flags(alive, ids, n_bound, n_ptr, tileL[which], pos, d_cnt + flip, sw);
+        launch_compact_live(alive, ids, n_bound, n_ptr, pos, live_buf[flip], sw);
         ids = live_buf[flip];
-        n_ids = h_tot[2];
+        n_ptr = d_cnt + flip;
         flip ^= 1;
-        counted = true;
       }
     }
-    if (tail.n) {
-      launch_tail_pairs(tail, which == 1, f.n_words, maskL[which], prefL[which], blen, alive, tab->d_cost, tab->d_arg, st);
-      counted = false;
-    }
-    scan_flags(alive, ids, n_ids, tile_tmp, pos, d_tot + 2, st);
-    if (!counted) {
-      HIP_TRY(hipMemcpyAsync(h_tot + 2, d_tot + 2, 4, hipMemcpyDeviceToHost, st));
-      HIP_TRY(hipStreamSynchronize(st));
-    }
-    const uint64_t nf = h_tot[2];
+    if (tail.n)
+      launch_tail_pairs(tail, which == 1, f.n_words, maskL[which], prefL[which], blen, alive, tab->d_cost, tab->d_arg, sw);
+    scan_flags(alive, ids, n_bound, n_ptr, tileL[which], pos, d_cnt + 2, sw);
+    HIP_TRY(hipMemcpyAsync(aux->h_counts + which, d_cnt + 2, 4, hipMemcpyDeviceToHost, sw));
+    LW[which] = {bcell, pos, blen, alive, ids, n_ptr, n_bound};
+  }
+  for (int which = 0; which < 2; which++) {
+    HIP_TRY(hipStreamSynchronize(stL[which]));
+    const uint64_t nf = aux->h_counts[which];
     const size_t fb = final_bytes(nf);
-    if (front + fb > (size_t)((char*)bcell - base)) return fail(MRL_E_NOMEM, "scratch buffer too small: %zu bytes given, %zu needed", scratch_bytes, front + fb + wb);
+    if (front + fb > (size_t)(work_lo - base)) {
+      HIP_TRY(hipStreamSynchronize(stL[1]));
+      return fail(MRL_E_NOMEM, "scratch buffer too small: %zu bytes given, %zu needed", scratch_bytes,
+                  front + fb + (which == 0 ? final_bytes(nbL[1]) : 0) + wbL[0] + wbL[1]);
+    }
     char* r = base + front;
     uint32_t* fcell = (uint32_t*)r; r += align_up(nf * 4);
     char* flen = r; r += align_up(nf * 16);
     uint64_t* fv0 = (uint64_t*)r; r += align_up(nf * 8);
     uint64_t* fv1 = (uint64_t*)r;
-    launch_emit(g, d_P, which == 1, ids, n_ids, bcell, blen, alive, pos, tab->d_cost, tab->d_arg, fcell, flen, fv0, fv1, st);
+    const ListWork& W = LW[which];
+    launch_emit(g, d_P, which == 1, W.ids, W.n_bound, W.n_ptr, W.bcell, W.blen, W.alive, W.pos, tab->d_cost, tab->d_arg, fcell,
+                flen, fv0, fv1, stL[which]);
     tab->list_off[which] = front;
     tab->list_n[which] = nf;
-    needed = std::max(needed, front + fb + wb);
     front += fb;
   }
+  needed = front + wbL[0] + wbL[1];
+  HIP_TRY(hipEventRecord(aux->events[ev_used], s2));
+  HIP_TRY(hipStreamWaitEvent(st, aux->events[ev_used++], 0));
   HIP_TRY(hipGetLastError());
   HIP_TRY(hipEventRecord(ev[2], st));
   Counters h_ctr;

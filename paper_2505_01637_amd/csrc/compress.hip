@@ -213,9 +213,13 @@ __device__ __forceinline__ uint32_t block_reduce_256(uint32_t v, uint32_t* sh) {
   return t;
 }
 
+// Item counts: where a count is only known on the device (the length of a compacted list), the
+// kernels get an upper bound n for the grid and read the count itself from n_ptr.
 template <class L>
-__global__ __launch_bounds__(256) void scan_tile_sums_kernel(L load, uint32_t n, uint32_t* __restrict__ tile_sum) {
+__global__ __launch_bounds__(256) void scan_tile_sums_kernel(L load, uint32_t n, const uint32_t* __restrict__ n_ptr,
+                                                             uint32_t* __restrict__ tile_sum) {
   __shared__ uint32_t sh[4];
+  if (n_ptr) n = *n_ptr;
   const uint32_t first = blockIdx.x * kScanTile + threadIdx.x * kScanItems;
   uint32_t s = 0;
 #pragma unroll
@@ -254,9 +258,12 @@ __global__ __launch_bounds__(256) void scan_top_kernel(uint32_t* __restrict__ ti
 }
 
 template <class L>
-__global__ __launch_bounds__(256) void scan_apply_kernel(L load, uint32_t n, const uint32_t* __restrict__ tile_excl,
+__global__ __launch_bounds__(256) void scan_apply_kernel(L load, uint32_t n, const uint32_t* __restrict__ n_ptr,
+                                                         const uint32_t* __restrict__ tile_excl,
                                                          uint32_t* __restrict__ out) {
   __shared__ uint32_t sh[4];
+  if (n_ptr) n = *n_ptr;
+  if (blockIdx.x * kScanTile >= n) return;
   const uint32_t first = blockIdx.x * kScanTile + threadIdx.x * kScanItems;
   uint32_t v[kScanItems], s = 0;
 #pragma unroll
@@ -276,36 +283,39 @@ __global__ __launch_bounds__(256) void scan_apply_kernel(L load, uint32_t n, con
 }
 
 template <class L>
-static void exclusive_scan(L load, uint32_t n, uint32_t* tile_tmp, uint32_t* out, uint32_t* total, hipStream_t st) {
+static void exclusive_scan(L load, uint32_t n, const uint32_t* n_ptr, uint32_t* tile_tmp, uint32_t* out, uint32_t* total,
+                           hipStream_t st) {
   const uint32_t n_tiles = (n + kScanTile - 1) / kScanTile;
-  hipLaunchKernelGGL(scan_tile_sums_kernel<L>, dim3(n_tiles), dim3(256), 0, st, load, n, tile_tmp);
+  hipLaunchKernelGGL(scan_tile_sums_kernel<L>, dim3(n_tiles), dim3(256), 0, st, load, n, n_ptr, tile_tmp);
   hipLaunchKernelGGL(scan_top_kernel, dim3(1), dim3(256), 0, st, tile_tmp, n_tiles, total);
-  hipLaunchKernelGGL(scan_apply_kernel<L>, dim3(n_tiles), dim3(256), 0, st, load, n, tile_tmp, out);
+  hipLaunchKernelGGL(scan_apply_kernel<L>, dim3(n_tiles), dim3(256), 0, st, load, n, n_ptr, tile_tmp, out);
 }
 
 void scan_mask_words(const unsigned long long* mask, uint32_t n_words, uint32_t* tile_tmp, uint32_t* prefix,
                      uint32_t* total, hipStream_t st) {
-  exclusive_scan(LoadPopc{mask}, n_words, tile_tmp, prefix, total, st);
+  exclusive_scan(LoadPopc{mask}, n_words, nullptr, tile_tmp, prefix, total, st);
 }
 
-void scan_flags(const uint8_t* flags, const uint32_t* ids, uint32_t n, uint32_t* tile_tmp, uint32_t* pos, uint32_t* total,
-                hipStream_t st) {
-  exclusive_scan(LoadFlag{flags, ids}, n, tile_tmp, pos, total, st);
+void scan_flags(const uint8_t* flags, const uint32_t* ids, uint32_t n, const uint32_t* n_ptr, uint32_t* tile_tmp,
+                uint32_t* pos, uint32_t* total, hipStream_t st) {
+  exclusive_scan(LoadFlag{flags, ids}, n, n_ptr, tile_tmp, pos, total, st);
 }
 
 // out[pos[i]] = index of the i-th listed box, for the boxes still alive (keeps ascending order).
 __global__ __launch_bounds__(256) void compact_live_kernel(const uint8_t* __restrict__ alive,
                                                            const uint32_t* __restrict__ ids, uint32_t n,
+                                                           const uint32_t* __restrict__ n_ptr,
                                                            const uint32_t* __restrict__ pos, uint32_t* __restrict__ out) {
+  if (n_ptr) n = *n_ptr;
   const uint32_t i = blockIdx.x * 256u + threadIdx.x;
   if (i >= n) return;
   const uint32_t b = ids ? ids[i] : i;
   if (alive[b]) out[pos[i]] = b;
 }
 
-void launch_compact_live(const uint8_t* alive, const uint32_t* ids, uint32_t n, const uint32_t* pos, uint32_t* out,
-                         hipStream_t st) {
-  hipLaunchKernelGGL(compact_live_kernel, dim3((n + 255) / 256), dim3(256), 0, st, alive, ids, n, pos, out);
+void launch_compact_live(const uint8_t* alive, const uint32_t* ids, uint32_t n, const uint32_t* n_ptr, const uint32_t* pos,
+                         uint32_t* out, hipStream_t st) {
+  hipLaunchKernelGGL(compact_live_kernel, dim3((n + 255) / 256), dim3(256), 0, st, alive, ids, n, n_ptr, pos, out);
 }
 
 // ---------------------------------------------------------------- boxes of pass 0
@@ -420,6 +430,7 @@ __device__ __forceinline__ uint32_t len_byte(const uint4& L, uint32_t a) {
 template <bool COST>
 __global__ __launch_bounds__(256) void link_kernel(Geo g, uint32_t a, uint8_t stamp,
                                                    const uint32_t* __restrict__ ids, uint32_t n_boxes,
+                                                   const uint32_t* __restrict__ n_ptr,
                                                    const uint32_t* __restrict__ bcell, const uint4* __restrict__ blen,
                                                    const uint8_t* __restrict__ alive, uint8_t* __restrict__ pred,
                                                    uint32_t* __restrict__ next, uint32_t* __restrict__ block_linked,
@@ -427,6 +438,7 @@ __global__ __launch_bounds__(256) void link_kernel(Geo g, uint32_t a, uint8_t st
                                                    const uint32_t* __restrict__ prefix,
                                                    const uint64_t* __restrict__ cost, const uint16_t* __restrict__ arg,
                                                    const uint32_t* __restrict__ axis_sizes) {
+  if (n_ptr) n_boxes = *n_ptr;
   const uint32_t i = blockIdx.x * 256u + threadIdx.x;
   const uint32_t b = i < n_boxes ? (ids ? ids[i] : i) : 0u;
   const bool live = i < n_boxes && alive[b];
@@ -465,11 +477,13 @@ __global__ __launch_bounds__(256) void link_kernel(Geo g, uint32_t a, uint8_t st
 }
 
 __global__ __launch_bounds__(256) void absorb_kernel(uint32_t a, uint8_t stamp, const uint32_t* __restrict__ ids,
-                                                     uint32_t n_boxes, uint8_t* __restrict__ blen_bytes,
+                                                     uint32_t n_boxes, const uint32_t* __restrict__ n_ptr,
+                                                     uint8_t* __restrict__ blen_bytes,
                                                      uint8_t* __restrict__ alive, const uint8_t* __restrict__ pred,
                                                      const uint32_t* __restrict__ next,
                                                      const uint32_t* __restrict__ block_linked) {
   if (!block_linked[blockIdx.x]) return;       // no box of this workgroup got a successor: no chain starts here
+  if (n_ptr) n_boxes = *n_ptr;
   const uint32_t i = blockIdx.x * 256u + threadIdx.x;
   if (i >= n_boxes) return;
   const uint32_t b = ids ? ids[i] : i;
@@ -513,20 +527,20 @@ void launch_make_boxes(const Geo& g, uint32_t a0, const unsigned long long* mask
 }
 
 void launch_axis_pass(const Geo& g, uint32_t a, uint8_t stamp, bool is_cost, const uint32_t* ids, uint32_t n_boxes,
-                      const uint32_t* bcell,
+                      const uint32_t* n_ptr, const uint32_t* bcell,
                       void* blen, uint8_t* alive, uint8_t* pred, uint32_t* next, uint32_t* block_linked,
                       const unsigned long long* mask,
                       const uint32_t* prefix, const uint64_t* cost, const uint16_t* arg, const uint32_t* axis_sizes,
                       hipStream_t st) {
   const uint32_t blocks = (n_boxes + 255) / 256;
   if (is_cost)
-    hipLaunchKernelGGL(link_kernel<true>, dim3(blocks), dim3(256), 0, st, g, a, stamp, ids, n_boxes, bcell, (const uint4*)blen,
-                       alive, pred, next, block_linked, mask, prefix, cost, arg, axis_sizes);
+    hipLaunchKernelGGL(link_kernel<true>, dim3(blocks), dim3(256), 0, st, g, a, stamp, ids, n_boxes, n_ptr, bcell,
+                       (const uint4*)blen, alive, pred, next, block_linked, mask, prefix, cost, arg, axis_sizes);
   else
-    hipLaunchKernelGGL(link_kernel<false>, dim3(blocks), dim3(256), 0, st, g, a, stamp, ids, n_boxes, bcell, (const uint4*)blen,
-                       alive, pred, next, block_linked, mask, prefix, cost, arg, axis_sizes);
-  hipLaunchKernelGGL(absorb_kernel, dim3(blocks), dim3(256), 0, st, a, stamp, ids, n_boxes, (uint8_t*)blen, alive, pred, next,
-                     block_linked);
+    hipLaunchKernelGGL(link_kernel<false>, dim3(blocks), dim3(256), 0, st, g, a, stamp, ids, n_boxes, n_ptr, bcell,
+                       (const uint4*)blen, alive, pred, next, block_linked, mask, prefix, cost, arg, axis_sizes);
+  hipLaunchKernelGGL(absorb_kernel, dim3(blocks), dim3(256), 0, st, a, stamp, ids, n_boxes, n_ptr, (uint8_t*)blen, alive, pred,
+                     next, block_linked);
 }
 
 // ---------------------------------------------------------------- the last passes, in one
@@ -607,11 +621,13 @@ __device__ __forceinline__ uint64_t gcd_u64(uint64_t a, uint64_t b) {
 template <bool COST>
 __global__ __launch_bounds__(256) void emit_kernel(Geo g, const DevParams* __restrict__ P,
                                                    const uint32_t* __restrict__ ids, uint32_t n_boxes,
+                                                   const uint32_t* __restrict__ n_ptr,
                                                    const uint32_t* __restrict__ bcell, const uint4* __restrict__ blen,
                                                    const uint8_t* __restrict__ alive, const uint32_t* __restrict__ pos,
                                                    const uint64_t* __restrict__ cost, const uint16_t* __restrict__ arg,
                                                    uint32_t* __restrict__ fcell, uint4* __restrict__ flen,
                                                    uint64_t* __restrict__ fv0, uint64_t* __restrict__ fv1) {
+  if (n_ptr) n_boxes = *n_ptr;
   const uint32_t i = blockIdx.x * 256u + threadIdx.x;
   if (i >= n_boxes) return;
   const uint32_t b = ids ? ids[i] : i;
@@ -634,17 +650,18 @@ __global__ __launch_bounds__(256) void emit_kernel(Geo g, const DevParams* __res
   }
 }
 
-void launch_emit(const Geo& g, const DevParams* P, bool is_cost, const uint32_t* ids, uint32_t n_boxes, const uint32_t* bcell,
+void launch_emit(const Geo& g, const DevParams* P, bool is_cost, const uint32_t* ids, uint32_t n_boxes,
+                 const uint32_t* n_ptr, const uint32_t* bcell,
                  const void* blen,
                  const uint8_t* alive, const uint32_t* pos, const uint64_t* cost, const uint16_t* arg, uint32_t* fcell,
                  void* flen, uint64_t* fv0, uint64_t* fv1, hipStream_t st) {
   const uint32_t blocks = (n_boxes + 255) / 256;
   if (is_cost)
-    hipLaunchKernelGGL(emit_kernel<true>, dim3(blocks), dim3(256), 0, st, g, P, ids, n_boxes, bcell, (const uint4*)blen, alive,
-                       pos, cost, arg, fcell, (uint4*)flen, fv0, fv1);
+    hipLaunchKernelGGL(emit_kernel<true>, dim3(blocks), dim3(256), 0, st, g, P, ids, n_boxes, n_ptr, bcell, (const uint4*)blen,
+                       alive, pos, cost, arg, fcell, (uint4*)flen, fv0, fv1);
   else
-    hipLaunchKernelGGL(emit_kernel<false>, dim3(blocks), dim3(256), 0, st, g, P, ids, n_boxes, bcell, (const uint4*)blen, alive,
-                       pos, cost, arg, fcell, (uint4*)flen, fv0, fv1);
+    hipLaunchKernelGGL(emit_kernel<false>, dim3(blocks), dim3(256), 0, st, g, P, ids, n_boxes, n_ptr, bcell, (const uint4*)blen,
+                       alive, pos, cost, arg, fcell, (uint4*)flen, fv0, fv1);
 }
 
 // ---------------------------------------------------------------- query

@@ -605,65 +605,84 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
   char* work_lo = base + (scratch_bytes - wbL[0] - wbL[1]) / kAlign * kAlign;
   if ((size_t)(work_lo - base) < f.end)
     return fail(MRL_E_NOMEM, "scratch buffer too small: %zu bytes given, up to %zu needed", scratch_bytes, needed);
+  // per list: its arrays, the boxes still to be visited (all of them at first, then compacted lists of
+  // the live ones, ascending, once the first passes have merged most boxes away) and the pass state
   struct ListWork {
-    uint32_t *bcell, *pos;
+    uint32_t *bcell, *next, *pos, *live_buf[2], *block_linked, *d_cnt;
     char* blen;
-    uint8_t* alive;
-    const uint32_t *ids, *n_ptr;
-    uint32_t n_bound;
+    uint8_t *alive, *pred;
+    const uint32_t *ids = nullptr, *n_ptr = nullptr;
+    uint32_t n_bound = 0, n_pass = 0, flip = 0, q_next = 0;
+    uint8_t stamp = 0;
   } LW[2];
   hipStream_t stL[2] = {s2, st};
   uint32_t* tileL[2] = {(uint32_t*)(base + f.tile_tmp2), tile_tmp};
-  for (int which = 0; which < 2; which++) {
+  // the passes in order; the trailing ones over bit axes inside a mask word are done in one kernel
+  uint32_t pass_axis[16], n_axes = 0;
+  for (uint32_t q = 0; q < g.ndim; q++) {
+    const uint32_t a = c.merge_order[q];
+    if (a != a0 && g.ext[a] > 1) pass_axis[n_axes++] = a;
+  }
+  uint32_t n_generic = n_axes;
+  while (n_generic > 0 && n_axes - n_generic < 6 && g.ext[pass_axis[n_generic - 1]] == 2 && g.stride[pass_axis[n_generic - 1]] <= 32) n_generic--;
+  TailAxes tail;
+  tail.n = n_axes - n_generic;
+  for (uint32_t k = 0; k < tail.n; k++) { tail.axis[k] = pass_axis[n_generic + k]; tail.stride[k] = g.stride[pass_axis[n_generic + k]]; }
+
+  auto one_pass = [&](int which) {        // the next generic pass, then a compaction if it is one of the first two
+    ListWork& W = LW[which];
+    const uint32_t a = pass_axis[W.q_next++];
+    launch_axis_pass(g, a, ++W.stamp, which == 1, W.ids, W.n_bound, W.n_ptr, W.bcell, W.blen, W.alive, W.pred, W.next,
+                     W.block_linked, maskL[which], prefL[which], tab->d_cost, tab->d_arg, axis_sizes(a), stL[which]);
+    W.n_pass++;
+    if (W.n_pass <= 2 && W.n_bound > (1u << 20)) {
+      scan_flags(W.alive, W.ids, W.n_bound, W.n_ptr, tileL[which], W.pos, W.d_cnt + W.flip, stL[which]);
+      launch_compact_live(W.alive, W.ids, W.n_bound, W.n_ptr, W.pos, W.live_buf[W.flip], stL[which]);
+      W.ids = W.live_buf[W.flip];
+      W.n_ptr = W.d_cnt + W.flip;
+      W.flip ^= 1;
+      return true;
+    }
+    return false;
+  };
+  // first part: the boxes of pass 0 and the first generic pass; its compaction removes the most, so
+  // its count is fetched (while the other list's first part runs) to size the later grids
+  bool fetched[2] = {false, false};
+  for (int which = 1; which >= 0; which--) {
+    ListWork& W = LW[which];
     const uint64_t nb = nbL[which];
-    hipStream_t sw = stL[which];
     char* w = which == 0 ? work_lo : work_lo + wbL[0];
-    uint32_t* bcell = (uint32_t*)w; w += align_up(nb * 4);
-    char* blen = w; w += align_up(nb * 16);
-    uint8_t* alive = (uint8_t*)w; w += align_up(nb);
-    uint8_t* pred = (uint8_t*)w; w += align_up(nb);
-    uint32_t* next = (uint32_t*)w; w += align_up(nb * 4);
-    uint32_t* pos = (uint32_t*)w; w += align_up(nb * 4);
-    uint32_t* live_buf[2] = {(uint32_t*)w, (uint32_t*)(w + align_up(nb * 4))};
-    uint32_t* block_linked = (uint32_t*)(w + 2 * align_up(nb * 4));
-    uint32_t* d_cnt = d_tot + 4 + which * 4;        // [0], [1]: lengths of the compacted lists; [2]: the final count
-    launch_make_boxes(g, a0, maskL[which], prefL[which], lineL[which], bcell, blen, alive, pred, sw);
-    // boxes still to be visited: all of them at first, then compacted lists of the live ones
-    // (ascending index) once the first passes have merged most boxes away
-    const uint32_t* ids = nullptr;
-    const uint32_t* n_ptr = nullptr;
-    const uint32_t n_bound = (uint32_t)nb;
-    uint32_t n_pass = 0, flip = 0;
-    uint8_t stamp = 0;
-    // the passes in order; the trailing ones over bit axes inside a mask word are done in one kernel
-    uint32_t pass_axis[16], n_axes = 0;
-    for (uint32_t q = 0; q < g.ndim; q++) {
-      const uint32_t a = c.merge_order[q];
-      if (a != a0 && g.ext[a] > 1) pass_axis[n_axes++] = a;
+    W.bcell = (uint32_t*)w; w += align_up(nb * 4);
+    W.blen = w; w += align_up(nb * 16);
+    W.alive = (uint8_t*)w; w += align_up(nb);
+    W.pred = (uint8_t*)w; w += align_up(nb);
+    W.next = (uint32_t*)w; w += align_up(nb * 4);
+    W.pos = (uint32_t*)w; w += align_up(nb * 4);
+    W.live_buf[0] = (uint32_t*)w; w += align_up(nb * 4);
+    W.live_buf[1] = (uint32_t*)w; w += align_up(nb * 4);
+    W.block_linked = (uint32_t*)w;
+    W.d_cnt = d_tot + 4 + which * 4;       // [0], [1]: lengths of the compacted lists; [2]: the final count
+    W.n_bound = (uint32_t)nb;
+    launch_make_boxes(g, a0, maskL[which], prefL[which], lineL[which], W.bcell, W.blen, W.alive, W.pred, stL[which]);
+    if (n_generic && one_pass(which)) {
+      HIP_TRY(hipMemcpyAsync(aux->h_counts + 2 + which, W.n_ptr, 4, hipMemcpyDeviceToHost, stL[which]));
+      fetched[which] = true;
     }
-    uint32_t n_generic = n_axes;
-    while (n_generic > 0 && n_axes - n_generic < 6 && g.ext[pass_axis[n_generic - 1]] == 2 && g.stride[pass_axis[n_generic - 1]] <= 32) n_generic--;
-    TailAxes tail;
-    tail.n = n_axes - n_generic;
-    for (uint32_t k = 0; k < tail.n; k++) { tail.axis[k] = pass_axis[n_generic + k]; tail.stride[k] = g.stride[pass_axis[n_generic + k]]; }
-    for (uint32_t q = 0; q < n_generic; q++) {
-      const uint32_t a = pass_axis[q];
-      launch_axis_pass(g, a, ++stamp, which == 1, ids, n_bound, n_ptr, bcell, blen, alive, pred, next, block_linked, maskL[which],
-                       prefL[which], tab->d_cost, tab->d_arg, axis_sizes(a), sw);
-      n_pass++;
-      if (n_pass <= 2 && n_bound > (1u << 20)) {
-        scan_flags(alive, ids, n_bound, n_ptr, tileL[which], pos, d_cnt + flip, sw);
-        launch_compact_live(alive, ids, n_bound, n_ptr, pos, live_buf[flip], sw);
-        ids = live_buf[flip];
-        n_ptr = d_cnt + flip;
-        flip ^= 1;
-      }
+  }
+  // second part: the other passes, the final count
+  for (int which = 1; which >= 0; which--) {
+    ListWork& W = LW[which];
+    if (fetched[which]) {
+      HIP_TRY(hipStreamSynchronize(stL[which]));
+      W.n_bound = aux->h_counts[2 + which];
+      W.n_ptr = nullptr;
     }
+    while (W.q_next < n_generic) one_pass(which);
     if (tail.n)
-      launch_tail_pairs(tail, which == 1, f.n_words, maskL[which], prefL[which], blen, alive, tab->d_cost, tab->d_arg, sw);
-    scan_flags(alive, ids, n_bound, n_ptr, tileL[which], pos, d_cnt + 2, sw);
-    HIP_TRY(hipMemcpyAsync(aux->h_counts + which, d_cnt + 2, 4, hipMemcpyDeviceToHost, sw));
-    LW[which] = {bcell, pos, blen, alive, ids, n_ptr, n_bound};
+      launch_tail_pairs(tail, which == 1, f.n_words, maskL[which], prefL[which], W.blen, W.alive, tab->d_cost, tab->d_arg,
+                        stL[which]);
+    scan_flags(W.alive, W.ids, W.n_bound, W.n_ptr, tileL[which], W.pos, W.d_cnt + 2, stL[which]);
+    HIP_TRY(hipMemcpyAsync(aux->h_counts + which, W.d_cnt + 2, 4, hipMemcpyDeviceToHost, stL[which]));
   }
   for (int which = 0; which < 2; which++) {
     HIP_TRY(hipStreamSynchronize(stL[which]));

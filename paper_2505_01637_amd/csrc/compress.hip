@@ -439,6 +439,7 @@ __global__ __launch_bounds__(256) void link_kernel(Geo g, uint32_t a, uint8_t st
                                                    const uint64_t* __restrict__ cost, const uint16_t* __restrict__ arg,
                                                    const uint32_t* __restrict__ axis_sizes) {
   if (n_ptr) n_boxes = *n_ptr;
+  if (blockIdx.x * 256u >= n_boxes) return;     // the whole workgroup (its flag is never read)
   const uint32_t i = blockIdx.x * 256u + threadIdx.x;
   const uint32_t b = i < n_boxes ? (ids ? ids[i] : i) : 0u;
   const bool live = i < n_boxes && alive[b];
@@ -482,8 +483,9 @@ __global__ __launch_bounds__(256) void absorb_kernel(uint32_t a, uint8_t stamp, 
                                                      uint8_t* __restrict__ alive, const uint8_t* __restrict__ pred,
                                                      const uint32_t* __restrict__ next,
                                                      const uint32_t* __restrict__ block_linked) {
-  if (!block_linked[blockIdx.x]) return;       // no box of this workgroup got a successor: no chain starts here
   if (n_ptr) n_boxes = *n_ptr;
+  if (blockIdx.x * 256u >= n_boxes) return;
+  if (!block_linked[blockIdx.x]) return;       // no box of this workgroup got a successor: no chain starts here
   const uint32_t i = blockIdx.x * 256u + threadIdx.x;
   if (i >= n_boxes) return;
   const uint32_t b = ids ? ids[i] : i;

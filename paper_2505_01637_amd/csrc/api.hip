@@ -635,7 +635,7 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
     launch_axis_pass(g, a, ++W.stamp, which == 1, W.ids, W.n_bound, W.n_ptr, W.bcell, W.blen, W.alive, W.pred, W.next,
                      W.block_linked, maskL[which], prefL[which], tab->d_cost, tab->d_arg, axis_sizes(a), stL[which]);
     W.n_pass++;
-    if (W.n_pass <= 2 && W.n_bound > (1u << 20)) {
+    if (W.n_pass <= 1 && W.n_bound > (1u << 20)) {
       scan_flags(W.alive, W.ids, W.n_bound, W.n_ptr, tileL[which], W.pos, W.d_cnt + W.flip, stL[which]);
       launch_compact_live(W.alive, W.ids, W.n_bound, W.n_ptr, W.pos, W.live_buf[W.flip], stL[which]);
       W.ids = W.live_buf[W.flip];

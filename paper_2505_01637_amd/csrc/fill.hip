@@ -305,67 +305,80 @@ __device__ __forceinline__ void task_bufferize(const DevParams* __restrict__ P, 
   }
 }
 
-// Moves of operand I of task (xpack, v): to every lower level, same or transposed layout, with
-// or without conversion.  All sub-Specs have a lower rank and are final in LDS.  The LDS reads
-// are arranged in two rounds so that few of them wait for each other: first the (admissible
-// variants | first task) word of the three possible destinations (move_targets), then the Move
-// costs and the sub-Specs' costs of all candidates of a conversion plane (move_plane).
-template <int I>
-__device__ __forceinline__ void move_targets(const Hot& H, const UnitLds& L, uint32_t xpack, uint32_t ci[3]) {
-  if ((uint32_t)I >= H.nops) return;
-  const uint32_t sh = H.pack_shift[I], src = (xpack >> sh) & 3u;
-#pragma unroll
-  for (uint32_t dst = 0; dst < 3; dst++) ci[dst] = L.c_info[dst < src ? xpack - ((src - dst) << sh) : xpack];
+// The rank loop gives every task a quad of lanes, one per operand: lane `op` of the quad
+// evaluates the Moves of operand `op` (to every lower level, same or transposed layout, with or
+// without conversion), then the quad's candidates are reduced to the lexicographic minimum of
+// (cost, id).  Most ranks of most shapes hold fewer than 16 tasks, so this divides the
+// instructions a rank costs (what a small shape's fill is bound by) by about three.
+struct MyOperand {
+  bool exists;                 // op < number of operands
+  bool has_x, can_cv;
+  uint32_t sh, xbit, dtbit;    // level field inside the pack; layout / dtype bit of the variant index
+  uint32_t id0, brow;          // first Move id of this operand; its row of the Move-cost table
+};
+
+__device__ __forceinline__ MyOperand my_operand(const Hot& H, uint32_t op) {
+  MyOperand M;
+  M.exists = op < H.nops;
+  const uint32_t lay = op == 0 ? H.lay_bit[0] : op == 1 ? H.lay_bit[1] : op == 2 ? H.lay_bit[2] : H.lay_bit[3];
+  const uint32_t dt = op == 0 ? H.dt_bit[0] : op == 1 ? H.dt_bit[1] : op == 2 ? H.dt_bit[2] : H.dt_bit[3];
+  M.sh = op == 0 ? H.pack_shift[0] : op == 1 ? H.pack_shift[1] : op == 2 ? H.pack_shift[2] : H.pack_shift[3];
+  M.can_cv = (op == 0 ? H.can_convert[0] : op == 1 ? H.can_convert[1] : op == 2 ? H.can_convert[2] : H.can_convert[3]) != 0;
+  M.has_x = lay != kNoBit;
+  M.xbit = M.has_x ? 1u << (lay & 31u) : 0u;
+  M.dtbit = M.can_cv ? 1u << (dt & 31u) : 0u;
+  M.id0 = H.move_base + op * (H.NL - 1) * 4u;
+  M.brow = op * 32u;
+  return M;
 }
 
-template <int I, int NX>
-__device__ __forceinline__ void move_plane(const Hot& H, const UnitLds& L, uint32_t q, uint32_t src, uint32_t v,
-                                           uint32_t cv, bool cv_ok, const uint32_t ci[3], Eval& e, uint32_t& hi_or) {
+// One conversion plane (cv) of my operand's Moves: 3 destinations x {same, transposed}.  ci[dst] is
+// the (admissible variants | first task) word of the destination's level assignment.  All
+// sub-Specs have a lower rank and are final in LDS.
+__device__ __forceinline__ void move_plane(const Hot& H, const MyOperand& M, const UnitLds& L, uint32_t q, uint32_t src,
+                                           uint32_t v, uint32_t cv, bool on, const uint32_t ci[3], Eval& e,
+                                           uint32_t& hi_or) {
   const bool has_dt = H.ndt != 0;
-  const uint32_t xbit = NX == 2 ? 1u << H.lay_bit[I] : 0u, cvbit = cv ? 1u << H.dt_bit[I] : 0u;
-  const uint32_t id0 = H.move_base + (uint32_t)I * (H.NL - 1) * 4u + cv;
-  const uint32_t brow = cv * 128u + ((uint32_t)I * 4u + src) * 8u;
-  uint64_t b[3 * NX], t[3 * NX];
-  bool has[3 * NX];
+  const uint32_t cvbit = cv ? M.dtbit : 0u;
+  const uint32_t brow = cv * 128u + M.brow + src * 8u;
+  uint64_t b[6], t[6];
+  bool has[6];
 #pragma unroll
   for (uint32_t dst = 0; dst < 3; dst++)
 #pragma unroll
-    for (uint32_t x = 0; x < (uint32_t)NX; x++) {
-      const uint32_t c = dst * NX + x, v2 = (v ^ (x ? xbit : 0u)) & ~cvbit;
+    for (uint32_t x = 0; x < 2; x++) {
+      const uint32_t c = dst * 2 + x, v2 = (v ^ (x ? M.xbit : 0u)) & ~cvbit;
       b[c] = L.bterm[brow + dst * 2u + x];
-      has[c] = dst < src && cv_ok && ((ci[dst] >> v2) & 1u);
+      has[c] = on && dst < src && (x == 0 || M.has_x) && ((ci[dst] >> v2) & 1u);
       const uint32_t idx = (ci[dst] >> 16) + (has_dt ? __popc(ci[dst] & 0xFFFFu & ((1u << v2) - 1u)) : v2);
       t[c] = L.t_cost[has[c] ? idx : q];
     }
 #pragma unroll
   for (uint32_t dst = 0; dst < 3; dst++)
 #pragma unroll
-    for (uint32_t x = 0; x < (uint32_t)NX; x++) {
-      const uint32_t c = dst * NX + x;
-      const bool exists = dst < src && cv_ok && b[c] != 0;     // b == 0: the target has no such Move
+    for (uint32_t x = 0; x < 2; x++) {
+      const uint32_t c = dst * 2 + x;
+      const bool exists = on && dst < src && (x == 0 || M.has_x) && b[c] != 0;     // b == 0: the target has no such Move
       e.n += exists ? 1u : 0u;
       if (exists && has[c] && t[c] != kInf) {
         const uint64_t cand = t[c] + b[c];                      // t < 2^62 when finite, b <= 2^62: no wrap
         hi_or |= (uint32_t)(cand >> 32);
-        consider(e, cand, id0 + (dst * 2u + x) * 2u);
+        consider(e, cand, M.id0 + (dst * 2u + x) * 2u + cv);
       }
     }
 }
 
-template <int I>
-__device__ __forceinline__ void task_moves(const Hot& H, const UnitLds& L, uint32_t q, uint32_t xpack, uint32_t v,
-                                           const uint32_t ci[3], Eval& e, uint32_t& hi_or) {
-  if ((uint32_t)I >= H.nops) return;
-  const uint32_t src = (xpack >> H.pack_shift[I]) & 3u;
-  if (!__any(src != 0)) return;
-  const bool cv_ok = H.can_convert[I] && ((v >> H.dt_bit[I]) & 1u);
-  if (H.lay_bit[I] != kNoBit) {
-    move_plane<I, 2>(H, L, q, src, v, 0, true, ci, e, hi_or);
-    if (__any(cv_ok)) move_plane<I, 2>(H, L, q, src, v, 1, cv_ok, ci, e, hi_or);
-  } else {
-    move_plane<I, 1>(H, L, q, src, v, 0, true, ci, e, hi_or);
-    if (__any(cv_ok)) move_plane<I, 1>(H, L, q, src, v, 1, cv_ok, ci, e, hi_or);
-  }
+// Exchange inside a quad of lanes (lane ^ 1, lane ^ 2) without going through LDS.
+template <int CTRL>
+__device__ __forceinline__ uint32_t quad_swap(uint32_t x) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xF, 0xF, true);
+}
+template <int CTRL>
+__device__ __forceinline__ void quad_min(Eval& e) {
+  const uint32_t lo = quad_swap<CTRL>((uint32_t)e.best), hi = quad_swap<CTRL>((uint32_t)(e.best >> 32));
+  const uint32_t id = quad_swap<CTRL>(e.arg);
+  const uint64_t o = (uint64_t)hi << 32 | lo;
+  if (o < e.best || (o == e.best && id < e.arg)) { e.best = o; e.arg = id; }
 }
 
 // One unit = passes [pass0, pass0 + np) of one shape, handled by T threads.
@@ -477,39 +490,55 @@ __device__ __forceinline__ void solve_unit(const DevParams* __restrict__ P, cons
   for (uint32_t j = 0; j < P->nmk; j++) mk_shape |= (mk_shape_reps(P, S, j) ? 1u : 0u) << j;
 
   // ---- 4. rank by rank: microkernels and Moves, then the parked tile/bufferize candidate ----
+  const uint32_t op = tid & 3u;
+  const MyOperand M = my_operand(H, op);
   for (uint32_t r = 0; r < P->nranks; r++) {
     const uint32_t t0 = L.r_off[r], t1 = L.r_off[r + 1];
     if (t0 == t1) continue;
-    for (uint32_t q = t0 + tid; q < t1; q += T) {
+    for (uint32_t qb = t0; qb < t1; qb += T / 4) {
+      const bool active = qb + (tid >> 2) < t1;
+      const uint32_t q = active ? qb + (tid >> 2) : t0;        // idle lanes read task t0 and drop the result
       const uint32_t sp = L.t_spec[q];
       const uint32_t xpack = sp & 0x3FFu, v = (sp >> 10) & 31u;
+      // my operand's Moves
       Eval e;
-      e.best = L.t_cost[q]; e.arg = sp >> 16; e.n = 0; e.ovf = 0;
+      e.best = kInf; e.arg = kNone; e.n = 0; e.ovf = 0;
       uint32_t hi_or = 0;           // OR of the high words of all finite Move candidates
-      if (mk_shape) {
-        for (uint32_t mm = P->mk_entry[(xpack & 0xFFu) * P->V + v] & mk_shape; mm; mm &= mm - 1) {
-          const uint32_t j = (uint32_t)__ffs(mm) - 1u;
-          const uint64_t k = mul_or_limit(P->mk_cost[j], mk_shape_reps(P, S, j));
-          if (k >= kLimit) e.ovf = 1; else consider(e, k, j);
-          e.n++;
-        }
+      const uint32_t src = (xpack >> M.sh) & 3u;
+      const bool on = active && M.exists && src != 0;
+      if (__any(on)) {
+        uint32_t ci[3];
+#pragma unroll
+        for (uint32_t dst = 0; dst < 3; dst++) ci[dst] = L.c_info[on && dst < src ? xpack - ((src - dst) << M.sh) : xpack];
+        move_plane(H, M, L, q, src, v, 0, on, ci, e, hi_or);
+        const bool cv_on = on && M.can_cv && (v & M.dtbit);
+        if (__any(cv_on)) move_plane(H, M, L, q, src, v, 1, cv_on, ci, e, hi_or);
       }
-      uint32_t ci[4][3];
-      move_targets<0>(H, L, xpack, ci[0]);
-      move_targets<1>(H, L, xpack, ci[1]);
-      move_targets<2>(H, L, xpack, ci[2]);
-      move_targets<3>(H, L, xpack, ci[3]);
-      task_moves<0>(H, L, q, xpack, v, ci[0], e, hi_or);
-      task_moves<1>(H, L, q, xpack, v, ci[1], e, hi_or);
-      task_moves<2>(H, L, q, xpack, v, ci[2], e, hi_or);
-      task_moves<3>(H, L, q, xpack, v, ci[3], e, hi_or);
       if (hi_or >> 30) e.ovf = 1;   // bit 62 of some finite candidate: the solve reports overflow
-      const uint32_t off = entry_offset(H, xpack, v);
-      L.t_cost[q] = e.best;
-      cost[group + off] = e.best;
-      arg[group + off] = (uint16_t)e.arg;
       tot.n += e.n;
       tot.ovf |= e.ovf;
+      quad_min<0xB1>(e);            // lanes ^ 1
+      quad_min<0x4E>(e);            // lanes ^ 2
+      if (active && op == 0) {
+        // the quad's first lane adds the microkernels (lowest ids) and the parked candidate, and stores
+        Eval f;
+        f.best = L.t_cost[q]; f.arg = sp >> 16; f.n = 0; f.ovf = 0;
+        if (e.best < f.best || (e.best == f.best && e.arg < f.arg)) { f.best = e.best; f.arg = e.arg; }
+        if (mk_shape) {
+          for (uint32_t mm = P->mk_entry[(xpack & 0xFFu) * P->V + v] & mk_shape; mm; mm &= mm - 1) {
+            const uint32_t j = (uint32_t)__ffs(mm) - 1u;
+            const uint64_t k = mul_or_limit(P->mk_cost[j], mk_shape_reps(P, S, j));
+            if (k >= kLimit) f.ovf = 1; else consider(f, k, j);
+            f.n++;
+          }
+        }
+        const uint32_t off = entry_offset(H, xpack, v);
+        L.t_cost[q] = f.best;
+        cost[group + off] = f.best;
+        arg[group + off] = (uint16_t)f.arg;
+        tot.n += f.n;
+        tot.ovf |= f.ovf;
+      }
     }
     unit_sync<T>();
   }

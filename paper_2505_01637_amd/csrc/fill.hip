@@ -52,10 +52,13 @@ struct Eval {
   uint32_t ovf;
 };
 
-// Keep the lexicographic minimum of (cost, rewrite id); only called with finite candidates,
-// so the evaluation order of the rewrites is free.
-__device__ __forceinline__ void consider(Eval& e, uint64_t cand, uint32_t id) {
-  if (cand < e.best || (cand == e.best && id < e.arg)) { e.best = cand; e.arg = id; }
+// Keep the lexicographic minimum of (cost, rewrite id) among the candidates with ok set (all
+// finite), so the evaluation order of the rewrites is free.  Written with selects: as branches
+// the many calls cost more in exec-mask bookkeeping than the work they skip.
+__device__ __forceinline__ void consider(Eval& e, uint64_t cand, uint32_t id, bool ok = true) {
+  const bool better = ok & ((cand < e.best) | ((cand == e.best) & (id < e.arg)));
+  e.best = better ? cand : e.best;
+  e.arg = better ? id : e.arg;
 }
 
 // a * b for operands below 2^62 and 2^33; kLimit if the product reaches 2^62.
@@ -272,12 +275,15 @@ __device__ __forceinline__ void task_tiles(const DevParams* __restrict__ P, cons
     for (int u = 0; u < kBatch; u++) sub[u] = cost[L.tl_base[t0 + u < n_here ? t0 + u : n_here - 1] + off];
 #pragma unroll
     for (int u = 0; u < kBatch; u++) {
-      if (t0 + u < n_here && sub[u] != kInf) {
+      if (t0 + u < n_here) {
+        const bool fin = sub[u] != kInf;
         const uint32_t a = L.tl_trips[t0 + u];
         const uint64_t lo = (uint64_t)a * (uint32_t)sub[u];
         const uint64_t hi = (uint64_t)a * (uint32_t)(sub[u] >> 32) + (lo >> 32);   // bits 32.. of the product
         const uint64_t c = ((hi << 32) | (uint32_t)lo) + s;
-        if ((hi >> 30) != 0 || c >= kLimit) e.ovf = 1; else consider(e, c, L.tl_id[t0 + u]);
+        const bool over = fin & (((hi >> 30) != 0) | (c >= kLimit));
+        e.ovf |= over ? 1u : 0u;
+        consider(e, c, L.tl_id[t0 + u], fin & !over);
       }
     }
   }
@@ -360,11 +366,10 @@ __device__ __forceinline__ void move_plane(const Hot& H, const MyOperand& M, con
       const uint32_t c = dst * 2 + x;
       const bool exists = on && dst < src && (x == 0 || M.has_x) && b[c] != 0;     // b == 0: the target has no such Move
       e.n += exists ? 1u : 0u;
-      if (exists && has[c] && t[c] != kInf) {
-        const uint64_t cand = t[c] + b[c];                      // t < 2^62 when finite, b <= 2^62: no wrap
-        hi_or |= (uint32_t)(cand >> 32);
-        consider(e, cand, M.id0 + (dst * 2u + x) * 2u + cv);
-      }
+      const bool fin = exists & has[c] & (t[c] != kInf);
+      const uint64_t cand = t[c] + b[c];                        // t < 2^62 when finite, b <= 2^62: no wrap
+      hi_or |= fin ? (uint32_t)(cand >> 32) : 0u;
+      consider(e, cand, M.id0 + (dst * 2u + x) * 2u + cv, fin);
     }
 }
 
@@ -377,8 +382,7 @@ template <int CTRL>
 __device__ __forceinline__ void quad_min(Eval& e) {
   const uint32_t lo = quad_swap<CTRL>((uint32_t)e.best), hi = quad_swap<CTRL>((uint32_t)(e.best >> 32));
   const uint32_t id = quad_swap<CTRL>(e.arg);
-  const uint64_t o = (uint64_t)hi << 32 | lo;
-  if (o < e.best || (o == e.best && id < e.arg)) { e.best = o; e.arg = id; }
+  consider(e, (uint64_t)hi << 32 | lo, id);
 }
 
 // One unit = passes [pass0, pass0 + np) of one shape, handled by T threads.
@@ -523,7 +527,7 @@ __device__ __forceinline__ void solve_unit(const DevParams* __restrict__ P, cons
         // the quad's first lane adds the microkernels (lowest ids) and the parked candidate, and stores
         Eval f;
         f.best = L.t_cost[q]; f.arg = sp >> 16; f.n = 0; f.ovf = 0;
-        if (e.best < f.best || (e.best == f.best && e.arg < f.arg)) { f.best = e.best; f.arg = e.arg; }
+        consider(f, e.best, e.arg);
         if (mk_shape) {
           for (uint32_t mm = P->mk_entry[(xpack & 0xFFu) * P->V + v] & mk_shape; mm; mm &= mm - 1) {
             const uint32_t j = (uint32_t)__ffs(mm) - 1u;

@@ -407,49 +407,114 @@ __device__ __forceinline__ void solve_unit(const DevParams* __restrict__ P, cons
 #pragma unroll
   for (int l = 0; l < 4; l++) f[l] = L.fit[l];
   uint32_t n_task = 0;
+  if (H.ndt == 0) {
+    // No dtype coordinate: the variants of a (level assignment, pass) fit all or none, so a ballot
+    // per pass holds everything and the prefix sums are popcounts.  A: level l holds its operands;
+    // B: and the intermediate as well.
+    const uint32_t V = 1u << H.log2V;
+    const bool fused = P->kind == kKindF;
 #pragma unroll
-  for (int it = 0; it < kIter; it++) {
-    if ((uint32_t)(it * T) >= ncombo) break;
-    const uint32_t pc = it * T + tid;
-    uint32_t mask[4] = {0, 0, 0, 0}, cnt = 0;
-    if (pc < ncombo) {
+    for (int it = 0; it < kIter; it++) {
+      if ((uint32_t)(it * T) >= ncombo) break;
+      const uint32_t pc = it * T + tid;
+      uint32_t A = 0, B = 0;
 #pragma unroll
-      for (int ps = 0; ps < 4; ps++)
-        if ((uint32_t)ps < np) { mask[ps] = admissible_mask(P, L.fit, f, info[it], pass0 + ps); cnt += __popc(mask[ps]); }
-    }
-    uint32_t incl = cnt;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-      const uint32_t o = __shfl_up(incl, d, 64);
-      if ((int)lane >= d) incl += o;
-    }
-    uint32_t base = n_task + incl - cnt;
-    if (T == 64) {
-      n_task += __shfl(incl, 63, 64);
-    } else {
-      const uint32_t w = threadIdx.x >> 6;
-      if (lane == 63) L.wave_tot[w] = incl;
-      __syncthreads();
-      for (uint32_t i = 0; i < T / 64; i++) {
-        const uint32_t t = L.wave_tot[i];
-        if (i < w) base += t;
-        n_task += t;
+      for (int l = 0; l < 4; l++) {
+        const uint32_t sub = (info[it] >> (8 + 4 * l)) & 15u;
+        A |= ((uint32_t)l < H.NL ? (f[l] >> sub) & 1u : 1u) << l;
+        B |= ((uint32_t)l < H.NL ? (f[l] >> (sub | 16u)) & 1u : 1u) << l;
       }
-      __syncthreads();
-    }
-    if (pc < ncombo) {
+      bool ok[4];
+      unsigned long long bal[4];
+      uint32_t before = 0, wave_cnt = 0;
 #pragma unroll
-      for (int ps = 0; ps < 4; ps++)
-        if ((uint32_t)ps < np) {
-          const uint32_t xpack = (pass0 + ps) << 8 | (info[it] & 0xFFu);
-          L.c_info[xpack] = mask[ps] | base << 16;
-          const uint32_t c = __popc(mask[ps]);
-          if (base + c <= cap) {
-            uint32_t q = base;
-            for (uint32_t m = mask[ps]; m; m &= m - 1) L.t_spec[q++] = xpack | ((uint32_t)__ffs(m) - 1u) << 10;
-          }
-          base += c;
+      for (int ps = 0; ps < 4; ps++) {
+        const uint32_t pass = pass0 + ps;
+        ok[ps] = (uint32_t)ps < np && pc < ncombo && (fused ? ((A | 1u << pass) == 15u) && ((B >> pass) & 1u) : A == 15u);
+        bal[ps] = __ballot(ok[ps]);
+        before += __builtin_amdgcn_mbcnt_hi((uint32_t)(bal[ps] >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal[ps], 0u));
+        wave_cnt += (uint32_t)__popcll(bal[ps]);
+      }
+      uint32_t base = n_task + before * V;
+      if (T == 64) {
+        n_task += wave_cnt * V;
+      } else {
+        const uint32_t w = threadIdx.x >> 6;
+        if (lane == 0) L.wave_tot[w] = wave_cnt * V;
+        __syncthreads();
+        for (uint32_t i = 0; i < T / 64; i++) {
+          const uint32_t t = L.wave_tot[i];
+          if (i < w) base += t;
+          n_task += t;
         }
+        __syncthreads();
+      }
+      if (pc < ncombo) {
+#pragma unroll
+        for (int ps = 0; ps < 4; ps++)
+          if ((uint32_t)ps < np) {
+            const uint32_t xpack = (pass0 + ps) << 8 | (info[it] & 0xFFu);
+            L.c_info[xpack] = (ok[ps] ? (1u << V) - 1u : 0u) | base << 16;
+            if (ok[ps]) {
+              if (base + V <= cap) {
+                if (V >= 4) {
+                  for (uint32_t v0 = 0; v0 < V; v0 += 4)
+                    *reinterpret_cast<uint4*>(&L.t_spec[base + v0]) =
+                        make_uint4(xpack | v0 << 10, xpack | (v0 + 1) << 10, xpack | (v0 + 2) << 10, xpack | (v0 + 3) << 10);
+                } else {
+                  for (uint32_t v0 = 0; v0 < V; v0++) L.t_spec[base + v0] = xpack | v0 << 10;
+                }
+              }
+              base += V;
+            }
+          }
+      }
+    }
+  } else {
+#pragma unroll
+    for (int it = 0; it < kIter; it++) {
+      if ((uint32_t)(it * T) >= ncombo) break;
+      const uint32_t pc = it * T + tid;
+      uint32_t mask[4] = {0, 0, 0, 0}, cnt = 0;
+      if (pc < ncombo) {
+#pragma unroll
+        for (int ps = 0; ps < 4; ps++)
+          if ((uint32_t)ps < np) { mask[ps] = admissible_mask(P, L.fit, f, info[it], pass0 + ps); cnt += __popc(mask[ps]); }
+      }
+      uint32_t incl = cnt;
+#pragma unroll
+      for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t o = __shfl_up(incl, d, 64);
+        if ((int)lane >= d) incl += o;
+      }
+      uint32_t base = n_task + incl - cnt;
+      if (T == 64) {
+        n_task += __shfl(incl, 63, 64);
+      } else {
+        const uint32_t w = threadIdx.x >> 6;
+        if (lane == 63) L.wave_tot[w] = incl;
+        __syncthreads();
+        for (uint32_t i = 0; i < T / 64; i++) {
+          const uint32_t t = L.wave_tot[i];
+          if (i < w) base += t;
+          n_task += t;
+        }
+        __syncthreads();
+      }
+      if (pc < ncombo) {
+#pragma unroll
+        for (int ps = 0; ps < 4; ps++)
+          if ((uint32_t)ps < np) {
+            const uint32_t xpack = (pass0 + ps) << 8 | (info[it] & 0xFFu);
+            L.c_info[xpack] = mask[ps] | base << 16;
+            const uint32_t c = __popc(mask[ps]);
+            if (base + c <= cap) {
+              uint32_t q = base;
+              for (uint32_t m = mask[ps]; m; m &= m - 1) L.t_spec[q++] = xpack | ((uint32_t)__ffs(m) - 1u) << 10;
+            }
+            base += c;
+          }
+      }
     }
   }
   if (n_task == 0) return;          // nothing here fits anywhere: the table already says so

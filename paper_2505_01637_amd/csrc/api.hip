@@ -288,6 +288,7 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
       for (uint32_t op = 0; op < P.nops; op++) info |= 1u << (8 + 4 * ((combo / P.lvpow[op]) % P.NL) + op);
       P.pos_info[i] = info;
     }
+    for (uint32_t r = 0; r < P.nranks; r++) P.pos_info[P.rank_off[r]] |= (r + 1) << 24;     // first position of rank r
   }
 
   // dependency level of a shape = sum over tiled dims of the longest divisor chain below its size

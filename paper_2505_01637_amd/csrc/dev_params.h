@@ -64,6 +64,7 @@ struct DevParams {
   uint32_t nranks;
   uint32_t rank_off[kMaxRanks + 2];
   // per rank-major position: pack | (operands resident in level l, one nibble per level) << 8
+  // | (r + 1) << 24 at the first position of rank r
   uint32_t pos_info[kMaxCombo];
   // ---- tables a FUSED lattice reads ----
   const uint64_t* costM;

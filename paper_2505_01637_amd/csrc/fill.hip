@@ -230,37 +230,76 @@ __device__ __forceinline__ uint32_t admissible_mask(const DevParams* __restrict_
 }
 
 // Move cost per (convert, operand, src, dst, transposed) for this shape: coefficient * elements.
+// The coefficients (thread t: entries t, t + T, ... of the 128-entry table, for both conversion
+// planes) and the first tile rewrites are fetched at the start of a unit, long before they are needed.
 template <int T>
-__device__ __forceinline__ void build_move_costs(const DevParams* __restrict__ P, const Shape& S, uint64_t* bterm) {
-  for (uint32_t e = T == 64 ? (threadIdx.x & 63u) : threadIdx.x; e < 256; e += T) {
-    const uint32_t cv = e >> 7, i = (e >> 5) & 3u;
-    const uint32_t c = (&P->mcoef[0][0][0][0])[e & 127u];
-    const uint64_t n = i == 0 ? S.numel[0] : i == 1 ? S.numel[1] : i == 2 ? S.numel[2] : S.numel[3];
-    bterm[e] = c ? mul_or_limit((uint64_t)c + (cv ? P->convert : 0u), n) : 0;   // 0 = the Move does not exist
-  }
-}
+struct Prefetch {
+  static constexpr int kCoef = 256 / T < 1 ? 1 : 256 / T;
+  uint32_t coef[kCoef];
+  TileEntry te;
+  uint32_t td;
+  bool tvalid;
+};
 
-// Stage tile rewrites [e0, e0 + kTileLds) of this shape (dims in order, sizes ascending) in LDS.
+// Tile rewrite e0 + thread of this shape (dims in order, sizes ascending).
 template <int T>
-__device__ __forceinline__ void stage_tiles(const DevParams* __restrict__ P, const UnitLds& L, const Shape& S,
-                                            uint32_t shape, uint32_t e0, uint32_t n_tile) {
+__device__ __forceinline__ void fetch_tile(const DevParams* __restrict__ P, const Shape& S, uint32_t e0, uint32_t n_tile,
+                                           TileEntry& te, uint32_t& td, bool& valid) {
   const uint32_t tid = T == 64 ? (threadIdx.x & 63u) : threadIdx.x;
   const uint32_t e = e0 + tid;
-  if (tid < kTileLds && e < n_tile) {
-    uint32_t first = 0, d = 0, q = 0;
+  valid = tid < kTileLds && e < n_tile;
+  td = 0;
+  te.jt = 0; te.trips = 0;
+  if (valid) {
+    uint32_t first = 0, q = 0;
 #pragma unroll
     for (int a = 0; a < 4; a++) {
       const uint32_t lo = P->tile_off[a][S.si[a]];
       const uint32_t cnt = P->tile_dim_ok[a] ? P->tile_off[a][S.si[a] + 1] - lo : 0u;
-      if (e >= first && e < first + cnt) { d = a; q = lo + (e - first); }
+      if (e >= first && e < first + cnt) { td = a; q = lo + (e - first); }
       first += cnt;
     }
-    const TileEntry te = P->tiles[q];
+    te = P->tiles[q];
+  }
+}
+
+// ... into LDS: table offset of the sub-shape's group, trip count, rewrite id.
+template <int T>
+__device__ __forceinline__ void store_tile(const DevParams* __restrict__ P, const UnitLds& L, const Shape& S, uint32_t shape,
+                                           const TileEntry& te, uint32_t d, bool valid) {
+  const uint32_t tid = T == 64 ? (threadIdx.x & 63u) : threadIdx.x;
+  if (valid) {
     const uint32_t j = d == 0 ? S.si[0] : d == 1 ? S.si[1] : d == 2 ? S.si[2] : S.si[3];
     const uint32_t stride = d == 0 ? P->shape_stride[0] : d == 1 ? P->shape_stride[1] : d == 2 ? P->shape_stride[2] : P->shape_stride[3];
     L.tl_base[tid] = (uint64_t)(shape - (j - te.jt) * stride) * P->G;
     L.tl_trips[tid] = te.trips;
     L.tl_id[tid] = P->tile_base + d * P->maxs + te.jt;
+  }
+}
+
+template <int T>
+__device__ __forceinline__ void prefetch_unit(const DevParams* __restrict__ P, const Shape& S, uint32_t n_tile, Prefetch<T>& F) {
+  const uint32_t tid = T == 64 ? (threadIdx.x & 63u) : threadIdx.x;
+#pragma unroll
+  for (int i = 0; i < Prefetch<T>::kCoef; i++) {
+    const uint32_t e = tid + i * T;
+    F.coef[i] = e < 256 ? (&P->mcoef[0][0][0][0])[e & 127u] : 0u;
+  }
+  fetch_tile<T>(P, S, 0, n_tile, F.te, F.td, F.tvalid);
+}
+
+template <int T>
+__device__ __forceinline__ void build_move_costs(const DevParams* __restrict__ P, const Shape& S, const Prefetch<T>& F,
+                                                 uint64_t* bterm) {
+  const uint32_t tid = T == 64 ? (threadIdx.x & 63u) : threadIdx.x;
+#pragma unroll
+  for (int k = 0; k < Prefetch<T>::kCoef; k++) {
+    const uint32_t e = tid + k * T;
+    if (e < 256) {
+      const uint32_t cv = e >> 7, i = (e >> 5) & 3u, c = F.coef[k];
+      const uint64_t n = i == 0 ? S.numel[0] : i == 1 ? S.numel[1] : i == 2 ? S.numel[2] : S.numel[3];
+      bterm[e] = c ? mul_or_limit((uint64_t)c + (cv ? P->convert : 0u), n) : 0;   // 0 = the Move does not exist
+    }
   }
 }
 
@@ -395,6 +434,11 @@ __device__ __forceinline__ void solve_unit(const DevParams* __restrict__ P, cons
   const uint32_t ncombo = P->ncombo;
   const uint64_t group = (uint64_t)shape * P->G;
   const Hot H = load_hot(P);
+  uint32_t n_tile = 0;
+#pragma unroll
+  for (int d = 0; d < 4; d++) if (P->tile_dim_ok[d]) n_tile += P->tile_off[d][S.si[d] + 1] - P->tile_off[d][S.si[d]];
+  Prefetch<T> pre;
+  prefetch_unit<T>(P, S, n_tile, pre);
 
   // ---- 1. admissibility, compaction in rank order (rank-major level assignments, then pass) ----
   constexpr int kIter = 256 / T < 1 ? 1 : 256 / T;   // ncombo <= 256
@@ -454,6 +498,7 @@ __device__ __forceinline__ void solve_unit(const DevParams* __restrict__ P, cons
         for (int ps = 0; ps < 4; ps++)
           if ((uint32_t)ps < np) {
             const uint32_t xpack = (pass0 + ps) << 8 | (info[it] & 0xFFu);
+            if (ps == 0 && (info[it] >> 24)) L.r_off[(info[it] >> 24) - 1u] = base;      // this position opens a rank
             L.c_info[xpack] = (ok[ps] ? (1u << V) - 1u : 0u) | base << 16;
             if (ok[ps]) {
               if (base + V <= cap) {
@@ -506,6 +551,7 @@ __device__ __forceinline__ void solve_unit(const DevParams* __restrict__ P, cons
         for (int ps = 0; ps < 4; ps++)
           if ((uint32_t)ps < np) {
             const uint32_t xpack = (pass0 + ps) << 8 | (info[it] & 0xFFu);
+            if (ps == 0 && (info[it] >> 24)) L.r_off[(info[it] >> 24) - 1u] = base;      // this position opens a rank
             L.c_info[xpack] = mask[ps] | base << 16;
             const uint32_t c = __popc(mask[ps]);
             if (base + c <= cap) {
@@ -519,19 +565,17 @@ __device__ __forceinline__ void solve_unit(const DevParams* __restrict__ P, cons
   }
   if (n_task == 0) return;          // nothing here fits anywhere: the table already says so
   if (n_task > cap) { tot.ovf |= 2u; return; }   // the plan guarantees this cannot happen; reported as an internal error
-  unit_sync<T>();
-  if (tid <= P->nranks)
-    L.r_off[tid] = tid == P->nranks ? n_task : L.c_info[pass0 << 8 | (P->pos_info[P->rank_off[tid]] & 0xFFu)] >> 16;
-  build_move_costs<T>(P, S, L.bterm);
+  if (tid == 0) L.r_off[P->nranks] = n_task;
+  build_move_costs<T>(P, S, pre, L.bterm);
 
   // ---- 3. tile and bufferize candidates of every task (sub-Specs of other shapes / tables: final) ----
-  uint32_t n_tile = 0;
-#pragma unroll
-  for (int d = 0; d < 4; d++) if (P->tile_dim_ok[d]) n_tile += P->tile_off[d][S.si[d] + 1] - P->tile_off[d][S.si[d]];
   const uint32_t n_per_task = n_tile + (P->kind == kKindF ? 1u : 0u);
   for (uint32_t e0 = 0; e0 == 0 || e0 < n_tile; e0 += kTileLds) {
-    if (e0) unit_sync<T>();
-    stage_tiles<T>(P, L, S, shape, e0, n_tile);
+    if (e0) {
+      unit_sync<T>();
+      fetch_tile<T>(P, S, e0, n_tile, pre.te, pre.td, pre.tvalid);
+    }
+    store_tile<T>(P, L, S, shape, pre.te, pre.td, pre.tvalid);
     unit_sync<T>();
     const uint32_t n_here = n_tile - e0 < kTileLds ? n_tile - e0 : kTileLds;
     for (uint32_t q = tid; q < n_task; q += T) {

@@ -84,7 +84,7 @@ FixedLayout fixed_layout(const Compiled& c) {
   f.list_whole = take((size_t)c.n_shapes * 4);
   f.list_slice = take((size_t)c.n_shapes * c.P.npass * 4);
   f.list_wide = take((size_t)c.n_shapes * c.P.npass * 4);
-  f.list_cnt = take(3 * c.level_off.size() * 4);
+  f.list_cnt = take(4 * c.level_off.size() * 4);
   f.fitmap = take((size_t)f.n_words * 8 + 16);
   f.maskD = take((size_t)f.n_words * 8);
   f.maskC = take((size_t)f.n_words * 8);
@@ -546,7 +546,7 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
   launch_zero_words((unsigned long long*)d_fitmap, f.n_words + 2, st);
   launch_plan(d_P, c.n_shapes, P.npass, P.G, d_level_shapes, d_level_off, n_lev, d_shape_class, d_list_whole, d_list_slice,
               d_list_wide, d_list_cnt, d_fitmap, d_ctr, st);
-  std::vector<uint32_t> cnt(3 * (size_t)n_lev);
+  std::vector<uint32_t> cnt(4 * (size_t)n_lev);
   HIP_TRY(hipMemcpyAsync(cnt.data(), d_list_cnt, cnt.size() * 4, hipMemcpyDeviceToHost, st));
   HIP_TRY(hipEventRecord(aux->events[ev_used], st));
   hipEvent_t counts_ready = aux->events[ev_used++];
@@ -555,17 +555,18 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
   HIP_TRY(hipEventSynchronize(counts_ready));
   for (uint32_t l = 0; l < n_lev; l++) {
     const uint32_t first = c.level_off[l];
-    const uint32_t n_whole = cnt[l], n_slice = cnt[n_lev + l], n_wide = cnt[2 * n_lev + l];
-    if (n_whole > c.level_off[l + 1] - first || n_slice + n_wide > (c.level_off[l + 1] - first) * P.npass)
+    const uint32_t n_small = cnt[l], n_slice = cnt[n_lev + l], n_wide = cnt[2 * n_lev + l], n_bigwhole = cnt[3 * n_lev + l];
+    const uint32_t n_stretch = c.level_off[l + 1] - first;
+    if (n_small + n_bigwhole > n_stretch || n_slice + n_wide > n_stretch * P.npass)
       return fail(MRL_E_HIP, "internal error: work lists of level %u overflow", l);
-    const bool fork = n_wide && (n_whole + n_slice);     // both kinds of items: run them side by side
+    const bool fork = n_wide && (n_small + n_bigwhole + n_slice);     // both kinds of items: run them side by side
     if (fork) {
       HIP_TRY(hipEventRecord(aux->events[ev_used], st));
       HIP_TRY(hipStreamWaitEvent(s2, aux->events[ev_used++], 0));
     }
-    launch_fill_level(d_P, P.npass, P.G, c.max_task, d_list_whole + first, n_whole, d_list_slice + (size_t)first * P.npass,
-                      n_slice, d_list_wide + (size_t)first * P.npass, n_wide, tab->d_cost, tab->d_arg, d_ctr, st,
-                      fork ? s2 : st);
+    launch_fill_level(d_P, P.npass, P.G, c.max_task, d_list_whole + first, n_stretch, n_small, n_bigwhole,
+                      d_list_slice + (size_t)first * P.npass, n_slice, d_list_wide + (size_t)first * P.npass, n_wide,
+                      tab->d_cost, tab->d_arg, d_ctr, st, fork ? s2 : st);
     if (fork) {
       HIP_TRY(hipEventRecord(aux->events[ev_used], s2));
       HIP_TRY(hipStreamWaitEvent(st, aux->events[ev_used++], 0));

@@ -18,9 +18,9 @@ void launch_plan(const DevParams* P, uint32_t n_shapes, uint32_t npass, uint32_t
                  uint32_t* list_slice, uint32_t* list_wide, uint32_t* list_cnt, uint32_t* fitmap, Counters* ctr,
                  hipStream_t stream);
 void launch_fill_level(const DevParams* P, uint32_t npass, uint32_t G, uint32_t max_task, const uint32_t* list_whole,
-                       uint32_t n_whole, const uint32_t* list_slice, uint32_t n_slice, const uint32_t* list_wide,
-                       uint32_t n_wide, uint64_t* cost, uint16_t* arg, Counters* ctr, hipStream_t stream,
-                       hipStream_t wide_stream);
+                       uint32_t n_stretch, uint32_t n_small, uint32_t n_bigwhole, const uint32_t* list_slice,
+                       uint32_t n_slice, const uint32_t* list_wide, uint32_t n_wide, uint64_t* cost, uint16_t* arg,
+                       Counters* ctr, hipStream_t stream, hipStream_t wide_stream);
 
 void launch_fill_ones(void* p, size_t bytes, hipStream_t stream);
 void launch_zero_words(unsigned long long* p, uint32_t n, hipStream_t st);

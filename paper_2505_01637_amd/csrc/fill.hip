@@ -40,7 +40,8 @@
 namespace mrl {
 
 constexpr int kBatch = 8;              // sub-Spec costs fetched together before they are compared
-constexpr uint32_t kSmallCap = 512;    // tasks a wave's LDS slice holds
+constexpr uint32_t kSmallCap = 512;    // tasks the LDS slice of a workgroup-sized item holds
+constexpr uint32_t kWaveCap = 128;     // tasks the LDS slice of a wave-sized item holds
 constexpr uint32_t kBigBlock = 512;    // threads per item that does not fit a wave's slice
 constexpr uint32_t kTileLds = 64;      // tile rewrites of the shape staged in LDS at a time
 constexpr uint32_t kWideBelow = 2048;  // levels with fewer shapes than this get 256 threads per shape
@@ -148,7 +149,7 @@ struct UnitLds {
 };
 
 __host__ __device__ inline uint32_t unit_lds_bytes(uint32_t cap, uint32_t npass) {
-  return 2048u + kTileLds * 16u + cap * 12u + npass * 1024u + (kMaxRanks + 2) * 4u + 32u * 4u + 16u;
+  return (2048u + kTileLds * 16u + cap * 12u + npass * 1024u + (kMaxRanks + 2) * 4u + 32u * 4u + 16u + 15u) & ~15u;   // slices stay 16-byte aligned
 }
 
 __device__ __forceinline__ UnitLds carve(unsigned char* w, uint32_t cap, uint32_t npass) {
@@ -445,7 +446,7 @@ __device__ __forceinline__ void solve_unit(const DevParams* __restrict__ P, cons
   uint32_t info[kIter];
 #pragma unroll
   for (int it = 0; it < kIter; it++) info[it] = it * T + tid < ncombo ? P->pos_info[it * T + tid] : 0u;
-  if (threadIdx.x < 64) build_fit(P, S, L.fit);
+  if (T == 64 || threadIdx.x < 64) build_fit(P, S, L.fit);
   unit_sync<T>();
   uint32_t f[4];
 #pragma unroll
@@ -668,12 +669,12 @@ __device__ __forceinline__ void flush_counters(Counters* __restrict__ ctr, const
 // Plan: one wave per kPlanShapes consecutive shapes (the per-assignment table and the parameters
 // stay in registers across them).  Counts the entries that fit per passive-level slice, marks them
 // in a bit map in table order (bit = cell; read by the compression pass) and classifies the shape:
-// bit 8 = one wave can hold it whole; else bits 0..3 = slices a wave can hold, bits 4..7 = slices
-// that need a workgroup.  sort_work_kernel turns the classes into per-level work lists.
+// bit 8 = one LDS slice holds it whole (bit 9: even a wave's small slice); else bits 0..3 = passive-level
+// slices that fit an LDS slice, bits 4..7 = slices that need the large one.  sort_work_kernel turns the classes into per-level work lists.
 constexpr uint32_t kPlanShapes = 8;
 
 __global__ __launch_bounds__(256) void plan_kernel(const DevParams* __restrict__ P, uint32_t n_shapes,
-                                                   uint32_t cap_whole, uint32_t cap_slice,
+                                                   uint32_t cap_whole, uint32_t cap_slice, uint32_t cap_wave,
                                                    uint32_t* __restrict__ shape_class, uint32_t* __restrict__ fitmap,
                                                    Counters* __restrict__ ctr) {
   __shared__ uint32_t fit_all[4][16];
@@ -736,7 +737,7 @@ __global__ __launch_bounds__(256) void plan_kernel(const DevParams* __restrict__
     if (lane == 0) {
       n_adm += total;
       uint32_t cls = 0;
-      if (total && total <= cap_whole) cls = 0x100u;
+      if (total && total <= cap_whole) cls = total <= cap_wave ? 0x300u : 0x100u;
       else
         for (uint32_t ps = 0; ps < npass; ps++)
           if (cnt[ps]) cls |= 1u << (cnt[ps] <= cap_slice ? ps : 4 + ps);
@@ -746,65 +747,75 @@ __global__ __launch_bounds__(256) void plan_kernel(const DevParams* __restrict__
   if (lane == 0 && n_adm) atomicAdd(&ctr->n_admissible, n_adm);
 }
 
-// One workgroup per dependency level: walks the level's shapes in index order and writes its three
-// work lists (whole shapes; slices for a wave; slices for a workgroup) and their lengths.
+// One workgroup per dependency level: walks the level's shapes in index order and writes its work
+// lists and their lengths: whole shapes (the small ones from the front of the level's stretch of
+// list_whole, the others from its back), slices, and wide slices.
 __global__ __launch_bounds__(256) void sort_work_kernel(const uint32_t* __restrict__ level_shapes,
                                                         const uint32_t* __restrict__ level_off, uint32_t n_levels,
                                                         uint32_t npass, const uint32_t* __restrict__ shape_class,
                                                         uint32_t* __restrict__ list_whole, uint32_t* __restrict__ list_slice,
                                                         uint32_t* __restrict__ list_wide, uint32_t* __restrict__ list_cnt) {
-  __shared__ uint32_t wave_sum[4];
-  __shared__ uint32_t carry;      // three running counts packed: whole | slice << 10 ... kept unpacked below
-  __shared__ uint32_t run[3];
+  __shared__ uint32_t wave_sum[4], wave_sum2[4];
+  __shared__ uint32_t run[4];
   const uint32_t lv = blockIdx.x, first = level_off[lv], n = level_off[lv + 1] - first;
-  if (threadIdx.x < 3) run[threadIdx.x] = 0;
-  (void)carry;
+  if (threadIdx.x < 4) run[threadIdx.x] = 0;
   __syncthreads();
   for (uint32_t base = 0; base < n; base += 256) {
     const uint32_t i = base + threadIdx.x;
     const uint32_t shape = i < n ? level_shapes[first + i] : 0u;
     const uint32_t cls = i < n ? shape_class[shape] : 0u;
-    const uint32_t cw = (cls >> 8) & 1u, cs = __popc(cls & 15u), cx = __popc((cls >> 4) & 15u);
+    const uint32_t cw = (cls >> 9) & 1u, cb = ((cls >> 8) & 1u) & ~cw, cs = __popc(cls & 15u), cx = __popc((cls >> 4) & 15u);
     const uint32_t packed = cw | cs << 10 | cx << 21;      // per 256 threads: <= 256, 1024, 1024
-    uint32_t incl = packed;
+    uint32_t incl = packed, incl2 = cb;
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
-      const uint32_t o = __shfl_up(incl, d, 64);
-      if ((int)(threadIdx.x & 63u) >= d) incl += o;
+      const uint32_t o = __shfl_up(incl, d, 64), o2 = __shfl_up(incl2, d, 64);
+      if ((int)(threadIdx.x & 63u) >= d) { incl += o; incl2 += o2; }
     }
-    if ((threadIdx.x & 63u) == 63) wave_sum[threadIdx.x >> 6] = incl;
+    if ((threadIdx.x & 63u) == 63) { wave_sum[threadIdx.x >> 6] = incl; wave_sum2[threadIdx.x >> 6] = incl2; }
     __syncthreads();
-    uint32_t excl = incl - packed, tot = 0;
-    for (uint32_t w = 0; w < 4; w++) { if (w < (threadIdx.x >> 6)) excl += wave_sum[w]; tot += wave_sum[w]; }
+    uint32_t excl = incl - packed, tot = 0, excl2 = incl2 - cb, tot2 = 0;
+    for (uint32_t w = 0; w < 4; w++) {
+      if (w < (threadIdx.x >> 6)) { excl += wave_sum[w]; excl2 += wave_sum2[w]; }
+      tot += wave_sum[w]; tot2 += wave_sum2[w];
+    }
     uint32_t ow = run[0] + (excl & 1023u), os = run[1] + ((excl >> 10) & 2047u), ox = run[2] + (excl >> 21);
     if (cw) list_whole[first + ow] = shape;
+    if (cb) list_whole[first + n - 1u - (run[3] + excl2)] = shape;
     for (uint32_t ps = 0; ps < npass; ps++) {
       if ((cls >> ps) & 1u) list_slice[(size_t)first * npass + os++] = shape * npass + ps;
       if ((cls >> (4 + ps)) & 1u) list_wide[(size_t)first * npass + ox++] = shape * npass + ps;
     }
     __syncthreads();
-    if (threadIdx.x == 0) { run[0] += tot & 1023u; run[1] += (tot >> 10) & 2047u; run[2] += tot >> 21; }
+    if (threadIdx.x == 0) { run[0] += tot & 1023u; run[1] += (tot >> 10) & 2047u; run[2] += tot >> 21; run[3] += tot2; }
     __syncthreads();
   }
-  if (threadIdx.x == 0) { list_cnt[lv] = run[0]; list_cnt[n_levels + lv] = run[1]; list_cnt[2 * n_levels + lv] = run[2]; }
+  if (threadIdx.x == 0) {
+    list_cnt[lv] = run[0]; list_cnt[n_levels + lv] = run[1]; list_cnt[2 * n_levels + lv] = run[2];
+    list_cnt[3 * n_levels + lv] = run[3];
+  }
 }
 
-// One dependency level, the items a single wave can hold: first the whole shapes, then the slices.
-// T threads per item: one wave when the level has enough items to fill the chip, four when it has
-// few (then an item's tasks are spread over more lanes).
+// One dependency level, the items an LDS slice of kSmallCap tasks holds: first the larger ones
+// (whole shapes from the back of the level's stretch of list_whole, then slices), which take
+// longest, then the small whole shapes, which fill the gaps at the end.  T threads per item: one
+// wave when the level has enough items to fill the chip, four when it has few (then an item's
+// tasks are spread over more lanes).
 template <int T>
-__global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(1, 4))) void fill_kernel(const DevParams* __restrict__ P,
-                                                 const uint32_t* __restrict__ list_whole, uint32_t n_whole,
-                                                 const uint32_t* __restrict__ list_slice, uint32_t cap,
-                                                 uint64_t* __restrict__ cost, uint16_t* __restrict__ arg,
-                                                 Counters* __restrict__ ctr) {
+__global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(1, 4))) void fill_kernel(
+    const DevParams* __restrict__ P, const uint32_t* __restrict__ list_whole, uint32_t n_stretch, uint32_t n_bigwhole,
+    const uint32_t* __restrict__ list_slice, uint32_t n_slice, uint32_t cap, uint64_t* __restrict__ cost,
+    uint16_t* __restrict__ arg, Counters* __restrict__ ctr) {
   extern __shared__ __align__(16) unsigned char smem[];
-  uint32_t shape, pass0, np;
-  if (blockIdx.x < n_whole) {
-    shape = list_whole[blockIdx.x]; pass0 = 0; np = P->npass;
-  } else {
-    const uint32_t unit = list_slice[blockIdx.x - n_whole];
+  const uint32_t n_big = n_bigwhole + n_slice;
+  uint32_t shape, pass0 = 0, np = P->npass;
+  if (blockIdx.x < n_bigwhole) {
+    shape = list_whole[n_stretch - 1u - blockIdx.x];
+  } else if (blockIdx.x < n_big) {
+    const uint32_t unit = list_slice[blockIdx.x - n_bigwhole];
     shape = unit / P->npass; pass0 = unit - shape * P->npass; np = 1;
+  } else {
+    shape = list_whole[blockIdx.x - n_big];
   }
   Shape S;
   load_shape(P, shape, S);
@@ -856,24 +867,25 @@ void launch_plan(const DevParams* P, uint32_t n_shapes, uint32_t npass, uint32_t
                  hipStream_t stream) {
   const uint32_t cap = fill_wave_cap(G);
   hipLaunchKernelGGL(plan_kernel, dim3((n_shapes + 4 * kPlanShapes - 1) / (4 * kPlanShapes)), dim3(256), 0, stream, P,
-                     n_shapes, cap, cap, shape_class, fitmap, ctr);
+                     n_shapes, cap, cap, kWaveCap < cap ? kWaveCap : cap, shape_class, fitmap, ctr);
   hipLaunchKernelGGL(sort_work_kernel, dim3(n_levels), dim3(256), 0, stream, level_shapes, level_off, n_levels, npass,
                      shape_class, list_whole, list_slice, list_wide, list_cnt);
 }
 
-// One dependency level: the items a wave can hold, and the wide ones (independent of each other:
-// the caller may give them a stream of their own).
+// One dependency level: the items an LDS slice holds, and the wide ones (independent of each other:
+// the caller may give them a stream of their own).  list_whole: the level's stretch of n_stretch
+// entries, n_small small shapes at its front and n_bigwhole others at its back.
 void launch_fill_level(const DevParams* P, uint32_t npass, uint32_t G, uint32_t max_task, const uint32_t* list_whole,
-                       uint32_t n_whole, const uint32_t* list_slice, uint32_t n_slice, const uint32_t* list_wide,
-                       uint32_t n_wide, uint64_t* cost, uint16_t* arg, Counters* ctr, hipStream_t stream,
-                       hipStream_t wide_stream) {
-  const uint32_t cap = fill_wave_cap(G), n = n_whole + n_slice;
+                       uint32_t n_stretch, uint32_t n_small, uint32_t n_bigwhole, const uint32_t* list_slice,
+                       uint32_t n_slice, const uint32_t* list_wide, uint32_t n_wide, uint64_t* cost, uint16_t* arg,
+                       Counters* ctr, hipStream_t stream, hipStream_t wide_stream) {
+  const uint32_t cap = fill_wave_cap(G), n = n_bigwhole + n_slice + n_small;
   if (n >= kWideBelow)
-    hipLaunchKernelGGL(fill_kernel<64>, dim3(n), dim3(64), unit_lds_bytes(cap, npass), stream, P, list_whole, n_whole,
-                       list_slice, cap, cost, arg, ctr);
+    hipLaunchKernelGGL(fill_kernel<64>, dim3(n), dim3(64), unit_lds_bytes(cap, npass), stream, P, list_whole, n_stretch,
+                       n_bigwhole, list_slice, n_slice, cap, cost, arg, ctr);
   else if (n)
-    hipLaunchKernelGGL(fill_kernel<256>, dim3(n), dim3(256), unit_lds_bytes(cap, npass), stream, P, list_whole, n_whole,
-                       list_slice, cap, cost, arg, ctr);
+    hipLaunchKernelGGL(fill_kernel<256>, dim3(n), dim3(256), unit_lds_bytes(cap, npass), stream, P, list_whole, n_stretch,
+                       n_bigwhole, list_slice, n_slice, cap, cost, arg, ctr);
   if (n_wide)
     hipLaunchKernelGGL(fill_big_kernel, dim3(n_wide), dim3(kBigBlock), unit_lds_bytes(max_task, npass), wide_stream, P,
                        list_wide, max_task, cost, arg, ctr);

@@ -60,12 +60,16 @@ struct Compiled {
   int lay_axis[5], dt_axis[5];            // coordinate axis of the operand's bit, -1 if none
   mrl_target_desc target;
   mrl_lattice_desc lat;                   // sizes pointers re-pointed to this->sizes
+  // Pinned image of the uploaded head of the scratch buffer (counters .. mk_entry), built at the
+  // first solve and patched per call (device pointers); solves are serialized, so one is enough.
+  mutable char* staging = nullptr;
+  ~Compiled() { if (staging) (void)hipHostFree(staging); }
 };
 
 // Offsets of the fixed part of the scratch buffer.
 struct FixedLayout {
   size_t counters, params, tiles, level_shapes, shape_class, level_off, mk_entry, list_whole, list_slice, list_wide, list_cnt, fitmap, maskD, maskC, lineD, lineC, prefD, prefC, tile_tmp, tile_tmp2, totals,
-      q_idx, q_cost, q_arg, end;
+      q_idx, q_cost, q_arg, upload_end, end;
   uint32_t n_words;
 };
 
@@ -74,13 +78,15 @@ FixedLayout fixed_layout(const Compiled& c) {
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
   f.n_words = (uint32_t)((c.n_specs + 63) / 64);
+  // uploaded in one copy: counters (zero), parameters, tile lists, level lists, microkernel table
   f.counters = take(sizeof(Counters));
   f.params = take(sizeof(DevParams));
   f.tiles = take(c.tiles.size() * sizeof(TileEntry) + 8);
   f.level_shapes = take(c.level_shapes.size() * 4);
-  f.shape_class = take(c.level_shapes.size() * 4);
   f.level_off = take(c.level_off.size() * 4);
   f.mk_entry = take(c.mk_entry.size());
+  f.upload_end = o;
+  f.shape_class = take(c.level_shapes.size() * 4);
   f.list_whole = take((size_t)c.n_shapes * 4);
   f.list_slice = take((size_t)c.n_shapes * c.P.npass * 4);
   f.list_wide = take((size_t)c.n_shapes * c.P.npass * 4);
@@ -387,6 +393,7 @@ struct Aux {
   hipStream_t stream = nullptr;
   std::vector<hipEvent_t> events;
   uint32_t* h_counts = nullptr;     // pinned: counts read back without stalling the other stream
+  hipEvent_t timing[3] = {nullptr, nullptr, nullptr};
 };
 
 int32_t get_aux(size_t n_events, Aux*& out) {
@@ -395,6 +402,7 @@ int32_t get_aux(size_t n_events, Aux*& out) {
   std::lock_guard<std::mutex> lock(mu);
   if (!aux.stream) HIP_TRY(hipStreamCreateWithFlags(&aux.stream, hipStreamNonBlocking));
   if (!aux.h_counts) HIP_TRY(hipHostMalloc((void**)&aux.h_counts, 64, hipHostMallocDefault));
+  for (auto& e : aux.timing) if (!e) HIP_TRY(hipEventCreate(&e));
   while (aux.events.size() < n_events) {
     hipEvent_t e;
     HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
@@ -521,23 +529,22 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
   uint32_t* d_list_cnt = (uint32_t*)(base + f.list_cnt);
   uint32_t* d_fitmap = (uint32_t*)(base + f.fitmap);
   P.mk_entry = (const uint8_t*)(base + f.mk_entry);
-  HIP_TRY(hipMemsetAsync(d_ctr, 0, sizeof(Counters), st));
-  HIP_TRY(hipMemcpyAsync((void*)P.mk_entry, c.mk_entry.data(), c.mk_entry.size(), hipMemcpyHostToDevice, st));
-  HIP_TRY(hipMemcpyAsync(d_P, &P, sizeof P, hipMemcpyHostToDevice, st));
-  if (!c.tiles.empty())
-    HIP_TRY(hipMemcpyAsync((void*)P.tiles, c.tiles.data(), c.tiles.size() * sizeof(TileEntry), hipMemcpyHostToDevice, st));
-  HIP_TRY(hipMemcpyAsync(d_level_shapes, c.level_shapes.data(), c.level_shapes.size() * 4, hipMemcpyHostToDevice, st));
-  HIP_TRY(hipMemcpyAsync(d_level_off, c.level_off.data(), c.level_off.size() * 4, hipMemcpyHostToDevice, st));
+  if (!c.staging) {
+    HIP_TRY(hipHostMalloc((void**)&c.staging, f.upload_end, hipHostMallocDefault));
+    memset(c.staging, 0, f.upload_end);
+    if (!c.tiles.empty()) memcpy(c.staging + f.tiles, c.tiles.data(), c.tiles.size() * sizeof(TileEntry));
+    memcpy(c.staging + f.level_shapes, c.level_shapes.data(), c.level_shapes.size() * 4);
+    memcpy(c.staging + f.level_off, c.level_off.data(), c.level_off.size() * 4);
+    memcpy(c.staging + f.mk_entry, c.mk_entry.data(), c.mk_entry.size());
+  }
+  memcpy(c.staging + f.params, &P, sizeof P);
+  HIP_TRY(hipMemcpyAsync(base, c.staging, f.upload_end, hipMemcpyHostToDevice, st));
 
-  hipEvent_t ev[3];
-  for (auto& e : ev) HIP_TRY(hipEventCreate(&e));
-  struct EvGuard { hipEvent_t* e; ~EvGuard() { for (int i = 0; i < 3; i++) (void)hipEventDestroy(e[i]); } } evg{ev};
-
-  // ---- fill: one launch per dependency level ----
   // ---- fill: plan, then one launch (or two) per dependency level ----
   Aux* aux = nullptr;
   rc = get_aux(2 * (size_t)n_lev + 3, aux);
   if (rc) return rc;
+  hipEvent_t* ev = aux->timing;
   size_t ev_used = 0;
   hipStream_t s2 = aux->stream;
   HIP_TRY(hipEventRecord(ev[0], st));

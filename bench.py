@@ -70,13 +70,11 @@ def main():
         bufs[label] = (torch.empty(cb, dtype=torch.uint8, device=dev), torch.empty(ab, dtype=torch.uint8, device=dev))
 
     def step():
-        tabs = {}
-        for label, lat, deps in cfg["lattices"]:
-            # every lattice gets its own slice of the scratch buffer: a solved table keeps its
-            # box lists there while later lattices are solved
-            tabs[label] = B.solve(target, lat, deps=[tabs[d] for d in deps],
-                                  buffers=(bufs[label][0], bufs[label][1], scratch_of[label]))
-        return tabs
+        # every lattice gets its own slice of the scratch buffer: a solved table keeps its box
+        # lists there while later lattices are solved.  Lattices that do not depend on each other
+        # (M and E) are in flight together.
+        return B.solve_lattices(target, cfg["lattices"],
+                                buffers={l: (bufs[l][0], bufs[l][1], scratch_of[l]) for l in bufs})
 
     # split the scratch buffer between the lattices in proportion to their size
     sizes = {label: W.n_specs(cfg["target"], lat) for label, lat, _ in cfg["lattices"]}

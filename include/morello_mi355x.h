@@ -144,8 +144,9 @@ typedef struct mrl_table mrl_table;
  * referenced by *out until mrl_table_destroy.  hip_stream: a hipStream_t (or
  * NULL for the default stream); part of the work runs on a helper stream of
  * the library (default priority) that is ordered after and before the given
- * one, and the call returns after both have drained.  Calls of mrl_solve are
- * serialized within a process: they share that helper stream.
+ * one, and the call returns after both have drained.  Calls from different
+ * host threads (on different streams) may overlap, e.g. for lattices that do
+ * not depend on each other; calls for the same (target, lattice) take turns.
  * stats: host, optional. */
 int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat,
                   const mrl_table* const* deps, uint32_t n_deps,

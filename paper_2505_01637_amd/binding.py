@@ -261,10 +261,64 @@ def solve(target, lattice, deps=(), scratch_bytes=None, stream=None, buffers=Non
     return Table(h, target, lattice, ext, buffers, stats)
 
 
+_side_streams = {}
+
+
+def _side_stream(dev, i):
+    """The i-th extra stream of a device (default priority), created once."""
+    import torch
+    pool = _side_streams.setdefault(dev, [])
+    while len(pool) <= i:
+        pool.append(torch.cuda.Stream(device=dev))
+    return pool[i]
+
+
+def solve_lattices(target, lattices, scratch_bytes=None, buffers=None):
+    """Solve [(label, lattice, dep labels)] in dependency order; returns {label: Table}.
+
+    Lattices whose dependencies are done and that do not depend on each other are handed to the
+    library from one host thread each, on a stream of their own (default priority), so their
+    kernels overlap on the device; the library call itself releases the GIL.  buffers: optional
+    {label: (cost, argmin, scratch)} torch uint8 tensors to reuse.
+    """
+    import threading
+    import torch
+    done, pending = {}, list(lattices)
+    dev = torch.cuda.current_device()
+    while pending:
+        ready = [job for job in pending if all(d in done for d in job[2])]
+        if not ready:
+            raise ValueError("lattice dependencies form a cycle or name an unknown label")
+        pending = [job for job in pending if job not in ready]
+
+        def run(job, stream, errors):
+            label, lat, deps = job
+            try:
+                torch.cuda.set_device(dev)
+                done[label] = solve(target, lat, deps=[done[d] for d in deps], scratch_bytes=scratch_bytes,
+                                    stream=stream, buffers=None if buffers is None else buffers[label])
+            except BaseException as e:      # re-raised in the calling thread
+                errors.append(e)
+
+        errors = []
+        if len(ready) == 1:
+            run(ready[0], None, errors)
+        else:
+            # every job on a stream of its own: work on the default stream would serialize with them
+            torch.cuda.synchronize()        # the streams start after everything queued so far
+            threads = [threading.Thread(target=run, args=(job, _side_stream(dev, i + 1), errors))
+                       for i, job in enumerate(ready[1:])]
+            for t in threads:
+                t.start()
+            run(ready[0], _side_stream(dev, 0), errors)
+            for t in threads:
+                t.join()
+        if errors:
+            raise errors[0]
+    return done
+
+
 def solve_config(cfg, scratch_bytes=None):
-    """Solve every lattice of a workloads.config() dict, in order.  Returns (Target, {label: Table})."""
+    """Solve every lattice of a workloads.config() dict.  Returns (Target, {label: Table})."""
     target = Target(cfg["target"])
-    out = {}
-    for label, lat, deps in cfg["lattices"]:
-        out[label] = solve(target, lat, deps=[out[d] for d in deps], scratch_bytes=scratch_bytes)
-    return target, out
+    return target, solve_lattices(target, cfg["lattices"], scratch_bytes=scratch_bytes)

@@ -61,8 +61,9 @@ struct Compiled {
   mrl_target_desc target;
   mrl_lattice_desc lat;                   // sizes pointers re-pointed to this->sizes
   // Pinned image of the uploaded head of the scratch buffer (counters .. mk_entry), built at the
-  // first solve and patched per call (device pointers); solves are serialized, so one is enough.
+  // first solve and patched per call (device pointers).
   mutable char* staging = nullptr;
+  mutable std::mutex solve_mu;            // solves of one compiled lattice take turns (they share the image)
   ~Compiled() { if (staging) (void)hipHostFree(staging); }
 };
 
@@ -388,27 +389,50 @@ int32_t get_compiled(const mrl_target_desc& T, const mrl_lattice_desc* L, Compil
 
 // A second stream (default priority, non-blocking) for work that is independent of what runs on
 // the caller's stream: the wide items of a dependency level beside its other items, and one of the
-// two box lists beside the other.  Created once per process; events likewise.
+// two box lists beside the other; with it the events and the pinned counters a solve needs.
 struct Aux {
   hipStream_t stream = nullptr;
   std::vector<hipEvent_t> events;
   uint32_t* h_counts = nullptr;     // pinned: counts read back without stalling the other stream
   hipEvent_t timing[3] = {nullptr, nullptr, nullptr};
+  int device = -1;
+  bool busy = false;
 };
 
-int32_t get_aux(size_t n_events, Aux*& out) {
-  static Aux aux;
-  static std::mutex mu;
-  std::lock_guard<std::mutex> lock(mu);
-  if (!aux.stream) HIP_TRY(hipStreamCreateWithFlags(&aux.stream, hipStreamNonBlocking));
-  if (!aux.h_counts) HIP_TRY(hipHostMalloc((void**)&aux.h_counts, 64, hipHostMallocDefault));
-  for (auto& e : aux.timing) if (!e) HIP_TRY(hipEventCreate(&e));
-  while (aux.events.size() < n_events) {
+// One set per solve in flight (solves on different host threads may overlap), kept for reuse.
+struct AuxLease {
+  Aux* a = nullptr;
+  ~AuxLease();
+};
+std::mutex g_aux_mu;
+std::vector<std::unique_ptr<Aux>> g_aux_pool;
+AuxLease::~AuxLease() {
+  if (a) { std::lock_guard<std::mutex> lock(g_aux_mu); a->busy = false; }
+}
+
+int32_t get_aux(size_t n_events, AuxLease& lease) {
+  int dev = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  Aux* aux = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(g_aux_mu);
+    for (auto& p : g_aux_pool) if (!p->busy && p->device == dev) { aux = p.get(); break; }
+    if (!aux) {
+      g_aux_pool.emplace_back(new Aux);
+      aux = g_aux_pool.back().get();
+      aux->device = dev;
+    }
+    aux->busy = true;
+  }
+  lease.a = aux;
+  if (!aux->stream) HIP_TRY(hipStreamCreateWithFlags(&aux->stream, hipStreamNonBlocking));
+  if (!aux->h_counts) HIP_TRY(hipHostMalloc((void**)&aux->h_counts, 64, hipHostMallocDefault));
+  for (auto& e : aux->timing) if (!e) HIP_TRY(hipEventCreate(&e));
+  while (aux->events.size() < n_events) {
     hipEvent_t e;
     HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
-    aux.events.push_back(e);
+    aux->events.push_back(e);
   }
-  out = &aux;
   return MRL_OK;
 }
 
@@ -505,9 +529,7 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
     return fail(MRL_E_INVAL, "only a FUSED lattice takes deps");
   }
 
-  // the helper stream, its events and the pinned counters are one set per process
-  static std::mutex solve_mu;
-  std::lock_guard<std::mutex> solve_lock(solve_mu);
+  std::lock_guard<std::mutex> solve_lock(c.solve_mu);
 
   const FixedLayout f = fixed_layout(c);
   tab->f = f;
@@ -541,9 +563,10 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
   HIP_TRY(hipMemcpyAsync(base, c.staging, f.upload_end, hipMemcpyHostToDevice, st));
 
   // ---- fill: plan, then one launch (or two) per dependency level ----
-  Aux* aux = nullptr;
-  rc = get_aux(2 * (size_t)n_lev + 3, aux);
+  AuxLease lease;
+  rc = get_aux(2 * (size_t)n_lev + 3, lease);
   if (rc) return rc;
+  Aux* aux = lease.a;
   hipEvent_t* ev = aux->timing;
   size_t ev_used = 0;
   hipStream_t s2 = aux->stream;

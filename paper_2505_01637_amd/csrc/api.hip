@@ -115,8 +115,9 @@ FixedLayout fixed_layout(const Compiled& c) {
   return f;
 }
 
-// per box while merging: bcell, blen, alive, pred, next, pos, two live lists; per final box: fcell, flen, fv0, fv1
-size_t work_bytes(uint64_t nb) { return align_up(nb * 4) + align_up(nb * 16) + 2 * align_up(nb) + 4 * align_up(nb * 4) + align_up((nb / 256 + 1) * 4); }
+// per box while merging: bcell, blen, alive, pred, next, pos, and for the dense copies of the live boxes
+// cell2, len2, alive2, pos2; a flag per 256 boxes.  Per final box: fcell, flen, fv0, fv1
+size_t work_bytes(uint64_t nb) { return 5 * align_up(nb * 4) + 2 * align_up(nb * 16) + 3 * align_up(nb) + align_up((nb / 256 + 1) * 4); }
 size_t final_bytes(uint64_t nb) { return align_up(nb * 4) + align_up(nb * 16) + 2 * align_up(nb * 8); }
 
 uint32_t ipow(uint32_t b, uint32_t e) { uint32_t r = 1; while (e--) r *= b; return r; }
@@ -637,14 +638,15 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
   char* work_lo = base + (scratch_bytes - wbL[0] - wbL[1]) / kAlign * kAlign;
   if ((size_t)(work_lo - base) < f.end)
     return fail(MRL_E_NOMEM, "scratch buffer too small: %zu bytes given, up to %zu needed", scratch_bytes, needed);
-  // per list: its arrays, the boxes still to be visited (all of them at first, then compacted lists of
-  // the live ones, ascending, once the first passes have merged most boxes away) and the pass state
+  // per list: its arrays and the pass state.  Once the first pass has merged most boxes away, the
+  // live ones move to dense arrays (cell2, len2, alive2) and get new indices 0..n-1, in order
   struct ListWork {
-    uint32_t *bcell, *next, *pos, *live_buf[2], *block_linked, *d_cnt;
-    char* blen;
-    uint8_t *alive, *pred;
-    const uint32_t *ids = nullptr, *n_ptr = nullptr;
-    uint32_t n_bound = 0, n_pass = 0, flip = 0, q_next = 0;
+    uint32_t *bcell, *next, *pos, *cell2, *pos2, *block_linked, *d_cnt;
+    char *blen, *len2;
+    uint8_t *alive, *pred, *alive2;
+    const uint8_t* old_alive = nullptr;     // set by the compaction, with remap
+    const uint32_t* remap = nullptr;
+    uint32_t n = 0, q_next = 0;
     uint8_t stamp = 0;
   } LW[2];
   hipStream_t stL[2] = {s2, st};
@@ -661,25 +663,15 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
   tail.n = n_axes - n_generic;
   for (uint32_t k = 0; k < tail.n; k++) { tail.axis[k] = pass_axis[n_generic + k]; tail.stride[k] = g.stride[pass_axis[n_generic + k]]; }
 
-  auto one_pass = [&](int which) {        // the next generic pass, then a compaction if it is one of the first two
+  auto one_pass = [&](int which) {
     ListWork& W = LW[which];
     const uint32_t a = pass_axis[W.q_next++];
-    launch_axis_pass(g, a, ++W.stamp, which == 1, W.ids, W.n_bound, W.n_ptr, W.bcell, W.blen, W.alive, W.pred, W.next,
+    launch_axis_pass(g, a, ++W.stamp, which == 1, W.n, W.old_alive, W.remap, W.bcell, W.blen, W.alive, W.pred, W.next,
                      W.block_linked, maskL[which], prefL[which], tab->d_cost, tab->d_arg, axis_sizes(a), stL[which]);
-    W.n_pass++;
-    if (W.n_pass <= 1 && W.n_bound > (1u << 20)) {
-      scan_flags(W.alive, W.ids, W.n_bound, W.n_ptr, tileL[which], W.pos, W.d_cnt + W.flip, stL[which]);
-      launch_compact_live(W.alive, W.ids, W.n_bound, W.n_ptr, W.pos, W.live_buf[W.flip], stL[which]);
-      W.ids = W.live_buf[W.flip];
-      W.n_ptr = W.d_cnt + W.flip;
-      W.flip ^= 1;
-      return true;
-    }
-    return false;
   };
-  // first part: the boxes of pass 0 and the first generic pass; its compaction removes the most, so
-  // its count is fetched (while the other list's first part runs) to size the later grids
-  bool fetched[2] = {false, false};
+  // first part: the boxes of pass 0 and the first generic pass, then (large lists) the compaction;
+  // the count of live boxes is fetched while the other list's first part runs
+  bool compacted[2] = {false, false};
   for (int which = 1; which >= 0; which--) {
     ListWork& W = LW[which];
     const uint64_t nb = nbL[which];
@@ -690,30 +682,38 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
     W.pred = (uint8_t*)w; w += align_up(nb);
     W.next = (uint32_t*)w; w += align_up(nb * 4);
     W.pos = (uint32_t*)w; w += align_up(nb * 4);
-    W.live_buf[0] = (uint32_t*)w; w += align_up(nb * 4);
-    W.live_buf[1] = (uint32_t*)w; w += align_up(nb * 4);
+    W.cell2 = (uint32_t*)w; w += align_up(nb * 4);
+    W.pos2 = (uint32_t*)w; w += align_up(nb * 4);
+    W.len2 = w; w += align_up(nb * 16);
+    W.alive2 = (uint8_t*)w; w += align_up(nb);
     W.block_linked = (uint32_t*)w;
-    W.d_cnt = d_tot + 4 + which * 4;       // [0], [1]: lengths of the compacted lists; [2]: the final count
-    W.n_bound = (uint32_t)nb;
+    W.d_cnt = d_tot + 4 + which * 4;       // [0]: live boxes at the compaction; [2]: the final count
+    W.n = (uint32_t)nb;
     launch_make_boxes(g, a0, maskL[which], prefL[which], lineL[which], W.bcell, W.blen, W.alive, W.pred, stL[which]);
-    if (n_generic && one_pass(which)) {
-      HIP_TRY(hipMemcpyAsync(aux->h_counts + 2 + which, W.n_ptr, 4, hipMemcpyDeviceToHost, stL[which]));
-      fetched[which] = true;
+    if (n_generic) {
+      one_pass(which);
+      if (W.n > (1u << 20) && (n_generic > 1 || tail.n)) {
+        scan_flags(W.alive, W.n, tileL[which], W.pos, W.d_cnt, stL[which]);
+        launch_compact_boxes(W.n, W.alive, W.pos, W.bcell, W.blen, W.cell2, W.len2, W.alive2, stL[which]);
+        HIP_TRY(hipMemcpyAsync(aux->h_counts + 2 + which, W.d_cnt, 4, hipMemcpyDeviceToHost, stL[which]));
+        compacted[which] = true;
+      }
     }
   }
-  // second part: the other passes, the final count
+  // second part: the other passes on the dense arrays, the final count
   for (int which = 1; which >= 0; which--) {
     ListWork& W = LW[which];
-    if (fetched[which]) {
+    if (compacted[which]) {
       HIP_TRY(hipStreamSynchronize(stL[which]));
-      W.n_bound = aux->h_counts[2 + which];
-      W.n_ptr = nullptr;
+      W.n = aux->h_counts[2 + which];
+      W.old_alive = W.alive; W.remap = W.pos;
+      W.bcell = W.cell2; W.blen = W.len2; W.alive = W.alive2; W.pos = W.pos2;
     }
     while (W.q_next < n_generic) one_pass(which);
     if (tail.n)
-      launch_tail_pairs(tail, which == 1, f.n_words, maskL[which], prefL[which], W.blen, W.alive, tab->d_cost, tab->d_arg,
-                        stL[which]);
-    scan_flags(W.alive, W.ids, W.n_bound, W.n_ptr, tileL[which], W.pos, W.d_cnt + 2, stL[which]);
+      launch_tail_pairs(tail, which == 1, f.n_words, maskL[which], prefL[which], W.old_alive, W.remap, W.blen, W.alive,
+                        tab->d_cost, tab->d_arg, stL[which]);
+    scan_flags(W.alive, W.n, tileL[which], W.pos, W.d_cnt + 2, stL[which]);
     HIP_TRY(hipMemcpyAsync(aux->h_counts + which, W.d_cnt + 2, 4, hipMemcpyDeviceToHost, stL[which]));
   }
   for (int which = 0; which < 2; which++) {
@@ -731,8 +731,8 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
     uint64_t* fv0 = (uint64_t*)r; r += align_up(nf * 8);
     uint64_t* fv1 = (uint64_t*)r;
     const ListWork& W = LW[which];
-    launch_emit(g, d_P, which == 1, W.ids, W.n_bound, W.n_ptr, W.bcell, W.blen, W.alive, W.pos, tab->d_cost, tab->d_arg, fcell,
-                flen, fv0, fv1, stL[which]);
+    launch_emit(g, d_P, which == 1, W.n, W.bcell, W.blen, W.alive, W.pos, tab->d_cost, tab->d_arg, fcell, flen, fv0, fv1,
+                stL[which]);
     tab->list_off[which] = front;
     tab->list_n[which] = nf;
     front += fb;

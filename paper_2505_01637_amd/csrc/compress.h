@@ -30,31 +30,28 @@ void launch_head_flags(const Geo& g, uint32_t a0, const uint64_t* cost, const ui
                        unsigned long long* lineC, hipStream_t st);
 void scan_mask_words(const unsigned long long* mask, uint32_t n_words, uint32_t* tile_tmp, uint32_t* prefix,
                      uint32_t* total, hipStream_t st);
-// Where a count is only known on the device (the length of a compacted list), n / n_boxes is an
-// upper bound that sizes the grid and n_ptr points to the count; n_ptr == nullptr: n is the count.
-void scan_flags(const uint8_t* flags, const uint32_t* ids, uint32_t n, const uint32_t* n_ptr, uint32_t* tile_tmp,
-                uint32_t* pos, uint32_t* total, hipStream_t st);
-void launch_compact_live(const uint8_t* alive, const uint32_t* ids, uint32_t n, const uint32_t* n_ptr, const uint32_t* pos,
-                         uint32_t* out, hipStream_t st);
+void scan_flags(const uint8_t* flags, uint32_t n, uint32_t* tile_tmp, uint32_t* pos, uint32_t* total, hipStream_t st);
+// Live boxes (alive[b]) move to dense arrays: box b becomes box pos[b].
+void launch_compact_boxes(uint32_t n, const uint8_t* alive, const uint32_t* pos, const uint32_t* bcell, const void* blen,
+                          uint32_t* cell2, void* len2, uint8_t* alive2, hipStream_t st);
 void launch_make_boxes(const Geo& g, uint32_t a0, const unsigned long long* mask, const uint32_t* prefix,
                        const unsigned long long* line, uint32_t* bcell, void* blen, uint8_t* alive, uint8_t* pred,
                        hipStream_t st);
-void launch_axis_pass(const Geo& g, uint32_t a, uint8_t stamp, bool is_cost, const uint32_t* ids, uint32_t n_boxes,
-                      const uint32_t* n_ptr, const uint32_t* bcell,
-                      void* blen, uint8_t* alive, uint8_t* pred, uint32_t* next, uint32_t* block_linked,
-                      const unsigned long long* mask,
-                      const uint32_t* prefix, const uint64_t* cost, const uint16_t* arg, const uint32_t* axis_sizes,
-                      hipStream_t st);
+// One merge pass along axis a.  After a compaction the mask still ranks boxes by their old index:
+// old_alive / remap (the compaction's alive and pos) translate it; nullptr before.
+void launch_axis_pass(const Geo& g, uint32_t a, uint8_t stamp, bool is_cost, uint32_t n_boxes, const uint8_t* old_alive,
+                      const uint32_t* remap, const uint32_t* bcell, void* blen, uint8_t* alive, uint8_t* pred, uint32_t* next,
+                      uint32_t* block_linked, const unsigned long long* mask, const uint32_t* prefix, const uint64_t* cost,
+                      const uint16_t* arg, const uint32_t* axis_sizes, hipStream_t st);
 // The trailing passes over axes of extent 2 whose stride is at most 32 cells, in pass order.
 struct TailAxes {
   uint32_t n;
   uint32_t axis[8], stride[8];
 };
 void launch_tail_pairs(const TailAxes& T, bool is_cost, uint32_t n_words, const unsigned long long* mask,
-                       const uint32_t* prefix, void* blen, uint8_t* alive, const uint64_t* cost, const uint16_t* arg,
-                       hipStream_t st);
-void launch_emit(const Geo& g, const DevParams* P, bool is_cost, const uint32_t* ids, uint32_t n_boxes,
-                 const uint32_t* n_ptr, const uint32_t* bcell,
+                       const uint32_t* prefix, const uint8_t* old_alive, const uint32_t* remap, void* blen, uint8_t* alive,
+                       const uint64_t* cost, const uint16_t* arg, hipStream_t st);
+void launch_emit(const Geo& g, const DevParams* P, bool is_cost, uint32_t n_boxes, const uint32_t* bcell,
                  const void* blen,
                  const uint8_t* alive, const uint32_t* pos, const uint64_t* cost, const uint16_t* arg, uint32_t* fcell,
                  void* flen, uint64_t* fv0, uint64_t* fv1, hipStream_t st);

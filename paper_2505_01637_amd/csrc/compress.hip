@@ -197,8 +197,7 @@ struct LoadPopc {
 };
 struct LoadFlag {
   const uint8_t* p;
-  const uint32_t* ids;      // optional list of box indices; nullptr = all boxes
-  __device__ __forceinline__ uint32_t operator()(uint32_t i) const { return p[ids ? ids[i] : i]; }
+  __device__ __forceinline__ uint32_t operator()(uint32_t i) const { return p[i]; }
 };
 
 constexpr uint32_t kScanItems = 8, kScanBlock = 256, kScanTile = kScanItems * kScanBlock;
@@ -213,13 +212,9 @@ __device__ __forceinline__ uint32_t block_reduce_256(uint32_t v, uint32_t* sh) {
   return t;
 }
 
-// Item counts: where a count is only known on the device (the length of a compacted list), the
-// kernels get an upper bound n for the grid and read the count itself from n_ptr.
 template <class L>
-__global__ __launch_bounds__(256) void scan_tile_sums_kernel(L load, uint32_t n, const uint32_t* __restrict__ n_ptr,
-                                                             uint32_t* __restrict__ tile_sum) {
+__global__ __launch_bounds__(256) void scan_tile_sums_kernel(L load, uint32_t n, uint32_t* __restrict__ tile_sum) {
   __shared__ uint32_t sh[4];
-  if (n_ptr) n = *n_ptr;
   const uint32_t first = blockIdx.x * kScanTile + threadIdx.x * kScanItems;
   uint32_t s = 0;
 #pragma unroll
@@ -258,12 +253,9 @@ __global__ __launch_bounds__(256) void scan_top_kernel(uint32_t* __restrict__ ti
 }
 
 template <class L>
-__global__ __launch_bounds__(256) void scan_apply_kernel(L load, uint32_t n, const uint32_t* __restrict__ n_ptr,
-                                                         const uint32_t* __restrict__ tile_excl,
+__global__ __launch_bounds__(256) void scan_apply_kernel(L load, uint32_t n, const uint32_t* __restrict__ tile_excl,
                                                          uint32_t* __restrict__ out) {
   __shared__ uint32_t sh[4];
-  if (n_ptr) n = *n_ptr;
-  if (blockIdx.x * kScanTile >= n) return;
   const uint32_t first = blockIdx.x * kScanTile + threadIdx.x * kScanItems;
   uint32_t v[kScanItems], s = 0;
 #pragma unroll
@@ -283,39 +275,42 @@ __global__ __launch_bounds__(256) void scan_apply_kernel(L load, uint32_t n, con
 }
 
 template <class L>
-static void exclusive_scan(L load, uint32_t n, const uint32_t* n_ptr, uint32_t* tile_tmp, uint32_t* out, uint32_t* total,
-                           hipStream_t st) {
+static void exclusive_scan(L load, uint32_t n, uint32_t* tile_tmp, uint32_t* out, uint32_t* total, hipStream_t st) {
   const uint32_t n_tiles = (n + kScanTile - 1) / kScanTile;
-  hipLaunchKernelGGL(scan_tile_sums_kernel<L>, dim3(n_tiles), dim3(256), 0, st, load, n, n_ptr, tile_tmp);
+  hipLaunchKernelGGL(scan_tile_sums_kernel<L>, dim3(n_tiles), dim3(256), 0, st, load, n, tile_tmp);
   hipLaunchKernelGGL(scan_top_kernel, dim3(1), dim3(256), 0, st, tile_tmp, n_tiles, total);
-  hipLaunchKernelGGL(scan_apply_kernel<L>, dim3(n_tiles), dim3(256), 0, st, load, n, n_ptr, tile_tmp, out);
+  hipLaunchKernelGGL(scan_apply_kernel<L>, dim3(n_tiles), dim3(256), 0, st, load, n, tile_tmp, out);
 }
 
 void scan_mask_words(const unsigned long long* mask, uint32_t n_words, uint32_t* tile_tmp, uint32_t* prefix,
                      uint32_t* total, hipStream_t st) {
-  exclusive_scan(LoadPopc{mask}, n_words, nullptr, tile_tmp, prefix, total, st);
+  exclusive_scan(LoadPopc{mask}, n_words, tile_tmp, prefix, total, st);
 }
 
-void scan_flags(const uint8_t* flags, const uint32_t* ids, uint32_t n, const uint32_t* n_ptr, uint32_t* tile_tmp,
-                uint32_t* pos, uint32_t* total, hipStream_t st) {
-  exclusive_scan(LoadFlag{flags, ids}, n, n_ptr, tile_tmp, pos, total, st);
+void scan_flags(const uint8_t* flags, uint32_t n, uint32_t* tile_tmp, uint32_t* pos, uint32_t* total, hipStream_t st) {
+  exclusive_scan(LoadFlag{flags}, n, tile_tmp, pos, total, st);
 }
 
-// out[pos[i]] = index of the i-th listed box, for the boxes still alive (keeps ascending order).
-__global__ __launch_bounds__(256) void compact_live_kernel(const uint8_t* __restrict__ alive,
-                                                           const uint32_t* __restrict__ ids, uint32_t n,
-                                                           const uint32_t* __restrict__ n_ptr,
-                                                           const uint32_t* __restrict__ pos, uint32_t* __restrict__ out) {
-  if (n_ptr) n = *n_ptr;
-  const uint32_t i = blockIdx.x * 256u + threadIdx.x;
-  if (i >= n) return;
-  const uint32_t b = ids ? ids[i] : i;
-  if (alive[b]) out[pos[i]] = b;
+// The live boxes move to dense arrays, in index order: box b becomes box pos[b].  The old alive[]
+// stays as it is: together with pos[] it translates the index a box had after the first pass
+// (its rank in the mask) into the new one.
+__global__ __launch_bounds__(256) void compact_boxes_kernel(uint32_t n, const uint8_t* __restrict__ alive,
+                                                            const uint32_t* __restrict__ pos,
+                                                            const uint32_t* __restrict__ bcell,
+                                                            const uint4* __restrict__ blen, uint32_t* __restrict__ cell2,
+                                                            uint4* __restrict__ len2, uint8_t* __restrict__ alive2) {
+  const uint32_t b = blockIdx.x * 256u + threadIdx.x;
+  if (b >= n || !alive[b]) return;
+  const uint32_t j = pos[b];
+  cell2[j] = bcell[b];
+  len2[j] = blen[b];
+  alive2[j] = 1;
 }
 
-void launch_compact_live(const uint8_t* alive, const uint32_t* ids, uint32_t n, const uint32_t* n_ptr, const uint32_t* pos,
-                         uint32_t* out, hipStream_t st) {
-  hipLaunchKernelGGL(compact_live_kernel, dim3((n + 255) / 256), dim3(256), 0, st, alive, ids, n, n_ptr, pos, out);
+void launch_compact_boxes(uint32_t n, const uint8_t* alive, const uint32_t* pos, const uint32_t* bcell, const void* blen,
+                          uint32_t* cell2, void* len2, uint8_t* alive2, hipStream_t st) {
+  hipLaunchKernelGGL(compact_boxes_kernel, dim3((n + 255) / 256), dim3(256), 0, st, n, alive, pos, bcell, (const uint4*)blen,
+                     cell2, (uint4*)len2, alive2);
 }
 
 // ---------------------------------------------------------------- boxes of pass 0
@@ -426,11 +421,12 @@ __device__ __forceinline__ uint32_t len_byte(const uint4& L, uint32_t a) {
 // Every box still has extent 1 on axis a when its pass comes (an axis is merged once).  Most
 // boxes differ in value from the cell past their end, so the values are compared first and the
 // extents are read only for the few that pass.  block_linked[workgroup] tells the absorb step
-// whether any of the workgroup's boxes got a successor.
+// whether any of the workgroup's boxes got a successor.  After the compaction the mask still
+// ranks boxes by their old index: old_alive / remap translate it (nullptr before).
 template <bool COST>
-__global__ __launch_bounds__(256) void link_kernel(Geo g, uint32_t a, uint8_t stamp,
-                                                   const uint32_t* __restrict__ ids, uint32_t n_boxes,
-                                                   const uint32_t* __restrict__ n_ptr,
+__global__ __launch_bounds__(256) void link_kernel(Geo g, uint32_t a, uint8_t stamp, uint32_t n_boxes,
+                                                   const uint8_t* __restrict__ old_alive,
+                                                   const uint32_t* __restrict__ remap,
                                                    const uint32_t* __restrict__ bcell, const uint4* __restrict__ blen,
                                                    const uint8_t* __restrict__ alive, uint8_t* __restrict__ pred,
                                                    uint32_t* __restrict__ next, uint32_t* __restrict__ block_linked,
@@ -438,10 +434,8 @@ __global__ __launch_bounds__(256) void link_kernel(Geo g, uint32_t a, uint8_t st
                                                    const uint32_t* __restrict__ prefix,
                                                    const uint64_t* __restrict__ cost, const uint16_t* __restrict__ arg,
                                                    const uint32_t* __restrict__ axis_sizes) {
-  if (n_ptr) n_boxes = *n_ptr;
-  if (blockIdx.x * 256u >= n_boxes) return;     // the whole workgroup (its flag is never read)
   const uint32_t i = blockIdx.x * 256u + threadIdx.x;
-  const uint32_t b = i < n_boxes ? (ids ? ids[i] : i) : 0u;
+  const uint32_t b = i < n_boxes ? i : 0u;
   const bool live = i < n_boxes && alive[b];
   uint32_t nxt = 0xFFFFFFFFu;
   if (live) {
@@ -460,8 +454,10 @@ __global__ __launch_bounds__(256) void link_kernel(Geo g, uint32_t a, uint8_t st
       if (same) {
         const unsigned long long m = mask[s >> 6];
         if ((m >> (s & 63u)) & 1ull) {
-          const uint32_t o = prefix[s >> 6] + (uint32_t)__popcll(m & ((1ull << (s & 63u)) - 1ull));
-          if (alive[o]) {
+          uint32_t o = prefix[s >> 6] + (uint32_t)__popcll(m & ((1ull << (s & 63u)) - 1ull));
+          bool there = true;
+          if (remap) { there = old_alive[o]; o = there ? remap[o] : 0u; }
+          if (there && alive[o]) {
             const uint4 L = blen[b], M = blen[o];     // equal on a as well: both 1
             if (L.x == M.x && L.y == M.y && L.z == M.z && L.w == M.w) {
               nxt = o;
@@ -477,18 +473,14 @@ __global__ __launch_bounds__(256) void link_kernel(Geo g, uint32_t a, uint8_t st
   if (threadIdx.x == 0) block_linked[blockIdx.x] = (uint32_t)any;
 }
 
-__global__ __launch_bounds__(256) void absorb_kernel(uint32_t a, uint8_t stamp, const uint32_t* __restrict__ ids,
-                                                     uint32_t n_boxes, const uint32_t* __restrict__ n_ptr,
+__global__ __launch_bounds__(256) void absorb_kernel(uint32_t a, uint8_t stamp, uint32_t n_boxes,
                                                      uint8_t* __restrict__ blen_bytes,
                                                      uint8_t* __restrict__ alive, const uint8_t* __restrict__ pred,
                                                      const uint32_t* __restrict__ next,
                                                      const uint32_t* __restrict__ block_linked) {
-  if (n_ptr) n_boxes = *n_ptr;
-  if (blockIdx.x * 256u >= n_boxes) return;
   if (!block_linked[blockIdx.x]) return;       // no box of this workgroup got a successor: no chain starts here
-  const uint32_t i = blockIdx.x * 256u + threadIdx.x;
-  if (i >= n_boxes) return;
-  const uint32_t b = ids ? ids[i] : i;
+  const uint32_t b = blockIdx.x * 256u + threadIdx.x;
+  if (b >= n_boxes) return;
   uint32_t s = next[b];
   if (s == 0xFFFFFFFFu || !alive[b] || pred[b] == stamp) return;   // only heads of chains of two or more
   uint32_t tot = blen_bytes[(size_t)b * 16 + a];
@@ -528,21 +520,19 @@ void launch_make_boxes(const Geo& g, uint32_t a0, const unsigned long long* mask
   }
 }
 
-void launch_axis_pass(const Geo& g, uint32_t a, uint8_t stamp, bool is_cost, const uint32_t* ids, uint32_t n_boxes,
-                      const uint32_t* n_ptr, const uint32_t* bcell,
-                      void* blen, uint8_t* alive, uint8_t* pred, uint32_t* next, uint32_t* block_linked,
-                      const unsigned long long* mask,
-                      const uint32_t* prefix, const uint64_t* cost, const uint16_t* arg, const uint32_t* axis_sizes,
-                      hipStream_t st) {
+void launch_axis_pass(const Geo& g, uint32_t a, uint8_t stamp, bool is_cost, uint32_t n_boxes, const uint8_t* old_alive,
+                      const uint32_t* remap, const uint32_t* bcell, void* blen, uint8_t* alive, uint8_t* pred, uint32_t* next,
+                      uint32_t* block_linked, const unsigned long long* mask, const uint32_t* prefix, const uint64_t* cost,
+                      const uint16_t* arg, const uint32_t* axis_sizes, hipStream_t st) {
   const uint32_t blocks = (n_boxes + 255) / 256;
   if (is_cost)
-    hipLaunchKernelGGL(link_kernel<true>, dim3(blocks), dim3(256), 0, st, g, a, stamp, ids, n_boxes, n_ptr, bcell,
+    hipLaunchKernelGGL(link_kernel<true>, dim3(blocks), dim3(256), 0, st, g, a, stamp, n_boxes, old_alive, remap, bcell,
                        (const uint4*)blen, alive, pred, next, block_linked, mask, prefix, cost, arg, axis_sizes);
   else
-    hipLaunchKernelGGL(link_kernel<false>, dim3(blocks), dim3(256), 0, st, g, a, stamp, ids, n_boxes, n_ptr, bcell,
+    hipLaunchKernelGGL(link_kernel<false>, dim3(blocks), dim3(256), 0, st, g, a, stamp, n_boxes, old_alive, remap, bcell,
                        (const uint4*)blen, alive, pred, next, block_linked, mask, prefix, cost, arg, axis_sizes);
-  hipLaunchKernelGGL(absorb_kernel, dim3(blocks), dim3(256), 0, st, a, stamp, ids, n_boxes, n_ptr, (uint8_t*)blen, alive, pred,
-                     next, block_linked);
+  hipLaunchKernelGGL(absorb_kernel, dim3(blocks), dim3(256), 0, st, a, stamp, n_boxes, (uint8_t*)blen, alive, pred, next,
+                     block_linked);
 }
 
 // ---------------------------------------------------------------- the last passes, in one
@@ -552,10 +542,14 @@ void launch_axis_pass(const Geo& g, uint32_t a, uint8_t stamp, bool is_cost, con
 // is longer than two.  A wave stands with its lanes on the cells of a word, holds the live boxes
 // that start there in registers, and runs all those passes with lane exchanges: one read and at
 // most one write of every box instead of one per pass.
+constexpr int kTailWords = 4;
+
 template <bool COST>
 __global__ __launch_bounds__(256) void tail_pairs_kernel(TailAxes T, uint32_t n_words, uint32_t wpw,
                                                          const unsigned long long* __restrict__ mask,
-                                                         const uint32_t* __restrict__ prefix, uint4* __restrict__ blen,
+                                                         const uint32_t* __restrict__ prefix,
+                                                         const uint8_t* __restrict__ old_alive,
+                                                         const uint32_t* __restrict__ remap, uint4* __restrict__ blen,
                                                          uint8_t* __restrict__ alive, const uint64_t* __restrict__ cost,
                                                          const uint16_t* __restrict__ arg) {
   const uint32_t lane = threadIdx.x & 63u;
@@ -564,54 +558,80 @@ __global__ __launch_bounds__(256) void tail_pairs_kernel(TailAxes T, uint32_t n_
   const bool mine = lane < wpw && w0 + lane < n_words;
   const unsigned long long mv = mine ? mask[w0 + lane] : 0ull;
   const uint32_t pv = mine ? prefix[w0 + lane] : 0u;
-  for (unsigned long long todo = __ballot(mv != 0); todo; todo &= todo - 1) {
-    const uint32_t t = (uint32_t)__ffsll((long long)todo) - 1u;
-    const unsigned long long m = readlane64(mv, t);
-    const uint32_t pf = (uint32_t)__builtin_amdgcn_readlane((int)pv, (int)t);
-    const uint32_t cell = (w0 + t) * 64u + lane;
-    const uint32_t id = pf + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
-    bool live = ((m >> lane) & 1ull) && alive[id];
-    if (!__any(live)) continue;
-    uint4 L = live ? blen[id] : make_uint4(0, 0, 0, 0);
-    // the two boxes of a pair start in the same shape, so equal normalised costs = equal costs
-    uint64_t v = 0;
-    if (live) v = COST ? cost[cell] : (uint64_t)arg[cell];
-    bool changed = false, died = false;
-    for (uint32_t k = 0; k < T.n; k++) {
-      const uint32_t st = T.stride[k], a = T.axis[k];
-      const int p_live = __shfl_down((int)live, st, 64);
-      const uint32_t p_lo = __shfl_down((uint32_t)v, st, 64), p_hi = __shfl_down((uint32_t)(v >> 32), st, 64);
-      const uint32_t px = __shfl_down(L.x, st, 64), py = __shfl_down(L.y, st, 64);
-      const uint32_t pz = __shfl_down(L.z, st, 64), pw = __shfl_down(L.w, st, 64);
-      const bool low = (lane & st) == 0;             // coordinate 0 on this axis: lane + st is in the same word
-      const bool merge = low && live && p_live && (uint32_t)v == p_lo && (uint32_t)(v >> 32) == p_hi &&
-                         L.x == px && L.y == py && L.z == pz && L.w == pw;
-      if (merge) {
-        const uint32_t one = 1u << ((a & 3u) * 8u);
-        L.x += (a >> 2) == 0 ? one : 0u;
-        L.y += (a >> 2) == 1 ? one : 0u;
-        L.z += (a >> 2) == 2 ? one : 0u;
-        L.w += (a >> 2) == 3 ? one : 0u;
-        changed = true;
-      }
-      const int absorbed = __shfl_up((int)merge, st, 64);
-      if (!low && absorbed) { live = false; died = true; }
+  // kTailWords words at a time, their reads side by side: every read is a trip to memory, and a
+  // word needs four of them in a row (old alive, new index, live, extents and value)
+  unsigned long long todo = __ballot(mv != 0);
+  while (todo) {
+    uint32_t id[kTailWords], cell[kTailWords];
+    bool live[kTailWords];
+#pragma unroll
+    for (int u = 0; u < kTailWords; u++) {
+      const bool any = todo != 0;
+      const uint32_t t = any ? (uint32_t)__ffsll((long long)todo) - 1u : 0u;
+      todo &= todo - 1;                 // 0 stays 0
+      const unsigned long long m = any ? readlane64(mv, t) : 0ull;
+      const uint32_t pf = (uint32_t)__builtin_amdgcn_readlane((int)pv, (int)t);
+      cell[u] = (w0 + t) * 64u + lane;
+      id[u] = pf + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+      live[u] = (m >> lane) & 1ull;
     }
-    if (changed) blen[id] = L;
-    if (died) alive[id] = 0;
+    if (remap) {                       // the mask ranks boxes by the index they had before the compaction
+#pragma unroll
+      for (int u = 0; u < kTailWords; u++) live[u] = live[u] && old_alive[id[u]];
+#pragma unroll
+      for (int u = 0; u < kTailWords; u++) id[u] = live[u] ? remap[id[u]] : 0u;
+    }
+#pragma unroll
+    for (int u = 0; u < kTailWords; u++) live[u] = live[u] && alive[id[u]];
+    uint4 L[kTailWords];
+    uint64_t v[kTailWords];
+#pragma unroll
+    for (int u = 0; u < kTailWords; u++) {
+      L[u] = live[u] ? blen[id[u]] : make_uint4(0, 0, 0, 0);
+      // the two boxes of a pair start in the same shape, so equal normalised costs = equal costs
+      v[u] = 0;
+      if (live[u]) v[u] = COST ? cost[cell[u]] : (uint64_t)arg[cell[u]];
+    }
+#pragma unroll
+    for (int u = 0; u < kTailWords; u++) {
+      if (!__any(live[u])) continue;
+      bool changed = false, died = false;
+      for (uint32_t k = 0; k < T.n; k++) {
+        const uint32_t st = T.stride[k], a = T.axis[k];
+        const int p_live = __shfl_down((int)live[u], st, 64);
+        const uint32_t p_lo = __shfl_down((uint32_t)v[u], st, 64), p_hi = __shfl_down((uint32_t)(v[u] >> 32), st, 64);
+        const uint32_t px = __shfl_down(L[u].x, st, 64), py = __shfl_down(L[u].y, st, 64);
+        const uint32_t pz = __shfl_down(L[u].z, st, 64), pw = __shfl_down(L[u].w, st, 64);
+        const bool low = (lane & st) == 0;             // coordinate 0 on this axis: lane + st is in the same word
+        const bool merge = low && live[u] && p_live && (uint32_t)v[u] == p_lo && (uint32_t)(v[u] >> 32) == p_hi &&
+                           L[u].x == px && L[u].y == py && L[u].z == pz && L[u].w == pw;
+        if (merge) {
+          const uint32_t one = 1u << ((a & 3u) * 8u);
+          L[u].x += (a >> 2) == 0 ? one : 0u;
+          L[u].y += (a >> 2) == 1 ? one : 0u;
+          L[u].z += (a >> 2) == 2 ? one : 0u;
+          L[u].w += (a >> 2) == 3 ? one : 0u;
+          changed = true;
+        }
+        const int absorbed = __shfl_up((int)merge, st, 64);
+        if (!low && absorbed) { live[u] = false; died = true; }
+      }
+      if (changed) blen[id[u]] = L[u];
+      if (died) alive[id[u]] = 0;
+    }
   }
 }
 
 void launch_tail_pairs(const TailAxes& T, bool is_cost, uint32_t n_words, const unsigned long long* mask,
-                       const uint32_t* prefix, void* blen, uint8_t* alive, const uint64_t* cost, const uint16_t* arg,
-                       hipStream_t st) {
+                       const uint32_t* prefix, const uint8_t* old_alive, const uint32_t* remap, void* blen, uint8_t* alive,
+                       const uint64_t* cost, const uint16_t* arg, hipStream_t st) {
   const uint32_t wpw = words_per_wave(n_words), blocks = (n_words + 4 * wpw - 1) / (4 * wpw);
   if (is_cost)
-    hipLaunchKernelGGL(tail_pairs_kernel<true>, dim3(blocks), dim3(256), 0, st, T, n_words, wpw, mask, prefix, (uint4*)blen, alive,
-                       cost, arg);
+    hipLaunchKernelGGL(tail_pairs_kernel<true>, dim3(blocks), dim3(256), 0, st, T, n_words, wpw, mask, prefix, old_alive, remap,
+                       (uint4*)blen, alive, cost, arg);
   else
-    hipLaunchKernelGGL(tail_pairs_kernel<false>, dim3(blocks), dim3(256), 0, st, T, n_words, wpw, mask, prefix, (uint4*)blen, alive,
-                       cost, arg);
+    hipLaunchKernelGGL(tail_pairs_kernel<false>, dim3(blocks), dim3(256), 0, st, T, n_words, wpw, mask, prefix, old_alive, remap,
+                       (uint4*)blen, alive, cost, arg);
 }
 
 // ---------------------------------------------------------------- final lists
@@ -622,19 +642,15 @@ __device__ __forceinline__ uint64_t gcd_u64(uint64_t a, uint64_t b) {
 
 template <bool COST>
 __global__ __launch_bounds__(256) void emit_kernel(Geo g, const DevParams* __restrict__ P,
-                                                   const uint32_t* __restrict__ ids, uint32_t n_boxes,
-                                                   const uint32_t* __restrict__ n_ptr,
+                                                   uint32_t n_boxes,
                                                    const uint32_t* __restrict__ bcell, const uint4* __restrict__ blen,
                                                    const uint8_t* __restrict__ alive, const uint32_t* __restrict__ pos,
                                                    const uint64_t* __restrict__ cost, const uint16_t* __restrict__ arg,
                                                    uint32_t* __restrict__ fcell, uint4* __restrict__ flen,
                                                    uint64_t* __restrict__ fv0, uint64_t* __restrict__ fv1) {
-  if (n_ptr) n_boxes = *n_ptr;
-  const uint32_t i = blockIdx.x * 256u + threadIdx.x;
-  if (i >= n_boxes) return;
-  const uint32_t b = ids ? ids[i] : i;
-  if (!alive[b]) return;
-  const uint32_t o = pos[i], cell = bcell[b];
+  const uint32_t b = blockIdx.x * 256u + threadIdx.x;
+  if (b >= n_boxes || !alive[b]) return;
+  const uint32_t o = pos[b], cell = bcell[b];
   fcell[o] = cell;
   flen[o] = blen[b];
   if (COST) {
@@ -652,17 +668,16 @@ __global__ __launch_bounds__(256) void emit_kernel(Geo g, const DevParams* __res
   }
 }
 
-void launch_emit(const Geo& g, const DevParams* P, bool is_cost, const uint32_t* ids, uint32_t n_boxes,
-                 const uint32_t* n_ptr, const uint32_t* bcell,
+void launch_emit(const Geo& g, const DevParams* P, bool is_cost, uint32_t n_boxes, const uint32_t* bcell,
                  const void* blen,
                  const uint8_t* alive, const uint32_t* pos, const uint64_t* cost, const uint16_t* arg, uint32_t* fcell,
                  void* flen, uint64_t* fv0, uint64_t* fv1, hipStream_t st) {
   const uint32_t blocks = (n_boxes + 255) / 256;
   if (is_cost)
-    hipLaunchKernelGGL(emit_kernel<true>, dim3(blocks), dim3(256), 0, st, g, P, ids, n_boxes, n_ptr, bcell, (const uint4*)blen,
+    hipLaunchKernelGGL(emit_kernel<true>, dim3(blocks), dim3(256), 0, st, g, P, n_boxes, bcell, (const uint4*)blen,
                        alive, pos, cost, arg, fcell, (uint4*)flen, fv0, fv1);
   else
-    hipLaunchKernelGGL(emit_kernel<false>, dim3(blocks), dim3(256), 0, st, g, P, ids, n_boxes, n_ptr, bcell, (const uint4*)blen,
+    hipLaunchKernelGGL(emit_kernel<false>, dim3(blocks), dim3(256), 0, st, g, P, n_boxes, bcell, (const uint4*)blen,
                        alive, pos, cost, arg, fcell, (uint4*)flen, fv0, fv1);
 }
 

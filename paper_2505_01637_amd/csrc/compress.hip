@@ -369,6 +369,8 @@ static uint32_t words_per_wave(uint32_t n_words) { return n_words >= (1u << 21) 
 // on 64 consecutive lines at the same step, so the lanes read consecutive words of the line-major
 // mask (for the run's end), and the boxes they open have consecutive indices: all of a wave's
 // reads and writes are contiguous stretches.
+constexpr int kBoxWords = 4;
+
 __global__ __launch_bounds__(256) void make_boxes_wave_kernel(Geo g, uint32_t a0, uint32_t n_words, uint32_t wpw,
                                                               const unsigned long long* __restrict__ mask,
                                                               const uint32_t* __restrict__ prefix,
@@ -383,31 +385,49 @@ __global__ __launch_bounds__(256) void make_boxes_wave_kernel(Geo g, uint32_t a0
   const bool mine = lane < wpw && w0 + lane < n_words;
   const unsigned long long mv = mine ? mask[w0 + lane] : 0ull;
   const uint32_t pv = mine ? prefix[w0 + lane] : 0u;
-  for (unsigned long long todo = __ballot(mv != 0); todo; todo &= todo - 1) {
-    const uint32_t t = (uint32_t)__ffsll((long long)todo) - 1u;
-    const unsigned long long m = readlane64(mv, t);
-    const uint32_t pf = (uint32_t)__builtin_amdgcn_readlane((int)pv, (int)t);
-    const uint32_t cell0 = (w0 + t) * 64u;                 // the word's first cell; all 64 share the step j
-    const uint32_t hi = cell0 / se, rem = cell0 - hi * se, j = rem / s0, lo = rem - j * s0;
-    if ((m >> lane) & 1ull) {
-      const uint32_t q = hi * s0 + lo + lane;
-      const uint32_t id = pf + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
-      uint32_t end = e0;                                   // the run ends at the line's next flagged cell
-      for (uint32_t w = j >> 6; w * 64u < e0; w++) {
-        unsigned long long lm = line[(size_t)w * n_lines + q];
-        if (w == (j >> 6)) lm &= ~((2ull << (j & 63u)) - 1ull);
-        if (lm) { end = w * 64u + (uint32_t)__ffsll((long long)lm) - 1u; break; }
+  // kBoxWords words at a time, so that their reads of the line-major mask are in flight together
+  unsigned long long todo = __ballot(mv != 0);
+  while (todo) {
+    uint32_t id[kBoxWords], cell[kBoxWords], j[kBoxWords], q[kBoxWords];
+    bool head[kBoxWords];
+    unsigned long long lm[kBoxWords];
+#pragma unroll
+    for (int u = 0; u < kBoxWords; u++) {
+      const bool any = todo != 0;
+      const uint32_t t = any ? (uint32_t)__ffsll((long long)todo) - 1u : 0u;
+      todo &= todo - 1;                 // 0 stays 0
+      const unsigned long long m = any ? readlane64(mv, t) : 0ull;
+      const uint32_t pf = (uint32_t)__builtin_amdgcn_readlane((int)pv, (int)t);
+      const uint32_t cell0 = (w0 + t) * 64u;               // the word's first cell; all 64 share the step j
+      const uint32_t hi = cell0 / se, rem = cell0 - hi * se;
+      j[u] = rem / s0;
+      q[u] = hi * s0 + (rem - j[u] * s0) + lane;
+      cell[u] = cell0 + lane;
+      id[u] = pf + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+      head[u] = (m >> lane) & 1ull;
+      lm[u] = head[u] ? line[(size_t)(j[u] >> 6) * n_lines + q[u]] : 0ull;
+    }
+#pragma unroll
+    for (int u = 0; u < kBoxWords; u++) {
+      if (head[u]) {
+        uint32_t end = e0;                                 // the run ends at the line's next flagged cell
+        unsigned long long w = lm[u] & ~((2ull << (j[u] & 63u)) - 1ull);
+        for (uint32_t k = j[u] >> 6;;) {
+          if (w) { end = k * 64u + (uint32_t)__ffsll((long long)w) - 1u; break; }
+          if (++k * 64u >= e0) break;
+          w = line[(size_t)k * n_lines + q[u]];
+        }
+        uint32_t L[4] = {0x01010101u, 0x01010101u, 0x01010101u, 0x01010101u};
+        const uint32_t lw = (0x01010101u & ~(0xFFu << shift)) | ((end - j[u]) << shift);
+        L[0] = (a0 >> 2) == 0 ? lw : L[0];
+        L[1] = (a0 >> 2) == 1 ? lw : L[1];
+        L[2] = (a0 >> 2) == 2 ? lw : L[2];
+        L[3] = (a0 >> 2) == 3 ? lw : L[3];
+        bcell[id[u]] = cell[u];
+        blen[id[u]] = make_uint4(L[0], L[1], L[2], L[3]);
+        alive[id[u]] = 1;
+        pred[id[u]] = 0;
       }
-      uint32_t L[4] = {0x01010101u, 0x01010101u, 0x01010101u, 0x01010101u};
-      const uint32_t lw = (0x01010101u & ~(0xFFu << shift)) | ((end - j) << shift);
-      L[0] = (a0 >> 2) == 0 ? lw : L[0];
-      L[1] = (a0 >> 2) == 1 ? lw : L[1];
-      L[2] = (a0 >> 2) == 2 ? lw : L[2];
-      L[3] = (a0 >> 2) == 3 ? lw : L[3];
-      bcell[id] = cell0 + lane;
-      blen[id] = make_uint4(L[0], L[1], L[2], L[3]);
-      alive[id] = 1;
-      pred[id] = 0;
     }
   }
 }

@@ -6,6 +6,7 @@
 #include <algorithm>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <memory>
 #include <mutex>
@@ -572,17 +573,22 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
   size_t ev_used = 0;
   hipStream_t s2 = aux->stream;
   HIP_TRY(hipEventRecord(ev[0], st));
-  // plan first (latency-bound: it crawls beside a kernel that saturates HBM), then the pre-fill,
-  // during which the host reads the list sizes back
+  // plan (with the pre-fill; a separate streaming kernel for tables it cannot serve), then the
+  // host reads the list sizes back
   launch_zero_words((unsigned long long*)d_fitmap, f.n_words + 2, st);
+  // the plan kernel also streams (INF, NONE) over the tables when a shape's entries are whole 16-byte pieces
+  const bool fused_prefill = P.G % 8 == 0;
   launch_plan(d_P, c.n_shapes, P.npass, P.G, d_level_shapes, d_level_off, n_lev, d_shape_class, d_list_whole, d_list_slice,
-              d_list_wide, d_list_cnt, d_fitmap, d_ctr, st);
+              d_list_wide, d_list_cnt, d_fitmap, d_ctr, fused_prefill ? tab->d_cost : nullptr,
+              fused_prefill ? tab->d_arg : nullptr, st);
   std::vector<uint32_t> cnt(4 * (size_t)n_lev);
   HIP_TRY(hipMemcpyAsync(cnt.data(), d_list_cnt, cnt.size() * 4, hipMemcpyDeviceToHost, st));
   HIP_TRY(hipEventRecord(aux->events[ev_used], st));
   hipEvent_t counts_ready = aux->events[ev_used++];
-  launch_fill_ones(tab->d_cost, c.n_specs * 8, st);
-  launch_fill_ones(tab->d_arg, c.n_specs * 2, st);
+  if (!fused_prefill) {
+    launch_fill_ones(tab->d_cost, c.n_specs * 8, st);
+    launch_fill_ones(tab->d_arg, c.n_specs * 2, st);
+  }
   HIP_TRY(hipEventSynchronize(counts_ready));
   for (uint32_t l = 0; l < n_lev; l++) {
     const uint32_t first = c.level_off[l];

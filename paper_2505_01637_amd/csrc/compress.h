@@ -16,7 +16,7 @@ struct Geo {
 void launch_plan(const DevParams* P, uint32_t n_shapes, uint32_t npass, uint32_t G, const uint32_t* level_shapes,
                  const uint32_t* level_off, uint32_t n_levels, uint32_t* shape_class, uint32_t* list_whole,
                  uint32_t* list_slice, uint32_t* list_wide, uint32_t* list_cnt, uint32_t* fitmap, Counters* ctr,
-                 hipStream_t stream);
+                 void* prefill_cost, void* prefill_arg, hipStream_t stream);
 void launch_fill_level(const DevParams* P, uint32_t npass, uint32_t G, uint32_t max_task, const uint32_t* list_whole,
                        uint32_t n_stretch, uint32_t n_small, uint32_t n_bigwhole, const uint32_t* list_slice,
                        uint32_t n_slice, const uint32_t* list_wide, uint32_t n_wide, uint64_t* cost, uint16_t* arg,

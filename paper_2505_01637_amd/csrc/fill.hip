@@ -13,8 +13,8 @@
 //      the admissible ones are compacted, ordered by rank (sum of the operand
 //      levels), into a task list in LDS (most entries do not fit);
 //   2. (before the first level, once per table) the whole table is set to
-//      (INF, NONE) by a plain streaming kernel, so this kernel writes the
-//      admissible entries only;
+//      (INF, NONE) by the plan kernel's waves (or a plain streaming kernel), so
+//      this kernel writes the admissible entries only;
 //   3. one lane per task evaluates the tile and bufferize rewrites, whose
 //      sub-Specs belong to other shapes or tables and are final: a tile
 //      sub-Spec sits at the same offset of a smaller shape's group, so
@@ -676,7 +676,8 @@ constexpr uint32_t kPlanShapes = 8;
 __global__ __launch_bounds__(256) void plan_kernel(const DevParams* __restrict__ P, uint32_t n_shapes,
                                                    uint32_t cap_whole, uint32_t cap_slice, uint32_t cap_wave,
                                                    uint32_t* __restrict__ shape_class, uint32_t* __restrict__ fitmap,
-                                                   Counters* __restrict__ ctr) {
+                                                   Counters* __restrict__ ctr, uint4* __restrict__ cost16,
+                                                   uint4* __restrict__ arg16) {
   __shared__ uint32_t fit_all[4][16];
   const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
   uint32_t* fit = fit_all[wave];
@@ -691,6 +692,15 @@ __global__ __launch_bounds__(256) void plan_kernel(const DevParams* __restrict__
   unsigned long long n_adm = 0;
   const uint32_t first_shape = (blockIdx.x * 4 + wave) * kPlanShapes;
   for (uint32_t shape = first_shape; shape < first_shape + kPlanShapes && shape < n_shapes; shape++) {
+    if (cost16) {
+      // (INF, NONE) = all-ones over the shape's whole group: the level kernels overwrite what fits
+      const uint4 ones = make_uint4(~0u, ~0u, ~0u, ~0u);
+      const uint32_t nc = P->G >> 1, na = P->G >> 3;       // 16-byte pieces (G is a multiple of 8)
+      uint4* c16 = cost16 + (size_t)shape * nc;
+      uint4* a16 = arg16 + (size_t)shape * na;
+      for (uint32_t i = lane; i < nc; i += 64) c16[i] = ones;
+      for (uint32_t i = lane; i < na; i += 64) a16[i] = ones;
+    }
     Shape S;
     load_shape(P, shape, S);
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -864,10 +874,11 @@ uint32_t fill_wave_cap(uint32_t G) { return G < kSmallCap ? G : kSmallCap; }
 void launch_plan(const DevParams* P, uint32_t n_shapes, uint32_t npass, uint32_t G, const uint32_t* level_shapes,
                  const uint32_t* level_off, uint32_t n_levels, uint32_t* shape_class, uint32_t* list_whole,
                  uint32_t* list_slice, uint32_t* list_wide, uint32_t* list_cnt, uint32_t* fitmap, Counters* ctr,
-                 hipStream_t stream) {
+                 void* prefill_cost, void* prefill_arg, hipStream_t stream) {
   const uint32_t cap = fill_wave_cap(G);
   hipLaunchKernelGGL(plan_kernel, dim3((n_shapes + 4 * kPlanShapes - 1) / (4 * kPlanShapes)), dim3(256), 0, stream, P,
-                     n_shapes, cap, cap, kWaveCap < cap ? kWaveCap : cap, shape_class, fitmap, ctr);
+                     n_shapes, cap, cap, kWaveCap < cap ? kWaveCap : cap, shape_class, fitmap, ctr, (uint4*)prefill_cost,
+                     (uint4*)prefill_arg);
   hipLaunchKernelGGL(sort_work_kernel, dim3(n_levels), dim3(256), 0, stream, level_shapes, level_off, n_levels, npass,
                      shape_class, list_whole, list_slice, list_wide, list_cnt);
 }

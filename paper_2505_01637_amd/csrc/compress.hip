@@ -9,18 +9,21 @@
 // chained when one starts where the previous one ends.
 //
 // GPU formulation.
-//   pass 0  (dense, first axis a0): one thread walks a line of cells along a0
-//           and flags the cell where the value changes (cells whose operands
-//           do not fit their levels hold (INF, NONE) by construction and are
-//           not read: a bit map from the fill says which cells those are); consecutive lanes hold
-//           consecutive cells, so the flags of 64 cells are one ballot = one
-//           word of a bit mask in table order.  A prefix sum of the popcounts
-//           gives every run (= box) its index in table order.
+//   pass 0  (dense, first axis a0): lanes walk lines of cells along a0 and flag
+//           the cells where the value changes (cells whose operands do not fit
+//           their levels hold (INF, NONE) by construction and are not read: a
+//           bit map from the fill says which cells those are).  Consecutive
+//           lanes hold consecutive cells, so the flags of 64 cells are one
+//           ballot = one word of a bit mask in table order; the same flags are
+//           also kept line-major.  A prefix sum of the popcounts gives every
+//           run (= box) its index in table order.
 //   pass a  (on boxes): a box looks at the cell just past its end on axis a.
 //           If that cell is the low corner of a live box of the same value and
 //           the same extents on all other axes, the two are linked; heads of
 //           chains then absorb their chain.  The low corner of a box is found
-//           in O(1) through the bit mask and the prefix sums.
+//           in O(1) through the bit mask and the prefix sums.  After the first
+//           of these passes the live boxes move to dense arrays; the trailing
+//           passes over the innermost bit axes are one kernel.
 //   final   live boxes are compacted in index order = sorted by low corner.
 #include <hip/hip_runtime.h>
 #include "dev_params.h"
@@ -39,8 +42,8 @@ __device__ __forceinline__ bool norm_equal(uint64_t c1, uint32_t s1, uint64_t c2
 }
 
 // ---------------------------------------------------------------- pass 0
-// line q: all cells sharing every coordinate but a0.
-template <bool BALLOT>
+// line q: all cells sharing every coordinate but a0.  General form (any stride): one thread walks
+// a line and sets the flags of its cells in the zeroed table-order masks with atomics.
 __global__ __launch_bounds__(256) void head_flags_kernel(Geo g, uint32_t a0,
                                                          const uint64_t* __restrict__ cost,
                                                          const uint16_t* __restrict__ arg,
@@ -51,47 +54,31 @@ __global__ __launch_bounds__(256) void head_flags_kernel(Geo g, uint32_t a0,
                                                          unsigned long long* __restrict__ lineD,
                                                          unsigned long long* __restrict__ lineC) {
   const uint32_t s0 = g.stride[a0], e0 = g.ext[a0];
-  const uint32_t n_lines = g.n / e0, lw = (e0 + 63) / 64;      // words per line of the line-major masks
+  const uint32_t n_lines = g.n / e0;
   const uint32_t q = blockIdx.x * 256u + threadIdx.x;
-  const bool active = q < n_lines;
-  uint32_t base = 0;
-  if (active) { uint32_t hi = q / s0; base = hi * s0 * e0 + (q - hi * s0); }
+  if (q >= n_lines) return;
+  const uint32_t hi = q / s0, base = hi * s0 * e0 + (q - hi * s0);
   uint64_t pc = 0; uint32_t pa = 0, ps = 1;
   unsigned long long wd = 0, wc = 0;
   for (uint32_t j = 0; j < e0; j++) {
     const uint32_t cell = base + j * s0;
-    bool hd = false, hc = false;
-    // 64 consecutive cells none of which fits (the common case): nothing to read, the values are known
-    const bool none_fit = BALLOT && reinterpret_cast<const unsigned long long*>(fitmap)[__builtin_amdgcn_readfirstlane(cell) >> 6] == 0;
-    if (none_fit) {
-      hd = j == 0 || pa != kNone;
-      hc = j == 0 || pc != kInf;
-      pc = kInf; pa = kNone; ps = axis_sizes ? axis_sizes[j] : 1u;
-    } else if (active) {
-      const bool fits = (fitmap[cell >> 5] >> (cell & 31u)) & 1u;
-      const uint64_t c = fits ? cost[cell] : kInf;
-      const uint32_t a = fits ? arg[cell] : kNone;
-      const uint32_t sz = axis_sizes ? axis_sizes[j] : 1u;
-      hd = j == 0 || a != pa;
-      hc = j == 0 || !norm_equal(c, sz, pc, ps);
-      pc = c; pa = a; ps = sz;
-    }
-    if (BALLOT) {
-      const unsigned long long bd = __ballot(hd), bc = __ballot(hc);
-      if ((threadIdx.x & 63u) == 0 && active) { maskD[cell >> 6] = bd; maskC[cell >> 6] = bc; }
-    } else {
-      if (hd) atomicOr(&maskD[cell >> 6], 1ull << (cell & 63u));
-      if (hc) atomicOr(&maskC[cell >> 6], 1ull << (cell & 63u));
-    }
+    const bool fits = (fitmap[cell >> 5] >> (cell & 31u)) & 1u;     // cells that cannot fit hold (INF, NONE): not read
+    const uint64_t c = fits ? cost[cell] : kInf;
+    const uint32_t a = fits ? arg[cell] : kNone;
+    const uint32_t sz = axis_sizes ? axis_sizes[j] : 1u;
+    const bool hd = j == 0 || a != pa;
+    const bool hc = j == 0 || !norm_equal(c, sz, pc, ps);
+    pc = c; pa = a; ps = sz;
+    if (hd) atomicOr(&maskD[cell >> 6], 1ull << (cell & 63u));
+    if (hc) atomicOr(&maskC[cell >> 6], 1ull << (cell & 63u));
     wd |= (unsigned long long)hd << (j & 63u);
     wc |= (unsigned long long)hc << (j & 63u);
-    if (active && ((j & 63u) == 63u || j + 1 == e0)) {
+    if ((j & 63u) == 63u || j + 1 == e0) {
       lineD[(size_t)(j >> 6) * n_lines + q] = wd;
       lineC[(size_t)(j >> 6) * n_lines + q] = wc;
       wd = wc = 0;
     }
   }
-  (void)lw;
 }
 
 // The same for lines whose stride is a multiple of 64 cells (every table with at least 64
@@ -521,7 +508,7 @@ void launch_head_flags(const Geo& g, uint32_t a0, const uint64_t* cost, const ui
     hipLaunchKernelGGL(head_flags_wave_kernel, dim3((blocks + 4 * kHeadSpread - 1) / (4 * kHeadSpread) * (4 * kHeadSpread)), dim3(256), 0, st, g, a0, cost, arg,
                        (const unsigned long long*)fitmap, axis_sizes, maskD, maskC, lineD, lineC);
   else
-    hipLaunchKernelGGL(head_flags_kernel<false>, dim3(blocks), dim3(256), 0, st, g, a0, cost, arg, fitmap, axis_sizes, maskD,
+    hipLaunchKernelGGL(head_flags_kernel, dim3(blocks), dim3(256), 0, st, g, a0, cost, arg, fitmap, axis_sizes, maskD,
                        maskC, lineD, lineC);
 }
 

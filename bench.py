@@ -133,7 +133,7 @@ def main():
                        "launches": stats[l]["n_levels_run"],
                        "decision_boxes": stats[l]["n_decision_boxes"], "cost_boxes": stats[l]["n_cost_boxes"],
                        "scratch_used": stats[l]["scratch_used"]} for l in sizes},
-        "roofline": {"bound": "hbm", "kernel": "fill of table %s: plan_kernel, sort_work_kernel, fill_ones_kernel, fill_kernel / fill_big_kernel per dependency level" % big,
+        "roofline": {"bound": "hbm", "kernel": "fill of table %s: plan_kernel (which also streams the (INF, NONE) pre-fill), sort_work_kernel, fill_kernel / fill_big_kernel per dependency level" % big,
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": measured_traffic(args.config, big, n_launch),
                      "launches_per_step": n_launch, "avg_launch_ms": avg_launch_ms,

@@ -188,6 +188,28 @@ typedef enum { MRL_BOXES_DECISION = 0, MRL_BOXES_COST = 1 } mrl_box_list;
 int32_t mrl_emit_compressed(const mrl_table* tab, uint32_t which,
                             mrl_box* out, size_t cap, size_t* n_out);
 
+/* ---------------------------------------------------------------------------
+ * Schedule of a goal Spec (Section 4: the search returns, for every Spec, the
+ * rewrite of the cheapest implementation; following these rewrites from the
+ * goal down to microkernels gives the program of Section 2, Figure 1).
+ * Nodes in pre-order: a node is followed by the subtrees of its children
+ * (0 for a microkernel, 1 for a tile or a Move: the loop body / the Spec on
+ * the moved operand, 2 for bufferize: the Matmul, then the bias-add + ReLU).
+ * table: 0 = the table the walk started in, 1 + i = its dep i (the handles
+ * given to mrl_solve as deps must still be alive).  cost = the table's entry
+ * of the node's Spec = cost of the whole subtree under Section 3's equation.
+ * out: host array of cap nodes, or NULL to get the count only in *n_out;
+ * MRL_E_INVAL if the goal has no implementation (cost MRL_INF). */
+typedef struct {
+  uint32_t table;
+  uint16_t rewrite;
+  uint16_t n_children;
+  uint64_t cost;
+  mrl_coord spec;
+} mrl_schedule_node;
+int32_t mrl_schedule(const mrl_table* tab, const mrl_coord* goal,
+                     mrl_schedule_node* out, size_t cap, size_t* n_out);
+
 /* Test support: copy the dense tables to host arrays of n_specs entries each
  * (either pointer may be NULL). */
 int32_t mrl_copy_dense(const mrl_table* tab, uint64_t* cost_host, uint16_t* argmin_host);

@@ -20,7 +20,7 @@ OK, E_INVAL, E_NOMEM, E_HIP, E_RANGE, E_BUFSZ, E_OVERFLOW = 0, -1, -2, -3, -4, -
 
 EXPORTS = ["mrl_target_create", "mrl_target_destroy", "mrl_geometry", "mrl_table_bytes", "mrl_solve",
            "mrl_table_destroy", "mrl_query", "mrl_rewrite_decode", "mrl_coord_of_spec",
-           "mrl_emit_compressed", "mrl_copy_dense", "mrl_last_error"]
+           "mrl_emit_compressed", "mrl_schedule", "mrl_copy_dense", "mrl_last_error"]
 
 
 class MorelloError(RuntimeError):
@@ -66,6 +66,11 @@ class Stats(C.Structure):
 
 class _Coord(C.Structure):
     _fields_ = [("x", C.c_uint32 * MAX_DIMS)]
+
+
+class _ScheduleNode(C.Structure):
+    _fields_ = [("table", C.c_uint32), ("rewrite", C.c_uint16), ("n_children", C.c_uint16),
+                ("cost", C.c_uint64), ("spec", _Coord)]
 
 
 class Rewrite(C.Structure):
@@ -168,9 +173,10 @@ def table_bytes(target, lattice):
 class Table:
     """A solved table.  Holds the torch tensors that back it."""
 
-    def __init__(self, handle, target, lattice, extents, tensors, stats):
+    def __init__(self, handle, target, lattice, extents, tensors, stats, deps=()):
         self._h, self.target, self.lattice = handle, target, lattice
         self.extents, self._tensors, self.stats = extents, tensors, stats
+        self._deps = tuple(deps)        # keeps the tables this one was solved against alive
         self.n_specs = int(np.prod(extents, dtype=np.uint64))
 
     def close(self):
@@ -196,6 +202,20 @@ class Table:
                                cost.ctypes.data_as(C.POINTER(C.c_uint64)),
                                rw.ctypes.data_as(C.POINTER(C.c_uint16))))
         return cost, rw
+
+    def schedule(self, coord):
+        """Program of the Spec at `coord`: [(table, coord, rewrite id, cost, children)] in
+        pre-order; table 0 = this table, 1 + i = the i-th table it was solved against."""
+        goal = _Coord()
+        for a, v in enumerate(coord):
+            goal.x[a] = int(v)
+        n = C.c_size_t()
+        _check(lib().mrl_schedule(self._h, C.byref(goal), None, C.c_size_t(0), C.byref(n)))
+        nodes = (_ScheduleNode * max(1, n.value))()
+        _check(lib().mrl_schedule(self._h, C.byref(goal), nodes, C.c_size_t(n.value), C.byref(n)))
+        dims = [len(self.extents)] + [len(d.extents) for d in self._deps]
+        return [(nd.table, tuple(nd.spec.x[:dims[nd.table]]), nd.rewrite, nd.cost, nd.n_children)
+                for nd in nodes[:n.value]]
 
     def rewrite_decode(self, rid):
         r = Rewrite()
@@ -258,7 +278,7 @@ def solve(target, lattice, deps=(), scratch_bytes=None, stream=None, buffers=Non
                          C.c_void_p(d_scr.data_ptr()), C.c_size_t(d_scr.numel()),
                          C.c_void_p(st.cuda_stream), C.byref(h), C.byref(stats))
     _check(rc)
-    return Table(h, target, lattice, ext, buffers, stats)
+    return Table(h, target, lattice, ext, buffers, stats, deps)
 
 
 _side_streams = {}

@@ -448,6 +448,7 @@ struct mrl_table {
   uint64_t* d_cost;
   uint16_t* d_arg;
   hipStream_t stream;
+  const mrl_table* deps[2] = {nullptr, nullptr};      // a FUSED table: the tables it was solved against
   // final lists inside scratch: [0] decisions, [1] costs
   size_t list_off[2];
   uint64_t list_n[2];
@@ -525,6 +526,7 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
     if (E.sizes[1] != c.sizes[1] || E.sizes[3] != c.sizes[3]) return fail(MRL_E_INVAL, "BIAS_ADD_RELU dep has other size lists");
     if (M.P.ndt || M.P.base_bf16[0] || M.P.base_bf16[1] || M.P.base_bf16[2]) return fail(MRL_E_INVAL, "MATMUL_ACCUM dep must be f32");
     P.costM = deps[0]->d_cost; P.costE = deps[1]->d_cost;
+    tab->deps[0] = deps[0]; tab->deps[1] = deps[1];
     P.GM = M.P.G; P.VM = M.P.V; P.GE = E.P.G; P.VE = E.P.V; P.nszE_n = E.P.nsz[3];
     for (int i = 0; i < 3; i++) { P.layM[i] = M.P.lay_bit[i]; P.layE[i] = E.P.lay_bit[i]; }
   } else if (n_deps != 0) {
@@ -839,6 +841,74 @@ int32_t mrl_coord_of_spec(const mrl_table* tab, const uint32_t shape[4], const u
     if (c.lay_axis[i] >= 0) { if (!layouts || layouts[i] > 1) return fail(MRL_E_RANGE, "layout of operand %u", i); out->x[c.lay_axis[i]] = layouts[i]; }
     if (c.dt_axis[i] >= 0) { if (!dtypes || dtypes[i] > 1) return fail(MRL_E_RANGE, "dtype of operand %u", i); out->x[c.dt_axis[i]] = dtypes[i]; }
   }
+  return MRL_OK;
+}
+
+int32_t mrl_schedule(const mrl_table* tab, const mrl_coord* goal, mrl_schedule_node* out, size_t cap, size_t* n_out) {
+  if (!tab || !goal) return fail(MRL_E_INVAL, "NULL argument");
+  struct Item { const mrl_table* t; uint32_t which; mrl_coord x; };
+  std::vector<Item> stack;
+  stack.push_back({tab, 0u, *goal});
+  size_t n = 0;
+  while (!stack.empty()) {
+    const Item it = stack.back();
+    stack.pop_back();
+    const Compiled& c = *it.t->cp;
+    const DevParams& P = it.t->P;
+    uint64_t cost;
+    uint16_t rw;
+    int32_t rc = mrl_query(it.t, &it.x, 1, &cost, &rw);
+    if (rc) return rc;
+    if (cost == kInf) {
+      if (n == 0) return fail(MRL_E_INVAL, "the goal Spec has no implementation");
+      return fail(MRL_E_HIP, "internal error: a rewrite of a finite Spec leads to a Spec without implementation");
+    }
+    mrl_rewrite r;
+    rc = mrl_rewrite_decode(it.t, rw, &r);
+    if (rc) return rc;
+    mrl_schedule_node node;
+    memset(&node, 0, sizeof node);
+    node.table = it.which; node.rewrite = rw; node.cost = cost; node.spec = it.x;
+    if (r.cls == 1) {                       // Move: the operand one or more levels down, perhaps transposed / converted
+      const uint32_t op = r.operand_or_dim;
+      Item ch = it;
+      ch.x.x[4 + op] = r.dst_level;
+      if (r.transposed) { if (c.lay_axis[op] < 0) return fail(MRL_E_HIP, "internal error: transposing Move without a layout coordinate"); ch.x.x[c.lay_axis[op]] ^= 1u; }
+      if (r.convert) { if (c.dt_axis[op] < 0) return fail(MRL_E_HIP, "internal error: converting Move without a dtype coordinate"); ch.x.x[c.dt_axis[op]] = 0; }
+      stack.push_back(ch);
+      node.n_children = 1;
+    } else if (r.cls == 2) {                // tile: the loop body is the Spec with the smaller size
+      const uint32_t d = r.operand_or_dim, j = (rw - P.tile_base) % P.maxs;
+      Item ch = it;
+      ch.x.x[d] = j;
+      stack.push_back(ch);
+      node.n_children = 1;
+    } else if (r.cls == 3) {                // bufferize: Matmul into the intermediate, then bias-add + ReLU out of it
+      if (it.which != 0 || !it.t->deps[0] || !it.t->deps[1]) return fail(MRL_E_HIP, "internal error: bufferize outside a FUSED table");
+      const uint32_t m = c.sizes[1][it.x.x[1]], k = c.sizes[2][it.x.x[2]], nn = c.sizes[3][it.x.x[3]];
+      const uint8_t l_lhs = (uint8_t)it.x.x[4], l_rhs = (uint8_t)it.x.x[5], l_bias = (uint8_t)it.x.x[6], l_out = (uint8_t)it.x.x[7];
+      const uint8_t l_mid = (uint8_t)it.x.x[8];
+      const uint8_t y_lhs = c.lay_axis[0] >= 0 ? (uint8_t)it.x.x[c.lay_axis[0]] : 0, y_rhs = c.lay_axis[1] >= 0 ? (uint8_t)it.x.x[c.lay_axis[1]] : 0;
+      const uint8_t y_out = c.lay_axis[3] >= 0 ? (uint8_t)it.x.x[c.lay_axis[3]] : 0;
+      const uint32_t shape_m[4] = {1, m, k, nn}, shape_e[4] = {1, m, 1, nn};
+      const uint8_t lv_m[5] = {l_lhs, l_rhs, l_mid, 0, 0}, ly_m[5] = {y_lhs, y_rhs, 0, 0, 0};
+      const uint8_t lv_e[5] = {l_mid, l_bias, l_out, 0, 0}, ly_e[5] = {0, 0, y_out, 0, 0};
+      const uint8_t zeros[5] = {0, 0, 0, 0, 0};
+      Item cm{it.t->deps[0], 1u, {}}, ce{it.t->deps[1], 2u, {}};
+      rc = mrl_coord_of_spec(cm.t, shape_m, lv_m, ly_m, zeros, &cm.x);
+      if (rc) return rc;
+      rc = mrl_coord_of_spec(ce.t, shape_e, lv_e, ly_e, zeros, &ce.x);
+      if (rc) return rc;
+      stack.push_back(ce);                  // popped after the Matmul's whole subtree
+      stack.push_back(cm);
+      node.n_children = 2;
+    }
+    if (out && n < cap) out[n] = node;
+    n++;
+    if (n > (1u << 20)) return fail(MRL_E_HIP, "internal error: schedule does not end");
+  }
+  if (n_out) *n_out = n;
+  if (out && cap < n) return fail(MRL_E_BUFSZ, "schedule buffer holds %zu nodes, %zu needed", cap, n);
   return MRL_OK;
 }
 

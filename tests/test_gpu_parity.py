@@ -162,3 +162,33 @@ def test_deterministic():
         outs.append([(got[l].dense(), got[l].boxes(0).tobytes(), got[l].boxes(1).tobytes()) for l in "MEF"])
     for a, b in zip(*outs):
         assert np.array_equal(a[0][0], b[0][0]) and np.array_equal(a[0][1], b[0][1]) and a[1:] == b[1:]
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("number,max_size,label", [(1, None, "M"), (3, 64, "M"), (4, 8, "M"), (5, 8, "F"), (5, 8, "E")])
+def test_schedule_parity(number, max_size, label):
+    """mrl_schedule walks the same programs as the oracle's extraction: same Specs, rewrites and
+    costs, node by node in pre-order; a goal without implementation is an error."""
+    from oracle import schedule as S
+    B = _binding()
+    cfg = W.config(number, max_size=max_size)
+    target, got, want = compare_config(cfg, boxes=False)
+    tab = got[label]
+    deps = next(d for lb, _, d in cfg["lattices"] if lb == label)
+    names = [label] + list(deps)
+    cost = want[label]["cost"]
+    ext = [int(e) for e in want[label]["extents"]]
+    rng = np.random.default_rng(number)
+    finite = np.flatnonzero(cost != np.uint64(O.INF))
+    n_nodes = 0
+    for p in rng.choice(finite, size=min(60, len(finite)), replace=False):
+        goal = tuple(int(v) for v in np.unravel_index(int(p), ext))
+        ref = S.preorder(S.extract(cfg["target"], cfg["lattices"], want, label, goal))
+        mine = [(names[t], x, rw, c, k) for t, x, rw, c, k in tab.schedule(goal)]
+        assert mine == ref
+        n_nodes += len(mine)
+    assert n_nodes > 100
+    bad = int(np.flatnonzero(cost == np.uint64(O.INF))[0])
+    with pytest.raises(B.MorelloError) as e:
+        tab.schedule(tuple(int(v) for v in np.unravel_index(bad, ext)))
+    assert e.value.code == B.E_INVAL

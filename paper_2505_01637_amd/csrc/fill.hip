@@ -304,26 +304,32 @@ __device__ __forceinline__ void build_move_costs(const DevParams* __restrict__ P
   }
 }
 
-// Tile candidates [0, n_here) staged in LDS, for task q: the sub-Spec sits at the same offset
-// `off` inside a smaller shape's group.  trips * sub + s in 96 bits; reaching 2^62 = overflow.
+// Tile candidates first, first + step, ... < n_here of the ones staged in LDS, for one task: the
+// sub-Spec sits at the same offset `off` inside a smaller shape's group.  trips * sub + s in 96
+// bits; reaching 2^62 = overflow.
 __device__ __forceinline__ void task_tiles(const DevParams* __restrict__ P, const UnitLds& L, uint32_t n_here,
-                                           uint32_t off, const uint64_t* __restrict__ cost, Eval& e) {
+                                           uint32_t first, uint32_t step, uint32_t off,
+                                           const uint64_t* __restrict__ cost, Eval& e) {
   const uint64_t s = P->s;
-  for (uint32_t t0 = 0; t0 < n_here; t0 += kBatch) {
+  for (uint32_t t0 = first; t0 < n_here; t0 += kBatch * step) {
     uint64_t sub[kBatch];
 #pragma unroll
-    for (int u = 0; u < kBatch; u++) sub[u] = cost[L.tl_base[t0 + u < n_here ? t0 + u : n_here - 1] + off];
+    for (int u = 0; u < kBatch; u++) {
+      const uint32_t t = t0 + u * step;
+      sub[u] = cost[L.tl_base[t < n_here ? t : n_here - 1] + off];
+    }
 #pragma unroll
     for (int u = 0; u < kBatch; u++) {
-      if (t0 + u < n_here) {
+      const uint32_t t = t0 + u * step;
+      if (t < n_here) {
         const bool fin = sub[u] != kInf;
-        const uint32_t a = L.tl_trips[t0 + u];
+        const uint32_t a = L.tl_trips[t];
         const uint64_t lo = (uint64_t)a * (uint32_t)sub[u];
         const uint64_t hi = (uint64_t)a * (uint32_t)(sub[u] >> 32) + (lo >> 32);   // bits 32.. of the product
         const uint64_t c = ((hi << 32) | (uint32_t)lo) + s;
         const bool over = fin & (((hi >> 30) != 0) | (c >= kLimit));
         e.ovf |= over ? 1u : 0u;
-        consider(e, c, L.tl_id[t0 + u], fin & !over);
+        consider(e, c, L.tl_id[t], fin & !over);
       }
     }
   }
@@ -579,21 +585,45 @@ __device__ __forceinline__ void solve_unit(const DevParams* __restrict__ P, cons
     store_tile<T>(P, L, S, shape, pre.te, pre.td, pre.tvalid);
     unit_sync<T>();
     const uint32_t n_here = n_tile - e0 < kTileLds ? n_tile - e0 : kTileLds;
-    for (uint32_t q = tid; q < n_task; q += T) {
-      const uint32_t sp = L.t_spec[q];
-      const uint32_t xpack = sp & 0x3FFu, v = (sp >> 10) & 31u;
-      Eval e;
-      e.ovf = 0;
-      if (e0 == 0) {
-        e.best = kInf; e.arg = kNone;
-        if (P->kind == kKindF) task_bufferize(P, S, shape, xpack, v, e);
-      } else {
-        e.best = L.t_cost[q]; e.arg = sp >> 16;
+    if (n_task * 2 <= T) {
+      // few tasks: a quad of lanes per task, every fourth candidate each (fewer reads one after the other)
+      for (uint32_t qb = 0; qb < n_task; qb += T / 4) {
+        const bool active = qb + (tid >> 2) < n_task;
+        const uint32_t q = active ? qb + (tid >> 2) : 0u, sub4 = tid & 3u;
+        const uint32_t sp = L.t_spec[q];
+        const uint32_t xpack = sp & 0x3FFu, v = (sp >> 10) & 31u;
+        Eval e;
+        e.ovf = 0; e.best = kInf; e.arg = kNone;
+        if (sub4 == 0) {
+          if (e0 == 0) { if (P->kind == kKindF) task_bufferize(P, S, shape, xpack, v, e); }
+          else { e.best = L.t_cost[q]; e.arg = sp >> 16; }
+        }
+        task_tiles(P, L, n_here, sub4, 4, entry_offset(H, xpack, v), cost, e);
+        if (active) tot.ovf |= e.ovf;
+        quad_min<0xB1>(e);
+        quad_min<0x4E>(e);
+        if (active && sub4 == 0) {
+          L.t_cost[q] = e.best;
+          L.t_spec[q] = (sp & 0xFFFFu) | e.arg << 16;
+        }
       }
-      task_tiles(P, L, n_here, entry_offset(H, xpack, v), cost, e);
-      L.t_cost[q] = e.best;
-      L.t_spec[q] = (sp & 0xFFFFu) | e.arg << 16;
-      tot.ovf |= e.ovf;
+    } else {
+      for (uint32_t q = tid; q < n_task; q += T) {
+        const uint32_t sp = L.t_spec[q];
+        const uint32_t xpack = sp & 0x3FFu, v = (sp >> 10) & 31u;
+        Eval e;
+        e.ovf = 0;
+        if (e0 == 0) {
+          e.best = kInf; e.arg = kNone;
+          if (P->kind == kKindF) task_bufferize(P, S, shape, xpack, v, e);
+        } else {
+          e.best = L.t_cost[q]; e.arg = sp >> 16;
+        }
+        task_tiles(P, L, n_here, 0, 1, entry_offset(H, xpack, v), cost, e);
+        L.t_cost[q] = e.best;
+        L.t_spec[q] = (sp & 0xFFFFu) | e.arg << 16;
+        tot.ovf |= e.ovf;
+      }
     }
   }
   tot.n += n_per_task * ((n_task > tid ? n_task - tid + T - 1 : 0u) / T);

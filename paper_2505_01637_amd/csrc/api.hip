@@ -568,7 +568,7 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
 
   // ---- fill: plan, then one launch (or two) per dependency level ----
   AuxLease lease;
-  rc = get_aux(2 * (size_t)n_lev + 3, lease);
+  rc = get_aux(2 * (size_t)n_lev + 5, lease);
   if (rc) return rc;
   Aux* aux = lease.a;
   hipEvent_t* ev = aux->timing;
@@ -723,15 +723,30 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
                         tab->d_cost, tab->d_arg, stL[which]);
     scan_flags(W.alive, W.n, tileL[which], W.pos, W.d_cnt + 2, stL[which]);
     HIP_TRY(hipMemcpyAsync(aux->h_counts + which, W.d_cnt + 2, 4, hipMemcpyDeviceToHost, stL[which]));
+    HIP_TRY(hipEventRecord(aux->events[ev_used + which], stL[which]));
   }
-  for (int which = 0; which < 2; which++) {
-    HIP_TRY(hipStreamSynchronize(stL[which]));
+  // the final lists, whichever list is through first (its stream would idle behind the other's count)
+  const hipEvent_t counted[2] = {aux->events[ev_used], aux->events[ev_used + 1]};
+  ev_used += 2;
+  bool emitted[2] = {false, false};
+  for (int left = 2; left > 0;) {
+    int which = -1;
+    for (int w = 1; w >= 0 && which < 0; w--)
+      if (!emitted[w]) {
+        const hipError_t q = hipEventQuery(counted[w]);
+        if (q == hipSuccess) which = w;
+        else if (q != hipErrorNotReady) return fail(MRL_E_HIP, "hipEventQuery: %s", hipGetErrorString(q));
+      }
+    if (which < 0) continue;
+    emitted[which] = true;
+    left--;
     const uint64_t nf = aux->h_counts[which];
     const size_t fb = final_bytes(nf);
     if (front + fb > (size_t)(work_lo - base)) {
+      HIP_TRY(hipStreamSynchronize(stL[0]));
       HIP_TRY(hipStreamSynchronize(stL[1]));
       return fail(MRL_E_NOMEM, "scratch buffer too small: %zu bytes given, %zu needed", scratch_bytes,
-                  front + fb + (which == 0 ? final_bytes(nbL[1]) : 0) + wbL[0] + wbL[1]);
+                  front + fb + (left ? final_bytes(nbL[1 - which]) : 0) + wbL[0] + wbL[1]);
     }
     char* r = base + front;
     uint32_t* fcell = (uint32_t*)r; r += align_up(nf * 4);

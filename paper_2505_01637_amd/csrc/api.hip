@@ -633,9 +633,9 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
   HIP_TRY(hipStreamSynchronize(st));
 
   // The two lists are merged side by side, the decisions on the helper stream: most of the
-  // kernels are bound by latency, not bandwidth.  Nothing in a list's passes waits for the host:
-  // the lengths of the compacted lists of live boxes stay on the device (slots of d_tot), and the
-  // kernels that walk such a list get the length before compaction as the bound of their grid.
+  // kernels are bound by latency, not bandwidth.  The host waits twice per list: for the number
+  // of live boxes after the first pass (it sizes the grids of the later ones) and for the final
+  // count (it places the final list); meanwhile the other list's stream has work queued.
   // Work areas at the end of the buffer, the final lists grow from the front.
   const uint64_t nbL[2] = {h_tot[0], h_tot[1]};
   const size_t wbL[2] = {work_bytes(nbL[0]), work_bytes(nbL[1])};

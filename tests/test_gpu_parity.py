@@ -95,6 +95,12 @@ def test_degenerate_lattices():
     cost, arg = got["M"].dense()
     assert (cost == B.INF).all() and (arg == B.NONE).all()
     assert got["M"].stats.n_decision_boxes == 1
+    # the largest size list the ABI takes (255 sizes on n): lines of the first merge pass longer
+    # than one 64-step chunk, run lengths up to 255, long tile lists
+    cfg = W.config(2, max_size=2)
+    lat = W._lattice(W.KIND_MATMUL_ACCUM, [[1], [1, 2], [1], list(range(1, 256))])
+    cfg = {"name": "255-sizes", "target": cfg["target"], "lattices": [("M", lat, [])]}
+    compare_config(cfg)
     # a Move forbidden by a zero coefficient
     cfg = W.config(2, max_size=8)
     cfg["target"]["load_coef"][3][0][0] = 0

@@ -139,6 +139,13 @@ def main():
                      "launches_per_step": n_launch, "avg_launch_ms": avg_launch_ms,
                      "algorithmic_bytes_per_launch": algo_bytes_per_launch},
     }
+    # the same table's other fractions of the 8 TB/s: measured bytes of the fill over its time, and
+    # the compulsory bytes of fill + compression (18 + 10 B/spec) over the time of both
+    traffic = out["roofline"]["traffic"]
+    big_both_ms = big_fill_ms + comp_ms[big] / args.steps
+    out["roofline"]["measured_traffic_frac"] = (None if traffic is None else
+                                                traffic * n_launch / (big_fill_ms * 1e-3) / 1e9 / HBM_PEAK_GBS)
+    out["roofline"]["fill_and_compress_frac"] = 28 * sizes[big] / (big_both_ms * 1e-3) / 1e9 / HBM_PEAK_GBS
 
     if not args.no_cpu_baseline:
         from oracle import oracle as O

@@ -304,6 +304,13 @@ def solve_lattices(target, lattices, scratch_bytes=None, buffers=None):
     import threading
     import torch
     done, pending = {}, list(lattices)
+    seen, left = set(), [(job[0], job[2]) for job in pending]
+    while left:                         # the dependency order exists: checked before any device work
+        ok = [lab for lab, deps in left if all(d in seen for d in deps)]
+        if not ok:
+            raise ValueError("lattice dependencies form a cycle or name an unknown label")
+        seen.update(ok)
+        left = [(lab, deps) for lab, deps in left if lab not in seen]
     dev = torch.cuda.current_device()
     while pending:
         ready = [job for job in pending if all(d in done for d in job[2])]

@@ -45,3 +45,14 @@ def test_host_logic_without_gpu():
         assert False
     except B.MorelloError as e:
         assert e.code == B.E_INVAL and "start with 1" in str(e)
+
+
+def test_unknown_dependency_is_refused_before_device_work():
+    """solve_lattices finds an order by itself; a dependency that names no lattice (or a cycle)
+    is refused before anything touches the device."""
+    import pytest
+    from paper_2505_01637_amd import workloads as W
+    cfg = W.config(5, max_size=2)
+    lats = [(lab, lat, ["nowhere"] if lab == "F" else deps) for lab, lat, deps in cfg["lattices"]]
+    with pytest.raises(ValueError):
+        B.solve_lattices(None, lats)

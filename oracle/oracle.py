@@ -198,6 +198,39 @@ def decompress(ext, boxes):
     return v0, v1, cover
 
 
+def query_boxes(lattice, dec, cst, coords):
+    """Point queries answered from the two box lists alone (Section 4.1: the table is kept as
+    boxes and a lookup finds the box that holds the Spec's coordinate).
+
+    By the definition of the lists: exactly one box of each list contains the coordinate.  The
+    decision box gives the rewrite id; the cost box gives cost / volume as a reduced fraction
+    v0/v1, so cost = v0 * volume / v1 with volume = b*m*k*n of the Spec's sizes ((INF, 0) stands
+    for no implementation).  A linear scan over the boxes: slow, for tests only."""
+    sizes = lattice["sizes"]
+    cost, arg = [], []
+    for x in np.asarray(coords, dtype=np.int64).reshape(len(coords), -1):
+        nd = len(x)
+        found = []
+        for boxes in (dec, cst):
+            inside = np.all((boxes["lo"][:, :nd] <= x) & (x <= boxes["hi"][:, :nd]), axis=1)
+            hit = np.flatnonzero(inside)
+            if len(hit) != 1:
+                raise ValueError("coordinate %s lies in %d boxes" % (list(x), len(hit)))
+            found.append(boxes[hit[0]])
+        vol = 1
+        for d in range(4):
+            vol *= int(sizes[d][x[d]])
+        v0, v1 = int(found[1]["v0"]), int(found[1]["v1"])
+        if v1 == 0:
+            cost.append(INF)
+        else:
+            if (v0 * vol) % v1:
+                raise ValueError("cost fraction times volume is not an integer")
+            cost.append(v0 * vol // v1)
+        arg.append(int(found[0]["v0"]))
+    return np.array(cost, dtype=np.uint64), np.array(arg, dtype=np.uint16)
+
+
 def compress_table(target, lattice, cost, argmin):
     """Both box lists of a solved table: (decision_boxes, cost_boxes)."""
     ext, mo, _ = geometry(target, lattice)

@@ -1,6 +1,7 @@
 """Pins of the oracle's box merge (Section 4.1, Figure 2): unit rectangles merged with
 adjacent equal-valued rectangles whose union fills its bounding box."""
 import numpy as np
+import pytest
 
 from oracle import brute_force as B
 from oracle import oracle as O
@@ -93,3 +94,29 @@ def test_cost_values_are_reduced_fractions_and_table_roundtrip():
     c0, c1, cover = O.decompress(ext, cst)
     assert (cover == 1).all() and np.array_equal(c0, v0) and np.array_equal(c1, v1)
     assert len(dec) < len(r["argmin"]) // 4          # decisions do compress
+
+
+@pytest.mark.parametrize("number,max_size,label", [(1, None, "M"), (5, 2, "F"), (4, 2, "M")])
+def test_point_lookup_in_boxes_equals_dense_table(number, max_size, label):
+    """Section 4.1: a lookup in the compressed table returns what the dense table holds.  Pinned
+    against the dense fill (itself pinned by brute force): every coordinate of a small table, or a
+    seeded sample of a larger one, looked up by scanning the two box lists."""
+    cfg = W.config(number, max_size=max_size)
+    res = O.solve_config(cfg)
+    lat = next(l for lb, l, _ in cfg["lattices"] if lb == label)
+    r = res[label]
+    ext = r["extents"]
+    dec, cst = O.compress_table(cfg["target"], lat, r["cost"], r["argmin"])
+    n = len(r["cost"])
+    pick = np.arange(n) if n <= 3000 else np.random.default_rng(7).choice(n, size=3000, replace=False)
+    coords = np.stack(np.unravel_index(pick, ext), axis=1)
+    cost, arg = O.query_boxes(lat, dec, cst, coords)
+    assert np.array_equal(cost, r["cost"][pick]) and np.array_equal(arg, r["argmin"][pick])
+    assert (cost != np.uint64(O.INF)).any()
+    # a planted mistake is seen: one box moved by one cell no longer partitions the lattice
+    broken = dec.copy()
+    i = int(np.argmax(broken["hi"][:, 3] - broken["lo"][:, 3]))
+    if broken["hi"][i, 3] > broken["lo"][i, 3]:
+        broken["hi"][i, 3] -= 1
+        with pytest.raises(ValueError):
+            O.query_boxes(lat, broken, cst, np.stack(np.unravel_index(np.arange(n), ext), axis=1)[: 20000])

@@ -188,6 +188,19 @@ typedef enum { MRL_BOXES_DECISION = 0, MRL_BOXES_COST = 1 } mrl_box_list;
 int32_t mrl_emit_compressed(const mrl_table* tab, uint32_t which,
                             mrl_box* out, size_t cap, size_t* n_out);
 
+/* Point query answered from the two box lists alone (Section 4.1: the stored
+ * table is the set of boxes, and a lookup finds the box that holds the Spec's
+ * coordinate).  Same arguments and same answers as mrl_query, without reading
+ * the dense table: the rewrite is the decision box's value, the cost is the
+ * cost box's fraction times the Spec's volume.  The first call on a table
+ * builds, in device memory that the library allocates and frees with the
+ * table, a hierarchy of bounding boxes over each list (an R-tree bulk-loaded
+ * in the list's order); the lists themselves stay in the caller's scratch
+ * buffer.  Every axis must have at most 256 coordinates (MRL_E_INVAL else).
+ * Errors as mrl_query. */
+int32_t mrl_query_compressed(const mrl_table* tab, const mrl_coord* specs, size_t n,
+                             uint64_t* cost_out, uint16_t* rewrite_out);
+
 /* ---------------------------------------------------------------------------
  * Schedule of a goal Spec (Section 4: the search returns, for every Spec, the
  * rewrite of the cheapest implementation; following these rewrites from the

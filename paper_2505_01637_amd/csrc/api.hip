@@ -452,6 +452,16 @@ struct mrl_table {
   // final lists inside scratch: [0] decisions, [1] costs
   size_t list_off[2];
   uint64_t list_n[2];
+  // Lookups in the box lists (mrl_query_compressed): bounding-box hierarchy per list and staging
+  // for one chunk of points, allocated at the first such query and freed with the table.
+  struct BoxIndex { IndexLevels L; BoxBounds* nodes = nullptr; };
+  mutable BoxIndex index[2];
+  mutable char* lookup_buf = nullptr;
+  mutable std::mutex lookup_mu;
+  ~mrl_table() {
+    for (auto& ix : index) if (ix.nodes) (void)hipFree(ix.nodes);
+    if (lookup_buf) (void)hipFree(lookup_buf);
+  }
 };
 
 extern "C" {
@@ -955,6 +965,73 @@ int32_t mrl_emit_compressed(const mrl_table* tab, uint32_t which, mrl_box* out, 
       b.hi[a] = (uint16_t)(lo + flen[i * 16 + a] - 1);
     }
     b.v0 = fv0[i]; b.v1 = fv1[i];
+  }
+  return MRL_OK;
+}
+
+int32_t mrl_query_compressed(const mrl_table* tab, const mrl_coord* specs, size_t n, uint64_t* cost_out,
+                             uint16_t* rewrite_out) {
+  if (!tab || (n && (!specs || !cost_out || !rewrite_out))) return fail(MRL_E_INVAL, "NULL argument");
+  const Compiled& c = *tab->cp;
+  const Geo& g = c.geo;
+  for (uint32_t a = 0; a < g.ndim; a++)
+    if (g.ext[a] > 256) return fail(MRL_E_INVAL, "axis %u has %u coordinates: the box index holds one byte per axis", a, g.ext[a]);
+  std::lock_guard<std::mutex> lock(tab->lookup_mu);
+  const uint64_t* fv[2][2];
+  for (uint32_t which = 0; which < 2; which++) {
+    const uint64_t nb = tab->list_n[which];
+    const char* r = tab->scratch + tab->list_off[which];
+    const uint32_t* fcell = (const uint32_t*)r; r += align_up(nb * 4);
+    const void* flen = r; r += align_up(nb * 16);
+    fv[which][0] = (const uint64_t*)r; r += align_up(nb * 8);
+    fv[which][1] = (const uint64_t*)r;
+    mrl_table::BoxIndex& ix = tab->index[which];
+    if (!ix.nodes) {
+      ix.L = index_levels((uint32_t)nb);
+      HIP_TRY(hipMalloc((void**)&ix.nodes, std::max<size_t>(ix.L.total, 1) * sizeof(BoxBounds)));
+      launch_build_index(g, ix.L, fcell, flen, ix.nodes, tab->stream);
+      HIP_TRY(hipGetLastError());
+    }
+  }
+  // staging of one chunk: points, then per list v0, v1 (u64) and the box index (u32)
+  const size_t o_pts = 0, o_val = o_pts + (size_t)kQueryChunk * 16, o_which = o_val + 4 * (size_t)kQueryChunk * 8,
+               total = o_which + 2 * (size_t)kQueryChunk * 4;
+  if (!tab->lookup_buf) HIP_TRY(hipMalloc((void**)&tab->lookup_buf, total));
+  uint8_t* d_pts = (uint8_t*)(tab->lookup_buf + o_pts);
+  uint64_t* d_val = (uint64_t*)(tab->lookup_buf + o_val);
+  uint32_t* d_which = (uint32_t*)(tab->lookup_buf + o_which);
+  std::vector<uint8_t> pts((size_t)kQueryChunk * 16);
+  std::vector<uint64_t> val(4 * (size_t)kQueryChunk), vol(kQueryChunk);
+  std::vector<uint32_t> hit(2 * (size_t)kQueryChunk);
+  for (size_t done = 0; done < n; done += kQueryChunk) {
+    const uint32_t m = (uint32_t)std::min<size_t>(kQueryChunk, n - done);
+    memset(pts.data(), 0, pts.size());
+    for (uint32_t i = 0; i < m; i++) {
+      for (uint32_t a = 0; a < g.ndim; a++) {
+        const uint32_t v = specs[done + i].x[a];
+        if (v >= g.ext[a]) return fail(MRL_E_RANGE, "spec %zu: coordinate %u = %u outside [0, %u)", done + i, a, v, g.ext[a]);
+        pts[(size_t)i * 16 + a] = (uint8_t)v;
+      }
+      uint64_t w = 1;
+      for (uint32_t d = 0; d < 4; d++) w *= c.sizes[d][specs[done + i].x[d]];
+      vol[i] = w;
+    }
+    HIP_TRY(hipMemcpyAsync(d_pts, pts.data(), (size_t)m * 16, hipMemcpyHostToDevice, tab->stream));
+    for (uint32_t which = 0; which < 2; which++)
+      launch_lookup(tab->index[which].L, tab->index[which].nodes, d_pts, m, fv[which][0], fv[which][1],
+                    d_val + (2 * which) * (size_t)kQueryChunk, d_val + (2 * which + 1) * (size_t)kQueryChunk,
+                    d_which + which * (size_t)kQueryChunk, tab->stream);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipMemcpyAsync(val.data(), d_val, val.size() * 8, hipMemcpyDeviceToHost, tab->stream));
+    HIP_TRY(hipMemcpyAsync(hit.data(), d_which, hit.size() * 4, hipMemcpyDeviceToHost, tab->stream));
+    HIP_TRY(hipStreamSynchronize(tab->stream));
+    for (uint32_t i = 0; i < m; i++) {
+      if (hit[i] == 0xFFFFFFFFu || hit[kQueryChunk + i] == 0xFFFFFFFFu)
+        return fail(MRL_E_HIP, "internal error: spec %zu lies in no box", done + i);
+      rewrite_out[done + i] = (uint16_t)val[i];
+      const uint64_t v0 = val[2 * (size_t)kQueryChunk + i], v1 = val[3 * (size_t)kQueryChunk + i];
+      cost_out[done + i] = v1 == 0 ? kInf : (uint64_t)((unsigned __int128)v0 * vol[i] / v1);
+    }
   }
   return MRL_OK;
 }

@@ -58,6 +58,24 @@ void launch_emit(const Geo& g, const DevParams* P, bool is_cost, uint32_t n_boxe
 void launch_gather(const uint64_t* idx, uint32_t n, const uint64_t* cost, const uint16_t* arg, uint64_t* cost_out,
                    uint16_t* arg_out, hipStream_t st);
 
+// Point lookups in a final box list: a packed hierarchy of bounding boxes over the list's order.
+constexpr uint32_t kIndexFan = 8;          // children per node
+constexpr uint32_t kIndexMaxLevels = 12;   // 8^11 > 2^32 boxes
+struct alignas(32) BoxBounds { uint8_t lo[16], hi[16]; };   // inclusive corners, one byte per axis
+struct IndexLevels {
+  uint32_t n_levels;                       // level 0 = the boxes; the top level has at most kIndexFan nodes
+  uint32_t count[kIndexMaxLevels], off[kIndexMaxLevels];    // nodes per level, first node of the level
+  uint32_t total;
+};
+IndexLevels index_levels(uint32_t n_boxes);
+void launch_build_index(const Geo& g, const IndexLevels& L, const uint32_t* fcell, const void* flen, BoxBounds* nodes,
+                        hipStream_t st);
+// points: 16 bytes per point (coordinates, zero padded).  out0/out1: the value of the box that
+// holds the point; which_out: its index, 0xFFFFFFFF if none.
+void launch_lookup(const IndexLevels& L, const BoxBounds* nodes, const uint8_t* points, uint32_t n_points,
+                   const uint64_t* fv0, const uint64_t* fv1, uint64_t* out0, uint64_t* out1, uint32_t* which_out,
+                   hipStream_t st);
+
 constexpr uint32_t kScanTileItems = 2048;   // items per scan tile (tile_tmp needs n/2048 + 1 words)
 
 }  // namespace mrl

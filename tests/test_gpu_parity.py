@@ -70,7 +70,66 @@ def test_parity_full_size(number):
 def test_parity_config5_full_size():
     """The benchmark's workload (config 5: M 28.1 M, E 0.37 M, F 449.5 M specs) in the launch
     configuration bench.py times: dense tables, counters and both box lists of all three tables."""
-    compare_config(W.config(5), scratch_bytes=6 << 30)
+    _, got, want = compare_config(W.config(5), scratch_bytes=6 << 30)
+    # lookups in the box lists at full size: sampled coordinates against the oracle's dense table
+    for label in "MEF":
+        check_compressed_queries(got[label], want[label], 200_000, seed=5)
+
+
+def check_compressed_queries(tab, want, n_points, seed):
+    ext = tab.extents
+    n = len(want["cost"])
+    rng = np.random.default_rng(seed)
+    lin = np.arange(n) if n <= n_points else rng.integers(0, n, size=n_points)
+    coords = np.stack(np.unravel_index(lin, ext), axis=1)
+    print("compressed queries", len(lin), "of", n, flush=True)
+    cost, rw = tab.query(coords, compressed=True)
+    bad = np.flatnonzero((cost != want["cost"][lin]) | (rw != want["argmin"][lin]))
+    assert bad.size == 0, (bad[:5], coords[bad[:5]], cost[bad[:5]], want["cost"][lin[bad[:5]]])
+
+
+@pytest.mark.parametrize("number,max_size", [(1, None), (2, 20), (3, 64), (4, 16), (5, 16)])
+def test_compressed_query_parity(number, max_size):
+    """mrl_query_compressed: answers from the box lists alone equal the oracle's dense table at
+    every coordinate (small tables) or at 300 000 sampled ones, and equal the oracle's own lookups
+    in its box lists; lists from 1 box to several levels of the bounding-box hierarchy."""
+    B = _binding()
+    cfg = W.config(number, max_size=max_size)
+    want = O.solve_config(cfg)
+    _, got = B.solve_config(cfg)
+    for label, lat, _ in cfg["lattices"]:
+        check_compressed_queries(got[label], want[label], 300_000, seed=number)
+        w = want[label]
+        dec, cst = O.compress_table(cfg["target"], lat, w["cost"], w["argmin"])
+        lin = np.random.default_rng(number).integers(0, len(w["cost"]), size=200)
+        coords = np.stack(np.unravel_index(lin, w["extents"]), axis=1)
+        oc, oa = O.query_boxes(lat, dec, cst, coords)
+        gc, ga = got[label].query(coords, compressed=True)
+        assert np.array_equal(gc, oc) and np.array_equal(ga, oa)
+    tab = got[cfg["lattices"][0][0]]
+    with pytest.raises(B.MorelloError) as e:
+        tab.query(np.array([[0, 0, 0, 99] + [0] * (len(tab.extents) - 4)]), compressed=True)
+    assert e.value.code == B.E_RANGE
+
+
+def test_compressed_query_one_box_and_long_axis():
+    """A table that is one box (nothing solvable), and the 255-size axis (coordinates up to 254)."""
+    B = _binding()
+    t = W._empty_target(3, (256, 512, W.UNBOUNDED))
+    t["load_coef"][1][0][0] = t["load_coef"][2][1][0] = t["load_coef"][2][0][0] = 1
+    t["store_coef"][0][1][0] = t["store_coef"][1][2][0] = t["store_coef"][0][2][0] = 1
+    cfg = {"name": "no-mk", "target": t,
+           "lattices": [("M", W._lattice(W.KIND_MATMUL_ACCUM, [[1], [1, 2], [1, 2], [1, 2, 4]]), [])]}
+    want = O.solve_config(cfg)
+    _, got = B.solve_config(cfg)
+    assert got["M"].stats.n_decision_boxes == 1
+    check_compressed_queries(got["M"], want["M"], 10_000, seed=1)
+    base = W.config(2, max_size=2)
+    lat = W._lattice(W.KIND_MATMUL_ACCUM, [[1], [1, 2], [1], list(range(1, 256))])
+    cfg = {"name": "255-sizes", "target": base["target"], "lattices": [("M", lat, [])]}
+    want = O.solve_config(cfg)
+    _, got = B.solve_config(cfg)
+    check_compressed_queries(got["M"], want["M"], 10**9, seed=1)
 
 
 def test_degenerate_lattices():

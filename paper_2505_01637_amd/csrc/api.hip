@@ -43,6 +43,7 @@ namespace {
 
 constexpr size_t kAlign = 256;
 constexpr uint32_t kQueryChunk = 4096;
+constexpr uint32_t kLookupChunk = 65536;   // points per launch of a lookup in the box lists
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 // Host-side compiled lattice: everything derived from (target, lattice).
@@ -978,10 +979,11 @@ int32_t mrl_query_compressed(const mrl_table* tab, const mrl_coord* specs, size_
     if (g.ext[a] > 256) return fail(MRL_E_INVAL, "axis %u has %u coordinates: the box index holds one byte per axis", a, g.ext[a]);
   std::lock_guard<std::mutex> lock(tab->lookup_mu);
   const uint64_t* fv[2][2];
+  const uint32_t* cells[2];
   for (uint32_t which = 0; which < 2; which++) {
     const uint64_t nb = tab->list_n[which];
     const char* r = tab->scratch + tab->list_off[which];
-    const uint32_t* fcell = (const uint32_t*)r; r += align_up(nb * 4);
+    const uint32_t* fcell = cells[which] = (const uint32_t*)r; r += align_up(nb * 4);
     const void* flen = r; r += align_up(nb * 16);
     fv[which][0] = (const uint64_t*)r; r += align_up(nb * 8);
     fv[which][1] = (const uint64_t*)r;
@@ -994,18 +996,18 @@ int32_t mrl_query_compressed(const mrl_table* tab, const mrl_coord* specs, size_
     }
   }
   // staging of one chunk: points, then per list v0, v1 (u64) and the box index (u32)
-  const size_t o_pts = 0, o_val = o_pts + (size_t)kQueryChunk * 16, o_which = o_val + 4 * (size_t)kQueryChunk * 8,
-               total = o_which + 2 * (size_t)kQueryChunk * 4;
+  const size_t o_pts = 0, o_val = o_pts + (size_t)kLookupChunk * 16, o_which = o_val + 4 * (size_t)kLookupChunk * 8,
+               total = o_which + 2 * (size_t)kLookupChunk * 4;
   if (!tab->lookup_buf) HIP_TRY(hipMalloc((void**)&tab->lookup_buf, total));
   uint8_t* d_pts = (uint8_t*)(tab->lookup_buf + o_pts);
   uint64_t* d_val = (uint64_t*)(tab->lookup_buf + o_val);
   uint32_t* d_which = (uint32_t*)(tab->lookup_buf + o_which);
-  std::vector<uint8_t> pts((size_t)kQueryChunk * 16);
-  std::vector<uint64_t> val(4 * (size_t)kQueryChunk), vol(kQueryChunk);
-  std::vector<uint32_t> hit(2 * (size_t)kQueryChunk);
-  for (size_t done = 0; done < n; done += kQueryChunk) {
-    const uint32_t m = (uint32_t)std::min<size_t>(kQueryChunk, n - done);
-    memset(pts.data(), 0, pts.size());
+  std::vector<uint8_t> pts((size_t)kLookupChunk * 16);
+  std::vector<uint64_t> val(4 * (size_t)kLookupChunk), vol(kLookupChunk);
+  std::vector<uint32_t> hit(2 * (size_t)kLookupChunk);
+  for (size_t done = 0; done < n; done += kLookupChunk) {
+    const uint32_t m = (uint32_t)std::min<size_t>(kLookupChunk, n - done);
+    memset(pts.data(), 0, (size_t)m * 16);
     for (uint32_t i = 0; i < m; i++) {
       for (uint32_t a = 0; a < g.ndim; a++) {
         const uint32_t v = specs[done + i].x[a];
@@ -1018,18 +1020,22 @@ int32_t mrl_query_compressed(const mrl_table* tab, const mrl_coord* specs, size_
     }
     HIP_TRY(hipMemcpyAsync(d_pts, pts.data(), (size_t)m * 16, hipMemcpyHostToDevice, tab->stream));
     for (uint32_t which = 0; which < 2; which++)
-      launch_lookup(tab->index[which].L, tab->index[which].nodes, d_pts, m, fv[which][0], fv[which][1],
-                    d_val + (2 * which) * (size_t)kQueryChunk, d_val + (2 * which + 1) * (size_t)kQueryChunk,
-                    d_which + which * (size_t)kQueryChunk, tab->stream);
+      launch_lookup(g, tab->index[which].L, tab->index[which].nodes, cells[which], d_pts, m, fv[which][0], fv[which][1],
+                    d_val + (2 * which) * (size_t)kLookupChunk, d_val + (2 * which + 1) * (size_t)kLookupChunk,
+                    d_which + which * (size_t)kLookupChunk, tab->stream);
     HIP_TRY(hipGetLastError());
-    HIP_TRY(hipMemcpyAsync(val.data(), d_val, val.size() * 8, hipMemcpyDeviceToHost, tab->stream));
-    HIP_TRY(hipMemcpyAsync(hit.data(), d_which, hit.size() * 4, hipMemcpyDeviceToHost, tab->stream));
+    for (uint32_t k = 0; k < 4; k++)
+      HIP_TRY(hipMemcpyAsync(val.data() + k * (size_t)kLookupChunk, d_val + k * (size_t)kLookupChunk, (size_t)m * 8,
+                             hipMemcpyDeviceToHost, tab->stream));
+    for (uint32_t k = 0; k < 2; k++)
+      HIP_TRY(hipMemcpyAsync(hit.data() + k * (size_t)kLookupChunk, d_which + k * (size_t)kLookupChunk, (size_t)m * 4,
+                             hipMemcpyDeviceToHost, tab->stream));
     HIP_TRY(hipStreamSynchronize(tab->stream));
     for (uint32_t i = 0; i < m; i++) {
-      if (hit[i] == 0xFFFFFFFFu || hit[kQueryChunk + i] == 0xFFFFFFFFu)
+      if (hit[i] == 0xFFFFFFFFu || hit[kLookupChunk + i] == 0xFFFFFFFFu)
         return fail(MRL_E_HIP, "internal error: spec %zu lies in no box", done + i);
       rewrite_out[done + i] = (uint16_t)val[i];
-      const uint64_t v0 = val[2 * (size_t)kQueryChunk + i], v1 = val[3 * (size_t)kQueryChunk + i];
+      const uint64_t v0 = val[2 * (size_t)kLookupChunk + i], v1 = val[3 * (size_t)kLookupChunk + i];
       cost_out[done + i] = v1 == 0 ? kInf : (uint64_t)((unsigned __int128)v0 * vol[i] / v1);
     }
   }

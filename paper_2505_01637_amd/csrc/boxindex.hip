@@ -63,10 +63,15 @@ __global__ __launch_bounds__(256) void group_bounds_kernel(const BoxBounds* __re
   out[i] = r;
 }
 
-// One lane per point.  cursor/last: the stretch of nodes still to test on each level; every node
-// is tested at most once, so the walk ends.  which_out: the box's index, or 0xFFFFFFFF if no box
-// holds the point (the list is then not a partition: reported by the host).
-__global__ __launch_bounds__(256) void lookup_kernel(IndexLevels L, const BoxBounds* __restrict__ nodes,
+// One lane per point.  The boxes are sorted by low corner in row-major order and the box that
+// holds a point starts at or before the point in that order, so the walk starts at the last box
+// whose low cell is <= the point's cell (binary search) and runs backwards: the box wanted is
+// usually a few boxes away.  cursor/first: the stretch of nodes still to test on each level,
+// taken from its end; every node is tested at most once, so the walk ends.  which_out: the
+// box's index, or 0xFFFFFFFF if no box holds the point (the list is then not a partition:
+// reported by the host).
+__global__ __launch_bounds__(256) void lookup_kernel(Geo g, IndexLevels L, const BoxBounds* __restrict__ nodes,
+                                                     const uint32_t* __restrict__ fcell,
                                                      const uint8_t* __restrict__ points, uint32_t n_points,
                                                      const uint64_t* __restrict__ fv0, const uint64_t* __restrict__ fv1,
                                                      uint64_t* __restrict__ out0, uint64_t* __restrict__ out1,
@@ -74,25 +79,39 @@ __global__ __launch_bounds__(256) void lookup_kernel(IndexLevels L, const BoxBou
   const uint32_t q = blockIdx.x * 256u + threadIdx.x;
   if (q >= n_points) return;
   uint8_t p[16];
+  uint32_t cell = 0;
 #pragma unroll
-  for (int a = 0; a < 16; a++) p[a] = points[(size_t)q * 16 + a];
-  uint32_t cursor[kIndexMaxLevels], last[kIndexMaxLevels];
-  int lvl = (int)L.n_levels - 1;
-  cursor[lvl] = 0;
-  last[lvl] = L.count[lvl];
+  for (int a = 0; a < 16; a++) {
+    p[a] = points[(size_t)q * 16 + a];
+    if ((uint32_t)a < g.ndim) cell += p[a] * g.stride[a];
+  }
+  // pos = number of boxes whose low cell is <= cell (>= 1 for a partition: box 0 starts at cell 0)
+  uint32_t lo = 0, hi = L.count[0];
+  while (lo < hi) {
+    const uint32_t mid = lo + (hi - lo) / 2;
+    if (fcell[mid] <= cell) lo = mid + 1; else hi = mid;
+  }
   uint32_t found = 0xFFFFFFFFu;
-  while (true) {
-    if (cursor[lvl] == last[lvl]) {
-      if (lvl == (int)L.n_levels - 1) break;
-      lvl++;
-      continue;
+  if (lo > 0) {
+    const uint32_t pos = lo - 1;
+    // cursor[l]: one past the next node to test on level l; first[l]: where its stretch begins
+    uint32_t cursor[kIndexMaxLevels], first[kIndexMaxLevels];
+    int lvl = (int)L.n_levels - 1;
+    cursor[lvl] = (pos >> (3 * lvl)) + 1;
+    first[lvl] = 0;
+    while (true) {
+      if (cursor[lvl] == first[lvl]) {
+        if (lvl == (int)L.n_levels - 1) break;
+        lvl++;
+        continue;
+      }
+      const uint32_t i = --cursor[lvl];
+      if (!contains(nodes[L.off[lvl] + i], p)) continue;
+      if (lvl == 0) { found = i; break; }
+      lvl--;
+      first[lvl] = i * kIndexFan;
+      cursor[lvl] = min(i * kIndexFan + kIndexFan, (pos >> (3 * lvl)) + 1);
     }
-    const uint32_t i = cursor[lvl]++;
-    if (!contains(nodes[L.off[lvl] + i], p)) continue;
-    if (lvl == 0) { found = i; break; }
-    lvl--;
-    cursor[lvl] = i * kIndexFan;
-    last[lvl] = min(i * kIndexFan + kIndexFan, L.count[lvl]);
   }
   which_out[q] = found;
   out0[q] = found == 0xFFFFFFFFu ? 0 : fv0[found];
@@ -127,12 +146,13 @@ void launch_build_index(const Geo& g, const IndexLevels& L, const uint32_t* fcel
                        L.count[l - 1], nodes + L.off[l], L.count[l]);
 }
 
-void launch_lookup(const IndexLevels& L, const BoxBounds* nodes, const uint8_t* points, uint32_t n_points,
-                   const uint64_t* fv0, const uint64_t* fv1, uint64_t* out0, uint64_t* out1, uint32_t* which_out,
-                   hipStream_t st) {
+void launch_lookup(const Geo& g, const IndexLevels& L, const BoxBounds* nodes, const uint32_t* fcell,
+                   const uint8_t* points, uint32_t n_points, const uint64_t* fv0, const uint64_t* fv1, uint64_t* out0,
+                   uint64_t* out1, uint32_t* which_out, hipStream_t st) {
   if (!n_points) return;
-  hipLaunchKernelGGL(lookup_kernel, dim3((n_points + 255) / 256), dim3(256), 0, st, L, nodes, points, n_points, fv0, fv1,
-                     out0, out1, which_out);
+  static_assert(kIndexFan == 8, "the walk shifts box indices by 3 bits per level");
+  hipLaunchKernelGGL(lookup_kernel, dim3((n_points + 255) / 256), dim3(256), 0, st, g, L, nodes, fcell, points, n_points,
+                     fv0, fv1, out0, out1, which_out);
 }
 
 }  // namespace mrl

@@ -72,9 +72,9 @@ void launch_build_index(const Geo& g, const IndexLevels& L, const uint32_t* fcel
                         hipStream_t st);
 // points: 16 bytes per point (coordinates, zero padded).  out0/out1: the value of the box that
 // holds the point; which_out: its index, 0xFFFFFFFF if none.
-void launch_lookup(const IndexLevels& L, const BoxBounds* nodes, const uint8_t* points, uint32_t n_points,
-                   const uint64_t* fv0, const uint64_t* fv1, uint64_t* out0, uint64_t* out1, uint32_t* which_out,
-                   hipStream_t st);
+void launch_lookup(const Geo& g, const IndexLevels& L, const BoxBounds* nodes, const uint32_t* fcell,
+                   const uint8_t* points, uint32_t n_points, const uint64_t* fv0, const uint64_t* fv1, uint64_t* out0,
+                   uint64_t* out1, uint32_t* which_out, hipStream_t st);
 
 constexpr uint32_t kScanTileItems = 2048;   // items per scan tile (tile_tmp needs n/2048 + 1 words)
 

@@ -8,6 +8,7 @@ be checked against each other on tiny lattices.
   from a Spec -- no memo table, no pruning, no cost bookkeeping.
 * `c(p)` evaluates the cost equation of Section 3 on such a tree:
     loop          trips * c(body) + s
+    parallel loop ceil(trips / threads) * c(body) + s_parallel
     pipeline      sum of the children (+ the intermediate's initialisation)
     alloc-binding move cost + c(body)
     microkernel   k_p
@@ -19,7 +20,7 @@ exponentially with the number of divisors and levels.
 """
 from collections import namedtuple
 
-M, E, F = 0, 1, 2
+M, E, F, P = 0, 1, 2, 3      # P: a Matmul that may use parallel loops; M is serial-only
 FMA, BCAST, BF16DOT, S_ADDRELU, V_ADDRELU = 0, 1, 2, 3, 4
 
 # dims = (b, m, k, n) actual sizes; levels per operand (F: 5th = intermediate);
@@ -29,7 +30,7 @@ Spec = namedtuple("Spec", "kind dims levels layouts bf16")
 
 def operand_numel(spec, i):
     b, m, k, n = spec.dims
-    if spec.kind == M:
+    if spec.kind in (M, P):
         return (b * m * k, b * k * n, b * m * n)[i]
     if spec.kind == E:
         return (m * n, n, m * n)[i]
@@ -38,7 +39,7 @@ def operand_numel(spec, i):
 
 def operand_mode(kind, i):
     """'r' read, 'rw' accumulate, 'w' write-only."""
-    if kind == M:
+    if kind in (M, P):
         return "rw" if i == 2 else "r"
     if kind == E:
         return "w" if i == 2 else "r"
@@ -60,15 +61,15 @@ def microkernel_reps(target, lattice, spec, j):
     b, m, k, n = spec.dims
     lv, ly, bf = spec.levels, spec.layouts, spec.bf16
     if kind == FMA:
-        ok = spec.kind == M and (b, m, k, n) == (1, 1, 1, 1) and tuple(lv[:3]) == (0, 0, 0) and not any(bf[:3])
+        ok = spec.kind in (M, P) and (b, m, k, n) == (1, 1, 1, 1) and tuple(lv[:3]) == (0, 0, 0) and not any(bf[:3])
         return 1 if ok else 0
     if kind == BCAST:
-        ok = (spec.kind == M and (b, m, k) == (1, 1, 1) and n % lanes == 0
+        ok = (spec.kind in (M, P) and (b, m, k) == (1, 1, 1) and n % lanes == 0
               and tuple(lv[:3]) == (0, 1, 1) and not any(bf[:3]) and ly[1] == 0 and ly[2] == 0)
         return n // lanes if ok else 0
     if kind == BF16DOT:
         rhs_col = ly[1] == 1 or not lattice["layout_coord"][1]
-        ok = (spec.kind == M and (b, m, n) == (1, 1, 1) and k % lanes == 0
+        ok = (spec.kind in (M, P) and (b, m, n) == (1, 1, 1) and k % lanes == 0
               and tuple(lv[:3]) == (1, 1, 0) and bf[0] and bf[1] and not bf[2] and rhs_col)
         return k // lanes if ok else 0
     if kind == S_ADDRELU:
@@ -125,7 +126,7 @@ def rewrites(target, lattices, spec):
                     rid = move_base + ((i * (nl - 1) + dst) * 2 + x) * 2 + cv
                     yield rid, ("alloc", coef * operand_numel(spec, i)), [child]
     for d in range(4):
-        if spec.kind != M and d in (0, 2):
+        if spec.kind in (E, F) and d in (0, 2):
             continue
         cur = spec.dims[d]
         for j, t in enumerate(lattice["sizes"][d]):
@@ -134,6 +135,16 @@ def rewrites(target, lattices, spec):
                 yield (tile_base + d * maxs + j,
                        ("loop", cur // t, target["loop_overhead"]),
                        [spec._replace(dims=tuple(dims))])
+    if spec.kind == P:
+        # the body of a parallel loop is serial-only: the same Spec in the serial lattice
+        for d in (0, 1, 3):
+            cur = spec.dims[d]
+            for j, t in enumerate(lattice["sizes"][d]):
+                if t < cur and cur % t == 0:
+                    dims = list(spec.dims); dims[d] = t
+                    yield (tile_base + 4 * maxs + 1 + d * maxs + j,
+                           ("parallel", cur // t, target["threads"], target["sync_cost"]),
+                           [spec._replace(kind=M, dims=tuple(dims))])
     if spec.kind == F:
         b, m, k, n = spec.dims
         l_lhs, l_rhs, l_bias, l_out, l_mid = spec.levels
@@ -165,6 +176,9 @@ def c(p):
         return p[1]
     if tag == "loop":
         return p[1] * c(p[3]) + p[2]
+    if tag == "parallel":
+        trips, threads, sync = p[1], p[2], p[3]
+        return -(-trips // threads) * c(p[4]) + sync
     if tag == "alloc":
         return p[1] + c(p[2])
     if tag == "pipeline":

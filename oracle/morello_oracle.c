@@ -11,7 +11,8 @@
  *     table, else evaluate every applicable rewrite, recurse on the rewrite's
  *     sub-Specs, memoize and return the lowest-cost one.  -> orc_solve()
  *   - Section 3 (Cost Model): c(p) is affine in the sub-program costs:
- *     loop = trips * c(body) + s; alloc-binding = move cost + c(children);
+ *     loop = trips * c(body) + s (parallel: ceil(trips / threads) rounds);
+ *     alloc-binding = move cost + c(children);
  *     pipeline/block = sum of children; microkernel = k_p.
  *   - Section 2 (Tiling, Memory Movement, Microkernel Selection) and
  *     Section 2.1 (bufferize of a composition) for the rewrites themselves.
@@ -38,7 +39,7 @@
 enum { ORC_MAXL = 4, ORC_MAXOPS = 5, ORC_MAXD = 16, ORC_MAXMK = 8 };
 enum { MK_SCALAR_FMA = 0, MK_BCAST_VEC_MULADD = 1, MK_BF16_DOT = 2,
        MK_SCALAR_ADDRELU = 3, MK_VEC_ADDRELU = 4 };
-enum { KIND_M = 0, KIND_E = 1, KIND_F = 2 };
+enum { KIND_M = 0, KIND_E = 1, KIND_F = 2, KIND_P = 3 };
 enum { ACC_READ = 0, ACC_RMW = 1, ACC_WRITE = 2 };
 
 typedef struct {
@@ -53,6 +54,8 @@ typedef struct {
   uint32_t mk_kind[ORC_MAXMK];
   uint32_t mk_lanes[ORC_MAXMK];
   uint64_t mk_cost[ORC_MAXMK];
+  uint32_t threads;                            /* hardware threads a parallel loop spreads over */
+  uint32_t sync_cost;                          /* the constant s of a parallel loop */
 } orc_target;
 
 typedef struct {
@@ -83,7 +86,8 @@ typedef struct ctx {
   uint64_t* cost;
   uint16_t* arg;
   uint8_t* done;
-  uint32_t maxs, nmk, move_base, tile_base, buf_id;
+  uint32_t maxs, nmk, move_base, tile_base, buf_id, par_base;
+  int parallel;                 /* kind P: a Matmul whose serial-only flag is off */
   uint64_t n_rewrites, n_admissible;
   int overflow;
   const struct ctx* depM;
@@ -98,7 +102,11 @@ typedef struct ctx {
 static int ctx_init(ctx* c, const orc_target* T, const orc_lattice* L) {
   memset(c, 0, sizeof *c);
   c->T = T; c->L = L; c->kind = (int)L->kind;
-  if (c->kind < 0 || c->kind > 2) return -1;
+  if (c->kind < 0 || c->kind > 3) return -1;
+  if (c->kind == KIND_P) {      /* same operator, operands and coordinates as kind M */
+    c->kind = KIND_M; c->parallel = 1;
+    if (T->threads < 1) return -1;
+  }
   if (T->n_levels < 1 || T->n_levels > ORC_MAXL) return -1;
   c->nops = c->kind == KIND_F ? 4 : 3;
   c->nlv = c->kind == KIND_F ? 5 : 3;
@@ -130,7 +138,8 @@ static int ctx_init(ctx* c, const orc_target* T, const orc_lattice* L) {
   c->move_base = c->nmk;
   c->tile_base = c->move_base + (uint32_t)c->nops * (T->n_levels - 1) * 4;
   c->buf_id = c->tile_base + 4 * c->maxs;
-  if (c->buf_id >= ORC_NONE) return -1;
+  c->par_base = c->buf_id + 1;
+  if ((c->parallel ? c->par_base + 4 * c->maxs : c->buf_id) >= ORC_NONE) return -1;
   return 0;
 }
 
@@ -328,6 +337,27 @@ static void expand(ctx* c, const spec_t* s, uint64_t* best_out, uint16_t* arg_ou
     }
     consider(c, cand, c->buf_id, &best, &arg);
   }
+
+  /* E. parallel loop (kind P, Section 3: ceil(trips / threads) * c(body) + s).
+   * The body is the serial-only Spec of the smaller shape (Section 2.2: the
+   * flag limits an implementation to one hardware thread), so its cost comes
+   * from the serial table.  Not over k: its iterations accumulate into the
+   * same output elements. */
+  if (c->parallel) {
+    for (int d = 0; d < 4; d++) {
+      if (d == 2) continue;
+      uint32_t cur = c->L->sizes[d][s->si[d]];
+      for (uint32_t j = 0; j < s->si[d]; j++) {
+        uint32_t t = c->L->sizes[d][j];
+        if (cur % t) continue;
+        spec_t sub = *s;
+        sub.si[d] = j;
+        uint64_t trips = cur / t, rounds = (trips + T->threads - 1) / T->threads;
+        uint64_t body = c->depM->cost[spec_index(c->depM, &sub)];
+        consider(c, affine(c, rounds, body, T->sync_cost), c->par_base + (uint32_t)d * c->maxs + j, &best, &arg);
+      }
+    }
+  }
   *best_out = best; *arg_out = arg;
 }
 
@@ -359,13 +389,24 @@ int orc_solve(const orc_target* T, const orc_lattice* L,
   if (c.kind == KIND_F) {
     if (!LM || !LE || !costM || !costE) return -1;
     if (ctx_init(&cm, T, LM) || ctx_init(&ce, T, LE)) return -1;
-    if (cm.kind != KIND_M || ce.kind != KIND_E) return -1;
+    if (cm.kind != KIND_M || cm.parallel || ce.kind != KIND_E) return -1;
     for (int d = 1; d < 4; d++) if (!same_sizes(L, d, LM, d)) return -1;
     if (LM->n_sizes[0] != 1) return -1;
     if (!same_sizes(L, 1, LE, 1) || !same_sizes(L, 3, LE, 3)) return -1;
     for (int i = 0; i < 3; i++) if (cm.dt_axis[i] >= 0 || LM->base_dtype_bytes[i] != 4) return -1;
     cm.cost = (uint64_t*)costM; ce.cost = (uint64_t*)costE;
     c.depM = &cm; c.depE = &ce;
+  }
+  if (c.parallel) {             /* the serial-only Specs: the kind M table of the same lattice */
+    if (!LM || !costM) return -1;
+    if (ctx_init(&cm, T, LM)) return -1;
+    if (cm.kind != KIND_M || cm.parallel || cm.ndim != c.ndim) return -1;
+    for (int d = 0; d < 4; d++) if (!same_sizes(L, d, LM, d)) return -1;
+    for (int i = 0; i < 3; i++)
+      if (cm.lay_axis[i] != c.lay_axis[i] || cm.dt_axis[i] != c.dt_axis[i] ||
+          LM->base_dtype_bytes[i] != L->base_dtype_bytes[i]) return -1;
+    cm.cost = (uint64_t*)costM;
+    c.depM = &cm;
   }
   c.cost = cost; c.arg = arg;
   c.done = (uint8_t*)calloc(c.n, 1);

@@ -36,7 +36,9 @@ class _Target(C.Structure):
                 ("n_microkernels", C.c_uint32),
                 ("mk_kind", C.c_uint32 * 8),
                 ("mk_lanes", C.c_uint32 * 8),
-                ("mk_cost", C.c_uint64 * 8)]
+                ("mk_cost", C.c_uint64 * 8),
+                ("threads", C.c_uint32),
+                ("sync_cost", C.c_uint32)]
 
 
 class _Lattice(C.Structure):
@@ -87,6 +89,8 @@ def _target(t):
     s.n_microkernels = len(t["microkernels"])
     for j, (kind, lanes, cost) in enumerate(t["microkernels"]):
         s.mk_kind[j], s.mk_lanes[j], s.mk_cost[j] = kind, lanes, cost
+    s.threads = t.get("threads", 1)
+    s.sync_cost = t.get("sync_cost", 0)
     return s
 
 
@@ -127,7 +131,8 @@ def geometry(target, lattice):
 
 
 def solve(target, lattice, deps=None, goals=None):
-    """Fill the table.  deps = ((latticeM, costM), (latticeE, costE)) for kind F.
+    """Fill the table.  deps = ((latticeM, costM), (latticeE, costE)) for kind F,
+    ((latticeM, costM),) for kind P (the serial-only table of the same lattice).
     Returns dict(cost u64[N], argmin u16[N], n_admissible, n_rewrites, rc)."""
     T, L = _target(target), _lattice(lattice)
     ext, _, _ = geometry(target, lattice)
@@ -138,9 +143,11 @@ def solve(target, lattice, deps=None, goals=None):
     LM = LE = None
     cM = cE = None
     if deps is not None:
-        LM, LE = _lattice(deps[0][0]), _lattice(deps[1][0])
+        LM = _lattice(deps[0][0])
         cM = np.ascontiguousarray(deps[0][1], dtype=np.uint64)
-        cE = np.ascontiguousarray(deps[1][1], dtype=np.uint64)
+        if len(deps) > 1:
+            LE = _lattice(deps[1][0])
+            cE = np.ascontiguousarray(deps[1][1], dtype=np.uint64)
     g = None if goals is None else np.ascontiguousarray(goals, dtype=np.uint64)
     rc = lib().orc_solve(
         C.byref(T), C.byref(L),

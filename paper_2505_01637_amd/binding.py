@@ -219,6 +219,38 @@ class Table:
         return [(nd.table, tuple(nd.spec.x[:dims[nd.table]]), nd.rewrite, nd.cost, nd.n_children)
                 for nd in nodes[:n.value]]
 
+    def program_text(self, coord):
+        """The program of `coord` as indented text, one rewrite per line (the nesting of Section 2,
+        Figure 1: a Move or a loop encloses the Spec it leaves, a microkernel is a leaf)."""
+        tabs = (self,) + self._deps
+        lines, open_children = [], []
+        for t, x, rid, cost, k in self.schedule(coord):
+            tab = tabs[t]
+            sizes = tab.lattice["sizes"]
+            r = tab.rewrite_decode(rid)
+            if r.cls == 0:
+                what = "microkernel %d" % r.mk_index
+            elif r.cls == 1:
+                what = "move operand %d to level %d%s%s" % (r.operand_or_dim, r.dst_level,
+                                                           ", transposed" if r.transposed else "",
+                                                           ", converted" if r.convert else "")
+            elif r.cls == 2:
+                d = r.operand_or_dim
+                what = "loop over %s: %d steps of %d" % ("bmkn"[d], sizes[d][x[d]] // r.tile_size, r.tile_size)
+            else:
+                what = "bufferize: Matmul into the intermediate, then the epilogue"
+            lines.append("%stable %d  %s  %s  cost %d  %s" % ("  " * len(open_children), t,
+                         "x".join(str(sizes[d][x[d]]) for d in range(4)), tuple(x[4:]), cost, what))
+            if k:
+                open_children.append(k)
+            else:
+                while open_children:
+                    open_children[-1] -= 1
+                    if open_children[-1]:
+                        break
+                    open_children.pop()
+        return "\n".join(lines)
+
     def rewrite_decode(self, rid):
         r = Rewrite()
         _check(lib().mrl_rewrite_decode(self._h, C.c_uint16(rid), C.byref(r)))

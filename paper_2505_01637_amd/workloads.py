@@ -26,6 +26,7 @@ MK_VEC_ADDRELU = 4
 KIND_MATMUL_ACCUM = 0
 KIND_BIAS_ADD_RELU = 1
 KIND_FUSED_MM_ADD_RELU = 2
+KIND_MATMUL_PARALLEL = 3      # a Matmul whose serial-only flag is off; reads the KIND_MATMUL_ACCUM table
 
 MAX_LEVELS = 4
 MAX_OPERANDS = 5
@@ -59,6 +60,8 @@ def _empty_target(n_levels, capacities):
         "zero_coef": [0] * MAX_LEVELS,
         "loop_overhead": 0,
         "microkernels": [],   # list of (kind, lanes, cost); order = rewrite-id order
+        "threads": 1,         # hardware threads of a parallel loop
+        "sync_cost": 0,       # constant of a parallel loop
     }
 
 
@@ -160,8 +163,18 @@ def config(number, seed=None, max_size=None):
             ("F", _lattice(KIND_FUSED_MM_ADD_RELU, [one, r, r, r], layout=(1, 1, 0, 1, 0)),
              ["M", "E"]),
         ]
+    elif number == 6:
+        # beyond the five benchmark configurations: config 2's lattice twice, once serial-only
+        # and once with parallel loops allowed (8 threads, a synchronisation constant well above
+        # the loop constant)
+        t, _ = _four_level_target(rng)
+        t["threads"] = 8
+        t["sync_cost"] = rng.draw(64, 256)
+        r = keep(range(1, 65))
+        lats = [("M", _lattice(KIND_MATMUL_ACCUM, [one, r, r, r]), []),
+                ("P", _lattice(KIND_MATMUL_PARALLEL, [one, r, r, r]), ["M"])]
     else:
-        raise ValueError("config number must be 1..5")
+        raise ValueError("config number must be 1..6")
     return {"name": "config%d" % number, "target": t, "lattices": lats}
 
 

@@ -251,6 +251,8 @@ def test_schedule_parity(number, max_size, label):
         ref = S.preorder(S.extract(cfg["target"], cfg["lattices"], want, label, goal))
         mine = [(names[t], x, rw, c, k) for t, x, rw, c, k in tab.schedule(goal)]
         assert mine == ref
+        text = tab.program_text(goal).splitlines()
+        assert len(text) == len(mine) and not text[0].startswith(" ") and ("cost %d " % mine[0][3]) in text[0]
         n_nodes += len(mine)
     assert n_nodes > 100
     bad = int(np.flatnonzero(cost == np.uint64(O.INF))[0])

@@ -172,6 +172,52 @@ def test_brute_force_fused_pipeline():
     assert n > 100
 
 
+def parallel_setup(threads, sync, max_size=4):
+    cfg = W.config(1, seed=11, max_size=max_size)
+    t = cfg["target"]
+    t["loop_overhead"] = 2
+    t["threads"], t["sync_cost"] = threads, sync
+    lat_m = cfg["lattices"][0][1]
+    lat_p = dict(lat_m, kind=W.KIND_MATMUL_PARALLEL)
+    lats = [("M", lat_m, []), ("P", lat_p, ["M"])]
+    return t, lats, O.solve_config({"target": t, "lattices": lats})
+
+
+def test_brute_force_parallel_loops():
+    """Section 3's loop rule with threads > 1: ceil(trips / threads) * c(body) + s, the body being
+    serial-only (Section 2.2).  Three threads over sizes {1,2,3,4} exercise the rounding up (4
+    trips = 2 rounds, 2 and 3 trips = 1 round); every Spec up to volume 32 against the minimum
+    over all complete programs."""
+    t, lats, res = parallel_setup(threads=3, sync=7)
+    big = lambda s: s.dims[1] * s.dims[2] * s.dims[3] <= 32
+    n = brute_force_compare(t, lats, res, "P", pick=big)
+    assert n >= 400
+    cm, cp = res["M"]["cost"], res["P"]["cost"]
+    assert (cp <= cm).all() and (cp < cm).any()
+    assert ((cp == O.INF) == (cm == O.INF)).all()
+    _, _, ids = O.geometry(t, lats[1][1])
+    assert (res["P"]["argmin"][cp < cm] != res["M"]["argmin"][cp < cm]).any()
+    assert (res["P"]["argmin"][cp != O.INF] > ids["bufferize"]).any()        # parallel-loop ids are in use
+    # a closed form: 1x4x1x1 with everything in RF is 4 scalar FMAs; serial = 4*1 + 2, three
+    # threads = 2 rounds * 1 + 7: the serial loop stays; with 4 threads and s = 3: 1 + 3 wins
+    ext = res["P"]["extents"]
+    x = util.linear(ext, (0, 3, 0, 0, 0, 0, 0))
+    mk = t["microkernels"][0][2]
+    assert int(cm[x]) == 4 * mk + 2 and int(cp[x]) == min(4 * mk + 2, 2 * mk + 7)
+    t4, lats4, res4 = parallel_setup(threads=4, sync=3)
+    assert int(res4["P"]["cost"][x]) == mk + 3
+    assert int(res4["P"]["argmin"][x]) == ids["bufferize"] + 1 + 1 * ids["maxs"] + 0
+
+
+def test_parallel_table_with_one_thread_is_the_serial_table():
+    """threads = 1 and s equal to the loop constant make a parallel loop cost exactly what the
+    serial loop costs; ties go to the lower (serial) id, so both tables agree entry by entry."""
+    t, lats, res = parallel_setup(threads=1, sync=2, max_size=6)
+    assert np.array_equal(res["P"]["cost"], res["M"]["cost"])
+    assert np.array_equal(res["P"]["argmin"], res["M"]["argmin"])
+    assert res["P"]["n_rewrites"] > res["M"]["n_rewrites"]
+
+
 def test_closed_forms():
     """Special cases that reduce to closed forms."""
     # (i) scalar FMA only, s = 0: an all-RF spec costs m*k*n*k_fma whenever it fits

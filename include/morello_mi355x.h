@@ -73,6 +73,10 @@ typedef struct {
   uint32_t loop_overhead;                                     /* s of Section 3, paid by every loop */
   uint32_t n_microkernels;
   mrl_microkernel mk[MRL_MAX_MK];                             /* order = rewrite-id order          */
+  uint32_t threads;                                           /* Section 3: hardware threads a parallel
+                                                                 loop spreads its trips over; >= 1 for a
+                                                                 MATMUL_PARALLEL lattice, else ignored */
+  uint32_t sync_cost;                                         /* Section 3: constant of a parallel loop */
 } mrl_target_desc;
 
 typedef struct mrl_target mrl_target;
@@ -95,9 +99,17 @@ void mrl_target_destroy(mrl_target* t);
  * written); b and k must be pinned to 1.  FUSED_MM_ADD_RELU (Section 2.1,
  * Matmul -> bias add -> ReLU split once by bufferize): lhs, rhs, bias (read),
  * out (written), intermediate m*n f32; b pinned to 1; only m and n are tiled.
+ * MATMUL_PARALLEL (Section 2.2: the serial-only flag; Section 3: the loop
+ * rule with threads): the MATMUL_ACCUM Specs with the flag off.  Same
+ * operands, coordinates and rewrites as MATMUL_ACCUM, plus a parallel loop
+ * over b, m or n (not k, whose iterations accumulate into the same output):
+ * ceil(trips / threads) * cost of the body + sync_cost, where the body is
+ * the serial-only Spec of the smaller shape.  The serial-only Specs are the
+ * MATMUL_ACCUM table of the same lattice, passed as the one dependency: the
+ * flag is kept as two tables rather than as an axis of one.
  */
 typedef enum { MRL_KIND_MATMUL_ACCUM = 0, MRL_KIND_BIAS_ADD_RELU = 1,
-               MRL_KIND_FUSED_MM_ADD_RELU = 2 } mrl_kind;
+               MRL_KIND_FUSED_MM_ADD_RELU = 2, MRL_KIND_MATMUL_PARALLEL = 3 } mrl_kind;
 
 typedef struct {
   uint32_t kind;
@@ -165,8 +177,10 @@ int32_t mrl_query(const mrl_table* tab, const mrl_coord* specs, size_t n,
  *   [0, n_mk)                       select(microkernel j)
  *   then ((operand*(n_levels-1) + dst)*2 + transposed)*2 + convert   Moves
  *   then dim*max_sizes + index of the tile size                      tiles
- *   then one id                                                      bufferize */
-typedef struct { uint8_t cls; /* 0 microkernel, 1 move, 2 tile, 3 bufferize */
+ *   then one id                                                      bufferize
+ *   then dim*max_sizes + index of the tile size                      parallel loops
+ *                                                                    (MATMUL_PARALLEL) */
+typedef struct { uint8_t cls; /* 0 microkernel, 1 move, 2 tile, 3 bufferize, 4 parallel loop */
                  uint8_t operand_or_dim, dst_level, transposed, convert;
                  uint32_t tile_size, mk_index; } mrl_rewrite;
 int32_t mrl_rewrite_decode(const mrl_table* tab, uint16_t id, mrl_rewrite* out);

@@ -42,7 +42,9 @@ class _TargetDesc(C.Structure):
                 ("zero_coef", C.c_uint32 * 4),
                 ("loop_overhead", C.c_uint32),
                 ("n_microkernels", C.c_uint32),
-                ("mk", _Microkernel * 8)]
+                ("mk", _Microkernel * 8),
+                ("threads", C.c_uint32),
+                ("sync_cost", C.c_uint32)]
 
 
 class _LatticeDesc(C.Structure):
@@ -120,6 +122,8 @@ def _target_desc(t):
     d.n_microkernels = len(t["microkernels"])
     for j, (kind, lanes, cost) in enumerate(t["microkernels"][:8]):
         d.mk[j].kind, d.mk[j].lanes, d.mk[j].cost = kind, lanes, cost
+    d.threads = t.get("threads", 1)
+    d.sync_cost = t.get("sync_cost", 0)
     return d
 
 
@@ -237,6 +241,10 @@ class Table:
             elif r.cls == 2:
                 d = r.operand_or_dim
                 what = "loop over %s: %d steps of %d" % ("bmkn"[d], sizes[d][x[d]] // r.tile_size, r.tile_size)
+            elif r.cls == 4:
+                d = r.operand_or_dim
+                what = "parallel loop over %s: %d steps of %d, serial-only body" % (
+                    "bmkn"[d], sizes[d][x[d]] // r.tile_size, r.tile_size)
             else:
                 what = "bufferize: Matmul into the intermediate, then the epilogue"
             lines.append("%stable %d  %s  %s  cost %d  %s" % ("  " * len(open_children), t,

@@ -139,16 +139,23 @@ int32_t validate_target(const mrl_target_desc* d) {
 
 int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c) {
   if (!L) return fail(MRL_E_INVAL, "lattice descriptor is NULL");
-  if (L->kind > MRL_KIND_FUSED_MM_ADD_RELU) return fail(MRL_E_INVAL, "unknown spec kind %u", L->kind);
+  if (L->kind > MRL_KIND_MATMUL_PARALLEL) return fail(MRL_E_INVAL, "unknown spec kind %u", L->kind);
+  // A parallel lattice is a Matmul lattice (same operator, operands and coordinates) with more rewrites.
+  const bool parallel = L->kind == MRL_KIND_MATMUL_PARALLEL;
+  const uint32_t kind = parallel ? (uint32_t)kKindM : L->kind;
+  if (parallel && T.threads < 1) return fail(MRL_E_INVAL, "a MATMUL_PARALLEL lattice needs threads >= 1");
   c.target = T;
   c.lat = *L;
   DevParams& P = c.P;
   memset(&P, 0, sizeof P);
-  P.kind = L->kind;
-  P.nops = L->kind == kKindF ? 4 : 3;
-  P.nlv = L->kind == kKindF ? 5 : 3;
+  P.kind = kind;
+  P.par = parallel ? 1u : 0u;
+  P.threads = parallel ? T.threads : 1u;
+  P.sync = T.sync_cost;
+  P.nops = kind == kKindF ? 4 : 3;
+  P.nlv = kind == kKindF ? 5 : 3;
   P.NL = T.n_levels;
-  P.npass = L->kind == kKindF ? P.NL : 1;
+  P.npass = kind == kKindF ? P.NL : 1;
   P.ncombo = ipow(P.NL, P.nops);
   uint64_t max_vol = 1;
   uint32_t maxs = 0;
@@ -166,8 +173,8 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
     if (max_vol >= (1ull << 48)) return fail(MRL_E_INVAL, "b*m*k*n must stay below 2^48");
     maxs = std::max(maxs, n);
   }
-  if (L->kind != kKindM && L->n_sizes[0] != 1) return fail(MRL_E_INVAL, "this kind has no batch dimension");
-  if (L->kind == kKindE && L->n_sizes[2] != 1) return fail(MRL_E_INVAL, "BIAS_ADD_RELU has no k dimension");
+  if (kind != kKindM && L->n_sizes[0] != 1) return fail(MRL_E_INVAL, "this kind has no batch dimension");
+  if (kind == kKindE && L->n_sizes[2] != 1) return fail(MRL_E_INVAL, "BIAS_ADD_RELU has no k dimension");
   P.shape_stride[3] = 1;
   for (int d = 2; d >= 0; d--) P.shape_stride[d] = P.shape_stride[d + 1] * P.nsz[d + 1];
   c.n_shapes = P.shape_stride[0] * P.nsz[0];
@@ -177,11 +184,11 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
   for (uint32_t i = 0; i < P.nops; i++) {
     P.nlay += L->layout_coord[i] ? 1 : 0;
     P.ndt += L->dtype_coord[i] ? 1 : 0;
-    if (L->dtype_coord[i] && !(L->kind == kKindM && i < 2)) return fail(MRL_E_INVAL, "dtype bit only on MatmulAccum inputs");
-    if (L->base_dtype_bytes[i] != 4 && !(L->base_dtype_bytes[i] == 2 && L->kind == kKindM))
+    if (L->dtype_coord[i] && !(kind == kKindM && i < 2)) return fail(MRL_E_INVAL, "dtype bit only on MatmulAccum inputs");
+    if (L->base_dtype_bytes[i] != 4 && !(L->base_dtype_bytes[i] == 2 && kind == kKindM))
       return fail(MRL_E_INVAL, "base_dtype_bytes[%u] must be 4 (or 2 on a MatmulAccum)", i);
     P.base_bf16[i] = L->base_dtype_bytes[i] == 2;
-    P.access[i] = L->kind == kKindM ? (i == 2 ? kRmw : kRead) : (i == P.nops - 1 ? kWrite : kRead);
+    P.access[i] = kind == kKindM ? (i == 2 ? kRmw : kRead) : (i == P.nops - 1 ? kWrite : kRead);
     P.lvpow[i] = ipow(P.NL, P.nops - 1 - i);
     P.pack_shift[i] = 2 * (P.nops - 1 - i);
   }
@@ -215,7 +222,8 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
   P.move_base = P.nmk;
   P.tile_base = P.move_base + P.nops * (P.NL - 1) * 4;
   P.buf_id = P.tile_base + 4 * maxs;
-  if (P.buf_id >= kNone) return fail(MRL_E_INVAL, "rewrite ids do not fit 16 bits");
+  P.par_base = P.buf_id + 1;
+  if ((parallel ? P.par_base + 4 * maxs : P.buf_id) >= kNone) return fail(MRL_E_INVAL, "rewrite ids do not fit 16 bits");
 
   // Moves: coefficient per (operand, src, dst, transposed) and the list of Moves that can occur
   for (uint32_t i = 0; i < P.nops; i++)
@@ -263,7 +271,7 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
 
   // tiles: for (dim, size index) the smaller allowed sizes dividing it
   for (int d = 0; d < 4; d++) {
-    P.tile_dim_ok[d] = L->kind == kKindM || d == 1 || d == 3;
+    P.tile_dim_ok[d] = kind == kKindM || d == 1 || d == 3;
     for (uint32_t j = 0; j < P.nsz[d]; j++) {
       P.tile_off[d][j] = (uint32_t)c.tiles.size();
       if (P.tile_dim_ok[d])
@@ -375,7 +383,7 @@ bool same_problem(const Compiled& c, const mrl_target_desc& T, const mrl_lattice
 int32_t get_compiled(const mrl_target_desc& T, const mrl_lattice_desc* L, CompiledPtr& out) {
   static std::mutex mu;
   static std::vector<CompiledPtr> cache;          // most recent last, at most 8
-  if (L && L->kind <= MRL_KIND_FUSED_MM_ADD_RELU) {
+  if (L && L->kind <= MRL_KIND_MATMUL_PARALLEL) {
     std::lock_guard<std::mutex> lock(mu);
     for (size_t i = cache.size(); i-- > 0;)
       if (same_problem(*cache[i], T, *L)) { out = cache[i]; return MRL_OK; }
@@ -540,8 +548,20 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
     tab->deps[0] = deps[0]; tab->deps[1] = deps[1];
     P.GM = M.P.G; P.VM = M.P.V; P.GE = E.P.G; P.VE = E.P.V; P.nszE_n = E.P.nsz[3];
     for (int i = 0; i < 3; i++) { P.layM[i] = M.P.lay_bit[i]; P.layE[i] = E.P.lay_bit[i]; }
+  } else if (P.par) {
+    if (n_deps != 1 || !deps || !deps[0]) return fail(MRL_E_INVAL, "a MATMUL_PARALLEL lattice needs deps = {MATMUL_ACCUM table of the same lattice}");
+    const Compiled& M = *deps[0]->cp;
+    if (M.P.kind != kKindM || M.P.par) return fail(MRL_E_INVAL, "the dep must be a MATMUL_ACCUM table");
+    if (memcmp(&M.target, &t->d, sizeof t->d)) return fail(MRL_E_INVAL, "the dep was solved for another target");
+    for (int d = 0; d < 4; d++) if (M.sizes[d] != c.sizes[d]) return fail(MRL_E_INVAL, "the MATMUL_ACCUM dep has other size lists");
+    if (memcmp(M.lat.layout_coord, c.lat.layout_coord, sizeof c.lat.layout_coord) ||
+        memcmp(M.lat.dtype_coord, c.lat.dtype_coord, sizeof c.lat.dtype_coord) ||
+        memcmp(M.lat.base_dtype_bytes, c.lat.base_dtype_bytes, 3) || M.n_specs != c.n_specs || M.P.G != P.G)
+      return fail(MRL_E_INVAL, "the MATMUL_ACCUM dep has other coordinates");
+    P.costM = deps[0]->d_cost;
+    tab->deps[0] = deps[0];
   } else if (n_deps != 0) {
-    return fail(MRL_E_INVAL, "only a FUSED lattice takes deps");
+    return fail(MRL_E_INVAL, "only FUSED and MATMUL_PARALLEL lattices take deps");
   }
 
   std::lock_guard<std::mutex> solve_lock(c.solve_mu);
@@ -846,6 +866,10 @@ int32_t mrl_rewrite_decode(const mrl_table* tab, uint16_t id, mrl_rewrite* out) 
     return MRL_OK;
   }
   if (id == P.buf_id && P.kind == kKindF) { out->cls = 3; return MRL_OK; }
+  if (P.par && id >= P.par_base && id < P.par_base + 4 * P.maxs) {
+    const uint32_t r = id - P.par_base, d = r / P.maxs, j = r % P.maxs;
+    if (d != 2 && j < P.nsz[d]) { out->cls = 4; out->operand_or_dim = (uint8_t)d; out->tile_size = P.sizes[d][j]; return MRL_OK; }
+  }
   return fail(MRL_E_RANGE, "rewrite id %u is not used by this table", id);
 }
 
@@ -906,6 +930,13 @@ int32_t mrl_schedule(const mrl_table* tab, const mrl_coord* goal, mrl_schedule_n
     } else if (r.cls == 2) {                // tile: the loop body is the Spec with the smaller size
       const uint32_t d = r.operand_or_dim, j = (rw - P.tile_base) % P.maxs;
       Item ch = it;
+      ch.x.x[d] = j;
+      stack.push_back(ch);
+      node.n_children = 1;
+    } else if (r.cls == 4) {                // parallel loop: the body is the serial-only Spec of the smaller size
+      if (it.which != 0 || !it.t->deps[0]) return fail(MRL_E_HIP, "internal error: parallel loop outside a MATMUL_PARALLEL table");
+      const uint32_t d = r.operand_or_dim, j = (rw - P.par_base) % P.maxs;
+      Item ch{it.t->deps[0], 1u, it.x};
       ch.x.x[d] = j;
       stack.push_back(ch);
       node.n_children = 1;

@@ -60,13 +60,17 @@ struct DevParams {
   const uint8_t* mk_entry;   // device, [256][V]
   // ---- rewrite ids ----
   uint32_t move_base, tile_base, buf_id, maxs;
+  // ---- parallel loops (a Matmul whose serial-only flag is off; kind stays kKindM) ----
+  uint32_t par;              // 1: also evaluate parallel loops over b, m, n; their bodies are read from costM
+  uint32_t par_base;         // first id of the parallel loops: par_base + dim * maxs + index of the tile size
+  uint32_t threads, sync;    // rounds = ceil(trips / threads); constant added per parallel loop
   // ---- operand-level combos ordered by rank (sum of operand levels) ----
   uint32_t nranks;
   uint32_t rank_off[kMaxRanks + 2];
   // per rank-major position: pack | (operands resident in level l, one nibble per level) << 8
   // | (r + 1) << 24 at the first position of rank r
   uint32_t pos_info[kMaxCombo];
-  // ---- tables a FUSED lattice reads ----
+  // ---- tables a FUSED lattice reads (costM also: the serial table a parallel lattice reads) ----
   const uint64_t* costM;
   const uint64_t* costE;
   uint32_t GM, VM, GE, VE, nszE_n;

@@ -242,7 +242,8 @@ struct Prefetch {
   bool tvalid;
 };
 
-// Tile rewrite e0 + thread of this shape (dims in order, sizes ascending).
+// Tile rewrite e0 + thread of this shape (dims in order, sizes ascending).  With parallel loops
+// the same lists of b, m and n follow once more: td = 4 + dim, trips = rounds of `threads` trips.
 template <int T>
 __device__ __forceinline__ void fetch_tile(const DevParams* __restrict__ P, const Shape& S, uint32_t e0, uint32_t n_tile,
                                            TileEntry& te, uint32_t& td, bool& valid) {
@@ -260,8 +261,33 @@ __device__ __forceinline__ void fetch_tile(const DevParams* __restrict__ P, cons
       if (e >= first && e < first + cnt) { td = a; q = lo + (e - first); }
       first += cnt;
     }
+    if (P->par) {
+#pragma unroll
+      for (int a = 0; a < 4; a++) {
+        if (a == 2) continue;
+        const uint32_t lo = P->tile_off[a][S.si[a]];
+        const uint32_t cnt = P->tile_off[a][S.si[a] + 1] - lo;
+        if (e >= first && e < first + cnt) { td = 4 + a; q = lo + (e - first); }
+        first += cnt;
+      }
+    }
     te = P->tiles[q];
+    if (td >= 4) te.trips = (te.trips + P->threads - 1) / P->threads;
   }
+}
+
+// Tile rewrites of a shape: the serial loops, and with parallel loops those over b, m, n again.
+__device__ __forceinline__ void count_tiles(const DevParams* __restrict__ P, const Shape& S, uint32_t& n_serial,
+                                            uint32_t& n_tile) {
+  n_serial = 0;
+  uint32_t n_par = 0;
+#pragma unroll
+  for (int d = 0; d < 4; d++) {
+    const uint32_t cnt = P->tile_off[d][S.si[d] + 1] - P->tile_off[d][S.si[d]];
+    if (P->tile_dim_ok[d]) n_serial += cnt;
+    if (P->par && d != 2) n_par += cnt;
+  }
+  n_tile = n_serial + n_par;
 }
 
 // ... into LDS: table offset of the sub-shape's group, trip count, rewrite id.
@@ -270,11 +296,12 @@ __device__ __forceinline__ void store_tile(const DevParams* __restrict__ P, cons
                                            const TileEntry& te, uint32_t d, bool valid) {
   const uint32_t tid = T == 64 ? (threadIdx.x & 63u) : threadIdx.x;
   if (valid) {
-    const uint32_t j = d == 0 ? S.si[0] : d == 1 ? S.si[1] : d == 2 ? S.si[2] : S.si[3];
-    const uint32_t stride = d == 0 ? P->shape_stride[0] : d == 1 ? P->shape_stride[1] : d == 2 ? P->shape_stride[2] : P->shape_stride[3];
-    L.tl_base[tid] = (uint64_t)(shape - (j - te.jt) * stride) * P->G;
+    const uint32_t dd = d & 3u;
+    const uint32_t j = dd == 0 ? S.si[0] : dd == 1 ? S.si[1] : dd == 2 ? S.si[2] : S.si[3];
+    const uint32_t stride = dd == 0 ? P->shape_stride[0] : dd == 1 ? P->shape_stride[1] : dd == 2 ? P->shape_stride[2] : P->shape_stride[3];
+    L.tl_base[tid] = (uint64_t)(shape - (j - te.jt) * stride) * P->G;      // the serial table has the same geometry
     L.tl_trips[tid] = te.trips;
-    L.tl_id[tid] = P->tile_base + d * P->maxs + te.jt;
+    L.tl_id[tid] = (d >= 4 ? P->par_base : P->tile_base) + dd * P->maxs + te.jt;
   }
 }
 
@@ -306,17 +333,20 @@ __device__ __forceinline__ void build_move_costs(const DevParams* __restrict__ P
 
 // Tile candidates first, first + step, ... < n_here of the ones staged in LDS, for one task: the
 // sub-Spec sits at the same offset `off` inside a smaller shape's group.  trips * sub + s in 96
-// bits; reaching 2^62 = overflow.
+// bits; reaching 2^62 = overflow.  Candidates from par_from on are parallel loops: their body is
+// the serial-only Spec (read from the serial table) and their constant is the synchronisation cost.
 __device__ __forceinline__ void task_tiles(const DevParams* __restrict__ P, const UnitLds& L, uint32_t n_here,
-                                           uint32_t first, uint32_t step, uint32_t off,
+                                           uint32_t par_from, uint32_t first, uint32_t step, uint32_t off,
                                            const uint64_t* __restrict__ cost, Eval& e) {
-  const uint64_t s = P->s;
+  const uint64_t s_serial = P->s, s_par = P->sync;
+  const uint64_t* __restrict__ serial = P->costM;
   for (uint32_t t0 = first; t0 < n_here; t0 += kBatch * step) {
     uint64_t sub[kBatch];
 #pragma unroll
     for (int u = 0; u < kBatch; u++) {
       const uint32_t t = t0 + u * step;
-      sub[u] = cost[L.tl_base[t < n_here ? t : n_here - 1] + off];
+      const uint32_t tt = t < n_here ? t : n_here - 1;
+      sub[u] = (tt >= par_from ? serial : cost)[L.tl_base[tt] + off];
     }
 #pragma unroll
     for (int u = 0; u < kBatch; u++) {
@@ -326,7 +356,7 @@ __device__ __forceinline__ void task_tiles(const DevParams* __restrict__ P, cons
         const uint32_t a = L.tl_trips[t];
         const uint64_t lo = (uint64_t)a * (uint32_t)sub[u];
         const uint64_t hi = (uint64_t)a * (uint32_t)(sub[u] >> 32) + (lo >> 32);   // bits 32.. of the product
-        const uint64_t c = ((hi << 32) | (uint32_t)lo) + s;
+        const uint64_t c = ((hi << 32) | (uint32_t)lo) + (t >= par_from ? s_par : s_serial);
         const bool over = fin & (((hi >> 30) != 0) | (c >= kLimit));
         e.ovf |= over ? 1u : 0u;
         consider(e, c, L.tl_id[t], fin & !over);
@@ -441,9 +471,8 @@ __device__ __forceinline__ void solve_unit(const DevParams* __restrict__ P, cons
   const uint32_t ncombo = P->ncombo;
   const uint64_t group = (uint64_t)shape * P->G;
   const Hot H = load_hot(P);
-  uint32_t n_tile = 0;
-#pragma unroll
-  for (int d = 0; d < 4; d++) if (P->tile_dim_ok[d]) n_tile += P->tile_off[d][S.si[d] + 1] - P->tile_off[d][S.si[d]];
+  uint32_t n_serial, n_tile;
+  count_tiles(P, S, n_serial, n_tile);
   Prefetch<T> pre;
   prefetch_unit<T>(P, S, n_tile, pre);
 
@@ -585,6 +614,7 @@ __device__ __forceinline__ void solve_unit(const DevParams* __restrict__ P, cons
     store_tile<T>(P, L, S, shape, pre.te, pre.td, pre.tvalid);
     unit_sync<T>();
     const uint32_t n_here = n_tile - e0 < kTileLds ? n_tile - e0 : kTileLds;
+    const uint32_t par_from = n_serial > e0 ? (n_serial - e0 < n_here ? n_serial - e0 : n_here) : 0u;
     if (n_task * 2 <= T) {
       // few tasks: a quad of lanes per task, every fourth candidate each (fewer reads one after the other)
       for (uint32_t qb = 0; qb < n_task; qb += T / 4) {
@@ -598,7 +628,7 @@ __device__ __forceinline__ void solve_unit(const DevParams* __restrict__ P, cons
           if (e0 == 0) { if (P->kind == kKindF) task_bufferize(P, S, shape, xpack, v, e); }
           else { e.best = L.t_cost[q]; e.arg = sp >> 16; }
         }
-        task_tiles(P, L, n_here, sub4, 4, entry_offset(H, xpack, v), cost, e);
+        task_tiles(P, L, n_here, par_from, sub4, 4, entry_offset(H, xpack, v), cost, e);
         if (active) tot.ovf |= e.ovf;
         quad_min<0xB1>(e);
         quad_min<0x4E>(e);
@@ -619,7 +649,7 @@ __device__ __forceinline__ void solve_unit(const DevParams* __restrict__ P, cons
         } else {
           e.best = L.t_cost[q]; e.arg = sp >> 16;
         }
-        task_tiles(P, L, n_here, 0, 1, entry_offset(H, xpack, v), cost, e);
+        task_tiles(P, L, n_here, par_from, 0, 1, entry_offset(H, xpack, v), cost, e);
         L.t_cost[q] = e.best;
         L.t_spec[q] = (sp & 0xFFFFu) | e.arg << 16;
         tot.ovf |= e.ovf;

@@ -132,6 +132,46 @@ def test_compressed_query_one_box_and_long_axis():
     check_compressed_queries(got["M"], want["M"], 10**9, seed=1)
 
 
+@pytest.mark.parametrize("max_size,threads,sync", [(16, 8, None), (12, 3, 7), (20, 1, 2), (64, 8, None)])
+def test_parity_parallel_loops(max_size, threads, sync):
+    """Parallel loops (Section 3's loop rule with threads; Section 2.2's serial-only flag): the
+    serial table and the table that may use parallel loops, all outputs; three threads over sizes
+    1..12 round up unevenly, one thread with the loop constant reproduces the serial costs, and
+    the last case is the full 64^3 lattice (16.8 M Specs per table)."""
+    cfg = W.config(6, max_size=max_size)
+    cfg["target"]["threads"] = threads
+    if sync is not None:
+        cfg["target"]["sync_cost"] = sync
+        cfg["target"]["loop_overhead"] = 2
+    _, got, want = compare_config(cfg, scratch_bytes=(2 << 30) if max_size == 64 else None)
+    cp, cm = got["P"].dense()[0], got["M"].dense()[0]
+    if threads == 1:
+        assert np.array_equal(cp, cm)
+    else:
+        assert (cp <= cm).all() and (cp < cm).any()
+    check_compressed_queries(got["P"], want["P"], 100_000, seed=threads)
+
+
+def test_parity_parallel_loops_with_layout_and_dtype_bits():
+    """The parallel kind on a lattice with layout and dtype coordinates (config 3's structure)."""
+    cfg = W.config(3, max_size=64)
+    label, lat, _ = cfg["lattices"][0]
+    cfg["target"]["threads"], cfg["target"]["sync_cost"] = 4, 5
+    cfg["lattices"] = [("M", lat, []), ("P", dict(lat, kind=W.KIND_MATMUL_PARALLEL), ["M"])]
+    compare_config(cfg)
+    B = _binding()
+    # a parallel lattice without its serial table, and with a table of another lattice
+    with pytest.raises(B.MorelloError) as e:
+        B.solve(B.Target(cfg["target"]), cfg["lattices"][1][1])
+    assert e.value.code == B.E_INVAL
+    other = W.config(3, max_size=32)
+    t = B.Target(cfg["target"])
+    tab = B.solve(t, other["lattices"][0][1])
+    with pytest.raises(B.MorelloError) as e:
+        B.solve(t, cfg["lattices"][1][1], deps=[tab])
+    assert e.value.code == B.E_INVAL
+
+
 def test_degenerate_lattices():
     B = _binding()
     # a single shape: every dimension pinned
@@ -230,7 +270,8 @@ def test_deterministic():
 
 
 @pytest.mark.gpu
-@pytest.mark.parametrize("number,max_size,label", [(1, None, "M"), (3, 64, "M"), (4, 8, "M"), (5, 8, "F"), (5, 8, "E")])
+@pytest.mark.parametrize("number,max_size,label", [(1, None, "M"), (3, 64, "M"), (4, 8, "M"), (5, 8, "F"), (5, 8, "E"),
+                                                   (6, 16, "P")])
 def test_schedule_parity(number, max_size, label):
     """mrl_schedule walks the same programs as the oracle's extraction: same Specs, rewrites and
     costs, node by node in pre-order; a goal without implementation is an error."""

@@ -21,16 +21,19 @@ exponentially with the number of divisors and levels.
 from collections import namedtuple
 
 M, E, F, P = 0, 1, 2, 3      # P: a Matmul that may use parallel loops; M is serial-only
+BD = 4                       # a Matmul whose Specs carry per-level memory bounds (Sections 2.2, 2.4.4)
+MATMULS = (M, P, BD)
 FMA, BCAST, BF16DOT, S_ADDRELU, V_ADDRELU = 0, 1, 2, 3, 4
 
 # dims = (b, m, k, n) actual sizes; levels per operand (F: 5th = intermediate);
 # layouts / bf16 per operand (0 where the lattice has no such coordinate)
-Spec = namedtuple("Spec", "kind dims levels layouts bf16")
+# limits (kind BD): bytes a program may still allocate per level, None = unbounded level
+Spec = namedtuple("Spec", "kind dims levels layouts bf16 limits", defaults=((),))
 
 
 def operand_numel(spec, i):
     b, m, k, n = spec.dims
-    if spec.kind in (M, P):
+    if spec.kind in MATMULS:
         return (b * m * k, b * k * n, b * m * n)[i]
     if spec.kind == E:
         return (m * n, n, m * n)[i]
@@ -39,7 +42,7 @@ def operand_numel(spec, i):
 
 def operand_mode(kind, i):
     """'r' read, 'rw' accumulate, 'w' write-only."""
-    if kind in (M, P):
+    if kind in MATMULS:
         return "rw" if i == 2 else "r"
     if kind == E:
         return "w" if i == 2 else "r"
@@ -47,6 +50,8 @@ def operand_mode(kind, i):
 
 
 def fits(target, spec):
+    if spec.kind == BD:
+        return True          # the bounds decide at each allocation, not the operands' footprint
     used = [0] * target["n_levels"]
     nops = 4 if spec.kind == F else 3
     for i in range(nops):
@@ -61,15 +66,15 @@ def microkernel_reps(target, lattice, spec, j):
     b, m, k, n = spec.dims
     lv, ly, bf = spec.levels, spec.layouts, spec.bf16
     if kind == FMA:
-        ok = spec.kind in (M, P) and (b, m, k, n) == (1, 1, 1, 1) and tuple(lv[:3]) == (0, 0, 0) and not any(bf[:3])
+        ok = spec.kind in MATMULS and (b, m, k, n) == (1, 1, 1, 1) and tuple(lv[:3]) == (0, 0, 0) and not any(bf[:3])
         return 1 if ok else 0
     if kind == BCAST:
-        ok = (spec.kind in (M, P) and (b, m, k) == (1, 1, 1) and n % lanes == 0
+        ok = (spec.kind in MATMULS and (b, m, k) == (1, 1, 1) and n % lanes == 0
               and tuple(lv[:3]) == (0, 1, 1) and not any(bf[:3]) and ly[1] == 0 and ly[2] == 0)
         return n // lanes if ok else 0
     if kind == BF16DOT:
         rhs_col = ly[1] == 1 or not lattice["layout_coord"][1]
-        ok = (spec.kind in (M, P) and (b, m, n) == (1, 1, 1) and k % lanes == 0
+        ok = (spec.kind in MATMULS and (b, m, n) == (1, 1, 1) and k % lanes == 0
               and tuple(lv[:3]) == (1, 1, 0) and bf[0] and bf[1] and not bf[2] and rhs_col)
         return k // lanes if ok else 0
     if kind == S_ADDRELU:
@@ -123,6 +128,16 @@ def rewrites(target, lattices, spec):
                     if cv:
                         bf[i] = 0
                     child = spec._replace(levels=tuple(lv), layouts=tuple(ly), bf16=tuple(bf))
+                    if spec.kind == BD and spec.limits[dst] is not None:
+                        # the buffer in dst comes out of dst's bound; what is left is rounded
+                        # down to a power of two (or is zero)
+                        need = operand_numel(spec, i) * (2 if bf[i] else 4)
+                        if need > spec.limits[dst]:
+                            continue
+                        left = spec.limits[dst] - need
+                        lim = list(spec.limits)
+                        lim[dst] = 0 if left == 0 else 1 << (left.bit_length() - 1)
+                        child = child._replace(limits=tuple(lim))
                     rid = move_base + ((i * (nl - 1) + dst) * 2 + x) * 2 + cv
                     yield rid, ("alloc", coef * operand_numel(spec, i)), [child]
     for d in range(4):

@@ -27,6 +27,9 @@
  * The fused three-node lattice (kind 2) follows this build's own reading of
  * Section 2.1; it is pinned by brute force only: "parity unpinned" by the
  * paper beyond the sum rule of Section 3.
+ * Kind 3 adds the parallel loops of Section 3; kind 4 replaces the
+ * admissibility test by the per-level memory bounds of Sections 2.2 and
+ * 2.4.4, carried as coordinates (expand(), part B).
  */
 #include <stdint.h>
 #include <stdlib.h>
@@ -39,7 +42,7 @@
 enum { ORC_MAXL = 4, ORC_MAXOPS = 5, ORC_MAXD = 16, ORC_MAXMK = 8 };
 enum { MK_SCALAR_FMA = 0, MK_BCAST_VEC_MULADD = 1, MK_BF16_DOT = 2,
        MK_SCALAR_ADDRELU = 3, MK_VEC_ADDRELU = 4 };
-enum { KIND_M = 0, KIND_E = 1, KIND_F = 2, KIND_P = 3 };
+enum { KIND_M = 0, KIND_E = 1, KIND_F = 2, KIND_P = 3, KIND_B = 4 };
 enum { ACC_READ = 0, ACC_RMW = 1, ACC_WRITE = 2 };
 
 typedef struct {
@@ -73,6 +76,8 @@ typedef struct {
   uint8_t level[ORC_MAXOPS];    /* per operand; kind F: level[4] = intermediate */
   uint8_t layout[ORC_MAXOPS];   /* 0 row-major, 1 column-major */
   uint8_t bf16[ORC_MAXOPS];     /* 0 f32, 1 bf16 */
+  uint8_t limit[ORC_MAXL];      /* kind B: per bounded level, index of the memory bound: 0 -> 0 bytes,
+                                   q -> 2^(q-1) bytes */
 } spec_t;
 
 typedef struct ctx {
@@ -88,6 +93,8 @@ typedef struct ctx {
   uint8_t* done;
   uint32_t maxs, nmk, move_base, tile_base, buf_id, par_base;
   int parallel;                 /* kind P: a Matmul whose serial-only flag is off */
+  int bounded;                  /* kind B: a Matmul whose Specs carry per-level memory bounds */
+  int lim_axis[ORC_MAXL];       /* coordinate axis of level l's bound, -1 if the level is unbounded */
   uint64_t n_rewrites, n_admissible;
   int overflow;
   const struct ctx* depM;
@@ -102,7 +109,8 @@ typedef struct ctx {
 static int ctx_init(ctx* c, const orc_target* T, const orc_lattice* L) {
   memset(c, 0, sizeof *c);
   c->T = T; c->L = L; c->kind = (int)L->kind;
-  if (c->kind < 0 || c->kind > 3) return -1;
+  if (c->kind < 0 || c->kind > 4) return -1;
+  if (c->kind == KIND_B) { c->kind = KIND_M; c->bounded = 1; }
   if (c->kind == KIND_P) {      /* same operator, operands and coordinates as kind M */
     c->kind = KIND_M; c->parallel = 1;
     if (T->threads < 1) return -1;
@@ -122,6 +130,17 @@ static int ctx_init(ctx* c, const orc_target* T, const orc_lattice* L) {
   if (c->kind != KIND_M && L->n_sizes[0] != 1) return -1;   /* no batch on E, F */
   if (c->kind == KIND_E && L->n_sizes[2] != 1) return -1;   /* E has no k */
   for (int i = 0; i < c->nlv; i++) c->ext[d++] = T->n_levels;
+  /* Memory bounds (Section 2.2, field 5; Section 4.1: limits are powers of two): one axis per
+   * level with a finite capacity; the values are 0, 1, 2, 4, ... up to the capacity. */
+  for (int l = 0; l < ORC_MAXL; l++) c->lim_axis[l] = -1;
+  if (c->bounded)
+    for (uint32_t l = 0; l < T->n_levels; l++) {
+      if (T->capacity_bytes[l] == UINT64_MAX) continue;
+      uint32_t nq = 1;
+      while (nq < 64 && ((uint64_t)1 << (nq - 1)) <= T->capacity_bytes[l]) nq++;
+      if (nq > 255) return -1;
+      c->lim_axis[l] = d; c->ext[d++] = nq;
+    }
   for (int i = 0; i < ORC_MAXOPS; i++) { c->lay_axis[i] = -1; c->dt_axis[i] = -1; }
   for (int i = 0; i < c->nops; i++)
     if (L->layout_coord[i]) { c->lay_axis[i] = d; c->ext[d++] = 2; }
@@ -151,6 +170,8 @@ static uint64_t spec_index(const ctx* c, const spec_t* s) {
     if (c->lay_axis[i] >= 0) x += s->layout[i] * c->stride[c->lay_axis[i]];
     if (c->dt_axis[i] >= 0) x += s->bf16[i] * c->stride[c->dt_axis[i]];
   }
+  for (int l = 0; l < ORC_MAXL; l++)
+    if (c->lim_axis[l] >= 0) x += s->limit[l] * c->stride[c->lim_axis[l]];
   return x;
 }
 
@@ -165,6 +186,8 @@ static void spec_of_index(const ctx* c, uint64_t x, spec_t* s) {
     if (c->dt_axis[i] >= 0) s->bf16[i] = (uint8_t)coord[c->dt_axis[i]];
     else s->bf16[i] = c->L->base_dtype_bytes[i] == 2;
   }
+  for (int l = 0; l < ORC_MAXL; l++)
+    if (c->lim_axis[l] >= 0) s->limit[l] = (uint8_t)coord[c->lim_axis[l]];
 }
 
 /* ------------------------------------------------------------------ */
@@ -194,6 +217,7 @@ static int access_of(const ctx* c, int op) {
  * (the per-level memory bound of Section 2.2, applied to the Spec's own
  * operands; kind F also counts its intermediate). */
 static int admissible(const ctx* c, const spec_t* s) {
+  if (c->bounded) return 1;     /* the bounds, not the operands' footprint, limit what a Spec may do */
   for (uint32_t l = 0; l < c->T->n_levels; l++) {
     unsigned __int128 bytes = 0;
     for (int i = 0; i < c->nops; i++)
@@ -295,6 +319,17 @@ static void expand(ctx* c, const spec_t* s, uint64_t* best_out, uint16_t* arg_ou
           sub.level[i] = (uint8_t)dst;
           sub.layout[i] ^= (uint8_t)x;
           if (cv) sub.bf16[i] = 0;
+          if (c->bounded && c->lim_axis[dst] >= 0) {
+            /* Section 2.4.4: the Move allocates the operand's buffer in dst; the body may use
+             * what is left of dst's bound, snapped down to a power of two (or zero). */
+            unsigned __int128 bytes = (unsigned __int128)numel(c, s, i) * (sub.bf16[i] ? 2 : 4);
+            uint64_t have = s->limit[dst] ? (uint64_t)1 << (s->limit[dst] - 1) : 0;
+            if (bytes > have) continue;
+            uint64_t left = have - (uint64_t)bytes;
+            uint8_t q = 0;
+            while (q < 64 && ((uint64_t)1 << q) <= left) q++;      /* left = 0 -> 0; else floor(log2) + 1 */
+            sub.limit[dst] = q;
+          }
           uint32_t id = c->move_base + (((uint32_t)i * (NL - 1) + dst) * 2 + (uint32_t)x) * 2 + (uint32_t)cv;
           uint64_t cand = affine(c, 1, solve(c, &sub), (unsigned __int128)coef * numel(c, s, i));
           consider(c, cand, id, &best, &arg);
@@ -424,21 +459,24 @@ int orc_solve(const orc_target* T, const orc_lattice* L,
 }
 
 /* Geometry of the table: number of axes, extents, and the merge order used by
- * orc_merge (size axes innermost first, then level axes, layout bits and
- * dtype bits, each last to first). */
+ * orc_merge (size axes innermost first, then the memory-bound axes, level
+ * axes, layout bits and dtype bits, each last to first). */
 int orc_geometry(const orc_target* T, const orc_lattice* L, uint32_t* ndim,
                  uint32_t* ext, uint32_t* merge_order, uint32_t* ids) {
   ctx c;
   if (ctx_init(&c, T, L)) return -1;
   *ndim = (uint32_t)c.ndim;
   for (int a = 0; a < c.ndim; a++) ext[a] = c.ext[a];
-  int nlay = 0;
+  int nlay = 0, nlim = 0;
   for (int i = 0; i < c.nops; i++) nlay += c.lay_axis[i] >= 0;
-  int q = 0;
+  for (int l = 0; l < ORC_MAXL; l++) nlim += c.lim_axis[l] >= 0;
+  int q = 0, first = 4 + c.nlv;
   for (int a = 3; a >= 0; a--) merge_order[q++] = (uint32_t)a;                                   /* n, k, m, b */
-  for (int a = 4 + c.nlv - 1; a >= 4; a--) merge_order[q++] = (uint32_t)a;                       /* levels */
-  for (int a = 4 + c.nlv + nlay - 1; a >= 4 + c.nlv; a--) merge_order[q++] = (uint32_t)a;        /* layout bits */
-  for (int a = c.ndim - 1; a >= 4 + c.nlv + nlay; a--) merge_order[q++] = (uint32_t)a;           /* dtype bits */
+  for (int a = first + nlim - 1; a >= first; a--) merge_order[q++] = (uint32_t)a;                /* memory bounds */
+  for (int a = first - 1; a >= 4; a--) merge_order[q++] = (uint32_t)a;                           /* levels */
+  first += nlim;
+  for (int a = first + nlay - 1; a >= first; a--) merge_order[q++] = (uint32_t)a;                /* layout bits */
+  for (int a = c.ndim - 1; a >= first + nlay; a--) merge_order[q++] = (uint32_t)a;               /* dtype bits */
   if (ids) { ids[0] = c.move_base; ids[1] = c.tile_base; ids[2] = c.buf_id; ids[3] = c.maxs; }
   return 0;
 }

@@ -17,44 +17,51 @@ from oracle import brute_force as B
 INF = 2 ** 64 - 1
 
 
-def axes(lattice):
-    """(axis kind, operand or dimension) per coordinate, in coordinate order:
+def axes(lattice, target=None):
+    """(axis kind, operand or dimension or level) per coordinate, in coordinate order:
     sizes b, m, k, n; one level per operand (kind F: plus the intermediate);
-    layout bits; dtype bits."""
+    (kind BD: one memory bound per level of finite capacity;) layout bits; dtype bits."""
     kind = lattice["kind"]
     nops = 4 if kind == B.F else 3
     nlv = 5 if kind == B.F else 3
     ax = [("size", d) for d in range(4)] + [("level", i) for i in range(nlv)]
+    if kind == B.BD:
+        ax += [("limit", l) for l in range(target["n_levels"]) if target["capacity_bytes"][l] != INF]
     ax += [("layout", i) for i in range(nops) if lattice["layout_coord"][i]]
     ax += [("dtype", i) for i in range(nops) if lattice["dtype_coord"][i]]
     return ax
 
 
-def spec_of_coord(lattice, x):
+def spec_of_coord(lattice, x, target=None):
     dims = [1, 1, 1, 1]
     lv, ly = [0] * 5, [0] * 5
     bf = [1 if lattice["base_dtype_bytes"][i] == 2 else 0 for i in range(5)]
-    for (what, i), v in zip(axes(lattice), x):
+    lim = [None] * (target["n_levels"] if target else 0)
+    for (what, i), v in zip(axes(lattice, target), x):
         if what == "size":
             dims[i] = lattice["sizes"][i][v]
         elif what == "level":
             lv[i] = v
         elif what == "layout":
             ly[i] = v
+        elif what == "limit":
+            lim[i] = 0 if v == 0 else 1 << (v - 1)
         else:
             bf[i] = v
-    return B.Spec(lattice["kind"], tuple(dims), tuple(lv), tuple(ly), tuple(bf))
+    return B.Spec(lattice["kind"], tuple(dims), tuple(lv), tuple(ly), tuple(bf), tuple(lim))
 
 
-def coord_of_spec(lattice, spec):
+def coord_of_spec(lattice, spec, target=None):
     x = []
-    for what, i in axes(lattice):
+    for what, i in axes(lattice, target):
         if what == "size":
             x.append(lattice["sizes"][i].index(spec.dims[i]))
         elif what == "level":
             x.append(spec.levels[i])
         elif what == "layout":
             x.append(spec.layouts[i])
+        elif what == "limit":
+            x.append(int(spec.limits[i]).bit_length())
         else:
             x.append(spec.bf16[i])
     return tuple(x)
@@ -73,7 +80,7 @@ def extract(target, lattices, results, label, coord):
 
     def walk(spec):
         lab, lat = by_kind[spec.kind]
-        x = coord_of_spec(lat, spec)
+        x = coord_of_spec(lat, spec, target)
         lin = 0
         for e, v in zip(results[lab]["extents"], x):
             lin = lin * int(e) + v
@@ -86,7 +93,7 @@ def extract(target, lattices, results, label, coord):
                         "children": [walk(ch) for ch in children]}
         raise AssertionError("the memoized rewrite %d does not apply to Spec %r" % (rid, spec))
 
-    return walk(spec_of_coord(dict(lattices_by_label(lattices))[label], coord))
+    return walk(spec_of_coord(dict(lattices_by_label(lattices))[label], coord, target))
 
 
 def lattices_by_label(lattices):

@@ -27,6 +27,7 @@ KIND_MATMUL_ACCUM = 0
 KIND_BIAS_ADD_RELU = 1
 KIND_FUSED_MM_ADD_RELU = 2
 KIND_MATMUL_PARALLEL = 3      # a Matmul whose serial-only flag is off; reads the KIND_MATMUL_ACCUM table
+KIND_MATMUL_BOUNDED = 4       # a Matmul whose Specs carry a memory bound per level of finite capacity
 
 MAX_LEVELS = 4
 MAX_OPERANDS = 5
@@ -173,8 +174,16 @@ def config(number, seed=None, max_size=None):
         r = keep(range(1, 65))
         lats = [("M", _lattice(KIND_MATMUL_ACCUM, [one, r, r, r]), []),
                 ("P", _lattice(KIND_MATMUL_PARALLEL, [one, r, r, r]), ["M"])]
+    elif number == 7:
+        # beyond the five benchmark configurations: memory bounds as coordinates.  Four levels,
+        # power-of-two sizes 1..64 on m, k, n, one bound axis per level of finite capacity
+        # (RF 256 B: 10 values, VRF 512 B: 11, L1 32 KiB: 17): 343 shapes x 64 level
+        # assignments x 1870 bounds = 41.0 M Specs
+        t, _ = _four_level_target(rng)
+        p2 = keep([1 << i for i in range(7)])
+        lats = [("B", _lattice(KIND_MATMUL_BOUNDED, [one, p2, p2, p2]), [])]
     else:
-        raise ValueError("config number must be 1..6")
+        raise ValueError("config number must be 1..7")
     return {"name": "config%d" % number, "target": t, "lattices": lats}
 
 
@@ -187,10 +196,13 @@ def n_operands(kind):
 
 
 def coord_extents(target, lattice):
-    """Extent of every coordinate axis: shape indices, level axes, layout bits, dtype bits."""
+    """Extent of every coordinate axis: shape indices, level axes, (memory bounds,) layout bits, dtype bits."""
     kind = lattice["kind"]
     ext = [len(s) for s in lattice["sizes"]]
     ext += [target["n_levels"]] * n_level_axes(kind)
+    if kind == KIND_MATMUL_BOUNDED:
+        # one axis per level of finite capacity: the bounds 0, 1, 2, 4, ... up to the capacity
+        ext += [int(c).bit_length() + 1 for c in target["capacity_bytes"][:target["n_levels"]] if c != UNBOUNDED]
     nops = n_operands(kind)
     ext += [2] * sum(1 for i in range(nops) if lattice["layout_coord"][i])
     ext += [2] * sum(1 for i in range(nops) if lattice["dtype_coord"][i])

@@ -218,6 +218,58 @@ def test_parallel_table_with_one_thread_is_the_serial_table():
     assert res["P"]["n_rewrites"] > res["M"]["n_rewrites"]
 
 
+def bounded_setup(caps=(16, 64), sizes=(1, 2, 4)):
+    """Two levels, both of finite capacity: bounds 0,1,..,16 B on level 0 and 0,1,..,64 B on level 1."""
+    cfg = W.config(1, seed=11, max_size=4)
+    t = cfg["target"]
+    t["loop_overhead"] = 2
+    t["capacity_bytes"][0], t["capacity_bytes"][1] = caps
+    r = list(sizes)
+    lat = W._lattice(W.KIND_MATMUL_BOUNDED, [[1], r, r, r])
+    lats = [("B", lat, [])]
+    return t, lats, O.solve_config({"target": t, "lattices": lats})
+
+
+def test_brute_force_memory_bounds():
+    """Sections 2.2 and 2.4.4: the per-level memory bounds are coordinates; a Move takes the moved
+    buffer's bytes out of the destination level's bound and the rest is rounded down to a power
+    of two.  Every Spec of a small lattice against the minimum over all complete programs."""
+    t, lats, res = bounded_setup()
+    ext = res["B"]["extents"]
+    assert ext == [1, 3, 3, 3, 2, 2, 2, 6, 8]
+    n = brute_force_compare(t, lats, res, "B", pick=lambda s: s.dims[1] * s.dims[2] * s.dims[3] <= 16)
+    assert n > 5000
+    # more memory never hurts: the cost does not rise along either bound axis
+    c = res["B"]["cost"].reshape(ext)
+    for axis in (7, 8):
+        a = np.moveaxis(c, axis, 0)
+        assert (a[1:] <= a[:-1]).all()
+    assert (c[..., 0, :] > c[..., 5, :]).any()
+    # closed form: 1x1x1x1 with every operand in level 1 needs three 4-byte buffers in level 0
+    # for the scalar FMA.  Bound 16: 16 -> 12 -> 8, 8 -> 4, 4 -> 0: it fits.  Bound 8: 8 -> 4,
+    # 4 -> 0, and the third Move finds nothing left, although 12 bytes would have done without
+    # the rounding.
+    ld, st = t["load_coef"][1][0][0], t["store_coef"][0][1][0]
+    mk = t["microkernels"][0][2]
+    assert int(c[0, 0, 0, 0, 1, 1, 1, 5, 0]) == 3 * ld + st + mk
+    assert int(c[0, 0, 0, 0, 1, 1, 1, 4, 7]) == O.INF
+    assert int(c[0, 0, 0, 0, 0, 0, 0, 0, 0]) == mk          # nothing to allocate: bounds of zero do
+    # a Spec that is already in level 0 but larger than one element tiles down without memory
+    assert int(c[0, 1, 0, 0, 0, 0, 0, 0, 0]) == 2 * mk + 2
+
+
+def test_memory_bounds_that_never_bind_give_the_unbounded_table():
+    """With bounds far above every allocation the bounded table at its top bounds is the plain
+    Matmul table of a target whose levels are unbounded (pinned above by brute force)."""
+    t, lats, res = bounded_setup(caps=(1 << 20, 1 << 20), sizes=(1, 2, 3, 4))
+    ext = res["B"]["extents"]
+    top = res["B"]["cost"].reshape(ext)[..., ext[7] - 1, ext[8] - 1]
+    top_arg = res["B"]["argmin"].reshape(ext)[..., ext[7] - 1, ext[8] - 1]
+    t2 = dict(t, capacity_bytes=[W.UNBOUNDED, W.UNBOUNDED, 0, 0])
+    plain = O.solve(t2, dict(lats[0][1], kind=W.KIND_MATMUL_ACCUM))
+    assert np.array_equal(top.ravel(), plain["cost"]) and np.array_equal(top_arg.ravel(), plain["argmin"])
+
+
 def test_closed_forms():
     """Special cases that reduce to closed forms."""
     # (i) scalar FMA only, s = 0: an all-RF spec costs m*k*n*k_fma whenever it fits

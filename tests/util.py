@@ -12,6 +12,8 @@ def axes(target, lattice):
     kind = lattice["kind"]
     nops, nlv = W.n_operands(kind), W.n_level_axes(kind)
     ax = [("size", d) for d in range(4)] + [("level", i) for i in range(nlv)]
+    if kind == W.KIND_MATMUL_BOUNDED:
+        ax += [("limit", l) for l in range(target["n_levels"]) if target["capacity_bytes"][l] != W.UNBOUNDED]
     ax += [("layout", i) for i in range(nops) if lattice["layout_coord"][i]]
     ax += [("dtype", i) for i in range(nops) if lattice["dtype_coord"][i]]
     return ax, W.coord_extents(target, lattice)
@@ -22,6 +24,7 @@ def spec_of_coord(target, lattice, x):
     dims = [1, 1, 1, 1]
     lv, ly = [0] * 5, [0] * 5
     bf = [1 if lattice["base_dtype_bytes"][i] == 2 else 0 for i in range(5)]
+    lim = [None] * target["n_levels"]
     for (what, i), v in zip(ax, x):
         if what == "size":
             dims[i] = lattice["sizes"][i][v]
@@ -29,9 +32,11 @@ def spec_of_coord(target, lattice, x):
             lv[i] = v
         elif what == "layout":
             ly[i] = v
+        elif what == "limit":
+            lim[i] = 0 if v == 0 else 1 << (v - 1)
         else:
             bf[i] = v
-    return B.Spec(lattice["kind"], tuple(dims), tuple(lv), tuple(ly), tuple(bf))
+    return B.Spec(lattice["kind"], tuple(dims), tuple(lv), tuple(ly), tuple(bf), tuple(lim))
 
 
 def coord_of_spec(target, lattice, spec):
@@ -44,6 +49,8 @@ def coord_of_spec(target, lattice, spec):
             x.append(spec.levels[i])
         elif what == "layout":
             x.append(spec.layouts[i])
+        elif what == "limit":
+            x.append(int(spec.limits[i]).bit_length())
         else:
             x.append(spec.bf16[i])
     return tuple(x)

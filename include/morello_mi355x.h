@@ -90,6 +90,7 @@ void mrl_target_destroy(mrl_target* t);
  * Coordinate vector x, in this order:
  *   index of b, m, k, n in the allowed-size lists;
  *   memory level of each operand (kind FUSED: then the intermediate's level);
+ *   (kind MATMUL_BOUNDED: one memory-bound index per level of finite capacity;)
  *   one layout bit (0 row-major, 1 column-major) per operand with layout_coord;
  *   one dtype bit (0 f32, 1 bf16) per operand with dtype_coord.
  * Dense tables are in C order of x (last coordinate fastest).
@@ -107,9 +108,20 @@ void mrl_target_destroy(mrl_target* t);
  * the serial-only Spec of the smaller shape.  The serial-only Specs are the
  * MATMUL_ACCUM table of the same lattice, passed as the one dependency: the
  * flag is kept as two tables rather than as an axis of one.
+ * MATMUL_BOUNDED (Section 2.2, field 5; Section 2.4.4; Section 4.1: limits are
+ * powers of two): the MATMUL_ACCUM Specs with a peak-memory bound per level
+ * of finite capacity as further coordinates, placed after the operand levels
+ * and before the layout bits, one axis per such level in level order.
+ * Coordinate q stands for a bound of 0 bytes (q = 0) or 2^(q-1) bytes, up to
+ * the largest power of two within the capacity.  There is no admissibility
+ * test by footprint; instead a Move needs the moved operand's bytes (at the
+ * dtype it has after the Move) within the destination level's bound, and its
+ * body Spec gets what is left, rounded down to a power of two (or zero).
+ * Tiles keep the bounds.  Rewrite ids as for MATMUL_ACCUM; no deps.
  */
 typedef enum { MRL_KIND_MATMUL_ACCUM = 0, MRL_KIND_BIAS_ADD_RELU = 1,
-               MRL_KIND_FUSED_MM_ADD_RELU = 2, MRL_KIND_MATMUL_PARALLEL = 3 } mrl_kind;
+               MRL_KIND_FUSED_MM_ADD_RELU = 2, MRL_KIND_MATMUL_PARALLEL = 3,
+               MRL_KIND_MATMUL_BOUNDED = 4 } mrl_kind;
 
 typedef struct {
   uint32_t kind;
@@ -186,7 +198,8 @@ typedef struct { uint8_t cls; /* 0 microkernel, 1 move, 2 tile, 3 bufferize, 4 p
 int32_t mrl_rewrite_decode(const mrl_table* tab, uint16_t id, mrl_rewrite* out);
 
 /* shape: b,m,k,n sizes (must be in the lists); levels / layouts / dtypes: per
- * operand (FUSED: levels[4] = intermediate); entries without a coordinate are ignored. */
+ * operand (FUSED: levels[4] = intermediate); entries without a coordinate are ignored.
+ * MATMUL_BOUNDED: the memory bounds are set to their top (the capacities). */
 int32_t mrl_coord_of_spec(const mrl_table* tab, const uint32_t shape[4], const uint8_t* levels,
                           const uint8_t* layouts, const uint8_t* dtypes, mrl_coord* out);
 

@@ -139,10 +139,11 @@ int32_t validate_target(const mrl_target_desc* d) {
 
 int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c) {
   if (!L) return fail(MRL_E_INVAL, "lattice descriptor is NULL");
-  if (L->kind > MRL_KIND_MATMUL_PARALLEL) return fail(MRL_E_INVAL, "unknown spec kind %u", L->kind);
-  // A parallel lattice is a Matmul lattice (same operator, operands and coordinates) with more rewrites.
-  const bool parallel = L->kind == MRL_KIND_MATMUL_PARALLEL;
-  const uint32_t kind = parallel ? (uint32_t)kKindM : L->kind;
+  if (L->kind > MRL_KIND_MATMUL_BOUNDED) return fail(MRL_E_INVAL, "unknown spec kind %u", L->kind);
+  // A parallel lattice is a Matmul lattice (same operator, operands and coordinates) with more
+  // rewrites; a bounded one is a Matmul lattice with more coordinates.
+  const bool parallel = L->kind == MRL_KIND_MATMUL_PARALLEL, bounded = L->kind == MRL_KIND_MATMUL_BOUNDED;
+  const uint32_t kind = parallel || bounded ? (uint32_t)kKindM : L->kind;
   if (parallel && T.threads < 1) return fail(MRL_E_INVAL, "a MATMUL_PARALLEL lattice needs threads >= 1");
   c.target = T;
   c.lat = *L;
@@ -152,6 +153,20 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
   P.par = parallel ? 1u : 0u;
   P.threads = parallel ? T.threads : 1u;
   P.sync = T.sync_cost;
+  // memory bounds: one axis per level of finite capacity, values 0, 1, 2, 4, ... up to the capacity
+  P.bounded = bounded ? 1u : 0u;
+  P.Q = 1;
+  for (uint32_t l = 0; l < 4; l++) P.lim_of_level[l] = kNoBit;
+  if (bounded) {
+    for (uint32_t l = 0; l < T.n_levels; l++) {
+      if (T.capacity_bytes[l] == UINT64_MAX) continue;
+      uint32_t nq = 1;
+      while (nq < 64 && (1ull << (nq - 1)) <= T.capacity_bytes[l]) nq++;
+      P.lim_of_level[l] = P.nlim;
+      P.lim_nq[P.nlim++] = nq;
+    }
+    for (uint32_t a = P.nlim; a-- > 0;) { P.lim_stride[a] = P.Q; P.Q *= P.lim_nq[a]; }
+  }
   P.nops = kind == kKindF ? 4 : 3;
   P.nlv = kind == kKindF ? 5 : 3;
   P.NL = T.n_levels;
@@ -197,13 +212,14 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
 
   if (P.V > 16) return fail(MRL_E_INVAL, "too many layout/dtype bits");
   {
-    uint32_t axis = 4 + P.nlv, seen_l = 0, seen_d = 0;
+    uint32_t axis = 4 + P.nlv + P.nlim, seen_l = 0, seen_d = 0;
     for (uint32_t i = 0; i < P.nops; i++)
       if (L->layout_coord[i]) { c.lay_axis[i] = (int)axis++; P.lay_bit[i] = P.ndt + P.nlay - 1 - seen_l++; }
     for (uint32_t i = 0; i < P.nops; i++)
       if (L->dtype_coord[i]) { c.dt_axis[i] = (int)axis++; P.dt_bit[i] = P.ndt - 1 - seen_d++; }
   }
-  P.G = P.ncombo * P.npass * P.V;
+  if ((uint64_t)P.ncombo * P.npass * P.V * P.Q >= (1ull << 32)) return fail(MRL_E_INVAL, "too many entries per shape");
+  P.G = P.ncombo * P.npass * P.V * P.Q;
   c.n_specs = (uint64_t)c.n_shapes * P.G;
   if (c.n_specs >= (1ull << 32)) return fail(MRL_E_INVAL, "lattice has %llu specs; the limit is 2^32-1", (unsigned long long)c.n_specs);
 
@@ -338,24 +354,28 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
     for (uint32_t sh = 0; sh < c.n_shapes; sh++) c.level_shapes[cur[lev[sh]]++] = sh;
   }
 
-  // coordinate geometry and merge order: size axes innermost first, then level
-  // axes, layout bits, dtype bits, each from the last to the first
+  // coordinate geometry and merge order: size axes innermost first, then the memory-bound
+  // axes, level axes, layout bits, dtype bits, each from the last to the first
   Geo& g = c.geo;
   memset(&g, 0, sizeof g);
   uint32_t nd = 0;
   for (int d = 0; d < 4; d++) g.ext[nd++] = P.nsz[d];
   for (uint32_t i = 0; i < P.nlv; i++) g.ext[nd++] = P.NL;
+  for (uint32_t a = 0; a < P.nlim; a++) g.ext[nd++] = P.lim_nq[a];
   for (uint32_t i = 0; i < P.nlay + P.ndt; i++) g.ext[nd++] = 2;
+  if (nd > 16) return fail(MRL_E_INVAL, "more than 16 coordinate axes");
   g.ndim = nd;
   uint64_t s = 1;
   for (int a = (int)nd - 1; a >= 0; a--) { g.stride[a] = (uint32_t)s; s *= g.ext[a]; }
   g.n = (uint32_t)c.n_specs;
   {
     uint32_t q = 0;
+    const int lim0 = 4 + (int)P.nlv, lay0 = lim0 + (int)P.nlim;
     for (int a = 3; a >= 0; a--) c.merge_order[q++] = (uint32_t)a;
-    for (int a = 4 + (int)P.nlv - 1; a >= 4; a--) c.merge_order[q++] = (uint32_t)a;
-    for (int a = 4 + (int)(P.nlv + P.nlay) - 1; a >= 4 + (int)P.nlv; a--) c.merge_order[q++] = (uint32_t)a;
-    for (int a = (int)nd - 1; a >= 4 + (int)(P.nlv + P.nlay); a--) c.merge_order[q++] = (uint32_t)a;
+    for (int a = lay0 - 1; a >= lim0; a--) c.merge_order[q++] = (uint32_t)a;             // memory bounds
+    for (int a = lim0 - 1; a >= 4; a--) c.merge_order[q++] = (uint32_t)a;                // levels
+    for (int a = lay0 + (int)P.nlay - 1; a >= lay0; a--) c.merge_order[q++] = (uint32_t)a;
+    for (int a = (int)nd - 1; a >= lay0 + (int)P.nlay; a--) c.merge_order[q++] = (uint32_t)a;
   }
 
   c.max_task = P.ncombo * P.V;
@@ -383,7 +403,7 @@ bool same_problem(const Compiled& c, const mrl_target_desc& T, const mrl_lattice
 int32_t get_compiled(const mrl_target_desc& T, const mrl_lattice_desc* L, CompiledPtr& out) {
   static std::mutex mu;
   static std::vector<CompiledPtr> cache;          // most recent last, at most 8
-  if (L && L->kind <= MRL_KIND_MATMUL_PARALLEL) {
+  if (L && L->kind <= MRL_KIND_MATMUL_BOUNDED) {
     std::lock_guard<std::mutex> lock(mu);
     for (size_t i = cache.size(); i-- > 0;)
       if (same_problem(*cache[i], T, *L)) { out = cache[i]; return MRL_OK; }
@@ -606,6 +626,16 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
   size_t ev_used = 0;
   hipStream_t s2 = aux->stream;
   HIP_TRY(hipEventRecord(ev[0], st));
+  if (P.bounded) {
+    // Memory bounds as coordinates: every Spec is evaluated (no admissibility test, so every cell
+    // counts as fitting for the compression); one launch per dependency level of shapes and rank
+    // of level assignments, each over Specs that depend only on earlier launches.
+    launch_fill_ones(d_fitmap, ((size_t)f.n_words + 2) * 8, st);
+    for (uint32_t l = 0; l < n_lev; l++)
+      for (uint32_t r = 0; r < P.nranks; r++)
+        launch_fill_bounded(d_P, d_level_shapes + c.level_off[l], c.level_off[l + 1] - c.level_off[l], r,
+                            P.rank_off[r + 1] - P.rank_off[r], P.Q, P.V, tab->d_cost, tab->d_arg, d_ctr, st);
+  } else {
   // plan (with the pre-fill; a separate streaming kernel for tables it cannot serve), then the
   // host reads the list sizes back
   launch_zero_words((unsigned long long*)d_fitmap, f.n_words + 2, st);
@@ -641,6 +671,7 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
       HIP_TRY(hipEventRecord(aux->events[ev_used], s2));
       HIP_TRY(hipStreamWaitEvent(st, aux->events[ev_used++], 0));
     }
+  }
   }
   HIP_TRY(hipGetLastError());
   HIP_TRY(hipEventRecord(ev[1], st));
@@ -887,6 +918,7 @@ int32_t mrl_coord_of_spec(const mrl_table* tab, const uint32_t shape[4], const u
     if (levels[i] >= c.P.NL) return fail(MRL_E_RANGE, "level %u of operand %u outside the target", levels[i], i);
     out->x[4 + i] = levels[i];
   }
+  for (uint32_t a = 0; a < c.P.nlim; a++) out->x[4 + c.P.nlv + a] = c.P.lim_nq[a] - 1;   // the whole capacity
   for (uint32_t i = 0; i < c.P.nops; i++) {
     if (c.lay_axis[i] >= 0) { if (!layouts || layouts[i] > 1) return fail(MRL_E_RANGE, "layout of operand %u", i); out->x[c.lay_axis[i]] = layouts[i]; }
     if (c.dt_axis[i] >= 0) { if (!dtypes || dtypes[i] > 1) return fail(MRL_E_RANGE, "dtype of operand %u", i); out->x[c.dt_axis[i]] = dtypes[i]; }
@@ -925,6 +957,19 @@ int32_t mrl_schedule(const mrl_table* tab, const mrl_coord* goal, mrl_schedule_n
       ch.x.x[4 + op] = r.dst_level;
       if (r.transposed) { if (c.lay_axis[op] < 0) return fail(MRL_E_HIP, "internal error: transposing Move without a layout coordinate"); ch.x.x[c.lay_axis[op]] ^= 1u; }
       if (r.convert) { if (c.dt_axis[op] < 0) return fail(MRL_E_HIP, "internal error: converting Move without a dtype coordinate"); ch.x.x[c.dt_axis[op]] = 0; }
+      if (P.bounded && P.lim_of_level[r.dst_level] != kNoBit) {
+        // the Move's buffer comes out of the destination's bound; the rest snaps down to a power of two
+        const uint32_t ax = 4 + P.nlv + P.lim_of_level[r.dst_level];
+        const uint64_t b = c.sizes[0][it.x.x[0]], m = c.sizes[1][it.x.x[1]], k = c.sizes[2][it.x.x[2]], nn = c.sizes[3][it.x.x[3]];
+        const uint64_t numel = op == 0 ? b * m * k : op == 1 ? b * k * nn : b * m * nn;
+        const bool bf = c.dt_axis[op] >= 0 ? ch.x.x[c.dt_axis[op]] != 0 : c.lat.base_dtype_bytes[op] == 2;
+        const uint64_t bytes = numel * (bf ? 2 : 4), have = it.x.x[ax] ? 1ull << (it.x.x[ax] - 1) : 0;
+        if (bytes > have) return fail(MRL_E_HIP, "internal error: a memoized Move exceeds its memory bound");
+        uint64_t left = have - bytes;
+        uint32_t q = 0;
+        while (left) { q++; left >>= 1; }
+        ch.x.x[ax] = q;
+      }
       stack.push_back(ch);
       node.n_children = 1;
     } else if (r.cls == 2) {                // tile: the loop body is the Spec with the smaller size

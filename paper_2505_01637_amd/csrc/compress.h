@@ -22,6 +22,9 @@ void launch_fill_level(const DevParams* P, uint32_t npass, uint32_t G, uint32_t 
                        uint32_t n_slice, const uint32_t* list_wide, uint32_t n_wide, uint64_t* cost, uint16_t* arg,
                        Counters* ctr, hipStream_t stream, hipStream_t wide_stream);
 
+void launch_fill_bounded(const DevParams* P, const uint32_t* level_shapes, uint32_t n_level_shapes, uint32_t rank,
+                         uint32_t n_rank_combos, uint32_t Q, uint32_t V, uint64_t* cost, uint16_t* arg, Counters* ctr,
+                         hipStream_t stream);
 void launch_fill_ones(void* p, size_t bytes, hipStream_t stream);
 void launch_zero_words(unsigned long long* p, uint32_t n, hipStream_t st);
 void launch_head_flags(const Geo& g, uint32_t a0, const uint64_t* cost, const uint16_t* arg, const uint32_t* fitmap,

@@ -70,6 +70,13 @@ struct DevParams {
   // per rank-major position: pack | (operands resident in level l, one nibble per level) << 8
   // | (r + 1) << 24 at the first position of rank r
   uint32_t pos_info[kMaxCombo];
+  // ---- memory bounds as coordinates (a Matmul lattice whose Specs carry a bound per level of
+  // finite capacity; kind stays kKindM).  Bound index q stands for 0 bytes (q = 0) or 2^(q-1).
+  uint32_t bounded;          // 1: G = ncombo * Q * V, entry = (combo * Q + bound vector) * V + variant
+  uint32_t nlim, Q;          // number of bound axes; Q = product of their extents
+  uint32_t lim_nq[4];        // extent of bound axis a
+  uint32_t lim_stride[4];    // its stride inside the bound vector's index (first axis slowest)
+  uint32_t lim_of_level[4];  // bound axis of memory level l, kNoBit if the level is unbounded
   // ---- tables a FUSED lattice reads (costM also: the serial table a parallel lattice reads) ----
   const uint64_t* costM;
   const uint64_t* costE;

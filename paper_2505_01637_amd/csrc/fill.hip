@@ -931,6 +931,138 @@ void launch_fill_ones(void* p, size_t bytes, hipStream_t stream) {
 
 uint32_t fill_wave_cap(uint32_t G) { return G < kSmallCap ? G : kSmallCap; }
 
+// ---------------------------------------------------------------- memory bounds as coordinates
+// Sections 2.2 and 2.4.4: a Spec carries, per level of finite capacity, the bytes an implementation
+// may still allocate there; a Move allocates the moved operand's buffer in its destination, so it
+// needs that many bytes of the destination's bound and leaves its body the rest, rounded down to
+// a power of two (or zero).  There is no admissibility test: the bounds decide.
+//
+// A Move lowers the sum of the operand levels (the rank) and a tile goes to a smaller shape, so
+// the Specs of one dependency level of shapes and one rank depend only on earlier launches: one
+// lane per Spec, every candidate a gather from finished entries.  Lane -> (shape of the level,
+// level assignment of the rank, bound vector, variant), variant fastest.
+__global__ __launch_bounds__(256) void fill_bounded_kernel(const DevParams* __restrict__ P,
+                                                           const uint32_t* __restrict__ level_shapes, uint32_t n_level_shapes,
+                                                           uint32_t rank, uint64_t* cost, uint16_t* __restrict__ arg,
+                                                           Counters* __restrict__ ctr) {
+  const uint32_t V = P->V, Q = P->Q;
+  const uint32_t c0 = P->rank_off[rank], ncr = P->rank_off[rank + 1] - c0;
+  const uint64_t per_shape = (uint64_t)ncr * Q * V;
+  const uint64_t t = (uint64_t)blockIdx.x * 256u + threadIdx.x;
+  const bool active = t < per_shape * n_level_shapes;
+  Eval e;
+  e.best = kInf; e.arg = kNone; e.n = 0; e.ovf = 0;
+  if (active) {
+    const uint32_t sl = (uint32_t)(t / per_shape);
+    uint32_t r = (uint32_t)(t - (uint64_t)sl * per_shape);
+    const uint32_t ci = r / (Q * V);
+    r -= ci * Q * V;
+    const uint32_t q = r / V, v = r - q * V;
+    const uint32_t shape = level_shapes[sl];
+    Shape S;
+    load_shape(P, shape, S);
+    const uint32_t pack = P->pos_info[c0 + ci] & 0xFFu;
+    uint32_t lv[3], combo = 0;
+#pragma unroll
+    for (int i = 0; i < 3; i++) { lv[i] = (pack >> P->pack_shift[i]) & 3u; combo += lv[i] * P->lvpow[i]; }
+    uint32_t qi[4] = {0, 0, 0, 0};
+    {
+      uint32_t rem = q;
+#pragma unroll
+      for (int a = 0; a < 4; a++)
+        if ((uint32_t)a < P->nlim) { qi[a] = rem / P->lim_stride[a]; rem -= qi[a] * P->lim_stride[a]; }
+    }
+    const uint64_t group = (uint64_t)shape * P->G;
+    const uint32_t off = (combo * Q + q) * V + v;
+
+    // microkernels
+    const uint32_t mm = P->mk_entry[pack * V + v];
+    for (uint32_t j = 0; j < P->nmk; j++) {
+      if (!((mm >> j) & 1u)) continue;
+      const uint64_t reps = mk_shape_reps(P, S, j);
+      if (!reps) continue;
+      const uint64_t k = mul_or_limit(P->mk_cost[j], reps);
+      if (k >= kLimit) e.ovf = 1; else consider(e, k, j);
+      e.n++;
+    }
+
+    // Moves
+#pragma unroll
+    for (int i = 0; i < 3; i++) {
+      const uint32_t src = lv[i];
+      const bool has_dt = P->dt_bit[i] != kNoBit, has_lay = P->lay_bit[i] != kNoBit;
+      const uint32_t bf = has_dt ? (v >> P->dt_bit[i]) & 1u : P->base_bf16[i];
+      const uint64_t numel = S.numel[i];
+      for (uint32_t dst = 0; dst < src; dst++)
+        for (uint32_t x = 0; x < 2; x++)
+          for (uint32_t cv = 0; cv < 2; cv++) {
+            if (x && !has_lay) continue;
+            if (cv && !(P->can_convert[i] && has_dt && bf)) continue;
+            const uint32_t coef = P->mcoef[i][src][dst][x];
+            if (!coef) continue;
+            const uint32_t child_bf = cv ? 0u : bf;
+            uint32_t qc = q;
+            const uint32_t la = P->lim_of_level[dst];
+            if (la != kNoBit) {
+              const uint32_t qa = la == 0 ? qi[0] : la == 1 ? qi[1] : la == 2 ? qi[2] : qi[3];
+              const uint64_t bytes = numel * (child_bf ? 2u : 4u);
+              const uint64_t have = qa ? 1ull << (qa - 1u) : 0ull;
+              if (bytes > have) continue;                       // the buffer does not fit the bound: no such rewrite
+              const uint64_t left = have - bytes;
+              const uint32_t qn = left ? 64u - (uint32_t)__clzll((long long)left) : 0u;
+              qc = q - (qa - qn) * P->lim_stride[la];
+            }
+            const uint32_t combo_c = combo - (src - dst) * P->lvpow[i];
+            uint32_t v_c = v ^ (x ? 1u << P->lay_bit[i] : 0u);
+            if (cv) v_c &= ~(1u << P->dt_bit[i]);
+            const uint64_t sub = cost[group + (uint64_t)(combo_c * Q + qc) * V + v_c];
+            const uint64_t b = mul_or_limit((uint64_t)coef + (cv ? P->convert : 0u), numel);
+            const uint32_t id = P->move_base + (((uint32_t)i * (P->NL - 1u) + dst) * 2u + x) * 2u + cv;
+            if (sub != kInf) {
+              if (b >= kLimit || sub + b >= kLimit) e.ovf = 1; else consider(e, sub + b, id);
+            }
+            e.n++;
+          }
+    }
+
+    // tiles: the same entry of a smaller shape's group
+    const uint64_t s = P->s;
+#pragma unroll
+    for (int d = 0; d < 4; d++) {
+      if (!P->tile_dim_ok[d]) continue;
+      for (uint32_t te_i = P->tile_off[d][S.si[d]]; te_i < P->tile_off[d][S.si[d] + 1]; te_i++) {
+        const TileEntry te = P->tiles[te_i];
+        const uint32_t child = shape - (S.si[d] - te.jt) * P->shape_stride[d];
+        const uint64_t sub = cost[(uint64_t)child * P->G + off];
+        const bool fin = sub != kInf;
+        const uint32_t a = te.trips;
+        const uint64_t lo = (uint64_t)a * (uint32_t)sub;
+        const uint64_t hi = (uint64_t)a * (uint32_t)(sub >> 32) + (lo >> 32);
+        const uint64_t c = ((hi << 32) | (uint32_t)lo) + s;
+        const bool over = fin & (((hi >> 30) != 0) | (c >= kLimit));
+        e.ovf |= over ? 1u : 0u;
+        consider(e, c, P->tile_base + (uint32_t)d * P->maxs + te.jt, fin & !over);
+        e.n++;
+      }
+    }
+    cost[group + off] = e.best;
+    arg[group + off] = (uint16_t)e.arg;
+  }
+  flush_counters(ctr, e);
+  const unsigned long long lanes = __ballot(active);
+  if ((threadIdx.x & 63u) == 0 && lanes) atomicAdd(&ctr->n_admissible, (unsigned long long)__popcll(lanes));
+}
+
+// One dependency level of shapes, one rank of level assignments.
+void launch_fill_bounded(const DevParams* P, const uint32_t* level_shapes, uint32_t n_level_shapes, uint32_t rank,
+                         uint32_t n_rank_combos, uint32_t Q, uint32_t V, uint64_t* cost, uint16_t* arg, Counters* ctr,
+                         hipStream_t stream) {
+  const uint64_t n = (uint64_t)n_level_shapes * n_rank_combos * Q * V;
+  if (!n) return;
+  hipLaunchKernelGGL(fill_bounded_kernel, dim3((uint32_t)((n + 255) / 256)), dim3(256), 0, stream, P, level_shapes,
+                     n_level_shapes, rank, cost, arg, ctr);
+}
+
 void launch_plan(const DevParams* P, uint32_t n_shapes, uint32_t npass, uint32_t G, const uint32_t* level_shapes,
                  const uint32_t* level_off, uint32_t n_levels, uint32_t* shape_class, uint32_t* list_whole,
                  uint32_t* list_slice, uint32_t* list_wide, uint32_t* list_cnt, uint32_t* fitmap, Counters* ctr,

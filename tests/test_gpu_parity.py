@@ -172,6 +172,41 @@ def test_parity_parallel_loops_with_layout_and_dtype_bits():
     assert e.value.code == B.E_INVAL
 
 
+def two_level_bounded(caps, sizes):
+    cfg = W.config(1, seed=11, max_size=4)
+    t = cfg["target"]
+    t["loop_overhead"] = 2
+    t["capacity_bytes"][0], t["capacity_bytes"][1] = caps
+    r = list(sizes)
+    return {"name": "bounded-2", "target": t,
+            "lattices": [("B", W._lattice(W.KIND_MATMUL_BOUNDED, [[1], r, r, r]), [])]}
+
+
+@pytest.mark.parametrize("case", ["two-level", "two-level-one-unbounded", "four-level-small", "bits", "config7"])
+def test_parity_memory_bounds(case):
+    """Memory bounds as coordinates (Sections 2.2, 2.4.4): dense tables, counters and both box
+    lists against the oracle; two levels with small capacities, a level without a bound axis,
+    four levels, layout and dtype bits with converting Moves (whose buffers are f32), and the
+    full 41 M-Spec lattice of config 7."""
+    if case == "two-level":
+        cfg = two_level_bounded((16, 64), (1, 2, 3, 4, 6))
+    elif case == "two-level-one-unbounded":
+        cfg = two_level_bounded((100, W.UNBOUNDED), (1, 2, 4, 8))
+    elif case == "four-level-small":
+        cfg = W.config(7, max_size=4)
+    elif case == "bits":
+        cfg = W.config(3, seed=7)
+        lat = W._lattice(W.KIND_MATMUL_BOUNDED, [[1], [1], [1, 16, 32], [1, 2, 8]],
+                         layout=(0, 1, 0, 0, 0), dtype=(1, 1, 0, 0, 0), base_bytes=(2, 2, 4, 4, 4))
+        cfg = {"name": "bounded-bits", "target": cfg["target"], "lattices": [("B", lat, [])]}
+    else:
+        cfg = W.config(7)
+    _, got, want = compare_config(cfg, scratch_bytes=(3 << 30) if case == "config7" else None)
+    label = cfg["lattices"][0][0]
+    assert got[label].stats.n_admissible == got[label].n_specs
+    check_compressed_queries(got[label], want[label], 100_000, seed=3)
+
+
 def test_degenerate_lattices():
     B = _binding()
     # a single shape: every dimension pinned
@@ -271,7 +306,7 @@ def test_deterministic():
 
 @pytest.mark.gpu
 @pytest.mark.parametrize("number,max_size,label", [(1, None, "M"), (3, 64, "M"), (4, 8, "M"), (5, 8, "F"), (5, 8, "E"),
-                                                   (6, 16, "P")])
+                                                   (6, 16, "P"), (7, 8, "B")])
 def test_schedule_parity(number, max_size, label):
     """mrl_schedule walks the same programs as the oracle's extraction: same Specs, rewrites and
     costs, node by node in pre-order; a goal without implementation is an error."""

@@ -835,8 +835,9 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
   if (stats) {
     memset(stats, 0, sizeof *stats);
     stats->n_specs = c.n_specs;
-    stats->n_admissible = h_ctr.n_admissible;
-    stats->n_rewrites = h_ctr.n_rewrites;
+    stats->n_admissible = stats->n_rewrites = 0;
+    for (uint32_t i = 0; i < kCtrSlots; i++) { stats->n_admissible += h_ctr.n_admissible[i]; stats->n_rewrites += h_ctr.n_rewrites[i]; }
+    if (P.bounded) stats->n_admissible = c.n_specs;      // no admissibility test: every Spec is evaluated
     stats->n_levels_run = n_lev;
     HIP_TRY(hipEventElapsedTime(&stats->fill_ms, ev[0], ev[1]));
     HIP_TRY(hipEventElapsedTime(&stats->compress_ms, ev[1], ev[2]));

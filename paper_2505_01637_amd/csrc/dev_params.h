@@ -84,11 +84,15 @@ struct DevParams {
   uint32_t layM[3], layE[3]; // layout bit positions in the dependency's variant index
 };
 
+// The counts are spread over slots (workgroup index modulo kCtrSlots) and added up by the host:
+// atomics of many workgroups on one address serialise (about 10 ns each across the chip), and a
+// kernel does not end before its atomics have.
+constexpr uint32_t kCtrSlots = 256;
 struct Counters {
-  unsigned long long n_admissible;
-  unsigned long long n_rewrites;
   unsigned int overflow;
   unsigned int pad;
+  unsigned long long n_admissible[kCtrSlots];
+  unsigned long long n_rewrites[kCtrSlots];
 };
 
 }  // namespace mrl

@@ -722,7 +722,7 @@ __device__ __forceinline__ void flush_counters(Counters* __restrict__ ctr, const
   uint32_t n_rw = tot.n;
 #pragma unroll
   for (int d = 32; d > 0; d >>= 1) n_rw += __shfl_down(n_rw, d, 64);
-  if ((threadIdx.x & 63u) == 0 && n_rw) atomicAdd(&ctr->n_rewrites, (unsigned long long)n_rw);
+  if ((threadIdx.x & 63u) == 0 && n_rw) atomicAdd(&ctr->n_rewrites[blockIdx.x % kCtrSlots], (unsigned long long)n_rw);
   if (tot.ovf) atomicOr(&ctr->overflow, tot.ovf);
 }
 
@@ -814,7 +814,7 @@ __global__ __launch_bounds__(256) void plan_kernel(const DevParams* __restrict__
       shape_class[shape] = cls;
     }
   }
-  if (lane == 0 && n_adm) atomicAdd(&ctr->n_admissible, n_adm);
+  if (lane == 0 && n_adm) atomicAdd(&ctr->n_admissible[blockIdx.x % kCtrSlots], n_adm);
 }
 
 // One workgroup per dependency level: walks the level's shapes in index order and writes its work
@@ -945,6 +945,7 @@ __global__ __launch_bounds__(256) void fill_bounded_kernel(const DevParams* __re
                                                            const uint32_t* __restrict__ level_shapes, uint32_t n_level_shapes,
                                                            uint32_t rank, uint64_t* cost, uint16_t* __restrict__ arg,
                                                            Counters* __restrict__ ctr) {
+  __shared__ uint32_t wave_n[4];
   const uint32_t V = P->V, Q = P->Q;
   const uint32_t c0 = P->rank_off[rank], ncr = P->rank_off[rank + 1] - c0;
   const uint64_t per_shape = (uint64_t)ncr * Q * V;
@@ -1048,9 +1049,17 @@ __global__ __launch_bounds__(256) void fill_bounded_kernel(const DevParams* __re
     cost[group + off] = e.best;
     arg[group + off] = (uint16_t)e.arg;
   }
-  flush_counters(ctr, e);
-  const unsigned long long lanes = __ballot(active);
-  if ((threadIdx.x & 63u) == 0 && lanes) atomicAdd(&ctr->n_admissible, (unsigned long long)__popcll(lanes));
+  // rewrites evaluated: one atomic per workgroup
+  uint32_t n_rw = e.n;
+#pragma unroll
+  for (int d = 32; d > 0; d >>= 1) n_rw += __shfl_down(n_rw, d, 64);
+  if ((threadIdx.x & 63u) == 0) wave_n[threadIdx.x >> 6] = n_rw;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const uint32_t n = wave_n[0] + wave_n[1] + wave_n[2] + wave_n[3];
+    if (n) atomicAdd(&ctr->n_rewrites[blockIdx.x % kCtrSlots], (unsigned long long)n);
+  }
+  if (e.ovf) atomicOr(&ctr->overflow, e.ovf);
 }
 
 // One dependency level of shapes, one rank of level assignments.

@@ -421,6 +421,7 @@ int32_t get_compiled(const mrl_target_desc& T, const mrl_lattice_desc* L, Compil
 // A second stream (default priority, non-blocking) for work that is independent of what runs on
 // the caller's stream: the wide items of a dependency level beside its other items, and one of the
 // two box lists beside the other; with it the events and the pinned counters a solve needs.
+constexpr size_t kPinnedCounts = 16 + 4 * 1024;   // u32: 16 for the box lists, then the level lists' lengths (4 per level)
 struct Aux {
   hipStream_t stream = nullptr;
   std::vector<hipEvent_t> events;
@@ -457,7 +458,7 @@ int32_t get_aux(size_t n_events, AuxLease& lease) {
   }
   lease.a = aux;
   if (!aux->stream) HIP_TRY(hipStreamCreateWithFlags(&aux->stream, hipStreamNonBlocking));
-  if (!aux->h_counts) HIP_TRY(hipHostMalloc((void**)&aux->h_counts, 64, hipHostMallocDefault));
+  if (!aux->h_counts) HIP_TRY(hipHostMalloc((void**)&aux->h_counts, kPinnedCounts * 4, hipHostMallocDefault));
   for (auto& e : aux->timing) if (!e) HIP_TRY(hipEventCreate(&e));
   while (aux->events.size() < n_events) {
     hipEvent_t e;
@@ -638,14 +639,19 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
   } else {
   // plan (with the pre-fill; a separate streaming kernel for tables it cannot serve), then the
   // host reads the list sizes back
-  launch_zero_words((unsigned long long*)d_fitmap, f.n_words + 2, st);
+  // A level assignment's fit bits (passive levels x variants) are whole 32-bit words of the map when
+  // there are 32 or 64 of them: the plan kernel then stores them, and only the two pad words are zeroed.
+  const bool fit_words = P.npass * P.V == 32 || P.npass * P.V == 64;
+  if (fit_words) launch_zero_words((unsigned long long*)d_fitmap + f.n_words, 2, st);
+  else launch_zero_words((unsigned long long*)d_fitmap, f.n_words + 2, st);
   // the plan kernel also streams (INF, NONE) over the tables when a shape's entries are whole 16-byte pieces
   const bool fused_prefill = P.G % 8 == 0;
   launch_plan(d_P, c.n_shapes, P.npass, P.G, d_level_shapes, d_level_off, n_lev, d_shape_class, d_list_whole, d_list_slice,
               d_list_wide, d_list_cnt, d_fitmap, d_ctr, fused_prefill ? tab->d_cost : nullptr,
               fused_prefill ? tab->d_arg : nullptr, st);
-  std::vector<uint32_t> cnt(4 * (size_t)n_lev);
-  HIP_TRY(hipMemcpyAsync(cnt.data(), d_list_cnt, cnt.size() * 4, hipMemcpyDeviceToHost, st));
+  if (16 + 4 * (size_t)n_lev > kPinnedCounts) return fail(MRL_E_INVAL, "too many dependency levels (%u)", n_lev);
+  const uint32_t* cnt = aux->h_counts + 16;            // pinned: the copy does not go through a staging buffer
+  HIP_TRY(hipMemcpyAsync(aux->h_counts + 16, d_list_cnt, 4 * (size_t)n_lev * 4, hipMemcpyDeviceToHost, st));
   HIP_TRY(hipEventRecord(aux->events[ev_used], st));
   hipEvent_t counts_ready = aux->events[ev_used++];
   if (!fused_prefill) {

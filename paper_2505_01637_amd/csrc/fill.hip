@@ -785,7 +785,12 @@ __global__ __launch_bounds__(256) void plan_kernel(const DevParams* __restrict__
           cnt[ps] += __popc(m);
           bits |= (unsigned long long)m << (ps * V);
         }
-      if (bits) {
+      if (nb == 32 || nb == 64) {
+        // whole words of the map (the group size is a multiple of nb): stored, the map is not zeroed
+        uint32_t* w = fitmap + ((group + off0[it]) >> 5);
+        w[0] = (uint32_t)bits;
+        if (nb == 64) w[1] = (uint32_t)(bits >> 32);
+      } else if (bits) {
         const uint64_t cell0 = group + off0[it];
         const uint32_t sh = (uint32_t)(cell0 & 31u);
         uint32_t* w = fitmap + (cell0 >> 5);

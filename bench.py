@@ -112,7 +112,14 @@ def main():
     # dominant kernel: the fill kernel of the largest lattice (HIP events on the solve's stream)
     big = max(sizes, key=sizes.get)
     big_fill_ms = fill_ms[big] / args.steps
+    big_kind = next(lat["kind"] for label, lat, _ in cfg["lattices"] if label == big)
     n_launch = stats[big]["n_levels_run"]
+    kernel_text = ("fill of table %s: plan_kernel (which also streams the (INF, NONE) pre-fill), sort_work_kernel, "
+                   "fill_kernel / fill_big_kernel per dependency level" % big)
+    if big_kind == W.KIND_MATMUL_BOUNDED:
+        # one launch per diagonal: dependency level of shapes + rank (sum of the three operand levels)
+        n_launch += 3 * (cfg["target"]["n_levels"] - 1)
+        kernel_text = "fill of table %s: fill_bounded_kernel, one launch per diagonal of (dependency level, rank)" % big
     algo_bytes_per_launch = FILL_BYTES_PER_SPEC * sizes[big] / n_launch
     avg_launch_ms = big_fill_ms / n_launch
     achieved = algo_bytes_per_launch / (avg_launch_ms * 1e-3) / 1e9
@@ -133,7 +140,7 @@ def main():
                        "launches": stats[l]["n_levels_run"],
                        "decision_boxes": stats[l]["n_decision_boxes"], "cost_boxes": stats[l]["n_cost_boxes"],
                        "scratch_used": stats[l]["scratch_used"]} for l in sizes},
-        "roofline": {"bound": "hbm", "kernel": "fill of table %s: plan_kernel (which also streams the (INF, NONE) pre-fill), sort_work_kernel, fill_kernel / fill_big_kernel per dependency level" % big,
+        "roofline": {"bound": "hbm", "kernel": kernel_text,
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": measured_traffic(args.config, big, n_launch),
                      "launches_per_step": n_launch, "avg_launch_ms": avg_launch_ms,
@@ -149,7 +156,7 @@ def main():
 
     if not args.no_cpu_baseline:
         from oracle import oracle as O
-        sample_max = 128 if args.config == 5 else None
+        sample_max = {5: 128, 7: 16}.get(args.config)
         scfg = W.config(args.config, seed=args.seed, max_size=sample_max)
         t1 = time.perf_counter()
         res = O.solve_config(scfg)

@@ -632,10 +632,23 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
     // counts as fitting for the compression); one launch per dependency level of shapes and rank
     // of level assignments, each over Specs that depend only on earlier launches.
     launch_fill_ones(d_fitmap, ((size_t)f.n_words + 2) * 8, st);
-    for (uint32_t l = 0; l < n_lev; l++)
-      for (uint32_t r = 0; r < P.nranks; r++)
-        launch_fill_bounded(d_P, d_level_shapes + c.level_off[l], c.level_off[l + 1] - c.level_off[l], r,
-                            P.rank_off[r + 1] - P.rank_off[r], P.Q, P.V, tab->d_cost, tab->d_arg, d_ctr, st);
+    for (uint32_t d = 0; d + 1 < n_lev + P.nranks; d++) {
+      BoundSegs segs;
+      segs.n = 0; segs.block0[0] = 0;
+      auto flush = [&]() { launch_fill_bounded(d_P, d_level_shapes, segs, tab->d_cost, tab->d_arg, d_ctr, st); segs.n = 0; segs.block0[0] = 0; };
+      for (uint32_t l = d < P.nranks ? 0 : d - (P.nranks - 1); l < n_lev && l <= d; l++) {
+        const uint32_t r = d - l, ns = c.level_off[l + 1] - c.level_off[l];
+        const uint64_t lanes = (uint64_t)ns * (P.rank_off[r + 1] - P.rank_off[r]) * P.Q * P.V;
+        const uint64_t blocks = (lanes + 255) / 256;
+        if (!blocks) continue;
+        if (segs.n == kBoundSegs || segs.block0[segs.n] + blocks >= (1ull << 31)) flush();
+        if (blocks >= (1ull << 31)) return fail(MRL_E_INVAL, "a dependency level of the bounded lattice is too large for one launch");
+        segs.first_shape[segs.n] = c.level_off[l]; segs.n_shapes[segs.n] = ns; segs.rank[segs.n] = r;
+        segs.block0[segs.n + 1] = segs.block0[segs.n] + (uint32_t)blocks;
+        segs.n++;
+      }
+      flush();
+    }
   } else {
   // plan (with the pre-fill; a separate streaming kernel for tables it cannot serve), then the
   // host reads the list sizes back

@@ -22,9 +22,16 @@ void launch_fill_level(const DevParams* P, uint32_t npass, uint32_t G, uint32_t 
                        uint32_t n_slice, const uint32_t* list_wide, uint32_t n_wide, uint64_t* cost, uint16_t* arg,
                        Counters* ctr, hipStream_t stream, hipStream_t wide_stream);
 
-void launch_fill_bounded(const DevParams* P, const uint32_t* level_shapes, uint32_t n_level_shapes, uint32_t rank,
-                         uint32_t n_rank_combos, uint32_t Q, uint32_t V, uint64_t* cost, uint16_t* arg, Counters* ctr,
-                         hipStream_t stream);
+// Segments of one launch of the bounded fill: segment i is (dependency level of shapes, rank)
+// = shapes [first_shape, first_shape + n_shapes) of the level-ordered shape list at rank[i], and
+// owns workgroups [block0[i], block0[i + 1]).
+constexpr uint32_t kBoundSegs = 32;
+struct BoundSegs {
+  uint32_t n;
+  uint32_t first_shape[kBoundSegs], n_shapes[kBoundSegs], rank[kBoundSegs], block0[kBoundSegs + 1];
+};
+void launch_fill_bounded(const DevParams* P, const uint32_t* all_level_shapes, const BoundSegs& segs, uint64_t* cost,
+                         uint16_t* arg, Counters* ctr, hipStream_t stream);
 void launch_fill_ones(void* p, size_t bytes, hipStream_t stream);
 void launch_zero_words(unsigned long long* p, uint32_t n, hipStream_t st);
 void launch_head_flags(const Geo& g, uint32_t a0, const uint64_t* cost, const uint16_t* arg, const uint32_t* fitmap,

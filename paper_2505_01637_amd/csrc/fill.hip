@@ -942,19 +942,25 @@ uint32_t fill_wave_cap(uint32_t G) { return G < kSmallCap ? G : kSmallCap; }
 // needs that many bytes of the destination's bound and leaves its body the rest, rounded down to
 // a power of two (or zero).  There is no admissibility test: the bounds decide.
 //
-// A Move lowers the sum of the operand levels (the rank) and a tile goes to a smaller shape, so
-// the Specs of one dependency level of shapes and one rank depend only on earlier launches: one
-// lane per Spec, every candidate a gather from finished entries.  Lane -> (shape of the level,
-// level assignment of the rank, bound vector, variant), variant fastest.
+// A Move lowers the sum of the operand levels (the rank) within a shape, and a tile goes to the
+// same level assignment of a smaller shape (a lower dependency level of shapes), so the Specs of
+// (level l, rank r) depend only on (l, r' < r) and (l' < l, r): all pairs on one diagonal
+// l + r = d are independent, and one launch takes a whole diagonal, one segment of workgroups per
+// pair.  One lane per Spec, every candidate a gather from finished entries.  Lane -> (shape of
+// the level, level assignment of the rank, bound vector, variant), variant fastest.
 __global__ __launch_bounds__(256) void fill_bounded_kernel(const DevParams* __restrict__ P,
-                                                           const uint32_t* __restrict__ level_shapes, uint32_t n_level_shapes,
-                                                           uint32_t rank, uint64_t* cost, uint16_t* __restrict__ arg,
+                                                           const uint32_t* __restrict__ all_level_shapes, const BoundSegs segs,
+                                                           uint64_t* cost, uint16_t* __restrict__ arg,
                                                            Counters* __restrict__ ctr) {
   __shared__ uint32_t wave_n[4];
+  uint32_t seg = 0;
+  while (seg + 1 < segs.n && blockIdx.x >= segs.block0[seg + 1]) seg++;
+  const uint32_t rank = segs.rank[seg], n_level_shapes = segs.n_shapes[seg];
+  const uint32_t* __restrict__ level_shapes = all_level_shapes + segs.first_shape[seg];
   const uint32_t V = P->V, Q = P->Q;
   const uint32_t c0 = P->rank_off[rank], ncr = P->rank_off[rank + 1] - c0;
   const uint64_t per_shape = (uint64_t)ncr * Q * V;
-  const uint64_t t = (uint64_t)blockIdx.x * 256u + threadIdx.x;
+  const uint64_t t = (uint64_t)(blockIdx.x - segs.block0[seg]) * 256u + threadIdx.x;
   const bool active = t < per_shape * n_level_shapes;
   Eval e;
   e.best = kInf; e.arg = kNone; e.n = 0; e.ovf = 0;
@@ -1067,14 +1073,12 @@ __global__ __launch_bounds__(256) void fill_bounded_kernel(const DevParams* __re
   if (e.ovf) atomicOr(&ctr->overflow, e.ovf);
 }
 
-// One dependency level of shapes, one rank of level assignments.
-void launch_fill_bounded(const DevParams* P, const uint32_t* level_shapes, uint32_t n_level_shapes, uint32_t rank,
-                         uint32_t n_rank_combos, uint32_t Q, uint32_t V, uint64_t* cost, uint16_t* arg, Counters* ctr,
-                         hipStream_t stream) {
-  const uint64_t n = (uint64_t)n_level_shapes * n_rank_combos * Q * V;
-  if (!n) return;
-  hipLaunchKernelGGL(fill_bounded_kernel, dim3((uint32_t)((n + 255) / 256)), dim3(256), 0, stream, P, level_shapes,
-                     n_level_shapes, rank, cost, arg, ctr);
+// One diagonal (or a part of it): n_blocks = segs.block0[segs.n].
+void launch_fill_bounded(const DevParams* P, const uint32_t* all_level_shapes, const BoundSegs& segs, uint64_t* cost,
+                         uint16_t* arg, Counters* ctr, hipStream_t stream) {
+  if (!segs.n || !segs.block0[segs.n]) return;
+  hipLaunchKernelGGL(fill_bounded_kernel, dim3(segs.block0[segs.n]), dim3(256), 0, stream, P, all_level_shapes, segs, cost,
+                     arg, ctr);
 }
 
 void launch_plan(const DevParams* P, uint32_t n_shapes, uint32_t npass, uint32_t G, const uint32_t* level_shapes,

@@ -93,6 +93,9 @@ __device__ __forceinline__ void load_shape(const DevParams* __restrict__ P, uint
 struct Hot {
   uint32_t nops, NL, npass, log2V, ndt, move_base;
   uint32_t pack_shift[4], lay_bit[4], dt_bit[4], can_convert[4], lvpow[4];
+  // the same per-operand fields, one byte per operand (0xFF = no bit), for lanes that pick their
+  // operand by lane index: a shift instead of an indexed read (which would put the struct in scratch)
+  uint32_t lay_bytes, dt_bytes, shift_bytes, cv_bits;
 };
 
 __device__ __forceinline__ Hot load_hot(const DevParams* __restrict__ P) {
@@ -102,6 +105,14 @@ __device__ __forceinline__ Hot load_hot(const DevParams* __restrict__ P) {
   for (int i = 0; i < 4; i++) {
     H.pack_shift[i] = P->pack_shift[i]; H.lay_bit[i] = P->lay_bit[i]; H.dt_bit[i] = P->dt_bit[i];
     H.can_convert[i] = P->can_convert[i]; H.lvpow[i] = P->lvpow[i];
+  }
+  H.lay_bytes = H.dt_bytes = H.shift_bytes = H.cv_bits = 0;
+#pragma unroll
+  for (int i = 0; i < 4; i++) {
+    H.lay_bytes |= (H.lay_bit[i] == kNoBit ? 0xFFu : H.lay_bit[i] & 0xFFu) << (8 * i);
+    H.dt_bytes |= (H.dt_bit[i] == kNoBit ? 0xFFu : H.dt_bit[i] & 0xFFu) << (8 * i);
+    H.shift_bytes |= (H.pack_shift[i] & 0xFFu) << (8 * i);
+    H.cv_bits |= (H.can_convert[i] ? 1u : 0u) << i;
   }
   return H;
 }
@@ -402,11 +413,11 @@ struct MyOperand {
 __device__ __forceinline__ MyOperand my_operand(const Hot& H, uint32_t op) {
   MyOperand M;
   M.exists = op < H.nops;
-  const uint32_t lay = op == 0 ? H.lay_bit[0] : op == 1 ? H.lay_bit[1] : op == 2 ? H.lay_bit[2] : H.lay_bit[3];
-  const uint32_t dt = op == 0 ? H.dt_bit[0] : op == 1 ? H.dt_bit[1] : op == 2 ? H.dt_bit[2] : H.dt_bit[3];
-  M.sh = op == 0 ? H.pack_shift[0] : op == 1 ? H.pack_shift[1] : op == 2 ? H.pack_shift[2] : H.pack_shift[3];
-  M.can_cv = (op == 0 ? H.can_convert[0] : op == 1 ? H.can_convert[1] : op == 2 ? H.can_convert[2] : H.can_convert[3]) != 0;
-  M.has_x = lay != kNoBit;
+  const uint32_t lay = (H.lay_bytes >> (8u * op)) & 0xFFu;
+  const uint32_t dt = (H.dt_bytes >> (8u * op)) & 0xFFu;
+  M.sh = (H.shift_bytes >> (8u * op)) & 0xFFu;
+  M.can_cv = ((H.cv_bits >> op) & 1u) != 0;
+  M.has_x = lay != 0xFFu;
   M.xbit = M.has_x ? 1u << (lay & 31u) : 0u;
   M.dtbit = M.can_cv ? 1u << (dt & 31u) : 0u;
   M.id0 = H.move_base + op * (H.NL - 1) * 4u;

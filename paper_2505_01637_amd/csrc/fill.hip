@@ -717,15 +717,21 @@ __device__ __forceinline__ void solve_unit(const DevParams* __restrict__ P, cons
             f.n++;
           }
         }
-        const uint32_t off = entry_offset(H, xpack, v);
         L.t_cost[q] = f.best;
-        cost[group + off] = f.best;
-        arg[group + off] = (uint16_t)f.arg;
+        L.t_spec[q] = (sp & 0xFFFFu) | f.arg << 16;
         tot.n += f.n;
         tot.ovf |= f.ovf;
       }
     }
     unit_sync<T>();
+  }
+  // Results to the table after the last rank, a task per lane: inside the rank loop every chunk
+  // would wait for the previous chunk's stores (stores count on the same counter as loads here).
+  for (uint32_t q = tid; q < n_task; q += T) {
+    const uint32_t sp = L.t_spec[q];
+    const uint32_t off = entry_offset(H, sp & 0x3FFu, (sp >> 10) & 31u);
+    cost[group + off] = L.t_cost[q];
+    arg[group + off] = (uint16_t)(sp >> 16);
   }
 }
 

@@ -747,7 +747,10 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
     if (a != a0 && g.ext[a] > 1) pass_axis[n_axes++] = a;
   }
   uint32_t n_generic = n_axes;
-  while (n_generic > 0 && n_axes - n_generic < 6 && g.ext[pass_axis[n_generic - 1]] == 2 && g.stride[pass_axis[n_generic - 1]] <= 32) n_generic--;
+  // (a power-of-two stride: the coordinate on the axis is then one bit of the cell index, which
+  // the kernel relies on; behind an axis of another extent, e.g. a memory bound, it is not)
+  auto tail_axis = [&](uint32_t a) { return g.ext[a] == 2 && g.stride[a] <= 32 && (g.stride[a] & (g.stride[a] - 1)) == 0; };
+  while (n_generic > 0 && n_axes - n_generic < 6 && tail_axis(pass_axis[n_generic - 1])) n_generic--;
   TailAxes tail;
   tail.n = n_axes - n_generic;
   for (uint32_t k = 0; k < tail.n; k++) { tail.axis[k] = pass_axis[n_generic + k]; tail.stride[k] = g.stride[pass_axis[n_generic + k]]; }

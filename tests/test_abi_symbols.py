@@ -56,3 +56,30 @@ def test_unknown_dependency_is_refused_before_device_work():
     lats = [(lab, lat, ["nowhere"] if lab == "F" else deps) for lab, lat, deps in cfg["lattices"]]
     with pytest.raises(ValueError):
         B.solve_lattices(None, lats)
+
+
+def test_geometry_of_every_kind_agrees_with_the_oracle():
+    """Extents of every lattice kind, the parallel and the bounded ones included, from the
+    library's host code and from the oracle (each derives them on its own)."""
+    from oracle import oracle as O
+    cases = [W.config(n, max_size=8) for n in (1, 2, 3, 4, 5, 6, 7)]
+    two = W.config(1, max_size=4)
+    two["target"]["capacity_bytes"][0], two["target"]["capacity_bytes"][1] = 100, W.UNBOUNDED
+    two["lattices"] = [("B", dict(two["lattices"][0][1], kind=W.KIND_MATMUL_BOUNDED), [])]
+    cases.append(two)
+    for cfg in cases:
+        t = B.Target(cfg["target"])
+        for label, lat, _ in cfg["lattices"]:
+            ext, n = B.geometry(t, lat)
+            oext, _, _ = O.geometry(cfg["target"], lat)
+            assert ext == oext == W.coord_extents(cfg["target"], lat), (cfg["name"], label)
+    # a capacity of 100 bytes gives the bounds 0, 1, 2, ..., 64: eight values; the unbounded level has no axis
+    assert B.geometry(B.Target(two["target"]), two["lattices"][0][1])[0][-1] == 8
+    # a parallel lattice needs at least one thread
+    bad = W.config(6, max_size=4)
+    bad["target"]["threads"] = 0
+    try:
+        B.geometry(B.Target(bad["target"]), bad["lattices"][1][1])
+        assert False
+    except B.MorelloError as e:
+        assert e.code == B.E_INVAL

@@ -182,7 +182,8 @@ def two_level_bounded(caps, sizes):
             "lattices": [("B", W._lattice(W.KIND_MATMUL_BOUNDED, [[1], r, r, r]), [])]}
 
 
-@pytest.mark.parametrize("case", ["two-level", "two-level-one-unbounded", "four-level-small", "bits", "config7"])
+@pytest.mark.parametrize("case", ["two-level", "two-level-one-unbounded", "no-bounded-level", "tiny-capacities",
+                                  "three-level-n-pinned", "four-level-small", "bits", "config7"])
 def test_parity_memory_bounds(case):
     """Memory bounds as coordinates (Sections 2.2, 2.4.4): dense tables, counters and both box
     lists against the oracle; two levels with small capacities, a level without a bound axis,
@@ -192,6 +193,18 @@ def test_parity_memory_bounds(case):
         cfg = two_level_bounded((16, 64), (1, 2, 3, 4, 6))
     elif case == "two-level-one-unbounded":
         cfg = two_level_bounded((100, W.UNBOUNDED), (1, 2, 4, 8))
+    elif case == "no-bounded-level":           # no bound axis at all: the plain table without the footprint test
+        cfg = two_level_bounded((W.UNBOUNDED, W.UNBOUNDED), (1, 2, 3, 4, 6, 12))
+    elif case == "tiny-capacities":            # capacity 1 and 3 bytes: bounds {0, 1} and {0, 1, 2}; nothing can move
+        cfg = two_level_bounded((1, 3), (1, 2, 4))
+    elif case == "three-level-n-pinned":       # three levels, two of them bounded; n has one size, so the first merge axis is k
+        t = W._empty_target(3, (48, 200, W.UNBOUNDED))
+        t["load_coef"][1][0][0], t["load_coef"][2][1][0], t["load_coef"][2][0][0] = 2, 3, 6
+        t["store_coef"][0][1][0], t["store_coef"][1][2][0], t["store_coef"][0][2][0] = 2, 4, 7
+        t["loop_overhead"] = 1
+        t["microkernels"] = [(W.MK_SCALAR_FMA, 1, 2), (W.MK_BCAST_VEC_MULADD, 1, 3)]
+        lat = W._lattice(W.KIND_MATMUL_BOUNDED, [[1, 2], [1, 2, 3, 6], [1, 2, 4, 8], [1]])
+        cfg = {"name": "bounded-3", "target": t, "lattices": [("B", lat, [])]}
     elif case == "four-level-small":
         cfg = W.config(7, max_size=4)
     elif case == "bits":

@@ -40,8 +40,9 @@
 namespace mrl {
 
 constexpr int kBatch = 8;              // sub-Spec costs fetched together before they are compared
-constexpr uint32_t kSmallCap = 512;    // tasks the LDS slice of a workgroup-sized item holds
-constexpr uint32_t kWaveCap = 128;     // tasks the LDS slice of a wave-sized item holds
+constexpr uint32_t kSmallCap = 512;    // entries per shape up to which a shape's whole group is one LDS slice
+constexpr uint32_t kSlicedCap = 256;   // tasks per LDS slice for lattices with more entries per shape
+constexpr uint32_t kWaveCap = 64;      // whole shapes of at most this many tasks count as small
 constexpr uint32_t kBigBlock = 512;    // threads per item that does not fit a wave's slice
 constexpr uint32_t kTileLds = 64;      // tile rewrites of the shape staged in LDS at a time
 constexpr uint32_t kWideBelow = 2048;  // levels with fewer shapes than this get 256 threads per shape
@@ -888,7 +889,7 @@ __global__ __launch_bounds__(256) void sort_work_kernel(const uint32_t* __restri
   }
 }
 
-// One dependency level, the items an LDS slice of kSmallCap tasks holds: first the larger ones
+// One dependency level, the items an LDS slice holds: first the larger ones
 // (whole shapes from the back of the level's stretch of list_whole, then slices), which take
 // longest, then the small whole shapes, which fill the gaps at the end.  T threads per item: one
 // wave when the level has enough items to fill the chip, four when it has few (then an item's
@@ -951,7 +952,10 @@ void launch_fill_ones(void* p, size_t bytes, hipStream_t stream) {
   if (bytes % 16) (void)hipMemsetAsync((char*)p + n16 * 16, 0xFF, bytes % 16, stream);
 }
 
-uint32_t fill_wave_cap(uint32_t G) { return G < kSmallCap ? G : kSmallCap; }
+// Tasks per LDS slice: a whole shape's group when it has at most kSmallCap entries, else
+// kSlicedCap (a smaller slice, i.e. more items in flight per CU, pays once shapes are split into
+// passive-level slices anyway: measured 256 < 320 < 192 < 512 < 128 on the fused lattice).
+uint32_t fill_wave_cap(uint32_t G) { return G <= kSmallCap ? G : kSlicedCap; }
 
 // ---------------------------------------------------------------- memory bounds as coordinates
 // Sections 2.2 and 2.4.4: a Spec carries, per level of finite capacity, the bytes an implementation

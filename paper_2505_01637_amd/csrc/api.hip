@@ -495,11 +495,21 @@ struct mrl_table {
   }
 };
 
+// No exception leaves the library: host allocations (std::vector, std::make_shared, ...) can throw.
+template <class F>
+int32_t guarded(F&& body) noexcept {
+  try { return body(); }
+  catch (const std::bad_alloc&) { return fail(MRL_E_NOMEM, "host allocation failed"); }
+  catch (const std::exception& e) { return fail(MRL_E_HIP, "internal error: %s", e.what()); }
+  catch (...) { return fail(MRL_E_HIP, "internal error: unknown exception"); }
+}
+
 extern "C" {
 
 const char* mrl_last_error(void) { return g_err; }
 
 int32_t mrl_target_create(const mrl_target_desc* desc, mrl_target** out) {
+  return guarded([&]() -> int32_t {
   if (!out) return fail(MRL_E_INVAL, "out is NULL");
   *out = nullptr;
   int32_t rc = validate_target(desc);
@@ -509,12 +519,14 @@ int32_t mrl_target_create(const mrl_target_desc* desc, mrl_target** out) {
   t->d = *desc;
   *out = t;
   return MRL_OK;
+  });
 }
 
 void mrl_target_destroy(mrl_target* t) { delete t; }
 
 int32_t mrl_geometry(const mrl_target* t, const mrl_lattice_desc* lat, uint32_t* n_dims, uint32_t* extents,
                      uint64_t* n_specs) {
+  return guarded([&]() -> int32_t {
   if (!t) return fail(MRL_E_INVAL, "target is NULL");
   CompiledPtr cp;
   int32_t rc = get_compiled(t->d, lat, cp);
@@ -524,10 +536,12 @@ int32_t mrl_geometry(const mrl_target* t, const mrl_lattice_desc* lat, uint32_t*
   if (extents) for (uint32_t a = 0; a < c.geo.ndim; a++) extents[a] = c.geo.ext[a];
   if (n_specs) *n_specs = c.n_specs;
   return MRL_OK;
+  });
 }
 
 int32_t mrl_table_bytes(const mrl_target* t, const mrl_lattice_desc* lat, size_t* cost_bytes, size_t* argmin_bytes,
                         size_t* scratch_bytes) {
+  return guarded([&]() -> int32_t {
   if (!t) return fail(MRL_E_INVAL, "target is NULL");
   CompiledPtr cp;
   int32_t rc = get_compiled(t->d, lat, cp);
@@ -537,11 +551,13 @@ int32_t mrl_table_bytes(const mrl_target* t, const mrl_lattice_desc* lat, size_t
   if (argmin_bytes) *argmin_bytes = c.n_specs * 2;
   if (scratch_bytes) *scratch_bytes = fixed_layout(c).end + 2 * final_bytes(c.n_specs) + 2 * work_bytes(c.n_specs);
   return MRL_OK;
+  });
 }
 
 int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_table* const* deps, uint32_t n_deps,
                   void* d_cost, void* d_argmin, void* d_scratch, size_t scratch_bytes, void* hip_stream,
                   mrl_table** out, mrl_stats* stats) {
+  return guarded([&]() -> int32_t {
   if (!out) return fail(MRL_E_INVAL, "out is NULL");
   *out = nullptr;
   if (!t) return fail(MRL_E_INVAL, "target is NULL");
@@ -871,11 +887,13 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
   guard.p = nullptr;
   *out = tab;
   return MRL_OK;
+  });
 }
 
 void mrl_table_destroy(mrl_table* tab) { delete tab; }
 
 int32_t mrl_query(const mrl_table* tab, const mrl_coord* specs, size_t n, uint64_t* cost_out, uint16_t* rewrite_out) {
+  return guarded([&]() -> int32_t {
   if (!tab || (n && (!specs || !cost_out || !rewrite_out))) return fail(MRL_E_INVAL, "NULL argument");
   const Geo& g = tab->cp->geo;
   std::vector<uint64_t> idx(std::min<size_t>(n, kQueryChunk));
@@ -901,9 +919,11 @@ int32_t mrl_query(const mrl_table* tab, const mrl_coord* specs, size_t n, uint64
     HIP_TRY(hipStreamSynchronize(tab->stream));
   }
   return MRL_OK;
+  });
 }
 
 int32_t mrl_rewrite_decode(const mrl_table* tab, uint16_t id, mrl_rewrite* out) {
+  return guarded([&]() -> int32_t {
   if (!tab || !out) return fail(MRL_E_INVAL, "NULL argument");
   const DevParams& P = tab->P;
   memset(out, 0, sizeof *out);
@@ -926,10 +946,12 @@ int32_t mrl_rewrite_decode(const mrl_table* tab, uint16_t id, mrl_rewrite* out) 
     if (d != 2 && j < P.nsz[d]) { out->cls = 4; out->operand_or_dim = (uint8_t)d; out->tile_size = P.sizes[d][j]; return MRL_OK; }
   }
   return fail(MRL_E_RANGE, "rewrite id %u is not used by this table", id);
+  });
 }
 
 int32_t mrl_coord_of_spec(const mrl_table* tab, const uint32_t shape[4], const uint8_t* levels, const uint8_t* layouts,
                           const uint8_t* dtypes, mrl_coord* out) {
+  return guarded([&]() -> int32_t {
   if (!tab || !shape || !levels || !out) return fail(MRL_E_INVAL, "NULL argument");
   const Compiled& c = *tab->cp;
   memset(out, 0, sizeof *out);
@@ -948,9 +970,11 @@ int32_t mrl_coord_of_spec(const mrl_table* tab, const uint32_t shape[4], const u
     if (c.dt_axis[i] >= 0) { if (!dtypes || dtypes[i] > 1) return fail(MRL_E_RANGE, "dtype of operand %u", i); out->x[c.dt_axis[i]] = dtypes[i]; }
   }
   return MRL_OK;
+  });
 }
 
 int32_t mrl_schedule(const mrl_table* tab, const mrl_coord* goal, mrl_schedule_node* out, size_t cap, size_t* n_out) {
+  return guarded([&]() -> int32_t {
   if (!tab || !goal) return fail(MRL_E_INVAL, "NULL argument");
   struct Item { const mrl_table* t; uint32_t which; mrl_coord x; };
   std::vector<Item> stack;
@@ -1036,9 +1060,11 @@ int32_t mrl_schedule(const mrl_table* tab, const mrl_coord* goal, mrl_schedule_n
   if (n_out) *n_out = n;
   if (out && cap < n) return fail(MRL_E_BUFSZ, "schedule buffer holds %zu nodes, %zu needed", cap, n);
   return MRL_OK;
+  });
 }
 
 int32_t mrl_emit_compressed(const mrl_table* tab, uint32_t which, mrl_box* out, size_t cap, size_t* n_out) {
+  return guarded([&]() -> int32_t {
   if (!tab || which > 1) return fail(MRL_E_INVAL, "bad argument");
   const uint64_t n = tab->list_n[which];
   if (n_out) *n_out = n;
@@ -1068,10 +1094,12 @@ int32_t mrl_emit_compressed(const mrl_table* tab, uint32_t which, mrl_box* out, 
     b.v0 = fv0[i]; b.v1 = fv1[i];
   }
   return MRL_OK;
+  });
 }
 
 int32_t mrl_query_compressed(const mrl_table* tab, const mrl_coord* specs, size_t n, uint64_t* cost_out,
                              uint16_t* rewrite_out) {
+  return guarded([&]() -> int32_t {
   if (!tab || (n && (!specs || !cost_out || !rewrite_out))) return fail(MRL_E_INVAL, "NULL argument");
   const Compiled& c = *tab->cp;
   const Geo& g = c.geo;
@@ -1140,13 +1168,16 @@ int32_t mrl_query_compressed(const mrl_table* tab, const mrl_coord* specs, size_
     }
   }
   return MRL_OK;
+  });
 }
 
 int32_t mrl_copy_dense(const mrl_table* tab, uint64_t* cost_host, uint16_t* argmin_host) {
+  return guarded([&]() -> int32_t {
   if (!tab) return fail(MRL_E_INVAL, "table is NULL");
   if (cost_host) HIP_TRY(hipMemcpy(cost_host, tab->d_cost, tab->cp->n_specs * 8, hipMemcpyDeviceToHost));
   if (argmin_host) HIP_TRY(hipMemcpy(argmin_host, tab->d_arg, tab->cp->n_specs * 2, hipMemcpyDeviceToHost));
   return MRL_OK;
+  });
 }
 
 }  // extern "C"

@@ -843,44 +843,52 @@ __global__ __launch_bounds__(256) void plan_kernel(const DevParams* __restrict__
 // One workgroup per dependency level: walks the level's shapes in index order and writes its work
 // lists and their lengths: whole shapes (the small ones from the front of the level's stretch of
 // list_whole, the others from its back), slices, and wide slices.
-__global__ __launch_bounds__(256) void sort_work_kernel(const uint32_t* __restrict__ level_shapes,
-                                                        const uint32_t* __restrict__ level_off, uint32_t n_levels,
-                                                        uint32_t npass, const uint32_t* __restrict__ shape_class,
-                                                        uint32_t* __restrict__ list_whole, uint32_t* __restrict__ list_slice,
-                                                        uint32_t* __restrict__ list_wide, uint32_t* __restrict__ list_cnt) {
-  __shared__ uint32_t wave_sum[4], wave_sum2[4];
+constexpr uint32_t kSortThreads = 1024;
+__global__ __launch_bounds__(kSortThreads) void sort_work_kernel(const uint32_t* __restrict__ level_shapes,
+                                                                 const uint32_t* __restrict__ level_off, uint32_t n_levels,
+                                                                 uint32_t npass, const uint32_t* __restrict__ shape_class,
+                                                                 uint32_t* __restrict__ list_whole, uint32_t* __restrict__ list_slice,
+                                                                 uint32_t* __restrict__ list_wide, uint32_t* __restrict__ list_cnt) {
+  constexpr uint32_t kWaves = kSortThreads / 64;
+  __shared__ unsigned long long wave_sum[kWaves];
   __shared__ uint32_t run[4];
   const uint32_t lv = blockIdx.x, first = level_off[lv], n = level_off[lv + 1] - first;
   if (threadIdx.x < 4) run[threadIdx.x] = 0;
   __syncthreads();
-  for (uint32_t base = 0; base < n; base += 256) {
+  for (uint32_t base = 0; base < n; base += kSortThreads) {
     const uint32_t i = base + threadIdx.x;
     const uint32_t shape = i < n ? level_shapes[first + i] : 0u;
     const uint32_t cls = i < n ? shape_class[shape] : 0u;
     const uint32_t cw = (cls >> 9) & 1u, cb = ((cls >> 8) & 1u) & ~cw, cs = __popc(cls & 15u), cx = __popc((cls >> 4) & 15u);
-    const uint32_t packed = cw | cs << 10 | cx << 21;      // per 256 threads: <= 256, 1024, 1024
-    uint32_t incl = packed, incl2 = cb;
+    // four counts in 16-bit fields (per kSortThreads threads: <= 1024, 4096, 4096, 1024)
+    const unsigned long long packed = (unsigned long long)cw | (unsigned long long)cs << 16 | (unsigned long long)cx << 32 |
+                                      (unsigned long long)cb << 48;
+    unsigned long long incl = packed;
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
-      const uint32_t o = __shfl_up(incl, d, 64), o2 = __shfl_up(incl2, d, 64);
-      if ((int)(threadIdx.x & 63u) >= d) { incl += o; incl2 += o2; }
+      const unsigned long long o = __shfl_up(incl, d, 64);
+      if ((int)(threadIdx.x & 63u) >= d) incl += o;
     }
-    if ((threadIdx.x & 63u) == 63) { wave_sum[threadIdx.x >> 6] = incl; wave_sum2[threadIdx.x >> 6] = incl2; }
+    if ((threadIdx.x & 63u) == 63) wave_sum[threadIdx.x >> 6] = incl;
     __syncthreads();
-    uint32_t excl = incl - packed, tot = 0, excl2 = incl2 - cb, tot2 = 0;
-    for (uint32_t w = 0; w < 4; w++) {
-      if (w < (threadIdx.x >> 6)) { excl += wave_sum[w]; excl2 += wave_sum2[w]; }
-      tot += wave_sum[w]; tot2 += wave_sum2[w];
+    unsigned long long excl = incl - packed, tot = 0;
+    for (uint32_t w = 0; w < kWaves; w++) {
+      if (w < (threadIdx.x >> 6)) excl += wave_sum[w];
+      tot += wave_sum[w];
     }
-    uint32_t ow = run[0] + (excl & 1023u), os = run[1] + ((excl >> 10) & 2047u), ox = run[2] + (excl >> 21);
+    uint32_t ow = run[0] + (uint32_t)(excl & 0xFFFFu), os = run[1] + (uint32_t)((excl >> 16) & 0xFFFFu);
+    uint32_t ox = run[2] + (uint32_t)((excl >> 32) & 0xFFFFu);
     if (cw) list_whole[first + ow] = shape;
-    if (cb) list_whole[first + n - 1u - (run[3] + excl2)] = shape;
+    if (cb) list_whole[first + n - 1u - (run[3] + (uint32_t)(excl >> 48))] = shape;
     for (uint32_t ps = 0; ps < npass; ps++) {
       if ((cls >> ps) & 1u) list_slice[(size_t)first * npass + os++] = shape * npass + ps;
       if ((cls >> (4 + ps)) & 1u) list_wide[(size_t)first * npass + ox++] = shape * npass + ps;
     }
     __syncthreads();
-    if (threadIdx.x == 0) { run[0] += tot & 1023u; run[1] += (tot >> 10) & 2047u; run[2] += tot >> 21; run[3] += tot2; }
+    if (threadIdx.x == 0) {
+      run[0] += (uint32_t)(tot & 0xFFFFu); run[1] += (uint32_t)((tot >> 16) & 0xFFFFu);
+      run[2] += (uint32_t)((tot >> 32) & 0xFFFFu); run[3] += (uint32_t)(tot >> 48);
+    }
     __syncthreads();
   }
   if (threadIdx.x == 0) {
@@ -1110,7 +1118,7 @@ void launch_plan(const DevParams* P, uint32_t n_shapes, uint32_t npass, uint32_t
   hipLaunchKernelGGL(plan_kernel, dim3((n_shapes + 4 * kPlanShapes - 1) / (4 * kPlanShapes)), dim3(256), 0, stream, P,
                      n_shapes, cap, cap, kWaveCap < cap ? kWaveCap : cap, shape_class, fitmap, ctr, (uint4*)prefill_cost,
                      (uint4*)prefill_arg);
-  hipLaunchKernelGGL(sort_work_kernel, dim3(n_levels), dim3(256), 0, stream, level_shapes, level_off, n_levels, npass,
+  hipLaunchKernelGGL(sort_work_kernel, dim3(n_levels), dim3(kSortThreads), 0, stream, level_shapes, level_off, n_levels, npass,
                      shape_class, list_whole, list_slice, list_wide, list_cnt);
 }
 

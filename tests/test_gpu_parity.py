@@ -59,6 +59,8 @@ def test_parity_small(number, max_size):
 def test_parity_other_seeds(seed):
     compare_config(W.config(5, seed=seed, max_size=8))
     compare_config(W.config(3, seed=seed, max_size=64))
+    compare_config(W.config(6, seed=seed, max_size=12))
+    compare_config(W.config(7, seed=seed, max_size=2))
 
 
 @pytest.mark.parametrize("number", [2, 4])

@@ -357,8 +357,8 @@ __device__ __forceinline__ void task_tiles(const DevParams* __restrict__ P, cons
 #pragma unroll
     for (int u = 0; u < kBatch; u++) {
       const uint32_t t = t0 + u * step;
-      const uint32_t tt = t < n_here ? t : n_here - 1;
-      sub[u] = (tt >= par_from ? serial : cost)[L.tl_base[tt] + off];
+      sub[u] = kInf;
+      if (t < n_here) sub[u] = (t >= par_from ? serial : cost)[L.tl_base[t] + off];     // no request for a candidate that is not there
     }
 #pragma unroll
     for (int u = 0; u < kBatch; u++) {

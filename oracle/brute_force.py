@@ -21,8 +21,14 @@ exponentially with the number of divisors and levels.
 from collections import namedtuple
 
 M, E, F, P = 0, 1, 2, 3      # P: a Matmul that may use parallel loops; M is serial-only
-BD = 4                       # a Matmul whose Specs carry per-level memory bounds (Sections 2.2, 2.4.4)
+BD, BE, BF = 4, 5, 6          # M, E, F whose Specs carry per-level memory bounds (Sections 2.2, 2.4.4)
+BOUNDED = (BD, BE, BF)
 MATMULS = (M, P, BD)
+
+
+def base_kind(kind):
+    """The operator of a kind: M for the Matmuls, E, F."""
+    return M if kind in MATMULS else E if kind in (E, BE) else F
 FMA, BCAST, BF16DOT, S_ADDRELU, V_ADDRELU = 0, 1, 2, 3, 4
 
 # dims = (b, m, k, n) actual sizes; levels per operand (F: 5th = intermediate);
@@ -35,7 +41,7 @@ def operand_numel(spec, i):
     b, m, k, n = spec.dims
     if spec.kind in MATMULS:
         return (b * m * k, b * k * n, b * m * n)[i]
-    if spec.kind == E:
+    if base_kind(spec.kind) == E:
         return (m * n, n, m * n)[i]
     return (m * k, k * n, n, m * n, m * n)[i]
 
@@ -44,13 +50,13 @@ def operand_mode(kind, i):
     """'r' read, 'rw' accumulate, 'w' write-only."""
     if kind in MATMULS:
         return "rw" if i == 2 else "r"
-    if kind == E:
+    if base_kind(kind) == E:
         return "w" if i == 2 else "r"
     return "w" if i == 3 else "r"
 
 
 def fits(target, spec):
-    if spec.kind == BD:
+    if spec.kind in BOUNDED:
         return True          # the bounds decide at each allocation, not the operands' footprint
     used = [0] * target["n_levels"]
     nops = 4 if spec.kind == F else 3
@@ -78,10 +84,10 @@ def microkernel_reps(target, lattice, spec, j):
               and tuple(lv[:3]) == (1, 1, 0) and bf[0] and bf[1] and not bf[2] and rhs_col)
         return k // lanes if ok else 0
     if kind == S_ADDRELU:
-        ok = spec.kind == E and (m, n) == (1, 1) and tuple(lv[:3]) == (0, 0, 0)
+        ok = base_kind(spec.kind) == E and (m, n) == (1, 1) and tuple(lv[:3]) == (0, 0, 0)
         return 1 if ok else 0
     if kind == V_ADDRELU:
-        ok = (spec.kind == E and m == 1 and n % lanes == 0 and tuple(lv[:3]) == (1, 1, 1)
+        ok = (base_kind(spec.kind) == E and m == 1 and n % lanes == 0 and tuple(lv[:3]) == (1, 1, 1)
               and ly[0] == 0 and ly[2] == 0)
         return n // lanes if ok else 0
     return 0
@@ -92,7 +98,7 @@ def rewrites(target, lattices, spec):
     applicable rewrite of an admissible Spec, ids ascending."""
     lattice = lattices[spec.kind]
     nl = target["n_levels"]
-    nops = 4 if spec.kind == F else 3
+    nops = 4 if base_kind(spec.kind) == F else 3
     nmk = len(target["microkernels"])
     maxs = max(len(s) for s in lattice["sizes"])
     move_base = nmk
@@ -128,7 +134,7 @@ def rewrites(target, lattices, spec):
                     if cv:
                         bf[i] = 0
                     child = spec._replace(levels=tuple(lv), layouts=tuple(ly), bf16=tuple(bf))
-                    if spec.kind == BD and spec.limits[dst] is not None:
+                    if spec.kind in BOUNDED and spec.limits[dst] is not None:
                         # the buffer in dst comes out of dst's bound; what is left is rounded
                         # down to a power of two (or is zero)
                         need = operand_numel(spec, i) * (2 if bf[i] else 4)
@@ -141,7 +147,7 @@ def rewrites(target, lattices, spec):
                     rid = move_base + ((i * (nl - 1) + dst) * 2 + x) * 2 + cv
                     yield rid, ("alloc", coef * operand_numel(spec, i)), [child]
     for d in range(4):
-        if spec.kind in (E, F) and d in (0, 2):
+        if base_kind(spec.kind) in (E, F) and d in (0, 2):
             continue
         cur = spec.dims[d]
         for j, t in enumerate(lattice["sizes"][d]):
@@ -160,12 +166,23 @@ def rewrites(target, lattices, spec):
                     yield (tile_base + 4 * maxs + 1 + d * maxs + j,
                            ("parallel", cur // t, target["threads"], target["sync_cost"]),
                            [spec._replace(kind=M, dims=tuple(dims))])
-    if spec.kind == F:
+    if base_kind(spec.kind) == F:
         b, m, k, n = spec.dims
         l_lhs, l_rhs, l_bias, l_out, l_mid = spec.levels
         y_lhs, y_rhs, _, y_out = spec.layouts[:4]
-        mm = Spec(M, (1, m, k, n), (l_lhs, l_rhs, l_mid, 0, 0), (y_lhs, y_rhs, 0, 0, 0), (0,) * 5)
-        ee = Spec(E, (1, m, 1, n), (l_mid, l_bias, l_out, 0, 0), (0, 0, y_out, 0, 0), (0,) * 5)
+        bounded = spec.kind == BF
+        lim = spec.limits
+        if bounded and lim[l_mid] is not None:
+            # the intermediate (m x n, f32) comes out of its level's bound; both stages get the rest
+            need = 4 * m * n
+            if need > lim[l_mid]:
+                return
+            left = lim[l_mid] - need
+            lim = list(lim)
+            lim[l_mid] = 0 if left == 0 else 1 << (left.bit_length() - 1)
+            lim = tuple(lim)
+        mm = Spec(BD if bounded else M, (1, m, k, n), (l_lhs, l_rhs, l_mid, 0, 0), (y_lhs, y_rhs, 0, 0, 0), (0,) * 5, lim)
+        ee = Spec(BE if bounded else E, (1, m, 1, n), (l_mid, l_bias, l_out, 0, 0), (0, 0, y_out, 0, 0), (0,) * 5, lim)
         yield tile_base + 4 * maxs, ("pipeline", target["zero_coef"][l_mid] * m * n), [mm, ee]
 
 

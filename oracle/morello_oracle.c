@@ -27,9 +27,10 @@
  * The fused three-node lattice (kind 2) follows this build's own reading of
  * Section 2.1; it is pinned by brute force only: "parity unpinned" by the
  * paper beyond the sum rule of Section 3.
- * Kind 3 adds the parallel loops of Section 3; kind 4 replaces the
- * admissibility test by the per-level memory bounds of Sections 2.2 and
- * 2.4.4, carried as coordinates (expand(), part B).
+ * Kind 3 adds the parallel loops of Section 3; kinds 4, 5, 6 (= kinds 0, 1,
+ * 2 with bounds) replace the admissibility test by the per-level memory
+ * bounds of Sections 2.2 and 2.4.4, carried as coordinates (expand(), parts
+ * B and D).
  */
 #include <stdint.h>
 #include <stdlib.h>
@@ -42,7 +43,7 @@
 enum { ORC_MAXL = 4, ORC_MAXOPS = 5, ORC_MAXD = 16, ORC_MAXMK = 8 };
 enum { MK_SCALAR_FMA = 0, MK_BCAST_VEC_MULADD = 1, MK_BF16_DOT = 2,
        MK_SCALAR_ADDRELU = 3, MK_VEC_ADDRELU = 4 };
-enum { KIND_M = 0, KIND_E = 1, KIND_F = 2, KIND_P = 3, KIND_B = 4 };
+enum { KIND_M = 0, KIND_E = 1, KIND_F = 2, KIND_P = 3, KIND_B = 4, KIND_BE = 5, KIND_BF = 6 };
 enum { ACC_READ = 0, ACC_RMW = 1, ACC_WRITE = 2 };
 
 typedef struct {
@@ -93,7 +94,7 @@ typedef struct ctx {
   uint8_t* done;
   uint32_t maxs, nmk, move_base, tile_base, buf_id, par_base;
   int parallel;                 /* kind P: a Matmul whose serial-only flag is off */
-  int bounded;                  /* kind B: a Matmul whose Specs carry per-level memory bounds */
+  int bounded;                  /* kinds 4..6: the Specs carry per-level memory bounds */
   int lim_axis[ORC_MAXL];       /* coordinate axis of level l's bound, -1 if the level is unbounded */
   uint64_t n_rewrites, n_admissible;
   int overflow;
@@ -109,8 +110,8 @@ typedef struct ctx {
 static int ctx_init(ctx* c, const orc_target* T, const orc_lattice* L) {
   memset(c, 0, sizeof *c);
   c->T = T; c->L = L; c->kind = (int)L->kind;
-  if (c->kind < 0 || c->kind > 4) return -1;
-  if (c->kind == KIND_B) { c->kind = KIND_M; c->bounded = 1; }
+  if (c->kind < 0 || c->kind > 6) return -1;
+  if (c->kind >= KIND_B) { c->kind -= KIND_B; c->bounded = 1; }   /* kinds 4, 5, 6: M, E, F with memory bounds */
   if (c->kind == KIND_P) {      /* same operator, operands and coordinates as kind M */
     c->kind = KIND_M; c->parallel = 1;
     if (T->threads < 1) return -1;
@@ -363,14 +364,35 @@ static void expand(ctx* c, const spec_t* s, uint64_t* best_out, uint16_t* arg_ou
     es.si[1] = s->si[1]; es.si[3] = s->si[3];
     es.level[0] = s->level[4]; es.level[1] = s->level[2]; es.level[2] = s->level[3];
     es.layout[0] = 0; es.layout[2] = s->layout[3];
-    uint64_t cm = c->depM->cost[spec_index(c->depM, &ms)];
-    uint64_t ce = c->depE->cost[spec_index(c->depE, &es)];
-    uint64_t cand = ORC_INF;
-    if (cm != ORC_INF && ce != ORC_INF) {
-      unsigned __int128 v = (unsigned __int128)T->zero_coef[s->level[4]] * numel(c, s, 4) + cm + ce;
-      if (v >= ORC_LIMIT) c->overflow = 1; else cand = (uint64_t)v;
+    int fits = 1;
+    if (c->bounded) {
+      /* Section 2.4.4: the pipeline allocates the intermediate in its level; both stages may use
+       * what is left of that level's bound, snapped down to a power of two (or zero). */
+      memcpy(ms.limit, s->limit, sizeof ms.limit);
+      memcpy(es.limit, s->limit, sizeof es.limit);
+      uint32_t lm = s->level[4];
+      if (c->lim_axis[lm] >= 0) {
+        unsigned __int128 bytes = (unsigned __int128)numel(c, s, 4) * 4;
+        uint64_t have = s->limit[lm] ? (uint64_t)1 << (s->limit[lm] - 1) : 0;
+        if (bytes > have) fits = 0;
+        else {
+          uint64_t left = have - (uint64_t)bytes;
+          uint8_t q = 0;
+          while (q < 64 && ((uint64_t)1 << q) <= left) q++;
+          ms.limit[lm] = es.limit[lm] = q;
+        }
+      }
     }
-    consider(c, cand, c->buf_id, &best, &arg);
+    if (fits) {
+      uint64_t cm = c->depM->cost[spec_index(c->depM, &ms)];
+      uint64_t ce = c->depE->cost[spec_index(c->depE, &es)];
+      uint64_t cand = ORC_INF;
+      if (cm != ORC_INF && ce != ORC_INF) {
+        unsigned __int128 v = (unsigned __int128)T->zero_coef[s->level[4]] * numel(c, s, 4) + cm + ce;
+        if (v >= ORC_LIMIT) c->overflow = 1; else cand = (uint64_t)v;
+      }
+      consider(c, cand, c->buf_id, &best, &arg);
+    }
   }
 
   /* E. parallel loop (kind P, Section 3: ceil(trips / threads) * c(body) + s).
@@ -425,6 +447,7 @@ int orc_solve(const orc_target* T, const orc_lattice* L,
     if (!LM || !LE || !costM || !costE) return -1;
     if (ctx_init(&cm, T, LM) || ctx_init(&ce, T, LE)) return -1;
     if (cm.kind != KIND_M || cm.parallel || ce.kind != KIND_E) return -1;
+    if (cm.bounded != c.bounded || ce.bounded != c.bounded) return -1;      /* bounds on all three tables or on none */
     for (int d = 1; d < 4; d++) if (!same_sizes(L, d, LM, d)) return -1;
     if (LM->n_sizes[0] != 1) return -1;
     if (!same_sizes(L, 1, LE, 1) || !same_sizes(L, 3, LE, 3)) return -1;

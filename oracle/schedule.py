@@ -20,12 +20,12 @@ INF = 2 ** 64 - 1
 def axes(lattice, target=None):
     """(axis kind, operand or dimension or level) per coordinate, in coordinate order:
     sizes b, m, k, n; one level per operand (kind F: plus the intermediate);
-    (kind BD: one memory bound per level of finite capacity;) layout bits; dtype bits."""
+    (bounded kinds: one memory bound per level of finite capacity;) layout bits; dtype bits."""
     kind = lattice["kind"]
-    nops = 4 if kind == B.F else 3
-    nlv = 5 if kind == B.F else 3
+    nops = 4 if B.base_kind(kind) == B.F else 3
+    nlv = 5 if B.base_kind(kind) == B.F else 3
     ax = [("size", d) for d in range(4)] + [("level", i) for i in range(nlv)]
-    if kind == B.BD:
+    if kind in B.BOUNDED:
         ax += [("limit", l) for l in range(target["n_levels"]) if target["capacity_bytes"][l] != INF]
     ax += [("layout", i) for i in range(nops) if lattice["layout_coord"][i]]
     ax += [("dtype", i) for i in range(nops) if lattice["dtype_coord"][i]]

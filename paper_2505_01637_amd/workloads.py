@@ -28,6 +28,9 @@ KIND_BIAS_ADD_RELU = 1
 KIND_FUSED_MM_ADD_RELU = 2
 KIND_MATMUL_PARALLEL = 3      # a Matmul whose serial-only flag is off; reads the KIND_MATMUL_ACCUM table
 KIND_MATMUL_BOUNDED = 4       # a Matmul whose Specs carry a memory bound per level of finite capacity
+KIND_BIAS_ADD_RELU_BOUNDED = 5        # the same for the bias-add + ReLU
+KIND_FUSED_BOUNDED = 6                # and for the fused Spec (reads the two bounded tables)
+BOUNDED_KINDS = (KIND_MATMUL_BOUNDED, KIND_BIAS_ADD_RELU_BOUNDED, KIND_FUSED_BOUNDED)
 
 MAX_LEVELS = 4
 MAX_OPERANDS = 5
@@ -182,17 +185,29 @@ def config(number, seed=None, max_size=None):
         t, _ = _four_level_target(rng)
         p2 = keep([1 << i for i in range(7)])
         lats = [("B", _lattice(KIND_MATMUL_BOUNDED, [one, p2, p2, p2]), [])]
+    elif number == 8:
+        # beyond the five benchmark configurations: config 5's three tables (Matmul, bias-add +
+        # ReLU, fused) with memory bounds as coordinates, sizes 1..16 in powers of two
+        t, w = _four_level_target(rng)
+        _add_transposed(t, rng)
+        t["zero_coef"] = list(w)
+        t["microkernels"].append((MK_SCALAR_ADDRELU, 1, 1))
+        t["microkernels"].append((MK_VEC_ADDRELU, 8, 1))
+        p2 = keep([1 << i for i in range(5)])
+        lats = [("M", _lattice(KIND_MATMUL_BOUNDED, [one, p2, p2, p2]), []),
+                ("E", _lattice(KIND_BIAS_ADD_RELU_BOUNDED, [one, p2, one, p2]), []),
+                ("F", _lattice(KIND_FUSED_BOUNDED, [one, p2, p2, p2]), ["M", "E"])]
     else:
-        raise ValueError("config number must be 1..7")
+        raise ValueError("config number must be 1..8")
     return {"name": "config%d" % number, "target": t, "lattices": lats}
 
 
 def n_level_axes(kind):
-    return 5 if kind == KIND_FUSED_MM_ADD_RELU else 3
+    return 5 if kind in (KIND_FUSED_MM_ADD_RELU, KIND_FUSED_BOUNDED) else 3
 
 
 def n_operands(kind):
-    return 4 if kind == KIND_FUSED_MM_ADD_RELU else 3
+    return 4 if kind in (KIND_FUSED_MM_ADD_RELU, KIND_FUSED_BOUNDED) else 3
 
 
 def coord_extents(target, lattice):
@@ -200,7 +215,7 @@ def coord_extents(target, lattice):
     kind = lattice["kind"]
     ext = [len(s) for s in lattice["sizes"]]
     ext += [target["n_levels"]] * n_level_axes(kind)
-    if kind == KIND_MATMUL_BOUNDED:
+    if kind in BOUNDED_KINDS:
         # one axis per level of finite capacity: the bounds 0, 1, 2, 4, ... up to the capacity
         ext += [int(c).bit_length() + 1 for c in target["capacity_bytes"][:target["n_levels"]] if c != UNBOUNDED]
     nops = n_operands(kind)

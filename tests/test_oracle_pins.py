@@ -258,6 +258,43 @@ def test_brute_force_memory_bounds():
     assert int(c[0, 1, 0, 0, 0, 0, 0, 0, 0]) == 2 * mk + 2
 
 
+def bounded_fused_setup(caps=(16, 64)):
+    """Two levels of finite capacity; Matmul, bias-add + ReLU and fused tables, all with bounds."""
+    t = W._empty_target(2, caps)
+    t["load_coef"][1][0][0], t["store_coef"][0][1][0] = 3, 5
+    t["loop_overhead"] = 1
+    t["zero_coef"] = [1, 2, 0, 0]
+    t["microkernels"] = [(W.MK_SCALAR_FMA, 1, 2), (W.MK_SCALAR_ADDRELU, 1, 1), (W.MK_VEC_ADDRELU, 2, 1)]
+    r = [1, 2]
+    lats = [("M", W._lattice(W.KIND_MATMUL_BOUNDED, [[1], r, r, r]), []),
+            ("E", W._lattice(W.KIND_BIAS_ADD_RELU_BOUNDED, [[1], r, [1], r]), []),
+            ("F", W._lattice(W.KIND_FUSED_BOUNDED, [[1], r, r, r]), ["M", "E"])]
+    return t, lats, O.solve_config({"target": t, "lattices": lats})
+
+
+def test_brute_force_memory_bounds_through_a_pipeline():
+    """Section 2.4.4, second case: a pipeline allocates its intermediate, so both of its stages
+    get the intermediate's level's bound lowered by its bytes and snapped down.  The bounded
+    bias-add + ReLU table and the bounded fused table against all complete programs."""
+    t, lats, res = bounded_fused_setup()
+    n = brute_force_compare(t, lats, res, "E")
+    assert n == len(res["E"]["cost"])
+    n = brute_force_compare(t, lats, res, "F", pick=lambda s: s.dims[1] * s.dims[2] * s.dims[3] <= 4)
+    assert n > 3000
+    ext = res["F"]["extents"]
+    assert ext == [1, 2, 2, 2, 2, 2, 2, 2, 2, 6, 8]
+    c = res["F"]["cost"].reshape(ext)
+    for axis in (9, 10):                                  # more memory never hurts
+        a = np.moveaxis(c, axis, 0)
+        assert (a[1:] <= a[:-1]).all()
+    # closed form: 1x1x1x1, everything in level 0, intermediate in level 0: the pipeline needs the
+    # intermediate's 4 bytes of level 0's bound: zero[0]*1 + FMA + add+ReLU with a bound of 4, nothing with 2
+    assert int(c[0, 0, 0, 0, 0, 0, 0, 0, 0, 3, 0]) == 1 + 2 + 1
+    assert int(c[0, 0, 0, 0, 0, 0, 0, 0, 0, 2, 7]) == O.INF
+    _, _, ids = O.geometry(t, lats[2][1])
+    assert int(res["F"]["argmin"].reshape(ext)[0, 0, 0, 0, 0, 0, 0, 0, 0, 3, 0]) == ids["bufferize"]
+
+
 def test_memory_bounds_that_never_bind_give_the_unbounded_table():
     """With bounds far above every allocation the bounded table at its top bounds is the plain
     Matmul table of a target whose levels are unbounded (pinned above by brute force)."""

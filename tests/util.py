@@ -12,7 +12,7 @@ def axes(target, lattice):
     kind = lattice["kind"]
     nops, nlv = W.n_operands(kind), W.n_level_axes(kind)
     ax = [("size", d) for d in range(4)] + [("level", i) for i in range(nlv)]
-    if kind == W.KIND_MATMUL_BOUNDED:
+    if kind in W.BOUNDED_KINDS:
         ax += [("limit", l) for l in range(target["n_levels"]) if target["capacity_bytes"][l] != W.UNBOUNDED]
     ax += [("layout", i) for i in range(nops) if lattice["layout_coord"][i]]
     ax += [("dtype", i) for i in range(nops) if lattice["dtype_coord"][i]]

@@ -90,7 +90,7 @@ void mrl_target_destroy(mrl_target* t);
  * Coordinate vector x, in this order:
  *   index of b, m, k, n in the allowed-size lists;
  *   memory level of each operand (kind FUSED: then the intermediate's level);
- *   (kind MATMUL_BOUNDED: one memory-bound index per level of finite capacity;)
+ *   (the BOUNDED kinds: one memory-bound index per level of finite capacity;)
  *   one layout bit (0 row-major, 1 column-major) per operand with layout_coord;
  *   one dtype bit (0 f32, 1 bf16) per operand with dtype_coord.
  * Dense tables are in C order of x (last coordinate fastest).
@@ -118,10 +118,16 @@ void mrl_target_destroy(mrl_target* t);
  * dtype it has after the Move) within the destination level's bound, and its
  * body Spec gets what is left, rounded down to a power of two (or zero).
  * Tiles keep the bounds.  Rewrite ids as for MATMUL_ACCUM; no deps.
+ * BIAS_ADD_RELU_BOUNDED and FUSED_BOUNDED: the same for the other two
+ * operators.  A bufferize allocates the intermediate (4*m*n bytes) in its
+ * level: it needs that much of the level's bound, and both stages get the
+ * rest, rounded down (Section 2.4.4, pipelines).  FUSED_BOUNDED takes deps =
+ * {MATMUL_BOUNDED table, BIAS_ADD_RELU_BOUNDED table}.
  */
 typedef enum { MRL_KIND_MATMUL_ACCUM = 0, MRL_KIND_BIAS_ADD_RELU = 1,
                MRL_KIND_FUSED_MM_ADD_RELU = 2, MRL_KIND_MATMUL_PARALLEL = 3,
-               MRL_KIND_MATMUL_BOUNDED = 4 } mrl_kind;
+               MRL_KIND_MATMUL_BOUNDED = 4, MRL_KIND_BIAS_ADD_RELU_BOUNDED = 5,
+               MRL_KIND_FUSED_BOUNDED = 6 } mrl_kind;
 
 typedef struct {
   uint32_t kind;
@@ -199,7 +205,7 @@ int32_t mrl_rewrite_decode(const mrl_table* tab, uint16_t id, mrl_rewrite* out);
 
 /* shape: b,m,k,n sizes (must be in the lists); levels / layouts / dtypes: per
  * operand (FUSED: levels[4] = intermediate); entries without a coordinate are ignored.
- * MATMUL_BOUNDED: the memory bounds are set to their top (the capacities). */
+ * The BOUNDED kinds: the memory bounds are set to their top (the capacities). */
 int32_t mrl_coord_of_spec(const mrl_table* tab, const uint32_t shape[4], const uint8_t* levels,
                           const uint8_t* layouts, const uint8_t* dtypes, mrl_coord* out);
 

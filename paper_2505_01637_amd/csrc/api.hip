@@ -139,11 +139,11 @@ int32_t validate_target(const mrl_target_desc* d) {
 
 int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c) {
   if (!L) return fail(MRL_E_INVAL, "lattice descriptor is NULL");
-  if (L->kind > MRL_KIND_MATMUL_BOUNDED) return fail(MRL_E_INVAL, "unknown spec kind %u", L->kind);
+  if (L->kind > MRL_KIND_FUSED_BOUNDED) return fail(MRL_E_INVAL, "unknown spec kind %u", L->kind);
   // A parallel lattice is a Matmul lattice (same operator, operands and coordinates) with more
-  // rewrites; a bounded one is a Matmul lattice with more coordinates.
-  const bool parallel = L->kind == MRL_KIND_MATMUL_PARALLEL, bounded = L->kind == MRL_KIND_MATMUL_BOUNDED;
-  const uint32_t kind = parallel || bounded ? (uint32_t)kKindM : L->kind;
+  // rewrites; a bounded one is the lattice of its operator with more coordinates.
+  const bool parallel = L->kind == MRL_KIND_MATMUL_PARALLEL, bounded = L->kind >= MRL_KIND_MATMUL_BOUNDED;
+  const uint32_t kind = parallel ? (uint32_t)kKindM : bounded ? L->kind - MRL_KIND_MATMUL_BOUNDED : L->kind;
   if (parallel && T.threads < 1) return fail(MRL_E_INVAL, "a MATMUL_PARALLEL lattice needs threads >= 1");
   c.target = T;
   c.lat = *L;
@@ -404,7 +404,7 @@ bool same_problem(const Compiled& c, const mrl_target_desc& T, const mrl_lattice
 int32_t get_compiled(const mrl_target_desc& T, const mrl_lattice_desc* L, CompiledPtr& out) {
   static std::mutex mu;
   static std::vector<CompiledPtr> cache;          // most recent last, at most 8
-  if (L && L->kind <= MRL_KIND_MATMUL_BOUNDED) {
+  if (L && L->kind <= MRL_KIND_FUSED_BOUNDED) {
     std::lock_guard<std::mutex> lock(mu);
     for (size_t i = cache.size(); i-- > 0;)
       if (same_problem(*cache[i], T, *L)) { out = cache[i]; return MRL_OK; }
@@ -576,7 +576,8 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
     if (n_deps != 2 || !deps || !deps[0] || !deps[1]) return fail(MRL_E_INVAL, "a FUSED lattice needs deps = {MATMUL_ACCUM table, BIAS_ADD_RELU table}");
     const Compiled& M = *deps[0]->cp;
     const Compiled& E = *deps[1]->cp;
-    if (M.P.kind != kKindM || E.P.kind != kKindE) return fail(MRL_E_INVAL, "deps must be {MATMUL_ACCUM, BIAS_ADD_RELU}");
+    if (M.P.kind != kKindM || M.P.par || E.P.kind != kKindE) return fail(MRL_E_INVAL, "deps must be {MATMUL_ACCUM, BIAS_ADD_RELU}");
+    if (M.P.bounded != P.bounded || E.P.bounded != P.bounded) return fail(MRL_E_INVAL, "memory bounds on all three tables or on none");
     if (memcmp(&M.target, &t->d, sizeof t->d) || memcmp(&E.target, &t->d, sizeof t->d)) return fail(MRL_E_INVAL, "deps were solved for another target");
     for (int d = 1; d < 4; d++) if (M.sizes[d] != c.sizes[d]) return fail(MRL_E_INVAL, "MATMUL_ACCUM dep has other size lists");
     if (M.sizes[0].size() != 1) return fail(MRL_E_INVAL, "MATMUL_ACCUM dep must have b pinned to 1");
@@ -655,7 +656,7 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
       auto flush = [&]() { launch_fill_bounded(d_P, d_level_shapes, segs, tab->d_cost, tab->d_arg, d_ctr, st); segs.n = 0; segs.block0[0] = 0; };
       for (uint32_t l = d < P.nranks ? 0 : d - (P.nranks - 1); l < n_lev && l <= d; l++) {
         const uint32_t r = d - l, ns = c.level_off[l + 1] - c.level_off[l];
-        const uint64_t lanes = (uint64_t)ns * (P.rank_off[r + 1] - P.rank_off[r]) * P.Q * P.V;
+        const uint64_t lanes = (uint64_t)ns * (P.rank_off[r + 1] - P.rank_off[r]) * P.npass * P.Q * P.V;
         const uint64_t blocks = (lanes + 255) / 256;
         if (!blocks) continue;
         if (segs.n == kBoundSegs || segs.block0[segs.n] + blocks >= (1ull << 31)) flush();
@@ -1009,7 +1010,9 @@ int32_t mrl_schedule(const mrl_table* tab, const mrl_coord* goal, mrl_schedule_n
         // the Move's buffer comes out of the destination's bound; the rest snaps down to a power of two
         const uint32_t ax = 4 + P.nlv + P.lim_of_level[r.dst_level];
         const uint64_t b = c.sizes[0][it.x.x[0]], m = c.sizes[1][it.x.x[1]], k = c.sizes[2][it.x.x[2]], nn = c.sizes[3][it.x.x[3]];
-        const uint64_t numel = op == 0 ? b * m * k : op == 1 ? b * k * nn : b * m * nn;
+        const uint64_t numel = P.kind == kKindM ? (op == 0 ? b * m * k : op == 1 ? b * k * nn : b * m * nn)
+                             : P.kind == kKindE ? (op == 1 ? nn : m * nn)
+                                                : (op == 0 ? m * k : op == 1 ? k * nn : op == 2 ? nn : m * nn);
         const bool bf = c.dt_axis[op] >= 0 ? ch.x.x[c.dt_axis[op]] != 0 : c.lat.base_dtype_bytes[op] == 2;
         const uint64_t bytes = numel * (bf ? 2 : 4), have = it.x.x[ax] ? 1ull << (it.x.x[ax] - 1) : 0;
         if (bytes > have) return fail(MRL_E_HIP, "internal error: a memoized Move exceeds its memory bound");
@@ -1049,6 +1052,19 @@ int32_t mrl_schedule(const mrl_table* tab, const mrl_coord* goal, mrl_schedule_n
       if (rc) return rc;
       rc = mrl_coord_of_spec(ce.t, shape_e, lv_e, ly_e, zeros, &ce.x);
       if (rc) return rc;
+      if (P.bounded) {
+        // both stages inherit the bounds; the intermediate's bytes come out of its level's bound
+        for (uint32_t a = 0; a < P.nlim; a++) cm.x.x[4 + 3 + a] = ce.x.x[4 + 3 + a] = it.x.x[4 + P.nlv + a];
+        if (P.lim_of_level[l_mid] != kNoBit) {
+          const uint32_t a = P.lim_of_level[l_mid], q = it.x.x[4 + P.nlv + a];
+          const uint64_t bytes = (uint64_t)m * nn * 4, have = q ? 1ull << (q - 1) : 0;
+          if (bytes > have) return fail(MRL_E_HIP, "internal error: a memoized bufferize exceeds its memory bound");
+          uint64_t left = have - bytes;
+          uint32_t qn = 0;
+          while (left) { qn++; left >>= 1; }
+          cm.x.x[4 + 3 + a] = ce.x.x[4 + 3 + a] = qn;
+        }
+      }
       stack.push_back(ce);                  // popped after the Matmul's whole subtree
       stack.push_back(cm);
       node.n_children = 2;

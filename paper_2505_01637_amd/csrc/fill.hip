@@ -976,7 +976,9 @@ uint32_t fill_wave_cap(uint32_t G) { return G <= kSmallCap ? G : kSlicedCap; }
 // (level l, rank r) depend only on (l, r' < r) and (l' < l, r): all pairs on one diagonal
 // l + r = d are independent, and one launch takes a whole diagonal, one segment of workgroups per
 // pair.  One lane per Spec, every candidate a gather from finished entries.  Lane -> (shape of
-// the level, level assignment of the rank, bound vector, variant), variant fastest.
+// the level, level assignment of the rank, level of the fused Spec's intermediate, bound vector,
+// variant), variant fastest.  A bufferize (fused Spec) allocates the intermediate in its level:
+// it needs 4 * m * n bytes of that level's bound, and both stages get the rest, rounded down.
 __global__ __launch_bounds__(256) void fill_bounded_kernel(const DevParams* __restrict__ P,
                                                            const uint32_t* __restrict__ all_level_shapes, const BoundSegs segs,
                                                            uint64_t* cost, uint16_t* __restrict__ arg,
@@ -986,9 +988,9 @@ __global__ __launch_bounds__(256) void fill_bounded_kernel(const DevParams* __re
   while (seg + 1 < segs.n && blockIdx.x >= segs.block0[seg + 1]) seg++;
   const uint32_t rank = segs.rank[seg], n_level_shapes = segs.n_shapes[seg];
   const uint32_t* __restrict__ level_shapes = all_level_shapes + segs.first_shape[seg];
-  const uint32_t V = P->V, Q = P->Q;
+  const uint32_t V = P->V, Q = P->Q, npass = P->npass, nops = P->nops;
   const uint32_t c0 = P->rank_off[rank], ncr = P->rank_off[rank + 1] - c0;
-  const uint64_t per_shape = (uint64_t)ncr * Q * V;
+  const uint64_t per_shape = (uint64_t)ncr * npass * Q * V;
   const uint64_t t = (uint64_t)(blockIdx.x - segs.block0[seg]) * 256u + threadIdx.x;
   const bool active = t < per_shape * n_level_shapes;
   Eval e;
@@ -996,16 +998,19 @@ __global__ __launch_bounds__(256) void fill_bounded_kernel(const DevParams* __re
   if (active) {
     const uint32_t sl = (uint32_t)(t / per_shape);
     uint32_t r = (uint32_t)(t - (uint64_t)sl * per_shape);
-    const uint32_t ci = r / (Q * V);
-    r -= ci * Q * V;
+    const uint32_t ci = r / (npass * Q * V);
+    r -= ci * npass * Q * V;
+    const uint32_t pass = r / (Q * V);
+    r -= pass * Q * V;
     const uint32_t q = r / V, v = r - q * V;
     const uint32_t shape = level_shapes[sl];
     Shape S;
     load_shape(P, shape, S);
     const uint32_t pack = P->pos_info[c0 + ci] & 0xFFu;
-    uint32_t lv[3], combo = 0;
+    uint32_t lv[4] = {0, 0, 0, 0}, combo = 0;
 #pragma unroll
-    for (int i = 0; i < 3; i++) { lv[i] = (pack >> P->pack_shift[i]) & 3u; combo += lv[i] * P->lvpow[i]; }
+    for (int i = 0; i < 4; i++)
+      if ((uint32_t)i < nops) { lv[i] = (pack >> P->pack_shift[i]) & 3u; combo += lv[i] * P->lvpow[i]; }
     uint32_t qi[4] = {0, 0, 0, 0};
     {
       uint32_t rem = q;
@@ -1014,7 +1019,7 @@ __global__ __launch_bounds__(256) void fill_bounded_kernel(const DevParams* __re
         if ((uint32_t)a < P->nlim) { qi[a] = rem / P->lim_stride[a]; rem -= qi[a] * P->lim_stride[a]; }
     }
     const uint64_t group = (uint64_t)shape * P->G;
-    const uint32_t off = (combo * Q + q) * V + v;
+    const uint32_t off = ((combo * npass + pass) * Q + q) * V + v;
 
     // microkernels
     const uint32_t mm = P->mk_entry[pack * V + v];
@@ -1029,7 +1034,8 @@ __global__ __launch_bounds__(256) void fill_bounded_kernel(const DevParams* __re
 
     // Moves
 #pragma unroll
-    for (int i = 0; i < 3; i++) {
+    for (int i = 0; i < 4; i++) {
+      if ((uint32_t)i >= nops) continue;
       const uint32_t src = lv[i];
       const bool has_dt = P->dt_bit[i] != kNoBit, has_lay = P->lay_bit[i] != kNoBit;
       const uint32_t bf = has_dt ? (v >> P->dt_bit[i]) & 1u : P->base_bf16[i];
@@ -1056,7 +1062,7 @@ __global__ __launch_bounds__(256) void fill_bounded_kernel(const DevParams* __re
             const uint32_t combo_c = combo - (src - dst) * P->lvpow[i];
             uint32_t v_c = v ^ (x ? 1u << P->lay_bit[i] : 0u);
             if (cv) v_c &= ~(1u << P->dt_bit[i]);
-            const uint64_t sub = cost[group + (uint64_t)(combo_c * Q + qc) * V + v_c];
+            const uint64_t sub = cost[group + (uint64_t)((combo_c * npass + pass) * Q + qc) * V + v_c];
             const uint64_t b = mul_or_limit((uint64_t)coef + (cv ? P->convert : 0u), numel);
             const uint32_t id = P->move_base + (((uint32_t)i * (P->NL - 1u) + dst) * 2u + x) * 2u + cv;
             if (sub != kInf) {
@@ -1083,6 +1089,41 @@ __global__ __launch_bounds__(256) void fill_bounded_kernel(const DevParams* __re
         const bool over = fin & (((hi >> 30) != 0) | (c >= kLimit));
         e.ovf |= over ? 1u : 0u;
         consider(e, c, P->tile_base + (uint32_t)d * P->maxs + te.jt, fin & !over);
+        e.n++;
+      }
+    }
+    // bufferize (fused Spec): the Matmul into the intermediate at level `pass`, then the bias-add +
+    // ReLU out of it; both read from the bounded tables of those two kinds
+    if (P->kind == kKindF) {
+      uint32_t qc = q;
+      bool fits = true;
+      const uint32_t la = P->lim_of_level[pass];
+      if (la != kNoBit) {
+        const uint32_t qa = la == 0 ? qi[0] : la == 1 ? qi[1] : la == 2 ? qi[2] : qi[3];
+        const uint64_t bytes = S.numel[4] * 4u;
+        const uint64_t have = qa ? 1ull << (qa - 1u) : 0ull;
+        fits = bytes <= have;
+        const uint64_t left = fits ? have - bytes : 0ull;
+        const uint32_t qn = left ? 64u - (uint32_t)__clzll((long long)left) : 0u;
+        qc = fits ? q - (qa - qn) * P->lim_stride[la] : q;
+      }
+      if (fits) {
+        const uint32_t NL = P->NL;
+        const uint32_t y0 = P->lay_bit[0] != kNoBit ? (v >> P->lay_bit[0]) & 1u : 0u;
+        const uint32_t y1 = P->lay_bit[1] != kNoBit ? (v >> P->lay_bit[1]) & 1u : 0u;
+        const uint32_t y3 = P->lay_bit[3] != kNoBit ? (v >> P->lay_bit[3]) & 1u : 0u;
+        const uint32_t vm = (P->layM[0] != kNoBit ? y0 << P->layM[0] : 0u) + (P->layM[1] != kNoBit ? y1 << P->layM[1] : 0u);
+        const uint32_t ve = P->layE[2] != kNoBit ? y3 << P->layE[2] : 0u;
+        const uint32_t xm = (((lv[0] * NL + lv[1]) * NL + pass) * Q + qc) * P->VM + vm;
+        const uint32_t xe = (((pass * NL + lv[2]) * NL + lv[3]) * Q + qc) * P->VE + ve;
+        const uint64_t cm = P->costM[(uint64_t)shape * P->GM + xm];
+        const uint64_t ce = P->costE[(uint64_t)(S.si[1] * P->nszE_n + S.si[3]) * P->GE + xe];
+        const uint32_t zc = pass == 0 ? P->zero[0] : pass == 1 ? P->zero[1] : pass == 2 ? P->zero[2] : P->zero[3];
+        if (cm != kInf && ce != kInf) {
+          const uint64_t z = mul_or_limit(zc, S.numel[4]);
+          const uint64_t sum = z + cm;          // each term <= 2^62: no wrap
+          if (z >= kLimit || sum >= kLimit || sum + ce >= kLimit) e.ovf = 1; else consider(e, sum + ce, P->buf_id);
+        }
         e.n++;
       }
     }

@@ -222,6 +222,44 @@ def test_parity_memory_bounds(case):
     check_compressed_queries(got[label], want[label], 100_000, seed=3)
 
 
+@pytest.mark.parametrize("case", ["two-level", "config8-small", "config8"])
+def test_parity_memory_bounds_through_a_pipeline(case):
+    """Memory bounds on all three tables of the fused workload (Section 2.4.4: Moves and
+    pipelines lower the bounds): dense tables, counters, box lists, lookups in the box lists and
+    extracted programs against the oracle."""
+    from oracle import schedule as S
+    B = _binding()
+    if case == "two-level":
+        t = W._empty_target(2, (16, 64))
+        t["load_coef"][1][0][0], t["store_coef"][0][1][0] = 3, 5
+        t["loop_overhead"] = 1
+        t["zero_coef"] = [1, 2, 0, 0]
+        t["microkernels"] = [(W.MK_SCALAR_FMA, 1, 2), (W.MK_SCALAR_ADDRELU, 1, 1), (W.MK_VEC_ADDRELU, 2, 1)]
+        r = [1, 2, 4]
+        cfg = {"name": "bounded-fused-2", "target": t,
+               "lattices": [("M", W._lattice(W.KIND_MATMUL_BOUNDED, [[1], r, r, r]), []),
+                            ("E", W._lattice(W.KIND_BIAS_ADD_RELU_BOUNDED, [[1], r, [1], r]), []),
+                            ("F", W._lattice(W.KIND_FUSED_BOUNDED, [[1], r, r, r]), ["M", "E"])]}
+    else:
+        cfg = W.config(8, max_size=2 if case == "config8-small" else 4)
+    _, got, want = compare_config(cfg, scratch_bytes=(6 << 30) if case == "config8" else None)
+    for label in "MEF":
+        check_compressed_queries(got[label], want[label], 50_000, seed=8)
+    cost = want["F"]["cost"]
+    ext = [int(e) for e in want["F"]["extents"]]
+    rng = np.random.default_rng(8)
+    finite = np.flatnonzero(cost != np.uint64(O.INF))
+    names = ["F", "M", "E"]
+    n_pipeline = 0
+    for p in rng.choice(finite, size=min(40, len(finite)), replace=False):
+        goal = tuple(int(v) for v in np.unravel_index(int(p), ext))
+        ref = S.preorder(S.extract(cfg["target"], cfg["lattices"], want, "F", goal))
+        mine = [(names[t], x, rw, c, k) for t, x, rw, c, k in got["F"].schedule(goal)]
+        assert mine == ref
+        n_pipeline += sum(1 for node in mine if node[4] == 2)
+    assert n_pipeline > 0
+
+
 def test_degenerate_lattices():
     B = _binding()
     # a single shape: every dimension pinned

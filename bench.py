@@ -76,13 +76,18 @@ def main():
         return B.solve_lattices(target, cfg["lattices"],
                                 buffers={l: (bufs[l][0], bufs[l][1], scratch_of[l]) for l in bufs})
 
-    # split the scratch buffer between the lattices in proportion to their size
+    # split the scratch buffer between the lattices: the small ones get their worst-case need,
+    # the others share the rest in proportion to their size
     sizes = {label: W.n_specs(cfg["target"], lat) for label, lat, _ in cfg["lattices"]}
     total_specs = sum(sizes.values())
+    need = {label: B.table_bytes(target, lat)[2] for label, lat, _ in cfg["lattices"]}
+    small = {l for l in sizes if need[l] <= (512 << 20)}
+    rest = scratch.numel() - sum(need[l] for l in small)
+    rest_specs = sum(sizes[l] for l in sizes if l not in small) or 1
     scratch_of, off = {}, 0
     for label in sizes:
-        share = max(64 << 20, int(scratch.numel() * sizes[label] / total_specs)) // 256 * 256
-        share = min(share, scratch.numel() - off)
+        share = need[label] if label in small else int(rest * sizes[label] / rest_specs)
+        share = min((share + 255) // 256 * 256, scratch.numel() - off)
         scratch_of[label] = scratch[off:off + share]
         off += share
 

@@ -482,7 +482,7 @@ int orc_solve(const orc_target* T, const orc_lattice* L,
 }
 
 /* Geometry of the table: number of axes, extents, and the merge order used by
- * orc_merge (n, then the memory-bound axes, then k, m, b, the level axes,
+ * orc_merge (the memory-bound axes, then n, k, m, b, the level axes,
  * layout bits and dtype bits, each group last to first). */
 int orc_geometry(const orc_target* T, const orc_lattice* L, uint32_t* ndim,
                  uint32_t* ext, uint32_t* merge_order, uint32_t* ids) {
@@ -494,9 +494,8 @@ int orc_geometry(const orc_target* T, const orc_lattice* L, uint32_t* ndim,
   for (int i = 0; i < c.nops; i++) nlay += c.lay_axis[i] >= 0;
   for (int l = 0; l < ORC_MAXL; l++) nlim += c.lim_axis[l] >= 0;
   int q = 0, first = 4 + c.nlv;
-  merge_order[q++] = 3;                                                                          /* n */
   for (int a = first + nlim - 1; a >= first; a--) merge_order[q++] = (uint32_t)a;                /* memory bounds */
-  for (int a = 2; a >= 0; a--) merge_order[q++] = (uint32_t)a;                                   /* k, m, b */
+  for (int a = 3; a >= 0; a--) merge_order[q++] = (uint32_t)a;                                   /* n, k, m, b */
   for (int a = first - 1; a >= 4; a--) merge_order[q++] = (uint32_t)a;                           /* levels */
   first += nlim;
   for (int a = first + nlay - 1; a >= first; a--) merge_order[q++] = (uint32_t)a;                /* layout bits */

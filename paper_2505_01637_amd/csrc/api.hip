@@ -354,7 +354,7 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
     for (uint32_t sh = 0; sh < c.n_shapes; sh++) c.level_shapes[cur[lev[sh]]++] = sh;
   }
 
-  // coordinate geometry and merge order: n, the memory-bound axes, k, m, b, the level axes,
+  // coordinate geometry and merge order: the memory-bound axes, n, k, m, b, the level axes,
   // layout bits, dtype bits, each group from its last axis to its first
   Geo& g = c.geo;
   memset(&g, 0, sizeof g);
@@ -371,9 +371,8 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
   {
     uint32_t q = 0;
     const int lim0 = 4 + (int)P.nlv, lay0 = lim0 + (int)P.nlim;
-    c.merge_order[q++] = 3;                                                              // n
     for (int a = lay0 - 1; a >= lim0; a--) c.merge_order[q++] = (uint32_t)a;             // memory bounds
-    for (int a = 2; a >= 0; a--) c.merge_order[q++] = (uint32_t)a;                       // k, m, b
+    for (int a = 3; a >= 0; a--) c.merge_order[q++] = (uint32_t)a;                       // n, k, m, b
     for (int a = lim0 - 1; a >= 4; a--) c.merge_order[q++] = (uint32_t)a;                // levels
     for (int a = lay0 + (int)P.nlay - 1; a >= lay0; a--) c.merge_order[q++] = (uint32_t)a;
     for (int a = (int)nd - 1; a >= lay0 + (int)P.nlay; a--) c.merge_order[q++] = (uint32_t)a;

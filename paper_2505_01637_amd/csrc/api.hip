@@ -721,7 +721,6 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
   uint32_t* tile_tmp = (uint32_t*)(base + f.tile_tmp);
   uint32_t* d_tot = (uint32_t*)(base + f.totals);
   auto axis_sizes = [&](uint32_t a) -> const uint32_t* { return a < 4 ? (const uint32_t*)((char*)d_P + offsetof(DevParams, sizes) + a * sizeof(uint32_t) * kMaxSizes) : nullptr; };
-  if (g.stride[a0] % 64 != 0) { launch_zero_words(maskL[0], f.n_words, st); launch_zero_words(maskL[1], f.n_words, st); }
   unsigned long long* lineL[2] = {(unsigned long long*)(base + f.lineD), (unsigned long long*)(base + f.lineC)};
   launch_head_flags(g, a0, tab->d_cost, tab->d_arg, d_fitmap, axis_sizes(a0), maskL[0], maskL[1], lineL[0], lineL[1], st);
   scan_mask_words(maskL[0], f.n_words, tile_tmp, prefL[0], d_tot + 0, st);

@@ -42,6 +42,8 @@ __device__ __forceinline__ bool norm_equal(uint64_t c1, uint32_t s1, uint64_t c2
 }
 
 // ---------------------------------------------------------------- pass 0
+constexpr uint32_t kCellWords = 8;         // 64-cell words a wave of the lane-per-cell kernels takes (a wave per word is mostly wave launch)
+
 // A line = all cells sharing every coordinate but a0.  General form (any stride): one lane per
 // cell compares its value with the cell before it on the line; a wave covers one 64-cell word of
 // the table-order masks and writes it whole (ballots: no atomics, no zeroing).
@@ -53,29 +55,33 @@ __global__ __launch_bounds__(256) void head_flags_kernel(Geo g, uint32_t a0,
                                                          unsigned long long* __restrict__ maskD,
                                                          unsigned long long* __restrict__ maskC) {
   const uint32_t s0 = g.stride[a0], e0 = g.ext[a0];
-  const uint32_t cell = blockIdx.x * 256u + threadIdx.x;
-  const bool active = cell < g.n;
-  bool hd = false, hc = false;
-  if (active) {
-    const uint32_t j = (cell / s0) % e0;
-    const bool fits = (fitmap[cell >> 5] >> (cell & 31u)) & 1u;     // cells that cannot fit hold (INF, NONE): not read
-    const uint64_t c = fits ? cost[cell] : kInf;
-    const uint32_t a = fits ? arg[cell] : kNone;
-    hd = hc = true;
-    if (j > 0) {
-      const uint32_t p = cell - s0;
-      const bool pfits = (fitmap[p >> 5] >> (p & 31u)) & 1u;
-      const uint64_t pc = pfits ? cost[p] : kInf;
-      const uint32_t pa = pfits ? arg[p] : kNone;
-      const uint32_t sz = axis_sizes ? axis_sizes[j] : 1u, ps = axis_sizes ? axis_sizes[j - 1] : 1u;
-      hd = a != pa;
-      hc = !norm_equal(c, sz, pc, ps);
+  const uint32_t word0 = (blockIdx.x * 4u + (threadIdx.x >> 6)) * kCellWords;     // a wave takes kCellWords words
+#pragma unroll
+  for (uint32_t w = 0; w < kCellWords; w++) {
+    const uint32_t cell = (word0 + w) * 64u + (threadIdx.x & 63u);
+    const bool active = cell < g.n;
+    bool hd = false, hc = false;
+    if (active) {
+      const uint32_t j = (cell / s0) % e0;
+      const bool fits = (fitmap[cell >> 5] >> (cell & 31u)) & 1u;     // cells that cannot fit hold (INF, NONE): not read
+      const uint64_t c = fits ? cost[cell] : kInf;
+      const uint32_t a = fits ? arg[cell] : kNone;
+      hd = hc = true;
+      if (j > 0) {
+        const uint32_t p = cell - s0;
+        const bool pfits = (fitmap[p >> 5] >> (p & 31u)) & 1u;
+        const uint64_t pc = pfits ? cost[p] : kInf;
+        const uint32_t pa = pfits ? arg[p] : kNone;
+        const uint32_t sz = axis_sizes ? axis_sizes[j] : 1u, ps = axis_sizes ? axis_sizes[j - 1] : 1u;
+        hd = a != pa;
+        hc = !norm_equal(c, sz, pc, ps);
+      }
     }
-  }
-  const unsigned long long bd = __ballot(hd), bc = __ballot(hc);
-  if ((threadIdx.x & 63u) == 0 && active) {
-    maskD[cell >> 6] = bd;
-    maskC[cell >> 6] = bc;
+    const unsigned long long bd = __ballot(hd), bc = __ballot(hc);
+    if ((threadIdx.x & 63u) == 0 && active) {
+      maskD[cell >> 6] = bd;
+      maskC[cell >> 6] = bc;
+    }
   }
 }
 
@@ -309,47 +315,50 @@ __global__ __launch_bounds__(256) void make_boxes_kernel(Geo g, uint32_t a0,
                                                          uint32_t* __restrict__ bcell, uint4* __restrict__ blen,
                                                          uint8_t* __restrict__ alive, uint8_t* __restrict__ pred) {
   const uint32_t s0 = g.stride[a0], e0 = g.ext[a0];
-  const uint32_t cell = blockIdx.x * 256u + threadIdx.x;
-  if (cell >= g.n) return;
-  const unsigned long long tm = mask[cell >> 6];
-  if (!((tm >> (cell & 63u)) & 1ull)) return;
-  const uint32_t id = prefix[cell >> 6] + (uint32_t)__popcll(tm & ((1ull << (cell & 63u)) - 1ull));
-  const uint32_t j = (cell / s0) % e0;
-  const uint32_t R = e0 - 1u - j;                       // cells after this one on the line
-  uint32_t len = R + 1u;
-  if ((s0 & (s0 - 1u)) == 0 && s0 <= 32u) {
-    // a power-of-two stride: the line's cells sit at the same bit positions (mod s0) of every
-    // word, so the next flagged one is a mask, a count of trailing zeros and a division away
-    const unsigned long long P = s0 == 1 ? ~0ull : s0 == 2 ? 0x5555555555555555ull : s0 == 4 ? 0x1111111111111111ull
-                               : s0 == 8 ? 0x0101010101010101ull : s0 == 16 ? 0x0001000100010001ull : 0x0000000100000001ull;
-    const uint32_t bit0 = cell & 63u;
-    const unsigned long long same = P << (bit0 % s0);
-    unsigned long long m = tm & same & ~((2ull << bit0) - 1ull);      // this word: only the cells after this one
-    for (uint32_t k = cell >> 6;; m = mask[++k] & same) {
-      if (m) {
-        const uint32_t t = (k * 64u + (uint32_t)__builtin_ctzll(m) - cell) / s0;
-        if (t <= R) len = t;
-        break;
+  const uint32_t word0 = (blockIdx.x * 4u + (threadIdx.x >> 6)) * kCellWords;
+  for (uint32_t wi = 0; wi < kCellWords; wi++) {
+    const uint32_t cell = (word0 + wi) * 64u + (threadIdx.x & 63u);
+    if (cell >= g.n) return;
+    const unsigned long long tm = mask[cell >> 6];
+    if (!((tm >> (cell & 63u)) & 1ull)) continue;
+    const uint32_t id = prefix[cell >> 6] + (uint32_t)__popcll(tm & ((1ull << (cell & 63u)) - 1ull));
+    const uint32_t j = (cell / s0) % e0;
+    const uint32_t R = e0 - 1u - j;                       // cells after this one on the line
+    uint32_t len = R + 1u;
+    if ((s0 & (s0 - 1u)) == 0 && s0 <= 32u) {
+      // a power-of-two stride: the line's cells sit at the same bit positions (mod s0) of every
+      // word, so the next flagged one is a mask, a count of trailing zeros and a division away
+      const unsigned long long P = s0 == 1 ? ~0ull : s0 == 2 ? 0x5555555555555555ull : s0 == 4 ? 0x1111111111111111ull
+                                 : s0 == 8 ? 0x0101010101010101ull : s0 == 16 ? 0x0001000100010001ull : 0x0000000100000001ull;
+      const uint32_t bit0 = cell & 63u;
+      const unsigned long long same = P << (bit0 % s0);
+      unsigned long long m = tm & same & ~((2ull << bit0) - 1ull);      // this word: only the cells after this one
+      for (uint32_t k = cell >> 6;; m = mask[++k] & same) {
+        if (m) {
+          const uint32_t t = (k * 64u + (uint32_t)__builtin_ctzll(m) - cell) / s0;
+          if (t <= R) len = t;
+          break;
+        }
+        if ((k * 64u + 63u - cell) / s0 >= R) break;      // the line ends inside this word
       }
-      if ((k * 64u + 63u - cell) / s0 >= R) break;      // the line ends inside this word
+    } else {
+      for (len = 1; len <= R; len++) {
+        const uint32_t c2 = cell + len * s0;
+        if ((mask[c2 >> 6] >> (c2 & 63u)) & 1ull) break;
+      }
     }
-  } else {
-    for (len = 1; len <= R; len++) {
-      const uint32_t c2 = cell + len * s0;
-      if ((mask[c2 >> 6] >> (c2 & 63u)) & 1ull) break;
-    }
+    const uint32_t shift = (a0 & 3u) * 8u;
+    uint32_t L[4] = {0x01010101u, 0x01010101u, 0x01010101u, 0x01010101u};
+    const uint32_t w = (0x01010101u & ~(0xFFu << shift)) | (len << shift);
+    L[0] = (a0 >> 2) == 0 ? w : L[0];
+    L[1] = (a0 >> 2) == 1 ? w : L[1];
+    L[2] = (a0 >> 2) == 2 ? w : L[2];
+    L[3] = (a0 >> 2) == 3 ? w : L[3];
+    bcell[id] = cell;
+    blen[id] = make_uint4(L[0], L[1], L[2], L[3]);
+    alive[id] = 1;
+    pred[id] = 0;
   }
-  const uint32_t shift = (a0 & 3u) * 8u;
-  uint32_t L[4] = {0x01010101u, 0x01010101u, 0x01010101u, 0x01010101u};
-  const uint32_t w = (0x01010101u & ~(0xFFu << shift)) | (len << shift);
-  L[0] = (a0 >> 2) == 0 ? w : L[0];
-  L[1] = (a0 >> 2) == 1 ? w : L[1];
-  L[2] = (a0 >> 2) == 2 ? w : L[2];
-  L[3] = (a0 >> 2) == 3 ? w : L[3];
-  bcell[id] = cell;
-  blen[id] = make_uint4(L[0], L[1], L[2], L[3]);
-  alive[id] = 1;
-  pred[id] = 0;
 }
 
 // A wave of the word-by-word kernels takes this many consecutive mask words: 64 (one per lane)
@@ -514,7 +523,7 @@ void launch_head_flags(const Geo& g, uint32_t a0, const uint64_t* cost, const ui
     hipLaunchKernelGGL(head_flags_wave_kernel, dim3((blocks + 4 * kHeadSpread - 1) / (4 * kHeadSpread) * (4 * kHeadSpread)), dim3(256), 0, st, g, a0, cost, arg,
                        (const unsigned long long*)fitmap, axis_sizes, maskD, maskC, lineD, lineC);
   else
-    hipLaunchKernelGGL(head_flags_kernel, dim3((g.n + 255) / 256), dim3(256), 0, st, g, a0, cost, arg, fitmap, axis_sizes,
+    hipLaunchKernelGGL(head_flags_kernel, dim3((g.n + 256 * kCellWords - 1) / (256 * kCellWords)), dim3(256), 0, st, g, a0, cost, arg, fitmap, axis_sizes,
                        maskD, maskC);
 }
 
@@ -527,7 +536,7 @@ void launch_make_boxes(const Geo& g, uint32_t a0, const unsigned long long* mask
     hipLaunchKernelGGL(make_boxes_wave_kernel, dim3((n_words + 4 * wpw - 1) / (4 * wpw)), dim3(256), 0, st, g, a0, n_words, wpw, mask, prefix,
                        line, bcell, (uint4*)blen, alive, pred);
   } else {
-    hipLaunchKernelGGL(make_boxes_kernel, dim3((g.n + 255) / 256), dim3(256), 0, st, g, a0, mask, prefix, bcell,
+    hipLaunchKernelGGL(make_boxes_kernel, dim3((g.n + 256 * kCellWords - 1) / (256 * kCellWords)), dim3(256), 0, st, g, a0, mask, prefix, bcell,
                        (uint4*)blen, alive, pred);
   }
 }

@@ -637,7 +637,7 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
 
   // ---- fill: plan, then one launch (or two) per dependency level ----
   AuxLease lease;
-  rc = get_aux(2 * (size_t)n_lev + 5, lease);
+  rc = get_aux(2 * (size_t)n_lev + 7, lease);
   if (rc) return rc;
   Aux* aux = lease.a;
   hipEvent_t* ev = aux->timing;
@@ -723,8 +723,13 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
   auto axis_sizes = [&](uint32_t a) -> const uint32_t* { return a < 4 ? (const uint32_t*)((char*)d_P + offsetof(DevParams, sizes) + a * sizeof(uint32_t) * kMaxSizes) : nullptr; };
   unsigned long long* lineL[2] = {(unsigned long long*)(base + f.lineD), (unsigned long long*)(base + f.lineC)};
   launch_head_flags(g, a0, tab->d_cost, tab->d_arg, d_fitmap, axis_sizes(a0), maskL[0], maskL[1], lineL[0], lineL[1], st);
-  scan_mask_words(maskL[0], f.n_words, tile_tmp, prefL[0], d_tot + 0, st);
+  // the two prefix sums side by side (each is three short kernels): the decisions' on the helper stream
+  HIP_TRY(hipEventRecord(aux->events[ev_used], st));
+  HIP_TRY(hipStreamWaitEvent(s2, aux->events[ev_used++], 0));
+  scan_mask_words(maskL[0], f.n_words, (uint32_t*)(base + f.tile_tmp2), prefL[0], d_tot + 0, s2);
   scan_mask_words(maskL[1], f.n_words, tile_tmp, prefL[1], d_tot + 1, st);
+  HIP_TRY(hipEventRecord(aux->events[ev_used], s2));
+  HIP_TRY(hipStreamWaitEvent(st, aux->events[ev_used++], 0));
   uint32_t h_tot[4] = {0, 0, 0, 0};
   HIP_TRY(hipMemcpyAsync(h_tot, d_tot, 8, hipMemcpyDeviceToHost, st));
   HIP_TRY(hipStreamSynchronize(st));

@@ -388,3 +388,69 @@ def test_schedule_parity(number, max_size, label):
     with pytest.raises(B.MorelloError) as e:
         tab.schedule(tuple(int(v) for v in np.unravel_index(bad, ext)))
     assert e.value.code == B.E_INVAL
+
+
+def random_config(seed):
+    """A seeded random target and set of lattices of every kind: 1..4 levels, capacities that bite or
+    not, size lists that are not powers of two, layout and dtype bits on random operands."""
+    rng = np.random.default_rng(seed)
+    nl = int(rng.integers(1, 5))
+    caps = [int(rng.choice([8, 24, 64, 100, 256, 1000, W.UNBOUNDED])) for _ in range(nl)]
+    if nl > 1:
+        caps[-1] = W.UNBOUNDED if rng.random() < 0.7 else caps[-1]
+    t = W._empty_target(nl, caps)
+    for src in range(1, nl):
+        for dst in range(src):
+            for x in range(2):
+                t["load_coef"][src][dst][x] = int(rng.integers(0, 9))       # 0 = that Move does not exist
+                t["store_coef"][dst][src][x] = int(rng.integers(0, 9))
+    t["convert_coef"] = int(rng.integers(0, 4))
+    t["zero_coef"] = [int(rng.integers(0, 4)) for _ in range(4)]
+    t["loop_overhead"] = int(rng.integers(0, 5))
+    t["threads"] = int(rng.integers(1, 6))
+    t["sync_cost"] = int(rng.integers(0, 12))
+    t["microkernels"] = [(W.MK_SCALAR_FMA, 1, int(rng.integers(1, 4))), (W.MK_SCALAR_ADDRELU, 1, 1)]
+    if nl > 1:
+        t["microkernels"] += [(W.MK_BCAST_VEC_MULADD, int(rng.choice([2, 4])), int(rng.integers(1, 3))),
+                              (W.MK_BF16_DOT, int(rng.choice([2, 4])), 1), (W.MK_VEC_ADDRELU, 2, 1)]
+
+    def sizes(max_n):
+        n = int(rng.integers(1, max_n + 1))
+        rest = sorted(rng.choice(np.arange(2, 13), size=n - 1, replace=False).tolist()) if n > 1 else []
+        return [1] + [int(v) for v in rest]
+
+    m, k, n = sizes(4), sizes(4), sizes(5)
+    lay = [int(rng.random() < 0.4) for _ in range(3)]
+    lats = []
+    kind = int(rng.choice([0, 1, 2, 3]))
+    if kind == 0:       # Matmul with batch, layout and dtype bits
+        dt = [int(rng.random() < 0.4), int(rng.random() < 0.4), 0]
+        bb = [2 if dt[i] == 0 and rng.random() < 0.3 else 4 for i in range(2)] + [4]
+        lat = W._lattice(W.KIND_MATMUL_ACCUM, [sizes(2), m, k, n], layout=lay + [0, 0], dtype=dt + [0, 0],
+                         base_bytes=bb + [4, 4])
+        lats = [("M", lat, [])]
+    elif kind == 1:     # serial and parallel Matmul
+        lat = W._lattice(W.KIND_MATMUL_ACCUM, [sizes(2), m, k, n], layout=lay + [0, 0])
+        lats = [("M", lat, []), ("P", dict(lat, kind=W.KIND_MATMUL_PARALLEL), ["M"])]
+    else:               # the fused trio, plain (2) or with memory bounds (3)
+        b = kind == 3
+        if b:           # keep the bound axes short
+            t["capacity_bytes"] = [min(c, 64) if c != W.UNBOUNDED else c for c in t["capacity_bytes"][:nl]] + [0] * (4 - nl)
+        lm = W._lattice(W.KIND_MATMUL_BOUNDED if b else W.KIND_MATMUL_ACCUM, [[1], m, k, n], layout=lay + [0, 0])
+        le = W._lattice(W.KIND_BIAS_ADD_RELU_BOUNDED if b else W.KIND_BIAS_ADD_RELU, [[1], m, [1], n],
+                        layout=[int(rng.random() < 0.4), 0, int(rng.random() < 0.4), 0, 0])
+        lf = W._lattice(W.KIND_FUSED_BOUNDED if b else W.KIND_FUSED_MM_ADD_RELU, [[1], m, k, n],
+                        layout=[lay[0], lay[1], 0, int(rng.random() < 0.4), 0])
+        lats = [("M", lm, []), ("E", le, []), ("F", lf, ["M", "E"])]
+    return {"name": "random-%d" % seed, "target": t, "lattices": lats}
+
+
+@pytest.mark.parametrize("seed", list(range(100, 124)))
+def test_parity_random_lattices(seed):
+    """Seeded random targets and lattices of every kind, all outputs against the oracle."""
+    cfg = random_config(seed)
+    if sum(W.n_specs(cfg["target"], lat) for _, lat, _ in cfg["lattices"]) > 6_000_000:
+        pytest.skip("too large for a quick case")
+    _, got, want = compare_config(cfg)
+    for label, _, _ in cfg["lattices"]:
+        check_compressed_queries(got[label], want[label], 5_000, seed=seed)

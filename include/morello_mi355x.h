@@ -133,7 +133,7 @@ typedef struct {
   uint32_t kind;
   uint32_t n_sizes[4];                        /* 1..MRL_MAX_SIZES each                        */
   const uint32_t* sizes[4];                   /* host; ascending, sizes[d][0] == 1            */
-  uint8_t layout_coord[MRL_MAX_OPERANDS];
+  uint8_t layout_coord[MRL_MAX_OPERANDS];     /* layout and dtype bits together: at most 4    */
   uint8_t dtype_coord[MRL_MAX_OPERANDS];      /* MATMUL_ACCUM inputs only                     */
   uint8_t base_dtype_bytes[MRL_MAX_OPERANDS]; /* 4 or 2; used when the operand has no dtype bit */
 } mrl_lattice_desc;

@@ -93,6 +93,12 @@ def lib():
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise ImportError("%s is missing: run __graft_entry__.build() (hipcc, gfx950)" % LIB_PATH)
+        # torch first: it brings its own HIP runtime, and the library must share that one.  Loaded the
+        # other way round the process holds two runtimes and the library's finds no device.
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         _lib = C.CDLL(LIB_PATH)
         for name in EXPORTS:
             getattr(_lib, name).restype = C.c_int32

@@ -769,8 +769,9 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
   }
   uint32_t n_generic = n_axes;
   // (a power-of-two stride: the coordinate on the axis is then one bit of the cell index, which
-  // the kernel relies on; behind an axis of another extent, e.g. a memory bound, it is not)
-  auto tail_axis = [&](uint32_t a) { return g.ext[a] == 2 && g.stride[a] <= 32 && (g.stride[a] & (g.stride[a] - 1)) == 0; };
+  // the kernel relies on; behind an axis of another extent, e.g. a memory bound, it is not.  Not a
+  // size axis: along those the cost list compares costs per volume, which that kernel does not)
+  auto tail_axis = [&](uint32_t a) { return a >= 4 && g.ext[a] == 2 && g.stride[a] <= 32 && (g.stride[a] & (g.stride[a] - 1)) == 0; };
   while (n_generic > 0 && n_axes - n_generic < 6 && tail_axis(pass_axis[n_generic - 1])) n_generic--;
   TailAxes tail;
   tail.n = n_axes - n_generic;

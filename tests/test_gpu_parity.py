@@ -425,6 +425,8 @@ def random_config(seed):
     kind = int(rng.choice([0, 1, 2, 3]))
     if kind == 0:       # Matmul with batch, layout and dtype bits
         dt = [int(rng.random() < 0.4), int(rng.random() < 0.4), 0]
+        if sum(lay) + sum(dt) > 4:          # the library takes four layout and dtype bits
+            dt[1] = 0
         bb = [2 if dt[i] == 0 and rng.random() < 0.3 else 4 for i in range(2)] + [4]
         lat = W._lattice(W.KIND_MATMUL_ACCUM, [sizes(2), m, k, n], layout=lay + [0, 0], dtype=dt + [0, 0],
                          base_bytes=bb + [4, 4])
@@ -445,9 +447,10 @@ def random_config(seed):
     return {"name": "random-%d" % seed, "target": t, "lattices": lats}
 
 
-@pytest.mark.parametrize("seed", list(range(100, 124)))
+@pytest.mark.parametrize("seed", list(range(100, 124)) + [1055])
 def test_parity_random_lattices(seed):
-    """Seeded random targets and lattices of every kind, all outputs against the oracle."""
+    """Seeded random targets and lattices of every kind, all outputs against the oracle (1055: size
+    axes of two sizes and small strides, which the fused last merge passes must leave alone)."""
     cfg = random_config(seed)
     if sum(W.n_specs(cfg["target"], lat) for _, lat, _ in cfg["lattices"]) > 6_000_000:
         pytest.skip("too large for a quick case")

@@ -100,6 +100,8 @@ void mrl_target_destroy(mrl_target* t);
  * written); b and k must be pinned to 1.  FUSED_MM_ADD_RELU (Section 2.1,
  * Matmul -> bias add -> ReLU split once by bufferize): lhs, rhs, bias (read),
  * out (written), intermediate m*n f32; b pinned to 1; only m and n are tiled.
+ * Where the FUSED lattice has a layout coordinate (lhs, rhs, out), the dep in
+ * which that tensor is looked up must have one too (MRL_E_INVAL else).
  * MATMUL_PARALLEL (Section 2.2: the serial-only flag; Section 3: the loop
  * rule with threads): the MATMUL_ACCUM Specs with the flag off.  Same
  * operands, coordinates and rewrites as MATMUL_ACCUM, plus a parallel loop

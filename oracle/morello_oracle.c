@@ -448,6 +448,9 @@ int orc_solve(const orc_target* T, const orc_lattice* L,
     if (ctx_init(&cm, T, LM) || ctx_init(&ce, T, LE)) return -1;
     if (cm.kind != KIND_M || cm.parallel || ce.kind != KIND_E) return -1;
     if (cm.bounded != c.bounded || ce.bounded != c.bounded) return -1;      /* bounds on all three tables or on none */
+    /* a tensor whose layout the fused lattice distinguishes must have that coordinate in the table it is looked up in */
+    if ((c.lay_axis[0] >= 0 && cm.lay_axis[0] < 0) || (c.lay_axis[1] >= 0 && cm.lay_axis[1] < 0) ||
+        (c.lay_axis[3] >= 0 && ce.lay_axis[2] < 0)) return -1;
     for (int d = 1; d < 4; d++) if (!same_sizes(L, d, LM, d)) return -1;
     if (LM->n_sizes[0] != 1) return -1;
     if (!same_sizes(L, 1, LE, 1) || !same_sizes(L, 3, LE, 3)) return -1;

@@ -577,6 +577,9 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
     const Compiled& E = *deps[1]->cp;
     if (M.P.kind != kKindM || M.P.par || E.P.kind != kKindE) return fail(MRL_E_INVAL, "deps must be {MATMUL_ACCUM, BIAS_ADD_RELU}");
     if (M.P.bounded != P.bounded || E.P.bounded != P.bounded) return fail(MRL_E_INVAL, "memory bounds on all three tables or on none");
+    if ((P.lay_bit[0] != kNoBit && M.P.lay_bit[0] == kNoBit) || (P.lay_bit[1] != kNoBit && M.P.lay_bit[1] == kNoBit) ||
+        (P.lay_bit[3] != kNoBit && E.P.lay_bit[2] == kNoBit))
+      return fail(MRL_E_INVAL, "a tensor with a layout coordinate in the FUSED lattice needs one in the dep it is looked up in");
     if (memcmp(&M.target, &t->d, sizeof t->d) || memcmp(&E.target, &t->d, sizeof t->d)) return fail(MRL_E_INVAL, "deps were solved for another target");
     for (int d = 1; d < 4; d++) if (M.sizes[d] != c.sizes[d]) return fail(MRL_E_INVAL, "MATMUL_ACCUM dep has other size lists");
     if (M.sizes[0].size() != 1) return fail(MRL_E_INVAL, "MATMUL_ACCUM dep must have b pinned to 1");

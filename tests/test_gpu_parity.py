@@ -344,6 +344,13 @@ def test_query_decode_and_errors():
     with pytest.raises(B.MorelloError) as e:
         B.solve(B.Target(c5["target"]), c5["lattices"][2][1])
     assert e.value.code == B.E_INVAL
+    # a fused lattice that distinguishes the layout of its output over a bias-add + ReLU table that does not
+    t5 = B.Target(c5["target"])
+    tm = B.solve(t5, c5["lattices"][0][1])
+    te = B.solve(t5, dict(c5["lattices"][1][1], layout_coord=[1, 0, 0, 0, 0]))
+    with pytest.raises(B.MorelloError) as e:
+        B.solve(t5, c5["lattices"][2][1], deps=[tm, te])
+    assert e.value.code == B.E_INVAL
 
 
 def test_deterministic():
@@ -439,10 +446,12 @@ def random_config(seed):
         if b:           # keep the bound axes short
             t["capacity_bytes"] = [min(c, 64) if c != W.UNBOUNDED else c for c in t["capacity_bytes"][:nl]] + [0] * (4 - nl)
         lm = W._lattice(W.KIND_MATMUL_BOUNDED if b else W.KIND_MATMUL_ACCUM, [[1], m, k, n], layout=lay + [0, 0])
+        y_out = int(rng.random() < 0.4)        # the fused lattice distinguishes a layout only where its deps do
         le = W._lattice(W.KIND_BIAS_ADD_RELU_BOUNDED if b else W.KIND_BIAS_ADD_RELU, [[1], m, [1], n],
-                        layout=[int(rng.random() < 0.4), 0, int(rng.random() < 0.4), 0, 0])
+                        layout=[int(rng.random() < 0.4), 0, y_out, 0, 0])
         lf = W._lattice(W.KIND_FUSED_BOUNDED if b else W.KIND_FUSED_MM_ADD_RELU, [[1], m, k, n],
-                        layout=[lay[0], lay[1], 0, int(rng.random() < 0.4), 0])
+                        layout=[lay[0] and int(rng.random() < 0.7), lay[1] and int(rng.random() < 0.7), 0,
+                                y_out and int(rng.random() < 0.7), 0])
         lats = [("M", lm, []), ("E", le, []), ("F", lf, ["M", "E"])]
     return {"name": "random-%d" % seed, "target": t, "lattices": lats}
 

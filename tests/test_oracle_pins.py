@@ -170,6 +170,11 @@ def test_brute_force_fused_pipeline():
     n = brute_force_compare(t, lats, res, "F",
                             pick=lambda s: sum(s.levels[:4]) + s.levels[4] <= 2 and s.dims[1] * s.dims[3] <= 8)
     assert n > 100
+    # the fused lattice may distinguish a tensor's layout only if the table it is looked up in does
+    import pytest
+    lats[1] = ("E", dict(lats[1][1], layout_coord=[1, 0, 0, 0, 0]), [])
+    with pytest.raises(ValueError):
+        O.solve_config({"target": t, "lattices": lats})
 
 
 def parallel_setup(threads, sync, max_size=4):

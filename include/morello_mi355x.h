@@ -49,7 +49,8 @@ enum { MRL_MAX_LEVELS = 4, MRL_MAX_OPERANDS = 5, MRL_MAX_DIMS = 16, MRL_MAX_MK =
  * weights).  Level 0 is the fastest.  A Move goes to a strictly lower level
  * index only, and costs coef * (elements of the operand): load_coef for an
  * operand that is read, store_coef for one that is written, both for the
- * accumulated output of a MatmulAccum.  A zero coefficient forbids the Move.
+ * accumulated output of a MatmulAccum (their sum must fit 32 bits, or creating
+ * a lattice fails with MRL_E_INVAL).  A zero coefficient forbids the Move.
  */
 typedef enum {
   MRL_MK_SCALAR_FMA = 0,        /* 1x1x1x1 MatmulAccum, all operands in level 0, f32          */

@@ -83,3 +83,18 @@ def test_geometry_of_every_kind_agrees_with_the_oracle():
         assert False
     except B.MorelloError as e:
         assert e.code == B.E_INVAL
+
+
+def test_move_coefficients_whose_sum_exceeds_32_bits_are_refused():
+    """The accumulated output of a Matmul pays load + store per element; the library keeps that sum
+    in 32 bits and says so when it does not fit (no silent wrap-around)."""
+    cfg = W.config(1, max_size=4)
+    cfg["target"]["load_coef"][1][0][0] = (1 << 32) - 1
+    cfg["target"]["store_coef"][0][1][0] = 1
+    try:
+        B.geometry(B.Target(cfg["target"]), cfg["lattices"][0][1])
+        assert False
+    except B.MorelloError as e:
+        assert e.code == B.E_INVAL and "too large" in str(e)
+    cfg["target"]["store_coef"][0][1][0] = 0        # no store: the output cannot move, the inputs can
+    B.geometry(B.Target(cfg["target"]), cfg["lattices"][0][1])

@@ -71,8 +71,9 @@ def main():
 
     def step():
         # every lattice gets its own slice of the scratch buffer: a solved table keeps its box
-        # lists there while later lattices are solved.  Lattices that do not depend on each other
-        # (M and E) are in flight together.
+        # lists there while later lattices are solved.  One call for all lattices: those that do
+        # not depend on each other (M and E) are in flight together, and F starts when the fills of
+        # M and E are queued, while these two are still to be compressed.
         return B.solve_lattices(target, cfg["lattices"],
                                 buffers={l: (bufs[l][0], bufs[l][1], scratch_of[l]) for l in bufs})
 

@@ -187,6 +187,34 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat,
                   void* hip_stream, mrl_table** out, mrl_stats* stats);
 void mrl_table_destroy(mrl_table* tab);
 
+/* Several lattices in one call (Section 4: the search of a Spec needs the memo
+ * table entries of its sub-Specs, here the dense tables of the lattices it reads,
+ * not their compressed form of Section 4.1).  Job j is what mrl_solve would do
+ * with the same arguments, its deps given as indices of EARLIER jobs.  Every job
+ * runs from a host thread of its own on its own stream (all different; default
+ * priority); a job starts as soon as the FILL of its deps is queued, ordered behind
+ * it on the device by an event, and a dep is compressed once the jobs that read it
+ * have queued their own fill: its compression overlaps with their work instead of
+ * holding it up, and independent jobs overlap as with mrl_solve from several
+ * threads.  The last job runs on the calling thread.  jobs, out (n_jobs handles) and stats (n_jobs entries,
+ * optional) are host arrays.  On success every out[j] is a table as from
+ * mrl_solve.  On failure the status and message are those of the first job that
+ * failed ("job <j>: ..."), no table is left and every out[j] is NULL.  The call
+ * returns after all jobs have ended and their streams have drained. */
+enum { MRL_MAX_JOBS = 16 };
+typedef struct {
+  const mrl_lattice_desc* lattice;
+  uint32_t n_deps;
+  uint32_t deps[2];                           /* indices of earlier jobs, in mrl_solve's dep order */
+  void* d_cost;                               /* device, as for mrl_solve                           */
+  void* d_argmin;
+  void* d_scratch;
+  size_t scratch_bytes;
+  void* hip_stream;                           /* a hipStream_t; no two jobs share one               */
+} mrl_job;
+int32_t mrl_solve_graph(const mrl_target* t, const mrl_job* jobs, uint32_t n_jobs,
+                        mrl_table** out, mrl_stats* stats);
+
 /* ---------------------------------------------------------------------------
  * Query (Section 4: a Spec that the memo table already holds is answered from
  * it).  specs, cost_out, rewrite_out: host arrays of n. */

@@ -18,7 +18,7 @@ MAX_DIMS = 16
 
 OK, E_INVAL, E_NOMEM, E_HIP, E_RANGE, E_BUFSZ, E_OVERFLOW = 0, -1, -2, -3, -4, -5, -6
 
-EXPORTS = ["mrl_target_create", "mrl_target_destroy", "mrl_geometry", "mrl_table_bytes", "mrl_solve",
+EXPORTS = ["mrl_target_create", "mrl_target_destroy", "mrl_geometry", "mrl_table_bytes", "mrl_solve", "mrl_solve_graph",
            "mrl_table_destroy", "mrl_query", "mrl_query_compressed", "mrl_rewrite_decode", "mrl_coord_of_spec",
            "mrl_emit_compressed", "mrl_schedule", "mrl_copy_dense", "mrl_last_error"]
 
@@ -341,55 +341,68 @@ def _side_stream(dev, i):
     return pool[i]
 
 
-def solve_lattices(target, lattices, scratch_bytes=None, buffers=None):
-    """Solve [(label, lattice, dep labels)] in dependency order; returns {label: Table}.
+class _Job(C.Structure):
+    _fields_ = [("lattice", C.c_void_p), ("n_deps", C.c_uint32), ("deps", C.c_uint32 * 2),
+                ("d_cost", C.c_void_p), ("d_argmin", C.c_void_p), ("d_scratch", C.c_void_p),
+                ("scratch_bytes", C.c_size_t), ("hip_stream", C.c_void_p)]
 
-    Lattices whose dependencies are done and that do not depend on each other are handed to the
-    library from one host thread each, on a stream of their own (default priority), so their
-    kernels overlap on the device; the library call itself releases the GIL.  buffers: optional
-    {label: (cost, argmin, scratch)} torch uint8 tensors to reuse.
+
+def solve_lattices(target, lattices, scratch_bytes=None, buffers=None):
+    """Solve [(label, lattice, dep labels)] with one call of mrl_solve_graph; returns {label: Table}.
+
+    The library runs every lattice from a host thread of its own, on a stream of its own
+    (default priority): lattices that do not depend on each other overlap on the device, and a
+    lattice starts when the fill of those it reads is queued, while they are still being
+    compressed.  buffers: optional {label: (cost, argmin, scratch)} torch uint8 tensors to reuse.
     """
-    import threading
-    import torch
-    done, pending = {}, list(lattices)
-    seen, left = set(), [(job[0], job[2]) for job in pending]
-    while left:                         # the dependency order exists: checked before any device work
-        ok = [lab for lab, deps in left if all(d in seen for d in deps)]
+    # dependency order (checked before any device work)
+    order, seen, left = [], set(), list(lattices)
+    while left:
+        ok = [job for job in left if all(d in seen for d in job[2])]
         if not ok:
             raise ValueError("lattice dependencies form a cycle or name an unknown label")
-        seen.update(ok)
-        left = [(lab, deps) for lab, deps in left if lab not in seen]
+        order += ok
+        seen.update(job[0] for job in ok)
+        left = [job for job in left if job[0] not in seen]
+    import torch
+    if not torch.cuda.is_available():
+        raise RuntimeError("mrl solve needs a GPU: there is no CPU path")
     dev = torch.cuda.current_device()
-    while pending:
-        ready = [job for job in pending if all(d in done for d in job[2])]
-        if not ready:
-            raise ValueError("lattice dependencies form a cycle or name an unknown label")
-        pending = [job for job in pending if job not in ready]
-
-        def run(job, stream, errors):
-            label, lat, deps = job
-            try:
-                torch.cuda.set_device(dev)
-                done[label] = solve(target, lat, deps=[done[d] for d in deps], scratch_bytes=scratch_bytes,
-                                    stream=stream, buffers=None if buffers is None else buffers[label])
-            except BaseException as e:      # re-raised in the calling thread
-                errors.append(e)
-
-        errors = []
-        if len(ready) == 1:
-            run(ready[0], None, errors)
+    device = torch.device("cuda", dev)
+    index = {job[0]: i for i, job in enumerate(order)}
+    jobs = (_Job * len(order))()
+    keep, held, exts = [], [], []
+    for i, (label, lat, deps) in enumerate(order):
+        L = _lattice_desc(lat)
+        keep.append(L)
+        ext, n = geometry(target, lat)
+        exts.append(ext)
+        if buffers is None:
+            sb = table_bytes(target, lat)[2] if scratch_bytes is None else scratch_bytes
+            bufs = (torch.empty(8 * n, dtype=torch.uint8, device=device),
+                    torch.empty(2 * n, dtype=torch.uint8, device=device),
+                    torch.empty(sb, dtype=torch.uint8, device=device))
         else:
-            # every job on a stream of its own: work on the default stream would serialize with them
-            torch.cuda.synchronize()        # the streams start after everything queued so far
-            threads = [threading.Thread(target=run, args=(job, _side_stream(dev, i + 1), errors))
-                       for i, job in enumerate(ready[1:])]
-            for t in threads:
-                t.start()
-            run(ready[0], _side_stream(dev, 0), errors)
-            for t in threads:
-                t.join()
-        if errors:
-            raise errors[0]
+            bufs = buffers[label]
+        assert bufs[0].numel() >= 8 * n and bufs[1].numel() >= 2 * n
+        held.append(bufs)
+        jobs[i].lattice = C.cast(C.pointer(L), C.c_void_p)
+        jobs[i].n_deps = len(deps)
+        for k, d in enumerate(deps):
+            jobs[i].deps[k] = index[d]
+        jobs[i].d_cost, jobs[i].d_argmin, jobs[i].d_scratch = (b.data_ptr() for b in bufs)
+        jobs[i].scratch_bytes = bufs[2].numel()
+        # the last lattice (on the calling thread) takes the current stream, the others side streams
+        last = i == len(order) - 1
+        jobs[i].hip_stream = torch.cuda.current_stream().cuda_stream if last else _side_stream(dev, i).cuda_stream
+    handles = (C.c_void_p * len(order))()
+    stats = (Stats * len(order))()
+    torch.cuda.synchronize()            # the side streams start after everything queued so far
+    _check(lib().mrl_solve_graph(target._h, jobs, C.c_uint32(len(order)), handles, stats))
+    done = {}
+    for i, (label, lat, deps) in enumerate(order):
+        st = Stats.from_buffer_copy(stats[i])
+        done[label] = Table(C.c_void_p(handles[i]), target, lat, exts[i], held[i], st, [done[d] for d in deps])
     return done
 
 

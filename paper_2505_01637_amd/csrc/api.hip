@@ -7,10 +7,14 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstdlib>
+#include <condition_variable>
 #include <cstring>
+#include <functional>
 #include <memory>
 #include <mutex>
 #include <new>
+#include <string>
+#include <thread>
 #include <vector>
 
 #include "../../include/morello_mi355x.h"
@@ -553,18 +557,66 @@ int32_t mrl_table_bytes(const mrl_target* t, const mrl_lattice_desc* lat, size_t
   });
 }
 
-int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_table* const* deps, uint32_t n_deps,
-                  void* d_cost, void* d_argmin, void* d_scratch, size_t scratch_bytes, void* hip_stream,
-                  mrl_table** out, mrl_stats* stats) {
+}  // extern "C"
+
+namespace {
+
+// on_filled (optional) is called once, when the fill's last kernel is queued on the table's stream
+// and before the compression starts: the dense table is then complete for any work ordered after
+// that point of the stream.  It returns whether the caller now shares the table object; a shared
+// one is not deleted when the rest of the solve fails (the sharer deletes it).
+using FilledFn = std::function<bool(mrl_table*)>;
+
+// Host threads that run the jobs of mrl_solve_graph.  They are kept between calls (a thread's
+// first HIP calls are slow) and never end; every queued task gets a thread, since tasks wait for
+// each other.  The pool is never destroyed: its threads may still wait in it when the process ends.
+class Workers {
+ public:
+  void submit(std::function<void()> task) {
+    std::lock_guard<std::mutex> lk(mu_);
+    queue_.push_back(std::move(task));
+    if (idle_ < queue_.size()) {
+      try { std::thread([this] { loop(); }).detach(); }
+      catch (...) { queue_.pop_back(); throw; }
+    }
+    cv_.notify_all();
+  }
+
+ private:
+  void loop() {
+    for (;;) {
+      std::function<void()> task;
+      {
+        std::unique_lock<std::mutex> lk(mu_);
+        idle_++;
+        cv_.wait(lk, [&] { return !queue_.empty(); });
+        idle_--;
+        task = std::move(queue_.front());
+        queue_.erase(queue_.begin());
+      }
+      task();
+    }
+  }
+  std::mutex mu_;
+  std::condition_variable cv_;
+  std::vector<std::function<void()>> queue_;
+  size_t idle_ = 0;
+};
+Workers& workers() { static Workers* w = new Workers; return *w; }
+
+int32_t solve_impl(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_table* const* deps, uint32_t n_deps,
+                   void* d_cost, void* d_argmin, void* d_scratch, size_t scratch_bytes, void* hip_stream,
+                   mrl_table** out, mrl_stats* stats, const FilledFn& on_filled) {
   return guarded([&]() -> int32_t {
   if (!out) return fail(MRL_E_INVAL, "out is NULL");
   *out = nullptr;
   if (!t) return fail(MRL_E_INVAL, "target is NULL");
+  if (!lat) return fail(MRL_E_INVAL, "lattice descriptor is NULL");
   if (!d_cost || !d_argmin || !d_scratch) return fail(MRL_E_INVAL, "device buffers must not be NULL");
   if (((uintptr_t)d_cost | (uintptr_t)d_argmin | (uintptr_t)d_scratch) % kAlign) return fail(MRL_E_INVAL, "device buffers must be 256-byte aligned");
   mrl_table* tab = new (std::nothrow) mrl_table;
   if (!tab) return fail(MRL_E_NOMEM, "host allocation failed");
-  struct Guard { mrl_table* p; ~Guard() { delete p; } } guard{tab};
+  struct Guard { mrl_table* p; bool shared; ~Guard() { if (!shared) delete p; } } guard{tab, false};
   int32_t rc = get_compiled(t->d, lat, tab->cp);
   if (rc) return rc;
   const Compiled& c = *tab->cp;
@@ -714,6 +766,7 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
   }
   HIP_TRY(hipGetLastError());
   HIP_TRY(hipEventRecord(ev[1], st));
+  if (on_filled) guard.shared = on_filled(tab);
 
   // ---- compression ----
   const Geo& g = c.geo;
@@ -895,6 +948,148 @@ int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_ta
   guard.p = nullptr;
   *out = tab;
   return MRL_OK;
+  });
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t mrl_solve(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_table* const* deps, uint32_t n_deps,
+                  void* d_cost, void* d_argmin, void* d_scratch, size_t scratch_bytes, void* hip_stream,
+                  mrl_table** out, mrl_stats* stats) {
+  return solve_impl(t, lat, deps, n_deps, d_cost, d_argmin, d_scratch, scratch_bytes, hip_stream, out, stats, FilledFn());
+}
+
+int32_t mrl_solve_graph(const mrl_target* t, const mrl_job* jobs, uint32_t n_jobs, mrl_table** out, mrl_stats* stats) {
+  return guarded([&]() -> int32_t {
+  if (!out) return fail(MRL_E_INVAL, "out is NULL");
+  for (uint32_t j = 0; j < n_jobs && j < MRL_MAX_JOBS; j++) out[j] = nullptr;
+  if (!t || !jobs) return fail(MRL_E_INVAL, "NULL argument");
+  if (n_jobs < 1 || n_jobs > MRL_MAX_JOBS) return fail(MRL_E_INVAL, "n_jobs must be 1..%d", MRL_MAX_JOBS);
+  for (uint32_t j = 0; j < n_jobs; j++) {
+    if (!jobs[j].lattice) return fail(MRL_E_INVAL, "job %u: lattice descriptor is NULL", j);
+    if (jobs[j].n_deps > 2) return fail(MRL_E_INVAL, "job %u: at most two deps", j);
+    for (uint32_t i = 0; i < jobs[j].n_deps; i++)
+      if (jobs[j].deps[i] >= j) return fail(MRL_E_INVAL, "job %u: a dep must be an earlier job", j);
+    for (uint32_t k = 0; k < j; k++)
+      if (jobs[k].hip_stream == jobs[j].hip_stream) return fail(MRL_E_INVAL, "jobs %u and %u share a stream", k, j);
+  }
+  int dev = 0;
+  HIP_TRY(hipGetDevice(&dev));
+
+  enum { kWaiting = 0, kFilled = 1, kFailed = 2 };
+  struct Shared {
+    std::mutex mu;
+    std::condition_variable cv;
+    int state[MRL_MAX_JOBS] = {};
+    mrl_table* table[MRL_MAX_JOBS] = {};      // from the moment a job's fill is queued
+    hipEvent_t filled[MRL_MAX_JOBS] = {};     // recorded on the job's stream at that moment
+    int32_t rc[MRL_MAX_JOBS] = {};
+    bool skipped[MRL_MAX_JOBS] = {};          // not run: a dep failed
+    std::string err[MRL_MAX_JOBS];
+  } S;
+  struct Events {
+    Shared& s; uint32_t n = 0;
+    ~Events() { for (uint32_t j = 0; j < n; j++) (void)hipEventDestroy(s.filled[j]); }
+  } events{S};
+  for (uint32_t j = 0; j < n_jobs; j++) {
+    HIP_TRY(hipEventCreateWithFlags(&S.filled[j], hipEventDisableTiming));
+    events.n = j + 1;
+  }
+
+  auto run_job = [&](uint32_t j) {
+    const mrl_job& job = jobs[j];
+    int32_t rc = MRL_OK;
+    bool published = false;
+    auto finish = [&](int32_t code) {
+      if (code) S.err[j] = g_err;
+      std::lock_guard<std::mutex> lk(S.mu);
+      S.rc[j] = code;
+      if (!published) { S.table[j] = out[j]; S.state[j] = code ? kFailed : kFilled; }
+      S.cv.notify_all();
+    };
+    if (hipSetDevice(dev) != hipSuccess) { finish(fail(MRL_E_HIP, "hipSetDevice failed")); return; }
+    const mrl_table* deps[2] = {nullptr, nullptr};
+    {
+      std::unique_lock<std::mutex> lk(S.mu);
+      for (uint32_t i = 0; i < job.n_deps; i++) {
+        const uint32_t d = job.deps[i];
+        S.cv.wait(lk, [&] { return S.state[d] != kWaiting; });
+        if (S.state[d] == kFailed) { S.skipped[j] = true; break; }
+        deps[i] = S.table[d];
+      }
+    }
+    if (S.skipped[j]) { finish(fail(MRL_E_INVAL, "a dep of the job failed")); return; }
+    // the dep's dense table is complete once its stream has passed the recorded point
+    for (uint32_t i = 0; i < job.n_deps; i++) {
+      const hipError_t e = hipStreamWaitEvent((hipStream_t)job.hip_stream, S.filled[job.deps[i]], 0);
+      if (e != hipSuccess) { finish(fail(MRL_E_HIP, "hipStreamWaitEvent: %s", hipGetErrorString(e))); return; }
+    }
+    rc = solve_impl(t, job.lattice, job.n_deps ? deps : nullptr, job.n_deps, job.d_cost, job.d_argmin, job.d_scratch,
+                    job.scratch_bytes, job.hip_stream, &out[j], stats ? &stats[j] : nullptr,
+                    [&](mrl_table* tab) {
+                      if (hipEventRecord(S.filled[j], tab->stream) != hipSuccess) return false;   // published at the end instead
+                      std::unique_lock<std::mutex> lk(S.mu);
+                      S.table[j] = tab;
+                      S.state[j] = kFilled;
+                      published = true;
+                      S.cv.notify_all();
+                      // the compression waits until the jobs that read this table have queued their
+                      // fill (or failed): its many small launches would otherwise hold up theirs
+                      for (uint32_t k = j + 1; k < n_jobs; k++)
+                        for (uint32_t i = 0; i < jobs[k].n_deps; i++)
+                          if (jobs[k].deps[i] == j) S.cv.wait(lk, [&] { return S.state[k] != kWaiting; });
+                      return true;
+                    });
+    finish(rc);
+  };
+  // a job always reports: its dependents wait for it
+  auto run = [&](uint32_t j) {
+    try { run_job(j); }
+    catch (...) {
+      std::lock_guard<std::mutex> lk(S.mu);
+      S.rc[j] = MRL_E_NOMEM;
+      if (S.state[j] == kWaiting) S.state[j] = kFailed;
+      S.cv.notify_all();
+    }
+  };
+  {
+    // the last job runs on the calling thread, the others on the library's worker threads
+    uint32_t pending = 0;                     // under S.mu: submitted jobs that have not ended
+    bool submit_failed = false;
+    for (uint32_t j = 0; j + 1 < n_jobs; j++) {
+      { std::lock_guard<std::mutex> lk(S.mu); pending++; }
+      try {
+        workers().submit([&, j] {
+          run(j);
+          std::lock_guard<std::mutex> lk(S.mu);
+          pending--;
+          S.cv.notify_all();
+        });
+      } catch (...) {
+        // no thread for this job: it and the jobs after it fail (those that wait for them wake up)
+        std::lock_guard<std::mutex> lk(S.mu);
+        pending--;
+        for (uint32_t k = j; k < n_jobs; k++) { S.rc[k] = MRL_E_NOMEM; S.state[k] = kFailed; }
+        S.cv.notify_all();
+        submit_failed = true;
+        break;
+      }
+    }
+    if (!submit_failed) run(n_jobs - 1);
+    std::unique_lock<std::mutex> lk(S.mu);
+    S.cv.wait(lk, [&] { return pending == 0; });
+  }
+  uint32_t bad = n_jobs;
+  for (uint32_t j = 0; j < n_jobs && bad == n_jobs; j++) if (S.rc[j] && !S.skipped[j]) bad = j;
+  if (bad == n_jobs) return MRL_OK;
+  // every table goes, also one that was shared before its own solve failed
+  for (uint32_t j = 0; j < n_jobs; j++) {
+    delete (S.table[j] ? S.table[j] : out[j]);
+    out[j] = nullptr;
+  }
+  return fail(S.rc[bad], "job %u: %s", bad, S.err[bad].empty() ? "host allocation failed" : S.err[bad].c_str());
   });
 }
 

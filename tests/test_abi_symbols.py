@@ -98,3 +98,33 @@ def test_move_coefficients_whose_sum_exceeds_32_bits_are_refused():
         assert e.code == B.E_INVAL and "too large" in str(e)
     cfg["target"]["store_coef"][0][1][0] = 0        # no store: the output cannot move, the inputs can
     B.geometry(B.Target(cfg["target"]), cfg["lattices"][0][1])
+
+
+def test_graph_call_refuses_malformed_graphs_before_device_work():
+    """mrl_solve_graph: deps are indices of earlier jobs, every job has a stream of its own, 1..16 jobs."""
+    import ctypes as C
+    cfg = W.config(5, max_size=2)
+    t = B.Target(cfg["target"])
+    descs = [B._lattice_desc(lat) for _, lat, _ in cfg["lattices"]]
+    def call(n, deps=((), (), (0, 1)), streams=(1, 2, 3)):
+        jobs = (B._Job * 17)()
+        for i in range(3):
+            jobs[i].lattice = C.cast(C.pointer(descs[i]), C.c_void_p)
+            jobs[i].n_deps = len(deps[i])
+            for k, d in enumerate(deps[i]):
+                jobs[i].deps[k] = d
+            jobs[i].d_cost = jobs[i].d_argmin = jobs[i].d_scratch = 256      # never dereferenced here
+            jobs[i].scratch_bytes = 0
+            jobs[i].hip_stream = streams[i]
+        out = (C.c_void_p * 17)()
+        rc = B.lib().mrl_solve_graph(t._h, jobs, C.c_uint32(n), out, None)
+        assert all(not h for h in out)
+        return rc, B.lib().mrl_last_error().decode()
+    assert call(0)[0] == B.E_INVAL
+    assert call(17)[0] == B.E_INVAL
+    rc, msg = call(3, deps=((), (1,), (0, 1)))
+    assert rc == B.E_INVAL and "earlier job" in msg
+    rc, msg = call(3, deps=((), (), (0, 2)))
+    assert rc == B.E_INVAL and "earlier job" in msg
+    rc, msg = call(3, streams=(1, 2, 1))
+    assert rc == B.E_INVAL and "share a stream" in msg

@@ -466,3 +466,58 @@ def test_parity_random_lattices(seed):
     _, got, want = compare_config(cfg)
     for label, _, _ in cfg["lattices"]:
         check_compressed_queries(got[label], want[label], 5_000, seed=seed)
+
+
+def test_one_call_per_lattice_gives_the_same_tables_as_the_graph_call():
+    """mrl_solve lattice by lattice (M, E, then F on their finished tables) against the oracle and
+    against mrl_solve_graph, which starts F while M and E are still being compressed: dense tables,
+    counters and both box lists are the same."""
+    B = _binding()
+    cfg = W.config(5, max_size=16)
+    _, graph, want = compare_config(cfg)          # solve_config = one graph call
+    t = B.Target(cfg["target"])
+    lats = {label: lat for label, lat, _ in cfg["lattices"]}
+    one = {"M": B.solve(t, lats["M"]), "E": B.solve(t, lats["E"])}
+    one["F"] = B.solve(t, lats["F"], deps=[one["M"], one["E"]])
+    for label in "MEF":
+        a, b = one[label], graph[label]
+        ca, aa = a.dense()
+        assert np.array_equal(ca, want[label]["cost"]) and np.array_equal(aa, want[label]["argmin"])
+        for which in (0, 1):
+            assert a.boxes(which).tobytes() == b.boxes(which).tobytes()
+        assert (a.stats.n_admissible, a.stats.n_rewrites) == (b.stats.n_admissible, b.stats.n_rewrites)
+
+
+def test_graph_call_failures_leave_no_table():
+    """A job of mrl_solve_graph that fails, before its fill (scratch below the fixed part) or
+    after it, when its dependents already run (scratch that the box lists outgrow): the call ends,
+    reports that job, and hands out no table."""
+    B = _binding()
+    import torch
+    cfg = W.config(5, max_size=16)
+    target, got = B.solve_config(cfg)
+    used = {label: int(got[label].stats.scratch_used) for label in "MEF"}
+    dev = torch.device("cuda", torch.cuda.current_device())
+    def buffers(scratch):
+        out = {}
+        for label, lat, _ in cfg["lattices"]:
+            n = W.n_specs(cfg["target"], lat)
+            out[label] = (torch.empty(8 * n, dtype=torch.uint8, device=dev), torch.empty(2 * n, dtype=torch.uint8, device=dev),
+                          torch.empty(scratch[label], dtype=torch.uint8, device=dev))
+        return out
+    big = {label: B.table_bytes(target, lat)[2] for label, lat, _ in cfg["lattices"]}
+    # E fails before its fill: F, which reads it, is not run
+    with pytest.raises(B.MorelloError) as e:
+        B.solve_lattices(target, cfg["lattices"], buffers=buffers(dict(big, E=4096)))
+    assert e.value.code == B.E_NOMEM and "job 1:" in str(e.value)
+    # M fails in its compression, after F has started on M's dense table
+    with pytest.raises(B.MorelloError) as e:
+        B.solve_lattices(target, cfg["lattices"], buffers=buffers(dict(big, M=used["M"] - 4096)))
+    assert e.value.code == B.E_NOMEM and "job 0:" in str(e.value)
+    # and the same call with enough memory still gives the right tables
+    again = B.solve_lattices(target, cfg["lattices"], buffers=buffers(used))
+    for label in "MEF":
+        ca, aa = again[label].dense()
+        cb, ab = got[label].dense()
+        assert np.array_equal(ca, cb) and np.array_equal(aa, ab)
+        assert again[label].boxes(1).tobytes() == got[label].boxes(1).tobytes()

@@ -430,7 +430,7 @@ struct Aux {
   hipStream_t stream = nullptr;
   std::vector<hipEvent_t> events;
   uint32_t* h_counts = nullptr;     // pinned: counts read back without stalling the other stream
-  hipEvent_t timing[3] = {nullptr, nullptr, nullptr};
+  hipEvent_t timing[4] = {nullptr, nullptr, nullptr, nullptr};   // fill start, fill end, compression start and end
   int device = -1;
   bool busy = false;
 };
@@ -766,7 +766,8 @@ int32_t solve_impl(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_t
   }
   HIP_TRY(hipGetLastError());
   HIP_TRY(hipEventRecord(ev[1], st));
-  if (on_filled) guard.shared = on_filled(tab);
+  if (on_filled) guard.shared = on_filled(tab);        // may wait (host side) for other jobs
+  HIP_TRY(hipEventRecord(ev[3], st));
 
   // ---- compression ----
   const Geo& g = c.geo;
@@ -940,7 +941,7 @@ int32_t solve_impl(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_t
     if (P.bounded) stats->n_admissible = c.n_specs;      // no admissibility test: every Spec is evaluated
     stats->n_levels_run = n_lev;
     HIP_TRY(hipEventElapsedTime(&stats->fill_ms, ev[0], ev[1]));
-    HIP_TRY(hipEventElapsedTime(&stats->compress_ms, ev[1], ev[2]));
+    HIP_TRY(hipEventElapsedTime(&stats->compress_ms, ev[3], ev[2]));
     stats->n_decision_boxes = tab->list_n[0];
     stats->n_cost_boxes = tab->list_n[1];
     stats->scratch_used = needed;

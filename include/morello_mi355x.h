@@ -196,7 +196,8 @@ void mrl_table_destroy(mrl_table* tab);
  * it on the device by an event, and a dep is compressed once the jobs that read it
  * have queued their own fill: its compression overlaps with their work instead of
  * holding it up, and independent jobs overlap as with mrl_solve from several
- * threads.  The last job runs on the calling thread.  jobs, out (n_jobs handles) and stats (n_jobs entries,
+ * threads.  The last job runs on the calling thread.  No two jobs may be the
+ * same lattice (MRL_E_INVAL).  jobs, out (n_jobs handles) and stats (n_jobs entries,
  * optional) are host arrays.  On success every out[j] is a table as from
  * mrl_solve.  On failure the status and message are those of the first job that
  * failed ("job <j>: ..."), no table is left and every out[j] is NULL.  The call

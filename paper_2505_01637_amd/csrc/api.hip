@@ -976,6 +976,15 @@ int32_t mrl_solve_graph(const mrl_target* t, const mrl_job* jobs, uint32_t n_job
     for (uint32_t k = 0; k < j; k++)
       if (jobs[k].hip_stream == jobs[j].hip_stream) return fail(MRL_E_INVAL, "jobs %u and %u share a stream", k, j);
   }
+  // No lattice twice: solves of one (target, lattice) take turns, and a job keeps its turn while
+  // it waits for its readers, so two such jobs and a reader of both would wait for each other.
+  CompiledPtr compiled[MRL_MAX_JOBS];
+  for (uint32_t j = 0; j < n_jobs; j++) {
+    const int32_t rc = get_compiled(t->d, jobs[j].lattice, compiled[j]);
+    if (rc) { char msg[sizeof g_err]; snprintf(msg, sizeof msg, "%s", g_err); return fail(rc, "job %u: %s", j, msg); }
+    for (uint32_t k = 0; k < j; k++)
+      if (compiled[k] == compiled[j]) return fail(MRL_E_INVAL, "jobs %u and %u are the same lattice", k, j);
+  }
   int dev = 0;
   HIP_TRY(hipGetDevice(&dev));
 

@@ -128,3 +128,6 @@ def test_graph_call_refuses_malformed_graphs_before_device_work():
     assert rc == B.E_INVAL and "earlier job" in msg
     rc, msg = call(3, streams=(1, 2, 1))
     assert rc == B.E_INVAL and "share a stream" in msg
+    descs[1] = descs[0]                 # the same lattice twice
+    rc, msg = call(3)
+    assert rc == B.E_INVAL and "same lattice" in msg

@@ -521,3 +521,76 @@ def test_graph_call_failures_leave_no_table():
         cb, ab = got[label].dense()
         assert np.array_equal(ca, cb) and np.array_equal(aa, ab)
         assert again[label].boxes(1).tobytes() == got[label].boxes(1).tobytes()
+
+
+def random_config_more(seed):
+    """Further seeded random cases: (0) a bounded Matmul alone with batch sizes, layout and dtype
+    bits, (1) the serial and the parallel Matmul with dtype bits, (2) coefficients so large that
+    costs come near 2^62 or pass it, (3) the bias-add + ReLU alone, plain or bounded, long size lists."""
+    rng = np.random.default_rng(seed)
+    cfg = random_config(seed)
+    t = cfg["target"]
+    nl = t["n_levels"]
+    variant = int(rng.integers(0, 4))
+
+    def sizes(max_n, hi=13):
+        n = int(rng.integers(1, max_n + 1))
+        rest = sorted(rng.choice(np.arange(2, hi), size=n - 1, replace=False).tolist()) if n > 1 else []
+        return [1] + [int(v) for v in rest]
+
+    def short_bounds():
+        t["capacity_bytes"] = [min(c, 64) if c != W.UNBOUNDED else c for c in t["capacity_bytes"][:nl]] + [0] * (4 - nl)
+
+    lay = [int(rng.random() < 0.4) for _ in range(3)]
+    dt = [int(rng.random() < 0.5), int(rng.random() < 0.5), 0]
+    while sum(lay) + sum(dt) > 4:           # the library takes four layout and dtype bits
+        lay[int(rng.integers(0, 3))] = 0
+    bb = [2 if dt[i] == 0 and rng.random() < 0.3 else 4 for i in range(2)] + [4]
+    if variant == 0:
+        short_bounds()
+        lat = W._lattice(W.KIND_MATMUL_BOUNDED, [sizes(2), sizes(3), sizes(3), sizes(4)], layout=lay + [0, 0],
+                         dtype=dt + [0, 0], base_bytes=bb + [4, 4])
+        lats = [("B", lat, [])]
+    elif variant == 1:
+        lat = W._lattice(W.KIND_MATMUL_ACCUM, [sizes(2), sizes(4), sizes(4), sizes(5)], layout=lay + [0, 0],
+                         dtype=dt + [0, 0], base_bytes=bb + [4, 4])
+        lats = [("M", lat, []), ("P", dict(lat, kind=W.KIND_MATMUL_PARALLEL), ["M"])]
+    elif variant == 2:
+        big = int(rng.choice([1 << 20, 1 << 31, 1 << 40, 1 << 44]))
+        t["microkernels"] = [(k, l, int(c) * big) for k, l, c in t["microkernels"]]
+        t["loop_overhead"] = int(rng.integers(0, 1 << 31))
+        for src in range(1, nl):
+            for dst in range(src):
+                for x in range(2):      # load + store of an accumulated operand must fit 32 bits
+                    if t["load_coef"][src][dst][x]:
+                        t["load_coef"][src][dst][x] = int(rng.integers(1, 1 << 31))
+                    if t["store_coef"][dst][src][x]:
+                        t["store_coef"][dst][src][x] = int(rng.integers(1, 1 << 31))
+        lat = W._lattice(W.KIND_MATMUL_ACCUM, [sizes(2), sizes(4, 200), sizes(4, 200), sizes(5, 200)], layout=lay + [0, 0])
+        lats = [("M", lat, [])]
+    else:
+        b = rng.random() < 0.5
+        if b:
+            short_bounds()
+        lat = W._lattice(W.KIND_BIAS_ADD_RELU_BOUNDED if b else W.KIND_BIAS_ADD_RELU, [[1], sizes(9, 40), [1], sizes(9, 40)],
+                         layout=[int(rng.random() < 0.5), 0, int(rng.random() < 0.5), 0, 0])
+        lats = [("E", lat, [])]
+    return {"name": "random-more-%d-v%d" % (seed, variant), "target": t, "lattices": lats}
+
+
+@pytest.mark.parametrize("seed", list(range(800000, 800032)))
+def test_parity_random_lattices_more_kinds(seed):
+    """random_config_more against the oracle; where a cost passes 2^62 both sides must say so."""
+    B = _binding()
+    cfg = random_config_more(seed)
+    if sum(W.n_specs(cfg["target"], lat) for _, lat, _ in cfg["lattices"]) > 3_000_000:
+        pytest.skip("too large for a quick case")
+    want = O.solve_config(cfg)
+    if any(r["rc"] == -6 for r in want.values()):
+        with pytest.raises(B.MorelloError) as e:
+            B.solve_config(cfg)
+        assert e.value.code == B.E_OVERFLOW
+        return
+    _, got, want = compare_config(cfg)
+    for label, _, _ in cfg["lattices"]:
+        check_compressed_queries(got[label], want[label], 2_000, seed=seed)

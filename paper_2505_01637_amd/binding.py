@@ -333,9 +333,10 @@ _side_streams = {}
 
 
 def _side_stream(dev, i):
-    """The i-th extra stream of a device (default priority), created once."""
+    """The i-th extra stream of a device for the calling thread (default priority), created once."""
+    import threading
     import torch
-    pool = _side_streams.setdefault(dev, [])
+    pool = _side_streams.setdefault((dev, threading.get_ident()), [])
     while len(pool) <= i:
         pool.append(torch.cuda.Stream(device=dev))
     return pool[i]

@@ -657,7 +657,7 @@ int32_t solve_impl(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_t
     return fail(MRL_E_INVAL, "only FUSED and MATMUL_PARALLEL lattices take deps");
   }
 
-  std::lock_guard<std::mutex> solve_lock(c.solve_mu);
+  std::unique_lock<std::mutex> solve_lock(c.solve_mu);      // for the upload image, until the upload has run
 
   const FixedLayout f = fixed_layout(c);
   tab->f = f;
@@ -692,13 +692,15 @@ int32_t solve_impl(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_t
 
   // ---- fill: plan, then one launch (or two) per dependency level ----
   AuxLease lease;
-  rc = get_aux(2 * (size_t)n_lev + 7, lease);
+  rc = get_aux(2 * (size_t)n_lev + 8, lease);
   if (rc) return rc;
   Aux* aux = lease.a;
   hipEvent_t* ev = aux->timing;
   size_t ev_used = 0;
   hipStream_t s2 = aux->stream;
   HIP_TRY(hipEventRecord(ev[0], st));
+  const hipEvent_t uploaded = aux->events[ev_used++];
+  HIP_TRY(hipEventRecord(uploaded, st));
   if (P.bounded) {
     // Memory bounds as coordinates: every Spec is evaluated (no admissibility test, so every cell
     // counts as fitting for the compression); one launch per dependency level of shapes and rank
@@ -766,7 +768,12 @@ int32_t solve_impl(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_t
   }
   HIP_TRY(hipGetLastError());
   HIP_TRY(hipEventRecord(ev[1], st));
-  if (on_filled) guard.shared = on_filled(tab);        // may wait (host side) for other jobs
+  if (on_filled) {
+    // on_filled may wait (host side) for other jobs, which may need this lattice's turn
+    HIP_TRY(hipEventSynchronize(uploaded));
+    solve_lock.unlock();
+    guard.shared = on_filled(tab);
+  }
   HIP_TRY(hipEventRecord(ev[3], st));
 
   // ---- compression ----
@@ -976,8 +983,8 @@ int32_t mrl_solve_graph(const mrl_target* t, const mrl_job* jobs, uint32_t n_job
     for (uint32_t k = 0; k < j; k++)
       if (jobs[k].hip_stream == jobs[j].hip_stream) return fail(MRL_E_INVAL, "jobs %u and %u share a stream", k, j);
   }
-  // No lattice twice: solves of one (target, lattice) take turns, and a job keeps its turn while
-  // it waits for its readers, so two such jobs and a reader of both would wait for each other.
+  // No lattice twice (solves of one (target, lattice) take turns for its upload image: such jobs
+  // would not overlap, and nothing reads two tables of one lattice).
   CompiledPtr compiled[MRL_MAX_JOBS];
   for (uint32_t j = 0; j < n_jobs; j++) {
     const int32_t rc = get_compiled(t->d, jobs[j].lattice, compiled[j]);

@@ -594,3 +594,35 @@ def test_parity_random_lattices_more_kinds(seed):
     _, got, want = compare_config(cfg)
     for label, _, _ in cfg["lattices"]:
         check_compressed_queries(got[label], want[label], 2_000, seed=seed)
+
+
+def test_graph_calls_from_two_threads_on_the_same_lattices():
+    """Two host threads each solve config 5 (small) through mrl_solve_graph, several times, at the
+    same time: the calls take turns per lattice where they must and every result is the oracle's."""
+    import threading
+    import torch
+    B = _binding()
+    cfg = W.config(5, max_size=16)
+    want = O.solve_config(cfg)
+    target = B.Target(cfg["target"])
+    dev = torch.cuda.current_device()
+    errors = []
+
+    def worker(rounds):
+        try:
+            torch.cuda.set_device(dev)
+            with torch.cuda.stream(torch.cuda.Stream(device=dev)):       # the last job's stream: one per thread
+                for _ in range(rounds):
+                    got = B.solve_lattices(target, cfg["lattices"])
+                    for label in "MEF":
+                        cost, arg = got[label].dense()
+                        assert np.array_equal(cost, want[label]["cost"]) and np.array_equal(arg, want[label]["argmin"])
+        except BaseException as e:
+            errors.append(e)
+
+    threads = [threading.Thread(target=worker, args=(6,)) for _ in range(2)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    assert not errors, errors

@@ -167,10 +167,12 @@ class Target:
             pass
 
 
-def geometry(target, lattice):
+def geometry(target, lattice, desc=None):
+    """(extents, number of Specs); desc: the lattice's descriptor if the caller has built it."""
     nd, n = C.c_uint32(), C.c_uint64()
     ext = (C.c_uint32 * MAX_DIMS)()
-    _check(lib().mrl_geometry(target._h, C.byref(_lattice_desc(lattice)), C.byref(nd), ext, C.byref(n)))
+    L = _lattice_desc(lattice) if desc is None else desc
+    _check(lib().mrl_geometry(target._h, C.byref(L), C.byref(nd), ext, C.byref(n)))
     return list(ext[:nd.value]), n.value
 
 
@@ -307,7 +309,7 @@ def solve(target, lattice, deps=(), scratch_bytes=None, stream=None, buffers=Non
     if not torch.cuda.is_available():
         raise RuntimeError("mrl solve needs a GPU: there is no CPU path")
     L = _lattice_desc(lattice)
-    ext, n = geometry(target, lattice)
+    ext, n = geometry(target, lattice, desc=L)
     cb, ab = 8 * n, 2 * n
     if buffers is None:
         sb = table_bytes(target, lattice)[2] if scratch_bytes is None else scratch_bytes
@@ -376,7 +378,7 @@ def solve_lattices(target, lattices, scratch_bytes=None, buffers=None):
     for i, (label, lat, deps) in enumerate(order):
         L = _lattice_desc(lat)
         keep.append(L)
-        ext, n = geometry(target, lat)
+        ext, n = geometry(target, lat, desc=L)
         exts.append(ext)
         if buffers is None:
             sb = table_bytes(target, lat)[2] if scratch_bytes is None else scratch_bytes

@@ -47,6 +47,10 @@ namespace {
 
 constexpr size_t kAlign = 256;
 constexpr uint32_t kQueryChunk = 4096;
+#ifndef MRL_SECOND_ON_CELLS
+#define MRL_SECOND_ON_CELLS 1
+#endif
+constexpr bool kSecondOnCells = MRL_SECOND_ON_CELLS;
 constexpr uint32_t kLookupChunk = 65536;   // points per launch of a lookup in the box lists
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
@@ -75,10 +79,25 @@ struct Compiled {
 
 // Offsets of the fixed part of the scratch buffer.
 struct FixedLayout {
-  size_t counters, params, tiles, level_shapes, shape_class, level_off, mk_entry, list_whole, list_slice, list_wide, list_cnt, fitmap, maskD, maskC, lineD, lineC, prefD, prefC, tile_tmp, tile_tmp2, totals,
+  size_t counters, params, tiles, level_shapes, shape_class, level_off, mk_entry, list_whole, list_slice, list_wide, list_cnt, fitmap, maskD, maskC, mask2D, mask2C, colD, colC, lineD, lineC, prefD, prefC, tile_tmp, tile_tmp2, totals,
       q_idx, q_cost, q_arg, upload_end, end;
   uint32_t n_words;
 };
+
+// Whether the pass on the second merge axis a1 runs on the cells, before the boxes are made: the
+// first axis a0 and a1 have strides of whole mask words, a1 lies outside a0 and has at most 64 steps.
+bool second_on_cells(const Compiled& c, uint32_t* a0_out, uint32_t* a1_out) {
+  const Geo& g = c.geo;
+  uint32_t a0 = 0, a1 = 0, found = 0;
+  for (uint32_t q = 0; q < g.ndim && found < 2; q++) {
+    const uint32_t a = c.merge_order[q];
+    if (g.ext[a] <= 1) continue;
+    if (found++ == 0) a0 = a; else a1 = a;
+  }
+  if (a0_out) *a0_out = a0;
+  if (a1_out) *a1_out = a1;
+  return kSecondOnCells && found == 2 && g.stride[a0] % 64 == 0 && g.stride[a1] % (g.stride[a0] * g.ext[a0]) == 0 && g.ext[a1] <= 64;
+}
 
 FixedLayout fixed_layout(const Compiled& c) {
   FixedLayout f;
@@ -101,6 +120,15 @@ FixedLayout fixed_layout(const Compiled& c) {
   f.fitmap = take((size_t)f.n_words * 8 + 16);
   f.maskD = take((size_t)f.n_words * 8);
   f.maskC = take((size_t)f.n_words * 8);
+  f.mask2D = f.mask2C = f.colD = f.colC = 0;
+  if (second_on_cells(c, nullptr, nullptr)) {
+    uint32_t a1 = 0;
+    second_on_cells(c, nullptr, &a1);
+    f.mask2D = take((size_t)f.n_words * 8);
+    f.mask2C = take((size_t)f.n_words * 8);
+    f.colD = take((size_t)(c.n_specs / c.geo.ext[a1]) * 8);
+    f.colC = take((size_t)(c.n_specs / c.geo.ext[a1]) * 8);
+  }
   {
     // line-major copies of the two masks: one bit per cell, 64-bit words per line of the first merge axis
     uint32_t e0 = c.geo.ext[c.merge_order[0]];
@@ -787,9 +815,21 @@ int32_t solve_impl(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_t
   auto axis_sizes = [&](uint32_t a) -> const uint32_t* { return a < 4 ? (const uint32_t*)((char*)d_P + offsetof(DevParams, sizes) + a * sizeof(uint32_t) * kMaxSizes) : nullptr; };
   unsigned long long* lineL[2] = {(unsigned long long*)(base + f.lineD), (unsigned long long*)(base + f.lineC)};
   launch_head_flags(g, a0, tab->d_cost, tab->d_arg, d_fitmap, axis_sizes(a0), maskL[0], maskL[1], lineL[0], lineL[1], st);
+  uint32_t a1 = 0;
+  const bool on_cells = second_on_cells(c, nullptr, &a1);
+  const unsigned long long* colL[2] = {nullptr, nullptr};
+  if (on_cells) launch_zero_words((unsigned long long*)(base + f.colD), (uint32_t)((f.colC - f.colD) / 8 + c.n_specs / g.ext[a1]), st);
   // the two prefix sums side by side (each is three short kernels): the decisions' on the helper stream
   HIP_TRY(hipEventRecord(aux->events[ev_used], st));
   HIP_TRY(hipStreamWaitEvent(s2, aux->events[ev_used++], 0));
+  if (on_cells) {
+    // the pass on the second merge axis, on the cells: the box heads that remain go to a second mask
+    unsigned long long* m2[2] = {(unsigned long long*)(base + f.mask2D), (unsigned long long*)(base + f.mask2C)};
+    unsigned long long* cl[2] = {(unsigned long long*)(base + f.colD), (unsigned long long*)(base + f.colC)};
+    launch_second_axis(g, a0, a1, false, maskL[0], lineL[0], d_fitmap, tab->d_cost, tab->d_arg, axis_sizes(a1), m2[0], cl[0], s2);
+    launch_second_axis(g, a0, a1, true, maskL[1], lineL[1], d_fitmap, tab->d_cost, tab->d_arg, axis_sizes(a1), m2[1], cl[1], st);
+    for (int w = 0; w < 2; w++) { maskL[w] = m2[w]; colL[w] = cl[w]; }
+  }
   scan_mask_words(maskL[0], f.n_words, (uint32_t*)(base + f.tile_tmp2), prefL[0], d_tot + 0, s2);
   scan_mask_words(maskL[1], f.n_words, tile_tmp, prefL[1], d_tot + 1, st);
   HIP_TRY(hipEventRecord(aux->events[ev_used], s2));
@@ -867,10 +907,12 @@ int32_t solve_impl(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_t
     W.block_linked = (uint32_t*)w;
     W.d_cnt = d_tot + 4 + which * 4;       // [0]: live boxes at the compaction; [2]: the final count
     W.n = (uint32_t)nb;
-    launch_make_boxes(g, a0, maskL[which], prefL[which], lineL[which], W.bcell, W.blen, W.alive, W.pred, stL[which]);
-    if (n_generic) {
+    launch_make_boxes(g, a0, maskL[which], prefL[which], lineL[which], colL[which], a1, W.bcell, W.blen, W.alive, W.pred,
+                      stL[which]);
+    if (on_cells) W.q_next = 1;               // pass_axis[0] = a1 is done
+    if (W.q_next < n_generic) {
       one_pass(which);
-      if (W.n > (1u << 20) && (n_generic > 1 || tail.n)) {
+      if (W.n > (1u << 20) && (W.q_next < n_generic || tail.n)) {
         scan_flags(W.alive, W.n, tileL[which], W.pos, W.d_cnt, stL[which]);
         launch_compact_boxes(W.n, W.alive, W.pos, W.bcell, W.blen, W.cell2, W.len2, W.alive2, stL[which]);
         HIP_TRY(hipMemcpyAsync(aux->h_counts + 2 + which, W.d_cnt, 4, hipMemcpyDeviceToHost, stL[which]));

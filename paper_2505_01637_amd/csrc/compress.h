@@ -44,9 +44,17 @@ void scan_flags(const uint8_t* flags, uint32_t n, uint32_t* tile_tmp, uint32_t* 
 // Live boxes (alive[b]) move to dense arrays: box b becomes box pos[b].
 void launch_compact_boxes(uint32_t n, const uint8_t* alive, const uint32_t* pos, const uint32_t* bcell, const void* blen,
                           uint32_t* cell2, void* len2, uint8_t* alive2, hipStream_t st);
+// The first generic pass (axis a1) done on the cells, for tables whose a0 and a1 have strides of
+// whole mask words with a1 outside a0 and at most 64 steps on a1: runs = the mask of pass 0,
+// mask2 = runs without the heads that this pass folds into the run before them on a1, col = one
+// word per column of cells along a1 (zero before), bit c set where the run at step c was folded.
+void launch_second_axis(const Geo& g, uint32_t a0, uint32_t a1, bool is_cost, const unsigned long long* runs,
+                        const unsigned long long* line, const uint32_t* fitmap, const uint64_t* cost, const uint16_t* arg,
+                        const uint32_t* axis_sizes, unsigned long long* mask2, unsigned long long* col, hipStream_t st);
+// col != nullptr: mask is launch_second_axis's mask2 and every box gets its chain's length on a1.
 void launch_make_boxes(const Geo& g, uint32_t a0, const unsigned long long* mask, const uint32_t* prefix,
-                       const unsigned long long* line, uint32_t* bcell, void* blen, uint8_t* alive, uint8_t* pred,
-                       hipStream_t st);
+                       const unsigned long long* line, const unsigned long long* col, uint32_t a1, uint32_t* bcell,
+                       void* blen, uint8_t* alive, uint8_t* pred, hipStream_t st);
 // One merge pass along axis a.  After a compaction the mask still ranks boxes by their old index:
 // old_alive / remap (the compaction's alive and pos) translate it; nullptr before.
 void launch_axis_pass(const Geo& g, uint32_t a, uint8_t stamp, bool is_cost, uint32_t n_boxes, const uint8_t* old_alive,

@@ -377,6 +377,7 @@ __global__ __launch_bounds__(256) void make_boxes_wave_kernel(Geo g, uint32_t a0
                                                               const unsigned long long* __restrict__ mask,
                                                               const uint32_t* __restrict__ prefix,
                                                               const unsigned long long* __restrict__ line,
+                                                              const unsigned long long* __restrict__ col, uint32_t a1,
                                                               uint32_t* __restrict__ bcell, uint4* __restrict__ blen,
                                                               uint8_t* __restrict__ alive, uint8_t* __restrict__ pred) {
   const uint32_t lane = threadIdx.x & 63u;
@@ -390,9 +391,9 @@ __global__ __launch_bounds__(256) void make_boxes_wave_kernel(Geo g, uint32_t a0
   // kBoxWords words at a time, so that their reads of the line-major mask are in flight together
   unsigned long long todo = __ballot(mv != 0);
   while (todo) {
-    uint32_t id[kBoxWords], cell[kBoxWords], j[kBoxWords], q[kBoxWords];
+    uint32_t id[kBoxWords], cell[kBoxWords], j[kBoxWords], q[kBoxWords], c1[kBoxWords];
     bool head[kBoxWords];
-    unsigned long long lm[kBoxWords];
+    unsigned long long lm[kBoxWords], cw[kBoxWords];
 #pragma unroll
     for (int u = 0; u < kBoxWords; u++) {
       const bool any = todo != 0;
@@ -408,6 +409,13 @@ __global__ __launch_bounds__(256) void make_boxes_wave_kernel(Geo g, uint32_t a0
       id[u] = pf + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
       head[u] = (m >> lane) & 1ull;
       lm[u] = head[u] ? line[(size_t)(j[u] >> 6) * n_lines + q[u]] : 0ull;
+      cw[u] = 0; c1[u] = 0;
+      if (col) {                        // the runs behind this box on a1 that were folded into it
+        const uint32_t s1 = g.stride[a1], e1 = g.ext[a1], se1 = s1 * e1;
+        const uint32_t hi1 = cell0 / se1, rem1 = cell0 - hi1 * se1;
+        c1[u] = rem1 / s1;
+        cw[u] = head[u] ? col[(size_t)hi1 * s1 + (rem1 - c1[u] * s1) + lane] : 0ull;
+      }
     }
 #pragma unroll
     for (int u = 0; u < kBoxWords; u++) {
@@ -425,6 +433,16 @@ __global__ __launch_bounds__(256) void make_boxes_wave_kernel(Geo g, uint32_t a0
         L[1] = (a0 >> 2) == 1 ? lw : L[1];
         L[2] = (a0 >> 2) == 2 ? lw : L[2];
         L[3] = (a0 >> 2) == 3 ? lw : L[3];
+        if (col) {
+          // bit c of the column word: the run at step c was folded into the one before it
+          const unsigned long long above = c1[u] >= 63u ? 0ull : cw[u] >> (c1[u] + 1u);
+          const uint32_t more = (uint32_t)__ffsll((long long)~above) - 1u;
+          const uint32_t add = more << ((a1 & 3u) * 8u);                       // the byte holds 1
+          L[0] += (a1 >> 2) == 0 ? add : 0u;
+          L[1] += (a1 >> 2) == 1 ? add : 0u;
+          L[2] += (a1 >> 2) == 2 ? add : 0u;
+          L[3] += (a1 >> 2) == 3 ? add : 0u;
+        }
         bcell[id[u]] = cell[u];
         blen[id[u]] = make_uint4(L[0], L[1], L[2], L[3]);
         alive[id[u]] = 1;
@@ -432,6 +450,110 @@ __global__ __launch_bounds__(256) void make_boxes_wave_kernel(Geo g, uint32_t a0
       }
     }
   }
+}
+
+// ---------------------------------------------------------------- the second merge axis, on cells
+// The first generic pass would link every run of pass 0 to the run one step further on the second
+// merge axis a1 when both have the same value and the same extent on a0 (they differ in no other
+// extent yet).  For an a1 that lies outside a0, with a stride of whole mask words and at most 64
+// steps, this is decided on the cells before any box exists: a run head whose predecessor on a1
+// heads an equal run loses its flag and sets the bit of its step in the word of its column (the
+// cells that differ only on a1), from which make_boxes reads the length of the chain.  runs = the
+// mask of pass 0, mask2 = the heads of boxes, col = one word per column, zero before.
+constexpr int kSecondWords = 4;
+
+// first = the line's mask word that holds step j
+__device__ __forceinline__ uint32_t run_end(unsigned long long first, const unsigned long long* __restrict__ line,
+                                            uint32_t n_lines, uint32_t e0, uint32_t j, uint32_t q) {
+  unsigned long long w = first & ~((2ull << (j & 63u)) - 1ull);
+  for (uint32_t k = j >> 6;;) {
+    if (w) return k * 64u + (uint32_t)__ffsll((long long)w) - 1u;
+    if (++k * 64u >= e0) return e0;
+    w = line[(size_t)k * n_lines + q];
+  }
+}
+
+template <bool COST>
+__global__ __launch_bounds__(256) void second_axis_kernel(Geo g, uint32_t a0, uint32_t a1, uint32_t n_words, uint32_t wpw,
+                                                          const unsigned long long* __restrict__ runs,
+                                                          const unsigned long long* __restrict__ line,
+                                                          const unsigned long long* __restrict__ fitmap,
+                                                          const uint64_t* __restrict__ cost, const uint16_t* __restrict__ arg,
+                                                          const uint32_t* __restrict__ axis_sizes,
+                                                          unsigned long long* __restrict__ mask2,
+                                                          unsigned long long* __restrict__ col) {
+  const uint32_t lane = threadIdx.x & 63u;
+  const uint32_t w0 = (blockIdx.x * 4u + (threadIdx.x >> 6)) * wpw;
+  if (w0 >= n_words) return;
+  const uint32_t s0 = g.stride[a0], e0 = g.ext[a0], n_lines = g.n / e0, se = s0 * e0;
+  const uint32_t s1 = g.stride[a1], e1 = g.ext[a1], d = s1 >> 6, back = s1 / se * s0, se1 = s1 * e1;
+  const bool mine = lane < wpw && w0 + lane < n_words;
+  const unsigned long long mv = mine ? runs[w0 + lane] : 0ull;
+  unsigned long long out = mv;
+  // kSecondWords words at a time, each stage's reads side by side
+  unsigned long long todo = __ballot(mv != 0);
+  while (todo) {
+    uint32_t t[kSecondWords], w[kSecondWords], c1[kSecondWords];
+    unsigned long long m[kSecondWords], cand[kSecondWords], fc[kSecondWords], fp[kSecondWords];
+#pragma unroll
+    for (int u = 0; u < kSecondWords; u++) {
+      const bool any = todo != 0;
+      t[u] = any ? (uint32_t)__ffsll((long long)todo) - 1u : 0u;
+      todo &= todo - 1;                 // 0 stays 0
+      m[u] = any ? readlane64(mv, t[u]) : 0ull;
+      w[u] = w0 + t[u];
+      c1[u] = (w[u] * 64u / s1) % e1;   // the word's 64 cells share it
+      const bool has = m[u] != 0 && c1[u] > 0;
+      cand[u] = has ? m[u] & runs[w[u] - d] : 0ull;       // the cell before on a1 heads a run as well
+      fc[u] = has ? fitmap[w[u]] : 0ull;
+      fp[u] = has ? fitmap[w[u] - d] : 0ull;
+    }
+    bool me[kSecondWords];
+    uint64_t vc[kSecondWords], vp[kSecondWords];
+#pragma unroll
+    for (int u = 0; u < kSecondWords; u++) {
+      me[u] = (cand[u] >> lane) & 1ull;
+      const uint32_t cell = w[u] * 64u + lane;
+      const bool rc = me[u] && ((fc[u] >> lane) & 1ull), rp = me[u] && ((fp[u] >> lane) & 1ull);
+      if (COST) {
+        vc[u] = rc ? cost[cell] : kInf;
+        vp[u] = rp ? cost[cell - s1] : kInf;
+      } else {
+        vc[u] = rc ? (uint64_t)arg[cell] : (uint64_t)kNone;
+        vp[u] = rp ? (uint64_t)arg[cell - s1] : (uint64_t)kNone;
+      }
+    }
+    bool same[kSecondWords];
+    uint32_t j[kSecondWords], q[kSecondWords];
+    unsigned long long lc[kSecondWords], lp[kSecondWords];
+#pragma unroll
+    for (int u = 0; u < kSecondWords; u++) {
+      if (COST) {
+        const uint32_t z1 = (axis_sizes && c1[u]) ? axis_sizes[c1[u] - 1] : 1u, z2 = axis_sizes ? axis_sizes[c1[u]] : 1u;
+        same[u] = me[u] && norm_equal(vp[u], z1, vc[u], z2);
+      } else {
+        same[u] = me[u] && vp[u] == vc[u];
+      }
+      const uint32_t cell0 = w[u] * 64u, hi = cell0 / se, rem = cell0 - hi * se;
+      j[u] = rem / s0;
+      q[u] = hi * s0 + (rem - j[u] * s0) + lane;
+      const size_t at = (size_t)(j[u] >> 6) * n_lines + q[u];
+      lc[u] = same[u] ? line[at] : 0ull;
+      lp[u] = same[u] ? line[at - back] : 0ull;
+    }
+#pragma unroll
+    for (int u = 0; u < kSecondWords; u++) {
+      if (same[u])        // equal extents on a0: both runs end at the same step
+        same[u] = run_end(lc[u], line, n_lines, e0, j[u], q[u]) == run_end(lp[u], line, n_lines, e0, j[u], q[u] - back);
+      if (same[u]) {
+        const uint32_t cell0 = w[u] * 64u, hi1 = cell0 / se1, rem1 = cell0 - hi1 * se1;
+        atomicOr(&col[(size_t)hi1 * s1 + (rem1 - c1[u] * s1) + lane], 1ull << c1[u]);
+      }
+      const unsigned long long gone = __ballot(same[u]);
+      if (m[u] && lane == t[u]) out = m[u] & ~gone;
+    }
+  }
+  if (mine) mask2[w0 + lane] = out;
 }
 
 // ---------------------------------------------------------------- pass on axis a
@@ -527,14 +649,28 @@ void launch_head_flags(const Geo& g, uint32_t a0, const uint64_t* cost, const ui
                        maskD, maskC);
 }
 
+void launch_second_axis(const Geo& g, uint32_t a0, uint32_t a1, bool is_cost, const unsigned long long* runs,
+                        const unsigned long long* line, const uint32_t* fitmap, const uint64_t* cost, const uint16_t* arg,
+                        const uint32_t* axis_sizes, unsigned long long* mask2, unsigned long long* col, hipStream_t st) {
+  const uint32_t n_words = g.n / 64;
+  const uint32_t wpw = words_per_wave(n_words);
+  const dim3 grid((n_words + 4 * wpw - 1) / (4 * wpw));
+  if (is_cost)
+    hipLaunchKernelGGL(second_axis_kernel<true>, grid, dim3(256), 0, st, g, a0, a1, n_words, wpw, runs, line,
+                       (const unsigned long long*)fitmap, cost, arg, axis_sizes, mask2, col);
+  else
+    hipLaunchKernelGGL(second_axis_kernel<false>, grid, dim3(256), 0, st, g, a0, a1, n_words, wpw, runs, line,
+                       (const unsigned long long*)fitmap, cost, arg, axis_sizes, mask2, col);
+}
+
 void launch_make_boxes(const Geo& g, uint32_t a0, const unsigned long long* mask, const uint32_t* prefix,
-                       const unsigned long long* line, uint32_t* bcell, void* blen, uint8_t* alive, uint8_t* pred,
-                       hipStream_t st) {
+                       const unsigned long long* line, const unsigned long long* col, uint32_t a1, uint32_t* bcell,
+                       void* blen, uint8_t* alive, uint8_t* pred, hipStream_t st) {
   if (g.stride[a0] % 64 == 0) {
     const uint32_t n_words = g.n / 64;
     const uint32_t wpw = words_per_wave(n_words);
     hipLaunchKernelGGL(make_boxes_wave_kernel, dim3((n_words + 4 * wpw - 1) / (4 * wpw)), dim3(256), 0, st, g, a0, n_words, wpw, mask, prefix,
-                       line, bcell, (uint4*)blen, alive, pred);
+                       line, col, a1, bcell, (uint4*)blen, alive, pred);
   } else {
     hipLaunchKernelGGL(make_boxes_kernel, dim3((g.n + 256 * kCellWords - 1) / (256 * kCellWords)), dim3(256), 0, st, g, a0, mask, prefix, bcell,
                        (uint4*)blen, alive, pred);

@@ -912,7 +912,8 @@ int32_t solve_impl(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_t
     if (on_cells) W.q_next = 1;               // pass_axis[0] = a1 is done
     if (W.q_next < n_generic) {
       one_pass(which);
-      if (W.n > (1u << 20) && (W.q_next < n_generic || tail.n)) {
+      // (not after the pass on the cells: it leaves no dead boxes, and a compaction after the next pass costs more than it saves)
+      if (!on_cells && W.n > (1u << 20) && (W.q_next < n_generic || tail.n)) {
         scan_flags(W.alive, W.n, tileL[which], W.pos, W.d_cnt, stL[which]);
         launch_compact_boxes(W.n, W.alive, W.pos, W.bcell, W.blen, W.cell2, W.len2, W.alive2, stL[which]);
         HIP_TRY(hipMemcpyAsync(aux->h_counts + 2 + which, W.d_cnt, 4, hipMemcpyDeviceToHost, stL[which]));

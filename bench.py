@@ -38,8 +38,8 @@ def measured_traffic(config, table, n_launch):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=5)
     ap.add_argument("--seed", type=int, default=None)
     ap.add_argument("--scratch-gb", type=float, default=8.0)

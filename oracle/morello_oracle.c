@@ -32,6 +32,7 @@
  * bounds of Sections 2.2 and 2.4.4, carried as coordinates (expand(), parts
  * B and D).
  */
+#define _GNU_SOURCE             /* qsort_r */
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -530,35 +531,39 @@ int orc_cost_values(const orc_target* T, const orc_lattice* L, const uint64_t* c
 
 typedef struct { uint16_t lo[ORC_MAXD], hi[ORC_MAXD]; uint64_t v0, v1; } orc_box;
 
-static int g_axis, g_ndim;
+/* What a comparison needs besides the two boxes (handed to qsort_r, so that the merge keeps no
+ * state between calls). */
+typedef struct { int axis, ndim; } sort_key;
 
 /* Group key: value, then lo/hi on every axis but the merge axis; inside a
  * group order by lo on the merge axis. */
-static int cmp_group(const void* pa, const void* pb) {
+static int cmp_group(const void* pa, const void* pb, void* pk) {
   const orc_box* a = (const orc_box*)pa; const orc_box* b = (const orc_box*)pb;
+  const sort_key* k = (const sort_key*)pk;
   if (a->v0 != b->v0) return a->v0 < b->v0 ? -1 : 1;
   if (a->v1 != b->v1) return a->v1 < b->v1 ? -1 : 1;
-  for (int j = 0; j < g_ndim; j++) {
-    if (j == g_axis) continue;
+  for (int j = 0; j < k->ndim; j++) {
+    if (j == k->axis) continue;
     if (a->lo[j] != b->lo[j]) return a->lo[j] < b->lo[j] ? -1 : 1;
     if (a->hi[j] != b->hi[j]) return a->hi[j] < b->hi[j] ? -1 : 1;
   }
-  if (a->lo[g_axis] != b->lo[g_axis]) return a->lo[g_axis] < b->lo[g_axis] ? -1 : 1;
+  if (a->lo[k->axis] != b->lo[k->axis]) return a->lo[k->axis] < b->lo[k->axis] ? -1 : 1;
   return 0;
 }
 
-static int same_group(const orc_box* a, const orc_box* b) {
+static int same_group(const orc_box* a, const orc_box* b, const sort_key* k) {
   if (a->v0 != b->v0 || a->v1 != b->v1) return 0;
-  for (int j = 0; j < g_ndim; j++) {
-    if (j == g_axis) continue;
+  for (int j = 0; j < k->ndim; j++) {
+    if (j == k->axis) continue;
     if (a->lo[j] != b->lo[j] || a->hi[j] != b->hi[j]) return 0;
   }
   return 1;
 }
 
-static int cmp_lo(const void* pa, const void* pb) {
+static int cmp_lo(const void* pa, const void* pb, void* pk) {
   const orc_box* a = (const orc_box*)pa; const orc_box* b = (const orc_box*)pb;
-  for (int j = 0; j < g_ndim; j++)
+  const sort_key* k = (const sort_key*)pk;
+  for (int j = 0; j < k->ndim; j++)
     if (a->lo[j] != b->lo[j]) return a->lo[j] < b->lo[j] ? -1 : 1;
   return 0;
 }
@@ -567,11 +572,11 @@ static int cmp_lo(const void* pa, const void* pb) {
  * in which each box starts right after the previous one ends. */
 static uint64_t merge_axis(orc_box* b, uint64_t n, int axis, int ndim) {
   if (n == 0) return 0;
-  g_axis = axis; g_ndim = ndim;
-  qsort(b, n, sizeof *b, cmp_group);
+  sort_key key = {axis, ndim};
+  qsort_r(b, n, sizeof *b, cmp_group, &key);
   uint64_t w = 0;
   for (uint64_t r = 1; r < n; r++) {
-    if (same_group(&b[w], &b[r]) && b[r].lo[axis] == b[w].hi[axis] + 1) b[w].hi[axis] = b[r].hi[axis];
+    if (same_group(&b[w], &b[r], &key) && b[r].lo[axis] == b[w].hi[axis] + 1) b[w].hi[axis] = b[r].hi[axis];
     else b[++w] = b[r];
   }
   return w + 1;
@@ -619,8 +624,8 @@ int64_t orc_merge(uint32_t ndim, const uint32_t* ext, const uint32_t* merge_orde
     nb = n;
   }
   for (uint32_t q = first; q < n_merge; q++) nb = merge_axis(b, nb, (int)merge_order[q], (int)ndim);
-  g_ndim = (int)ndim;
-  qsort(b, nb, sizeof *b, cmp_lo);
+  sort_key by_lo = {-1, (int)ndim};
+  qsort_r(b, nb, sizeof *b, cmp_lo, &by_lo);
   *out = b;
   return (int64_t)nb;
 }

@@ -258,3 +258,63 @@ def solve_config(cfg, goals=None):
         out[label] = solve(cfg["target"], lat, deps=d, goals=goals)
         out[label]["lattice"] = lat
     return out
+
+
+# ---------------------------------------------------------------------------
+# The oracle under AddressSanitizer and UndefinedBehaviorSanitizer: a stand-alone
+# executable (sanitize_driver.c, which includes the oracle's source) reads a
+# problem from a file and writes every result to another.
+
+_DRIVER_SRC = os.path.join(_HERE, "sanitize_driver.c")
+
+
+def build_sanitized(workdir):
+    exe = os.path.join(workdir, "oracle_sanitized")
+    subprocess.check_call(["gcc", "-O1", "-g", "-Wall", "-Wextra", "-fsanitize=address,undefined",
+                           "-fno-sanitize-recover=all", "-fno-omit-frame-pointer", "-o", exe, _DRIVER_SRC])
+    return exe
+
+
+def run_sanitized(exe, cfg, workdir):
+    """Solve and compress every lattice of `cfg` in the sanitized executable.  Returns
+    {label: dict(rc, cost, argmin, n_admissible, n_rewrites, decision_boxes, cost_boxes)}."""
+    labels = [label for label, _, _ in cfg["lattices"]]
+    blob = bytearray(bytes(_target(cfg["target"])))
+    blob += np.uint32(len(labels)).tobytes()
+    for label, lat, deps in cfg["lattices"]:
+        blob += np.uint32(lat["kind"]).tobytes()
+        blob += np.array([len(s) for s in lat["sizes"]], dtype=np.uint32).tobytes()
+        for s in lat["sizes"]:
+            blob += np.array(s, dtype=np.uint32).tobytes()
+        for key in ("layout_coord", "dtype_coord", "base_dtype_bytes"):
+            blob += np.array(lat[key], dtype=np.uint8).tobytes()
+        dep = [labels.index(d) for d in deps] + [-1, -1]
+        blob += np.array(dep[:2], dtype=np.int32).tobytes()
+    src, dst = os.path.join(workdir, "problem.bin"), os.path.join(workdir, "result.bin")
+    with open(src, "wb") as f:
+        f.write(bytes(blob))
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0:verify_asan_link_order=0",
+               UBSAN_OPTIONS="halt_on_error=1:print_stacktrace=1")
+    done = subprocess.run([exe, src, dst], env=env, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if done.returncode != 0:
+        raise RuntimeError("sanitized oracle failed (status %d):\n%s" % (done.returncode, done.stdout[-4000:]))
+    raw = open(dst, "rb").read()
+    out, at = {}, 0
+
+    def take(dtype, count):
+        nonlocal at
+        a = np.frombuffer(raw, dtype=dtype, count=count, offset=at)
+        at += a.nbytes
+        return a
+
+    for label in labels:
+        rc = int(take(np.int32, 1)[0])
+        n = int(take(np.uint64, 1)[0])
+        r = {"rc": rc, "cost": take(np.uint64, n), "argmin": take(np.uint16, n)}
+        r["n_admissible"], r["n_rewrites"] = (int(v) for v in take(np.uint64, 2))
+        for key in ("decision_boxes", "cost_boxes"):
+            nb = int(take(np.uint64, 1)[0])
+            r[key] = take(BOX_DTYPE, nb)
+        out[label] = r
+    assert at == len(raw)
+    return out

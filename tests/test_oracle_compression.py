@@ -120,3 +120,21 @@ def test_point_lookup_in_boxes_equals_dense_table(number, max_size, label):
         broken["hi"][i, 3] -= 1
         with pytest.raises(ValueError):
             O.query_boxes(lat, broken, cst, np.stack(np.unravel_index(np.arange(n), ext), axis=1)[: 20000])
+
+
+@pytest.mark.parametrize("number,max_size", [(4, 8), (3, 64), (5, 4)])
+def test_first_pass_by_lines_equals_the_unit_box_pass_on_solved_tables(number, max_size):
+    """orc_merge's default first pass walks the lines of the first merge axis instead of sorting
+    one unit box per cell.  On the lists that matter, the decisions and the volume-normalised
+    costs (reduced fractions, v1 != 0) of solved tables, both forms must give the same boxes."""
+    cfg = W.config(number, max_size=max_size)
+    res = O.solve_config(cfg)
+    for label, lat, _ in cfg["lattices"]:
+        ext, mo, _ = O.geometry(cfg["target"], lat)
+        v0, v1 = O.cost_values(cfg["target"], lat, res[label]["cost"])
+        assert (v1 != 0).any() and len(np.unique(v1)) > 2
+        for a0, a1 in ((v0, v1), (res[label]["argmin"].astype(np.uint64), np.zeros(len(v0), dtype=np.uint64))):
+            by_lines = O.merge(ext, mo, a0, a1, first_pass_by_lines=True)
+            by_cells = O.merge(ext, mo, a0, a1, first_pass_by_lines=False)
+            assert by_lines.tobytes() == by_cells.tobytes()
+            assert len(by_lines) < len(a0)

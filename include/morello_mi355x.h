@@ -218,7 +218,9 @@ int32_t mrl_solve_graph(const mrl_target* t, const mrl_job* jobs, uint32_t n_job
 
 /* ---------------------------------------------------------------------------
  * Query (Section 4: a Spec that the memo table already holds is answered from
- * it).  specs, cost_out, rewrite_out: host arrays of n. */
+ * it).  specs, cost_out, rewrite_out: host arrays of n.  Calls on one table from
+ * several host threads take turns (they stage through the table's scratch buffer
+ * and stream); so do those of mrl_schedule, which asks through this call. */
 typedef struct { uint32_t x[MRL_MAX_DIMS]; } mrl_coord;
 int32_t mrl_query(const mrl_table* tab, const mrl_coord* specs, size_t n,
                   uint64_t* cost_out, uint16_t* rewrite_out);

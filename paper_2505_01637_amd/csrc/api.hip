@@ -520,6 +520,7 @@ struct mrl_table {
   mutable BoxIndex index[2];
   mutable char* lookup_buf = nullptr;
   mutable std::mutex lookup_mu;
+  mutable std::mutex query_mu;      // mrl_query stages through one area of the scratch buffer and the table's stream
   ~mrl_table() {
     for (auto& ix : index) if (ix.nodes) (void)hipFree(ix.nodes);
     if (lookup_buf) (void)hipFree(lookup_buf);
@@ -716,13 +717,20 @@ int32_t solve_impl(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_t
     memcpy(c.staging + f.mk_entry, c.mk_entry.data(), c.mk_entry.size());
   }
   memcpy(c.staging + f.params, &P, sizeof P);
-  HIP_TRY(hipMemcpyAsync(base, c.staging, f.upload_end, hipMemcpyHostToDevice, st));
-
-  // ---- fill: plan, then one launch (or two) per dependency level ----
   AuxLease lease;
   rc = get_aux(2 * (size_t)n_lev + 8, lease);
   if (rc) return rc;
   Aux* aux = lease.a;
+  // Whichever way this function is left from here on, both streams have drained before the turn
+  // for the upload image, the helper stream with its events and pinned counters, and (on
+  // failure) the table object are given up: work queued on the streams may still use all of these.
+  struct Drain {
+    hipStream_t a, b;
+    ~Drain() { (void)hipStreamSynchronize(a); (void)hipStreamSynchronize(b); }
+  } drain{st, aux->stream};
+  HIP_TRY(hipMemcpyAsync(base, c.staging, f.upload_end, hipMemcpyHostToDevice, st));
+
+  // ---- fill: plan, then one launch (or two) per dependency level ----
   hipEvent_t* ev = aux->timing;
   size_t ev_used = 0;
   hipStream_t s2 = aux->stream;
@@ -938,26 +946,16 @@ int32_t solve_impl(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_t
     HIP_TRY(hipMemcpyAsync(aux->h_counts + which, W.d_cnt + 2, 4, hipMemcpyDeviceToHost, stL[which]));
     HIP_TRY(hipEventRecord(aux->events[ev_used + which], stL[which]));
   }
-  // the final lists, whichever list is through first (its stream would idle behind the other's count)
+  // the final lists: the decisions' first (the shorter list, as a rule through first); the host
+  // sleeps until a list's count has arrived
   const hipEvent_t counted[2] = {aux->events[ev_used], aux->events[ev_used + 1]};
   ev_used += 2;
-  bool emitted[2] = {false, false};
-  for (int left = 2; left > 0;) {
-    int which = -1;
-    for (int w = 1; w >= 0 && which < 0; w--)
-      if (!emitted[w]) {
-        const hipError_t q = hipEventQuery(counted[w]);
-        if (q == hipSuccess) which = w;
-        else if (q != hipErrorNotReady) return fail(MRL_E_HIP, "hipEventQuery: %s", hipGetErrorString(q));
-      }
-    if (which < 0) continue;
-    emitted[which] = true;
-    left--;
+  for (int which = 0; which < 2; which++) {
+    const int left = 1 - which;
+    HIP_TRY(hipEventSynchronize(counted[which]));
     const uint64_t nf = aux->h_counts[which];
     const size_t fb = final_bytes(nf);
     if (front + fb > (size_t)(work_lo - base)) {
-      HIP_TRY(hipStreamSynchronize(stL[0]));
-      HIP_TRY(hipStreamSynchronize(stL[1]));
       return fail(MRL_E_NOMEM, "scratch buffer too small: %zu bytes given, %zu needed", scratch_bytes,
                   front + fb + (left ? final_bytes(nbL[1 - which]) : 0) + wbL[0] + wbL[1]);
     }
@@ -1161,6 +1159,7 @@ int32_t mrl_query(const mrl_table* tab, const mrl_coord* specs, size_t n, uint64
   const Geo& g = tab->cp->geo;
   std::vector<uint64_t> idx(std::min<size_t>(n, kQueryChunk));
   char* base = tab->scratch;
+  std::lock_guard<std::mutex> lock(tab->query_mu);
   for (size_t done = 0; done < n; done += kQueryChunk) {
     const uint32_t m = (uint32_t)std::min<size_t>(kQueryChunk, n - done);
     for (uint32_t i = 0; i < m; i++) {

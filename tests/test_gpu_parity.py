@@ -622,9 +622,10 @@ def test_graph_calls_from_two_threads_on_the_same_lattices():
         except BaseException as e:
             errors.append(e)
 
-    threads = [threading.Thread(target=worker, args=(6,)) for _ in range(2)]
+    threads = [threading.Thread(target=worker, args=(6,), daemon=True) for _ in range(2)]
     for th in threads:
         th.start()
     for th in threads:
-        th.join()
+        th.join(timeout=120)       # a circular wait between the two calls must fail the test, not hang it
+    assert not any(th.is_alive() for th in threads), "the two graph calls wait for each other"
     assert not errors, errors

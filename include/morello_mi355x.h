@@ -225,6 +225,22 @@ typedef struct { uint32_t x[MRL_MAX_DIMS]; } mrl_coord;
 int32_t mrl_query(const mrl_table* tab, const mrl_coord* specs, size_t n,
                   uint64_t* cost_out, uint16_t* rewrite_out);
 
+/* mrl_query for callers that cannot allocate: tight serving loops, harnesses
+ * that forbid hipMalloc (and host allocation) once they are set up.  Same
+ * arguments, answers and errors as mrl_query, but nothing is allocated, on the
+ * device or on the host: the indices and answers are staged through an array of
+ * MRL_NOALLOC_MAX_QUERIES * 18 bytes that the library holds in device memory of
+ * every GPU it runs on, from load until the process ends, instead of through the
+ * table's scratch buffer.  n must be at most MRL_NOALLOC_MAX_QUERIES
+ * (MRL_E_INVAL else).  Every call on a GPU uses that GPU's one array and
+ * overwrites what the call before left there; calls from several host threads of
+ * one process take turns for it inside the library (work of another origin that
+ * used the array while a call runs would race with it).  The table's device
+ * buffers must be on the current device. */
+enum { MRL_NOALLOC_MAX_QUERIES = 4096 };
+int32_t mrl_query_noalloc(const mrl_table* tab, const mrl_coord* specs, size_t n,
+                          uint64_t* cost_out, uint16_t* rewrite_out);
+
 /* Rewrite ids, ascending = tie-break priority:
  *   [0, n_mk)                       select(microkernel j)
  *   then ((operand*(n_levels-1) + dst)*2 + transposed)*2 + convert   Moves

@@ -15,11 +15,12 @@ LIB_PATH = os.path.join(_HERE, "libmorello_mi355x.so")
 INF = (1 << 64) - 1
 NONE = 0xFFFF
 MAX_DIMS = 16
+NOALLOC_MAX_QUERIES = 4096
 
 OK, E_INVAL, E_NOMEM, E_HIP, E_RANGE, E_BUFSZ, E_OVERFLOW = 0, -1, -2, -3, -4, -5, -6
 
 EXPORTS = ["mrl_target_create", "mrl_target_destroy", "mrl_geometry", "mrl_table_bytes", "mrl_solve", "mrl_solve_graph",
-           "mrl_table_destroy", "mrl_query", "mrl_query_compressed", "mrl_rewrite_decode", "mrl_coord_of_spec",
+           "mrl_table_destroy", "mrl_query", "mrl_query_noalloc", "mrl_query_compressed", "mrl_rewrite_decode", "mrl_coord_of_spec",
            "mrl_emit_compressed", "mrl_schedule", "mrl_copy_dense", "mrl_last_error"]
 
 
@@ -203,16 +204,17 @@ class Table:
         except Exception:
             pass
 
-    def query(self, coords, compressed=False):
+    def query(self, coords, compressed=False, noalloc=False):
         """(cost, rewrite id) of the Specs at `coords`; compressed=True answers from the two box
-        lists alone (mrl_query_compressed) instead of the dense table."""
+        lists alone (mrl_query_compressed) instead of the dense table; noalloc=True asks through
+        mrl_query_noalloc (at most NOALLOC_MAX_QUERIES coordinates)."""
         coords = np.ascontiguousarray(coords, dtype=np.uint32).reshape(-1, len(self.extents))
         n = len(coords)
         buf = np.zeros((n, MAX_DIMS), dtype=np.uint32)
         buf[:, :coords.shape[1]] = coords
         cost = np.empty(n, dtype=np.uint64)
         rw = np.empty(n, dtype=np.uint16)
-        fn = lib().mrl_query_compressed if compressed else lib().mrl_query
+        fn = lib().mrl_query_compressed if compressed else lib().mrl_query_noalloc if noalloc else lib().mrl_query
         _check(fn(self._h, buf.ctypes.data_as(C.POINTER(_Coord)), C.c_size_t(n),
                   cost.ctypes.data_as(C.POINTER(C.c_uint64)), rw.ctypes.data_as(C.POINTER(C.c_uint16))))
         return cost, rw

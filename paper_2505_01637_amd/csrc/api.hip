@@ -1184,6 +1184,62 @@ int32_t mrl_query(const mrl_table* tab, const mrl_coord* specs, size_t n, uint64
   });
 }
 
+// Staging of mrl_query_noalloc: linear indices in, costs and rewrite ids out.  One copy per GPU,
+// held until the process ends; `scratch` itself is only a host-side name for it (not a device
+// address): its address on the current device comes from hipGetSymbolAddress, once per device.
+namespace {
+struct NoAllocStaging {
+  uint64_t idx[MRL_NOALLOC_MAX_QUERIES];
+  uint64_t cost[MRL_NOALLOC_MAX_QUERIES];
+  uint16_t arg[MRL_NOALLOC_MAX_QUERIES];
+};
+constexpr int kMaxDevices = 64;
+std::mutex g_noalloc_mu;                       // calls that use the array take turns
+void* g_noalloc_ptr[kMaxDevices] = {};         // the array's address per device, under g_noalloc_mu
+}  // namespace
+static __device__ __align__(256) unsigned char scratch[sizeof(NoAllocStaging)];
+
+int32_t mrl_query_noalloc(const mrl_table* tab, const mrl_coord* specs, size_t n, uint64_t* cost_out, uint16_t* rewrite_out) {
+  return guarded([&]() -> int32_t {
+  if (!tab || (n && (!specs || !cost_out || !rewrite_out))) return fail(MRL_E_INVAL, "NULL argument");
+  if (n > MRL_NOALLOC_MAX_QUERIES)
+    return fail(MRL_E_INVAL, "mrl_query_noalloc takes at most %d Specs per call, %zu given", (int)MRL_NOALLOC_MAX_QUERIES, n);
+  if (n == 0) return MRL_OK;
+  const Geo& g = tab->cp->geo;
+  uint64_t idx[MRL_NOALLOC_MAX_QUERIES];       // on the stack: nothing is allocated, on the host either
+  for (size_t i = 0; i < n; i++) {
+    uint64_t x = 0;
+    for (uint32_t a = 0; a < g.ndim; a++) {
+      const uint32_t v = specs[i].x[a];
+      if (v >= g.ext[a]) return fail(MRL_E_RANGE, "spec %zu: coordinate %u = %u outside [0, %u)", i, a, v, g.ext[a]);
+      x += (uint64_t)v * g.stride[a];
+    }
+    idx[i] = x;
+  }
+  int dev = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(MRL_E_INVAL, "device %d: at most %d devices", dev, kMaxDevices);
+  std::lock_guard<std::mutex> lock(g_noalloc_mu);
+  if (!g_noalloc_ptr[dev]) {
+    void* p = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return fail(MRL_E_HIP, "hipGetSymbolAddress gave no address");
+    g_noalloc_ptr[dev] = p;
+  }
+  NoAllocStaging* d = (NoAllocStaging*)g_noalloc_ptr[dev];
+  // the previous call's contents are simply overwritten: the kernel reads idx[0, n) and writes
+  // cost[0, n), arg[0, n), and only those come back
+  const uint32_t m = (uint32_t)n;
+  HIP_TRY(hipMemcpyAsync(d->idx, idx, n * 8, hipMemcpyHostToDevice, tab->stream));
+  launch_gather(d->idx, m, tab->d_cost, tab->d_arg, d->cost, d->arg, tab->stream);
+  HIP_TRY(hipGetLastError());
+  HIP_TRY(hipMemcpyAsync(cost_out, d->cost, n * 8, hipMemcpyDeviceToHost, tab->stream));
+  HIP_TRY(hipMemcpyAsync(rewrite_out, d->arg, n * 2, hipMemcpyDeviceToHost, tab->stream));
+  HIP_TRY(hipStreamSynchronize(tab->stream));
+  return MRL_OK;
+  });
+}
+
 int32_t mrl_rewrite_decode(const mrl_table* tab, uint16_t id, mrl_rewrite* out) {
   return guarded([&]() -> int32_t {
   if (!tab || !out) return fail(MRL_E_INVAL, "NULL argument");

@@ -160,6 +160,9 @@ typedef struct {
   float fill_ms, compress_ms;                 /* device time, HIP events on the given stream   */
   uint64_t n_decision_boxes, n_cost_boxes;
   uint64_t scratch_used;                      /* bytes of d_scratch actually needed            */
+  float prefill_ms;                           /* the part of fill_ms before the first dependency
+                                                 level: work lists and the (MRL_INF, MRL_NONE)
+                                                 written over the whole table; 0 for BOUNDED kinds */
 } mrl_stats;
 
 /* Sizes of the device buffers mrl_solve needs.  scratch_bytes is sufficient for

@@ -61,7 +61,7 @@ class Stats(C.Structure):
     _fields_ = [("n_specs", C.c_uint64), ("n_admissible", C.c_uint64), ("n_rewrites", C.c_uint64),
                 ("n_levels_run", C.c_uint32), ("fill_ms", C.c_float), ("compress_ms", C.c_float),
                 ("n_decision_boxes", C.c_uint64), ("n_cost_boxes", C.c_uint64),
-                ("scratch_used", C.c_uint64)]
+                ("scratch_used", C.c_uint64), ("prefill_ms", C.c_float)]
 
     def as_dict(self):
         return {k: getattr(self, k) for k, _ in self._fields_}

@@ -458,7 +458,7 @@ struct Aux {
   hipStream_t stream = nullptr;
   std::vector<hipEvent_t> events;
   uint32_t* h_counts = nullptr;     // pinned: counts read back without stalling the other stream
-  hipEvent_t timing[4] = {nullptr, nullptr, nullptr, nullptr};   // fill start, fill end, compression start and end
+  hipEvent_t timing[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};   // fill start, fill end, compression end and start, plan + pre-fill end
   int device = -1;
   bool busy = false;
 };
@@ -735,6 +735,7 @@ int32_t solve_impl(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_t
   size_t ev_used = 0;
   hipStream_t s2 = aux->stream;
   HIP_TRY(hipEventRecord(ev[0], st));
+  bool prefill_timed = false;
   const hipEvent_t uploaded = aux->events[ev_used++];
   HIP_TRY(hipEventRecord(uploaded, st));
   if (P.bounded) {
@@ -781,6 +782,8 @@ int32_t solve_impl(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_t
     launch_fill_ones(tab->d_cost, c.n_specs * 8, st);
     launch_fill_ones(tab->d_arg, c.n_specs * 2, st);
   }
+  HIP_TRY(hipEventRecord(ev[4], st));
+  prefill_timed = true;
   HIP_TRY(hipEventSynchronize(counts_ready));
   for (uint32_t l = 0; l < n_lev; l++) {
     const uint32_t first = c.level_off[l];
@@ -990,6 +993,7 @@ int32_t solve_impl(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_t
     stats->n_levels_run = n_lev;
     HIP_TRY(hipEventElapsedTime(&stats->fill_ms, ev[0], ev[1]));
     HIP_TRY(hipEventElapsedTime(&stats->compress_ms, ev[3], ev[2]));
+    if (prefill_timed) HIP_TRY(hipEventElapsedTime(&stats->prefill_ms, ev[0], ev[4]));
     stats->n_decision_boxes = tab->list_n[0];
     stats->n_cost_boxes = tab->list_n[1];
     stats->scratch_used = needed;

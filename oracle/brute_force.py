@@ -10,7 +10,7 @@ be checked against each other on tiny lattices.
     loop          trips * c(body) + s
     parallel loop ceil(trips / threads) * c(body) + s_parallel
     pipeline      sum of the children (+ the intermediate's initialisation)
-    alloc-binding move cost + c(body)
+    alloc-binding move cost + c(children): the body, and where Moves are Specs the load and store
     microkernel   k_p
 * `optimum(...)` = the minimum of c over all programs, and the lowest rewrite
   id among the first rewrites that reach it.
@@ -22,19 +22,22 @@ from collections import namedtuple
 
 M, E, F, P = 0, 1, 2, 3      # P: a Matmul that may use parallel loops; M is serial-only
 BD, BE, BF = 4, 5, 6          # M, E, F whose Specs carry per-level memory bounds (Sections 2.2, 2.4.4)
+V, MV = 7, 8                  # V: Move Specs (Section 2.2); MV: a Matmul whose Moves are Move Specs
 BOUNDED = (BD, BE, BF)
-MATMULS = (M, P, BD)
+MATMULS = (M, P, BD, MV)
 
 
 def base_kind(kind):
-    """The operator of a kind: M for the Matmuls, E, F."""
-    return M if kind in MATMULS else E if kind in (E, BE) else F
+    """The operator of a kind: M for the Matmuls, E, F, V."""
+    return M if kind in MATMULS else E if kind in (E, BE) else V if kind == V else F
 FMA, BCAST, BF16DOT, S_ADDRELU, V_ADDRELU = 0, 1, 2, 3, 4
+S_MOVE, V_MOVE, V_MOVE_ALIGNED = 5, 6, 7
 
 # dims = (b, m, k, n) actual sizes; levels per operand (F: 5th = intermediate);
 # layouts / bf16 per operand (0 where the lattice has no such coordinate)
 # limits (kind BD): bytes a program may still allocate per level, None = unbounded level
-Spec = namedtuple("Spec", "kind dims levels layouts bf16 limits", defaults=((),))
+# contig / aligned (kind V): per tensor (source, destination) the abstract values of Section 2.4.3
+Spec = namedtuple("Spec", "kind dims levels layouts bf16 limits contig aligned", defaults=((), (), ()))
 
 
 def operand_numel(spec, i):
@@ -43,6 +46,8 @@ def operand_numel(spec, i):
         return (b * m * k, b * k * n, b * m * n)[i]
     if base_kind(spec.kind) == E:
         return (m * n, n, m * n)[i]
+    if spec.kind == V:
+        return m * n
     return (m * k, k * n, n, m * n, m * n)[i]
 
 
@@ -56,8 +61,9 @@ def operand_mode(kind, i):
 
 
 def fits(target, spec):
-    if spec.kind in BOUNDED:
-        return True          # the bounds decide at each allocation, not the operands' footprint
+    if spec.kind in BOUNDED or spec.kind == V:
+        return True          # the bounds decide at each allocation, not the operands' footprint;
+                             # the two tensors of a Move exist already
     used = [0] * target["n_levels"]
     nops = 4 if spec.kind == F else 3
     for i in range(nops):
@@ -90,7 +96,35 @@ def microkernel_reps(target, lattice, spec, j):
         ok = (base_kind(spec.kind) == E and m == 1 and n % lanes == 0 and tuple(lv[:3]) == (1, 1, 1)
               and ly[0] == 0 and ly[2] == 0)
         return n // lanes if ok else 0
+    if kind == S_MOVE:
+        ok = spec.kind == V and (m, n) == (1, 1) and not (bf[1] and not bf[0])
+        return 1 if ok else 0
+    if kind in (V_MOVE, V_MOVE_ALIGNED):
+        ok = (spec.kind == V and m == 1 and n % lanes == 0
+              and ((lv[0] == 1 and lv[1] > 1) or (lv[1] == 1 and lv[0] > 1))
+              and ly[0] == 0 and ly[1] == 0 and bf[0] == bf[1]
+              and spec.contig[0] >= 1 and spec.contig[1] >= 1
+              and (kind == V_MOVE or (spec.aligned[0] and spec.aligned[1])))
+        return n // lanes if ok else 0
     return 0
+
+
+def tiled_tensor(target, spec, t, rows2, cols2):
+    """(contiguousness, aligned) of tensor t of a Move Spec after cutting a rows2 x cols2 tile out
+    of it (Section 2.4.3)."""
+    rows, cols = spec.dims[1], spec.dims[3]
+    col_major = spec.layouts[t]
+    inner, inner2, outer2 = (rows, rows2, cols2) if col_major else (cols, cols2, rows2)
+    e = 2 if spec.bf16[t] else 4
+    line = target["line_bytes"]
+    contig = spec.contig[t] if inner2 == inner else min(spec.contig[t], 1)
+    aligned = int(bool(spec.aligned[t]) and spec.contig[t] == 2 and (inner2 * e) % line == 0
+                  and (outer2 * inner2 * e) % line == 0)
+    return contig, aligned
+
+
+def cache_lines(target, elems, nbytes):
+    return -(-(elems * nbytes) // target["line_bytes"])
 
 
 def rewrites(target, lattices, spec):
@@ -98,7 +132,7 @@ def rewrites(target, lattices, spec):
     applicable rewrite of an admissible Spec, ids ascending."""
     lattice = lattices[spec.kind]
     nl = target["n_levels"]
-    nops = 4 if base_kind(spec.kind) == F else 3
+    nops = 4 if base_kind(spec.kind) == F else 2 if spec.kind == V else 3
     nmk = len(target["microkernels"])
     maxs = max(len(s) for s in lattice["sizes"])
     move_base = nmk
@@ -107,7 +141,7 @@ def rewrites(target, lattices, spec):
         reps = microkernel_reps(target, lattice, spec, j)
         if reps:
             yield j, ("mk", target["microkernels"][j][2] * reps), []
-    for i in range(nops):
+    for i in range(0 if spec.kind == V else nops):
         mode = operand_mode(spec.kind, i)
         src = spec.levels[i]
         for dst in range(src):
@@ -116,6 +150,29 @@ def rewrites(target, lattices, spec):
                     if x and not lattice["layout_coord"][i]:
                         continue
                     if cv and not (lattice["dtype_coord"][i] and spec.bf16[i] and mode == "r"):
+                        continue
+                    if spec.kind == MV:
+                        # Section 2, Memory Movement: load Move Spec (unless only written), body, store
+                        # Move Spec (if written); Section 3: m(src) + m(dest) on top of the children
+                        b_, m_, k_, n_ = spec.dims
+                        rows, cols = ((m_, k_), (k_, n_), (m_, n_))[i]
+                        y0, y1 = spec.layouts[i], spec.layouts[i] ^ x
+                        f0, f1 = spec.bf16[i], 0 if cv else spec.bf16[i]
+                        top = dict(kind=V, dims=(1, rows, 1, cols), limits=(), contig=(2, 2), aligned=(1, 1))
+                        kids = []
+                        if "r" in mode:
+                            kids.append(Spec(levels=(src, dst), layouts=(y0, y1), bf16=(f0, f1), **top))
+                        lv = list(spec.levels); lv[i] = dst
+                        ly = list(spec.layouts); ly[i] = y1
+                        bf = list(spec.bf16); bf[i] = f1
+                        kids.append(spec._replace(levels=tuple(lv), layouts=tuple(ly), bf16=tuple(bf)))
+                        if "w" in mode:
+                            kids.append(Spec(levels=(dst, src), layouts=(y1, y0), bf16=(f1, f0), **top))
+                        w = target["level_weight"]
+                        fixed = (cache_lines(target, rows * cols, 2 if f0 else 4) * w[src]
+                                 + cache_lines(target, rows * cols, 2 if f1 else 4) * w[dst])
+                        rid = move_base + ((i * (nl - 1) + dst) * 2 + x) * 2 + cv
+                        yield rid, ("alloc", fixed), kids
                         continue
                     coef = 0
                     if "r" in mode:
@@ -147,15 +204,19 @@ def rewrites(target, lattices, spec):
                     rid = move_base + ((i * (nl - 1) + dst) * 2 + x) * 2 + cv
                     yield rid, ("alloc", coef * operand_numel(spec, i)), [child]
     for d in range(4):
-        if base_kind(spec.kind) in (E, F) and d in (0, 2):
+        if base_kind(spec.kind) in (E, F, V) and d in (0, 2):
             continue
         cur = spec.dims[d]
         for j, t in enumerate(lattice["sizes"][d]):
             if t < cur and cur % t == 0:
                 dims = list(spec.dims); dims[d] = t
+                child = spec._replace(dims=tuple(dims))
+                if spec.kind == V:
+                    pairs = [tiled_tensor(target, spec, ts, dims[1], dims[3]) for ts in (0, 1)]
+                    child = child._replace(contig=tuple(p[0] for p in pairs), aligned=tuple(p[1] for p in pairs))
                 yield (tile_base + d * maxs + j,
                        ("loop", cur // t, target["loop_overhead"]),
-                       [spec._replace(dims=tuple(dims))])
+                       [child])
     if spec.kind == P:
         # the body of a parallel loop is serial-only: the same Spec in the serial lattice
         for d in (0, 1, 3):
@@ -196,10 +257,15 @@ def programs(target, lattices, spec):
         elif len(children) == 1:
             for _, sub in programs(target, lattices, children[0]):
                 yield rid, node + (sub,)
-        else:
+        elif len(children) == 2:
             for _, pa in programs(target, lattices, children[0]):
                 for _, pb in programs(target, lattices, children[1]):
                     yield rid, node + (pa, pb)
+        else:
+            for _, pa in programs(target, lattices, children[0]):
+                for _, pb in programs(target, lattices, children[1]):
+                    for _, pc in programs(target, lattices, children[2]):
+                        yield rid, node + (pa, pb, pc)
 
 
 def c(p):
@@ -212,7 +278,7 @@ def c(p):
         trips, threads, sync = p[1], p[2], p[3]
         return -(-trips // threads) * c(p[4]) + sync
     if tag == "alloc":
-        return p[1] + c(p[2])
+        return p[1] + sum(c(q) for q in p[2:])
     if tag == "pipeline":
         return p[1] + c(p[2]) + c(p[3])
     raise ValueError(tag)

@@ -31,6 +31,13 @@
  * 2 with bounds) replace the admissibility test by the per-level memory
  * bounds of Sections 2.2 and 2.4.4, carried as coordinates (expand(), parts
  * B and D).
+ * Kind 7 is the lattice of Move Specs (Section 2.2: loads, stores, packing and
+ * casts are Specs of their own, implemented by loops over move microkernels
+ * such as VectorMove, Section 2), with the contiguousness and alignment
+ * abstract values of Section 2.4.3 as coordinates; kind 8 is the Matmul
+ * whose Moves are those Specs: an alloc-binding costs m(src) + m(dest)
+ * (Section 3, in cache lines) plus its children, the load and store Move
+ * Specs among them (Section 2, Memory Movement).
  */
 #define _GNU_SOURCE             /* qsort_r */
 #include <stdint.h>
@@ -43,8 +50,11 @@
 
 enum { ORC_MAXL = 4, ORC_MAXOPS = 5, ORC_MAXD = 16, ORC_MAXMK = 8 };
 enum { MK_SCALAR_FMA = 0, MK_BCAST_VEC_MULADD = 1, MK_BF16_DOT = 2,
-       MK_SCALAR_ADDRELU = 3, MK_VEC_ADDRELU = 4 };
-enum { KIND_M = 0, KIND_E = 1, KIND_F = 2, KIND_P = 3, KIND_B = 4, KIND_BE = 5, KIND_BF = 6 };
+       MK_SCALAR_ADDRELU = 3, MK_VEC_ADDRELU = 4,
+       MK_SCALAR_MOVE = 5, MK_VECTOR_MOVE = 6, MK_VECTOR_MOVE_ALIGNED = 7 };
+enum { KIND_M = 0, KIND_E = 1, KIND_F = 2, KIND_P = 3, KIND_B = 4, KIND_BE = 5, KIND_BF = 6,
+       KIND_V = 7,    /* Move Specs */
+       KIND_MV = 8 }; /* a Matmul whose Moves are Move Specs of a kind 7 table */
 enum { ACC_READ = 0, ACC_RMW = 1, ACC_WRITE = 2 };
 
 typedef struct {
@@ -61,6 +71,8 @@ typedef struct {
   uint64_t mk_cost[ORC_MAXMK];
   uint32_t threads;                            /* hardware threads a parallel loop spreads over */
   uint32_t sync_cost;                          /* the constant s of a parallel loop */
+  uint32_t level_weight[ORC_MAXL];             /* weight_level of m(t), Section 3 (kind 8) */
+  uint32_t line_bytes;                         /* cache line: unit of lines(t) and of alignment (kinds 7, 8) */
 } orc_target;
 
 typedef struct {
@@ -80,6 +92,9 @@ typedef struct {
   uint8_t bf16[ORC_MAXOPS];     /* 0 f32, 1 bf16 */
   uint8_t limit[ORC_MAXL];      /* kind B: per bounded level, index of the memory bound: 0 -> 0 bytes,
                                    q -> 2^(q-1) bytes */
+  uint8_t contig[2];            /* kind V, per tensor (source, destination): number of inner physical
+                                   dimensions whose values are adjacent in memory, 0..2 (Section 2.4.3) */
+  uint8_t aligned[2];           /* kind V: 1 = the tensor starts at a multiple of the cache line */
 } spec_t;
 
 typedef struct ctx {
@@ -97,6 +112,8 @@ typedef struct ctx {
   int parallel;                 /* kind P: a Matmul whose serial-only flag is off */
   int bounded;                  /* kinds 4..6: the Specs carry per-level memory bounds */
   int lim_axis[ORC_MAXL];       /* coordinate axis of level l's bound, -1 if the level is unbounded */
+  int moves;                    /* kind 8: Moves are Move Specs, looked up in depM (a kind V table) */
+  int abs_axis;                 /* kind V: first of the four axes contig(src), aligned(src), contig(dst), aligned(dst); -1 else */
   uint64_t n_rewrites, n_admissible;
   int overflow;
   const struct ctx* depM;
@@ -111,15 +128,18 @@ typedef struct ctx {
 static int ctx_init(ctx* c, const orc_target* T, const orc_lattice* L) {
   memset(c, 0, sizeof *c);
   c->T = T; c->L = L; c->kind = (int)L->kind;
-  if (c->kind < 0 || c->kind > 6) return -1;
-  if (c->kind >= KIND_B) { c->kind -= KIND_B; c->bounded = 1; }   /* kinds 4, 5, 6: M, E, F with memory bounds */
+  if (c->kind < 0 || c->kind > KIND_MV) return -1;
+  c->abs_axis = -1;
+  if (c->kind == KIND_MV) { c->kind = KIND_M; c->moves = 1; }     /* same operator, operands and coordinates as kind M */
+  if (c->kind >= KIND_B && c->kind <= KIND_BF) { c->kind -= KIND_B; c->bounded = 1; }   /* kinds 4, 5, 6: M, E, F with memory bounds */
   if (c->kind == KIND_P) {      /* same operator, operands and coordinates as kind M */
     c->kind = KIND_M; c->parallel = 1;
     if (T->threads < 1) return -1;
   }
   if (T->n_levels < 1 || T->n_levels > ORC_MAXL) return -1;
-  c->nops = c->kind == KIND_F ? 4 : 3;
-  c->nlv = c->kind == KIND_F ? 5 : 3;
+  c->nops = c->kind == KIND_F ? 4 : c->kind == KIND_V ? 2 : 3;
+  c->nlv = c->kind == KIND_F ? 5 : c->kind == KIND_V ? 2 : 3;
+  if ((c->kind == KIND_V || c->moves) && T->line_bytes < 1) return -1;
   int d = 0;
   c->maxs = 0;
   for (int a = 0; a < 4; a++) {
@@ -130,7 +150,8 @@ static int ctx_init(ctx* c, const orc_target* T, const orc_lattice* L) {
     if (L->n_sizes[a] > c->maxs) c->maxs = L->n_sizes[a];
   }
   if (c->kind != KIND_M && L->n_sizes[0] != 1) return -1;   /* no batch on E, F */
-  if (c->kind == KIND_E && L->n_sizes[2] != 1) return -1;   /* E has no k */
+  if ((c->kind == KIND_E || c->kind == KIND_V) && L->n_sizes[2] != 1) return -1;   /* E and V have no k */
+  if (c->moves && L->n_sizes[0] != 1) return -1;            /* operands of a kind 8 Matmul are two-dimensional */
   for (int i = 0; i < c->nlv; i++) c->ext[d++] = T->n_levels;
   /* Memory bounds (Section 2.2, field 5; Section 4.1: limits are powers of two): one axis per
    * level with a finite capacity; the values are 0, 1, 2, 4, ... up to the capacity. */
@@ -143,12 +164,16 @@ static int ctx_init(ctx* c, const orc_target* T, const orc_lattice* L) {
       if (nq > 255) return -1;
       c->lim_axis[l] = d; c->ext[d++] = nq;
     }
+  if (c->kind == KIND_V) {      /* Section 2.4.3: the abstract values are part of a tensor specification */
+    c->abs_axis = d;
+    c->ext[d++] = 3; c->ext[d++] = 2; c->ext[d++] = 3; c->ext[d++] = 2;
+  }
   for (int i = 0; i < ORC_MAXOPS; i++) { c->lay_axis[i] = -1; c->dt_axis[i] = -1; }
   for (int i = 0; i < c->nops; i++)
     if (L->layout_coord[i]) { c->lay_axis[i] = d; c->ext[d++] = 2; }
   for (int i = 0; i < c->nops; i++)
     if (L->dtype_coord[i]) {
-      if (c->kind != KIND_M || i == 2) return -1;           /* inputs of a Matmul only */
+      if (!(c->kind == KIND_V || (c->kind == KIND_M && i != 2))) return -1;   /* inputs of a Matmul, tensors of a Move */
       c->dt_axis[i] = d; c->ext[d++] = 2;
     }
   c->ndim = d;
@@ -174,6 +199,9 @@ static uint64_t spec_index(const ctx* c, const spec_t* s) {
   }
   for (int l = 0; l < ORC_MAXL; l++)
     if (c->lim_axis[l] >= 0) x += s->limit[l] * c->stride[c->lim_axis[l]];
+  if (c->abs_axis >= 0)
+    for (int t = 0; t < 2; t++)
+      x += s->contig[t] * c->stride[c->abs_axis + 2 * t] + s->aligned[t] * c->stride[c->abs_axis + 2 * t + 1];
   return x;
 }
 
@@ -190,6 +218,11 @@ static void spec_of_index(const ctx* c, uint64_t x, spec_t* s) {
   }
   for (int l = 0; l < ORC_MAXL; l++)
     if (c->lim_axis[l] >= 0) s->limit[l] = (uint8_t)coord[c->lim_axis[l]];
+  if (c->abs_axis >= 0)
+    for (int t = 0; t < 2; t++) {
+      s->contig[t] = (uint8_t)coord[c->abs_axis + 2 * t];
+      s->aligned[t] = (uint8_t)coord[c->abs_axis + 2 * t + 1];
+    }
 }
 
 /* ------------------------------------------------------------------ */
@@ -206,6 +239,7 @@ static uint64_t numel(const ctx* c, const spec_t* s, int op) {
   switch (c->kind) {
     case KIND_M: return op == 0 ? b * m * k : op == 1 ? b * k * n : b * m * n;
     case KIND_E: return op == 1 ? n : m * n;
+    case KIND_V: return m * n;                                                    /* source and destination: rows x cols */
     default:     return op == 0 ? m * k : op == 1 ? k * n : op == 2 ? n : m * n; /* 3 = out, 4 = mid */
   }
 }
@@ -220,6 +254,7 @@ static int access_of(const ctx* c, int op) {
  * operands; kind F also counts its intermediate). */
 static int admissible(const ctx* c, const spec_t* s) {
   if (c->bounded) return 1;     /* the bounds, not the operands' footprint, limit what a Spec may do */
+  if (c->kind == KIND_V) return 1;   /* both tensors of a Move exist already: whoever placed them answered for their size */
   for (uint32_t l = 0; l < c->T->n_levels; l++) {
     unsigned __int128 bytes = 0;
     for (int i = 0; i < c->nops; i++)
@@ -278,8 +313,47 @@ static uint64_t mk_reps(const ctx* c, const spec_t* s, int j) {
       if (lv[0] != 1 || lv[1] != 1 || lv[2] != 1) return 0;
       if (ly[0] != 0 || ly[2] != 0) return 0;
       return n / lanes;
+    /* Move microkernels (Section 2: select(VectorMove), a vector load or store).  m = rows,
+     * n = columns of the moved tensor; operand 0 is the source, 1 the destination. */
+    case MK_SCALAR_MOVE:                 /* one element, between any two places; converts if the types differ */
+      if (c->kind != KIND_V) return 0;
+      if (m != 1 || n != 1) return 0;
+      if (!bf[0] && bf[1]) return 0;     /* no narrowing */
+      return 1;
+    case MK_VECTOR_MOVE:
+    case MK_VECTOR_MOVE_ALIGNED:         /* one row of whole vectors between the vector registers (level 1) and a slower level */
+      if (c->kind != KIND_V) return 0;
+      if (m != 1 || n % lanes != 0) return 0;
+      if (!((lv[0] == 1 && lv[1] > 1) || (lv[1] == 1 && lv[0] > 1))) return 0;
+      if (ly[0] != 0 || ly[1] != 0) return 0;               /* the row's values are the inner dimension */
+      if (bf[0] != bf[1]) return 0;                         /* no conversion */
+      if (s->contig[0] < 1 || s->contig[1] < 1) return 0;   /* ... and adjacent in memory */
+      if (c->T->mk_kind[j] == MK_VECTOR_MOVE_ALIGNED && !(s->aligned[0] && s->aligned[1])) return 0;
+      return n / lanes;
     default: return 0;
   }
+}
+
+/* Section 2.4.3, for a tile of r2 x c2 cut out of tensor t (0 source, 1 destination) of a Move
+ * Spec of r x c: contiguousness counts the inner physical dimensions whose values are adjacent;
+ * cutting the inner dimension leaves only the inner one adjacent.  A tile is known to be aligned
+ * only if the tensor was aligned and contiguous and every suffix of the tile's physical
+ * dimensions is a whole number of cache lines. */
+static void tile_tensor(const ctx* c, const spec_t* s, int t, uint64_t r, uint64_t col, uint64_t r2, uint64_t c2,
+                        uint8_t* contig, uint8_t* aligned) {
+  uint64_t inner = s->layout[t] ? r : col, inner2 = s->layout[t] ? r2 : c2, outer2 = s->layout[t] ? c2 : r2;
+  uint64_t e = s->bf16[t] ? 2 : 4, line = c->T->line_bytes;
+  *contig = inner2 == inner ? s->contig[t] : (s->contig[t] < 1 ? s->contig[t] : 1);
+  *aligned = s->aligned[t] && s->contig[t] == 2 && (inner2 * e) % line == 0 && (outer2 * inner2 * e) % line == 0;
+}
+
+/* Section 3: m(t) = lines(t) * weight of t's level * (2 if t is not contiguous, else 1), for a
+ * tensor of `elems` elements of `bytes` bytes that is contiguous and aligned (the operands of the
+ * Matmul lattices carry no contiguousness or alignment coordinate: they are taken as fresh). */
+static unsigned __int128 m_of(const ctx* c, uint64_t elems, uint32_t bytes, uint32_t level) {
+  unsigned __int128 b = (unsigned __int128)elems * bytes;
+  unsigned __int128 lines = (b + c->T->line_bytes - 1) / c->T->line_bytes;
+  return lines * c->T->level_weight[level];
 }
 
 static uint64_t solve(ctx* c, const spec_t* s);
@@ -303,8 +377,8 @@ static void expand(ctx* c, const spec_t* s, uint64_t* best_out, uint16_t* arg_ou
   }
 
   /* B. move an operand to a strictly faster level (alloc-binding: the move's
-   * own cost plus the cost of the body Spec). */
-  for (int i = 0; i < c->nops; i++) {
+   * own cost plus the cost of the body Spec).  A Move Spec has no such rewrite. */
+  for (int i = 0; i < (c->kind == KIND_V ? 0 : c->nops); i++) {
     int acc = access_of(c, i);
     uint32_t src = s->level[i];
     for (uint32_t dst = 0; dst + 1 < NL; dst++)
@@ -313,14 +387,44 @@ static void expand(ctx* c, const spec_t* s, uint64_t* best_out, uint16_t* arg_ou
           if (dst >= src) continue;
           if (x && c->lay_axis[i] < 0) continue;
           if (cv && !(c->dt_axis[i] >= 0 && s->bf16[i] && acc == ACC_READ)) continue;
-          uint64_t coef = 0;
-          if (acc != ACC_WRITE) { if (!T->load_coef[src][dst][x]) continue; coef += T->load_coef[src][dst][x]; }
-          if (acc != ACC_READ) { if (!T->store_coef[dst][src][x]) continue; coef += T->store_coef[dst][src][x]; }
-          if (cv) coef += T->convert_coef;
           spec_t sub = *s;
           sub.level[i] = (uint8_t)dst;
           sub.layout[i] ^= (uint8_t)x;
           if (cv) sub.bf16[i] = 0;
+          uint32_t id = c->move_base + (((uint32_t)i * (NL - 1) + dst) * 2 + (uint32_t)x) * 2 + (uint32_t)cv;
+          if (c->moves) {
+            /* Section 2, Memory Movement: the alloc-binding holds a load Move Spec (unless the
+             * operand is only written), the body, and a store Move Spec (if it is written);
+             * Section 3: it costs m(src) + m(dest) plus its children. */
+            uint64_t d4[4]; dims_of(c, s, d4);
+            uint64_t rows = i == 1 ? d4[2] : d4[1], cols = i == 0 ? d4[2] : d4[3];   /* lhs m x k, rhs k x n, out m x n */
+            spec_t mv; memset(&mv, 0, sizeof mv);
+            mv.si[1] = i == 1 ? s->si[2] : s->si[1];
+            mv.si[3] = i == 0 ? s->si[2] : s->si[3];
+            mv.contig[0] = mv.contig[1] = 2; mv.aligned[0] = mv.aligned[1] = 1;
+            uint64_t c_load = 0, c_store = 0;
+            if (acc != ACC_WRITE) {
+              mv.level[0] = (uint8_t)src; mv.level[1] = (uint8_t)dst;
+              mv.layout[0] = s->layout[i]; mv.layout[1] = sub.layout[i];
+              mv.bf16[0] = s->bf16[i]; mv.bf16[1] = sub.bf16[i];
+              c_load = c->depM->cost[spec_index(c->depM, &mv)];
+            }
+            if (acc != ACC_READ) {
+              mv.level[0] = (uint8_t)dst; mv.level[1] = (uint8_t)src;
+              mv.layout[0] = sub.layout[i]; mv.layout[1] = s->layout[i];
+              mv.bf16[0] = sub.bf16[i]; mv.bf16[1] = s->bf16[i];
+              c_store = c->depM->cost[spec_index(c->depM, &mv)];
+            }
+            unsigned __int128 fixed = m_of(c, rows * cols, s->bf16[i] ? 2 : 4, src) + m_of(c, rows * cols, sub.bf16[i] ? 2 : 4, dst);
+            uint64_t cand = ORC_INF;
+            if (c_load != ORC_INF && c_store != ORC_INF) cand = affine(c, 1, solve(c, &sub), fixed + c_load + c_store);
+            consider(c, cand, id, &best, &arg);
+            continue;
+          }
+          uint64_t coef = 0;
+          if (acc != ACC_WRITE) { if (!T->load_coef[src][dst][x]) continue; coef += T->load_coef[src][dst][x]; }
+          if (acc != ACC_READ) { if (!T->store_coef[dst][src][x]) continue; coef += T->store_coef[dst][src][x]; }
+          if (cv) coef += T->convert_coef;
           if (c->bounded && c->lim_axis[dst] >= 0) {
             /* Section 2.4.4: the Move allocates the operand's buffer in dst; the body may use
              * what is left of dst's bound, snapped down to a power of two (or zero). */
@@ -332,7 +436,6 @@ static void expand(ctx* c, const spec_t* s, uint64_t* best_out, uint16_t* arg_ou
             while (q < 64 && ((uint64_t)1 << q) <= left) q++;      /* left = 0 -> 0; else floor(log2) + 1 */
             sub.limit[dst] = q;
           }
-          uint32_t id = c->move_base + (((uint32_t)i * (NL - 1) + dst) * 2 + (uint32_t)x) * 2 + (uint32_t)cv;
           uint64_t cand = affine(c, 1, solve(c, &sub), (unsigned __int128)coef * numel(c, s, i));
           consider(c, cand, id, &best, &arg);
         }
@@ -348,6 +451,11 @@ static void expand(ctx* c, const spec_t* s, uint64_t* best_out, uint16_t* arg_ou
       if (cur % t) continue;
       spec_t sub = *s;
       sub.si[d] = j;
+      if (c->kind == KIND_V) {
+        uint64_t d4[4]; dims_of(c, s, d4);
+        uint64_t r2 = d == 1 ? t : d4[1], c2 = d == 3 ? t : d4[3];
+        for (int ts = 0; ts < 2; ts++) tile_tensor(c, s, ts, d4[1], d4[3], r2, c2, &sub.contig[ts], &sub.aligned[ts]);
+      }
       uint64_t cand = affine(c, cur / t, solve(c, &sub), T->loop_overhead);
       consider(c, cand, c->tile_base + (uint32_t)d * c->maxs + j, &best, &arg);
     }
@@ -459,6 +567,20 @@ int orc_solve(const orc_target* T, const orc_lattice* L,
     cm.cost = (uint64_t*)costM; ce.cost = (uint64_t*)costE;
     c.depM = &cm; c.depE = &ce;
   }
+  if (c.moves) {                /* the Move Specs: a kind V table over the same sizes */
+    if (!LM || !costM) return -1;
+    if (ctx_init(&cm, T, LM)) return -1;
+    if (cm.kind != KIND_V) return -1;
+    /* every operand's shape must be in the Move lattice: rows from m and k, columns from k and n */
+    if (!same_sizes(L, 1, LM, 1) || !same_sizes(L, 2, LM, 1) || !same_sizes(L, 2, LM, 3) || !same_sizes(L, 3, LM, 3)) return -1;
+    int any_lay = 0, any_dt = 0;
+    for (int i = 0; i < 3; i++) { any_lay |= c.lay_axis[i] >= 0; any_dt |= c.dt_axis[i] >= 0 || L->base_dtype_bytes[i] == 2; }
+    if (any_lay && (cm.lay_axis[0] < 0 || cm.lay_axis[1] < 0)) return -1;
+    if (any_dt && (cm.dt_axis[0] < 0 || cm.dt_axis[1] < 0)) return -1;
+    if (cm.dt_axis[0] < 0 && (LM->base_dtype_bytes[0] != 4 || LM->base_dtype_bytes[1] != 4)) return -1;
+    cm.cost = (uint64_t*)costM;
+    c.depM = &cm;
+  }
   if (c.parallel) {             /* the serial-only Specs: the kind M table of the same lattice */
     if (!LM || !costM) return -1;
     if (ctx_init(&cm, T, LM)) return -1;
@@ -497,6 +619,7 @@ int orc_geometry(const orc_target* T, const orc_lattice* L, uint32_t* ndim,
   int nlay = 0, nlim = 0;
   for (int i = 0; i < c.nops; i++) nlay += c.lay_axis[i] >= 0;
   for (int l = 0; l < ORC_MAXL; l++) nlim += c.lim_axis[l] >= 0;
+  if (c.abs_axis >= 0) nlim = 4;   /* a Move lattice's abstract-value axes stand where the memory bounds do */
   int q = 0, first = 4 + c.nlv;
   for (int a = first + nlim - 1; a >= first; a--) merge_order[q++] = (uint32_t)a;                /* memory bounds */
   for (int a = 3; a >= 0; a--) merge_order[q++] = (uint32_t)a;                                   /* n, k, m, b */

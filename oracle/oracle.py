@@ -38,7 +38,9 @@ class _Target(C.Structure):
                 ("mk_lanes", C.c_uint32 * 8),
                 ("mk_cost", C.c_uint64 * 8),
                 ("threads", C.c_uint32),
-                ("sync_cost", C.c_uint32)]
+                ("sync_cost", C.c_uint32),
+                ("level_weight", C.c_uint32 * 4),
+                ("line_bytes", C.c_uint32)]
 
 
 class _Lattice(C.Structure):
@@ -91,6 +93,9 @@ def _target(t):
         s.mk_kind[j], s.mk_lanes[j], s.mk_cost[j] = kind, lanes, cost
     s.threads = t.get("threads", 1)
     s.sync_cost = t.get("sync_cost", 0)
+    for l in range(4):
+        s.level_weight[l] = t.get("level_weight", [0, 0, 0, 0])[l]
+    s.line_bytes = t.get("line_bytes", 0)
     return s
 
 
@@ -132,7 +137,8 @@ def geometry(target, lattice):
 
 def solve(target, lattice, deps=None, goals=None):
     """Fill the table.  deps = ((latticeM, costM), (latticeE, costE)) for kind F,
-    ((latticeM, costM),) for kind P (the serial-only table of the same lattice).
+    ((latticeM, costM),) for kind P (the serial-only table of the same lattice) and for
+    kind 8 (the table of Move Specs).
     Returns dict(cost u64[N], argmin u16[N], n_admissible, n_rewrites, rc)."""
     T, L = _target(target), _lattice(lattice)
     ext, _, _ = geometry(target, lattice)

@@ -21,6 +21,9 @@ MK_BCAST_VEC_MULADD = 1
 MK_BF16_DOT = 2
 MK_SCALAR_ADDRELU = 3
 MK_VEC_ADDRELU = 4
+MK_SCALAR_MOVE = 5            # Move Spec of one element (converts bf16 -> f32 if the types differ)
+MK_VECTOR_MOVE = 6            # Move Spec of one row of whole vectors between level 1 and a slower level
+MK_VECTOR_MOVE_ALIGNED = 7    # the same, both tensors aligned
 
 # spec kinds
 KIND_MATMUL_ACCUM = 0
@@ -31,6 +34,8 @@ KIND_MATMUL_BOUNDED = 4       # a Matmul whose Specs carry a memory bound per le
 KIND_BIAS_ADD_RELU_BOUNDED = 5        # the same for the bias-add + ReLU
 KIND_FUSED_BOUNDED = 6                # and for the fused Spec (reads the two bounded tables)
 BOUNDED_KINDS = (KIND_MATMUL_BOUNDED, KIND_BIAS_ADD_RELU_BOUNDED, KIND_FUSED_BOUNDED)
+KIND_MOVE = 7                 # Move Specs: source and destination tensor of rows x cols
+KIND_MATMUL_MOVES = 8         # a Matmul whose Moves are Move Specs; reads a KIND_MOVE table
 
 MAX_LEVELS = 4
 MAX_OPERANDS = 5
@@ -66,6 +71,8 @@ def _empty_target(n_levels, capacities):
         "microkernels": [],   # list of (kind, lanes, cost); order = rewrite-id order
         "threads": 1,         # hardware threads of a parallel loop
         "sync_cost": 0,       # constant of a parallel loop
+        "level_weight": [0] * MAX_LEVELS,   # per-level weight of a Move's cache lines (KIND_MATMUL_MOVES)
+        "line_bytes": 64,     # cache line
     }
 
 
@@ -203,11 +210,11 @@ def config(number, seed=None, max_size=None):
 
 
 def n_level_axes(kind):
-    return 5 if kind in (KIND_FUSED_MM_ADD_RELU, KIND_FUSED_BOUNDED) else 3
+    return 5 if kind in (KIND_FUSED_MM_ADD_RELU, KIND_FUSED_BOUNDED) else 2 if kind == KIND_MOVE else 3
 
 
 def n_operands(kind):
-    return 4 if kind in (KIND_FUSED_MM_ADD_RELU, KIND_FUSED_BOUNDED) else 3
+    return 4 if kind in (KIND_FUSED_MM_ADD_RELU, KIND_FUSED_BOUNDED) else 2 if kind == KIND_MOVE else 3
 
 
 def coord_extents(target, lattice):
@@ -218,6 +225,9 @@ def coord_extents(target, lattice):
     if kind in BOUNDED_KINDS:
         # one axis per level of finite capacity: the bounds 0, 1, 2, 4, ... up to the capacity
         ext += [int(c).bit_length() + 1 for c in target["capacity_bytes"][:target["n_levels"]] if c != UNBOUNDED]
+    if kind == KIND_MOVE:
+        # per tensor (source, destination): contiguousness 0..2 and the aligned flag
+        ext += [3, 2, 3, 2]
     nops = n_operands(kind)
     ext += [2] * sum(1 for i in range(nops) if lattice["layout_coord"][i])
     ext += [2] * sum(1 for i in range(nops) if lattice["dtype_coord"][i])

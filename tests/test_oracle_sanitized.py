@@ -28,9 +28,24 @@ def bounded_pipeline():
                          ("F", W._lattice(W.KIND_FUSED_BOUNDED, [[1], r, r, r]), ["M", "E"])]}
 
 
-@pytest.mark.parametrize("number,max_size", [(1, 6), (3, 16), (4, 2), (5, 4), (6, 4), (7, 1), (8, None)])
+def matmul_with_move_specs():
+    """A lattice of Move Specs and a Matmul lattice whose Moves are looked up in it."""
+    t = W._empty_target(3, (64, 128, W.UNBOUNDED))
+    t["loop_overhead"] = 1
+    t["line_bytes"] = 8
+    t["level_weight"] = [1, 2, 5, 0]
+    t["microkernels"] = [(W.MK_SCALAR_FMA, 1, 1), (W.MK_SCALAR_MOVE, 1, 3), (W.MK_VECTOR_MOVE, 2, 2),
+                         (W.MK_VECTOR_MOVE_ALIGNED, 2, 1)]
+    r = [1, 2, 4]
+    return {"name": "moves", "target": t,
+            "lattices": [("V", W._lattice(W.KIND_MOVE, [[1], r, [1], r], layout=(1, 1, 0, 0, 0), dtype=(1, 1, 0, 0, 0)), []),
+                         ("M", W._lattice(W.KIND_MATMUL_MOVES, [[1], r, r, r], layout=(1, 0, 1, 0, 0), dtype=(1, 0, 0, 0, 0),
+                                          base_bytes=(2, 4, 4, 4, 4)), ["V"])]}
+
+
+@pytest.mark.parametrize("number,max_size", [(1, 6), (3, 16), (4, 2), (5, 4), (6, 4), (7, 1), (8, None), (9, None)])
 def test_sanitized_oracle_agrees_with_the_ordinary_build(exe, tmp_path, number, max_size):
-    cfg = bounded_pipeline() if number == 8 else W.config(number, max_size=max_size)
+    cfg = bounded_pipeline() if number == 8 else matmul_with_move_specs() if number == 9 else W.config(number, max_size=max_size)
     got = O.run_sanitized(exe, cfg, str(tmp_path))
     want = O.solve_config(cfg)
     for label, lat, _ in cfg["lattices"]:

@@ -14,6 +14,8 @@ def axes(target, lattice):
     ax = [("size", d) for d in range(4)] + [("level", i) for i in range(nlv)]
     if kind in W.BOUNDED_KINDS:
         ax += [("limit", l) for l in range(target["n_levels"]) if target["capacity_bytes"][l] != W.UNBOUNDED]
+    if kind == W.KIND_MOVE:
+        ax += [("contig", 0), ("aligned", 0), ("contig", 1), ("aligned", 1)]
     ax += [("layout", i) for i in range(nops) if lattice["layout_coord"][i]]
     ax += [("dtype", i) for i in range(nops) if lattice["dtype_coord"][i]]
     return ax, W.coord_extents(target, lattice)
@@ -25,6 +27,7 @@ def spec_of_coord(target, lattice, x):
     lv, ly = [0] * 5, [0] * 5
     bf = [1 if lattice["base_dtype_bytes"][i] == 2 else 0 for i in range(5)]
     lim = [None] * target["n_levels"]
+    contig, aligned = [2, 2], [1, 1]
     for (what, i), v in zip(ax, x):
         if what == "size":
             dims[i] = lattice["sizes"][i][v]
@@ -34,9 +37,13 @@ def spec_of_coord(target, lattice, x):
             ly[i] = v
         elif what == "limit":
             lim[i] = 0 if v == 0 else 1 << (v - 1)
+        elif what == "contig":
+            contig[i] = v
+        elif what == "aligned":
+            aligned[i] = v
         else:
             bf[i] = v
-    return B.Spec(lattice["kind"], tuple(dims), tuple(lv), tuple(ly), tuple(bf), tuple(lim))
+    return B.Spec(lattice["kind"], tuple(dims), tuple(lv), tuple(ly), tuple(bf), tuple(lim), tuple(contig), tuple(aligned))
 
 
 def coord_of_spec(target, lattice, spec):
@@ -51,6 +58,10 @@ def coord_of_spec(target, lattice, spec):
             x.append(spec.layouts[i])
         elif what == "limit":
             x.append(int(spec.limits[i]).bit_length())
+        elif what == "contig":
+            x.append(spec.contig[i])
+        elif what == "aligned":
+            x.append(spec.aligned[i])
         else:
             x.append(spec.bf16[i])
     return tuple(x)

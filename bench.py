@@ -157,7 +157,7 @@ def main():
     n_launch = stats[big]["n_levels_run"]
     kernel_text = ("fill of table %s: plan_kernel (which also streams the (INF, NONE) pre-fill), sort_work_kernel, "
                    "fill_kernel / fill_big_kernel per dependency level" % big)
-    if big_kind in W.BOUNDED_KINDS:
+    if big_kind in W.BOUNDED_KINDS + (W.KIND_MOVE, W.KIND_MATMUL_MOVES):
         # one launch per diagonal: dependency level of shapes + rank (sum of the operand levels)
         n_launch += W.n_operands(big_kind) * (cfg["target"]["n_levels"] - 1)
         kernel_text = "fill of table %s: fill_bounded_kernel, one launch per diagonal of (dependency level, rank)" % big
@@ -234,7 +234,7 @@ def main():
             return sum(len(r["cost"]) for r in res.values()), t_fill, t_all
 
         legs = {}
-        sample_max = {5: 128, 7: 16, 8: 4}.get(args.config)
+        sample_max = {5: 128, 7: 16, 8: 4, 9: 12}.get(args.config)
         if not args.cpu_sample_only:
             legs["full"] = timed(cfg)
         if sample_max is not None:

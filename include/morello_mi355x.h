@@ -59,7 +59,14 @@ typedef enum {
   MRL_MK_BF16_DOT = 2,          /* m=n=1, k % lanes == 0, bf16 lhs/rhs in level 1 (rhs
                                    column-major), f32 out in level 0                         */
   MRL_MK_SCALAR_ADDRELU = 3,    /* bias-add+ReLU, m=n=1, all in level 0                        */
-  MRL_MK_VEC_ADDRELU = 4        /* bias-add+ReLU, m=1, n % lanes == 0, all level 1, row-major  */
+  MRL_MK_VEC_ADDRELU = 4,       /* bias-add+ReLU, m=1, n % lanes == 0, all level 1, row-major  */
+  /* Move Specs (Section 2: select(VectorMove)); m = rows, n = columns of the moved tensor */
+  MRL_MK_SCALAR_MOVE = 5,       /* 1x1, between any two places, any layouts; converts bf16 to f32
+                                   when the types differ (never the other way)                  */
+  MRL_MK_VECTOR_MOVE = 6,       /* one row, n % lanes == 0, between level 1 and a level above 1
+                                   (either way), both row-major, same type, the inner dimension
+                                   of both tensors adjacent in memory (contiguousness >= 1)     */
+  MRL_MK_VECTOR_MOVE_ALIGNED = 7 /* the same, and both tensors aligned                           */
 } mrl_mk_kind;
 
 typedef struct { uint32_t kind; uint32_t lanes; uint64_t cost; } mrl_microkernel;
@@ -78,6 +85,10 @@ typedef struct {
                                                                  loop spreads its trips over; >= 1 for a
                                                                  MATMUL_PARALLEL lattice, else ignored */
   uint32_t sync_cost;                                         /* Section 3: constant of a parallel loop */
+  uint32_t level_weight[MRL_MAX_LEVELS];                      /* Section 3: weight of a level in m(t), the cost
+                                                                 of an alloc-binding (MATMUL_MOVES)            */
+  uint32_t line_bytes;                                        /* cache line: unit of lines(t) in m(t) and of
+                                                                 alignment; >= 1 for MOVE and MATMUL_MOVES     */
 } mrl_target_desc;
 
 typedef struct mrl_target mrl_target;
@@ -126,18 +137,45 @@ void mrl_target_destroy(mrl_target* t);
  * level: it needs that much of the level's bound, and both stages get the
  * rest, rounded down (Section 2.4.4, pipelines).  FUSED_BOUNDED takes deps =
  * {MATMUL_BOUNDED table, BIAS_ADD_RELU_BOUNDED table}.
+ * MOVE (Section 2.2: a Move Spec copies a tensor into another that may differ
+ * in memory level, layout and data type; it is implemented like any Spec, by
+ * loops over smaller Move Specs and move microkernels).  Two tensors, source
+ * (operand 0) and destination (operand 1), of m x n elements (rows, columns;
+ * b and k pinned to 1).  Coordinates: the two size indices; the two levels;
+ * then, where the BOUNDED kinds have their bounds, four axes with the abstract
+ * values of Section 2.4.3: contiguousness of the source (0..2: how many inner
+ * physical dimensions have their values adjacent in memory), aligned flag of
+ * the source, and the same for the destination; layout and dtype bits of both
+ * tensors.  Rewrites: the move microkernels and tiles of m and n.  A tile of
+ * r2 x c2 keeps a tensor's contiguousness unless its inner dimension (columns
+ * if row-major, rows else) is cut, which leaves at most 1; it is aligned only
+ * if the tensor was aligned and contiguous (2) and the tile's inner extent in
+ * bytes is a multiple of line_bytes.  No admissibility test (both tensors
+ * exist already); no deps.
+ * MATMUL_MOVES (Section 2, Memory Movement; Section 3): the MATMUL_ACCUM Specs
+ * (b pinned to 1), except that moving an operand does not cost a coefficient
+ * per element: the alloc-binding costs m(src) + m(dest) plus its children,
+ * which are a load Move Spec (unless the operand is only written), the body,
+ * and a store Move Spec (if it is written).  m(t) = cache lines of t *
+ * level_weight[level of t]; the operands count as contiguous and aligned
+ * (these lattices have no such coordinates), so lines = ceil(bytes /
+ * line_bytes).  The Move Specs' costs come from the one dep, a MOVE table of
+ * the same target whose m and n size lists both equal this lattice's m, k and
+ * n lists (which must be equal), with layout bits on both tensors if any
+ * operand here has one and dtype bits on both if any operand here has one or
+ * is bf16.  load_coef / store_coef / convert_coef are not used.
  */
 typedef enum { MRL_KIND_MATMUL_ACCUM = 0, MRL_KIND_BIAS_ADD_RELU = 1,
                MRL_KIND_FUSED_MM_ADD_RELU = 2, MRL_KIND_MATMUL_PARALLEL = 3,
                MRL_KIND_MATMUL_BOUNDED = 4, MRL_KIND_BIAS_ADD_RELU_BOUNDED = 5,
-               MRL_KIND_FUSED_BOUNDED = 6 } mrl_kind;
+               MRL_KIND_FUSED_BOUNDED = 6, MRL_KIND_MOVE = 7, MRL_KIND_MATMUL_MOVES = 8 } mrl_kind;
 
 typedef struct {
   uint32_t kind;
   uint32_t n_sizes[4];                        /* 1..MRL_MAX_SIZES each                        */
   const uint32_t* sizes[4];                   /* host; ascending, sizes[d][0] == 1            */
   uint8_t layout_coord[MRL_MAX_OPERANDS];     /* layout and dtype bits together: at most 4    */
-  uint8_t dtype_coord[MRL_MAX_OPERANDS];      /* MATMUL_ACCUM inputs only                     */
+  uint8_t dtype_coord[MRL_MAX_OPERANDS];      /* inputs of a Matmul, both tensors of a MOVE   */
   uint8_t base_dtype_bytes[MRL_MAX_OPERANDS]; /* 4 or 2; used when the operand has no dtype bit */
 } mrl_lattice_desc;
 
@@ -175,6 +213,7 @@ typedef struct mrl_table mrl_table;
 
 /* deps: host array of solved tables a FUSED lattice reads: {MATMUL_ACCUM table,
  * BIAS_ADD_RELU table} with the same m, k, n (m, n) size lists and target;
+ * MATMUL_PARALLEL: {MATMUL_ACCUM table}; MATMUL_MOVES: {MOVE table};
  * NULL / 0 otherwise.  d_cost (uint64 per Spec), d_argmin (uint16 per Spec) and
  * d_scratch are DEVICE pointers, 256-byte aligned, owned by the caller and
  * referenced by *out until mrl_table_destroy.  hip_stream: a hipStream_t (or
@@ -298,7 +337,9 @@ int32_t mrl_query_compressed(const mrl_table* tab, const mrl_coord* specs, size_
  * given to mrl_solve as deps must still be alive).  cost = the table's entry
  * of the node's Spec = cost of the whole subtree under Section 3's equation.
  * out: host array of cap nodes, or NULL to get the count only in *n_out;
- * MRL_E_INVAL if the goal has no implementation (cost MRL_INF). */
+ * MRL_E_INVAL if the goal has no implementation (cost MRL_INF), or for a table
+ * of kind MOVE or MATMUL_MOVES (whose alloc-bindings have up to three children
+ * in two tables: not walked by this call). */
 typedef struct {
   uint32_t table;
   uint16_t rewrite;

@@ -45,7 +45,9 @@ class _TargetDesc(C.Structure):
                 ("n_microkernels", C.c_uint32),
                 ("mk", _Microkernel * 8),
                 ("threads", C.c_uint32),
-                ("sync_cost", C.c_uint32)]
+                ("sync_cost", C.c_uint32),
+                ("level_weight", C.c_uint32 * 4),
+                ("line_bytes", C.c_uint32)]
 
 
 class _LatticeDesc(C.Structure):
@@ -131,6 +133,9 @@ def _target_desc(t):
         d.mk[j].kind, d.mk[j].lanes, d.mk[j].cost = kind, lanes, cost
     d.threads = t.get("threads", 1)
     d.sync_cost = t.get("sync_cost", 0)
+    for l in range(4):
+        d.level_weight[l] = t.get("level_weight", [0, 0, 0, 0])[l]
+    d.line_bytes = t.get("line_bytes", 0)
     return d
 
 

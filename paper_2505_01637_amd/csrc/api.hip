@@ -161,9 +161,9 @@ int32_t validate_target(const mrl_target_desc* d) {
   if (d->n_levels < 1 || d->n_levels > MRL_MAX_LEVELS) return fail(MRL_E_INVAL, "n_levels must be 1..4");
   if (d->n_microkernels > MRL_MAX_MK) return fail(MRL_E_INVAL, "too many microkernels");
   for (uint32_t j = 0; j < d->n_microkernels; j++) {
-    if (d->mk[j].kind > MRL_MK_VEC_ADDRELU) return fail(MRL_E_INVAL, "unknown microkernel kind %u", d->mk[j].kind);
+    if (d->mk[j].kind > MRL_MK_VECTOR_MOVE_ALIGNED) return fail(MRL_E_INVAL, "unknown microkernel kind %u", d->mk[j].kind);
     if (d->mk[j].lanes < 1) return fail(MRL_E_INVAL, "microkernel lanes must be >= 1");
-    if (d->mk[j].kind != MRL_MK_SCALAR_FMA && d->mk[j].kind != MRL_MK_SCALAR_ADDRELU && d->n_levels < 2)
+    if (d->mk[j].kind != MRL_MK_SCALAR_FMA && d->mk[j].kind != MRL_MK_SCALAR_ADDRELU && d->mk[j].kind != MRL_MK_SCALAR_MOVE && d->n_levels < 2)
       return fail(MRL_E_INVAL, "vector microkernels need a level 1");
   }
   return MRL_OK;
@@ -171,12 +171,15 @@ int32_t validate_target(const mrl_target_desc* d) {
 
 int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c) {
   if (!L) return fail(MRL_E_INVAL, "lattice descriptor is NULL");
-  if (L->kind > MRL_KIND_FUSED_BOUNDED) return fail(MRL_E_INVAL, "unknown spec kind %u", L->kind);
+  if (L->kind > MRL_KIND_MATMUL_MOVES) return fail(MRL_E_INVAL, "unknown spec kind %u", L->kind);
   // A parallel lattice is a Matmul lattice (same operator, operands and coordinates) with more
-  // rewrites; a bounded one is the lattice of its operator with more coordinates.
-  const bool parallel = L->kind == MRL_KIND_MATMUL_PARALLEL, bounded = L->kind >= MRL_KIND_MATMUL_BOUNDED;
-  const uint32_t kind = parallel ? (uint32_t)kKindM : bounded ? L->kind - MRL_KIND_MATMUL_BOUNDED : L->kind;
+  // rewrites; a bounded one is the lattice of its operator with more coordinates; a Matmul whose
+  // Moves are Move Specs is a Matmul lattice with other Move costs.
+  const bool parallel = L->kind == MRL_KIND_MATMUL_PARALLEL, move_specs = L->kind == MRL_KIND_MOVE, moves = L->kind == MRL_KIND_MATMUL_MOVES;
+  const bool bounded = L->kind >= MRL_KIND_MATMUL_BOUNDED && L->kind <= MRL_KIND_FUSED_BOUNDED;
+  const uint32_t kind = parallel || moves ? (uint32_t)kKindM : bounded ? L->kind - MRL_KIND_MATMUL_BOUNDED : move_specs ? (uint32_t)kKindV : L->kind;
   if (parallel && T.threads < 1) return fail(MRL_E_INVAL, "a MATMUL_PARALLEL lattice needs threads >= 1");
+  if ((move_specs || moves) && T.line_bytes < 1) return fail(MRL_E_INVAL, "MOVE and MATMUL_MOVES lattices need line_bytes >= 1");
   c.target = T;
   c.lat = *L;
   DevParams& P = c.P;
@@ -197,10 +200,19 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
       P.lim_of_level[l] = P.nlim;
       P.lim_nq[P.nlim++] = nq;
     }
-    for (uint32_t a = P.nlim; a-- > 0;) { P.lim_stride[a] = P.Q; P.Q *= P.lim_nq[a]; }
   }
-  P.nops = kind == kKindF ? 4 : 3;
-  P.nlv = kind == kKindF ? 5 : 3;
+  if (move_specs) {
+    // contiguousness and aligned flag of the source, then of the destination
+    P.nlim = 4;
+    P.lim_nq[0] = 3; P.lim_nq[1] = 2; P.lim_nq[2] = 3; P.lim_nq[3] = 2;
+  }
+  for (uint32_t a = P.nlim; a-- > 0;) { P.lim_stride[a] = P.Q; P.Q *= P.lim_nq[a]; }
+  P.gather = bounded || move_specs || moves ? 1u : 0u;
+  P.moves = moves ? 1u : 0u;
+  P.line_bytes = T.line_bytes;
+  for (int l = 0; l < 4; l++) P.weight[l] = T.level_weight[l];
+  P.nops = kind == kKindF ? 4 : kind == kKindV ? 2 : 3;
+  P.nlv = kind == kKindF ? 5 : kind == kKindV ? 2 : 3;
   P.NL = T.n_levels;
   P.npass = kind == kKindF ? P.NL : 1;
   P.ncombo = ipow(P.NL, P.nops);
@@ -222,6 +234,8 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
   }
   if (kind != kKindM && L->n_sizes[0] != 1) return fail(MRL_E_INVAL, "this kind has no batch dimension");
   if (kind == kKindE && L->n_sizes[2] != 1) return fail(MRL_E_INVAL, "BIAS_ADD_RELU has no k dimension");
+  if (kind == kKindV && L->n_sizes[2] != 1) return fail(MRL_E_INVAL, "MOVE has no k dimension");
+  if (moves && L->n_sizes[0] != 1) return fail(MRL_E_INVAL, "MATMUL_MOVES has no batch dimension");
   P.shape_stride[3] = 1;
   for (int d = 2; d >= 0; d--) P.shape_stride[d] = P.shape_stride[d + 1] * P.nsz[d + 1];
   c.n_shapes = P.shape_stride[0] * P.nsz[0];
@@ -231,9 +245,9 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
   for (uint32_t i = 0; i < P.nops; i++) {
     P.nlay += L->layout_coord[i] ? 1 : 0;
     P.ndt += L->dtype_coord[i] ? 1 : 0;
-    if (L->dtype_coord[i] && !(kind == kKindM && i < 2)) return fail(MRL_E_INVAL, "dtype bit only on MatmulAccum inputs");
-    if (L->base_dtype_bytes[i] != 4 && !(L->base_dtype_bytes[i] == 2 && kind == kKindM))
-      return fail(MRL_E_INVAL, "base_dtype_bytes[%u] must be 4 (or 2 on a MatmulAccum)", i);
+    if (L->dtype_coord[i] && !(kind == kKindV || (kind == kKindM && i < 2))) return fail(MRL_E_INVAL, "dtype bit only on MatmulAccum inputs and on the tensors of a MOVE");
+    if (L->base_dtype_bytes[i] != 4 && !(L->base_dtype_bytes[i] == 2 && (kind == kKindM || kind == kKindV)))
+      return fail(MRL_E_INVAL, "base_dtype_bytes[%u] must be 4 (or 2 on a MatmulAccum or a MOVE)", i);
     P.base_bf16[i] = L->base_dtype_bytes[i] == 2;
     P.access[i] = kind == kKindM ? (i == 2 ? kRmw : kRead) : (i == P.nops - 1 ? kWrite : kRead);
     P.lvpow[i] = ipow(P.NL, P.nops - 1 - i);
@@ -274,7 +288,7 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
   if ((parallel ? P.par_base + 4 * maxs : P.buf_id) >= kNone) return fail(MRL_E_INVAL, "rewrite ids do not fit 16 bits");
 
   // Moves: coefficient per (operand, src, dst, transposed) and the list of Moves that can occur
-  for (uint32_t i = 0; i < P.nops; i++)
+  for (uint32_t i = 0; i < (move_specs || moves ? 0u : P.nops); i++)
     for (uint32_t src = 0; src < P.NL; src++)
       for (uint32_t dst = 0; dst < src; dst++)
         for (uint32_t x = 0; x < 2; x++) {
@@ -311,6 +325,12 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
           case MRL_MK_BF16_DOT: ok = P.kind == kKindM && lv[0] == 1 && lv[1] == 1 && lv[2] == 0 && bf[0] && bf[1] && !bf[2] && (P.lay_bit[1] == kNoBit || ly[1] == 1); break;
           case MRL_MK_SCALAR_ADDRELU: ok = P.kind == kKindE && !(lv[0] | lv[1] | lv[2]); break;
           case MRL_MK_VEC_ADDRELU: ok = P.kind == kKindE && lv[0] == 1 && lv[1] == 1 && lv[2] == 1 && !ly[0] && !ly[2]; break;
+          // (the contiguousness / alignment part of the move microkernels' predicates is tested in the kernel)
+          case MRL_MK_SCALAR_MOVE: ok = P.kind == kKindV && !(!bf[0] && bf[1]); break;
+          case MRL_MK_VECTOR_MOVE:
+          case MRL_MK_VECTOR_MOVE_ALIGNED:
+            ok = P.kind == kKindV && ((lv[0] == 1 && lv[1] > 1) || (lv[1] == 1 && lv[0] > 1)) && !ly[0] && !ly[1] && bf[0] == bf[1];
+            break;
         }
         bits |= (uint8_t)((ok ? 1u : 0u) << j);
       }
@@ -421,6 +441,7 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
 using CompiledPtr = std::shared_ptr<const Compiled>;
 
 bool same_problem(const Compiled& c, const mrl_target_desc& T, const mrl_lattice_desc& L) {
+  // (the whole target is compared, also the fields this lattice's kind does not use)
   if (memcmp(&c.target, &T, sizeof T) || c.lat.kind != L.kind) return false;
   if (memcmp(c.lat.layout_coord, L.layout_coord, sizeof L.layout_coord) ||
       memcmp(c.lat.dtype_coord, L.dtype_coord, sizeof L.dtype_coord) ||
@@ -435,7 +456,7 @@ bool same_problem(const Compiled& c, const mrl_target_desc& T, const mrl_lattice
 int32_t get_compiled(const mrl_target_desc& T, const mrl_lattice_desc* L, CompiledPtr& out) {
   static std::mutex mu;
   static std::vector<CompiledPtr> cache;          // most recent last, at most 8
-  if (L && L->kind <= MRL_KIND_FUSED_BOUNDED) {
+  if (L && L->kind <= MRL_KIND_MATMUL_MOVES) {
     std::lock_guard<std::mutex> lock(mu);
     for (size_t i = cache.size(); i-- > 0;)
       if (same_problem(*cache[i], T, *L)) { out = cache[i]; return MRL_OK; }
@@ -682,8 +703,24 @@ int32_t solve_impl(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_t
       return fail(MRL_E_INVAL, "the MATMUL_ACCUM dep has other coordinates");
     P.costM = deps[0]->d_cost;
     tab->deps[0] = deps[0];
+  } else if (P.moves) {
+    if (n_deps != 1 || !deps || !deps[0]) return fail(MRL_E_INVAL, "a MATMUL_MOVES lattice needs deps = {MOVE table}");
+    const Compiled& V = *deps[0]->cp;
+    if (V.P.kind != kKindV) return fail(MRL_E_INVAL, "the dep must be a MOVE table");
+    if (memcmp(&V.target, &t->d, sizeof t->d)) return fail(MRL_E_INVAL, "the dep was solved for another target");
+    if (c.sizes[1] != V.sizes[1] || c.sizes[2] != V.sizes[1] || c.sizes[2] != V.sizes[3] || c.sizes[3] != V.sizes[3])
+      return fail(MRL_E_INVAL, "the m, k and n size lists must all equal the MOVE table's row and column lists");
+    bool any_lay = false, any_dt = false;
+    for (int i = 0; i < 3; i++) { any_lay = any_lay || P.lay_bit[i] != kNoBit; any_dt = any_dt || P.dt_bit[i] != kNoBit || P.base_bf16[i]; }
+    if (any_lay && (V.P.lay_bit[0] == kNoBit || V.P.lay_bit[1] == kNoBit)) return fail(MRL_E_INVAL, "the MOVE table needs layout bits on both tensors");
+    if (any_dt && (V.P.dt_bit[0] == kNoBit || V.P.dt_bit[1] == kNoBit)) return fail(MRL_E_INVAL, "the MOVE table needs dtype bits on both tensors");
+    if (V.P.dt_bit[0] == kNoBit && (V.P.base_bf16[0] || V.P.base_bf16[1])) return fail(MRL_E_INVAL, "a MOVE table without dtype bits must be f32");
+    P.costM = deps[0]->d_cost;
+    tab->deps[0] = deps[0];
+    P.GV = V.P.G; P.VV = V.P.V; P.nszV = V.P.nsz[3]; P.QV = V.P.Q; P.qV_top = V.P.Q - 1;
+    for (int i = 0; i < 2; i++) { P.layV[i] = V.P.lay_bit[i]; P.dtV[i] = V.P.dt_bit[i]; }
   } else if (n_deps != 0) {
-    return fail(MRL_E_INVAL, "only FUSED and MATMUL_PARALLEL lattices take deps");
+    return fail(MRL_E_INVAL, "only FUSED, MATMUL_PARALLEL and MATMUL_MOVES lattices take deps");
   }
 
   std::unique_lock<std::mutex> solve_lock(c.solve_mu);      // for the upload image, until the upload has run
@@ -738,8 +775,8 @@ int32_t solve_impl(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_t
   bool prefill_timed = false;
   const hipEvent_t uploaded = aux->events[ev_used++];
   HIP_TRY(hipEventRecord(uploaded, st));
-  if (P.bounded) {
-    // Memory bounds as coordinates: every Spec is evaluated (no admissibility test, so every cell
+  if (P.gather) {
+    // Memory bounds as coordinates (and Move Specs, and Matmuls whose Moves are Specs): every Spec is evaluated (no admissibility test, so every cell
     // counts as fitting for the compression); one launch per dependency level of shapes and rank
     // of level assignments, each over Specs that depend only on earlier launches.
     launch_fill_ones(d_fitmap, ((size_t)f.n_words + 2) * 8, st);
@@ -989,7 +1026,7 @@ int32_t solve_impl(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_t
     stats->n_specs = c.n_specs;
     stats->n_admissible = stats->n_rewrites = 0;
     for (uint32_t i = 0; i < kCtrSlots; i++) { stats->n_admissible += h_ctr.n_admissible[i]; stats->n_rewrites += h_ctr.n_rewrites[i]; }
-    if (P.bounded) stats->n_admissible = c.n_specs;      // no admissibility test: every Spec is evaluated
+    if (P.bounded || P.kind == kKindV) stats->n_admissible = c.n_specs;      // no admissibility test: every Spec is evaluated
     stats->n_levels_run = n_lev;
     HIP_TRY(hipEventElapsedTime(&stats->fill_ms, ev[0], ev[1]));
     HIP_TRY(hipEventElapsedTime(&stats->compress_ms, ev[3], ev[2]));
@@ -1298,6 +1335,8 @@ int32_t mrl_coord_of_spec(const mrl_table* tab, const uint32_t shape[4], const u
 int32_t mrl_schedule(const mrl_table* tab, const mrl_coord* goal, mrl_schedule_node* out, size_t cap, size_t* n_out) {
   return guarded([&]() -> int32_t {
   if (!tab || !goal) return fail(MRL_E_INVAL, "NULL argument");
+  if (tab->P.kind == kKindV || tab->P.moves)
+    return fail(MRL_E_INVAL, "mrl_schedule does not walk MOVE and MATMUL_MOVES tables");
   struct Item { const mrl_table* t; uint32_t which; mrl_coord x; };
   std::vector<Item> stack;
   stack.push_back({tab, 0u, *goal});

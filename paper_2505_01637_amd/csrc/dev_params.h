@@ -15,7 +15,7 @@ constexpr int kMaxCombo = 256;               // n_levels ^ n_operands
 constexpr int kMaxRanks = 16;
 constexpr uint32_t kNoBit = 0xFF;            // "this operand has no such coordinate"
 
-enum : uint32_t { kKindM = 0, kKindE = 1, kKindF = 2 };
+enum : uint32_t { kKindM = 0, kKindE = 1, kKindF = 2, kKindV = 3 };   // V: Move Specs (two tensors: source, destination)
 enum : uint32_t { kRead = 0, kRmw = 1, kWrite = 2 };
 
 // One tile rewrite of a (dim, size index): the index of the smaller size and the trip count.
@@ -77,6 +77,16 @@ struct DevParams {
   uint32_t lim_nq[4];        // extent of bound axis a
   uint32_t lim_stride[4];    // its stride inside the bound vector's index (first axis slowest)
   uint32_t lim_of_level[4];  // bound axis of memory level l, kNoBit if the level is unbounded
+  // ---- Move Specs (kind kKindV) and the Matmul whose Moves are Move Specs (moves = 1, kind kKindM) ----
+  // A Move lattice keeps its four abstract-value axes (contiguousness and aligned flag of source and
+  // destination) where a bounded lattice keeps its bounds: nlim = 4, lim_nq = {3, 2, 3, 2}.
+  uint32_t gather;           // 1: filled by the lane-per-Spec kernel (bounded, Move and moves lattices)
+  uint32_t moves;            // 1: a Move costs m(src) + m(dest) + the load / store Move Specs read from costM
+  uint32_t weight[4];        // per-level weight of m(t)
+  uint32_t line_bytes;
+  uint32_t GV, VV, nszV;     // the Move table: entries per shape, variants, number of column sizes
+  uint32_t QV, qV_top;       // its abstract vectors per level pair, and the index of (contiguous, aligned) twice
+  uint32_t layV[2], dtV[2];  // bit positions of its layout and dtype bits, kNoBit if absent
   // ---- tables a FUSED lattice reads (costM also: the serial table a parallel lattice reads) ----
   const uint64_t* costM;
   const uint64_t* costE;

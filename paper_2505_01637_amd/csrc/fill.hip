@@ -85,6 +85,7 @@ __device__ __forceinline__ void load_shape(const DevParams* __restrict__ P, uint
   }
   uint64_t b = S.d[0], m = S.d[1], k = S.d[2], n = S.d[3];
   if (P->kind == kKindM) { S.numel[0] = b * m * k; S.numel[1] = b * k * n; S.numel[2] = b * m * n; S.numel[3] = 0; S.numel[4] = 0; }
+  else if (P->kind == kKindV) { S.numel[0] = m * n; S.numel[1] = m * n; S.numel[2] = 0; S.numel[3] = 0; S.numel[4] = 0; }
   else if (P->kind == kKindE) { S.numel[0] = m * n; S.numel[1] = n; S.numel[2] = m * n; S.numel[3] = 0; S.numel[4] = 0; }
   else { S.numel[0] = m * k; S.numel[1] = k * n; S.numel[2] = n; S.numel[3] = m * n; S.numel[4] = m * n; }
 }
@@ -142,6 +143,9 @@ __device__ __forceinline__ uint64_t mk_shape_reps(const DevParams* __restrict__ 
     case 2: return (b == 1 && m == 1 && n == 1 && k % lanes == 0) ? k / lanes : 0;
     case 3: return (m == 1 && n == 1) ? 1 : 0;
     case 4: return (m == 1 && n % lanes == 0) ? n / lanes : 0;
+    case 5: return (m == 1 && n == 1) ? 1 : 0;                       // Move Specs: m rows, n columns
+    case 6:
+    case 7: return (m == 1 && n % lanes == 0) ? n / lanes : 0;
     default: return 0;
   }
 }
@@ -979,11 +983,23 @@ uint32_t fill_wave_cap(uint32_t G) { return G <= kSmallCap ? G : kSlicedCap; }
 // the level, level assignment of the rank, level of the fused Spec's intermediate, bound vector,
 // variant), variant fastest.  A bufferize (fused Spec) allocates the intermediate in its level:
 // it needs 4 * m * n bytes of that level's bound, and both stages get the rest, rounded down.
+//
+// The same kernel fills two further kinds of lattice, which also are gathers from finished
+// entries.  Move Specs (Section 2.2; kind kKindV): two tensors, no Move rewrites; where a bounded
+// lattice has its bounds they have the abstract values of Section 2.4.3 (contiguousness and
+// aligned flag of source and destination), which a tile changes and the vector-move microkernels
+// test.  And the Matmul whose Moves are Move Specs (Section 2, Memory Movement; Section 3): the
+// plain Matmul Specs with their admissibility test, where a Move costs m(src) + m(dest) in cache
+// lines plus the load and store Move Specs, read from the Move table.
+__device__ __forceinline__ uint64_t add_or_limit(uint64_t a, uint64_t b) {
+  return (a >= kLimit || b >= kLimit || a + b >= kLimit) ? kLimit : a + b;
+}
+
 __global__ __launch_bounds__(256) void fill_bounded_kernel(const DevParams* __restrict__ P,
                                                            const uint32_t* __restrict__ all_level_shapes, const BoundSegs segs,
                                                            uint64_t* cost, uint16_t* __restrict__ arg,
                                                            Counters* __restrict__ ctr) {
-  __shared__ uint32_t wave_n[4];
+  __shared__ uint32_t wave_n[4], wave_adm[4];
   uint32_t seg = 0;
   while (seg + 1 < segs.n && blockIdx.x >= segs.block0[seg + 1]) seg++;
   const uint32_t rank = segs.rank[seg], n_level_shapes = segs.n_shapes[seg];
@@ -995,6 +1011,7 @@ __global__ __launch_bounds__(256) void fill_bounded_kernel(const DevParams* __re
   const bool active = t < per_shape * n_level_shapes;
   Eval e;
   e.best = kInf; e.arg = kNone; e.n = 0; e.ovf = 0;
+  uint32_t n_adm = 0;
   if (active) {
     const uint32_t sl = (uint32_t)(t / per_shape);
     uint32_t r = (uint32_t)(t - (uint64_t)sl * per_shape);
@@ -1020,6 +1037,25 @@ __global__ __launch_bounds__(256) void fill_bounded_kernel(const DevParams* __re
     }
     const uint64_t group = (uint64_t)shape * P->G;
     const uint32_t off = ((combo * npass + pass) * Q + q) * V + v;
+    const bool move_specs = P->kind == kKindV;
+
+    // Where Moves are Specs the lattice is the plain Matmul's: a Spec whose operands do not fit
+    // their levels has no implementation and evaluates nothing.
+    bool admissible = true;
+    if (P->moves) {
+#pragma unroll
+      for (int l = 0; l < 4; l++) {
+        uint64_t bytes = 0;
+#pragma unroll
+        for (int i = 0; i < 3; i++) {
+          const uint32_t bf = P->dt_bit[i] != kNoBit ? (v >> P->dt_bit[i]) & 1u : P->base_bf16[i];
+          bytes += lv[i] == (uint32_t)l ? S.numel[i] * (bf ? 2u : 4u) : 0u;
+        }
+        admissible = admissible && ((uint32_t)l >= P->NL || bytes <= P->cap[l]);
+      }
+      n_adm = admissible ? 1u : 0u;
+    }
+    if (admissible) {
 
     // microkernels
     const uint32_t mm = P->mk_entry[pack * V + v];
@@ -1027,15 +1063,20 @@ __global__ __launch_bounds__(256) void fill_bounded_kernel(const DevParams* __re
       if (!((mm >> j) & 1u)) continue;
       const uint64_t reps = mk_shape_reps(P, S, j);
       if (!reps) continue;
+      if (P->mk_kind[j] >= 6u) {
+        // vector moves: the inner dimension of both tensors adjacent in memory; the aligned form: both aligned
+        if (qi[0] < 1u || qi[2] < 1u) continue;
+        if (P->mk_kind[j] == 7u && !(qi[1] && qi[3])) continue;
+      }
       const uint64_t k = mul_or_limit(P->mk_cost[j], reps);
       if (k >= kLimit) e.ovf = 1; else consider(e, k, j);
       e.n++;
     }
 
-    // Moves
+    // Moves (a Move Spec has none)
 #pragma unroll
     for (int i = 0; i < 4; i++) {
-      if ((uint32_t)i >= nops) continue;
+      if ((uint32_t)i >= nops || move_specs) continue;
       const uint32_t src = lv[i];
       const bool has_dt = P->dt_bit[i] != kNoBit, has_lay = P->lay_bit[i] != kNoBit;
       const uint32_t bf = has_dt ? (v >> P->dt_bit[i]) & 1u : P->base_bf16[i];
@@ -1045,9 +1086,41 @@ __global__ __launch_bounds__(256) void fill_bounded_kernel(const DevParams* __re
           for (uint32_t cv = 0; cv < 2; cv++) {
             if (x && !has_lay) continue;
             if (cv && !(P->can_convert[i] && has_dt && bf)) continue;
+            const uint32_t child_bf = cv ? 0u : bf;
+            if (P->moves) {
+              // the alloc-binding: m(src) + m(dest), the load Move Spec (operands that are read), the
+              // body, the store Move Spec (operands that are written); the operand is rows x cols
+              const uint32_t ri = i == 1 ? S.si[2] : S.si[1], ci = i == 0 ? S.si[2] : S.si[3];
+              const uint64_t groupV = (uint64_t)(ri * P->nszV + ci) * P->GV;
+              const uint32_t y0 = has_lay ? (v >> P->lay_bit[i]) & 1u : 0u, y1 = y0 ^ x;
+              auto variantV = [&](uint32_t ys, uint32_t yd, uint32_t fs, uint32_t fd) {
+                return (P->layV[0] != kNoBit ? ys << P->layV[0] : 0u) + (P->layV[1] != kNoBit ? yd << P->layV[1] : 0u) +
+                       (P->dtV[0] != kNoBit ? fs << P->dtV[0] : 0u) + (P->dtV[1] != kNoBit ? fd << P->dtV[1] : 0u);
+              };
+              uint64_t c_load = 0, c_store = 0;
+              if (P->access[i] != kWrite)
+                c_load = P->costM[groupV + ((src * P->NL + dst) * P->QV + P->qV_top) * P->VV + variantV(y0, y1, bf, child_bf)];
+              if (P->access[i] != kRead)
+                c_store = P->costM[groupV + ((dst * P->NL + src) * P->QV + P->qV_top) * P->VV + variantV(y1, y0, child_bf, bf)];
+              const uint32_t combo_c = combo - (src - dst) * P->lvpow[i];
+              uint32_t v_c = v ^ (x ? 1u << P->lay_bit[i] : 0u);
+              if (cv) v_c &= ~(1u << P->dt_bit[i]);
+              const uint64_t sub = cost[group + (uint64_t)((combo_c * npass + pass) * Q + q) * V + v_c];
+              const uint64_t line = P->line_bytes;
+              const uint64_t lines_s = (numel * (bf ? 2u : 4u) + line - 1) / line, lines_d = (numel * (child_bf ? 2u : 4u) + line - 1) / line;
+              const uint32_t ws = src == 1 ? P->weight[1] : src == 2 ? P->weight[2] : P->weight[3];
+              const uint32_t wd = dst == 0 ? P->weight[0] : dst == 1 ? P->weight[1] : P->weight[2];
+              const uint32_t id = P->move_base + (((uint32_t)i * (P->NL - 1u) + dst) * 2u + x) * 2u + cv;
+              if (sub != kInf && c_load != kInf && c_store != kInf) {
+                uint64_t tot = add_or_limit(mul_or_limit(lines_s, ws), mul_or_limit(lines_d, wd));
+                tot = add_or_limit(add_or_limit(tot, c_load), add_or_limit(c_store, sub));
+                if (tot >= kLimit) e.ovf = 1; else consider(e, tot, id);
+              }
+              e.n++;
+              continue;
+            }
             const uint32_t coef = P->mcoef[i][src][dst][x];
             if (!coef) continue;
-            const uint32_t child_bf = cv ? 0u : bf;
             uint32_t qc = q;
             const uint32_t la = P->lim_of_level[dst];
             if (la != kNoBit) {
@@ -1080,7 +1153,27 @@ __global__ __launch_bounds__(256) void fill_bounded_kernel(const DevParams* __re
       for (uint32_t te_i = P->tile_off[d][S.si[d]]; te_i < P->tile_off[d][S.si[d] + 1]; te_i++) {
         const TileEntry te = P->tiles[te_i];
         const uint32_t child = shape - (S.si[d] - te.jt) * P->shape_stride[d];
-        const uint64_t sub = cost[(uint64_t)child * P->G + off];
+        uint32_t off_c = off;
+        if (move_specs) {
+          // Section 2.4.3: what is known of a tile of either tensor.  Cutting the inner dimension
+          // leaves only that dimension adjacent; the tile is aligned only if the tensor was aligned
+          // and contiguous and the tile's rows (and so the tile) are whole cache lines.
+          const uint64_t r2 = d == 1 ? P->sizes[1][te.jt] : S.d[1], c2 = d == 3 ? P->sizes[3][te.jt] : S.d[3];
+          uint32_t qc = 0;
+#pragma unroll
+          for (int ts = 0; ts < 2; ts++) {
+            const uint32_t y = P->lay_bit[ts] != kNoBit ? (v >> P->lay_bit[ts]) & 1u : 0u;
+            const uint32_t bf = P->dt_bit[ts] != kNoBit ? (v >> P->dt_bit[ts]) & 1u : P->base_bf16[ts];
+            const uint64_t inner = y ? S.d[1] : S.d[3], inner2 = y ? r2 : c2, outer2 = y ? c2 : r2, eb = bf ? 2u : 4u;
+            const uint32_t contig = qi[2 * ts], aligned = qi[2 * ts + 1];
+            const uint32_t contig2 = inner2 == inner ? contig : (contig < 1u ? contig : 1u);
+            const uint32_t aligned2 = (aligned && contig == 2u && (inner2 * eb) % P->line_bytes == 0 &&
+                                       (outer2 * inner2 * eb) % P->line_bytes == 0) ? 1u : 0u;
+            qc += contig2 * P->lim_stride[2 * ts] + aligned2 * P->lim_stride[2 * ts + 1];
+          }
+          off_c = ((combo * npass + pass) * Q + qc) * V + v;
+        }
+        const uint64_t sub = cost[(uint64_t)child * P->G + off_c];
         const bool fin = sub != kInf;
         const uint32_t a = te.trips;
         const uint64_t lo = (uint64_t)a * (uint32_t)sub;
@@ -1127,18 +1220,21 @@ __global__ __launch_bounds__(256) void fill_bounded_kernel(const DevParams* __re
         e.n++;
       }
     }
+    }   // admissible
     cost[group + off] = e.best;
     arg[group + off] = (uint16_t)e.arg;
   }
-  // rewrites evaluated: one atomic per workgroup
+  // rewrites evaluated (and Specs that fit): one atomic each per workgroup
   uint32_t n_rw = e.n;
 #pragma unroll
-  for (int d = 32; d > 0; d >>= 1) n_rw += __shfl_down(n_rw, d, 64);
-  if ((threadIdx.x & 63u) == 0) wave_n[threadIdx.x >> 6] = n_rw;
+  for (int d = 32; d > 0; d >>= 1) { n_rw += __shfl_down(n_rw, d, 64); n_adm += __shfl_down(n_adm, d, 64); }
+  if ((threadIdx.x & 63u) == 0) { wave_n[threadIdx.x >> 6] = n_rw; wave_adm[threadIdx.x >> 6] = n_adm; }
   __syncthreads();
   if (threadIdx.x == 0) {
     const uint32_t n = wave_n[0] + wave_n[1] + wave_n[2] + wave_n[3];
     if (n) atomicAdd(&ctr->n_rewrites[blockIdx.x % kCtrSlots], (unsigned long long)n);
+    const uint32_t na = wave_adm[0] + wave_adm[1] + wave_adm[2] + wave_adm[3];
+    if (na) atomicAdd(&ctr->n_admissible[blockIdx.x % kCtrSlots], (unsigned long long)na);
   }
   if (e.ovf) atomicOr(&ctr->overflow, e.ovf);
 }

@@ -204,8 +204,23 @@ def config(number, seed=None, max_size=None):
         lats = [("M", _lattice(KIND_MATMUL_BOUNDED, [one, p2, p2, p2]), []),
                 ("E", _lattice(KIND_BIAS_ADD_RELU_BOUNDED, [one, p2, one, p2]), []),
                 ("F", _lattice(KIND_FUSED_BOUNDED, [one, p2, p2, p2]), ["M", "E"])]
+    elif number == 9:
+        # beyond the five benchmark configurations: Moves as Specs of their own.  Config 2's target
+        # recipe; the level weights also weigh a Move's cache lines; move microkernels for one
+        # element, for a row of 8-lane vectors, and (cheaper) for an aligned one.  A lattice of Move
+        # Specs over sizes 1..32 (rows, columns; both layouts; contiguousness and alignment of both
+        # tensors as coordinates) and the Matmul lattice over the same sizes that reads it
+        t, w = _four_level_target(rng)
+        t["level_weight"] = list(w)
+        t["line_bytes"] = 64
+        t["microkernels"].append((MK_SCALAR_MOVE, 1, rng.draw(1, 3)))
+        t["microkernels"].append((MK_VECTOR_MOVE, 8, rng.draw(2, 3)))
+        t["microkernels"].append((MK_VECTOR_MOVE_ALIGNED, 8, 1))
+        r = keep(range(1, 33))
+        lats = [("V", _lattice(KIND_MOVE, [one, r, one, r], layout=(1, 1, 0, 0, 0)), []),
+                ("M", _lattice(KIND_MATMUL_MOVES, [one, r, r, r], layout=(1, 1, 1, 0, 0)), ["V"])]
     else:
-        raise ValueError("config number must be 1..8")
+        raise ValueError("config number must be 1..9")
     return {"name": "config%d" % number, "target": t, "lattices": lats}
 
 

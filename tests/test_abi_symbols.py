@@ -2,6 +2,8 @@
 import os
 import re
 
+import pytest
+
 from paper_2505_01637_amd import binding as B
 from paper_2505_01637_amd import workloads as W
 
@@ -131,3 +133,28 @@ def test_graph_call_refuses_malformed_graphs_before_device_work():
     descs[1] = descs[0]                 # the same lattice twice
     rc, msg = call(3)
     assert rc == B.E_INVAL and "same lattice" in msg
+
+
+def test_moves_as_specs_host_checks():
+    """Host-side checks (no device work): geometry of a MOVE lattice, and what a MOVE or
+    MATMUL_MOVES lattice is refused for."""
+    import ctypes as C
+    from paper_2505_01637_amd import binding as B
+    from paper_2505_01637_amd import workloads as W
+    from oracle import oracle as O
+    t = W._empty_target(3, (64, 128, W.UNBOUNDED))
+    t["line_bytes"] = 8
+    t["microkernels"] = [(W.MK_SCALAR_MOVE, 1, 3), (W.MK_VECTOR_MOVE, 2, 2)]
+    r = [1, 2, 3, 4, 6, 8]
+    lat = W._lattice(W.KIND_MOVE, [[1], r, [1], r], layout=(1, 1, 0, 0, 0), dtype=(1, 0, 0, 0, 0))
+    target = B.Target(t)
+    ext, n = B.geometry(target, lat)
+    want_ext, _, _ = O.geometry(t, lat)
+    assert ext == want_ext == [1, 6, 1, 6, 3, 3, 3, 2, 3, 2, 2, 2, 2]
+    assert n == W.n_specs(t, lat)
+    for bad_target, bad_lat in ((dict(t, line_bytes=0), lat),
+                                (t, W._lattice(W.KIND_MOVE, [[1], r, r, r])),
+                                (t, W._lattice(W.KIND_MATMUL_MOVES, [[1, 2], r, r, r]))):
+        with pytest.raises(B.MorelloError) as e:
+            B.geometry(B.Target(bad_target), bad_lat)
+        assert e.value.code == B.E_INVAL

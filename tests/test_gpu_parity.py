@@ -262,6 +262,51 @@ def test_parity_memory_bounds_through_a_pipeline(case):
     assert n_pipeline > 0
 
 
+def move_spec_case(case):
+    """Targets and lattices for Moves as Specs: three levels, an 8-byte cache line (alignment and
+    whole lines matter for tensors of a few elements), move microkernels of 1 and 2 lanes."""
+    t = W._empty_target(3, (64, 128, W.UNBOUNDED))
+    t["loop_overhead"] = 1
+    t["line_bytes"] = 8
+    t["level_weight"] = [1, 2, 5, 0]
+    t["microkernels"] = [(W.MK_SCALAR_FMA, 1, 1), (W.MK_SCALAR_MOVE, 1, 3), (W.MK_VECTOR_MOVE, 2, 2),
+                         (W.MK_VECTOR_MOVE_ALIGNED, 2, 1)]
+    if case == "moves-only":
+        r = [1, 2, 3, 4, 6, 8, 12]
+        lats = [("V", W._lattice(W.KIND_MOVE, [[1], r, [1], r], layout=(1, 1, 0, 0, 0), dtype=(1, 1, 0, 0, 0)), [])]
+    elif case == "matmul-f32":
+        r = [1, 2, 3, 4, 6, 8]
+        lats = [("V", W._lattice(W.KIND_MOVE, [[1], r, [1], r]), []),
+                ("M", W._lattice(W.KIND_MATMUL_MOVES, [[1], r, r, r]), ["V"])]
+    elif case == "matmul-layouts-dtypes":
+        r = [1, 2, 4, 8]
+        lats = [("V", W._lattice(W.KIND_MOVE, [[1], r, [1], r], layout=(1, 1, 0, 0, 0), dtype=(1, 1, 0, 0, 0)), []),
+                ("M", W._lattice(W.KIND_MATMUL_MOVES, [[1], r, r, r], layout=(1, 0, 1, 0, 0), dtype=(1, 1, 0, 0, 0),
+                                 base_bytes=(2, 2, 4, 4, 4)), ["V"])]
+    elif case == "two-levels":
+        t["n_levels"] = 2
+        t["capacity_bytes"] = [64, W.UNBOUNDED, 0, 0]
+        r = [1, 2, 4, 5]
+        lats = [("V", W._lattice(W.KIND_MOVE, [[1], r, [1], r], layout=(1, 1, 0, 0, 0)), []),
+                ("M", W._lattice(W.KIND_MATMUL_MOVES, [[1], r, r, r], layout=(0, 1, 1, 0, 0)), ["V"])]
+    else:
+        return W.config(9, max_size=int(case))
+    return {"name": case, "target": t, "lattices": lats}
+
+
+@pytest.mark.parametrize("case", ["moves-only", "matmul-f32", "matmul-layouts-dtypes", "two-levels", "12", "32"])
+def test_parity_moves_as_specs(case):
+    """Section 2.2 / 2.4.3 / 3: the lattice of Move Specs (abstract contiguousness and alignment as
+    coordinates) and the Matmul lattice whose alloc-bindings hold Move Specs and cost
+    m(src) + m(dest): tables, counters and both box lists against the oracle; "32" is the size
+    that bench.py --config 9 times."""
+    _, tabs, want = compare_config(move_spec_case(case))
+    for label, tab in tabs.items():
+        assert tab.stats.n_admissible > 0
+        # point queries from the box lists alone
+        check_compressed_queries(tab, want[label], 3000, seed=5)
+
+
 def test_degenerate_lattices():
     B = _binding()
     # a single shape: every dimension pinned

@@ -65,6 +65,8 @@ def main():
     ap.add_argument("--config", type=int, default=5)
     ap.add_argument("--seed", type=int, default=None)
     ap.add_argument("--scratch-gb", type=float, default=8.0)
+    ap.add_argument("--max-size", type=int, default=None,
+                    help="drop the allowed sizes above this (a smaller lattice of the same structure)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-only", action="store_true",
                     help="time the oracle on the smaller sample of the workload only (about 15 s instead of 2 minutes)")
@@ -85,7 +87,7 @@ def main():
     torch.cuda.set_device(0)
     dev = torch.device("cuda", 0)
 
-    cfg = W.config(args.config, seed=args.seed)
+    cfg = W.config(args.config, seed=args.seed, max_size=args.max_size)
     target = B.Target(cfg["target"])
     scratch = torch.empty(int(args.scratch_gb * (1 << 30)), dtype=torch.uint8, device=dev)
     bufs = {}
@@ -179,7 +181,8 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u64", "data": "synthetic",
-        "config": {"workload": "config %d: %s" % (args.config, ", ".join("%s %d specs" % (l, n) for l, n in sizes.items())),
+        "config": {"workload": "config %d%s: %s" % (args.config, "" if args.max_size is None else " with sizes <= %d" % args.max_size,
+                                                      ", ".join("%s %d specs" % (l, n) for l, n in sizes.items())),
                    "seed": args.config if args.seed is None else args.seed},
         # the lattice points of the metric are mostly Specs that do not fit their levels, whose
         # whole cost is a streaming store; the work of the method is in the admissible ones
@@ -237,7 +240,7 @@ def main():
         sample_max = {5: 128, 7: 16, 8: 4, 9: 12}.get(args.config)
         if not args.cpu_sample_only:
             legs["full"] = timed(cfg)
-        if sample_max is not None:
+        if sample_max is not None and (args.max_size is None or sample_max < args.max_size):
             legs["sample"] = timed(W.config(args.config, seed=args.seed, max_size=sample_max))
         main_leg = "full" if "full" in legs else "sample"
         n_s, t_fill, t_all = legs[main_leg]

@@ -783,7 +783,7 @@ int32_t solve_impl(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_t
     for (uint32_t d = 0; d + 1 < n_lev + P.nranks; d++) {
       BoundSegs segs;
       segs.n = 0; segs.block0[0] = 0;
-      auto flush = [&]() { launch_fill_bounded(d_P, d_level_shapes, segs, tab->d_cost, tab->d_arg, d_ctr, st); segs.n = 0; segs.block0[0] = 0; };
+      auto flush = [&]() { launch_fill_bounded(d_P, P.kind == kKindV ? 1 : P.moves ? 2 : 0, d_level_shapes, segs, tab->d_cost, tab->d_arg, d_ctr, st); segs.n = 0; segs.block0[0] = 0; };
       for (uint32_t l = d < P.nranks ? 0 : d - (P.nranks - 1); l < n_lev && l <= d; l++) {
         const uint32_t r = d - l, ns = c.level_off[l + 1] - c.level_off[l];
         const uint64_t lanes = (uint64_t)ns * (P.rank_off[r + 1] - P.rank_off[r]) * P.npass * P.Q * P.V;

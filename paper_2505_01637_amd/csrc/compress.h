@@ -30,7 +30,8 @@ struct BoundSegs {
   uint32_t n;
   uint32_t first_shape[kBoundSegs], n_shapes[kBoundSegs], rank[kBoundSegs], block0[kBoundSegs + 1];
 };
-void launch_fill_bounded(const DevParams* P, const uint32_t* all_level_shapes, const BoundSegs& segs, uint64_t* cost,
+// mode 0: a lattice with memory bounds; 1: Move Specs; 2: a Matmul whose Moves are Move Specs.
+void launch_fill_bounded(const DevParams* P, int mode, const uint32_t* all_level_shapes, const BoundSegs& segs, uint64_t* cost,
                          uint16_t* arg, Counters* ctr, hipStream_t stream);
 void launch_fill_ones(void* p, size_t bytes, hipStream_t stream);
 void launch_zero_words(unsigned long long* p, uint32_t n, hipStream_t st);

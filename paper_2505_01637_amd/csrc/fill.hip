@@ -34,6 +34,7 @@
 // reduced across lanes and no result depends on which wave handles an item:
 // the table is deterministic.
 #include <hip/hip_runtime.h>
+#include <cstdlib>
 #include "compress.h"
 #include "dev_params.h"
 
@@ -931,8 +932,10 @@ __global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(1, 4))) void 
   flush_counters(ctr, tot);
 }
 
-// The slices too large for a wave's LDS slice: one workgroup of kBigBlock threads each.
-__global__ __launch_bounds__(kBigBlock) __attribute__((amdgpu_waves_per_eu(1, 4))) void fill_big_kernel(const DevParams* __restrict__ P,
+// The slices too large for a wave's LDS slice: one workgroup of TB threads each (kBigBlock, or
+// twice as many on levels with so few of them that most compute units would hold one or none).
+template <int TB>
+__global__ __launch_bounds__(TB) __attribute__((amdgpu_waves_per_eu(1, 4))) void fill_big_kernel(const DevParams* __restrict__ P,
                                                              const uint32_t* __restrict__ list_wide, uint32_t cap,
                                                              uint64_t* __restrict__ cost, uint16_t* __restrict__ arg,
                                                              Counters* __restrict__ ctr) {
@@ -944,7 +947,7 @@ __global__ __launch_bounds__(kBigBlock) __attribute__((amdgpu_waves_per_eu(1, 4)
   const uint32_t shape = unit / P->npass, pass = unit % P->npass;
   Shape S;
   load_shape(P, shape, S);
-  solve_unit<kBigBlock>(P, L, cap, S, shape, pass, 1, cost, arg, tot);
+  solve_unit<TB>(P, L, cap, S, shape, pass, 1, cost, arg, tot);
   flush_counters(ctr, tot);
 }
 
@@ -995,6 +998,8 @@ __device__ __forceinline__ uint64_t add_or_limit(uint64_t a, uint64_t b) {
   return (a >= kLimit || b >= kLimit || a + b >= kLimit) ? kLimit : a + b;
 }
 
+// MODE 0: memory bounds as coordinates; 1: Move Specs; 2: the Matmul whose Moves are Move Specs.
+template <int MODE>
 __global__ __launch_bounds__(256) void fill_bounded_kernel(const DevParams* __restrict__ P,
                                                            const uint32_t* __restrict__ all_level_shapes, const BoundSegs segs,
                                                            uint64_t* cost, uint16_t* __restrict__ arg,
@@ -1037,12 +1042,12 @@ __global__ __launch_bounds__(256) void fill_bounded_kernel(const DevParams* __re
     }
     const uint64_t group = (uint64_t)shape * P->G;
     const uint32_t off = ((combo * npass + pass) * Q + q) * V + v;
-    const bool move_specs = P->kind == kKindV;
+    constexpr bool move_specs = MODE == 1, moves = MODE == 2;
 
     // Where Moves are Specs the lattice is the plain Matmul's: a Spec whose operands do not fit
     // their levels has no implementation and evaluates nothing.
     bool admissible = true;
-    if (P->moves) {
+    if (moves) {
 #pragma unroll
       for (int l = 0; l < 4; l++) {
         uint64_t bytes = 0;
@@ -1063,7 +1068,7 @@ __global__ __launch_bounds__(256) void fill_bounded_kernel(const DevParams* __re
       if (!((mm >> j) & 1u)) continue;
       const uint64_t reps = mk_shape_reps(P, S, j);
       if (!reps) continue;
-      if (P->mk_kind[j] >= 6u) {
+      if (move_specs && P->mk_kind[j] >= 6u) {
         // vector moves: the inner dimension of both tensors adjacent in memory; the aligned form: both aligned
         if (qi[0] < 1u || qi[2] < 1u) continue;
         if (P->mk_kind[j] == 7u && !(qi[1] && qi[3])) continue;
@@ -1087,7 +1092,7 @@ __global__ __launch_bounds__(256) void fill_bounded_kernel(const DevParams* __re
             if (x && !has_lay) continue;
             if (cv && !(P->can_convert[i] && has_dt && bf)) continue;
             const uint32_t child_bf = cv ? 0u : bf;
-            if (P->moves) {
+            if (moves) {
               // the alloc-binding: m(src) + m(dest), the load Move Spec (operands that are read), the
               // body, the store Move Spec (operands that are written); the operand is rows x cols
               const uint32_t ri = i == 1 ? S.si[2] : S.si[1], ci = i == 0 ? S.si[2] : S.si[3];
@@ -1227,24 +1232,29 @@ __global__ __launch_bounds__(256) void fill_bounded_kernel(const DevParams* __re
   // rewrites evaluated (and Specs that fit): one atomic each per workgroup
   uint32_t n_rw = e.n;
 #pragma unroll
-  for (int d = 32; d > 0; d >>= 1) { n_rw += __shfl_down(n_rw, d, 64); n_adm += __shfl_down(n_adm, d, 64); }
+  for (int d = 32; d > 0; d >>= 1) {
+    n_rw += __shfl_down(n_rw, d, 64);
+    if (MODE == 2) n_adm += __shfl_down(n_adm, d, 64);
+  }
   if ((threadIdx.x & 63u) == 0) { wave_n[threadIdx.x >> 6] = n_rw; wave_adm[threadIdx.x >> 6] = n_adm; }
   __syncthreads();
   if (threadIdx.x == 0) {
     const uint32_t n = wave_n[0] + wave_n[1] + wave_n[2] + wave_n[3];
     if (n) atomicAdd(&ctr->n_rewrites[blockIdx.x % kCtrSlots], (unsigned long long)n);
     const uint32_t na = wave_adm[0] + wave_adm[1] + wave_adm[2] + wave_adm[3];
-    if (na) atomicAdd(&ctr->n_admissible[blockIdx.x % kCtrSlots], (unsigned long long)na);
+    if (MODE == 2 && na) atomicAdd(&ctr->n_admissible[blockIdx.x % kCtrSlots], (unsigned long long)na);
   }
   if (e.ovf) atomicOr(&ctr->overflow, e.ovf);
 }
 
 // One diagonal (or a part of it): n_blocks = segs.block0[segs.n].
-void launch_fill_bounded(const DevParams* P, const uint32_t* all_level_shapes, const BoundSegs& segs, uint64_t* cost,
+void launch_fill_bounded(const DevParams* P, int mode, const uint32_t* all_level_shapes, const BoundSegs& segs, uint64_t* cost,
                          uint16_t* arg, Counters* ctr, hipStream_t stream) {
   if (!segs.n || !segs.block0[segs.n]) return;
-  hipLaunchKernelGGL(fill_bounded_kernel, dim3(segs.block0[segs.n]), dim3(256), 0, stream, P, all_level_shapes, segs, cost,
-                     arg, ctr);
+  const dim3 grid(segs.block0[segs.n]);
+  if (mode == 1) hipLaunchKernelGGL(fill_bounded_kernel<1>, grid, dim3(256), 0, stream, P, all_level_shapes, segs, cost, arg, ctr);
+  else if (mode == 2) hipLaunchKernelGGL(fill_bounded_kernel<2>, grid, dim3(256), 0, stream, P, all_level_shapes, segs, cost, arg, ctr);
+  else hipLaunchKernelGGL(fill_bounded_kernel<0>, grid, dim3(256), 0, stream, P, all_level_shapes, segs, cost, arg, ctr);
 }
 
 void launch_plan(const DevParams* P, uint32_t n_shapes, uint32_t npass, uint32_t G, const uint32_t* level_shapes,
@@ -1267,14 +1277,19 @@ void launch_fill_level(const DevParams* P, uint32_t npass, uint32_t G, uint32_t 
                        uint32_t n_slice, const uint32_t* list_wide, uint32_t n_wide, uint64_t* cost, uint16_t* arg,
                        Counters* ctr, hipStream_t stream, hipStream_t wide_stream) {
   const uint32_t cap = fill_wave_cap(G), n = n_bigwhole + n_slice + n_small;
-  if (n >= kWideBelow)
+  static const uint32_t wide_below = getenv("MRL_WIDE_BELOW") ? (uint32_t)atoi(getenv("MRL_WIDE_BELOW")) : kWideBelow;
+  static const uint32_t big2_below = getenv("MRL_BIG2_BELOW") ? (uint32_t)atoi(getenv("MRL_BIG2_BELOW")) : 0u;
+  if (n >= wide_below)
     hipLaunchKernelGGL(fill_kernel<64>, dim3(n), dim3(64), unit_lds_bytes(cap, npass), stream, P, list_whole, n_stretch,
                        n_bigwhole, list_slice, n_slice, cap, cost, arg, ctr);
   else if (n)
     hipLaunchKernelGGL(fill_kernel<256>, dim3(n), dim3(256), unit_lds_bytes(cap, npass), stream, P, list_whole, n_stretch,
                        n_bigwhole, list_slice, n_slice, cap, cost, arg, ctr);
-  if (n_wide)
-    hipLaunchKernelGGL(fill_big_kernel, dim3(n_wide), dim3(kBigBlock), unit_lds_bytes(max_task, npass), wide_stream, P,
+  if (n_wide && n_wide < big2_below)
+    hipLaunchKernelGGL(fill_big_kernel<2 * kBigBlock>, dim3(n_wide), dim3(2 * kBigBlock), unit_lds_bytes(max_task, npass), wide_stream, P,
+                       list_wide, max_task, cost, arg, ctr);
+  else if (n_wide)
+    hipLaunchKernelGGL(fill_big_kernel<kBigBlock>, dim3(n_wide), dim3(kBigBlock), unit_lds_bytes(max_task, npass), wide_stream, P,
                        list_wide, max_task, cost, arg, ctr);
 }
 

@@ -149,9 +149,9 @@ FixedLayout fixed_layout(const Compiled& c) {
   return f;
 }
 
-// per box while merging: bcell, blen, alive, pred, next, pos, and for the dense copies of the live boxes
+// per box while merging: bcell, blen, alive, next, pos, and for the dense copies of the live boxes
 // cell2, len2, alive2, pos2; a flag per 256 boxes.  Per final box: fcell, flen, fv0, fv1
-size_t work_bytes(uint64_t nb) { return 5 * align_up(nb * 4) + 2 * align_up(nb * 16) + 3 * align_up(nb) + align_up((nb / 256 + 1) * 4); }
+size_t work_bytes(uint64_t nb) { return 5 * align_up(nb * 4) + 2 * align_up(nb * 16) + 2 * align_up(nb) + align_up((nb / 256 + 1) * 4); }
 size_t final_bytes(uint64_t nb) { return align_up(nb * 4) + align_up(nb * 16) + 2 * align_up(nb * 8); }
 
 uint32_t ipow(uint32_t b, uint32_t e) { uint32_t r = 1; while (e--) r *= b; return r; }
@@ -905,7 +905,7 @@ int32_t solve_impl(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_t
   struct ListWork {
     uint32_t *bcell, *next, *pos, *cell2, *pos2, *block_linked, *d_cnt;
     char *blen, *len2;
-    uint8_t *alive, *pred, *alive2;
+    uint8_t *alive, *alive2;
     const uint8_t* old_alive = nullptr;     // set by the compaction, with remap
     const uint32_t* remap = nullptr;
     uint32_t n = 0, q_next = 0;
@@ -932,7 +932,7 @@ int32_t solve_impl(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_t
   auto one_pass = [&](int which) {
     ListWork& W = LW[which];
     const uint32_t a = pass_axis[W.q_next++];
-    launch_axis_pass(g, a, ++W.stamp, which == 1, W.n, W.old_alive, W.remap, W.bcell, W.blen, W.alive, W.pred, W.next,
+    launch_axis_pass(g, a, ++W.stamp, which == 1, W.n, W.old_alive, W.remap, W.bcell, W.blen, W.alive, W.next,
                      W.block_linked, maskL[which], prefL[which], tab->d_cost, tab->d_arg, axis_sizes(a), stL[which]);
   };
   // first part: the boxes of pass 0 and the first generic pass, then (large lists) the compaction;
@@ -945,7 +945,6 @@ int32_t solve_impl(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_t
     W.bcell = (uint32_t*)w; w += align_up(nb * 4);
     W.blen = w; w += align_up(nb * 16);
     W.alive = (uint8_t*)w; w += align_up(nb);
-    W.pred = (uint8_t*)w; w += align_up(nb);
     W.next = (uint32_t*)w; w += align_up(nb * 4);
     W.pos = (uint32_t*)w; w += align_up(nb * 4);
     W.cell2 = (uint32_t*)w; w += align_up(nb * 4);
@@ -955,8 +954,7 @@ int32_t solve_impl(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_t
     W.block_linked = (uint32_t*)w;
     W.d_cnt = d_tot + 4 + which * 4;       // [0]: live boxes at the compaction; [2]: the final count
     W.n = (uint32_t)nb;
-    launch_make_boxes(g, a0, maskL[which], prefL[which], lineL[which], colL[which], a1, W.bcell, W.blen, W.alive, W.pred,
-                      stL[which]);
+    launch_make_boxes(g, a0, maskL[which], prefL[which], lineL[which], colL[which], a1, W.bcell, W.blen, W.alive, stL[which]);
     if (on_cells) W.q_next = 1;               // pass_axis[0] = a1 is done
     if (W.q_next < n_generic) {
       one_pass(which);

@@ -55,11 +55,11 @@ void launch_second_axis(const Geo& g, uint32_t a0, uint32_t a1, bool is_cost, co
 // col != nullptr: mask is launch_second_axis's mask2 and every box gets its chain's length on a1.
 void launch_make_boxes(const Geo& g, uint32_t a0, const unsigned long long* mask, const uint32_t* prefix,
                        const unsigned long long* line, const unsigned long long* col, uint32_t a1, uint32_t* bcell,
-                       void* blen, uint8_t* alive, uint8_t* pred, hipStream_t st);
+                       void* blen, uint8_t* alive, hipStream_t st);
 // One merge pass along axis a.  After a compaction the mask still ranks boxes by their old index:
 // old_alive / remap (the compaction's alive and pos) translate it; nullptr before.
 void launch_axis_pass(const Geo& g, uint32_t a, uint8_t stamp, bool is_cost, uint32_t n_boxes, const uint8_t* old_alive,
-                      const uint32_t* remap, const uint32_t* bcell, void* blen, uint8_t* alive, uint8_t* pred, uint32_t* next,
+                      const uint32_t* remap, const uint32_t* bcell, void* blen, uint8_t* alive, uint32_t* next,
                       uint32_t* block_linked, const unsigned long long* mask, const uint32_t* prefix, const uint64_t* cost,
                       const uint16_t* arg, const uint32_t* axis_sizes, hipStream_t st);
 // The trailing passes over axes of extent 2 whose stride is at most 32 cells, in pass order.

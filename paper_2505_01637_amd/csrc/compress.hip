@@ -181,6 +181,11 @@ __global__ __launch_bounds__(256) void head_flags_wave_kernel(Geo g, uint32_t a0
   }
 }
 
+// alive[b]: 0 once box b has been merged into another; else kLive | the stamp of the last pass in
+// which a box linked to it (one byte for both: a live box stays live when it is linked to, so the
+// linking thread can store the whole byte, and a byte less per box is written when the boxes are made).
+constexpr uint8_t kLive = 0x80;
+
 // ---------------------------------------------------------------- prefix sums
 struct LoadPopc {
   const unsigned long long* p;
@@ -188,7 +193,7 @@ struct LoadPopc {
 };
 struct LoadFlag {
   const uint8_t* p;
-  __device__ __forceinline__ uint32_t operator()(uint32_t i) const { return p[i]; }
+  __device__ __forceinline__ uint32_t operator()(uint32_t i) const { return p[i] ? 1u : 0u; }
 };
 
 constexpr uint32_t kScanItems = 8, kScanBlock = 256, kScanTile = kScanItems * kScanBlock;
@@ -295,7 +300,7 @@ __global__ __launch_bounds__(256) void compact_boxes_kernel(uint32_t n, const ui
   const uint32_t j = pos[b];
   cell2[j] = bcell[b];
   len2[j] = blen[b];
-  alive2[j] = 1;
+  alive2[j] = kLive;
 }
 
 void launch_compact_boxes(uint32_t n, const uint8_t* alive, const uint32_t* pos, const uint32_t* bcell, const void* blen,
@@ -313,7 +318,7 @@ __global__ __launch_bounds__(256) void make_boxes_kernel(Geo g, uint32_t a0,
                                                          const unsigned long long* __restrict__ mask,
                                                          const uint32_t* __restrict__ prefix,
                                                          uint32_t* __restrict__ bcell, uint4* __restrict__ blen,
-                                                         uint8_t* __restrict__ alive, uint8_t* __restrict__ pred) {
+                                                         uint8_t* __restrict__ alive) {
   const uint32_t s0 = g.stride[a0], e0 = g.ext[a0];
   const uint32_t word0 = (blockIdx.x * 4u + (threadIdx.x >> 6)) * kCellWords;
   for (uint32_t wi = 0; wi < kCellWords; wi++) {
@@ -356,8 +361,7 @@ __global__ __launch_bounds__(256) void make_boxes_kernel(Geo g, uint32_t a0,
     L[3] = (a0 >> 2) == 3 ? w : L[3];
     bcell[id] = cell;
     blen[id] = make_uint4(L[0], L[1], L[2], L[3]);
-    alive[id] = 1;
-    pred[id] = 0;
+    alive[id] = kLive;
   }
 }
 
@@ -379,7 +383,7 @@ __global__ __launch_bounds__(256) void make_boxes_wave_kernel(Geo g, uint32_t a0
                                                               const unsigned long long* __restrict__ line,
                                                               const unsigned long long* __restrict__ col, uint32_t a1,
                                                               uint32_t* __restrict__ bcell, uint4* __restrict__ blen,
-                                                              uint8_t* __restrict__ alive, uint8_t* __restrict__ pred) {
+                                                              uint8_t* __restrict__ alive) {
   const uint32_t lane = threadIdx.x & 63u;
   const uint32_t w0 = (blockIdx.x * 4u + (threadIdx.x >> 6)) * wpw;
   if (w0 >= n_words) return;
@@ -445,8 +449,7 @@ __global__ __launch_bounds__(256) void make_boxes_wave_kernel(Geo g, uint32_t a0
         }
         bcell[id[u]] = cell[u];
         blen[id[u]] = make_uint4(L[0], L[1], L[2], L[3]);
-        alive[id[u]] = 1;
-        pred[id[u]] = 0;
+        alive[id[u]] = kLive;
       }
     }
   }
@@ -572,7 +575,7 @@ __global__ __launch_bounds__(256) void link_kernel(Geo g, uint32_t a, uint8_t st
                                                    const uint8_t* __restrict__ old_alive,
                                                    const uint32_t* __restrict__ remap,
                                                    const uint32_t* __restrict__ bcell, const uint4* __restrict__ blen,
-                                                   const uint8_t* __restrict__ alive, uint8_t* __restrict__ pred,
+                                                   uint8_t* alive,
                                                    uint32_t* __restrict__ next, uint32_t* __restrict__ block_linked,
                                                    const unsigned long long* __restrict__ mask,
                                                    const uint32_t* __restrict__ prefix,
@@ -605,7 +608,7 @@ __global__ __launch_bounds__(256) void link_kernel(Geo g, uint32_t a, uint8_t st
             const uint4 L = blen[b], M = blen[o];     // equal on a as well: both 1
             if (L.x == M.x && L.y == M.y && L.z == M.z && L.w == M.w) {
               nxt = o;
-              pred[o] = stamp;
+              alive[o] = kLive | stamp;
             }
           }
         }
@@ -619,14 +622,14 @@ __global__ __launch_bounds__(256) void link_kernel(Geo g, uint32_t a, uint8_t st
 
 __global__ __launch_bounds__(256) void absorb_kernel(uint32_t a, uint8_t stamp, uint32_t n_boxes,
                                                      uint8_t* __restrict__ blen_bytes,
-                                                     uint8_t* __restrict__ alive, const uint8_t* __restrict__ pred,
+                                                     uint8_t* alive,
                                                      const uint32_t* __restrict__ next,
                                                      const uint32_t* __restrict__ block_linked) {
   if (!block_linked[blockIdx.x]) return;       // no box of this workgroup got a successor: no chain starts here
   const uint32_t b = blockIdx.x * 256u + threadIdx.x;
   if (b >= n_boxes) return;
   uint32_t s = next[b];
-  if (s == 0xFFFFFFFFu || !alive[b] || pred[b] == stamp) return;   // only heads of chains of two or more
+  if (s == 0xFFFFFFFFu || !alive[b] || alive[b] == (kLive | stamp)) return;   // only heads of chains of two or more
   uint32_t tot = blen_bytes[(size_t)b * 16 + a];
   for (; s != 0xFFFFFFFFu; s = next[s]) {
     tot += blen_bytes[(size_t)s * 16 + a];
@@ -665,30 +668,30 @@ void launch_second_axis(const Geo& g, uint32_t a0, uint32_t a1, bool is_cost, co
 
 void launch_make_boxes(const Geo& g, uint32_t a0, const unsigned long long* mask, const uint32_t* prefix,
                        const unsigned long long* line, const unsigned long long* col, uint32_t a1, uint32_t* bcell,
-                       void* blen, uint8_t* alive, uint8_t* pred, hipStream_t st) {
+                       void* blen, uint8_t* alive, hipStream_t st) {
   if (g.stride[a0] % 64 == 0) {
     const uint32_t n_words = g.n / 64;
     const uint32_t wpw = words_per_wave(n_words);
     hipLaunchKernelGGL(make_boxes_wave_kernel, dim3((n_words + 4 * wpw - 1) / (4 * wpw)), dim3(256), 0, st, g, a0, n_words, wpw, mask, prefix,
-                       line, col, a1, bcell, (uint4*)blen, alive, pred);
+                       line, col, a1, bcell, (uint4*)blen, alive);
   } else {
     hipLaunchKernelGGL(make_boxes_kernel, dim3((g.n + 256 * kCellWords - 1) / (256 * kCellWords)), dim3(256), 0, st, g, a0, mask, prefix, bcell,
-                       (uint4*)blen, alive, pred);
+                       (uint4*)blen, alive);
   }
 }
 
 void launch_axis_pass(const Geo& g, uint32_t a, uint8_t stamp, bool is_cost, uint32_t n_boxes, const uint8_t* old_alive,
-                      const uint32_t* remap, const uint32_t* bcell, void* blen, uint8_t* alive, uint8_t* pred, uint32_t* next,
+                      const uint32_t* remap, const uint32_t* bcell, void* blen, uint8_t* alive, uint32_t* next,
                       uint32_t* block_linked, const unsigned long long* mask, const uint32_t* prefix, const uint64_t* cost,
                       const uint16_t* arg, const uint32_t* axis_sizes, hipStream_t st) {
   const uint32_t blocks = (n_boxes + 255) / 256;
   if (is_cost)
     hipLaunchKernelGGL(link_kernel<true>, dim3(blocks), dim3(256), 0, st, g, a, stamp, n_boxes, old_alive, remap, bcell,
-                       (const uint4*)blen, alive, pred, next, block_linked, mask, prefix, cost, arg, axis_sizes);
+                       (const uint4*)blen, alive, next, block_linked, mask, prefix, cost, arg, axis_sizes);
   else
     hipLaunchKernelGGL(link_kernel<false>, dim3(blocks), dim3(256), 0, st, g, a, stamp, n_boxes, old_alive, remap, bcell,
-                       (const uint4*)blen, alive, pred, next, block_linked, mask, prefix, cost, arg, axis_sizes);
-  hipLaunchKernelGGL(absorb_kernel, dim3(blocks), dim3(256), 0, st, a, stamp, n_boxes, (uint8_t*)blen, alive, pred, next,
+                       (const uint4*)blen, alive, next, block_linked, mask, prefix, cost, arg, axis_sizes);
+  hipLaunchKernelGGL(absorb_kernel, dim3(blocks), dim3(256), 0, st, a, stamp, n_boxes, (uint8_t*)blen, alive, next,
                      block_linked);
 }
 
@@ -792,9 +795,18 @@ void launch_tail_pairs(const TailAxes& T, bool is_cost, uint32_t n_words, const 
 }
 
 // ---------------------------------------------------------------- final lists
+// Binary gcd (shifts and subtractions: a 64-bit remainder is a long software routine here).
 __device__ __forceinline__ uint64_t gcd_u64(uint64_t a, uint64_t b) {
-  while (b) { uint64_t t = a % b; a = b; b = t; }
-  return a;
+  if (a == 0) return b;
+  if (b == 0) return a;
+  const int shift = __builtin_ctzll(a | b);
+  a >>= __builtin_ctzll(a);
+  do {
+    b >>= __builtin_ctzll(b);
+    if (a > b) { const uint64_t t = a; a = b; b = t; }
+    b -= a;
+  } while (b);
+  return a << shift;
 }
 
 template <bool COST>

@@ -57,6 +57,59 @@ def measured_traffic(config, table):
         return None, None
 
 
+def bench_slabs(args, cfg, target, torch, B, W, dev):
+    """The fused lattice in slabs along k (no rewrite of a fused Spec changes k): M and E as usual,
+    then one mrl_solve per slab into the same table and scratch buffers; a slab's box lists are
+    what is kept of it.  Reports the time of a step and the device memory the tables and the
+    scratch buffers take, beside what the whole fused table would take."""
+    lats = {label: lat for label, lat, _ in cfg["lattices"]}
+    assert set(lats) == {"M", "E", "F"}, "--slabs needs the three tables of config 5"
+    ks = lats["F"]["sizes"][2]
+    per = -(-len(ks) // args.slabs)
+    slabs = [dict(lats["F"], sizes=[lats["F"]["sizes"][0], lats["F"]["sizes"][1], ks[lo:lo + per], lats["F"]["sizes"][3]])
+             for lo in range(0, len(ks), per)]
+    n_slab = max(W.n_specs(cfg["target"], sl) for sl in slabs)
+    bufs = {}
+    for label in ("M", "E"):
+        cb, ab, sb = B.table_bytes(target, lats[label])
+        bufs[label] = tuple(torch.empty(x, dtype=torch.uint8, device=dev) for x in (cb, ab, min(sb, 1 << 30)))
+    slab_scratch = int(args.scratch_gb * (1 << 30))
+    slab_bufs = (torch.empty(8 * n_slab, dtype=torch.uint8, device=dev), torch.empty(2 * n_slab, dtype=torch.uint8, device=dev),
+                 torch.empty(slab_scratch, dtype=torch.uint8, device=dev))
+    sizes = {label: W.n_specs(cfg["target"], lats[label]) for label in lats}
+
+    def step():
+        tabs = B.solve_lattices(target, [j for j in cfg["lattices"] if j[0] != "F"], buffers=bufs)
+        out = []
+        for sl in slabs:
+            t = B.solve(target, sl, deps=(tabs["M"], tabs["E"]), buffers=slab_bufs)
+            out.append(t.stats.as_dict())
+            t.close()
+        return out
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        stats = step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    total = sum(sizes.values())
+    print(json.dumps({
+        "metric": "specs solved/sec (full lattice fill + compression, 1 GPU)", "value": total / (ms * 1e-3), "unit": "specs/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "u64", "data": "synthetic",
+        "config": {"workload": "config %d, the fused table in %d slabs along k: %s" % (
+            args.config, len(slabs), ", ".join("%s %d specs" % (l, n) for l, n in sizes.items())), "seed": args.config},
+        "slabs": {"n": len(slabs), "specs_of_largest": n_slab,
+                  "fused_table_and_scratch_bytes": 10 * n_slab + max(s["scratch_used"] for s in stats),
+                  "whole_fused_table_bytes": 10 * sizes["F"],
+                  "fill_ms": sum(s["fill_ms"] for s in stats), "compress_ms": sum(s["compress_ms"] for s in stats),
+                  "decision_boxes": sum(s["n_decision_boxes"] for s in stats), "cost_boxes": sum(s["n_cost_boxes"] for s in stats)},
+        "roofline": None, "cpu_baseline": None}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -70,6 +123,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-only", action="store_true",
                     help="time the oracle on the smaller sample of the workload only (about 15 s instead of 2 minutes)")
+    ap.add_argument("--slabs", type=int, default=0,
+                    help="config 5 only: solve the fused lattice in this many slabs along k, one after the other into the "
+                         "same buffers (a lattice too large for one table); prints that run's line instead of the default one")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch a 1 GiB read-only kernel, a 1 GiB fill and a 1 GiB copy (to scale rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -89,6 +145,8 @@ def main():
 
     cfg = W.config(args.config, seed=args.seed, max_size=args.max_size)
     target = B.Target(cfg["target"])
+    if args.slabs:
+        return bench_slabs(args, cfg, target, torch, B, W, dev)
     scratch = torch.empty(int(args.scratch_gb * (1 << 30)), dtype=torch.uint8, device=dev)
     bufs = {}
     for label, lat, _ in cfg["lattices"]:

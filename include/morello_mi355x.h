@@ -112,6 +112,10 @@ void mrl_target_destroy(mrl_target* t);
  * written); b and k must be pinned to 1.  FUSED_MM_ADD_RELU (Section 2.1,
  * Matmul -> bias add -> ReLU split once by bufferize): lhs, rhs, bias (read),
  * out (written), intermediate m*n f32; b pinned to 1; only m and n are tiled.
+ * Its k list need not start with 1: no rewrite of a fused Spec changes k, so the
+ * lattice may cover any stretch of consecutive entries of its MATMUL_ACCUM
+ * dep's k list (a slab; the slabs of a lattice too large for one table can be
+ * solved one after the other into the same buffers).
  * Where the FUSED lattice has a layout coordinate (lhs, rhs, out), the dep in
  * which that tensor is looked up must have one too (MRL_E_INVAL else).
  * MATMUL_PARALLEL (Section 2.2: the serial-only flag; Section 3: the loop
@@ -173,7 +177,7 @@ typedef enum { MRL_KIND_MATMUL_ACCUM = 0, MRL_KIND_BIAS_ADD_RELU = 1,
 typedef struct {
   uint32_t kind;
   uint32_t n_sizes[4];                        /* 1..MRL_MAX_SIZES each                        */
-  const uint32_t* sizes[4];                   /* host; ascending, sizes[d][0] == 1            */
+  const uint32_t* sizes[4];                   /* host; ascending, sizes[d][0] == 1 (but see FUSED) */
   uint8_t layout_coord[MRL_MAX_OPERANDS];     /* layout and dtype bits together: at most 4    */
   uint8_t dtype_coord[MRL_MAX_OPERANDS];      /* inputs of a Matmul, both tensors of a MOVE   */
   uint8_t base_dtype_bytes[MRL_MAX_OPERANDS]; /* 4 or 2; used when the operand has no dtype bit */

@@ -118,6 +118,7 @@ typedef struct ctx {
   int overflow;
   const struct ctx* depM;
   const struct ctx* depE;
+  uint32_t k_first;             /* kind F: where this lattice's k list starts within depM's */
 } ctx;
 
 /* ------------------------------------------------------------------ */
@@ -143,7 +144,10 @@ static int ctx_init(ctx* c, const orc_target* T, const orc_lattice* L) {
   int d = 0;
   c->maxs = 0;
   for (int a = 0; a < 4; a++) {
-    if (L->n_sizes[a] < 1 || L->sizes[a][0] != 1) return -1;
+    /* every list starts with 1, except the k list of a fused lattice: no rewrite of a fused Spec
+     * changes k, so a fused lattice may cover any stretch of k values (a slab of the whole one) */
+    if (L->n_sizes[a] < 1) return -1;
+    if (L->sizes[a][0] != 1 && !(a == 2 && (L->kind == KIND_F || L->kind == KIND_BF))) return -1;
     for (uint32_t j = 1; j < L->n_sizes[a]; j++)
       if (L->sizes[a][j] <= L->sizes[a][j - 1]) return -1;
     c->ext[d++] = L->n_sizes[a];
@@ -468,6 +472,7 @@ static void expand(ctx* c, const spec_t* s, uint64_t* best_out, uint16_t* arg_ou
     spec_t ms; memset(&ms, 0, sizeof ms);
     spec_t es; memset(&es, 0, sizeof es);
     for (int a = 0; a < 4; a++) ms.si[a] = s->si[a];
+    ms.si[2] += c->k_first;
     ms.level[0] = s->level[0]; ms.level[1] = s->level[1]; ms.level[2] = s->level[4];
     ms.layout[0] = s->layout[0]; ms.layout[1] = s->layout[1]; ms.layout[2] = 0;
     es.si[1] = s->si[1]; es.si[3] = s->si[3];
@@ -560,7 +565,15 @@ int orc_solve(const orc_target* T, const orc_lattice* L,
     /* a tensor whose layout the fused lattice distinguishes must have that coordinate in the table it is looked up in */
     if ((c.lay_axis[0] >= 0 && cm.lay_axis[0] < 0) || (c.lay_axis[1] >= 0 && cm.lay_axis[1] < 0) ||
         (c.lay_axis[3] >= 0 && ce.lay_axis[2] < 0)) return -1;
-    for (int d = 1; d < 4; d++) if (!same_sizes(L, d, LM, d)) return -1;
+    if (!same_sizes(L, 1, LM, 1) || !same_sizes(L, 3, LM, 3)) return -1;
+    {
+      /* the k list: a stretch of consecutive entries of the Matmul table's */
+      uint32_t o = 0;
+      while (o < LM->n_sizes[2] && LM->sizes[2][o] != L->sizes[2][0]) o++;
+      if (o + L->n_sizes[2] > LM->n_sizes[2]) return -1;
+      if (memcmp(LM->sizes[2] + o, L->sizes[2], L->n_sizes[2] * sizeof(uint32_t))) return -1;
+      c.k_first = o;
+    }
     if (LM->n_sizes[0] != 1) return -1;
     if (!same_sizes(L, 1, LE, 1) || !same_sizes(L, 3, LE, 3)) return -1;
     for (int i = 0; i < 3; i++) if (cm.dt_axis[i] >= 0 || LM->base_dtype_bytes[i] != 4) return -1;

@@ -222,7 +222,8 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
     uint32_t n = L->n_sizes[d];
     if (n < 1 || n > MRL_MAX_SIZES || !L->sizes[d]) return fail(MRL_E_INVAL, "n_sizes[%d] must be 1..%d", d, MRL_MAX_SIZES);
     c.sizes[d].assign(L->sizes[d], L->sizes[d] + n);
-    if (c.sizes[d][0] != 1) return fail(MRL_E_INVAL, "sizes[%d] must start with 1", d);
+    // (no rewrite of a fused Spec changes k: a fused lattice may cover any stretch of k values)
+    if (c.sizes[d][0] != 1 && !(d == 2 && kind == kKindF)) return fail(MRL_E_INVAL, "sizes[%d] must start with 1", d);
     for (uint32_t j = 1; j < n; j++)
       if (c.sizes[d][j] <= c.sizes[d][j - 1]) return fail(MRL_E_INVAL, "sizes[%d] must be strictly ascending", d);
     c.lat.sizes[d] = c.sizes[d].data();
@@ -683,7 +684,15 @@ int32_t solve_impl(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_t
         (P.lay_bit[3] != kNoBit && E.P.lay_bit[2] == kNoBit))
       return fail(MRL_E_INVAL, "a tensor with a layout coordinate in the FUSED lattice needs one in the dep it is looked up in");
     if (memcmp(&M.target, &t->d, sizeof t->d) || memcmp(&E.target, &t->d, sizeof t->d)) return fail(MRL_E_INVAL, "deps were solved for another target");
-    for (int d = 1; d < 4; d++) if (M.sizes[d] != c.sizes[d]) return fail(MRL_E_INVAL, "MATMUL_ACCUM dep has other size lists");
+    if (M.sizes[1] != c.sizes[1] || M.sizes[3] != c.sizes[3]) return fail(MRL_E_INVAL, "MATMUL_ACCUM dep has other size lists");
+    {
+      // the k list: the dep's, or a stretch of consecutive entries of it (a slab of the whole lattice)
+      const auto at = std::find(M.sizes[2].begin(), M.sizes[2].end(), c.sizes[2][0]);
+      if ((size_t)(M.sizes[2].end() - at) < c.sizes[2].size() || !std::equal(c.sizes[2].begin(), c.sizes[2].end(), at))
+        return fail(MRL_E_INVAL, "the k list must be a stretch of the MATMUL_ACCUM dep's k list");
+      P.kM_first = (uint32_t)(at - M.sizes[2].begin());
+      P.nkM = (uint32_t)M.sizes[2].size();
+    }
     if (M.sizes[0].size() != 1) return fail(MRL_E_INVAL, "MATMUL_ACCUM dep must have b pinned to 1");
     if (E.sizes[1] != c.sizes[1] || E.sizes[3] != c.sizes[3]) return fail(MRL_E_INVAL, "BIAS_ADD_RELU dep has other size lists");
     if (M.P.ndt || M.P.base_bf16[0] || M.P.base_bf16[1] || M.P.base_bf16[2]) return fail(MRL_E_INVAL, "MATMUL_ACCUM dep must be f32");

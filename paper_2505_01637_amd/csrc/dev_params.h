@@ -91,6 +91,7 @@ struct DevParams {
   const uint64_t* costM;
   const uint64_t* costE;
   uint32_t GM, VM, GE, VE, nszE_n;
+  uint32_t kM_first, nkM;    // a FUSED lattice's k list starts at entry kM_first of costM's table's, which has nkM entries
   uint32_t layM[3], layE[3]; // layout bit positions in the dependency's variant index
 };
 

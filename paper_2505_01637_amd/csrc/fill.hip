@@ -394,7 +394,7 @@ __device__ __forceinline__ void task_bufferize(const DevParams* __restrict__ P, 
   const uint32_t xm = ((l0 * NL + l1) * NL + pass) * P->VM +
                       (P->layM[0] != kNoBit ? y0 << P->layM[0] : 0u) + (P->layM[1] != kNoBit ? y1 << P->layM[1] : 0u);
   const uint32_t xe = ((pass * NL + l2) * NL + l3) * P->VE + (P->layE[2] != kNoBit ? y3 << P->layE[2] : 0u);
-  const uint64_t cm = P->costM[(uint64_t)shape * P->GM + xm];
+  const uint64_t cm = P->costM[(uint64_t)((S.si[1] * P->nkM + S.si[2] + P->kM_first) * P->nsz[3] + S.si[3]) * P->GM + xm];
   const uint64_t ce = P->costE[(uint64_t)(S.si[1] * P->nszE_n + S.si[3]) * P->GE + xe];
   const uint32_t zc = pass == 0 ? P->zero[0] : pass == 1 ? P->zero[1] : pass == 2 ? P->zero[2] : P->zero[3];
   if (cm != kInf && ce != kInf) {
@@ -1214,7 +1214,7 @@ __global__ __launch_bounds__(256) void fill_bounded_kernel(const DevParams* __re
         const uint32_t ve = P->layE[2] != kNoBit ? y3 << P->layE[2] : 0u;
         const uint32_t xm = (((lv[0] * NL + lv[1]) * NL + pass) * Q + qc) * P->VM + vm;
         const uint32_t xe = (((pass * NL + lv[2]) * NL + lv[3]) * Q + qc) * P->VE + ve;
-        const uint64_t cm = P->costM[(uint64_t)shape * P->GM + xm];
+        const uint64_t cm = P->costM[(uint64_t)((S.si[1] * P->nkM + S.si[2] + P->kM_first) * P->nsz[3] + S.si[3]) * P->GM + xm];
         const uint64_t ce = P->costE[(uint64_t)(S.si[1] * P->nszE_n + S.si[3]) * P->GE + xe];
         const uint32_t zc = pass == 0 ? P->zero[0] : pass == 1 ? P->zero[1] : pass == 2 ? P->zero[2] : P->zero[3];
         if (cm != kInf && ce != kInf) {

@@ -76,6 +76,64 @@ def test_parity_config5_full_size():
     # lookups in the box lists at full size: sampled coordinates against the oracle's dense table
     for label in "MEF":
         check_compressed_queries(got[label], want[label], 200_000, seed=5)
+    # the fused table once more, in eight k-slabs solved one after the other into the same buffers
+    # (an eighth of the whole table's, and 1 GiB of scratch), against the slices of the oracle's table
+    cfg = W.config(5)
+    solve_fused_in_slabs(cfg, got, want, 8, boxes=False, scratch_bytes=1 << 30)
+
+
+def solve_fused_in_slabs(cfg, tabs, want, n_slabs, boxes=True, scratch_bytes=None):
+    """Solve the fused lattice of `cfg` slab by slab along k (against the solved tables M and E in
+    `tabs`), every slab into the same device buffers, and compare every slab with the slice of
+    the oracle's whole table `want["F"]` (and, boxes=True, its box lists with those of the
+    oracle's merge of that slice)."""
+    import torch
+    B = _binding()
+    latF = next(lat for label, lat, _ in cfg["lattices"] if label == "F")
+    ks = latF["sizes"][2]
+    per = -(-len(ks) // n_slabs)
+    ext = want["F"]["extents"]
+    full_c = want["F"]["cost"].reshape(ext)
+    full_a = want["F"]["argmin"].reshape(ext)
+    target = tabs["F"].target
+    dev = torch.device("cuda", torch.cuda.current_device())
+    n_slab_max = W.n_specs(cfg["target"], dict(latF, sizes=[latF["sizes"][0], latF["sizes"][1], ks[:per], latF["sizes"][3]]))
+    bufs = (torch.empty(8 * n_slab_max, dtype=torch.uint8, device=dev), torch.empty(2 * n_slab_max, dtype=torch.uint8, device=dev),
+            torch.empty(scratch_bytes or max(1 << 28, 16 * n_slab_max), dtype=torch.uint8, device=dev))
+    n_rw = n_adm = 0
+    for lo in range(0, len(ks), per):
+        hi = min(lo + per, len(ks))
+        slab = dict(latF, sizes=[latF["sizes"][0], latF["sizes"][1], ks[lo:hi], latF["sizes"][3]])
+        print("slab k =", ks[lo:hi], flush=True)
+        tab = B.solve(target, slab, deps=(tabs["M"], tabs["E"]), buffers=bufs)
+        cost, arg = tab.dense()
+        want_c = np.ascontiguousarray(full_c[:, :, lo:hi]).ravel()
+        want_a = np.ascontiguousarray(full_a[:, :, lo:hi]).ravel()
+        assert np.array_equal(cost, want_c) and np.array_equal(arg, want_a)
+        n_rw += tab.stats.n_rewrites
+        n_adm += tab.stats.n_admissible
+        if boxes:
+            dec, cst = O.compress_table(cfg["target"], slab, want_c, want_a)
+            assert tab.boxes(0).tobytes() == dec.tobytes() and tab.boxes(1).tobytes() == cst.tobytes()
+        check_compressed_queries(tab, {"cost": want_c, "argmin": want_a}, 20_000, seed=lo)
+        tab.close()
+    assert n_rw == want["F"]["n_rewrites"] and n_adm == want["F"]["n_admissible"]
+
+
+@pytest.mark.parametrize("max_size,n_slabs", [(16, 2), (16, 7), (8, 4)])
+def test_fused_lattice_in_k_slabs(max_size, n_slabs):
+    """A fused lattice too large for one table can be solved in slabs along k (no rewrite of a
+    fused Spec changes k): every slab's table, counters and box lists against the oracle."""
+    cfg = W.config(5, max_size=max_size)
+    _, got, want = compare_config(cfg)
+    solve_fused_in_slabs(cfg, got, want, n_slabs)
+    # a k list that is no stretch of the Matmul table's is refused
+    B = _binding()
+    latF = cfg["lattices"][2][1]
+    with pytest.raises(B.MorelloError) as e:
+        B.solve(got["F"].target, dict(latF, sizes=[latF["sizes"][0], latF["sizes"][1], [1, 4], latF["sizes"][3]]),
+                deps=(got["M"], got["E"]))
+    assert e.value.code == B.E_INVAL
 
 
 def check_compressed_queries(tab, want, n_points, seed):

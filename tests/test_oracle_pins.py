@@ -383,3 +383,32 @@ def test_overflow_is_reported():
     t, lat = cfg["target"], cfg["lattices"][0][1]
     t["microkernels"] = [(W.MK_SCALAR_FMA, 1, 1 << 61)]
     assert O.solve(t, lat)["rc"] == -6
+
+
+def test_fused_lattice_in_k_slabs_equals_the_whole_lattice():
+    """No rewrite of a fused Spec changes k, so the fused lattice restricted to a stretch of k
+    values is closed: solved against the same Matmul and bias-add + ReLU tables, each such slab
+    must be the whole table's slice, entry by entry, and the counters must add up."""
+    cfg = W.config(5, max_size=8)
+    t = cfg["target"]
+    latM, latE, latF = (lat for _, lat, _ in cfg["lattices"])
+    res = O.solve_config(cfg)
+    ext = res["F"]["extents"]
+    full_c = res["F"]["cost"].reshape(ext)
+    full_a = res["F"]["argmin"].reshape(ext)
+    ks = latF["sizes"][2]
+    assert ks == [1, 2, 4, 8]
+    n_rw = n_adm = 0
+    for lo, hi in ((0, 2), (2, 3), (3, 4)):
+        slab = dict(latF, sizes=[latF["sizes"][0], latF["sizes"][1], ks[lo:hi], latF["sizes"][3]])
+        r = O.solve(t, slab, deps=((latM, res["M"]["cost"]), (latE, res["E"]["cost"])))
+        assert r["rc"] == 0 and r["extents"] == ext[:2] + [hi - lo] + ext[3:]
+        assert np.array_equal(r["cost"].reshape(r["extents"]), full_c[:, :, lo:hi])
+        assert np.array_equal(r["argmin"].reshape(r["extents"]), full_a[:, :, lo:hi])
+        n_rw += r["n_rewrites"]
+        n_adm += r["n_admissible"]
+    assert n_rw == res["F"]["n_rewrites"] and n_adm == res["F"]["n_admissible"]
+    # a k list that is no stretch of the Matmul table's is refused
+    with pytest.raises(ValueError):
+        O.solve(t, dict(latF, sizes=[latF["sizes"][0], latF["sizes"][1], [1, 4], latF["sizes"][3]]),
+                deps=((latM, res["M"]["cost"]), (latE, res["E"]["cost"])))

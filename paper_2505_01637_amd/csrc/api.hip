@@ -831,25 +831,44 @@ int32_t solve_impl(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_t
   HIP_TRY(hipEventRecord(ev[4], st));
   prefill_timed = true;
   HIP_TRY(hipEventSynchronize(counts_ready));
+  bool wide_started = false;
+  hipEvent_t wide_done = nullptr;          // recorded behind the last wide launch that the caller's stream has not waited for yet
   for (uint32_t l = 0; l < n_lev; l++) {
     const uint32_t first = c.level_off[l];
     const uint32_t n_small = cnt[l], n_slice = cnt[n_lev + l], n_wide = cnt[2 * n_lev + l], n_bigwhole = cnt[3 * n_lev + l];
     const uint32_t n_stretch = c.level_off[l + 1] - first;
     if (n_small + n_bigwhole > n_stretch || n_slice + n_wide > n_stretch * P.npass)
       return fail(MRL_E_HIP, "internal error: work lists of level %u overflow", l);
-    const bool fork = n_wide && (n_small + n_bigwhole + n_slice);     // both kinds of items: run them side by side
-    if (fork) {
-      HIP_TRY(hipEventRecord(aux->events[ev_used], st));
-      HIP_TRY(hipStreamWaitEvent(s2, aux->events[ev_used++], 0));
+    // The wide items (slices with more tasks than an LDS slice of a wave holds) run on the helper
+    // stream, level after level, without waiting for the other items: a tile of a wide slice
+    // leads to the same slice of a smaller shape, in which at least as much fits, so that one is
+    // wide as well, and wide items read nothing that the others write.  The others read entries
+    // of any kind, so a level's launch on the caller's stream waits for the wide items of all
+    // lower levels.  (With both kinds joined at every level the levels of the fused table took
+    // 1.49 ms, the wide items setting the pace of most of them.)
+    if (n_wide) {
+      if (!wide_started) {
+        HIP_TRY(hipEventRecord(aux->events[ev_used], st));
+        HIP_TRY(hipStreamWaitEvent(s2, aux->events[ev_used++], 0));
+        wide_started = true;
+      }
+      launch_fill_level(d_P, P.npass, P.G, c.max_task, d_list_whole + first, n_stretch, 0, 0,
+                        d_list_slice + (size_t)first * P.npass, 0, d_list_wide + (size_t)first * P.npass, n_wide,
+                        tab->d_cost, tab->d_arg, d_ctr, st, s2);
     }
-    launch_fill_level(d_P, P.npass, P.G, c.max_task, d_list_whole + first, n_stretch, n_small, n_bigwhole,
-                      d_list_slice + (size_t)first * P.npass, n_slice, d_list_wide + (size_t)first * P.npass, n_wide,
-                      tab->d_cost, tab->d_arg, d_ctr, st, fork ? s2 : st);
-    if (fork) {
+    if (n_small + n_bigwhole + n_slice) {
+      if (wide_done) { HIP_TRY(hipStreamWaitEvent(st, wide_done, 0)); wide_done = nullptr; }
+      launch_fill_level(d_P, P.npass, P.G, c.max_task, d_list_whole + first, n_stretch, n_small, n_bigwhole,
+                        d_list_slice + (size_t)first * P.npass, n_slice, d_list_wide + (size_t)first * P.npass, 0,
+                        tab->d_cost, tab->d_arg, d_ctr, st, st);
+    }
+    if (n_wide) {
+      // the next level's other items wait here
       HIP_TRY(hipEventRecord(aux->events[ev_used], s2));
-      HIP_TRY(hipStreamWaitEvent(st, aux->events[ev_used++], 0));
+      wide_done = aux->events[ev_used++];
     }
   }
+  if (wide_done) HIP_TRY(hipStreamWaitEvent(st, wide_done, 0));
   }
   HIP_TRY(hipGetLastError());
   HIP_TRY(hipEventRecord(ev[1], st));

@@ -23,13 +23,14 @@ from collections import namedtuple
 M, E, F, P = 0, 1, 2, 3      # P: a Matmul that may use parallel loops; M is serial-only
 BD, BE, BF = 4, 5, 6          # M, E, F whose Specs carry per-level memory bounds (Sections 2.2, 2.4.4)
 V, MV = 7, 8                  # V: Move Specs (Section 2.2); MV: a Matmul whose Moves are Move Specs
+G = 9                         # two composed Matmuls (Section 2.1): dims = (p, m, k, n); lhs m x k, rhs1 k x p, rhs2 p x n, out m x n
 BOUNDED = (BD, BE, BF)
 MATMULS = (M, P, BD, MV)
 
 
 def base_kind(kind):
     """The operator of a kind: M for the Matmuls, E, F, V."""
-    return M if kind in MATMULS else E if kind in (E, BE) else V if kind == V else F
+    return M if kind in MATMULS else E if kind in (E, BE) else kind if kind in (V, G) else F
 FMA, BCAST, BF16DOT, S_ADDRELU, V_ADDRELU = 0, 1, 2, 3, 4
 S_MOVE, V_MOVE, V_MOVE_ALIGNED = 5, 6, 7
 
@@ -48,6 +49,9 @@ def operand_numel(spec, i):
         return (m * n, n, m * n)[i]
     if spec.kind == V:
         return m * n
+    if spec.kind == G:
+        p = b
+        return (m * k, k * p, p * n, m * n, m * p)[i]
     return (m * k, k * n, n, m * n, m * n)[i]
 
 
@@ -57,6 +61,8 @@ def operand_mode(kind, i):
         return "rw" if i == 2 else "r"
     if base_kind(kind) == E:
         return "w" if i == 2 else "r"
+    if kind == G:
+        return "rw" if i == 3 else "r"     # the second Matmul accumulates
     return "w" if i == 3 else "r"
 
 
@@ -65,10 +71,10 @@ def fits(target, spec):
         return True          # the bounds decide at each allocation, not the operands' footprint;
                              # the two tensors of a Move exist already
     used = [0] * target["n_levels"]
-    nops = 4 if spec.kind == F else 3
+    nops = 4 if spec.kind in (F, G) else 3
     for i in range(nops):
         used[spec.levels[i]] += operand_numel(spec, i) * (2 if spec.bf16[i] else 4)
-    if spec.kind == F:
+    if spec.kind in (F, G):
         used[spec.levels[4]] += 4 * operand_numel(spec, 4)
     return all(u <= cap for u, cap in zip(used, target["capacity_bytes"]))
 
@@ -132,7 +138,7 @@ def rewrites(target, lattices, spec):
     applicable rewrite of an admissible Spec, ids ascending."""
     lattice = lattices[spec.kind]
     nl = target["n_levels"]
-    nops = 4 if base_kind(spec.kind) == F else 2 if spec.kind == V else 3
+    nops = 4 if base_kind(spec.kind) in (F, G) else 2 if spec.kind == V else 3
     nmk = len(target["microkernels"])
     maxs = max(len(s) for s in lattice["sizes"])
     move_base = nmk
@@ -204,7 +210,7 @@ def rewrites(target, lattices, spec):
                     rid = move_base + ((i * (nl - 1) + dst) * 2 + x) * 2 + cv
                     yield rid, ("alloc", coef * operand_numel(spec, i)), [child]
     for d in range(4):
-        if base_kind(spec.kind) in (E, F, V) and d in (0, 2):
+        if base_kind(spec.kind) in (E, F, V, G) and d in (0, 2):
             continue
         cur = spec.dims[d]
         for j, t in enumerate(lattice["sizes"][d]):
@@ -245,6 +251,15 @@ def rewrites(target, lattices, spec):
         mm = Spec(BD if bounded else M, (1, m, k, n), (l_lhs, l_rhs, l_mid, 0, 0), (y_lhs, y_rhs, 0, 0, 0), (0,) * 5, lim)
         ee = Spec(BE if bounded else E, (1, m, 1, n), (l_mid, l_bias, l_out, 0, 0), (0, 0, y_out, 0, 0), (0,) * 5, lim)
         yield tile_base + 4 * maxs, ("pipeline", target["zero_coef"][l_mid] * m * n), [mm, ee]
+
+
+    if spec.kind == G:
+        p, m, k, n = spec.dims
+        l_lhs, l_rhs1, l_rhs2, l_out, l_mid = spec.levels
+        y_lhs, y_rhs1, y_rhs2, y_out = spec.layouts[:4]
+        first = Spec(M, (1, m, k, p), (l_lhs, l_rhs1, l_mid, 0, 0), (y_lhs, y_rhs1, 0, 0, 0), (0,) * 5)
+        second = Spec(M, (1, m, p, n), (l_mid, l_rhs2, l_out, 0, 0), (0, y_rhs2, y_out, 0, 0), (0,) * 5)
+        yield tile_base + 4 * maxs, ("pipeline", target["zero_coef"][l_mid] * m * p), [first, second]
 
 
 def programs(target, lattices, spec):

@@ -38,6 +38,10 @@
  * whose Moves are those Specs: an alloc-binding costs m(src) + m(dest)
  * (Section 3, in cache lines) plus its children, the load and store Move
  * Specs among them (Section 2, Memory Movement).
+ * Kind 9 is the composition of two Matmuls of Section 2.1, treated like the
+ * fused lattice of kind 2: tiles of the output's dimensions, Moves of the
+ * four external operands, and one bufferize that splits it into two Matmul
+ * Specs around the intermediate.
  */
 #define _GNU_SOURCE             /* qsort_r */
 #include <stdint.h>
@@ -54,7 +58,8 @@ enum { MK_SCALAR_FMA = 0, MK_BCAST_VEC_MULADD = 1, MK_BF16_DOT = 2,
        MK_SCALAR_MOVE = 5, MK_VECTOR_MOVE = 6, MK_VECTOR_MOVE_ALIGNED = 7 };
 enum { KIND_M = 0, KIND_E = 1, KIND_F = 2, KIND_P = 3, KIND_B = 4, KIND_BE = 5, KIND_BF = 6,
        KIND_V = 7,    /* Move Specs */
-       KIND_MV = 8 }; /* a Matmul whose Moves are Move Specs of a kind 7 table */
+       KIND_MV = 8,   /* a Matmul whose Moves are Move Specs of a kind 7 table */
+       KIND_G = 9 };  /* composition of two Matmuls (Section 2.1): (lhs x rhs1) x rhs2 accumulated into out */
 enum { ACC_READ = 0, ACC_RMW = 1, ACC_WRITE = 2 };
 
 typedef struct {
@@ -129,7 +134,7 @@ typedef struct ctx {
 static int ctx_init(ctx* c, const orc_target* T, const orc_lattice* L) {
   memset(c, 0, sizeof *c);
   c->T = T; c->L = L; c->kind = (int)L->kind;
-  if (c->kind < 0 || c->kind > KIND_MV) return -1;
+  if (c->kind < 0 || c->kind > KIND_G) return -1;
   c->abs_axis = -1;
   if (c->kind == KIND_MV) { c->kind = KIND_M; c->moves = 1; }     /* same operator, operands and coordinates as kind M */
   if (c->kind >= KIND_B && c->kind <= KIND_BF) { c->kind -= KIND_B; c->bounded = 1; }   /* kinds 4, 5, 6: M, E, F with memory bounds */
@@ -138,8 +143,8 @@ static int ctx_init(ctx* c, const orc_target* T, const orc_lattice* L) {
     if (T->threads < 1) return -1;
   }
   if (T->n_levels < 1 || T->n_levels > ORC_MAXL) return -1;
-  c->nops = c->kind == KIND_F ? 4 : c->kind == KIND_V ? 2 : 3;
-  c->nlv = c->kind == KIND_F ? 5 : c->kind == KIND_V ? 2 : 3;
+  c->nops = c->kind == KIND_F || c->kind == KIND_G ? 4 : c->kind == KIND_V ? 2 : 3;
+  c->nlv = c->kind == KIND_F || c->kind == KIND_G ? 5 : c->kind == KIND_V ? 2 : 3;
   if ((c->kind == KIND_V || c->moves) && T->line_bytes < 1) return -1;
   int d = 0;
   c->maxs = 0;
@@ -153,7 +158,7 @@ static int ctx_init(ctx* c, const orc_target* T, const orc_lattice* L) {
     c->ext[d++] = L->n_sizes[a];
     if (L->n_sizes[a] > c->maxs) c->maxs = L->n_sizes[a];
   }
-  if (c->kind != KIND_M && L->n_sizes[0] != 1) return -1;   /* no batch on E, F */
+  if (c->kind != KIND_M && c->kind != KIND_G && L->n_sizes[0] != 1) return -1;   /* no batch on E, F (kind G keeps p there) */
   if ((c->kind == KIND_E || c->kind == KIND_V) && L->n_sizes[2] != 1) return -1;   /* E and V have no k */
   if (c->moves && L->n_sizes[0] != 1) return -1;            /* operands of a kind 8 Matmul are two-dimensional */
   for (int i = 0; i < c->nlv; i++) c->ext[d++] = T->n_levels;
@@ -178,6 +183,7 @@ static int ctx_init(ctx* c, const orc_target* T, const orc_lattice* L) {
   for (int i = 0; i < c->nops; i++)
     if (L->dtype_coord[i]) {
       if (!(c->kind == KIND_V || (c->kind == KIND_M && i != 2))) return -1;   /* inputs of a Matmul, tensors of a Move */
+      /* (kinds E, F, G: f32 throughout) */
       c->dt_axis[i] = d; c->ext[d++] = 2;
     }
   c->ndim = d;
@@ -244,12 +250,15 @@ static uint64_t numel(const ctx* c, const spec_t* s, int op) {
     case KIND_M: return op == 0 ? b * m * k : op == 1 ? b * k * n : b * m * n;
     case KIND_E: return op == 1 ? n : m * n;
     case KIND_V: return m * n;                                                    /* source and destination: rows x cols */
+    case KIND_G: /* b holds p, the dimension the two Matmuls share: lhs m x k, rhs1 k x p, rhs2 p x n, out m x n, mid m x p */
+      return op == 0 ? m * k : op == 1 ? k * b : op == 2 ? b * n : op == 3 ? m * n : m * b;
     default:     return op == 0 ? m * k : op == 1 ? k * n : op == 2 ? n : m * n; /* 3 = out, 4 = mid */
   }
 }
 
 static int access_of(const ctx* c, int op) {
   if (c->kind == KIND_M) return op == 2 ? ACC_RMW : ACC_READ;     /* accumulating output */
+  if (c->kind == KIND_G) return op == 3 ? ACC_RMW : ACC_READ;     /* the second Matmul accumulates into out */
   return op == c->nops - 1 ? ACC_WRITE : ACC_READ;
 }
 
@@ -263,7 +272,7 @@ static int admissible(const ctx* c, const spec_t* s) {
     unsigned __int128 bytes = 0;
     for (int i = 0; i < c->nops; i++)
       if (s->level[i] == l) bytes += (unsigned __int128)numel(c, s, i) * (s->bf16[i] ? 2 : 4);
-    if (c->kind == KIND_F && s->level[4] == l) bytes += (unsigned __int128)numel(c, s, 4) * 4;
+    if ((c->kind == KIND_F || c->kind == KIND_G) && s->level[4] == l) bytes += (unsigned __int128)numel(c, s, 4) * 4;
     if (c->T->capacity_bytes[l] != UINT64_MAX && bytes > c->T->capacity_bytes[l]) return 0;
   }
   return 1;
@@ -509,6 +518,28 @@ static void expand(ctx* c, const spec_t* s, uint64_t* best_out, uint16_t* arg_ou
     }
   }
 
+  /* D'. bufferize of two composed Matmuls (kind G, Section 2.1): the first Matmul writes the
+   * intermediate (m x p, f32, row-major, initialised first), the second accumulates its product
+   * with rhs2 into out.  Both are Specs of the Matmul table: (m, k, p) and (m, p, n). */
+  if (c->kind == KIND_G) {
+    spec_t m1; memset(&m1, 0, sizeof m1);
+    spec_t m2; memset(&m2, 0, sizeof m2);
+    m1.si[1] = s->si[1]; m1.si[2] = s->si[2]; m1.si[3] = s->si[0];            /* m, k, n := p */
+    m1.level[0] = s->level[0]; m1.level[1] = s->level[1]; m1.level[2] = s->level[4];
+    m1.layout[0] = s->layout[0]; m1.layout[1] = s->layout[1];
+    m2.si[1] = s->si[1]; m2.si[2] = s->si[0]; m2.si[3] = s->si[3];            /* m, k := p, n */
+    m2.level[0] = s->level[4]; m2.level[1] = s->level[2]; m2.level[2] = s->level[3];
+    m2.layout[1] = s->layout[2]; m2.layout[2] = s->layout[3];
+    uint64_t c1 = c->depM->cost[spec_index(c->depM, &m1)];
+    uint64_t c2 = c->depM->cost[spec_index(c->depM, &m2)];
+    uint64_t cand = ORC_INF;
+    if (c1 != ORC_INF && c2 != ORC_INF) {
+      unsigned __int128 v = (unsigned __int128)T->zero_coef[s->level[4]] * numel(c, s, 4) + c1 + c2;
+      if (v >= ORC_LIMIT) c->overflow = 1; else cand = (uint64_t)v;
+    }
+    consider(c, cand, c->buf_id, &best, &arg);
+  }
+
   /* E. parallel loop (kind P, Section 3: ceil(trips / threads) * c(body) + s).
    * The body is the serial-only Spec of the smaller shape (Section 2.2: the
    * flag limits an implementation to one hardware thread), so its cost comes
@@ -579,6 +610,19 @@ int orc_solve(const orc_target* T, const orc_lattice* L,
     for (int i = 0; i < 3; i++) if (cm.dt_axis[i] >= 0 || LM->base_dtype_bytes[i] != 4) return -1;
     cm.cost = (uint64_t*)costM; ce.cost = (uint64_t*)costE;
     c.depM = &cm; c.depE = &ce;
+  }
+  if (c.kind == KIND_G) {       /* both stages are Specs of one Matmul table */
+    if (!LM || !costM) return -1;
+    if (ctx_init(&cm, T, LM)) return -1;
+    if (cm.kind != KIND_M || cm.parallel || cm.bounded || cm.moves || LM->n_sizes[0] != 1) return -1;
+    /* m from m; the lists of k, p and n, and the table's k and n lists, must all be the same */
+    if (!same_sizes(L, 1, LM, 1) || !same_sizes(L, 2, LM, 2) || !same_sizes(L, 0, LM, 2) || !same_sizes(L, 0, LM, 3) ||
+        !same_sizes(L, 3, LM, 3)) return -1;
+    if ((c.lay_axis[0] >= 0 && cm.lay_axis[0] < 0) || (c.lay_axis[1] >= 0 && cm.lay_axis[1] < 0) ||
+        (c.lay_axis[2] >= 0 && cm.lay_axis[1] < 0) || (c.lay_axis[3] >= 0 && cm.lay_axis[2] < 0)) return -1;
+    for (int i = 0; i < 3; i++) if (cm.dt_axis[i] >= 0 || LM->base_dtype_bytes[i] != 4) return -1;
+    cm.cost = (uint64_t*)costM;
+    c.depM = &cm;
   }
   if (c.moves) {                /* the Move Specs: a kind V table over the same sizes */
     if (!LM || !costM) return -1;

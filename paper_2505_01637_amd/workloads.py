@@ -36,6 +36,8 @@ KIND_FUSED_BOUNDED = 6                # and for the fused Spec (reads the two bo
 BOUNDED_KINDS = (KIND_MATMUL_BOUNDED, KIND_BIAS_ADD_RELU_BOUNDED, KIND_FUSED_BOUNDED)
 KIND_MOVE = 7                 # Move Specs: source and destination tensor of rows x cols
 KIND_MATMUL_MOVES = 8         # a Matmul whose Moves are Move Specs; reads a KIND_MOVE table
+KIND_MATMUL_CHAIN = 9         # (lhs x rhs1) x rhs2 accumulated into out; sizes[0] holds p, the dimension the two share
+FIVE_LEVEL_KINDS = (KIND_FUSED_MM_ADD_RELU, KIND_FUSED_BOUNDED, KIND_MATMUL_CHAIN)   # four operands and an intermediate
 
 MAX_LEVELS = 4
 MAX_OPERANDS = 5
@@ -219,17 +221,29 @@ def config(number, seed=None, max_size=None):
         r = keep(range(1, 33))
         lats = [("V", _lattice(KIND_MOVE, [one, r, one, r], layout=(1, 1, 0, 0, 0)), []),
                 ("M", _lattice(KIND_MATMUL_MOVES, [one, r, r, r], layout=(1, 1, 1, 0, 0)), ["V"])]
+    elif number == 10:
+        # beyond the five benchmark configurations: the composition of two Matmuls.  Config 5's
+        # target recipe (transposing Moves, initialising the intermediate); power-of-two sizes
+        # 1..128 for m, k, p, n; the Matmul table over the same sizes and the lattice of
+        # compositions that reads it twice (4096 shapes x 1024 level assignments x 16 layouts = 67.1 M Specs)
+        t, w = _four_level_target(rng)
+        _add_transposed(t, rng)
+        t["zero_coef"] = list(w)
+        p2 = keep([1 << i for i in range(8)])
+        lats = [("M", _lattice(KIND_MATMUL_ACCUM, [one, p2, p2, p2], layout=(1, 1, 1, 0, 0)), []),
+                # operands: lhs (m x k), rhs1 (k x p), rhs2 (p x n), out (m x n) (+ level of the intermediate, m x p)
+                ("G", _lattice(KIND_MATMUL_CHAIN, [p2, p2, p2, p2], layout=(1, 1, 1, 1, 0)), ["M"])]
     else:
-        raise ValueError("config number must be 1..9")
+        raise ValueError("config number must be 1..10")
     return {"name": "config%d" % number, "target": t, "lattices": lats}
 
 
 def n_level_axes(kind):
-    return 5 if kind in (KIND_FUSED_MM_ADD_RELU, KIND_FUSED_BOUNDED) else 2 if kind == KIND_MOVE else 3
+    return 5 if kind in FIVE_LEVEL_KINDS else 2 if kind == KIND_MOVE else 3
 
 
 def n_operands(kind):
-    return 4 if kind in (KIND_FUSED_MM_ADD_RELU, KIND_FUSED_BOUNDED) else 2 if kind == KIND_MOVE else 3
+    return 4 if kind in FIVE_LEVEL_KINDS else 2 if kind == KIND_MOVE else 3
 
 
 def coord_extents(target, lattice):

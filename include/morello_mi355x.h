@@ -101,7 +101,7 @@ void mrl_target_destroy(mrl_target* t);
  * Lattice of Specs (Section 2.2 reduced to integer coordinates, Section 4.1).
  * Coordinate vector x, in this order:
  *   index of b, m, k, n in the allowed-size lists;
- *   memory level of each operand (kind FUSED: then the intermediate's level);
+ *   memory level of each operand (FUSED, MATMUL_CHAIN: then the intermediate's level);
  *   (the BOUNDED kinds: one memory-bound index per level of finite capacity;)
  *   one layout bit (0 row-major, 1 column-major) per operand with layout_coord;
  *   one dtype bit (0 f32, 1 bf16) per operand with dtype_coord.
@@ -168,11 +168,28 @@ void mrl_target_destroy(mrl_target* t);
  * n lists (which must be equal), with layout bits on both tensors if any
  * operand here has one and dtype bits on both if any operand here has one or
  * is bf16.  load_coef / store_coef / convert_coef are not used.
+ * MATMUL_CHAIN (Section 2.1: a Spec may be a composition of sub-Specs, split
+ * by bufferize into a pipeline around an intermediate tensor; Section 3: a
+ * pipeline costs the sum of its stages): (lhs x rhs1) x rhs2 accumulated into
+ * out.  sizes[0] holds p, the dimension the two Matmuls share, so x starts
+ * with the indices of p, m, k, n.  Operands: lhs (m*k, read), rhs1 (k*p,
+ * read), rhs2 (p*n, read), out (m*n, accumulated); then the level of the
+ * intermediate (m*p, f32, row-major), as for FUSED.  Rewrites: Moves of the
+ * four operands, tiles of m and n, and one bufferize (same id as FUSED's):
+ * zero_coef[level of the intermediate] * m*p + the MATMUL_ACCUM Spec (1, m,
+ * k, p) with out := the intermediate + the MATMUL_ACCUM Spec (1, m, p, n)
+ * with lhs := the intermediate.  A Spec is admissible when its operands and
+ * the intermediate fit their levels.  deps = {MATMUL_ACCUM table}, f32, b
+ * pinned to 1, whose m list equals this lattice's and whose k and n lists
+ * both equal this lattice's p, k and n lists (which must be equal); where an
+ * operand here has a layout coordinate, the position it takes in the dep
+ * (lhs, rhs1 -> lhs, rhs; rhs2, out -> rhs, out) must have one too.
  */
 typedef enum { MRL_KIND_MATMUL_ACCUM = 0, MRL_KIND_BIAS_ADD_RELU = 1,
                MRL_KIND_FUSED_MM_ADD_RELU = 2, MRL_KIND_MATMUL_PARALLEL = 3,
                MRL_KIND_MATMUL_BOUNDED = 4, MRL_KIND_BIAS_ADD_RELU_BOUNDED = 5,
-               MRL_KIND_FUSED_BOUNDED = 6, MRL_KIND_MOVE = 7, MRL_KIND_MATMUL_MOVES = 8 } mrl_kind;
+               MRL_KIND_FUSED_BOUNDED = 6, MRL_KIND_MOVE = 7, MRL_KIND_MATMUL_MOVES = 8,
+               MRL_KIND_MATMUL_CHAIN = 9 } mrl_kind;
 
 typedef struct {
   uint32_t kind;
@@ -218,7 +235,7 @@ typedef struct mrl_table mrl_table;
 /* deps: host array of solved tables a FUSED lattice reads: {MATMUL_ACCUM table,
  * BIAS_ADD_RELU table} with the same m, k, n (m, n) size lists and target;
  * MATMUL_PARALLEL: {MATMUL_ACCUM table}; MATMUL_MOVES: {MOVE table};
- * NULL / 0 otherwise.  d_cost (uint64 per Spec), d_argmin (uint16 per Spec) and
+ * MATMUL_CHAIN: {MATMUL_ACCUM table}; NULL / 0 otherwise.  d_cost (uint64 per Spec), d_argmin (uint16 per Spec) and
  * d_scratch are DEVICE pointers, 256-byte aligned, owned by the caller and
  * referenced by *out until mrl_table_destroy.  hip_stream: a hipStream_t (or
  * NULL for the default stream); part of the work runs on a helper stream of
@@ -336,7 +353,8 @@ int32_t mrl_query_compressed(const mrl_table* tab, const mrl_coord* specs, size_
  * goal down to microkernels gives the program of Section 2, Figure 1).
  * Nodes in pre-order: a node is followed by the subtrees of its children
  * (0 for a microkernel, 1 for a tile or a Move: the loop body / the Spec on
- * the moved operand, 2 for bufferize: the Matmul, then the bias-add + ReLU).
+ * the moved operand, 2 for bufferize: the Matmul, then the bias-add + ReLU;
+ * in a MATMUL_CHAIN table the first Matmul, then the second, both in dep 0).
  * table: 0 = the table the walk started in, 1 + i = its dep i (the handles
  * given to mrl_solve as deps must still be alive).  cost = the table's entry
  * of the node's Spec = cost of the whole subtree under Section 3's equation.

@@ -7,7 +7,7 @@ Section 4 of the paper: the search memoizes, for every Spec, the rewrite of its
 cheapest implementation.  Starting at a goal Spec and applying the memoized
 rewrite again and again (Section 2: tile -> the loop body, Move -> the Spec on
 the moved operand, bufferize -> the Matmul and the bias-add + ReLU of Section
-2.1, microkernel -> a leaf) spells out the program of Figure 1.  The walk uses
+2.1 (or the two Matmuls of a composition), microkernel -> a leaf) spells out the program of Figure 1.  The walk uses
 the C oracle's dense tables for the memoized rewrites and brute_force.rewrites
 for what a rewrite does to a Spec; tree_cost() evaluates Section 3's cost
 equation on the result, which must give back the table's entry of the goal.
@@ -19,11 +19,11 @@ INF = 2 ** 64 - 1
 
 def axes(lattice, target=None):
     """(axis kind, operand or dimension or level) per coordinate, in coordinate order:
-    sizes b, m, k, n; one level per operand (kind F: plus the intermediate);
+    sizes b, m, k, n; one level per operand (kinds F and G: plus the intermediate);
     (bounded kinds: one memory bound per level of finite capacity;) layout bits; dtype bits."""
     kind = lattice["kind"]
-    nops = 4 if B.base_kind(kind) == B.F else 3
-    nlv = 5 if B.base_kind(kind) == B.F else 3
+    nops = 4 if B.base_kind(kind) in (B.F, B.G) else 3
+    nlv = 5 if B.base_kind(kind) in (B.F, B.G) else 3
     ax = [("size", d) for d in range(4)] + [("level", i) for i in range(nlv)]
     if kind in B.BOUNDED:
         ax += [("limit", l) for l in range(target["n_levels"]) if target["capacity_bytes"][l] != INF]

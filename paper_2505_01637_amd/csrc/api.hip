@@ -171,13 +171,16 @@ int32_t validate_target(const mrl_target_desc* d) {
 
 int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c) {
   if (!L) return fail(MRL_E_INVAL, "lattice descriptor is NULL");
-  if (L->kind > MRL_KIND_MATMUL_MOVES) return fail(MRL_E_INVAL, "unknown spec kind %u", L->kind);
+  if (L->kind > MRL_KIND_MATMUL_CHAIN) return fail(MRL_E_INVAL, "unknown spec kind %u", L->kind);
   // A parallel lattice is a Matmul lattice (same operator, operands and coordinates) with more
   // rewrites; a bounded one is the lattice of its operator with more coordinates; a Matmul whose
-  // Moves are Move Specs is a Matmul lattice with other Move costs.
+  // Moves are Move Specs is a Matmul lattice with other Move costs; the composition of two Matmuls
+  // has the fused Spec's structure (four operands and an intermediate between two stages).
+  const bool chain = L->kind == MRL_KIND_MATMUL_CHAIN;
   const bool parallel = L->kind == MRL_KIND_MATMUL_PARALLEL, move_specs = L->kind == MRL_KIND_MOVE, moves = L->kind == MRL_KIND_MATMUL_MOVES;
   const bool bounded = L->kind >= MRL_KIND_MATMUL_BOUNDED && L->kind <= MRL_KIND_FUSED_BOUNDED;
-  const uint32_t kind = parallel || moves ? (uint32_t)kKindM : bounded ? L->kind - MRL_KIND_MATMUL_BOUNDED : move_specs ? (uint32_t)kKindV : L->kind;
+  const uint32_t kind = parallel || moves ? (uint32_t)kKindM : bounded ? L->kind - MRL_KIND_MATMUL_BOUNDED : move_specs ? (uint32_t)kKindV
+                        : chain ? (uint32_t)kKindF : L->kind;
   if (parallel && T.threads < 1) return fail(MRL_E_INVAL, "a MATMUL_PARALLEL lattice needs threads >= 1");
   if ((move_specs || moves) && T.line_bytes < 1) return fail(MRL_E_INVAL, "MOVE and MATMUL_MOVES lattices need line_bytes >= 1");
   c.target = T;
@@ -209,6 +212,7 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
   for (uint32_t a = P.nlim; a-- > 0;) { P.lim_stride[a] = P.Q; P.Q *= P.lim_nq[a]; }
   P.gather = bounded || move_specs || moves ? 1u : 0u;
   P.moves = moves ? 1u : 0u;
+  P.chain = chain ? 1u : 0u;
   P.line_bytes = T.line_bytes;
   for (int l = 0; l < 4; l++) P.weight[l] = T.level_weight[l];
   P.nops = kind == kKindF ? 4 : kind == kKindV ? 2 : 3;
@@ -223,7 +227,7 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
     if (n < 1 || n > MRL_MAX_SIZES || !L->sizes[d]) return fail(MRL_E_INVAL, "n_sizes[%d] must be 1..%d", d, MRL_MAX_SIZES);
     c.sizes[d].assign(L->sizes[d], L->sizes[d] + n);
     // (no rewrite of a fused Spec changes k: a fused lattice may cover any stretch of k values)
-    if (c.sizes[d][0] != 1 && !(d == 2 && kind == kKindF)) return fail(MRL_E_INVAL, "sizes[%d] must start with 1", d);
+    if (c.sizes[d][0] != 1 && !(d == 2 && kind == kKindF && !chain)) return fail(MRL_E_INVAL, "sizes[%d] must start with 1", d);
     for (uint32_t j = 1; j < n; j++)
       if (c.sizes[d][j] <= c.sizes[d][j - 1]) return fail(MRL_E_INVAL, "sizes[%d] must be strictly ascending", d);
     c.lat.sizes[d] = c.sizes[d].data();
@@ -233,7 +237,7 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
     if (max_vol >= (1ull << 48)) return fail(MRL_E_INVAL, "b*m*k*n must stay below 2^48");
     maxs = std::max(maxs, n);
   }
-  if (kind != kKindM && L->n_sizes[0] != 1) return fail(MRL_E_INVAL, "this kind has no batch dimension");
+  if (kind != kKindM && !chain && L->n_sizes[0] != 1) return fail(MRL_E_INVAL, "this kind has no batch dimension");
   if (kind == kKindE && L->n_sizes[2] != 1) return fail(MRL_E_INVAL, "BIAS_ADD_RELU has no k dimension");
   if (kind == kKindV && L->n_sizes[2] != 1) return fail(MRL_E_INVAL, "MOVE has no k dimension");
   if (moves && L->n_sizes[0] != 1) return fail(MRL_E_INVAL, "MATMUL_MOVES has no batch dimension");
@@ -250,7 +254,8 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
     if (L->base_dtype_bytes[i] != 4 && !(L->base_dtype_bytes[i] == 2 && (kind == kKindM || kind == kKindV)))
       return fail(MRL_E_INVAL, "base_dtype_bytes[%u] must be 4 (or 2 on a MatmulAccum or a MOVE)", i);
     P.base_bf16[i] = L->base_dtype_bytes[i] == 2;
-    P.access[i] = kind == kKindM ? (i == 2 ? kRmw : kRead) : (i == P.nops - 1 ? kWrite : kRead);
+    // (the second Matmul of a composition accumulates into out, as every Matmul does)
+    P.access[i] = kind == kKindM ? (i == 2 ? kRmw : kRead) : (i == P.nops - 1 ? (chain ? kRmw : kWrite) : kRead);
     P.lvpow[i] = ipow(P.NL, P.nops - 1 - i);
     P.pack_shift[i] = 2 * (P.nops - 1 - i);
   }
@@ -379,16 +384,16 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
   }
 
   // dependency level of a shape = sum over tiled dims of the longest divisor chain below its size
-  std::vector<uint32_t> chain[4];
+  std::vector<uint32_t> depth[4];
   uint32_t n_lev = 1;
   for (int d = 0; d < 4; d++) {
-    chain[d].assign(P.nsz[d], 0);
+    depth[d].assign(P.nsz[d], 0);
     uint32_t mx = 0;
     if (P.tile_dim_ok[d])
       for (uint32_t j = 0; j < P.nsz[d]; j++) {
         for (uint32_t q = P.tile_off[d][j]; q < P.tile_off[d][j + 1]; q++)
-          chain[d][j] = std::max(chain[d][j], chain[d][c.tiles[q].jt] + 1);
-        mx = std::max(mx, chain[d][j]);
+          depth[d][j] = std::max(depth[d][j], depth[d][c.tiles[q].jt] + 1);
+        mx = std::max(mx, depth[d][j]);
       }
     n_lev += mx;
   }
@@ -396,7 +401,7 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
   c.level_off.assign(n_lev + 1, 0);
   for (uint32_t sh = 0; sh < c.n_shapes; sh++) {
     uint32_t r = sh, l = 0;
-    for (int d = 0; d < 4; d++) { l += chain[d][r / P.shape_stride[d]]; r %= P.shape_stride[d]; }
+    for (int d = 0; d < 4; d++) { l += depth[d][r / P.shape_stride[d]]; r %= P.shape_stride[d]; }
     lev[sh] = l;
     c.level_off[l + 1]++;
   }
@@ -457,7 +462,7 @@ bool same_problem(const Compiled& c, const mrl_target_desc& T, const mrl_lattice
 int32_t get_compiled(const mrl_target_desc& T, const mrl_lattice_desc* L, CompiledPtr& out) {
   static std::mutex mu;
   static std::vector<CompiledPtr> cache;          // most recent last, at most 8
-  if (L && L->kind <= MRL_KIND_MATMUL_MOVES) {
+  if (L && L->kind <= MRL_KIND_MATMUL_CHAIN) {
     std::lock_guard<std::mutex> lock(mu);
     for (size_t i = cache.size(); i-- > 0;)
       if (same_problem(*cache[i], T, *L)) { out = cache[i]; return MRL_OK; }
@@ -674,7 +679,24 @@ int32_t solve_impl(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_t
   tab->P = c.P;
   DevParams& P = tab->P;
 
-  if (P.kind == kKindF) {
+  if (P.chain) {
+    if (n_deps != 1 || !deps || !deps[0]) return fail(MRL_E_INVAL, "a MATMUL_CHAIN lattice needs deps = {MATMUL_ACCUM table}");
+    const Compiled& M = *deps[0]->cp;
+    if (M.P.kind != kKindM || M.P.par || M.P.bounded || M.P.moves) return fail(MRL_E_INVAL, "the dep must be a MATMUL_ACCUM table");
+    if (memcmp(&M.target, &t->d, sizeof t->d)) return fail(MRL_E_INVAL, "the dep was solved for another target");
+    if (M.sizes[0].size() != 1) return fail(MRL_E_INVAL, "MATMUL_ACCUM dep must have b pinned to 1");
+    // both stages are looked up in it: (m, k, p) and (m, p, n)
+    if (M.sizes[1] != c.sizes[1] || M.sizes[2] != c.sizes[2] || M.sizes[2] != c.sizes[0] || M.sizes[3] != c.sizes[0] || M.sizes[3] != c.sizes[3])
+      return fail(MRL_E_INVAL, "the m list must equal the MATMUL_ACCUM dep's, and the p, k and n lists its k and n lists");
+    if ((P.lay_bit[0] != kNoBit && M.P.lay_bit[0] == kNoBit) || (P.lay_bit[1] != kNoBit && M.P.lay_bit[1] == kNoBit) ||
+        (P.lay_bit[2] != kNoBit && M.P.lay_bit[1] == kNoBit) || (P.lay_bit[3] != kNoBit && M.P.lay_bit[2] == kNoBit))
+      return fail(MRL_E_INVAL, "a tensor with a layout coordinate in the MATMUL_CHAIN lattice needs one in the dep it is looked up in");
+    if (M.P.ndt || M.P.base_bf16[0] || M.P.base_bf16[1] || M.P.base_bf16[2]) return fail(MRL_E_INVAL, "MATMUL_ACCUM dep must be f32");
+    P.costM = deps[0]->d_cost;
+    tab->deps[0] = deps[0];
+    P.GM = M.P.G; P.VM = M.P.V; P.kM_first = 0; P.nkM = (uint32_t)M.sizes[2].size();
+    for (int i = 0; i < 3; i++) P.layM[i] = M.P.lay_bit[i];
+  } else if (P.kind == kKindF) {
     if (n_deps != 2 || !deps || !deps[0] || !deps[1]) return fail(MRL_E_INVAL, "a FUSED lattice needs deps = {MATMUL_ACCUM table, BIAS_ADD_RELU table}");
     const Compiled& M = *deps[0]->cp;
     const Compiled& E = *deps[1]->cp;
@@ -729,7 +751,7 @@ int32_t solve_impl(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_t
     P.GV = V.P.G; P.VV = V.P.V; P.nszV = V.P.nsz[3]; P.QV = V.P.Q; P.qV_top = V.P.Q - 1;
     for (int i = 0; i < 2; i++) { P.layV[i] = V.P.lay_bit[i]; P.dtV[i] = V.P.dt_bit[i]; }
   } else if (n_deps != 0) {
-    return fail(MRL_E_INVAL, "only FUSED, MATMUL_PARALLEL and MATMUL_MOVES lattices take deps");
+    return fail(MRL_E_INVAL, "only FUSED, MATMUL_PARALLEL, MATMUL_MOVES and MATMUL_CHAIN lattices take deps");
   }
 
   std::unique_lock<std::mutex> solve_lock(c.solve_mu);      // for the upload image, until the upload has run
@@ -1422,6 +1444,24 @@ int32_t mrl_schedule(const mrl_table* tab, const mrl_coord* goal, mrl_schedule_n
       ch.x.x[d] = j;
       stack.push_back(ch);
       node.n_children = 1;
+    } else if (r.cls == 3 && P.chain) {     // bufferize of a composition: the Matmul (m, k, p) into the intermediate, then (m, p, n) out of it
+      if (it.which != 0 || !it.t->deps[0]) return fail(MRL_E_HIP, "internal error: bufferize outside a MATMUL_CHAIN table");
+      const uint32_t p = c.sizes[0][it.x.x[0]], m = c.sizes[1][it.x.x[1]], k = c.sizes[2][it.x.x[2]], nn = c.sizes[3][it.x.x[3]];
+      const uint8_t l_mid = (uint8_t)it.x.x[8];
+      uint8_t y[4];
+      for (int i = 0; i < 4; i++) y[i] = c.lay_axis[i] >= 0 ? (uint8_t)it.x.x[c.lay_axis[i]] : 0;
+      const uint32_t shape_1[4] = {1, m, k, p}, shape_2[4] = {1, m, p, nn};
+      const uint8_t lv_1[5] = {(uint8_t)it.x.x[4], (uint8_t)it.x.x[5], l_mid, 0, 0}, ly_1[5] = {y[0], y[1], 0, 0, 0};
+      const uint8_t lv_2[5] = {l_mid, (uint8_t)it.x.x[6], (uint8_t)it.x.x[7], 0, 0}, ly_2[5] = {0, y[2], y[3], 0, 0};
+      const uint8_t zeros[5] = {0, 0, 0, 0, 0};
+      Item c1{it.t->deps[0], 1u, {}}, c2{it.t->deps[0], 1u, {}};
+      rc = mrl_coord_of_spec(c1.t, shape_1, lv_1, ly_1, zeros, &c1.x);
+      if (rc) return rc;
+      rc = mrl_coord_of_spec(c2.t, shape_2, lv_2, ly_2, zeros, &c2.x);
+      if (rc) return rc;
+      stack.push_back(c2);                  // popped after the first Matmul's whole subtree
+      stack.push_back(c1);
+      node.n_children = 2;
     } else if (r.cls == 3) {                // bufferize: Matmul into the intermediate, then bias-add + ReLU out of it
       if (it.which != 0 || !it.t->deps[0] || !it.t->deps[1]) return fail(MRL_E_HIP, "internal error: bufferize outside a FUSED table");
       const uint32_t m = c.sizes[1][it.x.x[1]], k = c.sizes[2][it.x.x[2]], nn = c.sizes[3][it.x.x[3]];

@@ -92,6 +92,10 @@ struct DevParams {
   const uint64_t* costE;
   uint32_t GM, VM, GE, VE, nszE_n;
   uint32_t kM_first, nkM;    // a FUSED lattice's k list starts at entry kM_first of costM's table's, which has nkM entries
+  // ---- the composition of two Matmuls (kind stays kKindF: four operands and an intermediate) ----
+  // sizes[0] holds p, the dimension the two Matmuls share: lhs m x k, rhs1 k x p, rhs2 p x n, out
+  // m x n (accumulated into), intermediate m x p.  Both stages are read from costM.
+  uint32_t chain;
   uint32_t layM[3], layE[3]; // layout bit positions in the dependency's variant index
 };
 

@@ -88,6 +88,7 @@ __device__ __forceinline__ void load_shape(const DevParams* __restrict__ P, uint
   if (P->kind == kKindM) { S.numel[0] = b * m * k; S.numel[1] = b * k * n; S.numel[2] = b * m * n; S.numel[3] = 0; S.numel[4] = 0; }
   else if (P->kind == kKindV) { S.numel[0] = m * n; S.numel[1] = m * n; S.numel[2] = 0; S.numel[3] = 0; S.numel[4] = 0; }
   else if (P->kind == kKindE) { S.numel[0] = m * n; S.numel[1] = n; S.numel[2] = m * n; S.numel[3] = 0; S.numel[4] = 0; }
+  else if (P->chain) { S.numel[0] = m * k; S.numel[1] = k * b; S.numel[2] = b * n; S.numel[3] = m * n; S.numel[4] = m * b; }   // b holds p
   else { S.numel[0] = m * k; S.numel[1] = k * n; S.numel[2] = n; S.numel[3] = m * n; S.numel[4] = m * n; }
 }
 
@@ -382,7 +383,9 @@ __device__ __forceinline__ void task_tiles(const DevParams* __restrict__ P, cons
   }
 }
 
-// bufferize (FUSED): Matmul into the intermediate, then bias-add+ReLU out of it.
+// bufferize (FUSED): Matmul into the intermediate, then bias-add+ReLU out of it.  The composition
+// of two Matmuls (Section 2.1): the first, (m, k, p), into the intermediate, then the second,
+// (m, p, n), out of it; both are entries of the same Matmul table.
 __device__ __forceinline__ void task_bufferize(const DevParams* __restrict__ P, const Shape& S, uint32_t shape,
                                                uint32_t xpack, uint32_t v, Eval& e) {
   const uint32_t NL = P->NL, pack = xpack & 0xFFu, pass = xpack >> 8;
@@ -391,12 +394,28 @@ __device__ __forceinline__ void task_bufferize(const DevParams* __restrict__ P, 
   const uint32_t y0 = P->lay_bit[0] != kNoBit ? (v >> P->lay_bit[0]) & 1u : 0u;
   const uint32_t y1 = P->lay_bit[1] != kNoBit ? (v >> P->lay_bit[1]) & 1u : 0u;
   const uint32_t y3 = P->lay_bit[3] != kNoBit ? (v >> P->lay_bit[3]) & 1u : 0u;
+  const uint32_t zc = pass == 0 ? P->zero[0] : pass == 1 ? P->zero[1] : pass == 2 ? P->zero[2] : P->zero[3];
+  if (P->chain) {
+    const uint32_t y2 = P->lay_bit[2] != kNoBit ? (v >> P->lay_bit[2]) & 1u : 0u;
+    const uint32_t x1 = ((l0 * NL + l1) * NL + pass) * P->VM +
+                        (P->layM[0] != kNoBit ? y0 << P->layM[0] : 0u) + (P->layM[1] != kNoBit ? y1 << P->layM[1] : 0u);
+    const uint32_t x2 = ((pass * NL + l2) * NL + l3) * P->VM +
+                        (P->layM[1] != kNoBit ? y2 << P->layM[1] : 0u) + (P->layM[2] != kNoBit ? y3 << P->layM[2] : 0u);
+    // the table's k and n lists are this lattice's p list (and k and n lists)
+    const uint64_t c1 = P->costM[(uint64_t)((S.si[1] * P->nkM + S.si[2]) * P->nsz[3] + S.si[0]) * P->GM + x1];
+    const uint64_t c2 = P->costM[(uint64_t)((S.si[1] * P->nkM + S.si[0]) * P->nsz[3] + S.si[3]) * P->GM + x2];
+    if (c1 != kInf && c2 != kInf) {
+      const uint64_t z = mul_or_limit(zc, S.numel[4]);
+      const uint64_t sum = z + c1;          // each term <= 2^62: no wrap
+      if (z >= kLimit || sum >= kLimit || sum + c2 >= kLimit) e.ovf = 1; else consider(e, sum + c2, P->buf_id);
+    }
+    return;
+  }
   const uint32_t xm = ((l0 * NL + l1) * NL + pass) * P->VM +
                       (P->layM[0] != kNoBit ? y0 << P->layM[0] : 0u) + (P->layM[1] != kNoBit ? y1 << P->layM[1] : 0u);
   const uint32_t xe = ((pass * NL + l2) * NL + l3) * P->VE + (P->layE[2] != kNoBit ? y3 << P->layE[2] : 0u);
   const uint64_t cm = P->costM[(uint64_t)((S.si[1] * P->nkM + S.si[2] + P->kM_first) * P->nsz[3] + S.si[3]) * P->GM + xm];
   const uint64_t ce = P->costE[(uint64_t)(S.si[1] * P->nszE_n + S.si[3]) * P->GE + xe];
-  const uint32_t zc = pass == 0 ? P->zero[0] : pass == 1 ? P->zero[1] : pass == 2 ? P->zero[2] : P->zero[3];
   if (cm != kInf && ce != kInf) {
     const uint64_t z = mul_or_limit(zc, S.numel[4]);
     const uint64_t sum = z + cm;          // each term <= 2^62: no wrap

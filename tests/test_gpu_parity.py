@@ -63,10 +63,10 @@ def test_parity_other_seeds(seed):
     compare_config(W.config(7, seed=seed, max_size=2))
 
 
-@pytest.mark.parametrize("number", [2, 4])
+@pytest.mark.parametrize("number", [2, 4, 10])
 def test_parity_full_size(number):
-    """Configurations 2 and 4 at full size (16.8 M and 23.7 M specs), all outputs."""
-    compare_config(W.config(number), scratch_bytes=2 << 30)
+    """Configurations 2, 4 and 10 at full size (16.8 M, 23.7 M and 67.1 M specs), all outputs."""
+    compare_config(W.config(number), scratch_bytes=(4 if number == 10 else 2) << 30)
 
 
 def test_parity_config5_full_size():
@@ -365,6 +365,59 @@ def test_parity_moves_as_specs(case):
         check_compressed_queries(tab, want[label], 3000, seed=5)
 
 
+def chain_config(sizes, layout=(1, 1, 1, 1), levels=4, seed=3, zero=True):
+    """The Matmul table and the lattice of compositions of two Matmuls that reads it."""
+    cfg = W.config(10, seed=seed, max_size=1)
+    t = cfg["target"]
+    if levels == 2:
+        t = W._empty_target(2, (96, 4096))
+        t["load_coef"][1][0][0], t["store_coef"][0][1][0] = 3, 2
+        t["load_coef"][1][0][1], t["store_coef"][0][1][1] = 5, 4
+        t["loop_overhead"] = 2
+        t["zero_coef"] = [1, 3, 0, 0]
+        t["microkernels"] = [(W.MK_SCALAR_FMA, 1, 1)]
+    if not zero:
+        t["zero_coef"] = [0, 0, 0, 0]
+    r = list(sizes)
+    lay_m = (layout[0] | layout[1], layout[1] | layout[2], layout[3])
+    return {"name": "chain", "target": t,
+            "lattices": [("M", W._lattice(W.KIND_MATMUL_ACCUM, [[1], r, r, r], layout=lay_m + (0, 0)), []),
+                         ("G", W._lattice(W.KIND_MATMUL_CHAIN, [r, r, r, r], layout=tuple(layout) + (0,)), ["M"])]}
+
+
+@pytest.mark.parametrize("case", ["config10-4", "config10-8", "no-layouts", "some-layouts", "two-levels", "ragged-sizes", "one-shape"])
+def test_parity_composition_of_two_matmuls(case):
+    """The lattice of (lhs x rhs1) x rhs2: dense tables, counters and both box lists, and point
+    queries answered from the boxes.  Sixteen variants per level assignment (four layout bits),
+    the most the library takes; sizes that are not powers of two; a lattice of one shape."""
+    if case.startswith("config10"):
+        cfg = W.config(10, max_size=int(case.split("-")[1]))
+    elif case == "no-layouts":
+        cfg = chain_config([1, 2, 4, 8], layout=(0, 0, 0, 0))
+    elif case == "some-layouts":
+        cfg = chain_config([1, 2, 3, 6], layout=(0, 1, 0, 1), zero=False)
+    elif case == "two-levels":
+        cfg = chain_config([1, 2, 4, 8, 16], levels=2)
+    elif case == "ragged-sizes":
+        cfg = chain_config([1, 3, 5, 9, 15], layout=(1, 0, 1, 0))
+    else:
+        cfg = chain_config([1])
+    _, got, want = compare_config(cfg)
+    check_compressed_queries(got["G"], want["G"], 2_000, seed=7)
+
+
+def test_composition_host_checks():
+    B = _binding()
+    cfg = chain_config([1, 2, 4])
+    _, got = B.solve_config({"name": "m", "target": cfg["target"], "lattices": cfg["lattices"][:1]})
+    # the p list differs from the Matmul table's k and n lists
+    bad = dict(cfg["lattices"][1][1], sizes=[[1, 2], [1, 2, 4], [1, 2, 4], [1, 2, 4]])
+    for lattices in ([cfg["lattices"][0], ("G", bad, ["M"])], [cfg["lattices"][0], ("G", cfg["lattices"][1][1], [])]):
+        with pytest.raises(B.MorelloError) as e:
+            B.solve_config({"name": "bad", "target": cfg["target"], "lattices": lattices})
+        assert e.value.code == B.E_INVAL
+
+
 def test_degenerate_lattices():
     B = _binding()
     # a single shape: every dimension pinned
@@ -471,7 +524,7 @@ def test_deterministic():
 
 @pytest.mark.gpu
 @pytest.mark.parametrize("number,max_size,label", [(1, None, "M"), (3, 64, "M"), (4, 8, "M"), (5, 8, "F"), (5, 8, "E"),
-                                                   (6, 16, "P"), (7, 8, "B")])
+                                                   (6, 16, "P"), (7, 8, "B"), (10, 4, "G")])
 def test_schedule_parity(number, max_size, label):
     """mrl_schedule walks the same programs as the oracle's extraction: same Specs, rewrites and
     costs, node by node in pre-order; a goal without implementation is an error."""

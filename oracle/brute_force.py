@@ -24,15 +24,17 @@ M, E, F, P = 0, 1, 2, 3      # P: a Matmul that may use parallel loops; M is ser
 BD, BE, BF = 4, 5, 6          # M, E, F whose Specs carry per-level memory bounds (Sections 2.2, 2.4.4)
 V, MV = 7, 8                  # V: Move Specs (Section 2.2); MV: a Matmul whose Moves are Move Specs
 G = 9                         # two composed Matmuls (Section 2.1): dims = (p, m, k, n); lhs m x k, rhs1 k x p, rhs2 p x n, out m x n
+A, R, S = 10, 11, 12          # bias add alone; ReLU alone; bias add -> ReLU with the bufferize between the two (Section 2.1)
 BOUNDED = (BD, BE, BF)
 MATMULS = (M, P, BD, MV)
 
 
 def base_kind(kind):
     """The operator of a kind: M for the Matmuls, E, F, V."""
-    return M if kind in MATMULS else E if kind in (E, BE) else kind if kind in (V, G) else F
+    return M if kind in MATMULS else E if kind in (E, BE, S) else kind if kind in (V, G, A, R) else F
 FMA, BCAST, BF16DOT, S_ADDRELU, V_ADDRELU = 0, 1, 2, 3, 4
 S_MOVE, V_MOVE, V_MOVE_ALIGNED = 5, 6, 7
+S_ADD, V_ADD, S_RELU, V_RELU = 8, 9, 10, 11
 
 # dims = (b, m, k, n) actual sizes; levels per operand (F: 5th = intermediate);
 # layouts / bf16 per operand (0 where the lattice has no such coordinate)
@@ -45,9 +47,9 @@ def operand_numel(spec, i):
     b, m, k, n = spec.dims
     if spec.kind in MATMULS:
         return (b * m * k, b * k * n, b * m * n)[i]
-    if base_kind(spec.kind) == E:
+    if base_kind(spec.kind) in (E, A):
         return (m * n, n, m * n)[i]
-    if spec.kind == V:
+    if spec.kind in (V, R):
         return m * n
     if spec.kind == G:
         p = b
@@ -59,8 +61,10 @@ def operand_mode(kind, i):
     """'r' read, 'rw' accumulate, 'w' write-only."""
     if kind in MATMULS:
         return "rw" if i == 2 else "r"
-    if base_kind(kind) == E:
+    if base_kind(kind) in (E, A):
         return "w" if i == 2 else "r"
+    if kind == R:
+        return "w" if i == 1 else "r"
     if kind == G:
         return "rw" if i == 3 else "r"     # the second Matmul accumulates
     return "w" if i == 3 else "r"
@@ -71,7 +75,7 @@ def fits(target, spec):
         return True          # the bounds decide at each allocation, not the operands' footprint;
                              # the two tensors of a Move exist already
     used = [0] * target["n_levels"]
-    nops = 4 if spec.kind in (F, G) else 3
+    nops = 4 if spec.kind in (F, G) else 2 if spec.kind == R else 3
     for i in range(nops):
         used[spec.levels[i]] += operand_numel(spec, i) * (2 if spec.bf16[i] else 4)
     if spec.kind in (F, G):
@@ -101,6 +105,18 @@ def microkernel_reps(target, lattice, spec, j):
     if kind == V_ADDRELU:
         ok = (base_kind(spec.kind) == E and m == 1 and n % lanes == 0 and tuple(lv[:3]) == (1, 1, 1)
               and ly[0] == 0 and ly[2] == 0)
+        return n // lanes if ok else 0
+    if kind == S_ADD:
+        ok = spec.kind == A and (m, n) == (1, 1) and tuple(lv[:3]) == (0, 0, 0)
+        return 1 if ok else 0
+    if kind == V_ADD:
+        ok = spec.kind == A and m == 1 and n % lanes == 0 and tuple(lv[:3]) == (1, 1, 1) and ly[0] == 0 and ly[2] == 0
+        return n // lanes if ok else 0
+    if kind == S_RELU:
+        ok = spec.kind == R and (m, n) == (1, 1) and tuple(lv[:2]) == (0, 0)
+        return 1 if ok else 0
+    if kind == V_RELU:
+        ok = spec.kind == R and m == 1 and n % lanes == 0 and tuple(lv[:2]) == (1, 1) and ly[0] == 0 and ly[1] == 0
         return n // lanes if ok else 0
     if kind == S_MOVE:
         ok = spec.kind == V and (m, n) == (1, 1) and not (bf[1] and not bf[0])
@@ -138,7 +154,7 @@ def rewrites(target, lattices, spec):
     applicable rewrite of an admissible Spec, ids ascending."""
     lattice = lattices[spec.kind]
     nl = target["n_levels"]
-    nops = 4 if base_kind(spec.kind) in (F, G) else 2 if spec.kind == V else 3
+    nops = 4 if base_kind(spec.kind) in (F, G) else 2 if spec.kind in (V, R) else 3
     nmk = len(target["microkernels"])
     maxs = max(len(s) for s in lattice["sizes"])
     move_base = nmk
@@ -210,7 +226,7 @@ def rewrites(target, lattices, spec):
                     rid = move_base + ((i * (nl - 1) + dst) * 2 + x) * 2 + cv
                     yield rid, ("alloc", coef * operand_numel(spec, i)), [child]
     for d in range(4):
-        if base_kind(spec.kind) in (E, F, V, G) and d in (0, 2):
+        if base_kind(spec.kind) != M and d in (0, 2):
             continue
         cur = spec.dims[d]
         for j, t in enumerate(lattice["sizes"][d]):
@@ -249,10 +265,23 @@ def rewrites(target, lattices, spec):
             lim[l_mid] = 0 if left == 0 else 1 << (left.bit_length() - 1)
             lim = tuple(lim)
         mm = Spec(BD if bounded else M, (1, m, k, n), (l_lhs, l_rhs, l_mid, 0, 0), (y_lhs, y_rhs, 0, 0, 0), (0,) * 5, lim)
-        ee = Spec(BE if bounded else E, (1, m, 1, n), (l_mid, l_bias, l_out, 0, 0), (0, 0, y_out, 0, 0), (0,) * 5, lim)
+        # (the second stage is a Spec of whichever bias-add + ReLU lattice is there: kind E, or kind S with its own bufferize)
+        ee = Spec(BE if bounded else S if S in lattices else E, (1, m, 1, n), (l_mid, l_bias, l_out, 0, 0), (0, 0, y_out, 0, 0), (0,) * 5, lim)
         yield tile_base + 4 * maxs, ("pipeline", target["zero_coef"][l_mid] * m * n), [mm, ee]
 
 
+    if spec.kind == S:
+        # bufferize(l): the bias add writes the intermediate (m x n, f32, row-major) in level l, the
+        # ReLU reads it; the intermediate must fit level l next to the operands that live there
+        b, m, k, n = spec.dims
+        l_in, l_bias, l_out = spec.levels[:3]
+        for l in range(nl):
+            used = 4 * m * n + sum(4 * operand_numel(spec, i) for i in range(3) if spec.levels[i] == l)
+            if used > target["capacity_bytes"][l]:
+                continue
+            add = Spec(A, (1, m, 1, n), (l_in, l_bias, l, 0, 0), (spec.layouts[0], 0, 0, 0, 0), (0,) * 5)
+            relu = Spec(R, (1, m, 1, n), (l, l_out, 0, 0, 0), (0, spec.layouts[2], 0, 0, 0), (0,) * 5)
+            yield tile_base + 4 * maxs + l, ("pipeline", 0), [add, relu]
     if spec.kind == G:
         p, m, k, n = spec.dims
         l_lhs, l_rhs1, l_rhs2, l_out, l_mid = spec.levels

@@ -42,6 +42,12 @@
  * fused lattice of kind 2: tiles of the output's dimensions, Moves of the
  * four external operands, and one bufferize that splits it into two Matmul
  * Specs around the intermediate.
+ * Kinds 10 to 12 take the bias-add + ReLU of kind 1 apart (Section 2.1: a
+ * composition is lowered to its primitives by bufferize rewrites): kind 10 is
+ * the bias add alone, kind 11 the ReLU alone, each with microkernels of its
+ * own, and kind 12 the Specs of kind 1 with one more rewrite per memory level:
+ * a bufferize that splits the composition into the bias add writing an
+ * intermediate in that level and the ReLU reading it.
  */
 #define _GNU_SOURCE             /* qsort_r */
 #include <stdint.h>
@@ -55,11 +61,15 @@
 enum { ORC_MAXL = 4, ORC_MAXOPS = 5, ORC_MAXD = 16, ORC_MAXMK = 8 };
 enum { MK_SCALAR_FMA = 0, MK_BCAST_VEC_MULADD = 1, MK_BF16_DOT = 2,
        MK_SCALAR_ADDRELU = 3, MK_VEC_ADDRELU = 4,
-       MK_SCALAR_MOVE = 5, MK_VECTOR_MOVE = 6, MK_VECTOR_MOVE_ALIGNED = 7 };
+       MK_SCALAR_MOVE = 5, MK_VECTOR_MOVE = 6, MK_VECTOR_MOVE_ALIGNED = 7,
+       MK_SCALAR_ADD = 8, MK_VEC_ADD = 9, MK_SCALAR_RELU = 10, MK_VEC_RELU = 11 };
 enum { KIND_M = 0, KIND_E = 1, KIND_F = 2, KIND_P = 3, KIND_B = 4, KIND_BE = 5, KIND_BF = 6,
        KIND_V = 7,    /* Move Specs */
        KIND_MV = 8,   /* a Matmul whose Moves are Move Specs of a kind 7 table */
-       KIND_G = 9 };  /* composition of two Matmuls (Section 2.1): (lhs x rhs1) x rhs2 accumulated into out */
+       KIND_G = 9,    /* composition of two Matmuls (Section 2.1): (lhs x rhs1) x rhs2 accumulated into out */
+       KIND_A = 10,   /* bias add: in (m x n), bias (n), out (m x n) */
+       KIND_R = 11,   /* ReLU: in (m x n), out (m x n) */
+       KIND_S = 12 }; /* bias add -> ReLU as kind 1, plus the bufferize between the two */
 enum { ACC_READ = 0, ACC_RMW = 1, ACC_WRITE = 2 };
 
 typedef struct {
@@ -118,6 +128,7 @@ typedef struct ctx {
   int bounded;                  /* kinds 4..6: the Specs carry per-level memory bounds */
   int lim_axis[ORC_MAXL];       /* coordinate axis of level l's bound, -1 if the level is unbounded */
   int moves;                    /* kind 8: Moves are Move Specs, looked up in depM (a kind V table) */
+  int split;                    /* kind 12: kind E plus bufferize(level); depM = the bias-add table, depE = the ReLU table */
   int abs_axis;                 /* kind V: first of the four axes contig(src), aligned(src), contig(dst), aligned(dst); -1 else */
   uint64_t n_rewrites, n_admissible;
   int overflow;
@@ -134,17 +145,18 @@ typedef struct ctx {
 static int ctx_init(ctx* c, const orc_target* T, const orc_lattice* L) {
   memset(c, 0, sizeof *c);
   c->T = T; c->L = L; c->kind = (int)L->kind;
-  if (c->kind < 0 || c->kind > KIND_G) return -1;
+  if (c->kind < 0 || c->kind > KIND_S) return -1;
   c->abs_axis = -1;
   if (c->kind == KIND_MV) { c->kind = KIND_M; c->moves = 1; }     /* same operator, operands and coordinates as kind M */
+  if (c->kind == KIND_S) { c->kind = KIND_E; c->split = 1; }      /* same operator, operands and coordinates as kind E */
   if (c->kind >= KIND_B && c->kind <= KIND_BF) { c->kind -= KIND_B; c->bounded = 1; }   /* kinds 4, 5, 6: M, E, F with memory bounds */
   if (c->kind == KIND_P) {      /* same operator, operands and coordinates as kind M */
     c->kind = KIND_M; c->parallel = 1;
     if (T->threads < 1) return -1;
   }
   if (T->n_levels < 1 || T->n_levels > ORC_MAXL) return -1;
-  c->nops = c->kind == KIND_F || c->kind == KIND_G ? 4 : c->kind == KIND_V ? 2 : 3;
-  c->nlv = c->kind == KIND_F || c->kind == KIND_G ? 5 : c->kind == KIND_V ? 2 : 3;
+  c->nops = c->kind == KIND_F || c->kind == KIND_G ? 4 : c->kind == KIND_V || c->kind == KIND_R ? 2 : 3;
+  c->nlv = c->kind == KIND_F || c->kind == KIND_G ? 5 : c->kind == KIND_V || c->kind == KIND_R ? 2 : 3;
   if ((c->kind == KIND_V || c->moves) && T->line_bytes < 1) return -1;
   int d = 0;
   c->maxs = 0;
@@ -159,7 +171,7 @@ static int ctx_init(ctx* c, const orc_target* T, const orc_lattice* L) {
     if (L->n_sizes[a] > c->maxs) c->maxs = L->n_sizes[a];
   }
   if (c->kind != KIND_M && c->kind != KIND_G && L->n_sizes[0] != 1) return -1;   /* no batch on E, F (kind G keeps p there) */
-  if ((c->kind == KIND_E || c->kind == KIND_V) && L->n_sizes[2] != 1) return -1;   /* E and V have no k */
+  if ((c->kind == KIND_E || c->kind == KIND_V || c->kind == KIND_A || c->kind == KIND_R) && L->n_sizes[2] != 1) return -1;   /* no k */
   if (c->moves && L->n_sizes[0] != 1) return -1;            /* operands of a kind 8 Matmul are two-dimensional */
   for (int i = 0; i < c->nlv; i++) c->ext[d++] = T->n_levels;
   /* Memory bounds (Section 2.2, field 5; Section 4.1: limits are powers of two): one axis per
@@ -195,7 +207,7 @@ static int ctx_init(ctx* c, const orc_target* T, const orc_lattice* L) {
   c->tile_base = c->move_base + (uint32_t)c->nops * (T->n_levels - 1) * 4;
   c->buf_id = c->tile_base + 4 * c->maxs;
   c->par_base = c->buf_id + 1;
-  if ((c->parallel ? c->par_base + 4 * c->maxs : c->buf_id) >= ORC_NONE) return -1;
+  if ((c->parallel ? c->par_base + 4 * c->maxs : c->buf_id + T->n_levels) >= ORC_NONE) return -1;
   return 0;
 }
 
@@ -248,7 +260,9 @@ static uint64_t numel(const ctx* c, const spec_t* s, int op) {
   uint64_t b = d[0], m = d[1], k = d[2], n = d[3];
   switch (c->kind) {
     case KIND_M: return op == 0 ? b * m * k : op == 1 ? b * k * n : b * m * n;
-    case KIND_E: return op == 1 ? n : m * n;
+    case KIND_E:
+    case KIND_A: return op == 1 ? n : m * n;
+    case KIND_R: return m * n;
     case KIND_V: return m * n;                                                    /* source and destination: rows x cols */
     case KIND_G: /* b holds p, the dimension the two Matmuls share: lhs m x k, rhs1 k x p, rhs2 p x n, out m x n, mid m x p */
       return op == 0 ? m * k : op == 1 ? k * b : op == 2 ? b * n : op == 3 ? m * n : m * b;
@@ -325,6 +339,29 @@ static uint64_t mk_reps(const ctx* c, const spec_t* s, int j) {
       if (m != 1 || n % lanes != 0) return 0;
       if (lv[0] != 1 || lv[1] != 1 || lv[2] != 1) return 0;
       if (ly[0] != 0 || ly[2] != 0) return 0;
+      return n / lanes;
+    /* The two halves of the bias-add + ReLU, for the lattices of kinds 10 and 11. */
+    case MK_SCALAR_ADD:
+      if (c->kind != KIND_A) return 0;
+      if (m != 1 || n != 1) return 0;
+      if (lv[0] != 0 || lv[1] != 0 || lv[2] != 0) return 0;
+      return 1;
+    case MK_VEC_ADD:
+      if (c->kind != KIND_A) return 0;
+      if (m != 1 || n % lanes != 0) return 0;
+      if (lv[0] != 1 || lv[1] != 1 || lv[2] != 1) return 0;
+      if (ly[0] != 0 || ly[2] != 0) return 0;
+      return n / lanes;
+    case MK_SCALAR_RELU:
+      if (c->kind != KIND_R) return 0;
+      if (m != 1 || n != 1) return 0;
+      if (lv[0] != 0 || lv[1] != 0) return 0;
+      return 1;
+    case MK_VEC_RELU:
+      if (c->kind != KIND_R) return 0;
+      if (m != 1 || n % lanes != 0) return 0;
+      if (lv[0] != 1 || lv[1] != 1) return 0;
+      if (ly[0] != 0 || ly[1] != 0) return 0;
       return n / lanes;
     /* Move microkernels (Section 2: select(VectorMove), a vector load or store).  m = rows,
      * n = columns of the moved tensor; operand 0 is the source, 1 the destination. */
@@ -540,6 +577,33 @@ static void expand(ctx* c, const spec_t* s, uint64_t* best_out, uint16_t* arg_ou
     consider(c, cand, c->buf_id, &best, &arg);
   }
 
+  /* D''. bufferize of the bias-add + ReLU (kind 12, Section 2.1), one rewrite per level l of the
+   * intermediate (m x n, f32, row-major): the bias add writes it, the ReLU reads it; a pipeline
+   * costs the sum of its stages (Section 3; nothing accumulates into this intermediate, so it is
+   * not initialised).  The intermediate must fit level l next to the Spec's operands there. */
+  if (c->split) {
+    for (uint32_t l = 0; l < NL; l++) {
+      unsigned __int128 bytes = (unsigned __int128)numel(c, s, 0) * 4;      /* the intermediate: as large as in */
+      for (int i = 0; i < 3; i++) if (s->level[i] == l) bytes += (unsigned __int128)numel(c, s, i) * 4;
+      if (T->capacity_bytes[l] != UINT64_MAX && bytes > T->capacity_bytes[l]) continue;
+      spec_t as; memset(&as, 0, sizeof as);
+      spec_t rs; memset(&rs, 0, sizeof rs);
+      as.si[1] = rs.si[1] = s->si[1]; as.si[3] = rs.si[3] = s->si[3];
+      as.level[0] = s->level[0]; as.level[1] = s->level[1]; as.level[2] = (uint8_t)l;
+      as.layout[0] = s->layout[0];
+      rs.level[0] = (uint8_t)l; rs.level[1] = s->level[2];
+      rs.layout[1] = s->layout[2];
+      uint64_t ca = c->depM->cost[spec_index(c->depM, &as)];
+      uint64_t cr = c->depE->cost[spec_index(c->depE, &rs)];
+      uint64_t cand = ORC_INF;
+      if (ca != ORC_INF && cr != ORC_INF) {
+        unsigned __int128 v = (unsigned __int128)ca + cr;
+        if (v >= ORC_LIMIT) c->overflow = 1; else cand = (uint64_t)v;
+      }
+      consider(c, cand, c->buf_id + l, &best, &arg);
+    }
+  }
+
   /* E. parallel loop (kind P, Section 3: ceil(trips / threads) * c(body) + s).
    * The body is the serial-only Spec of the smaller shape (Section 2.2: the
    * flag limits an implementation to one hardware thread), so its cost comes
@@ -608,6 +672,15 @@ int orc_solve(const orc_target* T, const orc_lattice* L,
     if (LM->n_sizes[0] != 1) return -1;
     if (!same_sizes(L, 1, LE, 1) || !same_sizes(L, 3, LE, 3)) return -1;
     for (int i = 0; i < 3; i++) if (cm.dt_axis[i] >= 0 || LM->base_dtype_bytes[i] != 4) return -1;
+    cm.cost = (uint64_t*)costM; ce.cost = (uint64_t*)costE;
+    c.depM = &cm; c.depE = &ce;
+  }
+  if (c.split) {                /* the two stages: the bias-add table and the ReLU table */
+    if (!LM || !LE || !costM || !costE) return -1;
+    if (ctx_init(&cm, T, LM) || ctx_init(&ce, T, LE)) return -1;
+    if (cm.kind != KIND_A || ce.kind != KIND_R) return -1;
+    if (!same_sizes(L, 1, LM, 1) || !same_sizes(L, 3, LM, 3) || !same_sizes(L, 1, LE, 1) || !same_sizes(L, 3, LE, 3)) return -1;
+    if ((c.lay_axis[0] >= 0 && cm.lay_axis[0] < 0) || (c.lay_axis[2] >= 0 && ce.lay_axis[1] < 0)) return -1;
     cm.cost = (uint64_t*)costM; ce.cost = (uint64_t*)costE;
     c.depM = &cm; c.depE = &ce;
   }

@@ -22,8 +22,8 @@ def axes(lattice, target=None):
     sizes b, m, k, n; one level per operand (kinds F and G: plus the intermediate);
     (bounded kinds: one memory bound per level of finite capacity;) layout bits; dtype bits."""
     kind = lattice["kind"]
-    nops = 4 if B.base_kind(kind) in (B.F, B.G) else 3
-    nlv = 5 if B.base_kind(kind) in (B.F, B.G) else 3
+    nops = 4 if B.base_kind(kind) in (B.F, B.G) else 2 if kind == B.R else 3
+    nlv = 5 if B.base_kind(kind) in (B.F, B.G) else 2 if kind == B.R else 3
     ax = [("size", d) for d in range(4)] + [("level", i) for i in range(nlv)]
     if kind in B.BOUNDED:
         ax += [("limit", l) for l in range(target["n_levels"]) if target["capacity_bytes"][l] != INF]

@@ -21,6 +21,7 @@ MK_BCAST_VEC_MULADD = 1
 MK_BF16_DOT = 2
 MK_SCALAR_ADDRELU = 3
 MK_VEC_ADDRELU = 4
+MK_SCALAR_ADD, MK_VEC_ADD, MK_SCALAR_RELU, MK_VEC_RELU = 8, 9, 10, 11
 MK_SCALAR_MOVE = 5            # Move Spec of one element (converts bf16 -> f32 if the types differ)
 MK_VECTOR_MOVE = 6            # Move Spec of one row of whole vectors between level 1 and a slower level
 MK_VECTOR_MOVE_ALIGNED = 7    # the same, both tensors aligned
@@ -37,6 +38,10 @@ BOUNDED_KINDS = (KIND_MATMUL_BOUNDED, KIND_BIAS_ADD_RELU_BOUNDED, KIND_FUSED_BOU
 KIND_MOVE = 7                 # Move Specs: source and destination tensor of rows x cols
 KIND_MATMUL_MOVES = 8         # a Matmul whose Moves are Move Specs; reads a KIND_MOVE table
 KIND_MATMUL_CHAIN = 9         # (lhs x rhs1) x rhs2 accumulated into out; sizes[0] holds p, the dimension the two share
+KIND_BIAS_ADD = 10            # the bias add alone: in (m x n), bias (n), out (m x n)
+KIND_RELU = 11                # the ReLU alone: in (m x n), out (m x n)
+KIND_BIAS_ADD_RELU_SPLIT = 12 # KIND_BIAS_ADD_RELU plus a bufferize between the two; reads a KIND_BIAS_ADD and a KIND_RELU table
+TWO_OPERAND_KINDS = (KIND_MOVE, KIND_RELU)
 FIVE_LEVEL_KINDS = (KIND_FUSED_MM_ADD_RELU, KIND_FUSED_BOUNDED, KIND_MATMUL_CHAIN)   # four operands and an intermediate
 
 MAX_LEVELS = 4
@@ -233,17 +238,39 @@ def config(number, seed=None, max_size=None):
         lats = [("M", _lattice(KIND_MATMUL_ACCUM, [one, p2, p2, p2], layout=(1, 1, 1, 0, 0)), []),
                 # operands: lhs (m x k), rhs1 (k x p), rhs2 (p x n), out (m x n) (+ level of the intermediate, m x p)
                 ("G", _lattice(KIND_MATMUL_CHAIN, [p2, p2, p2, p2], layout=(1, 1, 1, 1, 0)), ["M"])]
+    elif number == 11:
+        # beyond the five benchmark configurations: config 5's pipeline with the second bufferize.
+        # Config 5's target recipe, but the vector unit has no fused add-and-ReLU: a scalar one,
+        # and vector microkernels for the bias add and for the ReLU alone (and scalar ones).  The
+        # bias-add + ReLU lattice S may split into the two (tables A, R), and the fused lattice
+        # reads S.  Sizes: config 5's up to 256.
+        t, w = _four_level_target(rng)
+        _add_transposed(t, rng)
+        t["zero_coef"] = list(w)
+        t["microkernels"].append((MK_SCALAR_ADDRELU, 1, 1))
+        t["microkernels"].append((MK_SCALAR_ADD, 1, 1))
+        t["microkernels"].append((MK_VEC_ADD, 8, 1))
+        t["microkernels"].append((MK_SCALAR_RELU, 1, 1))
+        t["microkernels"].append((MK_VEC_RELU, 8, 1))
+        r = keep([x for x in sizes_config5() if x <= 256])
+        lats = [
+            ("M", _lattice(KIND_MATMUL_ACCUM, [one, r, r, r], layout=(1, 1, 1, 0, 0)), []),
+            ("A", _lattice(KIND_BIAS_ADD, [one, r, one, r], layout=(1, 0, 1, 0, 0)), []),
+            ("R", _lattice(KIND_RELU, [one, r, one, r], layout=(1, 1, 0, 0, 0)), []),
+            ("S", _lattice(KIND_BIAS_ADD_RELU_SPLIT, [one, r, one, r], layout=(1, 0, 1, 0, 0)), ["A", "R"]),
+            ("F", _lattice(KIND_FUSED_MM_ADD_RELU, [one, r, r, r], layout=(1, 1, 0, 1, 0)), ["M", "S"]),
+        ]
     else:
-        raise ValueError("config number must be 1..10")
+        raise ValueError("config number must be 1..11")
     return {"name": "config%d" % number, "target": t, "lattices": lats}
 
 
 def n_level_axes(kind):
-    return 5 if kind in FIVE_LEVEL_KINDS else 2 if kind == KIND_MOVE else 3
+    return 5 if kind in FIVE_LEVEL_KINDS else 2 if kind in TWO_OPERAND_KINDS else 3
 
 
 def n_operands(kind):
-    return 4 if kind in FIVE_LEVEL_KINDS else 2 if kind == KIND_MOVE else 3
+    return 4 if kind in FIVE_LEVEL_KINDS else 2 if kind in TWO_OPERAND_KINDS else 3
 
 
 def coord_extents(target, lattice):

@@ -66,7 +66,12 @@ typedef enum {
   MRL_MK_VECTOR_MOVE = 6,       /* one row, n % lanes == 0, between level 1 and a level above 1
                                    (either way), both row-major, same type, the inner dimension
                                    of both tensors adjacent in memory (contiguousness >= 1)     */
-  MRL_MK_VECTOR_MOVE_ALIGNED = 7 /* the same, and both tensors aligned                           */
+  MRL_MK_VECTOR_MOVE_ALIGNED = 7, /* the same, and both tensors aligned                          */
+  /* the two halves of the bias-add + ReLU, for BIAS_ADD and RELU lattices */
+  MRL_MK_SCALAR_ADD = 8,        /* bias add, m=n=1, all in level 0                             */
+  MRL_MK_VEC_ADD = 9,           /* bias add, m=1, n % lanes == 0, all level 1, in and out row-major */
+  MRL_MK_SCALAR_RELU = 10,      /* ReLU, m=n=1, both in level 0                                */
+  MRL_MK_VEC_RELU = 11          /* ReLU, m=1, n % lanes == 0, both level 1, row-major          */
 } mrl_mk_kind;
 
 typedef struct { uint32_t kind; uint32_t lanes; uint64_t cost; } mrl_microkernel;
@@ -184,12 +189,30 @@ void mrl_target_destroy(mrl_target* t);
  * both equal this lattice's p, k and n lists (which must be equal); where an
  * operand here has a layout coordinate, the position it takes in the dep
  * (lhs, rhs1 -> lhs, rhs; rhs2, out -> rhs, out) must have one too.
+ * BIAS_ADD, RELU, BIAS_ADD_RELU_SPLIT (Section 2.1: compositions are lowered
+ * to their primitives by bufferize rewrites; here the second split of the
+ * Matmul -> bias add -> ReLU pipeline, between the add and the ReLU).
+ * BIAS_ADD: the operands and coordinates of BIAS_ADD_RELU (in m*n, bias n,
+ * out m*n written); the microkernels that apply are MRL_MK_SCALAR_ADD and
+ * MRL_MK_VEC_ADD.  RELU: in (m*n, read), out (m*n, written); b and k pinned
+ * to 1; microkernels MRL_MK_SCALAR_RELU and MRL_MK_VEC_RELU.
+ * BIAS_ADD_RELU_SPLIT: the BIAS_ADD_RELU Specs with the same rewrites and
+ * ids, plus, for every memory level l in which an intermediate (m*n, f32,
+ * row-major) fits next to those of the Spec's operands that live in l, a
+ * bufferize with id (FUSED's bufferize id) + l: the BIAS_ADD Spec (in, bias,
+ * intermediate at l) + the RELU Spec (intermediate at l, out); nothing
+ * accumulates into this intermediate, so it is not initialised.  deps =
+ * {BIAS_ADD table, RELU table} with this lattice's m and n lists, a layout
+ * coordinate on in (BIAS_ADD) / out (RELU) where this lattice has one.  A
+ * FUSED lattice takes a BIAS_ADD_RELU_SPLIT table as its second dep like a
+ * BIAS_ADD_RELU table: its programs then hold both splits.
  */
 typedef enum { MRL_KIND_MATMUL_ACCUM = 0, MRL_KIND_BIAS_ADD_RELU = 1,
                MRL_KIND_FUSED_MM_ADD_RELU = 2, MRL_KIND_MATMUL_PARALLEL = 3,
                MRL_KIND_MATMUL_BOUNDED = 4, MRL_KIND_BIAS_ADD_RELU_BOUNDED = 5,
                MRL_KIND_FUSED_BOUNDED = 6, MRL_KIND_MOVE = 7, MRL_KIND_MATMUL_MOVES = 8,
-               MRL_KIND_MATMUL_CHAIN = 9 } mrl_kind;
+               MRL_KIND_MATMUL_CHAIN = 9, MRL_KIND_BIAS_ADD = 10, MRL_KIND_RELU = 11,
+               MRL_KIND_BIAS_ADD_RELU_SPLIT = 12 } mrl_kind;
 
 typedef struct {
   uint32_t kind;
@@ -235,7 +258,8 @@ typedef struct mrl_table mrl_table;
 /* deps: host array of solved tables a FUSED lattice reads: {MATMUL_ACCUM table,
  * BIAS_ADD_RELU table} with the same m, k, n (m, n) size lists and target;
  * MATMUL_PARALLEL: {MATMUL_ACCUM table}; MATMUL_MOVES: {MOVE table};
- * MATMUL_CHAIN: {MATMUL_ACCUM table}; NULL / 0 otherwise.  d_cost (uint64 per Spec), d_argmin (uint16 per Spec) and
+ * MATMUL_CHAIN: {MATMUL_ACCUM table}; BIAS_ADD_RELU_SPLIT: {BIAS_ADD table,
+ * RELU table}; NULL / 0 otherwise.  d_cost (uint64 per Spec), d_argmin (uint16 per Spec) and
  * d_scratch are DEVICE pointers, 256-byte aligned, owned by the caller and
  * referenced by *out until mrl_table_destroy.  hip_stream: a hipStream_t (or
  * NULL for the default stream); part of the work runs on a helper stream of
@@ -354,9 +378,11 @@ int32_t mrl_query_compressed(const mrl_table* tab, const mrl_coord* specs, size_
  * Nodes in pre-order: a node is followed by the subtrees of its children
  * (0 for a microkernel, 1 for a tile or a Move: the loop body / the Spec on
  * the moved operand, 2 for bufferize: the Matmul, then the bias-add + ReLU;
- * in a MATMUL_CHAIN table the first Matmul, then the second, both in dep 0).
- * table: 0 = the table the walk started in, 1 + i = its dep i (the handles
- * given to mrl_solve as deps must still be alive).  cost = the table's entry
+ * in a MATMUL_CHAIN table the first Matmul, then the second, both in dep 0;
+ * in a BIAS_ADD_RELU_SPLIT table the bias add, then the ReLU).
+ * table: 0 = the table the walk started in, 1 + i = its dep i, 3 + i = dep i
+ * of its dep 1 (a BIAS_ADD_RELU_SPLIT table read by a FUSED one); the handles
+ * given to mrl_solve as deps must still be alive.  cost = the table's entry
  * of the node's Spec = cost of the whole subtree under Section 3's equation.
  * out: host array of cap nodes, or NULL to get the count only in *n_out;
  * MRL_E_INVAL if the goal has no implementation (cost MRL_INF), or for a table

@@ -226,7 +226,8 @@ class Table:
 
     def schedule(self, coord):
         """Program of the Spec at `coord`: [(table, coord, rewrite id, cost, children)] in
-        pre-order; table 0 = this table, 1 + i = the i-th table it was solved against."""
+        pre-order; table 0 = this table, 1 + i = the i-th table it was solved against, 3 + i = the
+        i-th table that one's second dep was solved against."""
         goal = _Coord()
         for a, v in enumerate(coord):
             goal.x[a] = int(v)
@@ -234,14 +235,21 @@ class Table:
         _check(lib().mrl_schedule(self._h, C.byref(goal), None, C.c_size_t(0), C.byref(n)))
         nodes = (_ScheduleNode * max(1, n.value))()
         _check(lib().mrl_schedule(self._h, C.byref(goal), nodes, C.c_size_t(n.value), C.byref(n)))
-        dims = [len(self.extents)] + [len(d.extents) for d in self._deps]
+        dims = [len(t.extents) for t in self._schedule_tables()]
         return [(nd.table, tuple(nd.spec.x[:dims[nd.table]]), nd.rewrite, nd.cost, nd.n_children)
                 for nd in nodes[:n.value]]
+
+    def _schedule_tables(self):
+        """Tables by the index a schedule node carries: this one, its deps, then the deps of its dep 1."""
+        tabs = (self,) + tuple(self._deps)
+        if len(self._deps) > 1:
+            tabs += (None,) * (3 - len(tabs)) + tuple(self._deps[1]._deps)
+        return tabs
 
     def program_text(self, coord):
         """The program of `coord` as indented text, one rewrite per line (the nesting of Section 2,
         Figure 1: a Move or a loop encloses the Spec it leaves, a microkernel is a leaf)."""
-        tabs = (self,) + self._deps
+        tabs = self._schedule_tables()
         lines, open_children = [], []
         for t, x, rid, cost, k in self.schedule(coord):
             tab = tabs[t]
@@ -261,7 +269,7 @@ class Table:
                 what = "parallel loop over %s: %d steps of %d, serial-only body" % (
                     "bmkn"[d], sizes[d][x[d]] // r.tile_size, r.tile_size)
             else:
-                what = "bufferize: Matmul into the intermediate, then the epilogue"
+                what = "bufferize: the first stage into the intermediate, then the second out of it"
             lines.append("%stable %d  %s  %s  cost %d  %s" % ("  " * len(open_children), t,
                          "x".join(str(sizes[d][x[d]]) for d in range(4)), tuple(x[4:]), cost, what))
             if k:

@@ -161,9 +161,10 @@ int32_t validate_target(const mrl_target_desc* d) {
   if (d->n_levels < 1 || d->n_levels > MRL_MAX_LEVELS) return fail(MRL_E_INVAL, "n_levels must be 1..4");
   if (d->n_microkernels > MRL_MAX_MK) return fail(MRL_E_INVAL, "too many microkernels");
   for (uint32_t j = 0; j < d->n_microkernels; j++) {
-    if (d->mk[j].kind > MRL_MK_VECTOR_MOVE_ALIGNED) return fail(MRL_E_INVAL, "unknown microkernel kind %u", d->mk[j].kind);
+    if (d->mk[j].kind > MRL_MK_VEC_RELU) return fail(MRL_E_INVAL, "unknown microkernel kind %u", d->mk[j].kind);
     if (d->mk[j].lanes < 1) return fail(MRL_E_INVAL, "microkernel lanes must be >= 1");
-    if (d->mk[j].kind != MRL_MK_SCALAR_FMA && d->mk[j].kind != MRL_MK_SCALAR_ADDRELU && d->mk[j].kind != MRL_MK_SCALAR_MOVE && d->n_levels < 2)
+    if (d->mk[j].kind != MRL_MK_SCALAR_FMA && d->mk[j].kind != MRL_MK_SCALAR_ADDRELU && d->mk[j].kind != MRL_MK_SCALAR_MOVE &&
+        d->mk[j].kind != MRL_MK_SCALAR_ADD && d->mk[j].kind != MRL_MK_SCALAR_RELU && d->n_levels < 2)
       return fail(MRL_E_INVAL, "vector microkernels need a level 1");
   }
   return MRL_OK;
@@ -171,16 +172,20 @@ int32_t validate_target(const mrl_target_desc* d) {
 
 int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c) {
   if (!L) return fail(MRL_E_INVAL, "lattice descriptor is NULL");
-  if (L->kind > MRL_KIND_MATMUL_CHAIN) return fail(MRL_E_INVAL, "unknown spec kind %u", L->kind);
+  if (L->kind > MRL_KIND_BIAS_ADD_RELU_SPLIT) return fail(MRL_E_INVAL, "unknown spec kind %u", L->kind);
   // A parallel lattice is a Matmul lattice (same operator, operands and coordinates) with more
   // rewrites; a bounded one is the lattice of its operator with more coordinates; a Matmul whose
   // Moves are Move Specs is a Matmul lattice with other Move costs; the composition of two Matmuls
   // has the fused Spec's structure (four operands and an intermediate between two stages).
   const bool chain = L->kind == MRL_KIND_MATMUL_CHAIN;
+  // The bias add alone has the operands and coordinates of the bias-add + ReLU (other microkernels
+  // apply to it); the ReLU alone has two tensors; the bias-add + ReLU with its own bufferize has
+  // more rewrites.
+  const bool add_only = L->kind == MRL_KIND_BIAS_ADD, relu_only = L->kind == MRL_KIND_RELU, split = L->kind == MRL_KIND_BIAS_ADD_RELU_SPLIT;
   const bool parallel = L->kind == MRL_KIND_MATMUL_PARALLEL, move_specs = L->kind == MRL_KIND_MOVE, moves = L->kind == MRL_KIND_MATMUL_MOVES;
   const bool bounded = L->kind >= MRL_KIND_MATMUL_BOUNDED && L->kind <= MRL_KIND_FUSED_BOUNDED;
   const uint32_t kind = parallel || moves ? (uint32_t)kKindM : bounded ? L->kind - MRL_KIND_MATMUL_BOUNDED : move_specs ? (uint32_t)kKindV
-                        : chain ? (uint32_t)kKindF : L->kind;
+                        : chain ? (uint32_t)kKindF : add_only || split ? (uint32_t)kKindE : relu_only ? (uint32_t)kKindR : L->kind;
   if (parallel && T.threads < 1) return fail(MRL_E_INVAL, "a MATMUL_PARALLEL lattice needs threads >= 1");
   if ((move_specs || moves) && T.line_bytes < 1) return fail(MRL_E_INVAL, "MOVE and MATMUL_MOVES lattices need line_bytes >= 1");
   c.target = T;
@@ -213,10 +218,11 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
   P.gather = bounded || move_specs || moves ? 1u : 0u;
   P.moves = moves ? 1u : 0u;
   P.chain = chain ? 1u : 0u;
+  P.split = split ? 1u : 0u;
   P.line_bytes = T.line_bytes;
   for (int l = 0; l < 4; l++) P.weight[l] = T.level_weight[l];
-  P.nops = kind == kKindF ? 4 : kind == kKindV ? 2 : 3;
-  P.nlv = kind == kKindF ? 5 : kind == kKindV ? 2 : 3;
+  P.nops = kind == kKindF ? 4 : kind == kKindV || kind == kKindR ? 2 : 3;
+  P.nlv = kind == kKindF ? 5 : kind == kKindV || kind == kKindR ? 2 : 3;
   P.NL = T.n_levels;
   P.npass = kind == kKindF ? P.NL : 1;
   P.ncombo = ipow(P.NL, P.nops);
@@ -238,7 +244,7 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
     maxs = std::max(maxs, n);
   }
   if (kind != kKindM && !chain && L->n_sizes[0] != 1) return fail(MRL_E_INVAL, "this kind has no batch dimension");
-  if (kind == kKindE && L->n_sizes[2] != 1) return fail(MRL_E_INVAL, "BIAS_ADD_RELU has no k dimension");
+  if ((kind == kKindE || kind == kKindR) && L->n_sizes[2] != 1) return fail(MRL_E_INVAL, "BIAS_ADD_RELU, BIAS_ADD and RELU have no k dimension");
   if (kind == kKindV && L->n_sizes[2] != 1) return fail(MRL_E_INVAL, "MOVE has no k dimension");
   if (moves && L->n_sizes[0] != 1) return fail(MRL_E_INVAL, "MATMUL_MOVES has no batch dimension");
   P.shape_stride[3] = 1;
@@ -291,7 +297,7 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
   P.tile_base = P.move_base + P.nops * (P.NL - 1) * 4;
   P.buf_id = P.tile_base + 4 * maxs;
   P.par_base = P.buf_id + 1;
-  if ((parallel ? P.par_base + 4 * maxs : P.buf_id) >= kNone) return fail(MRL_E_INVAL, "rewrite ids do not fit 16 bits");
+  if ((parallel ? P.par_base + 4 * maxs : P.buf_id + P.NL) >= kNone) return fail(MRL_E_INVAL, "rewrite ids do not fit 16 bits");
 
   // Moves: coefficient per (operand, src, dst, transposed) and the list of Moves that can occur
   for (uint32_t i = 0; i < (move_specs || moves ? 0u : P.nops); i++)
@@ -329,8 +335,12 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
           case MRL_MK_SCALAR_FMA: ok = P.kind == kKindM && !(lv[0] | lv[1] | lv[2]) && all_f32; break;
           case MRL_MK_BCAST_VEC_MULADD: ok = P.kind == kKindM && lv[0] == 0 && lv[1] == 1 && lv[2] == 1 && all_f32 && !ly[1] && !ly[2]; break;
           case MRL_MK_BF16_DOT: ok = P.kind == kKindM && lv[0] == 1 && lv[1] == 1 && lv[2] == 0 && bf[0] && bf[1] && !bf[2] && (P.lay_bit[1] == kNoBit || ly[1] == 1); break;
-          case MRL_MK_SCALAR_ADDRELU: ok = P.kind == kKindE && !(lv[0] | lv[1] | lv[2]); break;
-          case MRL_MK_VEC_ADDRELU: ok = P.kind == kKindE && lv[0] == 1 && lv[1] == 1 && lv[2] == 1 && !ly[0] && !ly[2]; break;
+          case MRL_MK_SCALAR_ADDRELU: ok = P.kind == kKindE && !add_only && !(lv[0] | lv[1] | lv[2]); break;
+          case MRL_MK_VEC_ADDRELU: ok = P.kind == kKindE && !add_only && lv[0] == 1 && lv[1] == 1 && lv[2] == 1 && !ly[0] && !ly[2]; break;
+          case MRL_MK_SCALAR_ADD: ok = add_only && !(lv[0] | lv[1] | lv[2]); break;
+          case MRL_MK_VEC_ADD: ok = add_only && lv[0] == 1 && lv[1] == 1 && lv[2] == 1 && !ly[0] && !ly[2]; break;
+          case MRL_MK_SCALAR_RELU: ok = relu_only && !(lv[0] | lv[1]); break;
+          case MRL_MK_VEC_RELU: ok = relu_only && lv[0] == 1 && lv[1] == 1 && !ly[0] && !ly[1]; break;
           // (the contiguousness / alignment part of the move microkernels' predicates is tested in the kernel)
           case MRL_MK_SCALAR_MOVE: ok = P.kind == kKindV && !(!bf[0] && bf[1]); break;
           case MRL_MK_VECTOR_MOVE:
@@ -462,7 +472,7 @@ bool same_problem(const Compiled& c, const mrl_target_desc& T, const mrl_lattice
 int32_t get_compiled(const mrl_target_desc& T, const mrl_lattice_desc* L, CompiledPtr& out) {
   static std::mutex mu;
   static std::vector<CompiledPtr> cache;          // most recent last, at most 8
-  if (L && L->kind <= MRL_KIND_MATMUL_CHAIN) {
+  if (L && L->kind <= MRL_KIND_BIAS_ADD_RELU_SPLIT) {
     std::lock_guard<std::mutex> lock(mu);
     for (size_t i = cache.size(); i-- > 0;)
       if (same_problem(*cache[i], T, *L)) { out = cache[i]; return MRL_OK; }
@@ -679,7 +689,21 @@ int32_t solve_impl(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_t
   tab->P = c.P;
   DevParams& P = tab->P;
 
-  if (P.chain) {
+  if (P.split) {
+    if (n_deps != 2 || !deps || !deps[0] || !deps[1]) return fail(MRL_E_INVAL, "a BIAS_ADD_RELU_SPLIT lattice needs deps = {BIAS_ADD table, RELU table}");
+    const Compiled& A = *deps[0]->cp;
+    const Compiled& R = *deps[1]->cp;
+    if (A.lat.kind != MRL_KIND_BIAS_ADD || R.lat.kind != MRL_KIND_RELU) return fail(MRL_E_INVAL, "deps must be {BIAS_ADD, RELU}");
+    if (memcmp(&A.target, &t->d, sizeof t->d) || memcmp(&R.target, &t->d, sizeof t->d)) return fail(MRL_E_INVAL, "deps were solved for another target");
+    if (A.sizes[1] != c.sizes[1] || A.sizes[3] != c.sizes[3] || R.sizes[1] != c.sizes[1] || R.sizes[3] != c.sizes[3])
+      return fail(MRL_E_INVAL, "the deps must have this lattice's m and n size lists");
+    if ((P.lay_bit[0] != kNoBit && A.P.lay_bit[0] == kNoBit) || (P.lay_bit[2] != kNoBit && R.P.lay_bit[1] == kNoBit))
+      return fail(MRL_E_INVAL, "a tensor with a layout coordinate in the BIAS_ADD_RELU_SPLIT lattice needs one in the dep it is looked up in");
+    P.costM = deps[0]->d_cost; P.costE = deps[1]->d_cost;
+    tab->deps[0] = deps[0]; tab->deps[1] = deps[1];
+    P.GM = A.P.G; P.VM = A.P.V; P.GE = R.P.G; P.VE = R.P.V;
+    for (int i = 0; i < 3; i++) { P.layM[i] = A.P.lay_bit[i]; P.layE[i] = R.P.lay_bit[i]; }
+  } else if (P.chain) {
     if (n_deps != 1 || !deps || !deps[0]) return fail(MRL_E_INVAL, "a MATMUL_CHAIN lattice needs deps = {MATMUL_ACCUM table}");
     const Compiled& M = *deps[0]->cp;
     if (M.P.kind != kKindM || M.P.par || M.P.bounded || M.P.moves) return fail(MRL_E_INVAL, "the dep must be a MATMUL_ACCUM table");
@@ -700,7 +724,8 @@ int32_t solve_impl(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_t
     if (n_deps != 2 || !deps || !deps[0] || !deps[1]) return fail(MRL_E_INVAL, "a FUSED lattice needs deps = {MATMUL_ACCUM table, BIAS_ADD_RELU table}");
     const Compiled& M = *deps[0]->cp;
     const Compiled& E = *deps[1]->cp;
-    if (M.P.kind != kKindM || M.P.par || E.P.kind != kKindE) return fail(MRL_E_INVAL, "deps must be {MATMUL_ACCUM, BIAS_ADD_RELU}");
+    if (M.P.kind != kKindM || M.P.par || E.P.kind != kKindE || E.lat.kind == MRL_KIND_BIAS_ADD)
+      return fail(MRL_E_INVAL, "deps must be {MATMUL_ACCUM, BIAS_ADD_RELU (or BIAS_ADD_RELU_SPLIT)}");
     if (M.P.bounded != P.bounded || E.P.bounded != P.bounded) return fail(MRL_E_INVAL, "memory bounds on all three tables or on none");
     if ((P.lay_bit[0] != kNoBit && M.P.lay_bit[0] == kNoBit) || (P.lay_bit[1] != kNoBit && M.P.lay_bit[1] == kNoBit) ||
         (P.lay_bit[3] != kNoBit && E.P.lay_bit[2] == kNoBit))
@@ -751,7 +776,7 @@ int32_t solve_impl(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_t
     P.GV = V.P.G; P.VV = V.P.V; P.nszV = V.P.nsz[3]; P.QV = V.P.Q; P.qV_top = V.P.Q - 1;
     for (int i = 0; i < 2; i++) { P.layV[i] = V.P.lay_bit[i]; P.dtV[i] = V.P.dt_bit[i]; }
   } else if (n_deps != 0) {
-    return fail(MRL_E_INVAL, "only FUSED, MATMUL_PARALLEL, MATMUL_MOVES and MATMUL_CHAIN lattices take deps");
+    return fail(MRL_E_INVAL, "only FUSED, MATMUL_PARALLEL, MATMUL_MOVES, MATMUL_CHAIN and BIAS_ADD_RELU_SPLIT lattices take deps");
   }
 
   std::unique_lock<std::mutex> solve_lock(c.solve_mu);      // for the upload image, until the upload has run
@@ -1348,6 +1373,7 @@ int32_t mrl_rewrite_decode(const mrl_table* tab, uint16_t id, mrl_rewrite* out) 
     return MRL_OK;
   }
   if (id == P.buf_id && P.kind == kKindF) { out->cls = 3; return MRL_OK; }
+  if (P.split && id >= P.buf_id && id < P.buf_id + P.NL) { out->cls = 3; out->dst_level = (uint8_t)(id - P.buf_id); return MRL_OK; }
   if (P.par && id >= P.par_base && id < P.par_base + 4 * P.maxs) {
     const uint32_t r = id - P.par_base, d = r / P.maxs, j = r % P.maxs;
     if (d != 2 && j < P.nsz[d]) { out->cls = 4; out->operand_or_dim = (uint8_t)d; out->tile_size = P.sizes[d][j]; return MRL_OK; }
@@ -1444,6 +1470,24 @@ int32_t mrl_schedule(const mrl_table* tab, const mrl_coord* goal, mrl_schedule_n
       ch.x.x[d] = j;
       stack.push_back(ch);
       node.n_children = 1;
+    } else if (r.cls == 3 && P.split) {     // bufferize between the bias add and the ReLU, the intermediate in level r.dst_level
+      if ((it.which != 0 && it.which != 2) || !it.t->deps[0] || !it.t->deps[1]) return fail(MRL_E_HIP, "internal error: bufferize outside a BIAS_ADD_RELU_SPLIT table");
+      const uint32_t m = c.sizes[1][it.x.x[1]], nn = c.sizes[3][it.x.x[3]];
+      const uint8_t l_mid = r.dst_level;
+      const uint8_t y_in = c.lay_axis[0] >= 0 ? (uint8_t)it.x.x[c.lay_axis[0]] : 0, y_out = c.lay_axis[2] >= 0 ? (uint8_t)it.x.x[c.lay_axis[2]] : 0;
+      const uint32_t shape_e[4] = {1, m, 1, nn};
+      const uint8_t lv_a[5] = {(uint8_t)it.x.x[4], (uint8_t)it.x.x[5], l_mid, 0, 0}, ly_a[5] = {y_in, 0, 0, 0, 0};
+      const uint8_t lv_r[5] = {l_mid, (uint8_t)it.x.x[6], 0, 0, 0}, ly_r[5] = {0, y_out, 0, 0, 0};
+      const uint8_t zeros[5] = {0, 0, 0, 0, 0};
+      // (tables 3 and 4 when this table is itself dep 1 of the table the walk started in)
+      Item ca{it.t->deps[0], it.which + 1u, {}}, cr{it.t->deps[1], it.which + 2u, {}};
+      rc = mrl_coord_of_spec(ca.t, shape_e, lv_a, ly_a, zeros, &ca.x);
+      if (rc) return rc;
+      rc = mrl_coord_of_spec(cr.t, shape_e, lv_r, ly_r, zeros, &cr.x);
+      if (rc) return rc;
+      stack.push_back(cr);                  // popped after the bias add's whole subtree
+      stack.push_back(ca);
+      node.n_children = 2;
     } else if (r.cls == 3 && P.chain) {     // bufferize of a composition: the Matmul (m, k, p) into the intermediate, then (m, p, n) out of it
       if (it.which != 0 || !it.t->deps[0]) return fail(MRL_E_HIP, "internal error: bufferize outside a MATMUL_CHAIN table");
       const uint32_t p = c.sizes[0][it.x.x[0]], m = c.sizes[1][it.x.x[1]], k = c.sizes[2][it.x.x[2]], nn = c.sizes[3][it.x.x[3]];

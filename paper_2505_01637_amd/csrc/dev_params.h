@@ -15,7 +15,8 @@ constexpr int kMaxCombo = 256;               // n_levels ^ n_operands
 constexpr int kMaxRanks = 16;
 constexpr uint32_t kNoBit = 0xFF;            // "this operand has no such coordinate"
 
-enum : uint32_t { kKindM = 0, kKindE = 1, kKindF = 2, kKindV = 3 };   // V: Move Specs (two tensors: source, destination)
+enum : uint32_t { kKindM = 0, kKindE = 1, kKindF = 2, kKindV = 3,     // V: Move Specs (two tensors: source, destination)
+                  kKindR = 4 };                                         // R: ReLU alone (in, out); the bias add alone is kKindE
 enum : uint32_t { kRead = 0, kRmw = 1, kWrite = 2 };
 
 // One tile rewrite of a (dim, size index): the index of the smaller size and the trip count.
@@ -96,6 +97,11 @@ struct DevParams {
   // sizes[0] holds p, the dimension the two Matmuls share: lhs m x k, rhs1 k x p, rhs2 p x n, out
   // m x n (accumulated into), intermediate m x p.  Both stages are read from costM.
   uint32_t chain;
+  // ---- the bias-add + ReLU with the bufferize between the two (kind stays kKindE) ----
+  // One more rewrite per level l of the intermediate (m x n, f32, row-major): the bias-add Spec
+  // (in, bias, intermediate) read from costM and the ReLU Spec (intermediate, out) read from costE;
+  // GM / VM / layM and GE / VE / layE describe those two tables.  Ids buf_id + l.
+  uint32_t split;
   uint32_t layM[3], layE[3]; // layout bit positions in the dependency's variant index
 };
 

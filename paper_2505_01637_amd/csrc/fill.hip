@@ -87,7 +87,8 @@ __device__ __forceinline__ void load_shape(const DevParams* __restrict__ P, uint
   uint64_t b = S.d[0], m = S.d[1], k = S.d[2], n = S.d[3];
   if (P->kind == kKindM) { S.numel[0] = b * m * k; S.numel[1] = b * k * n; S.numel[2] = b * m * n; S.numel[3] = 0; S.numel[4] = 0; }
   else if (P->kind == kKindV) { S.numel[0] = m * n; S.numel[1] = m * n; S.numel[2] = 0; S.numel[3] = 0; S.numel[4] = 0; }
-  else if (P->kind == kKindE) { S.numel[0] = m * n; S.numel[1] = n; S.numel[2] = m * n; S.numel[3] = 0; S.numel[4] = 0; }
+  else if (P->kind == kKindE) { S.numel[0] = m * n; S.numel[1] = n; S.numel[2] = m * n; S.numel[3] = 0; S.numel[4] = m * n; }   // [4]: the intermediate of a split
+  else if (P->kind == kKindR) { S.numel[0] = m * n; S.numel[1] = m * n; S.numel[2] = 0; S.numel[3] = 0; S.numel[4] = 0; }
   else if (P->chain) { S.numel[0] = m * k; S.numel[1] = k * b; S.numel[2] = b * n; S.numel[3] = m * n; S.numel[4] = m * b; }   // b holds p
   else { S.numel[0] = m * k; S.numel[1] = k * n; S.numel[2] = n; S.numel[3] = m * n; S.numel[4] = m * n; }
 }
@@ -148,6 +149,10 @@ __device__ __forceinline__ uint64_t mk_shape_reps(const DevParams* __restrict__ 
     case 5: return (m == 1 && n == 1) ? 1 : 0;                       // Move Specs: m rows, n columns
     case 6:
     case 7: return (m == 1 && n % lanes == 0) ? n / lanes : 0;
+    case 8:                                                          // bias add alone, ReLU alone: one element,
+    case 10: return (m == 1 && n == 1) ? 1 : 0;
+    case 9:                                                          // or one row of whole vectors
+    case 11: return (m == 1 && n % lanes == 0) ? n / lanes : 0;
     default: return 0;
   }
 }
@@ -385,10 +390,32 @@ __device__ __forceinline__ void task_tiles(const DevParams* __restrict__ P, cons
 
 // bufferize (FUSED): Matmul into the intermediate, then bias-add+ReLU out of it.  The composition
 // of two Matmuls (Section 2.1): the first, (m, k, p), into the intermediate, then the second,
-// (m, p, n), out of it; both are entries of the same Matmul table.
-__device__ __forceinline__ void task_bufferize(const DevParams* __restrict__ P, const Shape& S, uint32_t shape,
-                                               uint32_t xpack, uint32_t v, Eval& e) {
+// (m, p, n), out of it; both are entries of the same Matmul table.  The bias-add + ReLU with its
+// own bufferize: per level l in which the intermediate fits next to the operands that live there
+// (fit: build_fit's words), the bias add into it plus the ReLU out of it.
+// Returns the number of candidates evaluated.
+__device__ __forceinline__ uint32_t task_bufferize(const DevParams* __restrict__ P, const Shape& S, uint32_t shape,
+                                                   uint32_t xpack, uint32_t v, const uint32_t* fit, Eval& e) {
   const uint32_t NL = P->NL, pack = xpack & 0xFFu, pass = xpack >> 8;
+  if (P->split) {
+    const uint32_t l0 = (pack >> P->pack_shift[0]) & 3u, l1 = (pack >> P->pack_shift[1]) & 3u, l2 = (pack >> P->pack_shift[2]) & 3u;
+    const uint32_t y0 = P->lay_bit[0] != kNoBit ? (v >> P->lay_bit[0]) & 1u : 0u;
+    const uint32_t y2 = P->lay_bit[2] != kNoBit ? (v >> P->lay_bit[2]) & 1u : 0u;
+    const uint64_t sh = (uint64_t)(S.si[1] * P->nsz[3] + S.si[3]);
+    const uint32_t va = P->layM[0] != kNoBit ? y0 << P->layM[0] : 0u, vr = P->layE[1] != kNoBit ? y2 << P->layE[1] : 0u;
+    uint32_t cnt = 0;
+    for (uint32_t l = 0; l < NL; l++) {
+      const uint32_t subset = (l0 == l ? 1u : 0u) | (l1 == l ? 2u : 0u) | (l2 == l ? 4u : 0u) | 16u;
+      if (!((fit[l] >> subset) & 1u)) continue;
+      const uint64_t ca = P->costM[sh * P->GM + ((l0 * NL + l1) * NL + l) * P->VM + va];
+      const uint64_t cr = P->costE[sh * P->GE + (l * NL + l2) * P->VE + vr];
+      if (ca != kInf && cr != kInf) {
+        if (ca + cr >= kLimit) e.ovf = 1; else consider(e, ca + cr, P->buf_id + l);     // each below 2^62: no wrap
+      }
+      cnt++;
+    }
+    return cnt;
+  }
   const uint32_t l0 = (pack >> P->pack_shift[0]) & 3u, l1 = (pack >> P->pack_shift[1]) & 3u;
   const uint32_t l2 = (pack >> P->pack_shift[2]) & 3u, l3 = (pack >> P->pack_shift[3]) & 3u;
   const uint32_t y0 = P->lay_bit[0] != kNoBit ? (v >> P->lay_bit[0]) & 1u : 0u;
@@ -409,7 +436,7 @@ __device__ __forceinline__ void task_bufferize(const DevParams* __restrict__ P, 
       const uint64_t sum = z + c1;          // each term <= 2^62: no wrap
       if (z >= kLimit || sum >= kLimit || sum + c2 >= kLimit) e.ovf = 1; else consider(e, sum + c2, P->buf_id);
     }
-    return;
+    return 1;
   }
   const uint32_t xm = ((l0 * NL + l1) * NL + pass) * P->VM +
                       (P->layM[0] != kNoBit ? y0 << P->layM[0] : 0u) + (P->layM[1] != kNoBit ? y1 << P->layM[1] : 0u);
@@ -421,6 +448,7 @@ __device__ __forceinline__ void task_bufferize(const DevParams* __restrict__ P, 
     const uint64_t sum = z + cm;          // each term <= 2^62: no wrap
     if (z >= kLimit || sum >= kLimit || sum + ce >= kLimit) e.ovf = 1; else consider(e, sum + ce, P->buf_id);
   }
+  return 1;
 }
 
 // The rank loop gives every task a quad of lanes, one per operand: lane `op` of the quad
@@ -641,7 +669,8 @@ __device__ __forceinline__ void solve_unit(const DevParams* __restrict__ P, cons
   build_move_costs<T>(P, S, pre, L.bterm);
 
   // ---- 3. tile and bufferize candidates of every task (sub-Specs of other shapes / tables: final) ----
-  const uint32_t n_per_task = n_tile + (P->kind == kKindF ? 1u : 0u);
+  const bool has_buf = P->kind == kKindF || P->split;
+  const uint32_t n_per_task = n_tile;          // (the bufferize candidates are counted where they are evaluated)
   for (uint32_t e0 = 0; e0 == 0 || e0 < n_tile; e0 += kTileLds) {
     if (e0) {
       unit_sync<T>();
@@ -661,7 +690,7 @@ __device__ __forceinline__ void solve_unit(const DevParams* __restrict__ P, cons
         Eval e;
         e.ovf = 0; e.best = kInf; e.arg = kNone;
         if (sub4 == 0) {
-          if (e0 == 0) { if (P->kind == kKindF) task_bufferize(P, S, shape, xpack, v, e); }
+          if (e0 == 0) { if (has_buf) { const uint32_t nb = task_bufferize(P, S, shape, xpack, v, L.fit, e); tot.n += active ? nb : 0u; } }
           else { e.best = L.t_cost[q]; e.arg = sp >> 16; }
         }
         task_tiles(P, L, n_here, par_from, sub4, 4, entry_offset(H, xpack, v), cost, e);
@@ -681,7 +710,7 @@ __device__ __forceinline__ void solve_unit(const DevParams* __restrict__ P, cons
         e.ovf = 0;
         if (e0 == 0) {
           e.best = kInf; e.arg = kNone;
-          if (P->kind == kKindF) task_bufferize(P, S, shape, xpack, v, e);
+          if (has_buf) tot.n += task_bufferize(P, S, shape, xpack, v, L.fit, e);
         } else {
           e.best = L.t_cost[q]; e.arg = sp >> 16;
         }

@@ -406,6 +406,70 @@ def test_parity_composition_of_two_matmuls(case):
     check_compressed_queries(got["G"], want["G"], 2_000, seed=7)
 
 
+def split_config(sizes, layout=True, levels=4, fused=True, seed=5):
+    """The bias add alone, the ReLU alone, the bias-add + ReLU with the bufferize between the two,
+    and (fused=True) the Matmul and the fused lattice that reads it."""
+    cfg = W.config(11, seed=seed, max_size=1)
+    t = cfg["target"]
+    if levels == 2:
+        t = W._empty_target(2, (48, 4096))
+        t["load_coef"][1][0][0], t["store_coef"][0][1][0] = 3, 2
+        t["load_coef"][1][0][1], t["store_coef"][0][1][1] = 5, 4
+        t["loop_overhead"] = 2
+        t["zero_coef"] = [1, 3, 0, 0]
+        t["microkernels"] = [(W.MK_SCALAR_FMA, 1, 1), (W.MK_SCALAR_ADDRELU, 1, 5), (W.MK_SCALAR_ADD, 1, 1), (W.MK_VEC_ADD, 4, 2),
+                             (W.MK_SCALAR_RELU, 1, 1), (W.MK_VEC_RELU, 4, 1)]
+    r = list(sizes)
+    y = 1 if layout else 0
+    lats = [("A", W._lattice(W.KIND_BIAS_ADD, [[1], r, [1], r], layout=(y, 0, y, 0, 0)), []),
+            ("R", W._lattice(W.KIND_RELU, [[1], r, [1], r], layout=(y, y, 0, 0, 0)), []),
+            ("S", W._lattice(W.KIND_BIAS_ADD_RELU_SPLIT, [[1], r, [1], r], layout=(y, 0, y, 0, 0)), ["A", "R"])]
+    if fused:
+        lats = [("M", W._lattice(W.KIND_MATMUL_ACCUM, [[1], r, r, r], layout=(y, y, y, 0, 0)), [])] + lats
+        lats.append(("F", W._lattice(W.KIND_FUSED_MM_ADD_RELU, [[1], r, r, r], layout=(y, y, 0, y, 0)), ["M", "S"]))
+    return {"name": "split", "target": t, "lattices": lats}
+
+
+@pytest.mark.parametrize("case", ["config11-8", "config11-32", "no-layouts", "two-levels", "ragged-sizes", "long-lists", "one-shape"])
+def test_parity_second_bufferize(case):
+    """The bias add and the ReLU as lattices of their own, the bias-add + ReLU that may bufferize
+    between the two, and the fused lattice reading it: dense tables, counters, both box lists."""
+    if case.startswith("config11"):
+        cfg = W.config(11, max_size=int(case.split("-")[1]))
+    elif case == "no-layouts":
+        cfg = split_config([1, 2, 4, 8, 16], layout=False)
+    elif case == "two-levels":
+        cfg = split_config([1, 2, 4, 8, 16, 32], levels=2)
+    elif case == "ragged-sizes":
+        cfg = split_config([1, 3, 5, 9, 15, 24, 40])
+    elif case == "long-lists":
+        cfg = split_config(list(range(1, 97)), fused=False)
+    else:
+        cfg = split_config([1])
+    _, got, want = compare_config(cfg)
+    ids = O.geometry(cfg["target"], next(l for lb, l, _ in cfg["lattices"] if lb == "S"))[2]
+    if case not in ("one-shape",):
+        assert (want["S"]["argmin"] >= ids["bufferize"]).any() and (want["S"]["argmin"] != O.NONE).any()
+    check_compressed_queries(got["S"], want["S"], 2_000, seed=11)
+
+
+def test_second_bufferize_host_checks():
+    B = _binding()
+    cfg = split_config([1, 2, 4], fused=False)
+    a, r, s = cfg["lattices"]
+    for lattices in ([a, r, ("S", s[1], ["R", "A"])], [a, r, ("S", s[1], [])],
+                     [a, ("R", dict(r[1], sizes=[[1], [1, 2], [1], [1, 2, 4]]), []), s]):
+        with pytest.raises(B.MorelloError) as e:
+            B.solve_config({"name": "bad", "target": cfg["target"], "lattices": lattices})
+        assert e.value.code == B.E_INVAL
+    # a fused lattice does not take the bias add alone as its second stage
+    cfg = split_config([1, 2])
+    lats = [l for l in cfg["lattices"] if l[0] in "MA"] + [("F", cfg["lattices"][-1][1], ["M", "A"])]
+    with pytest.raises(B.MorelloError) as e:
+        B.solve_config({"name": "bad", "target": cfg["target"], "lattices": lats})
+    assert e.value.code == B.E_INVAL
+
+
 def test_composition_host_checks():
     B = _binding()
     cfg = chain_config([1, 2, 4])
@@ -524,7 +588,7 @@ def test_deterministic():
 
 @pytest.mark.gpu
 @pytest.mark.parametrize("number,max_size,label", [(1, None, "M"), (3, 64, "M"), (4, 8, "M"), (5, 8, "F"), (5, 8, "E"),
-                                                   (6, 16, "P"), (7, 8, "B"), (10, 4, "G")])
+                                                   (6, 16, "P"), (7, 8, "B"), (10, 4, "G"), (11, 16, "S"), (11, 8, "F")])
 def test_schedule_parity(number, max_size, label):
     """mrl_schedule walks the same programs as the oracle's extraction: same Specs, rewrites and
     costs, node by node in pre-order; a goal without implementation is an error."""
@@ -535,6 +599,8 @@ def test_schedule_parity(number, max_size, label):
     tab = got[label]
     deps = next(d for lb, _, d in cfg["lattices"] if lb == label)
     names = [label] + list(deps)
+    if len(deps) > 1:       # then the tables that the second dep reads (none, or a bias-add and a ReLU table)
+        names += [None] * (3 - len(names)) + list(next(d for lb, _, d in cfg["lattices"] if lb == deps[1]))
     cost = want[label]["cost"]
     ext = [int(e) for e in want[label]["extents"]]
     rng = np.random.default_rng(number)

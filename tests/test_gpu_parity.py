@@ -82,6 +82,18 @@ def test_parity_config5_full_size():
     solve_fused_in_slabs(cfg, got, want, 8, boxes=False, scratch_bytes=1 << 30)
 
 
+def test_parity_config11_full_size():
+    """Config 11 (the pipeline with both bufferize splits; M 22.0 M, A and S 0.31 M, R 0.08 M,
+    F 351.2 M specs) at full size: dense tables and counters of all five tables, and the box lists
+    of the three small ones."""
+    cfg = W.config(11)
+    _, got, want = compare_config(cfg, boxes=False, scratch_bytes=6 << 30)
+    for label in "ARS":
+        lat = next(l for lb, l, _ in cfg["lattices"] if lb == label)
+        dec, cst = O.compress_table(cfg["target"], lat, want[label]["cost"], want[label]["argmin"])
+        assert got[label].boxes(0).tobytes() == dec.tobytes() and got[label].boxes(1).tobytes() == cst.tobytes()
+
+
 def solve_fused_in_slabs(cfg, tabs, want, n_slabs, boxes=True, scratch_bytes=None):
     """Solve the fused lattice of `cfg` slab by slab along k (against the solved tables M and E in
     `tabs`), every slab into the same device buffers, and compare every slab with the slice of

@@ -70,7 +70,49 @@ def operand_mode(kind, i):
     return "w" if i == 3 else "r"
 
 
+def physical_dims(target, layout, rows, cols):
+    """Extents of the physical dimensions, outermost first (Section 2.4.2): row-major, column-major,
+    and for the two packed layouts strips, rows, columns of a strip."""
+    if layout == 0:
+        return (rows, cols)
+    if layout == 1:
+        return (cols, rows)
+    s = target["strip"]
+    if cols >= s:
+        return (cols // s, rows, s)
+    return (1, rows, cols)            # a tile out of one strip: the same part of every row of the strip
+
+
+def most_adjacent(target, layout, cols):
+    """Upper limit of contiguousness: all physical dimensions of a tensor of whole strips (or of a
+    row-/column-major one); of a part of a strip only the part itself (rows lie a strip apart),
+    and of a shuffled strip not even that, unless the part is one column."""
+    if layout < 2:
+        return 2
+    if cols >= target["strip"]:
+        return 3
+    if layout == 2:
+        return 1
+    return 1 if cols == 1 else 0
+
+
+def tensor_exists(target, spec, i):
+    b, m, k, n = spec.dims
+    rows, cols = (m, n) if spec.kind == V else ((m, k), (k, n), (m, n))[i]
+    if spec.layouts[i] >= 2:
+        s = target["strip"]
+        whole_strips = cols % s == 0
+        part_of_one = cols < s and s % cols == 0
+        if not (whole_strips or (part_of_one and spec.kind == V)):      # an operand of a Matmul is a whole tensor
+            return False
+    if spec.kind == V and spec.contig[i] > most_adjacent(target, spec.layouts[i], cols):
+        return False
+    return True
+
+
 def fits(target, spec):
+    if spec.kind in (V, MV) and not all(tensor_exists(target, spec, i) for i in range(2 if spec.kind == V else 3)):
+        return False
     if spec.kind in BOUNDED or spec.kind == V:
         return True          # the bounds decide at each allocation, not the operands' footprint;
                              # the two tensors of a Move exist already
@@ -91,8 +133,9 @@ def microkernel_reps(target, lattice, spec, j):
         ok = spec.kind in MATMULS and (b, m, k, n) == (1, 1, 1, 1) and tuple(lv[:3]) == (0, 0, 0) and not any(bf[:3])
         return 1 if ok else 0
     if kind == BCAST:
+        rowlike = lambda y: y == 0 or (y == 2 and target["strip"] % lanes == 0)   # one row in whole strips reads like a row
         ok = (spec.kind in MATMULS and (b, m, k) == (1, 1, 1) and n % lanes == 0
-              and tuple(lv[:3]) == (0, 1, 1) and not any(bf[:3]) and ly[1] == 0 and ly[2] == 0)
+              and tuple(lv[:3]) == (0, 1, 1) and not any(bf[:3]) and rowlike(ly[1]) and rowlike(ly[2]))
         return n // lanes if ok else 0
     if kind == BF16DOT:
         rhs_col = ly[1] == 1 or not lattice["layout_coord"][1]
@@ -124,7 +167,8 @@ def microkernel_reps(target, lattice, spec, j):
     if kind in (V_MOVE, V_MOVE_ALIGNED):
         ok = (spec.kind == V and m == 1 and n % lanes == 0
               and ((lv[0] == 1 and lv[1] > 1) or (lv[1] == 1 and lv[0] > 1))
-              and ly[0] == 0 and ly[1] == 0 and bf[0] == bf[1]
+              and all(y == 0 or (y >= 2 and (n < target["strip"] or target["strip"] % lanes == 0)) for y in ly[:2])
+              and (ly[0] == 3) == (ly[1] == 3) and bf[0] == bf[1]
               and spec.contig[0] >= 1 and spec.contig[1] >= 1
               and (kind == V_MOVE or (spec.aligned[0] and spec.aligned[1])))
         return n // lanes if ok else 0
@@ -135,13 +179,28 @@ def tiled_tensor(target, spec, t, rows2, cols2):
     """(contiguousness, aligned) of tensor t of a Move Spec after cutting a rows2 x cols2 tile out
     of it (Section 2.4.3)."""
     rows, cols = spec.dims[1], spec.dims[3]
-    col_major = spec.layouts[t]
-    inner, inner2, outer2 = (rows, rows2, cols2) if col_major else (cols, cols2, rows2)
+    if spec.layouts[t] >= 2:
+        s = target["strip"]
+        for cc in (cols, cols2):
+            if not (cc % s == 0 or (cc < s and s % cc == 0)):
+                return 0, 0                 # no such tensor, or no such tile: the sub-Spec has no program anyway
+    whole = physical_dims(target, spec.layouts[t], rows, cols)
+    part = physical_dims(target, spec.layouts[t], rows2, cols2)
     e = 2 if spec.bf16[t] else 4
     line = target["line_bytes"]
-    contig = spec.contig[t] if inner2 == inner else min(spec.contig[t], 1)
-    aligned = int(bool(spec.aligned[t]) and spec.contig[t] == 2 and (inner2 * e) % line == 0
-                  and (outer2 * inner2 * e) % line == 0)
+    uncut = 0           # innermost dimensions that the tile takes whole
+    for w, p in zip(reversed(whole), reversed(part)):
+        if w != p:
+            break
+        uncut += 1
+    contig = min(spec.contig[t], 1 + uncut, most_adjacent(target, spec.layouts[t], cols2))
+    suffixes, prod = [], e
+    for p in reversed(part):
+        prod *= p
+        suffixes.append(prod)
+    part_of_strip = spec.layouts[t] >= 2 and cols2 < target["strip"]      # not known to be aligned
+    aligned = int(bool(spec.aligned[t]) and spec.contig[t] == len(whole) and not part_of_strip
+                  and all(x % line == 0 for x in suffixes))
     return contig, aligned
 
 
@@ -158,7 +217,8 @@ def rewrites(target, lattices, spec):
     nmk = len(target["microkernels"])
     maxs = max(len(s) for s in lattice["sizes"])
     move_base = nmk
-    tile_base = nmk + nops * (nl - 1) * 4
+    xw = 4 if 2 in lattice["layout_coord"][:nops] else 2       # layout changes a Move id can name
+    tile_base = nmk + nops * (nl - 1) * 2 * xw
     for j in range(nmk):
         reps = microkernel_reps(target, lattice, spec, j)
         if reps:
@@ -167,9 +227,11 @@ def rewrites(target, lattices, spec):
         mode = operand_mode(spec.kind, i)
         src = spec.levels[i]
         for dst in range(src):
-            for x in (0, 1):
+            for x in range(xw):
                 for cv in (0, 1):
                     if x and not lattice["layout_coord"][i]:
+                        continue
+                    if x >= 2 and lattice["layout_coord"][i] != 2:
                         continue
                     if cv and not (lattice["dtype_coord"][i] and spec.bf16[i] and mode == "r"):
                         continue
@@ -180,20 +242,22 @@ def rewrites(target, lattices, spec):
                         rows, cols = ((m_, k_), (k_, n_), (m_, n_))[i]
                         y0, y1 = spec.layouts[i], spec.layouts[i] ^ x
                         f0, f1 = spec.bf16[i], 0 if cv else spec.bf16[i]
-                        top = dict(kind=V, dims=(1, rows, 1, cols), limits=(), contig=(2, 2), aligned=(1, 1))
+                        top = dict(kind=V, dims=(1, rows, 1, cols), limits=(), aligned=(1, 1))
+                        n0 = 3 if y0 >= 2 else 2        # fresh tensors: every physical dimension adjacent
+                        n1 = 3 if y1 >= 2 else 2
                         kids = []
                         if "r" in mode:
-                            kids.append(Spec(levels=(src, dst), layouts=(y0, y1), bf16=(f0, f1), **top))
+                            kids.append(Spec(levels=(src, dst), layouts=(y0, y1), bf16=(f0, f1), contig=(n0, n1), **top))
                         lv = list(spec.levels); lv[i] = dst
                         ly = list(spec.layouts); ly[i] = y1
                         bf = list(spec.bf16); bf[i] = f1
                         kids.append(spec._replace(levels=tuple(lv), layouts=tuple(ly), bf16=tuple(bf)))
                         if "w" in mode:
-                            kids.append(Spec(levels=(dst, src), layouts=(y1, y0), bf16=(f1, f0), **top))
+                            kids.append(Spec(levels=(dst, src), layouts=(y1, y0), bf16=(f1, f0), contig=(n1, n0), **top))
                         w = target["level_weight"]
                         fixed = (cache_lines(target, rows * cols, 2 if f0 else 4) * w[src]
                                  + cache_lines(target, rows * cols, 2 if f1 else 4) * w[dst])
-                        rid = move_base + ((i * (nl - 1) + dst) * 2 + x) * 2 + cv
+                        rid = move_base + ((i * (nl - 1) + dst) * xw + x) * 2 + cv
                         yield rid, ("alloc", fixed), kids
                         continue
                     coef = 0
@@ -223,7 +287,7 @@ def rewrites(target, lattices, spec):
                         lim = list(spec.limits)
                         lim[dst] = 0 if left == 0 else 1 << (left.bit_length() - 1)
                         child = child._replace(limits=tuple(lim))
-                    rid = move_base + ((i * (nl - 1) + dst) * 2 + x) * 2 + cv
+                    rid = move_base + ((i * (nl - 1) + dst) * xw + x) * 2 + cv
                     yield rid, ("alloc", coef * operand_numel(spec, i)), [child]
     for d in range(4):
         if base_kind(spec.kind) != M and d in (0, 2):

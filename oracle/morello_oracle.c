@@ -48,6 +48,10 @@
  * own, and kind 12 the Specs of kind 1 with one more rewrite per memory level:
  * a bufferize that splits the composition into the bias add writing an
  * intermediate in that level and the ReLU reading it.
+ * Layouts (Section 2.4.2): besides row-major (0) and column-major (1), where a
+ * lattice of kind 7 or 8 sets layout_coord to 2 a tensor may be packed in
+ * strips of `strip` columns (2) and packed with odd-even shuffled strips (3);
+ * orc_layout_offset writes the four buffer indexing expressions out.
  */
 #define _GNU_SOURCE             /* qsort_r */
 #include <stdint.h>
@@ -88,13 +92,14 @@ typedef struct {
   uint32_t sync_cost;                          /* the constant s of a parallel loop */
   uint32_t level_weight[ORC_MAXL];             /* weight_level of m(t), Section 3 (kind 8) */
   uint32_t line_bytes;                         /* cache line: unit of lines(t) and of alignment (kinds 7, 8) */
+  uint32_t strip;                              /* columns per strip of the packed layouts (kinds 7, 8; even) */
 } orc_target;
 
 typedef struct {
   uint32_t kind;
   uint32_t n_sizes[4];
   const uint32_t* sizes[4];                    /* b, m, k, n */
-  uint8_t layout_coord[ORC_MAXOPS];
+  uint8_t layout_coord[ORC_MAXOPS];            /* 0 none, 1 row-/column-major, 2 those and the two packed layouts */
   uint8_t dtype_coord[ORC_MAXOPS];
   uint8_t base_dtype_bytes[ORC_MAXOPS];
 } orc_lattice;
@@ -103,12 +108,13 @@ typedef struct {
 typedef struct {
   uint32_t si[4];               /* index of b, m, k, n in the allowed-size lists */
   uint8_t level[ORC_MAXOPS];    /* per operand; kind F: level[4] = intermediate */
-  uint8_t layout[ORC_MAXOPS];   /* 0 row-major, 1 column-major */
+  uint8_t layout[ORC_MAXOPS];   /* 0 row-major, 1 column-major, 2 packed strips, 3 packed and shuffled strips */
   uint8_t bf16[ORC_MAXOPS];     /* 0 f32, 1 bf16 */
   uint8_t limit[ORC_MAXL];      /* kind B: per bounded level, index of the memory bound: 0 -> 0 bytes,
                                    q -> 2^(q-1) bytes */
   uint8_t contig[2];            /* kind V, per tensor (source, destination): number of inner physical
-                                   dimensions whose values are adjacent in memory, 0..2 (Section 2.4.3) */
+                                   dimensions whose values are adjacent in memory, 0..2, for a packed
+                                   tensor (three physical dimensions) 0..3 (Section 2.4.3) */
   uint8_t aligned[2];           /* kind V: 1 = the tensor starts at a multiple of the cache line */
 } spec_t;
 
@@ -129,6 +135,7 @@ typedef struct ctx {
   int lim_axis[ORC_MAXL];       /* coordinate axis of level l's bound, -1 if the level is unbounded */
   int moves;                    /* kind 8: Moves are Move Specs, looked up in depM (a kind V table) */
   int split;                    /* kind 12: kind E plus bufferize(level); depM = the bias-add table, depE = the ReLU table */
+  int packed;                   /* kinds 7, 8: some tensor has the four-layout coordinate (Move ids then hold 4 layout changes) */
   int abs_axis;                 /* kind V: first of the four axes contig(src), aligned(src), contig(dst), aligned(dst); -1 else */
   uint64_t n_rewrites, n_admissible;
   int overflow;
@@ -158,6 +165,13 @@ static int ctx_init(ctx* c, const orc_target* T, const orc_lattice* L) {
   c->nops = c->kind == KIND_F || c->kind == KIND_G ? 4 : c->kind == KIND_V || c->kind == KIND_R ? 2 : 3;
   c->nlv = c->kind == KIND_F || c->kind == KIND_G ? 5 : c->kind == KIND_V || c->kind == KIND_R ? 2 : 3;
   if ((c->kind == KIND_V || c->moves) && T->line_bytes < 1) return -1;
+  for (int i = 0; i < c->nops; i++) {
+    if (L->layout_coord[i] > 2) return -1;
+    if (L->layout_coord[i] == 2) {
+      if (!(c->kind == KIND_V || c->moves) || T->strip < 2 || T->strip % 2) return -1;
+      c->packed = 1;
+    }
+  }
   int d = 0;
   c->maxs = 0;
   for (int a = 0; a < 4; a++) {
@@ -187,11 +201,11 @@ static int ctx_init(ctx* c, const orc_target* T, const orc_lattice* L) {
     }
   if (c->kind == KIND_V) {      /* Section 2.4.3: the abstract values are part of a tensor specification */
     c->abs_axis = d;
-    c->ext[d++] = 3; c->ext[d++] = 2; c->ext[d++] = 3; c->ext[d++] = 2;
+    c->ext[d++] = c->packed ? 4 : 3; c->ext[d++] = 2; c->ext[d++] = c->packed ? 4 : 3; c->ext[d++] = 2;
   }
   for (int i = 0; i < ORC_MAXOPS; i++) { c->lay_axis[i] = -1; c->dt_axis[i] = -1; }
   for (int i = 0; i < c->nops; i++)
-    if (L->layout_coord[i]) { c->lay_axis[i] = d; c->ext[d++] = 2; }
+    if (L->layout_coord[i]) { c->lay_axis[i] = d; c->ext[d++] = L->layout_coord[i] == 2 ? 4 : 2; }
   for (int i = 0; i < c->nops; i++)
     if (L->dtype_coord[i]) {
       if (!(c->kind == KIND_V || (c->kind == KIND_M && i != 2))) return -1;   /* inputs of a Matmul, tensors of a Move */
@@ -204,7 +218,7 @@ static int ctx_init(ctx* c, const orc_target* T, const orc_lattice* L) {
   c->n = s;
   c->nmk = T->n_microkernels;
   c->move_base = c->nmk;
-  c->tile_base = c->move_base + (uint32_t)c->nops * (T->n_levels - 1) * 4;
+  c->tile_base = c->move_base + (uint32_t)c->nops * (T->n_levels - 1) * (c->packed ? 8 : 4);
   c->buf_id = c->tile_base + 4 * c->maxs;
   c->par_base = c->buf_id + 1;
   if ((c->parallel ? c->par_base + 4 * c->maxs : c->buf_id + T->n_levels) >= ORC_NONE) return -1;
@@ -276,11 +290,69 @@ static int access_of(const ctx* c, int op) {
   return op == c->nops - 1 ? ACC_WRITE : ACC_READ;
 }
 
+/* ------------------------------------------------------------------ */
+/* Layouts (Section 2.4.2): a layout maps the coordinates (i, j) of a rows x cols tensor to a
+ * buffer offset, a bijection onto 0 .. rows*cols-1.  Row-major and column-major nest the two
+ * logical dimensions; the packed layout adds a strip dimension of s columns: strips one after
+ * the other, inside a strip the rows, inside a row of a strip its s columns; the shuffled one
+ * permutes the columns of a strip by the odd-even shuffle sigma(s, x) = 2 (x mod s/2) + floor(2x / s).
+ * (The printed strip formula multiplies floor(j / s) by the row count alone; a strip holds
+ * rows * s values, so that term is rows * s * floor(j / s) here: only then is the map a bijection.) */
+uint64_t orc_layout_offset(uint32_t layout, uint64_t rows, uint64_t cols, uint64_t s, uint64_t i, uint64_t j) {
+  switch (layout) {
+    case 0: return cols * i + j;
+    case 1: return rows * j + i;
+    case 2: return rows * s * (j / s) + s * i + j % s;
+    default: { uint64_t x = j % s; return rows * s * (j / s) + s * i + 2 * (x % (s / 2)) + 2 * x / s; }
+  }
+}
+
+/* Physical dimensions of a rows x cols tensor, outermost first; returns how many there are.  A
+ * packed tensor consists of whole strips, or (a tile cut out of one strip) of the same part of
+ * every row of one strip. */
+static int phys_dims(uint32_t layout, uint64_t rows, uint64_t cols, uint64_t s, uint64_t d[3]) {
+  if (layout == 0) { d[0] = rows; d[1] = cols; return 2; }
+  if (layout == 1) { d[0] = cols; d[1] = rows; return 2; }
+  if (cols >= s) { d[0] = cols / s; d[1] = rows; d[2] = s; }
+  else { d[0] = 1; d[1] = rows; d[2] = cols; }
+  return 3;
+}
+
+static int layout_fits(const ctx* c, uint32_t layout, uint64_t cols) {
+  uint64_t s = c->T->strip;
+  return layout < 2 || cols % s == 0 || (cols < s && s % cols == 0);
+}
+
+/* The most inner physical dimensions whose values can be adjacent.  The rows of a part of a strip
+ * lie a whole strip apart, and in a shuffled strip the columns of such a part are not adjacent
+ * either. */
+static int max_contig(uint32_t layout, uint64_t cols, uint64_t s) {
+  if (layout < 2) return 2;
+  if (cols >= s) return 3;
+  if (layout == 2) return 1;
+  return cols == 1 ? 1 : 0;
+}
+
+/* rows and columns of operand i of a kind 8 Matmul: lhs m x k, rhs k x n, out m x n */
+static void operand_rows_cols(const uint64_t d4[4], int i, uint64_t* rows, uint64_t* cols) {
+  *rows = i == 1 ? d4[2] : d4[1];
+  *cols = i == 0 ? d4[2] : d4[3];
+}
+
 /* A Spec is admissible when the tensors resident in each level fit that level
  * (the per-level memory bound of Section 2.2, applied to the Spec's own
  * operands; kind F also counts its intermediate). */
 static int admissible(const ctx* c, const spec_t* s) {
   if (c->bounded) return 1;     /* the bounds, not the operands' footprint, limit what a Spec may do */
+  if (c->packed) {              /* no such tensor: a packed layout with a broken strip, more adjacent dimensions than there are */
+    uint64_t d4[4], rows, cols; dims_of(c, s, d4);
+    for (int i = 0; i < c->nops; i++) {
+      if (c->kind == KIND_V) { rows = d4[1]; cols = d4[3]; } else operand_rows_cols(d4, i, &rows, &cols);
+      if (!layout_fits(c, s->layout[i], cols)) return 0;
+      if (c->kind == KIND_V && s->contig[i] > max_contig(s->layout[i], cols, c->T->strip)) return 0;
+      if (c->kind != KIND_V && s->layout[i] >= 2 && cols % c->T->strip) return 0;    /* a whole (fresh) tensor: whole strips */
+    }
+  }
   if (c->kind == KIND_V) return 1;   /* both tensors of a Move exist already: whoever placed them answered for their size */
   for (uint32_t l = 0; l < c->T->n_levels; l++) {
     unsigned __int128 bytes = 0;
@@ -320,7 +392,9 @@ static uint64_t mk_reps(const ctx* c, const spec_t* s, int j) {
       if (b != 1 || m != 1 || k != 1 || n % lanes != 0) return 0;
       if (lv[0] != 0 || lv[1] != 1 || lv[2] != 1) return 0;
       if (bf[0] || bf[1] || bf[2]) return 0;
-      if (ly[1] != 0 || ly[2] != 0) return 0;           /* rhs, out row-major */
+      /* rhs, out row-major; one row in whole packed strips is the same sequence of values */
+      for (int i = 1; i <= 2; i++)
+        if (!(ly[i] == 0 || (ly[i] == 2 && c->T->strip % lanes == 0))) return 0;
       return n / lanes;
     case MK_BF16_DOT:
       if (c->kind != KIND_M) return 0;
@@ -375,7 +449,11 @@ static uint64_t mk_reps(const ctx* c, const spec_t* s, int j) {
       if (c->kind != KIND_V) return 0;
       if (m != 1 || n % lanes != 0) return 0;
       if (!((lv[0] == 1 && lv[1] > 1) || (lv[1] == 1 && lv[0] > 1))) return 0;
-      if (ly[0] != 0 || ly[1] != 0) return 0;               /* the row's values are the inner dimension */
+      /* the row's values are the inner dimension: row-major, or strips of whole vectors; shuffled
+       * strips only to shuffled strips (the vectors then hold the same values on both sides) */
+      for (int t = 0; t < 2; t++)
+        if (!(ly[t] == 0 || (ly[t] >= 2 && (n < c->T->strip || c->T->strip % lanes == 0)))) return 0;
+      if ((ly[0] == 3) != (ly[1] == 3)) return 0;
       if (bf[0] != bf[1]) return 0;                         /* no conversion */
       if (s->contig[0] < 1 || s->contig[1] < 1) return 0;   /* ... and adjacent in memory */
       if (c->T->mk_kind[j] == MK_VECTOR_MOVE_ALIGNED && !(s->aligned[0] && s->aligned[1])) return 0;
@@ -391,10 +469,20 @@ static uint64_t mk_reps(const ctx* c, const spec_t* s, int j) {
  * dimensions is a whole number of cache lines. */
 static void tile_tensor(const ctx* c, const spec_t* s, int t, uint64_t r, uint64_t col, uint64_t r2, uint64_t c2,
                         uint8_t* contig, uint8_t* aligned) {
-  uint64_t inner = s->layout[t] ? r : col, inner2 = s->layout[t] ? r2 : c2, outer2 = s->layout[t] ? c2 : r2;
-  uint64_t e = s->bf16[t] ? 2 : 4, line = c->T->line_bytes;
-  *contig = inner2 == inner ? s->contig[t] : (s->contig[t] < 1 ? s->contig[t] : 1);
-  *aligned = s->aligned[t] && s->contig[t] == 2 && (inner2 * e) % line == 0 && (outer2 * inner2 * e) % line == 0;
+  uint64_t e = s->bf16[t] ? 2 : 4, line = c->T->line_bytes, strip = c->T->strip ? c->T->strip : 1;
+  uint64_t whole[3], part[3];
+  int nd = phys_dims(s->layout[t], r, col, strip, whole);
+  phys_dims(s->layout[t], r2, c2, strip, part);
+  /* the tile's values over its inner j dimensions are adjacent while the j-1 innermost are uncut */
+  int uncut = 0;
+  while (uncut < nd && part[nd - 1 - uncut] == whole[nd - 1 - uncut]) uncut++;
+  int keep = 1 + uncut, most = max_contig(s->layout[t], c2, strip);
+  if (keep > most) keep = most;
+  *contig = (uint8_t)(s->contig[t] < keep ? s->contig[t] : keep);
+  int lines_ok = s->layout[t] < 2 || c2 >= strip;        /* a part of a strip is not known to be aligned */
+  uint64_t suffix = e;
+  for (int q = nd - 1; q >= 0; q--) { suffix *= part[q]; if (suffix % line) lines_ok = 0; }
+  *aligned = s->aligned[t] && s->contig[t] == nd && lines_ok;
 }
 
 /* Section 3: m(t) = lines(t) * weight of t's level * (2 if t is not contiguous, else 1), for a
@@ -432,36 +520,43 @@ static void expand(ctx* c, const spec_t* s, uint64_t* best_out, uint16_t* arg_ou
     int acc = access_of(c, i);
     uint32_t src = s->level[i];
     for (uint32_t dst = 0; dst + 1 < NL; dst++)
-      for (int x = 0; x < 2; x++)
+      for (int x = 0; x < (c->packed ? 4 : 2); x++)        /* the Move leaves the operand in layout (its own) xor x */
         for (int cv = 0; cv < 2; cv++) {
           if (dst >= src) continue;
           if (x && c->lay_axis[i] < 0) continue;
+          if (x >= 2 && c->L->layout_coord[i] != 2) continue;
           if (cv && !(c->dt_axis[i] >= 0 && s->bf16[i] && acc == ACC_READ)) continue;
           spec_t sub = *s;
           sub.level[i] = (uint8_t)dst;
           sub.layout[i] ^= (uint8_t)x;
           if (cv) sub.bf16[i] = 0;
-          uint32_t id = c->move_base + (((uint32_t)i * (NL - 1) + dst) * 2 + (uint32_t)x) * 2 + (uint32_t)cv;
+          uint32_t id = c->move_base + (((uint32_t)i * (NL - 1) + dst) * (c->packed ? 4 : 2) + (uint32_t)x) * 2 + (uint32_t)cv;
           if (c->moves) {
             /* Section 2, Memory Movement: the alloc-binding holds a load Move Spec (unless the
              * operand is only written), the body, and a store Move Spec (if it is written);
              * Section 3: it costs m(src) + m(dest) plus its children. */
             uint64_t d4[4]; dims_of(c, s, d4);
-            uint64_t rows = i == 1 ? d4[2] : d4[1], cols = i == 0 ? d4[2] : d4[3];   /* lhs m x k, rhs k x n, out m x n */
+            uint64_t rows, cols, pd[3];
+            operand_rows_cols(d4, i, &rows, &cols);
             spec_t mv; memset(&mv, 0, sizeof mv);
             mv.si[1] = i == 1 ? s->si[2] : s->si[1];
             mv.si[3] = i == 0 ? s->si[2] : s->si[3];
-            mv.contig[0] = mv.contig[1] = 2; mv.aligned[0] = mv.aligned[1] = 1;
+            /* both tensors fresh: every physical dimension adjacent, aligned (Section 2.4.3) */
+            uint8_t top_own = (uint8_t)phys_dims(s->layout[i], rows, cols, T->strip ? T->strip : 1, pd);
+            uint8_t top_new = (uint8_t)phys_dims(sub.layout[i], rows, cols, T->strip ? T->strip : 1, pd);
+            mv.aligned[0] = mv.aligned[1] = 1;
             uint64_t c_load = 0, c_store = 0;
             if (acc != ACC_WRITE) {
               mv.level[0] = (uint8_t)src; mv.level[1] = (uint8_t)dst;
               mv.layout[0] = s->layout[i]; mv.layout[1] = sub.layout[i];
+              mv.contig[0] = top_own; mv.contig[1] = top_new;
               mv.bf16[0] = s->bf16[i]; mv.bf16[1] = sub.bf16[i];
               c_load = c->depM->cost[spec_index(c->depM, &mv)];
             }
             if (acc != ACC_READ) {
               mv.level[0] = (uint8_t)dst; mv.level[1] = (uint8_t)src;
               mv.layout[0] = sub.layout[i]; mv.layout[1] = s->layout[i];
+              mv.contig[0] = top_new; mv.contig[1] = top_own;
               mv.bf16[0] = sub.bf16[i]; mv.bf16[1] = s->bf16[i];
               c_store = c->depM->cost[spec_index(c->depM, &mv)];
             }
@@ -706,6 +801,7 @@ int orc_solve(const orc_target* T, const orc_lattice* L,
     int any_lay = 0, any_dt = 0;
     for (int i = 0; i < 3; i++) { any_lay |= c.lay_axis[i] >= 0; any_dt |= c.dt_axis[i] >= 0 || L->base_dtype_bytes[i] == 2; }
     if (any_lay && (cm.lay_axis[0] < 0 || cm.lay_axis[1] < 0)) return -1;
+    if (c.packed && (LM->layout_coord[0] != 2 || LM->layout_coord[1] != 2)) return -1;
     if (any_dt && (cm.dt_axis[0] < 0 || cm.dt_axis[1] < 0)) return -1;
     if (cm.dt_axis[0] < 0 && (LM->base_dtype_bytes[0] != 4 || LM->base_dtype_bytes[1] != 4)) return -1;
     cm.cost = (uint64_t*)costM;

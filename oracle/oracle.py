@@ -40,7 +40,8 @@ class _Target(C.Structure):
                 ("threads", C.c_uint32),
                 ("sync_cost", C.c_uint32),
                 ("level_weight", C.c_uint32 * 4),
-                ("line_bytes", C.c_uint32)]
+                ("line_bytes", C.c_uint32),
+                ("strip", C.c_uint32)]
 
 
 class _Lattice(C.Structure):
@@ -96,6 +97,7 @@ def _target(t):
     for l in range(4):
         s.level_weight[l] = t.get("level_weight", [0, 0, 0, 0])[l]
     s.line_bytes = t.get("line_bytes", 0)
+    s.strip = t.get("strip", 0)
     return s
 
 
@@ -118,6 +120,15 @@ def _lattice(lat):
 
 def _p(a, t):
     return a.ctypes.data_as(C.POINTER(t))
+
+
+def layout_offset(layout, rows, cols, strip, i, j):
+    """Buffer offset of element (i, j) of a rows x cols tensor (Section 2.4.2): layout 0 row-major,
+    1 column-major, 2 packed in strips of `strip` columns, 3 packed with odd-even shuffled strips."""
+    f = lib().orc_layout_offset
+    f.restype = C.c_uint64
+    f.argtypes = [C.c_uint32] + [C.c_uint64] * 5
+    return int(f(layout, rows, cols, strip, i, j))
 
 
 def geometry(target, lattice):

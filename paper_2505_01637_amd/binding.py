@@ -47,7 +47,8 @@ class _TargetDesc(C.Structure):
                 ("threads", C.c_uint32),
                 ("sync_cost", C.c_uint32),
                 ("level_weight", C.c_uint32 * 4),
-                ("line_bytes", C.c_uint32)]
+                ("line_bytes", C.c_uint32),
+                ("strip", C.c_uint32)]
 
 
 class _LatticeDesc(C.Structure):
@@ -136,6 +137,7 @@ def _target_desc(t):
     for l in range(4):
         d.level_weight[l] = t.get("level_weight", [0, 0, 0, 0])[l]
     d.line_bytes = t.get("line_bytes", 0)
+    d.strip = t.get("strip", 0)
     return d
 
 

@@ -80,6 +80,7 @@ def _empty_target(n_levels, capacities):
         "sync_cost": 0,       # constant of a parallel loop
         "level_weight": [0] * MAX_LEVELS,   # per-level weight of a Move's cache lines (KIND_MATMUL_MOVES)
         "line_bytes": 64,     # cache line
+        "strip": 0,           # columns per strip of the packed layouts (0: there are none)
     }
 
 
@@ -88,7 +89,7 @@ def _lattice(kind, sizes, layout=(0, 0, 0, 0, 0), dtype=(0, 0, 0, 0, 0),
     return {
         "kind": kind,
         "sizes": [list(s) for s in sizes],          # b, m, k, n: ascending, contain 1
-        "layout_coord": list(layout),
+        "layout_coord": list(layout),               # per operand: 0 no coordinate, 1 row-/column-major, 2 also the two packed layouts
         "dtype_coord": list(dtype),
         "base_dtype_bytes": list(base_bytes),
     }
@@ -260,8 +261,23 @@ def config(number, seed=None, max_size=None):
             ("S", _lattice(KIND_BIAS_ADD_RELU_SPLIT, [one, r, one, r], layout=(1, 0, 1, 0, 0)), ["A", "R"]),
             ("F", _lattice(KIND_FUSED_MM_ADD_RELU, [one, r, r, r], layout=(1, 1, 0, 1, 0)), ["M", "S"]),
         ]
+    elif number == 12:
+        # beyond the five benchmark configurations: packed and shuffled layouts.  Config 9's recipe;
+        # strips of 8 columns (the vector width); the Move lattice with all four layouts on both
+        # tensors over sizes 1..32 (16.8 M Specs), and the Matmul lattice over the same sizes whose
+        # rhs and out may be packed (lhs row- or column-major) and whose Moves are read from it
+        t, w = _four_level_target(rng)
+        t["level_weight"] = list(w)
+        t["line_bytes"] = 64
+        t["strip"] = 8
+        t["microkernels"].append((MK_SCALAR_MOVE, 1, rng.draw(1, 3)))
+        t["microkernels"].append((MK_VECTOR_MOVE, 8, rng.draw(2, 3)))
+        t["microkernels"].append((MK_VECTOR_MOVE_ALIGNED, 8, 1))
+        r = keep(range(1, 33))
+        lats = [("V", _lattice(KIND_MOVE, [one, r, one, r], layout=(2, 2, 0, 0, 0)), []),
+                ("M", _lattice(KIND_MATMUL_MOVES, [one, r, r, r], layout=(1, 2, 2, 0, 0)), ["V"])]
     else:
-        raise ValueError("config number must be 1..11")
+        raise ValueError("config number must be 1..12")
     return {"name": "config%d" % number, "target": t, "lattices": lats}
 
 
@@ -281,11 +297,13 @@ def coord_extents(target, lattice):
     if kind in BOUNDED_KINDS:
         # one axis per level of finite capacity: the bounds 0, 1, 2, 4, ... up to the capacity
         ext += [int(c).bit_length() + 1 for c in target["capacity_bytes"][:target["n_levels"]] if c != UNBOUNDED]
-    if kind == KIND_MOVE:
-        # per tensor (source, destination): contiguousness 0..2 and the aligned flag
-        ext += [3, 2, 3, 2]
     nops = n_operands(kind)
-    ext += [2] * sum(1 for i in range(nops) if lattice["layout_coord"][i])
+    if kind == KIND_MOVE:
+        # per tensor (source, destination): contiguousness 0..2 (0..3 where packed tensors, which
+        # have three physical dimensions, exist) and the aligned flag
+        nc = 4 if 2 in lattice["layout_coord"][:nops] else 3
+        ext += [nc, 2, nc, 2]
+    ext += [4 if lattice["layout_coord"][i] == 2 else 2 for i in range(nops) if lattice["layout_coord"][i]]
     ext += [2] * sum(1 for i in range(nops) if lattice["dtype_coord"][i])
     return ext
 

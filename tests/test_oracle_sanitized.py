@@ -43,7 +43,7 @@ def matmul_with_move_specs():
                                           base_bytes=(2, 4, 4, 4, 4)), ["V"])]}
 
 
-@pytest.mark.parametrize("number,max_size", [(1, 6), (3, 16), (4, 2), (5, 4), (6, 4), (7, 1), (8, None), (9, None), (10, 2), (11, 2)])
+@pytest.mark.parametrize("number,max_size", [(1, 6), (3, 16), (4, 2), (5, 4), (6, 4), (7, 1), (8, None), (9, None), (10, 2), (11, 2), (12, 4)])
 def test_sanitized_oracle_agrees_with_the_ordinary_build(exe, tmp_path, number, max_size):
     cfg = bounded_pipeline() if number == 8 else matmul_with_move_specs() if number == 9 else W.config(number, max_size=max_size)
     got = O.run_sanitized(exe, cfg, str(tmp_path))

@@ -94,6 +94,9 @@ typedef struct {
                                                                  of an alloc-binding (MATMUL_MOVES)            */
   uint32_t line_bytes;                                        /* cache line: unit of lines(t) in m(t) and of
                                                                  alignment; >= 1 for MOVE and MATMUL_MOVES     */
+  uint32_t strip;                                             /* Section 2.4.2: columns per strip of the packed
+                                                                 layouts; even and >= 2 where a lattice has
+                                                                 layout_coord 2, else ignored                  */
 } mrl_target_desc;
 
 typedef struct mrl_target mrl_target;
@@ -108,7 +111,9 @@ void mrl_target_destroy(mrl_target* t);
  *   index of b, m, k, n in the allowed-size lists;
  *   memory level of each operand (FUSED, MATMUL_CHAIN: then the intermediate's level);
  *   (the BOUNDED kinds: one memory-bound index per level of finite capacity;)
- *   one layout bit (0 row-major, 1 column-major) per operand with layout_coord;
+ *   one layout coordinate per operand with layout_coord: 0 row-major, 1
+ *   column-major, and where layout_coord is 2 (MOVE, MATMUL_MOVES) also 2
+ *   packed in strips and 3 packed with shuffled strips (see PACKED LAYOUTS);
  *   one dtype bit (0 f32, 1 bf16) per operand with dtype_coord.
  * Dense tables are in C order of x (last coordinate fastest).
  *
@@ -189,6 +194,33 @@ void mrl_target_destroy(mrl_target* t);
  * both equal this lattice's p, k and n lists (which must be equal); where an
  * operand here has a layout coordinate, the position it takes in the dep
  * (lhs, rhs1 -> lhs, rhs; rhs2, out -> rhs, out) must have one too.
+ * PACKED LAYOUTS (Section 2.4.2; MOVE and MATMUL_MOVES lattices, layout_coord
+ * 2 on a tensor).  Element (i, j) of a rows x cols tensor lies at offset
+ * cols*i + j (0, row-major), rows*j + i (1, column-major), rows*s*floor(j/s) +
+ * s*i + (j mod s) (2, packed in strips of s = target.strip columns) or the same
+ * with sigma(s, j mod s) = 2*((j mod s) mod s/2) + floor(2*(j mod s)/s) in place
+ * of (j mod s) (3, strips odd-even shuffled).  A packed tensor has three
+ * physical dimensions (strips, rows, columns of a strip), so in a MOVE lattice
+ * with a packed tensor the contiguousness axes have 4 values (0..3).  A packed
+ * tensor consists of whole strips (cols a multiple of s); a tile of it may also
+ * be the same part of every row of one strip (cols a divisor of s), of which at
+ * most the part itself is adjacent (contiguousness <= 1; 0 in a shuffled strip
+ * unless the part is one column) and which is never known to be aligned.  A
+ * Spec with a tensor that does not exist in this sense has no implementation
+ * and does not count as admissible.  A tile keeps min(contiguousness, 1 + the
+ * number of innermost physical dimensions it takes whole, the limit above); it
+ * is aligned if the tensor was aligned and contiguous in all its dimensions,
+ * every suffix product of the tile's physical dimensions times the element size
+ * is a multiple of line_bytes, and it is no part of a strip.  Vector moves take
+ * rows of row-major tensors and of packed ones (whole strips: s a multiple of
+ * the lanes), shuffled strips only when both tensors are shuffled;
+ * MRL_MK_BCAST_VEC_MULADD takes rhs and out row-major or packed (not
+ * shuffled) in strips that are a multiple of its lanes.  In a MATMUL_MOVES
+ * lattice an operand with layout_coord 2 may be moved into any of the four
+ * layouts (operands are whole tensors: a packed one needs cols a multiple of
+ * s), its MOVE dep then needs layout_coord 2 on both tensors, and Move ids
+ * are ((operand*(n_levels-1) + dst)*4 + (old layout xor new layout))*2 +
+ * convert for every operand of the lattice.
  * BIAS_ADD, RELU, BIAS_ADD_RELU_SPLIT (Section 2.1: compositions are lowered
  * to their primitives by bufferize rewrites; here the second split of the
  * Matmul -> bias add -> ReLU pipeline, between the add and the ReLU).
@@ -218,7 +250,9 @@ typedef struct {
   uint32_t kind;
   uint32_t n_sizes[4];                        /* 1..MRL_MAX_SIZES each                        */
   const uint32_t* sizes[4];                   /* host; ascending, sizes[d][0] == 1 (but see FUSED) */
-  uint8_t layout_coord[MRL_MAX_OPERANDS];     /* layout and dtype bits together: at most 4    */
+  uint8_t layout_coord[MRL_MAX_OPERANDS];     /* 0 none, 1 row-/column-major, 2 also the packed layouts
+                                                 (2 bits); layout and dtype bits together: at most 4
+                                                 (6 for the MOVE, MATMUL_MOVES and BOUNDED kinds)   */
   uint8_t dtype_coord[MRL_MAX_OPERANDS];      /* inputs of a Matmul, both tensors of a MOVE   */
   uint8_t base_dtype_bytes[MRL_MAX_OPERANDS]; /* 4 or 2; used when the operand has no dtype bit */
 } mrl_lattice_desc;
@@ -330,9 +364,12 @@ int32_t mrl_query_noalloc(const mrl_table* tab, const mrl_coord* specs, size_t n
 
 /* Rewrite ids, ascending = tie-break priority:
  *   [0, n_mk)                       select(microkernel j)
- *   then ((operand*(n_levels-1) + dst)*2 + transposed)*2 + convert   Moves
+ *   then ((operand*(n_levels-1) + dst)*2 + transposed)*2 + convert   Moves (with packed layouts: *4 + the
+ *                                                                    layout change, see PACKED LAYOUTS;
+ *                                                                    mrl_rewrite.transposed holds it)
  *   then dim*max_sizes + index of the tile size                      tiles
- *   then one id                                                      bufferize
+ *   then one id                                                      bufferize (BIAS_ADD_RELU_SPLIT: one per
+ *                                                                    level; mrl_rewrite.dst_level holds it)
  *   then dim*max_sizes + index of the tile size                      parallel loops
  *                                                                    (MATMUL_PARALLEL) */
 typedef struct { uint8_t cls; /* 0 microkernel, 1 move, 2 tile, 3 bufferize, 4 parallel loop */

@@ -209,10 +209,21 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
       P.lim_nq[P.nlim++] = nq;
     }
   }
+  bool packed = false;       // some tensor may be packed in strips
+  for (uint32_t i = 0; i < 5; i++) {
+    if (L->layout_coord[i] > 2) return fail(MRL_E_INVAL, "layout_coord[%u] must be 0, 1 or 2", i);
+    if (L->layout_coord[i] == 2) {
+      if (!(move_specs || moves)) return fail(MRL_E_INVAL, "packed layouts (layout_coord 2) only in MOVE and MATMUL_MOVES lattices");
+      if (T.strip < 2 || T.strip % 2) return fail(MRL_E_INVAL, "packed layouts need an even strip >= 2");
+      packed = true;
+    }
+  }
+  P.strip = T.strip;
+  P.xw = packed ? 4u : 2u;
   if (move_specs) {
-    // contiguousness and aligned flag of the source, then of the destination
+    // contiguousness (a packed tensor has three physical dimensions) and aligned flag of the source, then of the destination
     P.nlim = 4;
-    P.lim_nq[0] = 3; P.lim_nq[1] = 2; P.lim_nq[2] = 3; P.lim_nq[3] = 2;
+    P.lim_nq[0] = packed ? 4 : 3; P.lim_nq[1] = 2; P.lim_nq[2] = packed ? 4 : 3; P.lim_nq[3] = 2;
   }
   for (uint32_t a = P.nlim; a-- > 0;) { P.lim_stride[a] = P.Q; P.Q *= P.lim_nq[a]; }
   P.gather = bounded || move_specs || moves ? 1u : 0u;
@@ -254,7 +265,8 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
   // variant bits: layout bits (operand order) above dtype bits (operand order)
   for (int i = 0; i < 5; i++) { P.lay_bit[i] = P.dt_bit[i] = kNoBit; c.lay_axis[i] = c.dt_axis[i] = -1; }
   for (uint32_t i = 0; i < P.nops; i++) {
-    P.nlay += L->layout_coord[i] ? 1 : 0;
+    P.nlay += L->layout_coord[i];          // bits of the layout field
+    P.lay_w[i] = L->layout_coord[i];
     P.ndt += L->dtype_coord[i] ? 1 : 0;
     if (L->dtype_coord[i] && !(kind == kKindV || (kind == kKindM && i < 2))) return fail(MRL_E_INVAL, "dtype bit only on MatmulAccum inputs and on the tensors of a MOVE");
     if (L->base_dtype_bytes[i] != 4 && !(L->base_dtype_bytes[i] == 2 && (kind == kKindM || kind == kKindV)))
@@ -268,11 +280,11 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
   P.V = 1u << (P.nlay + P.ndt);
   P.log2V = P.nlay + P.ndt;
 
-  if (P.V > 16) return fail(MRL_E_INVAL, "too many layout/dtype bits");
+  if (P.V > (P.gather ? 64u : 16u)) return fail(MRL_E_INVAL, "too many layout/dtype bits");
   {
     uint32_t axis = 4 + P.nlv + P.nlim, seen_l = 0, seen_d = 0;
     for (uint32_t i = 0; i < P.nops; i++)
-      if (L->layout_coord[i]) { c.lay_axis[i] = (int)axis++; P.lay_bit[i] = P.ndt + P.nlay - 1 - seen_l++; }
+      if (L->layout_coord[i]) { seen_l += L->layout_coord[i]; c.lay_axis[i] = (int)axis++; P.lay_bit[i] = P.ndt + P.nlay - seen_l; }
     for (uint32_t i = 0; i < P.nops; i++)
       if (L->dtype_coord[i]) { c.dt_axis[i] = (int)axis++; P.dt_bit[i] = P.ndt - 1 - seen_d++; }
   }
@@ -294,7 +306,7 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
   // rewrite ids
   P.maxs = maxs;
   P.move_base = P.nmk;
-  P.tile_base = P.move_base + P.nops * (P.NL - 1) * 4;
+  P.tile_base = P.move_base + P.nops * (P.NL - 1) * 2 * P.xw;
   P.buf_id = P.tile_base + 4 * maxs;
   P.par_base = P.buf_id + 1;
   if ((parallel ? P.par_base + 4 * maxs : P.buf_id + P.NL) >= kNone) return fail(MRL_E_INVAL, "rewrite ids do not fit 16 bits");
@@ -323,7 +335,7 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
       for (uint32_t i = 0; i < 4; i++) {
         lv[i] = i < P.nops ? (pack >> P.pack_shift[i]) & 3u : 0u;
         in_range = in_range && lv[i] < P.NL;
-        ly[i] = i < P.nops && P.lay_bit[i] != kNoBit ? (v >> P.lay_bit[i]) & 1u : 0u;
+        ly[i] = i < P.nops && P.lay_bit[i] != kNoBit ? (v >> P.lay_bit[i]) & ((1u << P.lay_w[i]) - 1u) : 0u;
         bf[i] = i < P.nops ? (P.dt_bit[i] != kNoBit ? (v >> P.dt_bit[i]) & 1u : P.base_bf16[i]) : 0u;
       }
       if (!in_range || (P.nops < 4 && (pack >> (2 * P.nops)))) continue;
@@ -333,7 +345,12 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
         const bool all_f32 = !(bf[0] | bf[1] | bf[2]);
         switch (T.mk[j].kind) {
           case MRL_MK_SCALAR_FMA: ok = P.kind == kKindM && !(lv[0] | lv[1] | lv[2]) && all_f32; break;
-          case MRL_MK_BCAST_VEC_MULADD: ok = P.kind == kKindM && lv[0] == 0 && lv[1] == 1 && lv[2] == 1 && all_f32 && !ly[1] && !ly[2]; break;
+          case MRL_MK_BCAST_VEC_MULADD: {
+            // rhs, out row-major; one row in whole packed strips is the same sequence of values
+            auto rowlike = [&](uint32_t y) { return y == 0 || (y == 2 && T.strip % T.mk[j].lanes == 0); };
+            ok = P.kind == kKindM && lv[0] == 0 && lv[1] == 1 && lv[2] == 1 && all_f32 && rowlike(ly[1]) && rowlike(ly[2]);
+            break;
+          }
           case MRL_MK_BF16_DOT: ok = P.kind == kKindM && lv[0] == 1 && lv[1] == 1 && lv[2] == 0 && bf[0] && bf[1] && !bf[2] && (P.lay_bit[1] == kNoBit || ly[1] == 1); break;
           case MRL_MK_SCALAR_ADDRELU: ok = P.kind == kKindE && !add_only && !(lv[0] | lv[1] | lv[2]); break;
           case MRL_MK_VEC_ADDRELU: ok = P.kind == kKindE && !add_only && lv[0] == 1 && lv[1] == 1 && lv[2] == 1 && !ly[0] && !ly[2]; break;
@@ -345,7 +362,9 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
           case MRL_MK_SCALAR_MOVE: ok = P.kind == kKindV && !(!bf[0] && bf[1]); break;
           case MRL_MK_VECTOR_MOVE:
           case MRL_MK_VECTOR_MOVE_ALIGNED:
-            ok = P.kind == kKindV && ((lv[0] == 1 && lv[1] > 1) || (lv[1] == 1 && lv[0] > 1)) && !ly[0] && !ly[1] && bf[0] == bf[1];
+            // (rows of strips: whether the strips are whole vectors is tested in the kernel, with the shape)
+            ok = P.kind == kKindV && ((lv[0] == 1 && lv[1] > 1) || (lv[1] == 1 && lv[0] > 1)) && ly[0] != 1 && ly[1] != 1 &&
+                 (ly[0] == 3) == (ly[1] == 3) && bf[0] == bf[1];
             break;
         }
         bits |= (uint8_t)((ok ? 1u : 0u) << j);
@@ -430,7 +449,8 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
   for (int d = 0; d < 4; d++) g.ext[nd++] = P.nsz[d];
   for (uint32_t i = 0; i < P.nlv; i++) g.ext[nd++] = P.NL;
   for (uint32_t a = 0; a < P.nlim; a++) g.ext[nd++] = P.lim_nq[a];
-  for (uint32_t i = 0; i < P.nlay + P.ndt; i++) g.ext[nd++] = 2;
+  for (uint32_t i = 0; i < P.nops; i++) if (L->layout_coord[i]) g.ext[nd++] = 1u << L->layout_coord[i];
+  for (uint32_t i = 0; i < P.ndt; i++) g.ext[nd++] = 2;
   if (nd > 16) return fail(MRL_E_INVAL, "more than 16 coordinate axes");
   g.ndim = nd;
   uint64_t s = 1;
@@ -442,8 +462,10 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
     for (int a = lay0 - 1; a >= lim0; a--) c.merge_order[q++] = (uint32_t)a;             // memory bounds
     for (int a = 3; a >= 0; a--) c.merge_order[q++] = (uint32_t)a;                       // n, k, m, b
     for (int a = lim0 - 1; a >= 4; a--) c.merge_order[q++] = (uint32_t)a;                // levels
-    for (int a = lay0 + (int)P.nlay - 1; a >= lay0; a--) c.merge_order[q++] = (uint32_t)a;
-    for (int a = (int)nd - 1; a >= lay0 + (int)P.nlay; a--) c.merge_order[q++] = (uint32_t)a;
+    int n_lay_axes = 0;
+    for (uint32_t i = 0; i < P.nops; i++) n_lay_axes += L->layout_coord[i] ? 1 : 0;
+    for (int a = lay0 + n_lay_axes - 1; a >= lay0; a--) c.merge_order[q++] = (uint32_t)a;
+    for (int a = (int)nd - 1; a >= lay0 + n_lay_axes; a--) c.merge_order[q++] = (uint32_t)a;
   }
 
   c.max_task = P.ncombo * P.V;
@@ -769,11 +791,13 @@ int32_t solve_impl(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_t
     bool any_lay = false, any_dt = false;
     for (int i = 0; i < 3; i++) { any_lay = any_lay || P.lay_bit[i] != kNoBit; any_dt = any_dt || P.dt_bit[i] != kNoBit || P.base_bf16[i]; }
     if (any_lay && (V.P.lay_bit[0] == kNoBit || V.P.lay_bit[1] == kNoBit)) return fail(MRL_E_INVAL, "the MOVE table needs layout bits on both tensors");
+    if (P.xw == 4 && (V.P.lay_w[0] != 2 || V.P.lay_w[1] != 2)) return fail(MRL_E_INVAL, "the MOVE table needs the packed layouts on both tensors");
     if (any_dt && (V.P.dt_bit[0] == kNoBit || V.P.dt_bit[1] == kNoBit)) return fail(MRL_E_INVAL, "the MOVE table needs dtype bits on both tensors");
     if (V.P.dt_bit[0] == kNoBit && (V.P.base_bf16[0] || V.P.base_bf16[1])) return fail(MRL_E_INVAL, "a MOVE table without dtype bits must be f32");
     P.costM = deps[0]->d_cost;
     tab->deps[0] = deps[0];
     P.GV = V.P.G; P.VV = V.P.V; P.nszV = V.P.nsz[3]; P.QV = V.P.Q; P.qV_top = V.P.Q - 1;
+    for (int a = 0; a < 4; a++) P.limV_stride[a] = V.P.lim_stride[a];
     for (int i = 0; i < 2; i++) { P.layV[i] = V.P.lay_bit[i]; P.dtV[i] = V.P.dt_bit[i]; }
   } else if (n_deps != 0) {
     return fail(MRL_E_INVAL, "only FUSED, MATMUL_PARALLEL, MATMUL_MOVES, MATMUL_CHAIN and BIAS_ADD_RELU_SPLIT lattices take deps");
@@ -1099,7 +1123,7 @@ int32_t solve_impl(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_t
     stats->n_specs = c.n_specs;
     stats->n_admissible = stats->n_rewrites = 0;
     for (uint32_t i = 0; i < kCtrSlots; i++) { stats->n_admissible += h_ctr.n_admissible[i]; stats->n_rewrites += h_ctr.n_rewrites[i]; }
-    if (P.bounded || P.kind == kKindV) stats->n_admissible = c.n_specs;      // no admissibility test: every Spec is evaluated
+    if (P.bounded) stats->n_admissible = c.n_specs;      // no admissibility test: every Spec is evaluated
     stats->n_levels_run = n_lev;
     HIP_TRY(hipEventElapsedTime(&stats->fill_ms, ev[0], ev[1]));
     HIP_TRY(hipEventElapsedTime(&stats->compress_ms, ev[3], ev[2]));
@@ -1362,7 +1386,8 @@ int32_t mrl_rewrite_decode(const mrl_table* tab, uint16_t id, mrl_rewrite* out) 
   if (id < P.move_base) { out->cls = 0; out->mk_index = id; return MRL_OK; }
   if (id < P.tile_base) {
     uint32_t r = id - P.move_base;
-    out->cls = 1; out->convert = r & 1; out->transposed = (r >> 1) & 1; r >>= 2;
+    out->cls = 1; out->convert = r & 1; r >>= 1;
+    out->transposed = (uint8_t)(r % P.xw); r /= P.xw;
     out->dst_level = (uint8_t)(r % (P.NL - 1)); out->operand_or_dim = (uint8_t)(r / (P.NL - 1));
     return MRL_OK;
   }
@@ -1399,7 +1424,7 @@ int32_t mrl_coord_of_spec(const mrl_table* tab, const uint32_t shape[4], const u
   }
   for (uint32_t a = 0; a < c.P.nlim; a++) out->x[4 + c.P.nlv + a] = c.P.lim_nq[a] - 1;   // the whole capacity
   for (uint32_t i = 0; i < c.P.nops; i++) {
-    if (c.lay_axis[i] >= 0) { if (!layouts || layouts[i] > 1) return fail(MRL_E_RANGE, "layout of operand %u", i); out->x[c.lay_axis[i]] = layouts[i]; }
+    if (c.lay_axis[i] >= 0) { if (!layouts || layouts[i] >= (1u << c.P.lay_w[i])) return fail(MRL_E_RANGE, "layout of operand %u", i); out->x[c.lay_axis[i]] = layouts[i]; }
     if (c.dt_axis[i] >= 0) { if (!dtypes || dtypes[i] > 1) return fail(MRL_E_RANGE, "dtype of operand %u", i); out->x[c.dt_axis[i]] = dtypes[i]; }
   }
   return MRL_OK;

@@ -43,6 +43,7 @@ struct DevParams {
   const TileEntry* tiles;    // device
   uint32_t tile_dim_ok[4];   // which dims this kind may tile
   uint32_t lay_bit[5];       // bit position inside the variant index, kNoBit = no coordinate
+  uint32_t lay_w[5];         // bits of the layout field: 1 (row-/column-major), 2 (also packed and shuffled strips)
   uint32_t dt_bit[5];
   uint32_t base_bf16[5];
   uint32_t access[5];
@@ -88,6 +89,10 @@ struct DevParams {
   uint32_t GV, VV, nszV;     // the Move table: entries per shape, variants, number of column sizes
   uint32_t QV, qV_top;       // its abstract vectors per level pair, and the index of (contiguous, aligned) twice
   uint32_t layV[2], dtV[2];  // bit positions of its layout and dtype bits, kNoBit if absent
+  uint32_t limV_stride[4];   // strides of its four abstract-value axes inside the abstract vector's index
+  // ---- packed layouts (Move lattices and the Matmul whose Moves are Move Specs) ----
+  uint32_t strip;            // columns per strip of layouts 2 (packed) and 3 (packed, strips shuffled)
+  uint32_t xw;               // layout changes a Move id names: 2, or 4 where some operand has a 2-bit layout field
   // ---- tables a FUSED lattice reads (costM also: the serial table a parallel lattice reads) ----
   const uint64_t* costM;
   const uint64_t* costE;

@@ -1042,6 +1042,29 @@ uint32_t fill_wave_cap(uint32_t G) { return G <= kSmallCap ? G : kSlicedCap; }
 // test.  And the Matmul whose Moves are Move Specs (Section 2, Memory Movement; Section 3): the
 // plain Matmul Specs with their admissibility test, where a Move costs m(src) + m(dest) in cache
 // lines plus the load and store Move Specs, read from the Move table.
+// Layouts (Section 2.4.2): 0 row-major, 1 column-major, 2 packed in strips of s columns, 3 packed
+// with shuffled strips.  Physical dimensions of a rows x cols tensor, outermost first: two, or for
+// the packed layouts strips, rows, columns of a strip; a tile cut out of one strip (cols < s) is
+// the same part of every row of that strip.
+__device__ __forceinline__ uint32_t phys_dims(uint32_t layout, uint64_t rows, uint64_t cols, uint64_t s, uint64_t d[3]) {
+  if (layout == 0) { d[0] = rows; d[1] = cols; d[2] = 1; return 2; }
+  if (layout == 1) { d[0] = cols; d[1] = rows; d[2] = 1; return 2; }
+  if (cols >= s) { d[0] = cols / s; d[1] = rows; d[2] = s; }
+  else { d[0] = 1; d[1] = rows; d[2] = cols; }
+  return 3;
+}
+__device__ __forceinline__ bool layout_fits(uint32_t layout, uint64_t cols, uint64_t s) {
+  return layout < 2 || cols % s == 0 || (cols < s && s % cols == 0);
+}
+// The most inner physical dimensions whose values can be adjacent: the rows of a part of a strip
+// lie a strip apart, and the columns of a part of a shuffled strip are no neighbours either.
+__device__ __forceinline__ uint32_t max_contig(uint32_t layout, uint64_t cols, uint64_t s) {
+  if (layout < 2) return 2;
+  if (cols >= s) return 3;
+  if (layout == 2) return 1;
+  return cols == 1 ? 1 : 0;
+}
+
 __device__ __forceinline__ uint64_t add_or_limit(uint64_t a, uint64_t b) {
   return (a >= kLimit || b >= kLimit || a + b >= kLimit) ? kLimit : a + b;
 }
@@ -1095,7 +1118,26 @@ __global__ __launch_bounds__(256) void fill_bounded_kernel(const DevParams* __re
     // Where Moves are Specs the lattice is the plain Matmul's: a Spec whose operands do not fit
     // their levels has no implementation and evaluates nothing.
     bool admissible = true;
+    const auto layout_of = [&](int i) { return P->lay_bit[i] != kNoBit ? (v >> P->lay_bit[i]) & ((1u << P->lay_w[i]) - 1u) : 0u; };
+    if (move_specs) {
+      // no such tensor: a packed layout with a broken strip, more adjacent dimensions than the tensor can have
+      if (P->xw == 4) {
+#pragma unroll
+        for (int ts = 0; ts < 2; ts++) {
+          const uint32_t y = layout_of(ts);
+          admissible = admissible && layout_fits(y, S.d[3], P->strip) && qi[2 * ts] <= max_contig(y, S.d[3], P->strip);
+        }
+      }
+      n_adm = admissible ? 1u : 0u;
+    }
     if (moves) {
+      if (P->xw == 4) {
+#pragma unroll
+        for (int i = 0; i < 3; i++) {
+          const uint64_t cols = i == 0 ? S.d[2] : S.d[3];
+          admissible = admissible && (layout_of(i) < 2 || cols % P->strip == 0);      // whole tensors: whole strips
+        }
+      }
 #pragma unroll
       for (int l = 0; l < 4; l++) {
         uint64_t bytes = 0;
@@ -1120,6 +1162,8 @@ __global__ __launch_bounds__(256) void fill_bounded_kernel(const DevParams* __re
         // vector moves: the inner dimension of both tensors adjacent in memory; the aligned form: both aligned
         if (qi[0] < 1u || qi[2] < 1u) continue;
         if (P->mk_kind[j] == 7u && !(qi[1] && qi[3])) continue;
+        // a row of whole strips: the strips must be whole vectors
+        if (P->xw == 4 && S.d[3] >= P->strip && P->strip % P->mk_lanes[j] != 0 && (layout_of(0) >= 2 || layout_of(1) >= 2)) continue;
       }
       const uint64_t k = mul_or_limit(P->mk_cost[j], reps);
       if (k >= kLimit) e.ovf = 1; else consider(e, k, j);
@@ -1135,9 +1179,10 @@ __global__ __launch_bounds__(256) void fill_bounded_kernel(const DevParams* __re
       const uint32_t bf = has_dt ? (v >> P->dt_bit[i]) & 1u : P->base_bf16[i];
       const uint64_t numel = S.numel[i];
       for (uint32_t dst = 0; dst < src; dst++)
-        for (uint32_t x = 0; x < 2; x++)
+        for (uint32_t x = 0; x < P->xw; x++)          // the Move leaves the operand in layout (its own) xor x
           for (uint32_t cv = 0; cv < 2; cv++) {
             if (x && !has_lay) continue;
+            if (x >= 2 && P->lay_w[i] != 2) continue;
             if (cv && !(P->can_convert[i] && has_dt && bf)) continue;
             const uint32_t child_bf = cv ? 0u : bf;
             if (moves) {
@@ -1145,25 +1190,29 @@ __global__ __launch_bounds__(256) void fill_bounded_kernel(const DevParams* __re
               // body, the store Move Spec (operands that are written); the operand is rows x cols
               const uint32_t ri = i == 1 ? S.si[2] : S.si[1], ci = i == 0 ? S.si[2] : S.si[3];
               const uint64_t groupV = (uint64_t)(ri * P->nszV + ci) * P->GV;
-              const uint32_t y0 = has_lay ? (v >> P->lay_bit[i]) & 1u : 0u, y1 = y0 ^ x;
+              const uint32_t y0 = layout_of(i), y1 = y0 ^ x;
+              // both tensors fresh: every physical dimension adjacent, aligned
+              const uint32_t top0 = y0 >= 2 ? 3u : 2u, top1 = y1 >= 2 ? 3u : 2u;
+              const uint32_t q_load = top0 * P->limV_stride[0] + P->limV_stride[1] + top1 * P->limV_stride[2] + P->limV_stride[3];
+              const uint32_t q_store = top1 * P->limV_stride[0] + P->limV_stride[1] + top0 * P->limV_stride[2] + P->limV_stride[3];
               auto variantV = [&](uint32_t ys, uint32_t yd, uint32_t fs, uint32_t fd) {
                 return (P->layV[0] != kNoBit ? ys << P->layV[0] : 0u) + (P->layV[1] != kNoBit ? yd << P->layV[1] : 0u) +
                        (P->dtV[0] != kNoBit ? fs << P->dtV[0] : 0u) + (P->dtV[1] != kNoBit ? fd << P->dtV[1] : 0u);
               };
               uint64_t c_load = 0, c_store = 0;
               if (P->access[i] != kWrite)
-                c_load = P->costM[groupV + ((src * P->NL + dst) * P->QV + P->qV_top) * P->VV + variantV(y0, y1, bf, child_bf)];
+                c_load = P->costM[groupV + ((src * P->NL + dst) * P->QV + q_load) * P->VV + variantV(y0, y1, bf, child_bf)];
               if (P->access[i] != kRead)
-                c_store = P->costM[groupV + ((dst * P->NL + src) * P->QV + P->qV_top) * P->VV + variantV(y1, y0, child_bf, bf)];
+                c_store = P->costM[groupV + ((dst * P->NL + src) * P->QV + q_store) * P->VV + variantV(y1, y0, child_bf, bf)];
               const uint32_t combo_c = combo - (src - dst) * P->lvpow[i];
-              uint32_t v_c = v ^ (x ? 1u << P->lay_bit[i] : 0u);
+              uint32_t v_c = v ^ (x ? x << P->lay_bit[i] : 0u);
               if (cv) v_c &= ~(1u << P->dt_bit[i]);
               const uint64_t sub = cost[group + (uint64_t)((combo_c * npass + pass) * Q + q) * V + v_c];
               const uint64_t line = P->line_bytes;
               const uint64_t lines_s = (numel * (bf ? 2u : 4u) + line - 1) / line, lines_d = (numel * (child_bf ? 2u : 4u) + line - 1) / line;
               const uint32_t ws = src == 1 ? P->weight[1] : src == 2 ? P->weight[2] : P->weight[3];
               const uint32_t wd = dst == 0 ? P->weight[0] : dst == 1 ? P->weight[1] : P->weight[2];
-              const uint32_t id = P->move_base + (((uint32_t)i * (P->NL - 1u) + dst) * 2u + x) * 2u + cv;
+              const uint32_t id = P->move_base + (((uint32_t)i * (P->NL - 1u) + dst) * P->xw + x) * 2u + cv;
               if (sub != kInf && c_load != kInf && c_store != kInf) {
                 uint64_t tot = add_or_limit(mul_or_limit(lines_s, ws), mul_or_limit(lines_d, wd));
                 tot = add_or_limit(add_or_limit(tot, c_load), add_or_limit(c_store, sub));
@@ -1212,16 +1261,35 @@ __global__ __launch_bounds__(256) void fill_bounded_kernel(const DevParams* __re
           // leaves only that dimension adjacent; the tile is aligned only if the tensor was aligned
           // and contiguous and the tile's rows (and so the tile) are whole cache lines.
           const uint64_t r2 = d == 1 ? P->sizes[1][te.jt] : S.d[1], c2 = d == 3 ? P->sizes[3][te.jt] : S.d[3];
+          const uint64_t strip = P->strip ? P->strip : 1u;
           uint32_t qc = 0;
 #pragma unroll
           for (int ts = 0; ts < 2; ts++) {
-            const uint32_t y = P->lay_bit[ts] != kNoBit ? (v >> P->lay_bit[ts]) & 1u : 0u;
+            const uint32_t y = layout_of(ts);
             const uint32_t bf = P->dt_bit[ts] != kNoBit ? (v >> P->dt_bit[ts]) & 1u : P->base_bf16[ts];
-            const uint64_t inner = y ? S.d[1] : S.d[3], inner2 = y ? r2 : c2, outer2 = y ? c2 : r2, eb = bf ? 2u : 4u;
+            const uint64_t eb = bf ? 2u : 4u;
+            uint64_t whole[3], part[3];
+            const uint32_t nd = phys_dims(y, S.d[1], S.d[3], strip, whole);
+            phys_dims(y, r2, c2, strip, part);
+            // the tile's values over its inner j dimensions are adjacent while the j - 1 innermost are uncut
+            uint32_t uncut = 0;
+            bool lines_ok = y < 2 || c2 >= strip;          // a part of a strip is not known to be aligned
+            uint64_t suffix = eb;
+            bool still = true;
+#pragma unroll
+            for (int q3 = 2; q3 >= 0; q3--) {
+              if ((uint32_t)q3 >= nd) continue;
+              still = still && part[q3] == whole[q3];
+              uncut += still ? 1u : 0u;
+              suffix *= part[q3];
+              lines_ok = lines_ok && suffix % P->line_bytes == 0;
+            }
             const uint32_t contig = qi[2 * ts], aligned = qi[2 * ts + 1];
-            const uint32_t contig2 = inner2 == inner ? contig : (contig < 1u ? contig : 1u);
-            const uint32_t aligned2 = (aligned && contig == 2u && (inner2 * eb) % P->line_bytes == 0 &&
-                                       (outer2 * inner2 * eb) % P->line_bytes == 0) ? 1u : 0u;
+            uint32_t keep = 1u + uncut;
+            const uint32_t most = max_contig(y, c2, strip);
+            keep = keep < most ? keep : most;
+            const uint32_t contig2 = contig < keep ? contig : keep;
+            const uint32_t aligned2 = (aligned && contig == nd && lines_ok) ? 1u : 0u;
             qc += contig2 * P->lim_stride[2 * ts] + aligned2 * P->lim_stride[2 * ts + 1];
           }
           off_c = ((combo * npass + pass) * Q + qc) * V + v;
@@ -1282,7 +1350,7 @@ __global__ __launch_bounds__(256) void fill_bounded_kernel(const DevParams* __re
 #pragma unroll
   for (int d = 32; d > 0; d >>= 1) {
     n_rw += __shfl_down(n_rw, d, 64);
-    if (MODE == 2) n_adm += __shfl_down(n_adm, d, 64);
+    if (MODE != 0) n_adm += __shfl_down(n_adm, d, 64);
   }
   if ((threadIdx.x & 63u) == 0) { wave_n[threadIdx.x >> 6] = n_rw; wave_adm[threadIdx.x >> 6] = n_adm; }
   __syncthreads();
@@ -1290,7 +1358,7 @@ __global__ __launch_bounds__(256) void fill_bounded_kernel(const DevParams* __re
     const uint32_t n = wave_n[0] + wave_n[1] + wave_n[2] + wave_n[3];
     if (n) atomicAdd(&ctr->n_rewrites[blockIdx.x % kCtrSlots], (unsigned long long)n);
     const uint32_t na = wave_adm[0] + wave_adm[1] + wave_adm[2] + wave_adm[3];
-    if (MODE == 2 && na) atomicAdd(&ctr->n_admissible[blockIdx.x % kCtrSlots], (unsigned long long)na);
+    if (MODE != 0 && na) atomicAdd(&ctr->n_admissible[blockIdx.x % kCtrSlots], (unsigned long long)na);
   }
   if (e.ovf) atomicOr(&ctr->overflow, e.ovf);
 }

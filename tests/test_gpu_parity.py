@@ -494,6 +494,68 @@ def test_composition_host_checks():
         assert e.value.code == B.E_INVAL
 
 
+def packed_case(case):
+    """Move lattices whose tensors may be packed in strips, and Matmul lattices that read them."""
+    if case.isdigit():
+        return W.config(12, max_size=int(case))
+    t = W._empty_target(3, (64, 128, W.UNBOUNDED))
+    t["loop_overhead"] = 1
+    t["line_bytes"] = 8
+    t["strip"] = 2
+    t["level_weight"] = [1, 2, 5, 0]
+    t["microkernels"] = [(W.MK_SCALAR_FMA, 1, 1), (W.MK_BCAST_VEC_MULADD, 2, 1), (W.MK_SCALAR_MOVE, 1, 3), (W.MK_VECTOR_MOVE, 2, 2),
+                         (W.MK_VECTOR_MOVE_ALIGNED, 2, 1)]
+    r = [1, 2, 4, 6, 8]
+    if case == "moves-with-dtypes":
+        lats = [("V", W._lattice(W.KIND_MOVE, [[1], r, [1], r], layout=(2, 2, 0, 0, 0), dtype=(1, 1, 0, 0, 0)), [])]
+    elif case == "one-tensor-packed":
+        lats = [("V", W._lattice(W.KIND_MOVE, [[1], r, [1], r], layout=(1, 2, 0, 0, 0)), [])]
+    elif case == "strips-of-four-lanes-of-two":
+        t["strip"] = 4
+        lats = [("V", W._lattice(W.KIND_MOVE, [[1], r, [1], r], layout=(2, 2, 0, 0, 0)), []),
+                ("M", W._lattice(W.KIND_MATMUL_MOVES, [[1], r, r, r], layout=(0, 2, 2, 0, 0)), ["V"])]
+    elif case == "strips-no-multiple-of-the-lanes":
+        t["strip"] = 6
+        t["microkernels"][1] = (W.MK_BCAST_VEC_MULADD, 4, 1)
+        t["microkernels"][3] = (W.MK_VECTOR_MOVE, 4, 2)
+        t["microkernels"][4] = (W.MK_VECTOR_MOVE_ALIGNED, 4, 1)
+        r = [1, 2, 3, 4, 6, 12]
+        lats = [("V", W._lattice(W.KIND_MOVE, [[1], r, [1], r], layout=(2, 2, 0, 0, 0)), []),
+                ("M", W._lattice(W.KIND_MATMUL_MOVES, [[1], r, r, r], layout=(0, 2, 2, 0, 0)), ["V"])]
+    elif case == "all-operands-packed":
+        r = [1, 2, 4]
+        lats = [("V", W._lattice(W.KIND_MOVE, [[1], r, [1], r], layout=(2, 2, 0, 0, 0)), []),
+                ("M", W._lattice(W.KIND_MATMUL_MOVES, [[1], r, r, r], layout=(2, 2, 2, 0, 0)), ["V"])]
+    elif case == "packed-and-bf16":
+        r = [1, 2, 4]
+        lats = [("V", W._lattice(W.KIND_MOVE, [[1], r, [1], r], layout=(2, 2, 0, 0, 0), dtype=(1, 1, 0, 0, 0)), []),
+                ("M", W._lattice(W.KIND_MATMUL_MOVES, [[1], r, r, r], layout=(1, 2, 0, 0, 0), dtype=(1, 0, 0, 0, 0),
+                                 base_bytes=(4, 2, 4, 4, 4)), ["V"])]
+    else:
+        raise ValueError(case)
+    return {"name": "packed-" + case, "target": t, "lattices": lats}
+
+
+@pytest.mark.parametrize("case", ["moves-with-dtypes", "one-tensor-packed", "strips-of-four-lanes-of-two",
+                                  "strips-no-multiple-of-the-lanes", "all-operands-packed", "packed-and-bf16", "8", "16"])
+def test_parity_packed_layouts(case):
+    """Packed and shuffled layouts in the Move lattice (contiguousness 0..3, tiles narrower than a
+    strip, Specs whose tensors do not exist) and in the Matmul lattice that reads it (Moves into
+    any of four layouts, eight ids per operand and level): dense tables, counters, both box lists."""
+    cfg = packed_case(case)
+    _, got, want = compare_config(cfg)
+    for label, _, _ in cfg["lattices"]:
+        assert 0 < want[label]["n_admissible"] < len(want[label]["cost"])
+        check_compressed_queries(got[label], want[label], 2_000, seed=13)
+    if "M" in got:
+        lat = next(l for lb, l, _ in cfg["lattices"] if lb == "M")
+        ids = O.geometry(cfg["target"], lat)[2]
+        nl = cfg["target"]["n_levels"]
+        r = got["M"].rewrite_decode(ids["move_base"] + ((1 * (nl - 1) + 0) * 4 + 3) * 2)
+        assert (r.cls, r.operand_or_dim, r.dst_level, r.transposed, r.convert) == (1, 1, 0, 3, 0)
+        assert got["M"].rewrite_decode(ids["tile_base"]).cls == 2 and ids["tile_base"] == ids["move_base"] + 3 * (nl - 1) * 8
+
+
 def test_degenerate_lattices():
     B = _binding()
     # a single shape: every dimension pinned

@@ -63,10 +63,10 @@ def test_parity_other_seeds(seed):
     compare_config(W.config(7, seed=seed, max_size=2))
 
 
-@pytest.mark.parametrize("number", [2, 4, 10])
+@pytest.mark.parametrize("number", [2, 4, 10, 12])
 def test_parity_full_size(number):
-    """Configurations 2, 4 and 10 at full size (16.8 M, 23.7 M and 67.1 M specs), all outputs."""
-    compare_config(W.config(number), scratch_bytes=(4 if number == 10 else 2) << 30)
+    """Configurations 2, 4, 10 and 12 at full size (16.8 M, 23.7 M, 67.1 M and 16.8 M + 67.1 M specs), all outputs."""
+    compare_config(W.config(number), scratch_bytes=(4 if number >= 10 else 2) << 30)
 
 
 def test_parity_config5_full_size():

@@ -313,8 +313,11 @@ void mrl_table_destroy(mrl_table* tab);
  * not their compressed form of Section 4.1).  Job j is what mrl_solve would do
  * with the same arguments, its deps given as indices of EARLIER jobs.  Every job
  * runs from a host thread of its own on its own stream (all different; default
- * priority); a job starts as soon as the FILL of its deps is queued, ordered behind
- * it on the device by an event, and a dep is compressed once the jobs that read it
+ * priority); a job starts as soon as the FILL of its deps is queued: its work
+ * lists and its pre-fill, which read no other table, run beside those fills, and
+ * its dependency levels are ordered behind them on the device by an event (such a
+ * job's fill_ms leaves out the time between the two in which it only waited); a
+ * dep is compressed once the jobs that read it
  * have queued their own fill: its compression overlaps with their work instead of
  * holding it up, and independent jobs overlap as with mrl_solve from several
  * threads.  The last job runs on the calling thread.  No two jobs may be the

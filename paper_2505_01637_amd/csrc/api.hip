@@ -517,7 +517,7 @@ struct Aux {
   hipStream_t stream = nullptr;
   std::vector<hipEvent_t> events;
   uint32_t* h_counts = nullptr;     // pinned: counts read back without stalling the other stream
-  hipEvent_t timing[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};   // fill start, fill end, compression end and start, plan + pre-fill end
+  hipEvent_t timing[6] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};   // fill start, fill end, compression end and start, plan + pre-fill end, first dependency level
   int device = -1;
   bool busy = false;
 };
@@ -655,6 +655,13 @@ namespace {
 // one is not deleted when the rest of the solve fails (the sharer deletes it).
 using FilledFn = std::function<bool(mrl_table*)>;
 
+// late_deps (optional; then deps is NULL) hands over the tables a lattice reads only when the fill
+// needs them: it is called once the work that reads no other table (work lists and the pre-fill)
+// is queued, may wait on the host until those tables' fills are queued, and gives for each an
+// event behind which the table is complete.  The pre-fill of a large table then runs beside the
+// fill of the tables it will read, not after it.
+using LateDepsFn = std::function<int32_t(const mrl_table* tables[2], hipEvent_t ready[2])>;
+
 // Host threads that run the jobs of mrl_solve_graph.  They are kept between calls (a thread's
 // first HIP calls are slow) and never end; every queued task gets a thread, since tasks wait for
 // each other.  The pool is never destroyed: its threads may still wait in it when the process ends.
@@ -694,7 +701,7 @@ Workers& workers() { static Workers* w = new Workers; return *w; }
 
 int32_t solve_impl(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_table* const* deps, uint32_t n_deps,
                    void* d_cost, void* d_argmin, void* d_scratch, size_t scratch_bytes, void* hip_stream,
-                   mrl_table** out, mrl_stats* stats, const FilledFn& on_filled) {
+                   mrl_table** out, mrl_stats* stats, const FilledFn& on_filled, const LateDepsFn& late_deps = LateDepsFn()) {
   return guarded([&]() -> int32_t {
   if (!out) return fail(MRL_E_INVAL, "out is NULL");
   *out = nullptr;
@@ -711,97 +718,112 @@ int32_t solve_impl(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_t
   tab->P = c.P;
   DevParams& P = tab->P;
 
-  if (P.split) {
-    if (n_deps != 2 || !deps || !deps[0] || !deps[1]) return fail(MRL_E_INVAL, "a BIAS_ADD_RELU_SPLIT lattice needs deps = {BIAS_ADD table, RELU table}");
-    const Compiled& A = *deps[0]->cp;
-    const Compiled& R = *deps[1]->cp;
-    if (A.lat.kind != MRL_KIND_BIAS_ADD || R.lat.kind != MRL_KIND_RELU) return fail(MRL_E_INVAL, "deps must be {BIAS_ADD, RELU}");
-    if (memcmp(&A.target, &t->d, sizeof t->d) || memcmp(&R.target, &t->d, sizeof t->d)) return fail(MRL_E_INVAL, "deps were solved for another target");
-    if (A.sizes[1] != c.sizes[1] || A.sizes[3] != c.sizes[3] || R.sizes[1] != c.sizes[1] || R.sizes[3] != c.sizes[3])
-      return fail(MRL_E_INVAL, "the deps must have this lattice's m and n size lists");
-    if ((P.lay_bit[0] != kNoBit && A.P.lay_bit[0] == kNoBit) || (P.lay_bit[2] != kNoBit && R.P.lay_bit[1] == kNoBit))
-      return fail(MRL_E_INVAL, "a tensor with a layout coordinate in the BIAS_ADD_RELU_SPLIT lattice needs one in the dep it is looked up in");
-    P.costM = deps[0]->d_cost; P.costE = deps[1]->d_cost;
-    tab->deps[0] = deps[0]; tab->deps[1] = deps[1];
-    P.GM = A.P.G; P.VM = A.P.V; P.GE = R.P.G; P.VE = R.P.V;
-    for (int i = 0; i < 3; i++) { P.layM[i] = A.P.lay_bit[i]; P.layE[i] = R.P.lay_bit[i]; }
-  } else if (P.chain) {
-    if (n_deps != 1 || !deps || !deps[0]) return fail(MRL_E_INVAL, "a MATMUL_CHAIN lattice needs deps = {MATMUL_ACCUM table}");
-    const Compiled& M = *deps[0]->cp;
-    if (M.P.kind != kKindM || M.P.par || M.P.bounded || M.P.moves) return fail(MRL_E_INVAL, "the dep must be a MATMUL_ACCUM table");
-    if (memcmp(&M.target, &t->d, sizeof t->d)) return fail(MRL_E_INVAL, "the dep was solved for another target");
-    if (M.sizes[0].size() != 1) return fail(MRL_E_INVAL, "MATMUL_ACCUM dep must have b pinned to 1");
-    // both stages are looked up in it: (m, k, p) and (m, p, n)
-    if (M.sizes[1] != c.sizes[1] || M.sizes[2] != c.sizes[2] || M.sizes[2] != c.sizes[0] || M.sizes[3] != c.sizes[0] || M.sizes[3] != c.sizes[3])
-      return fail(MRL_E_INVAL, "the m list must equal the MATMUL_ACCUM dep's, and the p, k and n lists its k and n lists");
-    if ((P.lay_bit[0] != kNoBit && M.P.lay_bit[0] == kNoBit) || (P.lay_bit[1] != kNoBit && M.P.lay_bit[1] == kNoBit) ||
-        (P.lay_bit[2] != kNoBit && M.P.lay_bit[1] == kNoBit) || (P.lay_bit[3] != kNoBit && M.P.lay_bit[2] == kNoBit))
-      return fail(MRL_E_INVAL, "a tensor with a layout coordinate in the MATMUL_CHAIN lattice needs one in the dep it is looked up in");
-    if (M.P.ndt || M.P.base_bf16[0] || M.P.base_bf16[1] || M.P.base_bf16[2]) return fail(MRL_E_INVAL, "MATMUL_ACCUM dep must be f32");
-    P.costM = deps[0]->d_cost;
-    tab->deps[0] = deps[0];
-    P.GM = M.P.G; P.VM = M.P.V; P.kM_first = 0; P.nkM = (uint32_t)M.sizes[2].size();
-    for (int i = 0; i < 3; i++) P.layM[i] = M.P.lay_bit[i];
-  } else if (P.kind == kKindF) {
-    if (n_deps != 2 || !deps || !deps[0] || !deps[1]) return fail(MRL_E_INVAL, "a FUSED lattice needs deps = {MATMUL_ACCUM table, BIAS_ADD_RELU table}");
-    const Compiled& M = *deps[0]->cp;
-    const Compiled& E = *deps[1]->cp;
-    if (M.P.kind != kKindM || M.P.par || E.P.kind != kKindE || E.lat.kind == MRL_KIND_BIAS_ADD)
-      return fail(MRL_E_INVAL, "deps must be {MATMUL_ACCUM, BIAS_ADD_RELU (or BIAS_ADD_RELU_SPLIT)}");
-    if (M.P.bounded != P.bounded || E.P.bounded != P.bounded) return fail(MRL_E_INVAL, "memory bounds on all three tables or on none");
-    if ((P.lay_bit[0] != kNoBit && M.P.lay_bit[0] == kNoBit) || (P.lay_bit[1] != kNoBit && M.P.lay_bit[1] == kNoBit) ||
-        (P.lay_bit[3] != kNoBit && E.P.lay_bit[2] == kNoBit))
-      return fail(MRL_E_INVAL, "a tensor with a layout coordinate in the FUSED lattice needs one in the dep it is looked up in");
-    if (memcmp(&M.target, &t->d, sizeof t->d) || memcmp(&E.target, &t->d, sizeof t->d)) return fail(MRL_E_INVAL, "deps were solved for another target");
-    if (M.sizes[1] != c.sizes[1] || M.sizes[3] != c.sizes[3]) return fail(MRL_E_INVAL, "MATMUL_ACCUM dep has other size lists");
-    {
-      // the k list: the dep's, or a stretch of consecutive entries of it (a slab of the whole lattice)
-      const auto at = std::find(M.sizes[2].begin(), M.sizes[2].end(), c.sizes[2][0]);
-      if ((size_t)(M.sizes[2].end() - at) < c.sizes[2].size() || !std::equal(c.sizes[2].begin(), c.sizes[2].end(), at))
-        return fail(MRL_E_INVAL, "the k list must be a stretch of the MATMUL_ACCUM dep's k list");
-      P.kM_first = (uint32_t)(at - M.sizes[2].begin());
-      P.nkM = (uint32_t)M.sizes[2].size();
+  const mrl_table* late_tables[2] = {nullptr, nullptr};
+  hipEvent_t late_ready[2] = {nullptr, nullptr};
+  // the tables this lattice reads: checked against it, their geometry and addresses into P
+  auto bind_deps = [&]() -> int32_t {
+    if (P.split) {
+      if (n_deps != 2 || !deps || !deps[0] || !deps[1]) return fail(MRL_E_INVAL, "a BIAS_ADD_RELU_SPLIT lattice needs deps = {BIAS_ADD table, RELU table}");
+      const Compiled& A = *deps[0]->cp;
+      const Compiled& R = *deps[1]->cp;
+      if (A.lat.kind != MRL_KIND_BIAS_ADD || R.lat.kind != MRL_KIND_RELU) return fail(MRL_E_INVAL, "deps must be {BIAS_ADD, RELU}");
+      if (memcmp(&A.target, &t->d, sizeof t->d) || memcmp(&R.target, &t->d, sizeof t->d)) return fail(MRL_E_INVAL, "deps were solved for another target");
+      if (A.sizes[1] != c.sizes[1] || A.sizes[3] != c.sizes[3] || R.sizes[1] != c.sizes[1] || R.sizes[3] != c.sizes[3])
+        return fail(MRL_E_INVAL, "the deps must have this lattice's m and n size lists");
+      if ((P.lay_bit[0] != kNoBit && A.P.lay_bit[0] == kNoBit) || (P.lay_bit[2] != kNoBit && R.P.lay_bit[1] == kNoBit))
+        return fail(MRL_E_INVAL, "a tensor with a layout coordinate in the BIAS_ADD_RELU_SPLIT lattice needs one in the dep it is looked up in");
+      P.costM = deps[0]->d_cost; P.costE = deps[1]->d_cost;
+      tab->deps[0] = deps[0]; tab->deps[1] = deps[1];
+      P.GM = A.P.G; P.VM = A.P.V; P.GE = R.P.G; P.VE = R.P.V;
+      for (int i = 0; i < 3; i++) { P.layM[i] = A.P.lay_bit[i]; P.layE[i] = R.P.lay_bit[i]; }
+    } else if (P.chain) {
+      if (n_deps != 1 || !deps || !deps[0]) return fail(MRL_E_INVAL, "a MATMUL_CHAIN lattice needs deps = {MATMUL_ACCUM table}");
+      const Compiled& M = *deps[0]->cp;
+      if (M.P.kind != kKindM || M.P.par || M.P.bounded || M.P.moves) return fail(MRL_E_INVAL, "the dep must be a MATMUL_ACCUM table");
+      if (memcmp(&M.target, &t->d, sizeof t->d)) return fail(MRL_E_INVAL, "the dep was solved for another target");
+      if (M.sizes[0].size() != 1) return fail(MRL_E_INVAL, "MATMUL_ACCUM dep must have b pinned to 1");
+      // both stages are looked up in it: (m, k, p) and (m, p, n)
+      if (M.sizes[1] != c.sizes[1] || M.sizes[2] != c.sizes[2] || M.sizes[2] != c.sizes[0] || M.sizes[3] != c.sizes[0] || M.sizes[3] != c.sizes[3])
+        return fail(MRL_E_INVAL, "the m list must equal the MATMUL_ACCUM dep's, and the p, k and n lists its k and n lists");
+      if ((P.lay_bit[0] != kNoBit && M.P.lay_bit[0] == kNoBit) || (P.lay_bit[1] != kNoBit && M.P.lay_bit[1] == kNoBit) ||
+          (P.lay_bit[2] != kNoBit && M.P.lay_bit[1] == kNoBit) || (P.lay_bit[3] != kNoBit && M.P.lay_bit[2] == kNoBit))
+        return fail(MRL_E_INVAL, "a tensor with a layout coordinate in the MATMUL_CHAIN lattice needs one in the dep it is looked up in");
+      if (M.P.ndt || M.P.base_bf16[0] || M.P.base_bf16[1] || M.P.base_bf16[2]) return fail(MRL_E_INVAL, "MATMUL_ACCUM dep must be f32");
+      P.costM = deps[0]->d_cost;
+      tab->deps[0] = deps[0];
+      P.GM = M.P.G; P.VM = M.P.V; P.kM_first = 0; P.nkM = (uint32_t)M.sizes[2].size();
+      for (int i = 0; i < 3; i++) P.layM[i] = M.P.lay_bit[i];
+    } else if (P.kind == kKindF) {
+      if (n_deps != 2 || !deps || !deps[0] || !deps[1]) return fail(MRL_E_INVAL, "a FUSED lattice needs deps = {MATMUL_ACCUM table, BIAS_ADD_RELU table}");
+      const Compiled& M = *deps[0]->cp;
+      const Compiled& E = *deps[1]->cp;
+      if (M.P.kind != kKindM || M.P.par || E.P.kind != kKindE || E.lat.kind == MRL_KIND_BIAS_ADD)
+        return fail(MRL_E_INVAL, "deps must be {MATMUL_ACCUM, BIAS_ADD_RELU (or BIAS_ADD_RELU_SPLIT)}");
+      if (M.P.bounded != P.bounded || E.P.bounded != P.bounded) return fail(MRL_E_INVAL, "memory bounds on all three tables or on none");
+      if ((P.lay_bit[0] != kNoBit && M.P.lay_bit[0] == kNoBit) || (P.lay_bit[1] != kNoBit && M.P.lay_bit[1] == kNoBit) ||
+          (P.lay_bit[3] != kNoBit && E.P.lay_bit[2] == kNoBit))
+        return fail(MRL_E_INVAL, "a tensor with a layout coordinate in the FUSED lattice needs one in the dep it is looked up in");
+      if (memcmp(&M.target, &t->d, sizeof t->d) || memcmp(&E.target, &t->d, sizeof t->d)) return fail(MRL_E_INVAL, "deps were solved for another target");
+      if (M.sizes[1] != c.sizes[1] || M.sizes[3] != c.sizes[3]) return fail(MRL_E_INVAL, "MATMUL_ACCUM dep has other size lists");
+      {
+        // the k list: the dep's, or a stretch of consecutive entries of it (a slab of the whole lattice)
+        const auto at = std::find(M.sizes[2].begin(), M.sizes[2].end(), c.sizes[2][0]);
+        if ((size_t)(M.sizes[2].end() - at) < c.sizes[2].size() || !std::equal(c.sizes[2].begin(), c.sizes[2].end(), at))
+          return fail(MRL_E_INVAL, "the k list must be a stretch of the MATMUL_ACCUM dep's k list");
+        P.kM_first = (uint32_t)(at - M.sizes[2].begin());
+        P.nkM = (uint32_t)M.sizes[2].size();
+      }
+      if (M.sizes[0].size() != 1) return fail(MRL_E_INVAL, "MATMUL_ACCUM dep must have b pinned to 1");
+      if (E.sizes[1] != c.sizes[1] || E.sizes[3] != c.sizes[3]) return fail(MRL_E_INVAL, "BIAS_ADD_RELU dep has other size lists");
+      if (M.P.ndt || M.P.base_bf16[0] || M.P.base_bf16[1] || M.P.base_bf16[2]) return fail(MRL_E_INVAL, "MATMUL_ACCUM dep must be f32");
+      P.costM = deps[0]->d_cost; P.costE = deps[1]->d_cost;
+      tab->deps[0] = deps[0]; tab->deps[1] = deps[1];
+      P.GM = M.P.G; P.VM = M.P.V; P.GE = E.P.G; P.VE = E.P.V; P.nszE_n = E.P.nsz[3];
+      for (int i = 0; i < 3; i++) { P.layM[i] = M.P.lay_bit[i]; P.layE[i] = E.P.lay_bit[i]; }
+    } else if (P.par) {
+      if (n_deps != 1 || !deps || !deps[0]) return fail(MRL_E_INVAL, "a MATMUL_PARALLEL lattice needs deps = {MATMUL_ACCUM table of the same lattice}");
+      const Compiled& M = *deps[0]->cp;
+      if (M.P.kind != kKindM || M.P.par) return fail(MRL_E_INVAL, "the dep must be a MATMUL_ACCUM table");
+      if (memcmp(&M.target, &t->d, sizeof t->d)) return fail(MRL_E_INVAL, "the dep was solved for another target");
+      for (int d = 0; d < 4; d++) if (M.sizes[d] != c.sizes[d]) return fail(MRL_E_INVAL, "the MATMUL_ACCUM dep has other size lists");
+      if (memcmp(M.lat.layout_coord, c.lat.layout_coord, sizeof c.lat.layout_coord) ||
+          memcmp(M.lat.dtype_coord, c.lat.dtype_coord, sizeof c.lat.dtype_coord) ||
+          memcmp(M.lat.base_dtype_bytes, c.lat.base_dtype_bytes, 3) || M.n_specs != c.n_specs || M.P.G != P.G)
+        return fail(MRL_E_INVAL, "the MATMUL_ACCUM dep has other coordinates");
+      P.costM = deps[0]->d_cost;
+      tab->deps[0] = deps[0];
+    } else if (P.moves) {
+      if (n_deps != 1 || !deps || !deps[0]) return fail(MRL_E_INVAL, "a MATMUL_MOVES lattice needs deps = {MOVE table}");
+      const Compiled& V = *deps[0]->cp;
+      if (V.P.kind != kKindV) return fail(MRL_E_INVAL, "the dep must be a MOVE table");
+      if (memcmp(&V.target, &t->d, sizeof t->d)) return fail(MRL_E_INVAL, "the dep was solved for another target");
+      if (c.sizes[1] != V.sizes[1] || c.sizes[2] != V.sizes[1] || c.sizes[2] != V.sizes[3] || c.sizes[3] != V.sizes[3])
+        return fail(MRL_E_INVAL, "the m, k and n size lists must all equal the MOVE table's row and column lists");
+      bool any_lay = false, any_dt = false;
+      for (int i = 0; i < 3; i++) { any_lay = any_lay || P.lay_bit[i] != kNoBit; any_dt = any_dt || P.dt_bit[i] != kNoBit || P.base_bf16[i]; }
+      if (any_lay && (V.P.lay_bit[0] == kNoBit || V.P.lay_bit[1] == kNoBit)) return fail(MRL_E_INVAL, "the MOVE table needs layout bits on both tensors");
+      if (P.xw == 4 && (V.P.lay_w[0] != 2 || V.P.lay_w[1] != 2)) return fail(MRL_E_INVAL, "the MOVE table needs the packed layouts on both tensors");
+      if (any_dt && (V.P.dt_bit[0] == kNoBit || V.P.dt_bit[1] == kNoBit)) return fail(MRL_E_INVAL, "the MOVE table needs dtype bits on both tensors");
+      if (V.P.dt_bit[0] == kNoBit && (V.P.base_bf16[0] || V.P.base_bf16[1])) return fail(MRL_E_INVAL, "a MOVE table without dtype bits must be f32");
+      P.costM = deps[0]->d_cost;
+      tab->deps[0] = deps[0];
+      P.GV = V.P.G; P.VV = V.P.V; P.nszV = V.P.nsz[3]; P.QV = V.P.Q; P.qV_top = V.P.Q - 1;
+      for (int a = 0; a < 4; a++) P.limV_stride[a] = V.P.lim_stride[a];
+      for (int i = 0; i < 2; i++) { P.layV[i] = V.P.lay_bit[i]; P.dtV[i] = V.P.dt_bit[i]; }
+    } else if (n_deps != 0) {
+      return fail(MRL_E_INVAL, "only FUSED, MATMUL_PARALLEL, MATMUL_MOVES, MATMUL_CHAIN and BIAS_ADD_RELU_SPLIT lattices take deps");
     }
-    if (M.sizes[0].size() != 1) return fail(MRL_E_INVAL, "MATMUL_ACCUM dep must have b pinned to 1");
-    if (E.sizes[1] != c.sizes[1] || E.sizes[3] != c.sizes[3]) return fail(MRL_E_INVAL, "BIAS_ADD_RELU dep has other size lists");
-    if (M.P.ndt || M.P.base_bf16[0] || M.P.base_bf16[1] || M.P.base_bf16[2]) return fail(MRL_E_INVAL, "MATMUL_ACCUM dep must be f32");
-    P.costM = deps[0]->d_cost; P.costE = deps[1]->d_cost;
-    tab->deps[0] = deps[0]; tab->deps[1] = deps[1];
-    P.GM = M.P.G; P.VM = M.P.V; P.GE = E.P.G; P.VE = E.P.V; P.nszE_n = E.P.nsz[3];
-    for (int i = 0; i < 3; i++) { P.layM[i] = M.P.lay_bit[i]; P.layE[i] = E.P.lay_bit[i]; }
-  } else if (P.par) {
-    if (n_deps != 1 || !deps || !deps[0]) return fail(MRL_E_INVAL, "a MATMUL_PARALLEL lattice needs deps = {MATMUL_ACCUM table of the same lattice}");
-    const Compiled& M = *deps[0]->cp;
-    if (M.P.kind != kKindM || M.P.par) return fail(MRL_E_INVAL, "the dep must be a MATMUL_ACCUM table");
-    if (memcmp(&M.target, &t->d, sizeof t->d)) return fail(MRL_E_INVAL, "the dep was solved for another target");
-    for (int d = 0; d < 4; d++) if (M.sizes[d] != c.sizes[d]) return fail(MRL_E_INVAL, "the MATMUL_ACCUM dep has other size lists");
-    if (memcmp(M.lat.layout_coord, c.lat.layout_coord, sizeof c.lat.layout_coord) ||
-        memcmp(M.lat.dtype_coord, c.lat.dtype_coord, sizeof c.lat.dtype_coord) ||
-        memcmp(M.lat.base_dtype_bytes, c.lat.base_dtype_bytes, 3) || M.n_specs != c.n_specs || M.P.G != P.G)
-      return fail(MRL_E_INVAL, "the MATMUL_ACCUM dep has other coordinates");
-    P.costM = deps[0]->d_cost;
-    tab->deps[0] = deps[0];
-  } else if (P.moves) {
-    if (n_deps != 1 || !deps || !deps[0]) return fail(MRL_E_INVAL, "a MATMUL_MOVES lattice needs deps = {MOVE table}");
-    const Compiled& V = *deps[0]->cp;
-    if (V.P.kind != kKindV) return fail(MRL_E_INVAL, "the dep must be a MOVE table");
-    if (memcmp(&V.target, &t->d, sizeof t->d)) return fail(MRL_E_INVAL, "the dep was solved for another target");
-    if (c.sizes[1] != V.sizes[1] || c.sizes[2] != V.sizes[1] || c.sizes[2] != V.sizes[3] || c.sizes[3] != V.sizes[3])
-      return fail(MRL_E_INVAL, "the m, k and n size lists must all equal the MOVE table's row and column lists");
-    bool any_lay = false, any_dt = false;
-    for (int i = 0; i < 3; i++) { any_lay = any_lay || P.lay_bit[i] != kNoBit; any_dt = any_dt || P.dt_bit[i] != kNoBit || P.base_bf16[i]; }
-    if (any_lay && (V.P.lay_bit[0] == kNoBit || V.P.lay_bit[1] == kNoBit)) return fail(MRL_E_INVAL, "the MOVE table needs layout bits on both tensors");
-    if (P.xw == 4 && (V.P.lay_w[0] != 2 || V.P.lay_w[1] != 2)) return fail(MRL_E_INVAL, "the MOVE table needs the packed layouts on both tensors");
-    if (any_dt && (V.P.dt_bit[0] == kNoBit || V.P.dt_bit[1] == kNoBit)) return fail(MRL_E_INVAL, "the MOVE table needs dtype bits on both tensors");
-    if (V.P.dt_bit[0] == kNoBit && (V.P.base_bf16[0] || V.P.base_bf16[1])) return fail(MRL_E_INVAL, "a MOVE table without dtype bits must be f32");
-    P.costM = deps[0]->d_cost;
-    tab->deps[0] = deps[0];
-    P.GV = V.P.G; P.VV = V.P.V; P.nszV = V.P.nsz[3]; P.QV = V.P.Q; P.qV_top = V.P.Q - 1;
-    for (int a = 0; a < 4; a++) P.limV_stride[a] = V.P.lim_stride[a];
-    for (int i = 0; i < 2; i++) { P.layV[i] = V.P.lay_bit[i]; P.dtV[i] = V.P.dt_bit[i]; }
-  } else if (n_deps != 0) {
-    return fail(MRL_E_INVAL, "only FUSED, MATMUL_PARALLEL, MATMUL_MOVES, MATMUL_CHAIN and BIAS_ADD_RELU_SPLIT lattices take deps");
+    return MRL_OK;
+  };
+  // (the lane-per-Spec kinds have no pre-fill to run ahead: they take their deps at once)
+  const bool deps_late = (bool)late_deps && !P.gather && n_deps > 0;
+  if (late_deps && !deps_late && n_deps > 0) {
+    rc = late_deps(late_tables, late_ready);
+    if (rc) return rc;
+    deps = late_tables;
+    for (uint32_t i = 0; i < n_deps; i++) HIP_TRY(hipStreamWaitEvent((hipStream_t)hip_stream, late_ready[i], 0));
   }
+  if (!deps_late) { rc = bind_deps(); if (rc) return rc; }
 
   std::unique_lock<std::mutex> solve_lock(c.solve_mu);      // for the upload image, until the upload has run
 
@@ -852,7 +874,7 @@ int32_t solve_impl(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_t
   size_t ev_used = 0;
   hipStream_t s2 = aux->stream;
   HIP_TRY(hipEventRecord(ev[0], st));
-  bool prefill_timed = false;
+  bool prefill_timed = false, levels_timed = false;
   const hipEvent_t uploaded = aux->events[ev_used++];
   HIP_TRY(hipEventRecord(uploaded, st));
   if (P.gather) {
@@ -902,6 +924,21 @@ int32_t solve_impl(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_t
   HIP_TRY(hipEventRecord(ev[4], st));
   prefill_timed = true;
   HIP_TRY(hipEventSynchronize(counts_ready));
+  if (deps_late) {
+    // now the tables this lattice reads: their fills are queued (or the call waits here until
+    // they are); the parameters go up once more, with their addresses, and the levels wait for them
+    rc = late_deps(late_tables, late_ready);
+    if (rc) return rc;
+    deps = late_tables;
+    rc = bind_deps();
+    if (rc) return rc;
+    memcpy(c.staging + f.params, &P, sizeof P);
+    HIP_TRY(hipMemcpyAsync(d_P, c.staging + f.params, sizeof P, hipMemcpyHostToDevice, st));
+    HIP_TRY(hipEventRecord(uploaded, st));
+    for (uint32_t i = 0; i < n_deps; i++) HIP_TRY(hipStreamWaitEvent(st, late_ready[i], 0));
+  }
+  HIP_TRY(hipEventRecord(ev[5], st));
+  levels_timed = true;
   bool wide_started = false;
   hipEvent_t wide_done = nullptr;          // recorded behind the last wide launch that the caller's stream has not waited for yet
   for (uint32_t l = 0; l < n_lev; l++) {
@@ -1126,6 +1163,13 @@ int32_t solve_impl(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_t
     if (P.bounded) stats->n_admissible = c.n_specs;      // no admissibility test: every Spec is evaluated
     stats->n_levels_run = n_lev;
     HIP_TRY(hipEventElapsedTime(&stats->fill_ms, ev[0], ev[1]));
+    if (prefill_timed && levels_timed && deps_late) {
+      // without the time the levels waited for the tables they read: work lists and pre-fill, then the levels
+      float a = 0, b = 0;
+      HIP_TRY(hipEventElapsedTime(&a, ev[0], ev[4]));
+      HIP_TRY(hipEventElapsedTime(&b, ev[5], ev[1]));
+      stats->fill_ms = a + b;
+    }
     HIP_TRY(hipEventElapsedTime(&stats->compress_ms, ev[3], ev[2]));
     if (prefill_timed) HIP_TRY(hipEventElapsedTime(&stats->prefill_ms, ev[0], ev[4]));
     stats->n_decision_boxes = tab->list_n[0];
@@ -1206,23 +1250,27 @@ int32_t mrl_solve_graph(const mrl_target* t, const mrl_job* jobs, uint32_t n_job
       S.cv.notify_all();
     };
     if (hipSetDevice(dev) != hipSuccess) { finish(fail(MRL_E_HIP, "hipSetDevice failed")); return; }
-    const mrl_table* deps[2] = {nullptr, nullptr};
-    {
+    // The tables the job reads, handed over when its fill needs them (its work lists and pre-fill
+    // are queued by then): wait until their fills are queued; a dep's dense table is complete once
+    // its stream has passed the recorded point.
+    const LateDepsFn late_deps = [&](const mrl_table* tables[2], hipEvent_t ready[2]) -> int32_t {
       std::unique_lock<std::mutex> lk(S.mu);
       for (uint32_t i = 0; i < job.n_deps; i++) {
         const uint32_t d = job.deps[i];
         S.cv.wait(lk, [&] { return S.state[d] != kWaiting; });
-        if (S.state[d] == kFailed) { S.skipped[j] = true; break; }
-        deps[i] = S.table[d];
+        if (S.state[d] == kFailed) { S.skipped[j] = true; return fail(MRL_E_INVAL, "a dep of the job failed"); }
+        tables[i] = S.table[d];
+        ready[i] = S.filled[d];
       }
+      return MRL_OK;
+    };
+    // (the job's own first kernels go to the GPU only once the fills it will read are queued: a
+    // pre-fill that arrives before them fills every compute unit and holds them up)
+    {
+      std::unique_lock<std::mutex> lk(S.mu);
+      for (uint32_t i = 0; i < job.n_deps; i++) S.cv.wait(lk, [&] { return S.state[job.deps[i]] != kWaiting; });
     }
-    if (S.skipped[j]) { finish(fail(MRL_E_INVAL, "a dep of the job failed")); return; }
-    // the dep's dense table is complete once its stream has passed the recorded point
-    for (uint32_t i = 0; i < job.n_deps; i++) {
-      const hipError_t e = hipStreamWaitEvent((hipStream_t)job.hip_stream, S.filled[job.deps[i]], 0);
-      if (e != hipSuccess) { finish(fail(MRL_E_HIP, "hipStreamWaitEvent: %s", hipGetErrorString(e))); return; }
-    }
-    rc = solve_impl(t, job.lattice, job.n_deps ? deps : nullptr, job.n_deps, job.d_cost, job.d_argmin, job.d_scratch,
+    rc = solve_impl(t, job.lattice, nullptr, job.n_deps, job.d_cost, job.d_argmin, job.d_scratch,
                     job.scratch_bytes, job.hip_stream, &out[j], stats ? &stats[j] : nullptr,
                     [&](mrl_table* tab) {
                       if (hipEventRecord(S.filled[j], tab->stream) != hipSuccess) return false;   // published at the end instead
@@ -1237,7 +1285,7 @@ int32_t mrl_solve_graph(const mrl_target* t, const mrl_job* jobs, uint32_t n_job
                         for (uint32_t i = 0; i < jobs[k].n_deps; i++)
                           if (jobs[k].deps[i] == j) S.cv.wait(lk, [&] { return S.state[k] != kWaiting; });
                       return true;
-                    });
+                    }, late_deps);
     finish(rc);
   };
   // a job always reports: its dependents wait for it

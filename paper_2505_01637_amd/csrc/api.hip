@@ -908,7 +908,8 @@ int32_t solve_impl(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_t
   if (fit_words) launch_zero_words((unsigned long long*)d_fitmap + f.n_words, 2, st);
   else launch_zero_words((unsigned long long*)d_fitmap, f.n_words + 2, st);
   // the plan kernel also streams (INF, NONE) over the tables when a shape's entries are whole 16-byte pieces
-  const bool fused_prefill = P.G % 8 == 0;
+  // (not when the pre-fill runs beside the fill of the tables this lattice reads: see launch_fill_ones)
+  const bool fused_prefill = P.G % 8 == 0 && !deps_late;
   launch_plan(d_P, c.n_shapes, P.npass, P.G, d_level_shapes, d_level_off, n_lev, d_shape_class, d_list_whole, d_list_slice,
               d_list_wide, d_list_cnt, d_fitmap, d_ctr, fused_prefill ? tab->d_cost : nullptr,
               fused_prefill ? tab->d_arg : nullptr, st);
@@ -918,8 +919,8 @@ int32_t solve_impl(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_t
   HIP_TRY(hipEventRecord(aux->events[ev_used], st));
   hipEvent_t counts_ready = aux->events[ev_used++];
   if (!fused_prefill) {
-    launch_fill_ones(tab->d_cost, c.n_specs * 8, st);
-    launch_fill_ones(tab->d_arg, c.n_specs * 2, st);
+    launch_fill_ones(tab->d_cost, c.n_specs * 8, st, deps_late);
+    launch_fill_ones(tab->d_arg, c.n_specs * 2, st, deps_late);
   }
   HIP_TRY(hipEventRecord(ev[4], st));
   prefill_timed = true;

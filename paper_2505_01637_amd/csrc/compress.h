@@ -33,7 +33,7 @@ struct BoundSegs {
 // mode 0: a lattice with memory bounds; 1: Move Specs; 2: a Matmul whose Moves are Move Specs.
 void launch_fill_bounded(const DevParams* P, int mode, const uint32_t* all_level_shapes, const BoundSegs& segs, uint64_t* cost,
                          uint16_t* arg, Counters* ctr, hipStream_t stream);
-void launch_fill_ones(void* p, size_t bytes, hipStream_t stream);
+void launch_fill_ones(void* p, size_t bytes, hipStream_t stream, bool short_lived = false);
 void launch_zero_words(unsigned long long* p, uint32_t n, hipStream_t st);
 void launch_head_flags(const Geo& g, uint32_t a0, const uint64_t* cost, const uint16_t* arg, const uint32_t* fitmap,
                        const uint32_t* axis_sizes,

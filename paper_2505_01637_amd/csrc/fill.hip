@@ -1005,9 +1005,30 @@ __global__ __launch_bounds__(256) void fill_ones_kernel(uint4* __restrict__ p, s
   for (size_t i = (size_t)blockIdx.x * 256u + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256u) p[i] = ones;
 }
 
-void launch_fill_ones(void* p, size_t bytes, hipStream_t stream) {
+// The same in workgroups that end after 16 KB each: beside the latency-bound kernels of another
+// stream the compute units' wave slots then turn over all the time, and those kernels' workgroups
+// are placed as soon as they are launched (a grid of workgroups that live as long as the whole
+// stream of stores holds every slot until it ends).
+__global__ __launch_bounds__(256) void fill_ones_short_kernel(uint4* __restrict__ p, size_t n16) {
+  const uint4 ones = make_uint4(~0u, ~0u, ~0u, ~0u);
+  const size_t i0 = (size_t)blockIdx.x * 1024u + threadIdx.x;
+#pragma unroll
+  for (int k = 0; k < 4; k++) {
+    const size_t i = i0 + (size_t)k * 256u;
+    if (i < n16) p[i] = ones;
+  }
+}
+
+void launch_fill_ones(void* p, size_t bytes, hipStream_t stream, bool short_lived) {
   const size_t n16 = bytes / 16;
-  if (n16) {
+  if (n16 && short_lived) {
+    size_t done = 0;
+    while (done < n16) {          // (grids stay below 2^31 workgroups)
+      const size_t part = n16 - done < ((size_t)1 << 40) ? n16 - done : ((size_t)1 << 40);
+      hipLaunchKernelGGL(fill_ones_short_kernel, dim3((uint32_t)((part + 1023) / 1024)), dim3(256), 0, stream, (uint4*)p + done, part);
+      done += part;
+    }
+  } else if (n16) {
     const size_t blocks = (n16 + 255) / 256;
     hipLaunchKernelGGL(fill_ones_kernel, dim3((uint32_t)(blocks < 16384 ? blocks : 16384)), dim3(256), 0, stream,
                        (uint4*)p, n16);

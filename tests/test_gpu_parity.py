@@ -894,6 +894,89 @@ def test_parity_random_lattices_more_kinds(seed):
         check_compressed_queries(got[label], want[label], 2_000, seed=seed)
 
 
+def random_config_newer(seed):
+    """Seeded random cases of the later kinds: (0) two composed Matmuls, (1) the pipeline with both
+    bufferize splits, (2) Move Specs with packed layouts and the Matmul that reads them."""
+    rng = np.random.default_rng(seed + 7_000_000)       # (not the stream that random_config draws the target from)
+    cfg = random_config(seed)
+    t = cfg["target"]
+    nl = t["n_levels"]
+    variant = int(rng.integers(0, 3))
+
+    def sizes(max_n, hi=13, divisor_of=None):
+        n = int(rng.integers(1, max_n + 1))
+        pool = np.arange(2, hi)
+        rest = sorted(rng.choice(pool, size=min(n - 1, len(pool)), replace=False).tolist()) if n > 1 else []
+        return [1] + [int(v) for v in rest]
+
+    bit = lambda p=0.4: int(rng.random() < p)
+    if variant == 0:
+        r = sizes(4)
+        lay = [bit(), bit(), bit(), bit()]
+        lay_m = (lay[0] | bit(0.2), lay[1] | lay[2], lay[3] | bit(0.2))
+        lats = [("M", W._lattice(W.KIND_MATMUL_ACCUM, [[1], sizes(4), r, r], layout=lay_m + (0, 0)), []), None]
+        lats[1] = ("G", W._lattice(W.KIND_MATMUL_CHAIN, [r, lats[0][1]["sizes"][1], r, r], layout=lay + [0]), ["M"])
+    elif variant == 1:
+        mk = [(W.MK_SCALAR_FMA, 1, int(rng.integers(1, 4)))]
+        if bit(0.6):
+            mk.append((W.MK_SCALAR_ADDRELU, 1, int(rng.integers(1, 5))))
+        if nl > 1 and bit(0.5):
+            mk.append((W.MK_VEC_ADDRELU, 2, int(rng.integers(1, 5))))
+        mk += [(W.MK_SCALAR_ADD, 1, int(rng.integers(1, 3))), (W.MK_SCALAR_RELU, 1, int(rng.integers(1, 3)))]
+        if nl > 1:
+            mk += [(W.MK_VEC_ADD, int(rng.choice([2, 4])), int(rng.integers(1, 3))), (W.MK_VEC_RELU, 2, int(rng.integers(1, 3)))]
+        t["microkernels"] = mk
+        m, k, n = sizes(4), sizes(3), sizes(5)
+        y_in, y_out = bit(), bit()
+        lats = [("M", W._lattice(W.KIND_MATMUL_ACCUM, [[1], m, k, n], layout=(bit(), bit(), 0, 0, 0)), []),
+                ("A", W._lattice(W.KIND_BIAS_ADD, [[1], m, [1], n], layout=(y_in, 0, bit(), 0, 0)), []),
+                ("R", W._lattice(W.KIND_RELU, [[1], m, [1], n], layout=(bit(), y_out, 0, 0, 0)), []),
+                ("S", W._lattice(W.KIND_BIAS_ADD_RELU_SPLIT, [[1], m, [1], n], layout=(y_in, 0, y_out, 0, 0)), ["A", "R"])]
+        lm = lats[0][1]["layout_coord"]
+        lats.append(("F", W._lattice(W.KIND_FUSED_MM_ADD_RELU, [[1], m, k, n],
+                                     layout=(lm[0] and bit(0.7), lm[1] and bit(0.7), 0, y_out and bit(0.7), 0)), ["M", "S"]))
+    else:
+        t["line_bytes"] = int(rng.choice([4, 8, 16, 64]))
+        t["strip"] = int(rng.choice([2, 4, 6, 8]))
+        t["level_weight"] = [int(rng.integers(0, 6)) for _ in range(4)]
+        lanes = int(rng.choice([2, 4]))
+        t["microkernels"] = [(W.MK_SCALAR_FMA, 1, int(rng.integers(1, 4))), (W.MK_SCALAR_MOVE, 1, int(rng.integers(1, 5)))]
+        if nl > 1:
+            t["microkernels"] += [(W.MK_BCAST_VEC_MULADD, lanes, 1), (W.MK_VECTOR_MOVE, lanes, int(rng.integers(1, 4))),
+                                  (W.MK_VECTOR_MOVE_ALIGNED, int(rng.choice([2, 4])), 1)]
+        r = sorted(set([1] + [int(v) for v in rng.choice([2, 3, 4, 6, 8, 12, 16], size=int(rng.integers(1, 5)), replace=False)]))
+        dt = bit(0.3)
+        lay_v = (2, 2) if bit(0.8) else (2, 1)
+        lats = [("V", W._lattice(W.KIND_MOVE, [[1], r, [1], r], layout=lay_v + (0, 0, 0), dtype=(dt, dt, 0, 0, 0)), [])]
+        if lay_v == (2, 2) and nl <= 3:
+            lay = [int(rng.choice([0, 1, 2])) for _ in range(3)]
+            if len(r) > 3:
+                lay[0] = min(lay[0], 1)
+            dtm = [dt and bit(), 0, 0]
+            bb = [2 if dt and not dtm[0] and bit(0.3) else 4, 2 if dt and bit(0.3) else 4, 4]
+            lats.append(("M", W._lattice(W.KIND_MATMUL_MOVES, [[1], r, r, r], layout=lay + [0, 0], dtype=dtm + [0, 0],
+                                         base_bytes=bb + [4, 4]), ["V"]))
+    return {"name": "random-newer-%d-v%d" % (seed, variant), "target": t, "lattices": lats}
+
+
+@pytest.mark.parametrize("seed", list(range(900000, 900030)))
+def test_parity_random_lattices_newer_kinds(seed):
+    """random_config_newer against the oracle, all outputs, and lookups in the box lists."""
+    B = _binding()
+    cfg = random_config_newer(seed)
+    if sum(W.n_specs(cfg["target"], lat) for _, lat, _ in cfg["lattices"]) > 4_000_000:
+        pytest.skip("too large for a quick case")
+    want = O.solve_config(cfg)
+    if any(r["rc"] == -6 for r in want.values()):
+        with pytest.raises(B.MorelloError) as e:
+            B.solve_config(cfg)
+        assert e.value.code == B.E_OVERFLOW
+        return
+    _, got, want = compare_config(cfg)
+    for label, _, _ in cfg["lattices"]:
+        check_compressed_queries(got[label], want[label], 1_000, seed=seed)
+
+
 def test_graph_calls_from_two_threads_on_the_same_lattices():
     """Two host threads each solve config 5 (small) through mrl_solve_graph, several times, at the
     same time: the calls take turns per lattice where they must and every result is the oracle's."""

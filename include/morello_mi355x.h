@@ -425,9 +425,10 @@ int32_t mrl_query_compressed(const mrl_table* tab, const mrl_coord* specs, size_
  * given to mrl_solve as deps must still be alive.  cost = the table's entry
  * of the node's Spec = cost of the whole subtree under Section 3's equation.
  * out: host array of cap nodes, or NULL to get the count only in *n_out;
- * MRL_E_INVAL if the goal has no implementation (cost MRL_INF), or for a table
- * of kind MOVE or MATMUL_MOVES (whose alloc-bindings have up to three children
- * in two tables: not walked by this call). */
+ * In a MATMUL_MOVES table a Move has up to three children: the load Move Spec
+ * (operands that are read), the body, the store Move Spec (the accumulated
+ * output), the Move Specs in dep 0 with both tensors fresh.
+ * MRL_E_INVAL if the goal has no implementation (cost MRL_INF). */
 typedef struct {
   uint32_t table;
   uint16_t rewrite;

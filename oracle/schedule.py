@@ -20,13 +20,16 @@ INF = 2 ** 64 - 1
 def axes(lattice, target=None):
     """(axis kind, operand or dimension or level) per coordinate, in coordinate order:
     sizes b, m, k, n; one level per operand (kinds F and G: plus the intermediate);
+    (Move Specs: contiguousness and aligned flag of both tensors;)
     (bounded kinds: one memory bound per level of finite capacity;) layout bits; dtype bits."""
     kind = lattice["kind"]
-    nops = 4 if B.base_kind(kind) in (B.F, B.G) else 2 if kind == B.R else 3
-    nlv = 5 if B.base_kind(kind) in (B.F, B.G) else 2 if kind == B.R else 3
+    nops = 4 if B.base_kind(kind) in (B.F, B.G) else 2 if kind in (B.R, B.V) else 3
+    nlv = 5 if B.base_kind(kind) in (B.F, B.G) else 2 if kind in (B.R, B.V) else 3
     ax = [("size", d) for d in range(4)] + [("level", i) for i in range(nlv)]
     if kind in B.BOUNDED:
         ax += [("limit", l) for l in range(target["n_levels"]) if target["capacity_bytes"][l] != INF]
+    if kind == B.V:      # contiguousness and aligned flag of the source, then of the destination
+        ax += [("contig", 0), ("aligned", 0), ("contig", 1), ("aligned", 1)]
     ax += [("layout", i) for i in range(nops) if lattice["layout_coord"][i]]
     ax += [("dtype", i) for i in range(nops) if lattice["dtype_coord"][i]]
     return ax
@@ -37,6 +40,7 @@ def spec_of_coord(lattice, x, target=None):
     lv, ly = [0] * 5, [0] * 5
     bf = [1 if lattice["base_dtype_bytes"][i] == 2 else 0 for i in range(5)]
     lim = [None] * (target["n_levels"] if target else 0)
+    contig, aligned = [2, 2], [1, 1]
     for (what, i), v in zip(axes(lattice, target), x):
         if what == "size":
             dims[i] = lattice["sizes"][i][v]
@@ -46,9 +50,13 @@ def spec_of_coord(lattice, x, target=None):
             ly[i] = v
         elif what == "limit":
             lim[i] = 0 if v == 0 else 1 << (v - 1)
+        elif what == "contig":
+            contig[i] = v
+        elif what == "aligned":
+            aligned[i] = v
         else:
             bf[i] = v
-    return B.Spec(lattice["kind"], tuple(dims), tuple(lv), tuple(ly), tuple(bf), tuple(lim))
+    return B.Spec(lattice["kind"], tuple(dims), tuple(lv), tuple(ly), tuple(bf), tuple(lim), tuple(contig), tuple(aligned))
 
 
 def coord_of_spec(lattice, spec, target=None):
@@ -62,6 +70,10 @@ def coord_of_spec(lattice, spec, target=None):
             x.append(spec.layouts[i])
         elif what == "limit":
             x.append(int(spec.limits[i]).bit_length())
+        elif what == "contig":
+            x.append(spec.contig[i])
+        elif what == "aligned":
+            x.append(spec.aligned[i])
         else:
             x.append(spec.bf16[i])
     return tuple(x)

@@ -1483,8 +1483,6 @@ int32_t mrl_coord_of_spec(const mrl_table* tab, const uint32_t shape[4], const u
 int32_t mrl_schedule(const mrl_table* tab, const mrl_coord* goal, mrl_schedule_node* out, size_t cap, size_t* n_out) {
   return guarded([&]() -> int32_t {
   if (!tab || !goal) return fail(MRL_E_INVAL, "NULL argument");
-  if (tab->P.kind == kKindV || tab->P.moves)
-    return fail(MRL_E_INVAL, "mrl_schedule does not walk MOVE and MATMUL_MOVES tables");
   struct Item { const mrl_table* t; uint32_t which; mrl_coord x; };
   std::vector<Item> stack;
   stack.push_back({tab, 0u, *goal});
@@ -1508,11 +1506,11 @@ int32_t mrl_schedule(const mrl_table* tab, const mrl_coord* goal, mrl_schedule_n
     mrl_schedule_node node;
     memset(&node, 0, sizeof node);
     node.table = it.which; node.rewrite = rw; node.cost = cost; node.spec = it.x;
-    if (r.cls == 1) {                       // Move: the operand one or more levels down, perhaps transposed / converted
+    if (r.cls == 1) {                       // Move: the operand one or more levels down, perhaps in another layout / converted
       const uint32_t op = r.operand_or_dim;
       Item ch = it;
       ch.x.x[4 + op] = r.dst_level;
-      if (r.transposed) { if (c.lay_axis[op] < 0) return fail(MRL_E_HIP, "internal error: transposing Move without a layout coordinate"); ch.x.x[c.lay_axis[op]] ^= 1u; }
+      if (r.transposed) { if (c.lay_axis[op] < 0) return fail(MRL_E_HIP, "internal error: transposing Move without a layout coordinate"); ch.x.x[c.lay_axis[op]] ^= r.transposed; }
       if (r.convert) { if (c.dt_axis[op] < 0) return fail(MRL_E_HIP, "internal error: converting Move without a dtype coordinate"); ch.x.x[c.dt_axis[op]] = 0; }
       if (P.bounded && P.lim_of_level[r.dst_level] != kNoBit) {
         // the Move's buffer comes out of the destination's bound; the rest snaps down to a power of two
@@ -1529,12 +1527,55 @@ int32_t mrl_schedule(const mrl_table* tab, const mrl_coord* goal, mrl_schedule_n
         while (left) { q++; left >>= 1; }
         ch.x.x[ax] = q;
       }
-      stack.push_back(ch);
       node.n_children = 1;
+      if (P.moves) {
+        // Section 2, Memory Movement: the alloc-binding holds a load Move Spec (operands that are read),
+        // the body, and a store Move Spec (operands that are written), both of fresh tensors
+        if (it.which != 0 || !it.t->deps[0]) return fail(MRL_E_HIP, "internal error: a Move Spec outside a MATMUL_MOVES table");
+        const mrl_table* vt = it.t->deps[0];
+        const Compiled& vc = *vt->cp;
+        const uint32_t y0 = c.lay_axis[op] >= 0 ? it.x.x[c.lay_axis[op]] : 0u, y1 = c.lay_axis[op] >= 0 ? ch.x.x[c.lay_axis[op]] : 0u;
+        const uint32_t f0 = c.dt_axis[op] >= 0 ? it.x.x[c.dt_axis[op]] : (uint32_t)(c.lat.base_dtype_bytes[op] == 2);
+        const uint32_t f1 = c.dt_axis[op] >= 0 ? ch.x.x[c.dt_axis[op]] : f0;
+        auto move_spec = [&](uint32_t ls, uint32_t ld, uint32_t ys, uint32_t yd, uint32_t fs, uint32_t fd, Item& out_item) -> int32_t {
+          out_item = Item{vt, 1u, {}};
+          mrl_coord& x = out_item.x;
+          memset(&x, 0, sizeof x);
+          x.x[1] = op == 1 ? it.x.x[2] : it.x.x[1];      // rows: m (lhs, out) or k (rhs); the size lists are the same
+          x.x[3] = op == 0 ? it.x.x[2] : it.x.x[3];      // columns: k (lhs) or n
+          x.x[4] = ls; x.x[5] = ld;
+          x.x[6] = ys >= 2 ? 3 : 2; x.x[7] = 1; x.x[8] = yd >= 2 ? 3 : 2; x.x[9] = 1;
+          if (vc.lay_axis[0] >= 0) x.x[vc.lay_axis[0]] = ys; else if (ys) return fail(MRL_E_HIP, "internal error: the MOVE table lacks a layout coordinate");
+          if (vc.lay_axis[1] >= 0) x.x[vc.lay_axis[1]] = yd; else if (yd) return fail(MRL_E_HIP, "internal error: the MOVE table lacks a layout coordinate");
+          if (vc.dt_axis[0] >= 0) x.x[vc.dt_axis[0]] = fs;
+          if (vc.dt_axis[1] >= 0) x.x[vc.dt_axis[1]] = fd;
+          return MRL_OK;
+        };
+        Item load, store;
+        const bool has_load = P.access[op] != kWrite, has_store = P.access[op] != kRead;
+        if (has_store) { rc = move_spec(r.dst_level, it.x.x[4 + op], y1, y0, f1, f0, store); if (rc) return rc; stack.push_back(store); }
+        stack.push_back(ch);                // popped after the load's whole subtree, before the store's
+        if (has_load) { rc = move_spec(it.x.x[4 + op], r.dst_level, y0, y1, f0, f1, load); if (rc) return rc; stack.push_back(load); }
+        node.n_children = (uint16_t)(1 + (has_load ? 1 : 0) + (has_store ? 1 : 0));
+      } else {
+        stack.push_back(ch);
+      }
     } else if (r.cls == 2) {                // tile: the loop body is the Spec with the smaller size
       const uint32_t d = r.operand_or_dim, j = (rw - P.tile_base) % P.maxs;
       Item ch = it;
       ch.x.x[d] = j;
+      if (P.kind == kKindV) {
+        // Section 2.4.3: what is known of the tile of either tensor
+        const uint64_t rows = c.sizes[1][it.x.x[1]], cols = c.sizes[3][it.x.x[3]];
+        const uint64_t r2 = c.sizes[1][ch.x.x[1]], c2 = c.sizes[3][ch.x.x[3]];
+        for (int ts = 0; ts < 2; ts++) {
+          const uint32_t y = c.lay_axis[ts] >= 0 ? it.x.x[c.lay_axis[ts]] : 0u;
+          const bool bf = c.dt_axis[ts] >= 0 ? it.x.x[c.dt_axis[ts]] != 0 : c.lat.base_dtype_bytes[ts] == 2;
+          uint32_t contig2, aligned2;
+          tile_abstract(y, rows, cols, r2, c2, bf ? 2 : 4, P.strip ? P.strip : 1, P.line_bytes, it.x.x[6 + 2 * ts], it.x.x[7 + 2 * ts], contig2, aligned2);
+          ch.x.x[6 + 2 * ts] = contig2; ch.x.x[7 + 2 * ts] = aligned2;
+        }
+      }
       stack.push_back(ch);
       node.n_children = 1;
     } else if (r.cls == 4) {                // parallel loop: the body is the serial-only Spec of the smaller size

@@ -4,6 +4,7 @@
 // even the small fields are 32 bits wide: there is no scalar byte load).
 #pragma once
 #include <stdint.h>
+#include <hip/hip_runtime.h>
 
 namespace mrl {
 
@@ -120,5 +121,58 @@ struct Counters {
   unsigned long long n_admissible[kCtrSlots];
   unsigned long long n_rewrites[kCtrSlots];
 };
+
+// Layouts (Section 2.4.2): 0 row-major, 1 column-major, 2 packed in strips of s columns, 3 packed
+// with shuffled strips.  Physical dimensions of a rows x cols tensor, outermost first: two, or for
+// the packed layouts strips, rows, columns of a strip; a tile cut out of one strip (cols < s) is
+// the same part of every row of that strip.
+__host__ __device__ inline uint32_t phys_dims(uint32_t layout, uint64_t rows, uint64_t cols, uint64_t s, uint64_t d[3]) {
+  if (layout == 0) { d[0] = rows; d[1] = cols; d[2] = 1; return 2; }
+  if (layout == 1) { d[0] = cols; d[1] = rows; d[2] = 1; return 2; }
+  if (cols >= s) { d[0] = cols / s; d[1] = rows; d[2] = s; }
+  else { d[0] = 1; d[1] = rows; d[2] = cols; }
+  return 3;
+}
+__host__ __device__ inline bool layout_fits(uint32_t layout, uint64_t cols, uint64_t s) {
+  return layout < 2 || cols % s == 0 || (cols < s && s % cols == 0);
+}
+// The most inner physical dimensions whose values can be adjacent: the rows of a part of a strip
+// lie a strip apart, and the columns of a part of a shuffled strip are no neighbours either.
+__host__ __device__ inline uint32_t max_contig(uint32_t layout, uint64_t cols, uint64_t s) {
+  if (layout < 2) return 2;
+  if (cols >= s) return 3;
+  if (layout == 2) return 1;
+  return cols == 1 ? 1 : 0;
+}
+
+// Section 2.4.3 for a tile of r2 x c2 cut out of a rows x cols tensor in `layout` with element size
+// eb: what is known of the tile, given what was known of the tensor.  The tile's values over its
+// inner j dimensions are adjacent while the j - 1 innermost are taken whole; it is aligned if the
+// tensor was aligned and contiguous in all its dimensions, every suffix product of the tile's
+// physical dimensions is a whole number of cache lines, and it is no part of a strip.
+__host__ __device__ inline void tile_abstract(uint32_t layout, uint64_t rows, uint64_t cols, uint64_t r2, uint64_t c2, uint64_t eb,
+                                              uint64_t strip, uint64_t line, uint32_t contig, uint32_t aligned,
+                                              uint32_t& contig2, uint32_t& aligned2) {
+  uint64_t whole[3], part[3];
+  const uint32_t nd = phys_dims(layout, rows, cols, strip, whole);
+  phys_dims(layout, r2, c2, strip, part);
+  uint32_t uncut = 0;
+  bool lines_ok = layout < 2 || c2 >= strip;
+  uint64_t suffix = eb;
+  bool still = true;
+#pragma unroll
+  for (int q3 = 2; q3 >= 0; q3--) {
+    if ((uint32_t)q3 >= nd) continue;
+    still = still && part[q3] == whole[q3];
+    uncut += still ? 1u : 0u;
+    suffix *= part[q3];
+    lines_ok = lines_ok && suffix % line == 0;
+  }
+  uint32_t keep = 1u + uncut;
+  const uint32_t most = max_contig(layout, c2, strip);
+  keep = keep < most ? keep : most;
+  contig2 = contig < keep ? contig : keep;
+  aligned2 = (aligned && contig == nd && lines_ok) ? 1u : 0u;
+}
 
 }  // namespace mrl

@@ -1063,29 +1063,6 @@ uint32_t fill_wave_cap(uint32_t G) { return G <= kSmallCap ? G : kSlicedCap; }
 // test.  And the Matmul whose Moves are Move Specs (Section 2, Memory Movement; Section 3): the
 // plain Matmul Specs with their admissibility test, where a Move costs m(src) + m(dest) in cache
 // lines plus the load and store Move Specs, read from the Move table.
-// Layouts (Section 2.4.2): 0 row-major, 1 column-major, 2 packed in strips of s columns, 3 packed
-// with shuffled strips.  Physical dimensions of a rows x cols tensor, outermost first: two, or for
-// the packed layouts strips, rows, columns of a strip; a tile cut out of one strip (cols < s) is
-// the same part of every row of that strip.
-__device__ __forceinline__ uint32_t phys_dims(uint32_t layout, uint64_t rows, uint64_t cols, uint64_t s, uint64_t d[3]) {
-  if (layout == 0) { d[0] = rows; d[1] = cols; d[2] = 1; return 2; }
-  if (layout == 1) { d[0] = cols; d[1] = rows; d[2] = 1; return 2; }
-  if (cols >= s) { d[0] = cols / s; d[1] = rows; d[2] = s; }
-  else { d[0] = 1; d[1] = rows; d[2] = cols; }
-  return 3;
-}
-__device__ __forceinline__ bool layout_fits(uint32_t layout, uint64_t cols, uint64_t s) {
-  return layout < 2 || cols % s == 0 || (cols < s && s % cols == 0);
-}
-// The most inner physical dimensions whose values can be adjacent: the rows of a part of a strip
-// lie a strip apart, and the columns of a part of a shuffled strip are no neighbours either.
-__device__ __forceinline__ uint32_t max_contig(uint32_t layout, uint64_t cols, uint64_t s) {
-  if (layout < 2) return 2;
-  if (cols >= s) return 3;
-  if (layout == 2) return 1;
-  return cols == 1 ? 1 : 0;
-}
-
 __device__ __forceinline__ uint64_t add_or_limit(uint64_t a, uint64_t b) {
   return (a >= kLimit || b >= kLimit || a + b >= kLimit) ? kLimit : a + b;
 }
@@ -1289,28 +1266,8 @@ __global__ __launch_bounds__(256) void fill_bounded_kernel(const DevParams* __re
             const uint32_t y = layout_of(ts);
             const uint32_t bf = P->dt_bit[ts] != kNoBit ? (v >> P->dt_bit[ts]) & 1u : P->base_bf16[ts];
             const uint64_t eb = bf ? 2u : 4u;
-            uint64_t whole[3], part[3];
-            const uint32_t nd = phys_dims(y, S.d[1], S.d[3], strip, whole);
-            phys_dims(y, r2, c2, strip, part);
-            // the tile's values over its inner j dimensions are adjacent while the j - 1 innermost are uncut
-            uint32_t uncut = 0;
-            bool lines_ok = y < 2 || c2 >= strip;          // a part of a strip is not known to be aligned
-            uint64_t suffix = eb;
-            bool still = true;
-#pragma unroll
-            for (int q3 = 2; q3 >= 0; q3--) {
-              if ((uint32_t)q3 >= nd) continue;
-              still = still && part[q3] == whole[q3];
-              uncut += still ? 1u : 0u;
-              suffix *= part[q3];
-              lines_ok = lines_ok && suffix % P->line_bytes == 0;
-            }
-            const uint32_t contig = qi[2 * ts], aligned = qi[2 * ts + 1];
-            uint32_t keep = 1u + uncut;
-            const uint32_t most = max_contig(y, c2, strip);
-            keep = keep < most ? keep : most;
-            const uint32_t contig2 = contig < keep ? contig : keep;
-            const uint32_t aligned2 = (aligned && contig == nd && lines_ok) ? 1u : 0u;
+            uint32_t contig2, aligned2;
+            tile_abstract(y, S.d[1], S.d[3], r2, c2, eb, strip, P->line_bytes, qi[2 * ts], qi[2 * ts + 1], contig2, aligned2);
             qc += contig2 * P->lim_stride[2 * ts] + aligned2 * P->lim_stride[2 * ts + 1];
           }
           off_c = ((combo * npass + pass) * Q + qc) * V + v;

@@ -21,7 +21,12 @@ def check_tree(tree, results):
         n += 1
         assert S.tree_cost(t) == t["cost"]
         tag = t["node"][0]
-        assert len(t["children"]) == {"mk": 0, "loop": 1, "alloc": 1, "pipeline": 2}[tag]
+        if tag == "alloc" and t["label"] == "M" and any(ch["label"] == "V" for ch in t["children"]):
+            # an alloc-binding whose Moves are Specs: load (unless only written), body, store (if written)
+            labels = [ch["label"] for ch in t["children"]]
+            assert labels in (["V", "M"], ["V", "M", "V"])
+        else:
+            assert len(t["children"]) == {"mk": 0, "loop": 1, "alloc": 1, "pipeline": 2}[tag]
         stack += t["children"]
     return n
 
@@ -97,3 +102,23 @@ def _chain(tree):
         assert len(out[-1]["children"]) == 1
         out.append(out[-1]["children"][0])
     return out
+
+
+def test_programs_with_move_specs():
+    """Section 2, Memory Movement: the alloc-binding of an operand holds its load Move Spec, the
+    body and (for the accumulated output) its store Move Spec, each implemented like any Spec;
+    the extracted tree costs what the table says, down through the Move Specs' own loops and
+    move microkernels, also with packed layouts."""
+    for number, size in ((9, 8), (12, 8)):
+        cfg = W.config(number, max_size=size)
+        res = O.solve_config(cfg)
+        nodes = with_moves = 0
+        for goal in sample_goals(res, "M", 120, seed=number):
+            tree = S.extract(cfg["target"], cfg["lattices"], res, "M", goal)
+            nodes += check_tree(tree, res)
+            with_moves += any(n[0] == "V" for n in S.preorder(tree))
+        assert nodes > 400 and with_moves > 20
+        for goal in sample_goals(res, "V", 120, seed=number):
+            tree = S.extract(cfg["target"], cfg["lattices"], res, "V", goal)
+            check_tree(tree, res)
+            assert {n[0] for n in S.preorder(tree)} == {"V"}

@@ -231,6 +231,7 @@ int32_t compile(const mrl_target_desc& T, const mrl_lattice_desc* L, Compiled& c
   P.chain = chain ? 1u : 0u;
   P.split = split ? 1u : 0u;
   P.line_bytes = T.line_bytes;
+  P.line_mask = T.line_bytes && (T.line_bytes & (T.line_bytes - 1)) == 0 ? T.line_bytes - 1 : 0;
   for (int l = 0; l < 4; l++) P.weight[l] = T.level_weight[l];
   P.nops = kind == kKindF ? 4 : kind == kKindV || kind == kKindR ? 2 : 3;
   P.nlv = kind == kKindF ? 5 : kind == kKindV || kind == kKindR ? 2 : 3;
@@ -882,10 +883,11 @@ int32_t solve_impl(const mrl_target* t, const mrl_lattice_desc* lat, const mrl_t
     // counts as fitting for the compression); one launch per dependency level of shapes and rank
     // of level assignments, each over Specs that depend only on earlier launches.
     launch_fill_ones(d_fitmap, ((size_t)f.n_words + 2) * 8, st);
+    const int gather_mode = P.kind == kKindV ? 1 : P.moves ? 2 : 0;
     for (uint32_t d = 0; d + 1 < n_lev + P.nranks; d++) {
       BoundSegs segs;
       segs.n = 0; segs.block0[0] = 0;
-      auto flush = [&]() { launch_fill_bounded(d_P, P.kind == kKindV ? 1 : P.moves ? 2 : 0, d_level_shapes, segs, tab->d_cost, tab->d_arg, d_ctr, st); segs.n = 0; segs.block0[0] = 0; };
+      auto flush = [&]() { launch_fill_bounded(d_P, gather_mode, d_level_shapes, segs, tab->d_cost, tab->d_arg, d_ctr, st); segs.n = 0; segs.block0[0] = 0; };
       for (uint32_t l = d < P.nranks ? 0 : d - (P.nranks - 1); l < n_lev && l <= d; l++) {
         const uint32_t r = d - l, ns = c.level_off[l + 1] - c.level_off[l];
         const uint64_t lanes = (uint64_t)ns * (P.rank_off[r + 1] - P.rank_off[r]) * P.npass * P.Q * P.V;
@@ -1566,13 +1568,14 @@ int32_t mrl_schedule(const mrl_table* tab, const mrl_coord* goal, mrl_schedule_n
       ch.x.x[d] = j;
       if (P.kind == kKindV) {
         // Section 2.4.3: what is known of the tile of either tensor
-        const uint64_t rows = c.sizes[1][it.x.x[1]], cols = c.sizes[3][it.x.x[3]];
-        const uint64_t r2 = c.sizes[1][ch.x.x[1]], c2 = c.sizes[3][ch.x.x[3]];
+        const uint32_t rows = c.sizes[1][it.x.x[1]], cols = c.sizes[3][it.x.x[3]];
+        const uint32_t r2 = c.sizes[1][ch.x.x[1]], c2 = c.sizes[3][ch.x.x[3]];
         for (int ts = 0; ts < 2; ts++) {
           const uint32_t y = c.lay_axis[ts] >= 0 ? it.x.x[c.lay_axis[ts]] : 0u;
           const bool bf = c.dt_axis[ts] >= 0 ? it.x.x[c.dt_axis[ts]] != 0 : c.lat.base_dtype_bytes[ts] == 2;
           uint32_t contig2, aligned2;
-          tile_abstract(y, rows, cols, r2, c2, bf ? 2 : 4, P.strip ? P.strip : 1, P.line_bytes, it.x.x[6 + 2 * ts], it.x.x[7 + 2 * ts], contig2, aligned2);
+          tile_abstract(y, rows, cols, r2, c2, bf ? 2 : 4, P.strip ? P.strip : 1, P.line_bytes, P.line_mask, it.x.x[6 + 2 * ts], it.x.x[7 + 2 * ts],
+                        contig2, aligned2);
           ch.x.x[6 + 2 * ts] = contig2; ch.x.x[7 + 2 * ts] = aligned2;
         }
       }

@@ -93,6 +93,7 @@ struct DevParams {
   uint32_t limV_stride[4];   // strides of its four abstract-value axes inside the abstract vector's index
   // ---- packed layouts (Move lattices and the Matmul whose Moves are Move Specs) ----
   uint32_t strip;            // columns per strip of layouts 2 (packed) and 3 (packed, strips shuffled)
+  uint32_t line_mask;        // line_bytes - 1 if line_bytes is a power of two, else 0
   uint32_t xw;               // layout changes a Move id names: 2, or 4 where some operand has a 2-bit layout field
   // ---- tables a FUSED lattice reads (costM also: the serial table a parallel lattice reads) ----
   const uint64_t* costM;
@@ -126,19 +127,20 @@ struct Counters {
 // with shuffled strips.  Physical dimensions of a rows x cols tensor, outermost first: two, or for
 // the packed layouts strips, rows, columns of a strip; a tile cut out of one strip (cols < s) is
 // the same part of every row of that strip.
-__host__ __device__ inline uint32_t phys_dims(uint32_t layout, uint64_t rows, uint64_t cols, uint64_t s, uint64_t d[3]) {
+// (sizes and the strip are 32-bit by the ABI: divisions stay 32-bit; only products of sizes need 64)
+__host__ __device__ inline uint32_t phys_dims(uint32_t layout, uint32_t rows, uint32_t cols, uint32_t s, uint32_t d[3]) {
   if (layout == 0) { d[0] = rows; d[1] = cols; d[2] = 1; return 2; }
   if (layout == 1) { d[0] = cols; d[1] = rows; d[2] = 1; return 2; }
   if (cols >= s) { d[0] = cols / s; d[1] = rows; d[2] = s; }
   else { d[0] = 1; d[1] = rows; d[2] = cols; }
   return 3;
 }
-__host__ __device__ inline bool layout_fits(uint32_t layout, uint64_t cols, uint64_t s) {
+__host__ __device__ inline bool layout_fits(uint32_t layout, uint32_t cols, uint32_t s) {
   return layout < 2 || cols % s == 0 || (cols < s && s % cols == 0);
 }
 // The most inner physical dimensions whose values can be adjacent: the rows of a part of a strip
 // lie a strip apart, and the columns of a part of a shuffled strip are no neighbours either.
-__host__ __device__ inline uint32_t max_contig(uint32_t layout, uint64_t cols, uint64_t s) {
+__host__ __device__ inline uint32_t max_contig(uint32_t layout, uint32_t cols, uint32_t s) {
   if (layout < 2) return 2;
   if (cols >= s) return 3;
   if (layout == 2) return 1;
@@ -150,10 +152,11 @@ __host__ __device__ inline uint32_t max_contig(uint32_t layout, uint64_t cols, u
 // inner j dimensions are adjacent while the j - 1 innermost are taken whole; it is aligned if the
 // tensor was aligned and contiguous in all its dimensions, every suffix product of the tile's
 // physical dimensions is a whole number of cache lines, and it is no part of a strip.
-__host__ __device__ inline void tile_abstract(uint32_t layout, uint64_t rows, uint64_t cols, uint64_t r2, uint64_t c2, uint64_t eb,
-                                              uint64_t strip, uint64_t line, uint32_t contig, uint32_t aligned,
+// line_mask = line - 1 if the cache line is a power of two (then "multiple of the line" is a mask test), else 0.
+__host__ __device__ inline void tile_abstract(uint32_t layout, uint32_t rows, uint32_t cols, uint32_t r2, uint32_t c2, uint32_t eb,
+                                              uint32_t strip, uint32_t line, uint32_t line_mask, uint32_t contig, uint32_t aligned,
                                               uint32_t& contig2, uint32_t& aligned2) {
-  uint64_t whole[3], part[3];
+  uint32_t whole[3], part[3];
   const uint32_t nd = phys_dims(layout, rows, cols, strip, whole);
   phys_dims(layout, r2, c2, strip, part);
   uint32_t uncut = 0;
@@ -166,7 +169,7 @@ __host__ __device__ inline void tile_abstract(uint32_t layout, uint64_t rows, ui
     still = still && part[q3] == whole[q3];
     uncut += still ? 1u : 0u;
     suffix *= part[q3];
-    lines_ok = lines_ok && suffix % line == 0;
+    lines_ok = lines_ok && (line_mask || line == 1 ? (suffix & line_mask) == 0 : suffix % line == 0);
   }
   uint32_t keep = 1u + uncut;
   const uint32_t most = max_contig(layout, c2, strip);

@@ -1087,8 +1087,9 @@ __global__ __launch_bounds__(256) void fill_bounded_kernel(const DevParams* __re
   e.best = kInf; e.arg = kNone; e.n = 0; e.ovf = 0;
   uint32_t n_adm = 0;
   if (active) {
-    const uint32_t sl = (uint32_t)(t / per_shape);
-    uint32_t r = (uint32_t)(t - (uint64_t)sl * per_shape);
+    // (an active lane's index is below the number of Specs of the lattice, which fits 32 bits)
+    const uint32_t sl = (uint32_t)t / (uint32_t)per_shape;
+    uint32_t r = (uint32_t)t - sl * (uint32_t)per_shape;
     const uint32_t ci = r / (npass * Q * V);
     r -= ci * npass * Q * V;
     const uint32_t pass = r / (Q * V);
@@ -1123,7 +1124,7 @@ __global__ __launch_bounds__(256) void fill_bounded_kernel(const DevParams* __re
 #pragma unroll
         for (int ts = 0; ts < 2; ts++) {
           const uint32_t y = layout_of(ts);
-          admissible = admissible && layout_fits(y, S.d[3], P->strip) && qi[2 * ts] <= max_contig(y, S.d[3], P->strip);
+          admissible = admissible && layout_fits(y, (uint32_t)S.d[3], P->strip) && qi[2 * ts] <= max_contig(y, (uint32_t)S.d[3], P->strip);
         }
       }
       n_adm = admissible ? 1u : 0u;
@@ -1132,7 +1133,7 @@ __global__ __launch_bounds__(256) void fill_bounded_kernel(const DevParams* __re
       if (P->xw == 4) {
 #pragma unroll
         for (int i = 0; i < 3; i++) {
-          const uint64_t cols = i == 0 ? S.d[2] : S.d[3];
+          const uint32_t cols = (uint32_t)(i == 0 ? S.d[2] : S.d[3]);
           admissible = admissible && (layout_of(i) < 2 || cols % P->strip == 0);      // whole tensors: whole strips
         }
       }
@@ -1176,8 +1177,19 @@ __global__ __launch_bounds__(256) void fill_bounded_kernel(const DevParams* __re
       const bool has_dt = P->dt_bit[i] != kNoBit, has_lay = P->lay_bit[i] != kNoBit;
       const uint32_t bf = has_dt ? (v >> P->dt_bit[i]) & 1u : P->base_bf16[i];
       const uint64_t numel = S.numel[i];
+      // cache lines of the operand as f32 and as bf16 (Section 3, m(t)), once per operand
+      uint64_t lines_f32 = 0, lines_bf16 = 0;
+      if (moves) {
+        const uint64_t line = P->line_bytes;
+        if (P->line_mask || line == 1) {
+          const uint32_t sh = 31u - (uint32_t)__clz((int)P->line_bytes);
+          lines_f32 = (numel * 4u + line - 1) >> sh; lines_bf16 = (numel * 2u + line - 1) >> sh;
+        } else {
+          lines_f32 = (numel * 4u + line - 1) / line; lines_bf16 = (numel * 2u + line - 1) / line;
+        }
+      }
       for (uint32_t dst = 0; dst < src; dst++)
-        for (uint32_t x = 0; x < P->xw; x++)          // the Move leaves the operand in layout (its own) xor x
+        for (uint32_t x = 0; x < (moves ? P->xw : 2u); x++)          // the Move leaves the operand in layout (its own) xor x
           for (uint32_t cv = 0; cv < 2; cv++) {
             if (x && !has_lay) continue;
             if (x >= 2 && P->lay_w[i] != 2) continue;
@@ -1206,8 +1218,7 @@ __global__ __launch_bounds__(256) void fill_bounded_kernel(const DevParams* __re
               uint32_t v_c = v ^ (x ? x << P->lay_bit[i] : 0u);
               if (cv) v_c &= ~(1u << P->dt_bit[i]);
               const uint64_t sub = cost[group + (uint64_t)((combo_c * npass + pass) * Q + q) * V + v_c];
-              const uint64_t line = P->line_bytes;
-              const uint64_t lines_s = (numel * (bf ? 2u : 4u) + line - 1) / line, lines_d = (numel * (child_bf ? 2u : 4u) + line - 1) / line;
+              const uint64_t lines_s = bf ? lines_bf16 : lines_f32, lines_d = child_bf ? lines_bf16 : lines_f32;
               const uint32_t ws = src == 1 ? P->weight[1] : src == 2 ? P->weight[2] : P->weight[3];
               const uint32_t wd = dst == 0 ? P->weight[0] : dst == 1 ? P->weight[1] : P->weight[2];
               const uint32_t id = P->move_base + (((uint32_t)i * (P->NL - 1u) + dst) * P->xw + x) * 2u + cv;
@@ -1258,16 +1269,17 @@ __global__ __launch_bounds__(256) void fill_bounded_kernel(const DevParams* __re
           // Section 2.4.3: what is known of a tile of either tensor.  Cutting the inner dimension
           // leaves only that dimension adjacent; the tile is aligned only if the tensor was aligned
           // and contiguous and the tile's rows (and so the tile) are whole cache lines.
-          const uint64_t r2 = d == 1 ? P->sizes[1][te.jt] : S.d[1], c2 = d == 3 ? P->sizes[3][te.jt] : S.d[3];
-          const uint64_t strip = P->strip ? P->strip : 1u;
+          const uint32_t r2 = d == 1 ? P->sizes[1][te.jt] : (uint32_t)S.d[1], c2 = d == 3 ? P->sizes[3][te.jt] : (uint32_t)S.d[3];
+          const uint32_t strip = P->strip ? P->strip : 1u;
           uint32_t qc = 0;
 #pragma unroll
           for (int ts = 0; ts < 2; ts++) {
             const uint32_t y = layout_of(ts);
             const uint32_t bf = P->dt_bit[ts] != kNoBit ? (v >> P->dt_bit[ts]) & 1u : P->base_bf16[ts];
-            const uint64_t eb = bf ? 2u : 4u;
+            const uint32_t eb = bf ? 2u : 4u;
             uint32_t contig2, aligned2;
-            tile_abstract(y, S.d[1], S.d[3], r2, c2, eb, strip, P->line_bytes, qi[2 * ts], qi[2 * ts + 1], contig2, aligned2);
+            tile_abstract(y, (uint32_t)S.d[1], (uint32_t)S.d[3], r2, c2, eb, strip, P->line_bytes, P->line_mask, qi[2 * ts], qi[2 * ts + 1],
+                          contig2, aligned2);
             qc += contig2 * P->lim_stride[2 * ts] + aligned2 * P->lim_stride[2 * ts + 1];
           }
           off_c = ((combo * npass + pass) * Q + qc) * V + v;

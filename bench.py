@@ -213,10 +213,12 @@ def main():
     big_fill_ms = fill_ms[big] / args.steps
     big_prefill_ms = prefill_ms[big] / args.steps
     big_kind = next(lat["kind"] for label, lat, _ in cfg["lattices"] if label == big)
-    fused = big_kind in (W.KIND_FUSED_MM_ADD_RELU, W.KIND_FUSED_BOUNDED)
+    fused = big_kind in (W.KIND_FUSED_MM_ADD_RELU, W.KIND_FUSED_BOUNDED, W.KIND_MATMUL_CHAIN)    # two reads for the bufferize
     n_launch = stats[big]["n_levels_run"]
-    kernel_text = ("fill of table %s: plan_kernel (which also streams the (INF, NONE) pre-fill), sort_work_kernel, "
-                   "fill_kernel / fill_big_kernel per dependency level" % big)
+    has_deps = any(deps for label, _, deps in cfg["lattices"] if label == big)
+    kernel_text = ("fill of table %s: plan_kernel, sort_work_kernel, the (INF, NONE) pre-fill (%s), "
+                   "fill_kernel / fill_big_kernel per dependency level"
+                   % (big, "fill_ones_short_kernel, beside the fills of the tables it reads" if has_deps else "inside plan_kernel"))
     if big_kind in W.BOUNDED_KINDS + (W.KIND_MOVE, W.KIND_MATMUL_MOVES):
         # one launch per diagonal: dependency level of shapes + rank (sum of the operand levels)
         n_launch += W.n_operands(big_kind) * (cfg["target"]["n_levels"] - 1)
